@@ -1,0 +1,236 @@
+/*
+ * cwac.h - C ABI of the MI355X (gfx950) library for the QwT-v2 hot path:
+ * a W8A8 quantized linear layer whose GEMM epilogue carries the folded
+ * channel-wise affine compensation (CWAC), and the calibration pass that fits it.
+ *
+ * Conventions (all entry points)
+ *   - Pointers marked "device" are device addresses owned by the caller and must
+ *     stay valid until the work enqueued on `stream` has finished.  Pointers
+ *     marked "host" are ordinary host pointers read or written during the call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     device work is enqueued asynchronously on it; no call synchronizes.
+ *   - The library allocates no device memory and keeps no state between calls;
+ *     scratch space is passed in as an explicit workspace.
+ *   - Errors are reported through the return value; when a call returns an error
+ *     nothing has been launched.  No call aborts or throws.
+ *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
+ *   - Rounding is round-half-to-even everywhere ("the rounding function" of
+ *     Sec. 3.2).  The fp32 epilogue is a fixed sequence of single fp32
+ *     operations without fused multiply-add, so integer codes are reproducible
+ *     bit for bit.
+ */
+#ifndef CWAC_H_
+#define CWAC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t cwac_status;
+enum {
+  CWAC_OK = 0,
+  CWAC_E_NULL = -1,      /* a required pointer is NULL */
+  CWAC_E_SHAPE = -2,     /* a size is out of the supported range */
+  CWAC_E_ALIGN = -3,     /* a pointer or leading dimension violates the stated alignment */
+  CWAC_E_MODE = -4,      /* inconsistent mode / optional-argument combination */
+  CWAC_E_WORKSPACE = -5, /* workspace missing or too small */
+  CWAC_E_LAUNCH = -6     /* the HIP runtime refused a launch */
+};
+
+/* Static description of an error code (host). */
+const char *cwac_status_string(cwac_status s);
+
+/* ------------------------------------------------------------------------- */
+/* Quantizers - Sec. 3.2, Eq. 1-2                                             */
+/* ------------------------------------------------------------------------- */
+
+/* Workspace bytes needed by cwac_range_f32 for `count` elements. */
+size_t cwac_range_workspace(int64_t count);
+
+/* min and max of a contiguous fp32 tensor, the inputs of Eq. 2.
+ *   x        device, [count], count >= 1
+ *   minmax   device, float[2]: {min, max}
+ *   workspace device, at least cwac_range_workspace(count) bytes, 8-byte aligned */
+cwac_status cwac_range_f32(const float *x, int64_t count, float *minmax, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* Eq. 2 (host arithmetic, fp32): s = (max - min) / (2^bits - 1),
+ * z = clip(round(-min / s), 0, 2^bits - 1); s is floored at FLT_MIN * 2^bits so
+ * that a constant tensor stays quantizable.  bits in [2, 8].
+ *   s, z     host outputs; z is the zero-point of the UNSIGNED code of Eq. 1.
+ * For signed 8-bit storage use z - 128 as zero-point (see cwac_quantize_act). */
+cwac_status cwac_qparams_from_range(float mn, float mx, int32_t bits, float *s, int32_t *z);
+
+/* Eq. 1 with per-tensor parameters, 8 bit, signed storage:
+ * q = clip(round(x / s) + (z + 128), 0, 255) - 128, i.e. the Eq. 1 code shifted
+ * by 128 together with its zero-point (s * (q - z) is unchanged).
+ *   x   device fp32 [rows, k], leading dimension ldx
+ *   q   device int8 [rows, k], leading dimension ldq
+ *   s   scale (> 0), z signed zero-point in [-128, 127] */
+cwac_status cwac_quantize_act(const float *x, int64_t ldx, int64_t rows, int32_t k, float s,
+                              int32_t z, int8_t *q, int64_t ldq, void *stream);
+
+/* Symmetric per-row quantizer (per output channel for weights [N, K]; per token
+ * for activations [M, K]): scale[r] = max_k |x[r,k]| / 127 (floored at
+ * FLT_MIN * 256), q = clip(round(x / scale[r]), -127, 127), zero-point 0.
+ *   x device fp32 [rows, k]; scale device fp32 [rows]; q device int8 [rows, k] */
+cwac_status cwac_quantize_rows_sym(const float *x, int64_t ldx, int64_t rows, int32_t k,
+                                   float *scale, int8_t *q, int64_t ldq, void *stream);
+
+/* colsum[n] = sum_k w_q[n, k]: the Z_x W_q term of Eq. 7 is Z_x * colsum[n].
+ *   w_q device int8 [n, k]; colsum device int32 [n] */
+cwac_status cwac_colsum(const int8_t *w_q, int64_t ldw, int32_t n, int32_t k, int32_t *colsum,
+                        void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Calibration statistics and closed-form fit - Sec. 3.3, Eq. 3-5             */
+/* ------------------------------------------------------------------------- */
+
+/* The calibration state is a caller-owned DEVICE buffer of cwac_stats_bytes(c_out)
+ * bytes, 16-byte aligned.  Layout (stable, so that a caller may copy it out and
+ * resume later):
+ *   bytes  0..7    int64  n            rows accumulated so far
+ *   bytes  8..11   int32  c_out
+ *   bytes 12..63   reserved (zero)
+ *   float  pivot_q[c_out], float pivot_f[c_out]   per-channel shift, fixed by the
+ *                                                  first row ever accumulated
+ *   double sum[5][c_out]   over all rows so far, with dq = y_quant - pivot_q and
+ *                          df = y_full - pivot_f:
+ *                          sum dq, sum df, sum dq*dq, sum dq*df, sum df*df        */
+size_t cwac_stats_bytes(int32_t c_out);
+
+/* Sets the state to "no rows seen".  stats: device. */
+cwac_status cwac_stats_reset(void *stats, int32_t c_out, void *stream);
+
+/* Workspace bytes needed by cwac_calibrate_stats for one call with these sizes. */
+size_t cwac_calibrate_stats_workspace(int64_t n_rows, int32_t c_out);
+
+/* Accumulates one batch of calibration outputs into the state: for every output
+ * channel the sums listed above over the batch's rows (Y_full and Y_quant of
+ * Sec. 3.3; rows = calibration samples x tokens).  May be called any number of
+ * times; the result does not depend on how the rows are split into batches
+ * beyond fp64 summation order, and is bit-reproducible for a given split.
+ *   y_full, y_quant  device fp32 [n_rows, c_out], leading dimensions ld_full, ld_quant
+ *   n_rows >= 0 (0 is a no-op), 1 <= c_out <= 65536
+ *   stats      device, in/out
+ *   workspace  device, >= cwac_calibrate_stats_workspace(n_rows, c_out) bytes, 16-byte aligned
+ * Fast path when c_out, ld_full, ld_quant are multiples of 4 and both matrices
+ * are 16-byte aligned; any other layout takes a slower generic kernel. */
+cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full, const float *y_quant,
+                                 int64_t ld_quant, int64_t n_rows, int32_t c_out, void *stats,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* Eq. 4-5 per channel from the state, evaluated in fp64 and rounded to fp32:
+ *   alpha = Cov(Y_full, Y_quant) / Var(Y_quant),  beta = E[Y_full] - alpha E[Y_quant].
+ * Channels where the regression is undetermined (no rows; Var(Y_quant) not above
+ * var_eps * max(E[Y_quant]^2, 1e-300)) or whose slope is exactly 0 (which Eq. 10
+ * cannot fold) get alpha = 1, beta = E[Y_full] - E[Y_quant] and are counted.
+ *   alpha, beta    device fp32 [c_out]
+ *   moments        device fp64 [5][c_out] or NULL: E[Y_full], E[Y_quant],
+ *                  Var(Y_quant), Cov(Y_quant, Y_full), Var(Y_full), all with 1/n
+ *   n_degenerate   device int32[1] or NULL: number of fallback channels */
+cwac_status cwac_solve(const void *stats, int32_t c_out, double var_eps, float *alpha,
+                       float *beta, double *moments, int32_t *n_degenerate, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Fold into the engine parameters - Sec. 3.4, Eq. 7-8 and Eq. 10-11          */
+/* ------------------------------------------------------------------------- */
+
+enum { CWAC_EPI_INT_OFFSET = 0, CWAC_EPI_FP_BIAS = 1 };
+
+/* Quantization parameters of one layer in the notation of Sec. 3.4 (host struct).
+ * Weights are symmetric per output channel (Z_W = 0), so of the four terms of
+ * Eq. 7 only W_q x_q and Z_x W_q remain. */
+typedef struct cwac_qparams {
+  int32_t mode;          /* CWAC_EPI_INT_OFFSET: beta rounded into the integer offset (Eq. 10);
+                            CWAC_EPI_FP_BIAS: beta kept as an fp32 bias added after the multiplier */
+  int32_t act_per_token; /* 0: per-tensor (S_x, Z_x) below; 1: per-row scales s_x_row[m], Z_x = 0
+                            (requires CWAC_EPI_FP_BIAS) */
+  float s_x;             /* S_x (ignored when act_per_token) */
+  int32_t z_x;           /* Z_x, signed-storage zero-point */
+  float s_r;             /* S_r */
+  int32_t z_r;           /* Z_r, signed-storage zero-point */
+  int32_t qmin, qmax;    /* output code range, e.g. -128, 127; -128 <= qmin <= qmax <= 127 */
+} cwac_qparams;
+
+/* Per-output-channel engine parameters, evaluated in fp64 and rounded once.
+ * alpha == NULL and beta == NULL mean alpha = 1, beta = 0: the plain PTQ layer of
+ * Eq. 7-8.  With a = alpha[n], unit = S_x * S_W[n]:
+ *   INT_OFFSET:  mult[n]   = (float)(((a * S_x) * S_W[n]) / S_r)                       (Eq. 11)
+ *                offset[n] = sat(round(beta[n] / ((a * S_x) * S_W[n])) + round(bias[n] / unit))
+ *                            - Z_x * colsum[n]                                          (Eq. 10)
+ *                sat clamps to +-2^30 so that accumulator + offset cannot wrap.
+ *   FP_BIAS:     mult[n]   = as above (per-tensor) or (float)((a * S_W[n]) / S_r) (per-token)
+ *                fbias[n]  = (float)((a * bias[n] + beta[n]) / S_r)
+ *                offset[n] = -Z_x * colsum[n]
+ *   alpha, beta, s_w, bias (nullable = no bias), colsum: device [n_out]
+ *   qp           host
+ *   mult, offset device [n_out]; fbias device [n_out], required in FP_BIAS mode
+ *   n_saturated  device int32[1] or NULL: channels whose offset was clamped
+ * With s_r = 1, alpha = beta = NULL and FP_BIAS mode, (mult, fbias, offset) are the
+ * dequantization parameters that make the forward return Y_quant of Sec. 3.3. */
+cwac_status cwac_fold(const float *alpha, const float *beta, const float *s_w, const float *bias,
+                      const int32_t *colsum, int32_t n_out, const cwac_qparams *qp, float *mult,
+                      int32_t *offset, float *fbias, int32_t *n_saturated, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Quantized linear layer with the compensation in its epilogue - Eq. 10      */
+/* ------------------------------------------------------------------------- */
+
+enum { CWAC_OUT_INT8 = 0, CWAC_OUT_FP32 = 1, CWAC_OUT_INT32 = 2 };
+
+/* out = epilogue(x_q * w_q^T), int8 x int8 -> int32 on the matrix cores, the
+ * accumulators never leaving registers.  Per output element (m, n):
+ *   t = acc[m,n] + offset[n]                    int32        (offset NULL: 0)
+ *   f = (float)t                                round to nearest even
+ *   f = f * s_x_row[m]                          only if s_x_row != NULL
+ *   u = f * mult[n]
+ *   u = u + fbias[n]                            only if fbias != NULL
+ *   CWAC_OUT_INT8:  r = clamp(rint(u), qmin - Z_r, qmax - Z_r) in fp32;
+ *                   out = (int8)((int32)r + Z_r)               (Eq. 10, clip of Eq. 1)
+ *   CWAC_OUT_FP32:  out = u       (calibration forward: Y_quant, Sec. 3.3)
+ *   CWAC_OUT_INT32: out = t       (raw accumulator + offset; mult, fbias, s_x_row unused)
+ *
+ *   x_q   device int8 [m, k], ldx;  w_q device int8 [n, k], ldw (nn.Linear layout)
+ *   m >= 1, n >= 1, 16 <= k <= 32768, k % 16 == 0; x_q, w_q 16-byte aligned,
+ *   ldx % 16 == 0, ldw % 16 == 0
+ *   qp    host; supplies z_r, qmin, qmax for CWAC_OUT_INT8 (may be NULL otherwise)
+ *   mult  device fp32 [n] (required unless CWAC_OUT_INT32)
+ *   offset device int32 [n] or NULL; fbias device fp32 [n] or NULL;
+ *   s_x_row device fp32 [m] or NULL
+ *   out   device, element type per out_kind, [m, n] with leading dimension ldo >= n;
+ *         vectorized stores need out aligned to 16 bytes and ldo * sizeof(element)
+ *         a multiple of 16, other layouts take an element-wise store path */
+cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
+                                 int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
+                                 const float *mult, const int32_t *offset, const float *fbias,
+                                 const float *s_x_row, int32_t out_kind, void *out, int64_t ldo,
+                                 void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Un-fused comparators (what the fold removes; Sec. 3.3 last sentence,       */
+/* Sec. 3.4 first paragraph)                                                  */
+/* ------------------------------------------------------------------------- */
+
+/* The same epilogue as a separate pass over int32 accumulators in memory
+ * (4 bytes read + 1 written per element instead of none).
+ *   acc device int32 [m, n], ldacc; other arguments as in qlinear_cwac_forward;
+ *   out_kind CWAC_OUT_INT8 or CWAC_OUT_FP32 */
+cwac_status cwac_epilogue_int32(const int32_t *acc, int64_t ldacc, int64_t m, int32_t n,
+                                const cwac_qparams *qp, const float *mult, const int32_t *offset,
+                                const float *fbias, const float *s_x_row, int32_t out_kind,
+                                void *out, int64_t ldo, void *stream);
+
+/* The compensation as a separate module: out = alpha .* y + beta (two fp32
+ * roundings), y and out device fp32 [rows, c], may alias. */
+cwac_status cwac_apply_unfolded(const float *y, int64_t ldy, int64_t rows, int32_t c,
+                                const float *alpha, const float *beta, float *out, int64_t ldo,
+                                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CWAC_H_ */

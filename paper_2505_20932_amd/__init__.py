@@ -1,0 +1,15 @@
+"""MI355X-native hot path of QwT-v2: W8A8 quantized linear layer with the folded
+channel-wise affine compensation in its GEMM epilogue, and the calibration
+statistics / closed-form fit / fold that produce its parameters.
+
+``binding`` exposes the C-ABI entry points of libcwac_hip.so one to one;
+``synth`` draws the seeded synthetic workloads."""
+from . import synth  # noqa: F401
+from . import binding  # noqa: F401
+from .binding import (  # noqa: F401
+    CWAC_EPI_FP_BIAS, CWAC_EPI_INT_OFFSET, CWAC_OUT_FP32, CWAC_OUT_INT8, CWAC_OUT_INT32,
+    CwacError, cwac_apply_unfolded, cwac_calibrate_stats, cwac_calibrate_stats_workspace,
+    cwac_colsum, cwac_epilogue_int32, cwac_fold, cwac_qparams, cwac_qparams_from_range,
+    cwac_quantize_act, cwac_quantize_rows_sym, cwac_range_f32, cwac_range_workspace, cwac_solve,
+    cwac_stats_bytes, cwac_stats_reset, make_qparams, qlinear_cwac_forward,
+)

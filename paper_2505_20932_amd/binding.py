@@ -1,0 +1,218 @@
+"""Thin ctypes binding of libcwac_hip.so: one Python function per C entry point,
+same names, argument marshalling only.  torch supplies device memory and the
+stream handle; every step of the path runs in the library's HIP kernels.  There
+is no fallback: a missing library or an error status raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch  # imported first so that the library binds to torch's HIP runtime
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libcwac_hip.so")
+
+CWAC_OK = 0
+CWAC_EPI_INT_OFFSET, CWAC_EPI_FP_BIAS = 0, 1
+CWAC_OUT_INT8, CWAC_OUT_FP32, CWAC_OUT_INT32 = 0, 1, 2
+
+EXPORTS = (
+    "cwac_status_string", "cwac_range_workspace", "cwac_range_f32", "cwac_qparams_from_range",
+    "cwac_quantize_act", "cwac_quantize_rows_sym", "cwac_colsum", "cwac_stats_bytes",
+    "cwac_stats_reset", "cwac_calibrate_stats_workspace", "cwac_calibrate_stats", "cwac_solve",
+    "cwac_fold", "qlinear_cwac_forward", "cwac_epilogue_int32", "cwac_apply_unfolded",
+)
+
+
+class cwac_qparams(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("act_per_token", C.c_int32), ("s_x", C.c_float),
+                ("z_x", C.c_int32), ("s_r", C.c_float), ("z_r", C.c_int32),
+                ("qmin", C.c_int32), ("qmax", C.c_int32)]
+
+
+class CwacError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the HIP library built in-tree (see build.py); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise CwacError(f"{LIB_PATH} is missing: build it with "
+                            "`python -m paper_2505_20932_amd.build` (no fallback path exists)")
+        l = C.CDLL(LIB_PATH)
+        vp, i64, i32, f32, f64, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_double, C.c_size_t
+        qpp = C.POINTER(cwac_qparams)
+        sig = {
+            "cwac_status_string": (C.c_char_p, [i32]),
+            "cwac_range_workspace": (sz, [i64]),
+            "cwac_range_f32": (i32, [vp, i64, vp, vp, sz, vp]),
+            "cwac_qparams_from_range": (i32, [f32, f32, i32, C.POINTER(f32), C.POINTER(i32)]),
+            "cwac_quantize_act": (i32, [vp, i64, i64, i32, f32, i32, vp, i64, vp]),
+            "cwac_quantize_rows_sym": (i32, [vp, i64, i64, i32, vp, vp, i64, vp]),
+            "cwac_colsum": (i32, [vp, i64, i32, i32, vp, vp]),
+            "cwac_stats_bytes": (sz, [i32]),
+            "cwac_stats_reset": (i32, [vp, i32, vp]),
+            "cwac_calibrate_stats_workspace": (sz, [i64, i32]),
+            "cwac_calibrate_stats": (i32, [vp, i64, vp, i64, i64, i32, vp, vp, sz, vp]),
+            "cwac_solve": (i32, [vp, i32, f64, vp, vp, vp, vp, vp]),
+            "cwac_fold": (i32, [vp, vp, vp, vp, vp, i32, qpp, vp, vp, vp, vp, vp]),
+            "qlinear_cwac_forward": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp, vp, vp,
+                                           i32, vp, i64, vp]),
+            "cwac_epilogue_int32": (i32, [vp, i64, i64, i32, qpp, vp, vp, vp, vp, i32, vp, i64, vp]),
+            "cwac_apply_unfolded": (i32, [vp, i64, i64, i32, vp, vp, vp, i64, vp]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != CWAC_OK:
+        msg = lib().cwac_status_string(status).decode()
+        raise CwacError(f"{what}: {msg} ({status})")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda, "device tensor expected"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _rowmajor(t: torch.Tensor) -> int:
+    assert t.dim() == 2 and t.stride(1) == 1, "row-major 2-D tensor expected"
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def make_qparams(mode=CWAC_EPI_INT_OFFSET, act_per_token=False, s_x=1.0, z_x=0, s_r=1.0, z_r=0,
+                 qmin=-128, qmax=127) -> cwac_qparams:
+    return cwac_qparams(int(mode), int(bool(act_per_token)), float(s_x), int(z_x), float(s_r),
+                        int(z_r), int(qmin), int(qmax))
+
+
+# --------------------------------------------------------------------------- quantizers
+def cwac_range_workspace(count: int) -> int:
+    return int(lib().cwac_range_workspace(count))
+
+
+def cwac_range_f32(x: torch.Tensor, minmax: torch.Tensor, workspace: torch.Tensor, stream=None):
+    assert x.dtype == torch.float32 and x.is_contiguous() and minmax.dtype == torch.float32
+    _check(lib().cwac_range_f32(_ptr(x), x.numel(), _ptr(minmax), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)),
+           "cwac_range_f32")
+
+
+def cwac_qparams_from_range(mn: float, mx: float, bits: int = 8):
+    s, z = C.c_float(), C.c_int32()
+    _check(lib().cwac_qparams_from_range(mn, mx, bits, C.byref(s), C.byref(z)),
+           "cwac_qparams_from_range")
+    return s.value, z.value
+
+
+def cwac_quantize_act(x: torch.Tensor, s: float, z: int, q: torch.Tensor, stream=None):
+    assert x.dtype == torch.float32 and q.dtype == torch.int8 and x.shape == q.shape
+    _check(lib().cwac_quantize_act(_ptr(x), _rowmajor(x), x.shape[0], x.shape[1], s, z, _ptr(q),
+                                   _rowmajor(q), _stream(stream)), "cwac_quantize_act")
+
+
+def cwac_quantize_rows_sym(x: torch.Tensor, scale: torch.Tensor, q: torch.Tensor, stream=None):
+    assert x.dtype == torch.float32 and q.dtype == torch.int8 and scale.dtype == torch.float32
+    assert x.shape == q.shape and scale.numel() == x.shape[0]
+    _check(lib().cwac_quantize_rows_sym(_ptr(x), _rowmajor(x), x.shape[0], x.shape[1], _ptr(scale),
+                                        _ptr(q), _rowmajor(q), _stream(stream)),
+           "cwac_quantize_rows_sym")
+
+
+def cwac_colsum(w_q: torch.Tensor, colsum: torch.Tensor, stream=None):
+    assert w_q.dtype == torch.int8 and colsum.dtype == torch.int32
+    _check(lib().cwac_colsum(_ptr(w_q), _rowmajor(w_q), w_q.shape[0], w_q.shape[1], _ptr(colsum),
+                             _stream(stream)), "cwac_colsum")
+
+
+# --------------------------------------------------------------------------- calibration
+def cwac_stats_bytes(c_out: int) -> int:
+    return int(lib().cwac_stats_bytes(c_out))
+
+
+def cwac_stats_reset(stats: torch.Tensor, c_out: int, stream=None):
+    _check(lib().cwac_stats_reset(_ptr(stats), c_out, _stream(stream)), "cwac_stats_reset")
+
+
+def cwac_calibrate_stats_workspace(n_rows: int, c_out: int) -> int:
+    return int(lib().cwac_calibrate_stats_workspace(n_rows, c_out))
+
+
+def cwac_calibrate_stats(y_full: torch.Tensor, y_quant: torch.Tensor, stats: torch.Tensor,
+                         workspace: torch.Tensor, stream=None):
+    assert y_full.dtype == torch.float32 and y_quant.dtype == torch.float32
+    assert y_full.shape == y_quant.shape
+    n_rows, c_out = y_full.shape
+    _check(lib().cwac_calibrate_stats(_ptr(y_full), _rowmajor(y_full), _ptr(y_quant),
+                                      _rowmajor(y_quant), n_rows, c_out, _ptr(stats),
+                                      _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(),
+                                      _stream(stream)), "cwac_calibrate_stats")
+
+
+def cwac_solve(stats: torch.Tensor, c_out: int, alpha: torch.Tensor, beta: torch.Tensor,
+               moments: Optional[torch.Tensor] = None, n_degenerate: Optional[torch.Tensor] = None,
+               var_eps: float = 1e-12, stream=None):
+    assert alpha.dtype == torch.float32 and beta.dtype == torch.float32
+    assert moments is None or (moments.dtype == torch.float64 and moments.numel() == 5 * c_out)
+    _check(lib().cwac_solve(_ptr(stats), c_out, var_eps, _ptr(alpha), _ptr(beta), _ptr(moments),
+                            _ptr(n_degenerate), _stream(stream)), "cwac_solve")
+
+
+# --------------------------------------------------------------------------- fold
+def cwac_fold(alpha, beta, s_w, bias, colsum, qp: cwac_qparams, mult, offset, fbias=None,
+              n_saturated=None, stream=None):
+    _check(lib().cwac_fold(_ptr(alpha), _ptr(beta), _ptr(s_w), _ptr(bias), _ptr(colsum),
+                           s_w.numel(), C.byref(qp), _ptr(mult), _ptr(offset), _ptr(fbias),
+                           _ptr(n_saturated), _stream(stream)), "cwac_fold")
+
+
+# --------------------------------------------------------------------------- forward
+_OUT_DTYPE = {CWAC_OUT_INT8: torch.int8, CWAC_OUT_FP32: torch.float32, CWAC_OUT_INT32: torch.int32}
+
+
+def qlinear_cwac_forward(x_q: torch.Tensor, w_q: torch.Tensor, qp: Optional[cwac_qparams], mult,
+                         offset, fbias, s_x_row, out_kind: int, out: torch.Tensor, stream=None):
+    assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8
+    assert out.dtype == _OUT_DTYPE[out_kind]
+    m, k = x_q.shape
+    n, k2 = w_q.shape
+    assert k == k2 and out.shape == (m, n)
+    _check(lib().qlinear_cwac_forward(_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n,
+                                      k, C.byref(qp) if qp is not None else None, _ptr(mult),
+                                      _ptr(offset), _ptr(fbias), _ptr(s_x_row), out_kind, _ptr(out),
+                                      _rowmajor(out), _stream(stream)), "qlinear_cwac_forward")
+
+
+def cwac_epilogue_int32(acc: torch.Tensor, qp, mult, offset, fbias, s_x_row, out_kind: int,
+                        out: torch.Tensor, stream=None):
+    assert acc.dtype == torch.int32 and out.dtype == _OUT_DTYPE[out_kind]
+    m, n = acc.shape
+    _check(lib().cwac_epilogue_int32(_ptr(acc), _rowmajor(acc), m, n,
+                                     C.byref(qp) if qp is not None else None, _ptr(mult),
+                                     _ptr(offset), _ptr(fbias), _ptr(s_x_row), out_kind, _ptr(out),
+                                     _rowmajor(out), _stream(stream)), "cwac_epilogue_int32")
+
+
+def cwac_apply_unfolded(y: torch.Tensor, alpha, beta, out: torch.Tensor, stream=None):
+    assert y.dtype == torch.float32 and out.dtype == torch.float32 and y.shape == out.shape
+    _check(lib().cwac_apply_unfolded(_ptr(y), _rowmajor(y), y.shape[0], y.shape[1], _ptr(alpha),
+                                     _ptr(beta), _ptr(out), _rowmajor(out), _stream(stream)),
+           "cwac_apply_unfolded")

@@ -1,0 +1,348 @@
+// Quantized linear layer with the CWAC epilogue (Sec. 3.4, Eq. 10) for gfx950.
+//
+// acc = x_q * w_q^T on the int8 matrix cores (v_mfma_i32_32x32x32_i8), A/B
+// panels staged through LDS, the int32 accumulators kept in registers, and the
+// whole epilogue (offset add, int->fp32, multiplier, optional fp32 bias, round,
+// clamp, pack) applied to them in registers, so that compensation costs no
+// extra pass over memory.
+//
+// Operand orientation.  The MFMA computes D[i][j] = sum_k A[i][k] B[j][k] with a
+// lane owning one column j and, per 32x32 tile, 4 groups of 4 consecutive rows i.
+// Feeding the WEIGHT tile as A (i <-> output channel n) and the ACTIVATION tile
+// as B (j <-> token row m) makes every lane hold 4 consecutive output channels
+// of one token, which is exactly a packed 4 x int8 (or one float4) store into
+// the row-major [M, N] output.
+#include <stdlib.h>
+
+#include "cwac_internal.h"
+
+namespace cwac {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct FwdParams {
+  const int8_t *x;
+  const int8_t *w;
+  int64_t ldx, ldw, ldo;
+  int64_t m;
+  int n, k;
+  const float *mult;
+  const int32_t *offset;
+  const float *fbias;
+  const float *sx_row;
+  void *out;
+  float lo, hi;
+  int zr;
+  int vec_store;  // output layout allows 4-element vector stores
+  int tiles_m, tiles_n;
+};
+
+// LDS tile: ROWS x BK bytes, 16-byte chunks XOR-swizzled inside each row so that
+// the 16 lanes that read the same chunk index of 16 consecutive rows (one MFMA
+// operand fetch) and the 8 lanes that write one row hit distinct banks.
+template <int BK>
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+  constexpr int CPR = BK / 16;  // chunks per row
+  return row * BK + (((chunk ^ (row >> 1)) & (CPR - 1)) << 4);
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN>
+struct Tile {
+  static constexpr int NT = 64 * WGM * WGN;
+  static constexpr int WM = BM / WGM, WN = BN / WGN;
+  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int CPR = BK / 16;
+  static constexpr int XCH = BM * CPR / NT;  // 16-byte chunks per thread, activation tile
+  static constexpr int WCH = BN * CPR / NT;  // 16-byte chunks per thread, weight tile
+  static_assert(BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0, "wave tile must be whole MFMA tiles");
+  static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile must split evenly over threads");
+  static_assert(BK % 32 == 0 && CPR >= 2 && (CPR & (CPR - 1)) == 0, "BK must be a power of two >= 32");
+};
+
+// Workgroup id -> output tile.  Consecutive workgroup ids are dealt round-robin
+// to the 8 XCDs (each with its own L2), so ids are first regrouped so that every
+// XCD works on a contiguous range of tiles, and tiles are then walked in bands of
+// GROUP_M tile-rows so that the tiles in flight on one XCD share weight and
+// activation panels in its L2.
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn) {
+  const int total = tiles_m * tiles_n;
+  constexpr int XCDS = 8;
+  const int per = total / XCDS, rem = total - per * XCDS;
+  const int xcd = pid % XCDS, local = pid / XCDS;
+  // ids dealt to xcd: `per` of them, plus one more for the first `rem` xcds
+  const int start = xcd * per + (xcd < rem ? xcd : rem);
+  const int id = start + local;
+  constexpr int GROUP_M = 8;
+  const int band = GROUP_M * tiles_n;
+  const int g = id / band;
+  const int first_m = g * GROUP_M;
+  const int rows = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+  const int in = id - g * band;
+  tm = first_m + in % rows;
+  tn = in / rows;
+}
+
+template <int OUT_KIND, bool INT_ONLY>
+struct Epilogue {
+  // Applies Eq. 10 to 4 consecutive channels nn..nn+3 of row mm and stores them.
+  __device__ static __forceinline__ void run(const FwdParams &p, int64_t mm, int nn,
+                                             const int (&acc)[4], const float (&mu)[4],
+                                             const int (&off)[4], const float (&fb)[4],
+                                             float rs) {
+    if (OUT_KIND == CWAC_OUT_INT32) {
+      int t[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) t[r] = acc[r] + off[r];
+      int32_t *o = static_cast<int32_t *>(p.out) + mm * p.ldo + nn;
+      if (p.vec_store && nn + 3 < p.n) {
+        *reinterpret_cast<int4 *>(o) = make_int4(t[0], t[1], t[2], t[3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < p.n) o[r] = t[r];
+      }
+      return;
+    }
+    float u[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float f = (float)(acc[r] + off[r]);
+      if (!INT_ONLY) {
+        if (p.sx_row) f = f * rs;
+      }
+      float v = f * mu[r];
+      if (!INT_ONLY) {
+        if (p.fbias) v = v + fb[r];
+      }
+      u[r] = v;
+    }
+    if (OUT_KIND == CWAC_OUT_FP32) {
+      float *o = static_cast<float *>(p.out) + mm * p.ldo + nn;
+      if (p.vec_store && nn + 3 < p.n) {
+        *reinterpret_cast<float4 *>(o) = make_float4(u[0], u[1], u[2], u[3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < p.n) o[r] = u[r];
+      }
+    } else {
+      int c[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) c[r] = requant_code(u[r], p.lo, p.hi, p.zr);
+      int8_t *o = static_cast<int8_t *>(p.out) + mm * p.ldo + nn;
+      if (p.vec_store && nn + 3 < p.n) {
+        *reinterpret_cast<uint32_t *>(o) = (uint32_t)(c[0] & 0xff) | ((uint32_t)(c[1] & 0xff) << 8) |
+                                           ((uint32_t)(c[2] & 0xff) << 16) | ((uint32_t)c[3] << 24);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < p.n) o[r] = (int8_t)c[r];
+      }
+    }
+  }
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, int OUT_KIND, bool INT_ONLY>
+__global__ __launch_bounds__(64 * WGM * WGN) void qlinear_kernel(const FwdParams p) {
+  using T = Tile<BM, BN, BK, WGM, WGN>;
+  constexpr int NT = T::NT, TM = T::TM, TN = T::TN, CPR = T::CPR;
+
+  __shared__ __attribute__((aligned(16))) int8_t lds_x[BM * BK];
+  __shared__ __attribute__((aligned(16))) int8_t lds_w[BN * BK];
+
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int64_t bm0 = (int64_t)tile_m * BM;
+  const int bn0 = tile_n * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % WGM, wave_n = wave / WGM;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  // ---- global -> register staging: thread owns chunk (row, c) = (q / CPR, q % CPR), q = tid + i*NT
+  const int ld_c = tid % CPR;
+  const int ld_r = tid / CPR;
+  constexpr int RSTEP = NT / CPR;  // rows between a thread's successive chunks
+  const int8_t *xg[T::XCH];
+  const int8_t *wg[T::WCH];
+#pragma unroll
+  for (int i = 0; i < T::XCH; ++i) {
+    int64_t r = bm0 + ld_r + i * RSTEP;
+    if (r > p.m - 1) r = p.m - 1;  // rows past the edge re-read the last row; never stored
+    xg[i] = p.x + r * p.ldx + ld_c * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < T::WCH; ++i) {
+    int r = bn0 + ld_r + i * RSTEP;
+    if (r > p.n - 1) r = p.n - 1;
+    wg[i] = p.w + (int64_t)r * p.ldw + ld_c * 16;
+  }
+  v4i xr[T::XCH], wr[T::WCH];
+
+  auto load_stage = [&](int k0) {
+    const bool in_k = (k0 + ld_c * 16) < p.k;  // k % 16 == 0: a chunk is all in or all out
+#pragma unroll
+    for (int i = 0; i < T::XCH; ++i)
+      xr[i] = in_k ? *reinterpret_cast<const v4i *>(xg[i] + k0) : v4i{0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < T::WCH; ++i)
+      wr[i] = in_k ? *reinterpret_cast<const v4i *>(wg[i] + k0) : v4i{0, 0, 0, 0};
+  };
+  auto store_stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < T::XCH; ++i)
+      *reinterpret_cast<v4i *>(lds_x + lds_off<BK>(ld_r + i * RSTEP, ld_c)) = xr[i];
+#pragma unroll
+    for (int i = 0; i < T::WCH; ++i)
+      *reinterpret_cast<v4i *>(lds_w + lds_off<BK>(ld_r + i * RSTEP, ld_c)) = wr[i];
+  };
+
+  v16i acc[TN][TM];
+#pragma unroll
+  for (int a = 0; a < TN; ++a)
+#pragma unroll
+    for (int b = 0; b < TM; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0;
+
+  const int xrow0 = wave_m * T::WM + l32;
+  const int wrow0 = wave_n * T::WN + l32;
+
+  const int kt_count = (p.k + BK - 1) / BK;
+  load_stage(0);
+  for (int kt = 0; kt < kt_count; ++kt) {
+    store_stage();
+    __syncthreads();
+    if (kt + 1 < kt_count) load_stage((kt + 1) * BK);  // in flight while this stage is multiplied
+#pragma unroll
+    for (int kk = 0; kk < BK / 32; ++kk) {
+      const int chunk = 2 * kk + half;
+      v4i fw[TN], fx[TM];
+#pragma unroll
+      for (int a = 0; a < TN; ++a)
+        fw[a] = *reinterpret_cast<const v4i *>(lds_w + lds_off<BK>(wrow0 + a * 32, chunk));
+#pragma unroll
+      for (int b = 0; b < TM; ++b)
+        fx[b] = *reinterpret_cast<const v4i *>(lds_x + lds_off<BK>(xrow0 + b * 32, chunk));
+#pragma unroll
+      for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue on the register-resident accumulators -------------------------
+  // accumulator element 4*g + r of tile (a, b): channel n = bn0 + wave_n*WN + a*32 + 8*g + 4*half + r,
+  // token m = bm0 + wave_m*WM + b*32 + l32.
+#pragma unroll
+  for (int a = 0; a < TN; ++a) {
+    const int nb = bn0 + wave_n * T::WN + a * 32 + 4 * half;
+    float mu[4][4], fb[4][4];
+    int off[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        int idx = nb + 8 * g + r;
+        if (idx > p.n - 1) idx = p.n - 1;  // clamped read; such channels are never stored
+        off[g][r] = p.offset ? p.offset[idx] : 0;
+        mu[g][r] = (OUT_KIND != CWAC_OUT_INT32) ? p.mult[idx] : 0.0f;
+        fb[g][r] = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.fbias) ? p.fbias[idx] : 0.0f;
+      }
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+      const int64_t mm = bm0 + wave_m * T::WM + b * 32 + l32;
+      if (mm < p.m) {
+        const float rs = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.sx_row) ? p.sx_row[mm] : 1.0f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int nn = nb + 8 * g;
+          if (nn < p.n) {
+            const int av[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                               acc[a][b][4 * g + 3]};
+            Epilogue<OUT_KIND, INT_ONLY>::run(p, mm, nn, av, mu[g], off[g], fb[g], rs);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN>
+cwac_status launch_tile(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
+  p.tiles_m = (int)ceil_div(p.m, BM);
+  p.tiles_n = (int)ceil_div(p.n, BN);
+  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
+  if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
+  const dim3 grid((unsigned)blocks), block(64 * WGM * WGN);
+  if (out_kind == CWAC_OUT_INT8) {
+    if (int_only)
+      qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT8, true><<<grid, block, 0, st>>>(p);
+    else
+      qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT8, false><<<grid, block, 0, st>>>(p);
+  } else if (out_kind == CWAC_OUT_FP32) {
+    qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_FP32, false><<<grid, block, 0, st>>>(p);
+  } else {
+    qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT32, false><<<grid, block, 0, st>>>(p);
+  }
+  return launch_status();
+}
+
+}  // namespace
+}  // namespace cwac
+
+using namespace cwac;
+
+extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                            int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                            const cwac_qparams *qp, const float *mult,
+                                            const int32_t *offset, const float *fbias,
+                                            const float *s_x_row, int32_t out_kind, void *out,
+                                            int64_t ldo, void *stream) {
+  if (!x_q || !w_q || !out) return CWAC_E_NULL;
+  if (out_kind != CWAC_OUT_INT8 && out_kind != CWAC_OUT_FP32 && out_kind != CWAC_OUT_INT32)
+    return CWAC_E_MODE;
+  if (out_kind != CWAC_OUT_INT32 && !mult) return CWAC_E_NULL;
+  if (m < 1 || m > ((int64_t)1 << 40) || n < 1 || k < 16 || k > 32768 || (k % 16) != 0)
+    return CWAC_E_SHAPE;
+  if (ldx < k || ldw < k || ldo < n) return CWAC_E_SHAPE;
+  if (!aligned(x_q, 16) || !aligned(w_q, 16) || (ldx % 16) != 0 || (ldw % 16) != 0)
+    return CWAC_E_ALIGN;
+  FwdParams p;
+  p.x = x_q; p.w = w_q; p.ldx = ldx; p.ldw = ldw; p.ldo = ldo;
+  p.m = m; p.n = n; p.k = k;
+  p.mult = mult; p.offset = offset; p.fbias = fbias; p.sx_row = s_x_row; p.out = out;
+  p.lo = p.hi = 0.0f; p.zr = 0;
+  if (out_kind == CWAC_OUT_INT8) {
+    if (!qp) return CWAC_E_NULL;
+    if (qp->qmin < -128 || qp->qmax > 127 || qp->qmin > qp->qmax) return CWAC_E_SHAPE;
+    if (qp->z_r < -(1 << 20) || qp->z_r > (1 << 20)) return CWAC_E_SHAPE;
+    p.zr = qp->z_r;
+    p.lo = (float)(qp->qmin - qp->z_r);
+    p.hi = (float)(qp->qmax - qp->z_r);
+  }
+  const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
+  if (!aligned(out, esz)) return CWAC_E_ALIGN;
+  p.vec_store = ((ldo * esz) % (4 * esz) == 0) && aligned(out, 4 * esz);
+  const bool int_only = (out_kind == CWAC_OUT_INT8) && !fbias && !s_x_row;
+  hipStream_t st = as_stream(stream);
+
+  // Tile choice: the largest tile that still gives the 256 compute units at least
+  // two workgroups each; small problems fall back to small tiles.
+  const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
+  const int64_t t128 = ceil_div(m, 128) * ceil_div(n, 128);
+  int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
+  // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a tile shape (results are identical).
+  if (const char *e = getenv("CWAC_FWD_TILE")) {
+    const int v = atoi(e);
+    if (v == 256 || v == 128 || v == 64) tile = v;
+  }
+  if (tile == 256) return launch_tile<256, 256, 128, 2, 2>(p, out_kind, int_only, st);
+  if (tile == 128) return launch_tile<128, 128, 128, 2, 2>(p, out_kind, int_only, st);
+  return launch_tile<64, 64, 128, 2, 2>(p, out_kind, int_only, st);
+}

@@ -1,0 +1,98 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the public header declares, rejects bad arguments before launching
+anything, and its host-side Eq. 2 agrees with the oracle bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2505_20932_amd as P
+from paper_2505_20932_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cwac.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b(?:cwac_status|size_t|const char \*)\s*\*?\s*(\w+)\s*\(", text)
+    return sorted(set(names))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2505_20932_amd import build
+        build.build_library(verbose=False)
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    declared = _declared_functions()
+    assert "qlinear_cwac_forward" in declared and "cwac_calibrate_stats" in declared
+    assert "cwac_solve" in declared and "cwac_fold" in declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in cwac.h but not exported"
+    assert sorted(binding.EXPORTS) == declared
+    for name in declared:                       # the Python binding carries the same names
+        if name != "cwac_status_string":
+            assert hasattr(P, name) or hasattr(binding, name)
+
+
+def test_status_strings(lib):
+    for code in range(0, -7, -1):
+        s = lib.cwac_status_string(code)
+        assert s and s != b"unknown status"
+    assert lib.cwac_status_string(-99) == b"unknown status"
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(binding.cwac_qparams) == 32
+    assert binding.cwac_qparams.s_r.offset == 16 and binding.cwac_qparams.qmax.offset == 28
+
+
+def test_sizes(lib):
+    assert P.cwac_stats_bytes(1152) == 64 + 48 * 1152
+    assert P.cwac_stats_bytes(0) == 0
+    assert P.cwac_calibrate_stats_workspace(6304, 1152) >= 5 * 8 * 1152
+    assert P.cwac_range_workspace(10) > 0
+
+
+def test_argument_errors_launch_nothing(lib):
+    qp = binding.make_qparams()
+    null = None
+    # NULL pointers
+    assert lib.qlinear_cwac_forward(null, 16, null, 16, 1, 1, 16, C.byref(qp), null, null, null,
+                                    null, 0, null, 1, null) == -1
+    assert lib.cwac_calibrate_stats(null, 4, null, 4, 4, 4, null, null, 0, null) == -1
+    assert lib.cwac_fold(null, null, null, null, null, 4, C.byref(qp), null, null, null, null,
+                         null) == -1
+    assert lib.cwac_solve(null, 4, 1e-12, null, null, null, null, null) == -1
+    # shapes / alignment / modes are checked with fake (never dereferenced) addresses
+    a = C.c_void_p(4096)
+    assert lib.qlinear_cwac_forward(a, 24, a, 24, 4, 4, 24, C.byref(qp), a, a, null, null, 0, a, 4,
+                                    null) == -2          # k % 16 != 0
+    assert lib.qlinear_cwac_forward(a, 32, a, 32, 4, 4, 32, C.byref(qp), a, a, null, null, 7, a, 4,
+                                    null) == -4          # unknown out_kind
+    assert lib.qlinear_cwac_forward(C.c_void_p(4100), 32, a, 32, 4, 4, 32, C.byref(qp), a, a, null,
+                                    null, 0, a, 4, null) == -3   # misaligned x_q
+    assert lib.qlinear_cwac_forward(a, 32, a, 32, 4, 4, 65536, C.byref(qp), a, a, null, null, 0, a,
+                                    4, null) == -2       # k too large for int32 accumulation
+    bad = binding.make_qparams(mode=0, act_per_token=True)
+    assert lib.cwac_fold(null, null, a, null, a, 4, C.byref(bad), a, a, null, null, null) == -4
+    assert lib.cwac_calibrate_stats(a, 4, a, 4, 8, 4, a, null, 0, null) == -5   # no workspace
+    assert lib.cwac_calibrate_stats(a, 4, a, 4, 0, 4, a, null, 0, null) == 0    # empty batch: no-op
+    assert lib.cwac_calibrate_stats(a, 2, a, 4, 8, 4, a, a, 1 << 20, null) == -2  # ld < c_out
+
+
+def test_eq2_host_function_matches_oracle(orc, lib):
+    x = synth.normal(5, 0, 1000).numpy()
+    cases = [(-64.0, 191.0), (float(x.min()), float(x.max())), (0.0, 0.0), (-1e-3, 7.5),
+             (3.0, 4.0), (-9.0, -2.0)]
+    for bits in (4, 6, 8):
+        for mn, mx in cases:
+            s, z = P.cwac_qparams_from_range(mn, mx, bits)
+            s0, z0 = orc.qparams_asym(mn, mx, bits)
+            assert np.float32(s) == s0 and z == z0, (mn, mx, bits)
