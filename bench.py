@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the QwT-v2 hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic batch, for every
+linear layer of the workload:
+    calibration forward (int8 GEMM -> fp32 Y_quant)      qlinear_cwac_forward, fp32 out
+    per-channel statistics of (Y_full, Y_quant)          cwac_stats_reset + cwac_calibrate_stats
+    closed-form fit                                      cwac_solve
+    fold into the engine parameters                      cwac_fold
+    inference forward (int8 GEMM + CWAC epilogue -> int8) qlinear_cwac_forward, int8 out
+All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "W8A8 GEMM+CWAC epilogue TOPS (% int8 MFMA peak); calib stats GB/s (% HBM)"
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+class LayerState:
+    pass
+
+
+def setup_layers(P, synth, torch, cfg: int, dev: str, cal_rows: int):
+    """Synthetic fp32 tensors of the workload -> device-resident quantized inputs.
+    Quantization and parameter preparation run in the library's own kernels; the
+    full-precision layer output Y_full is upstream of the path (torch fp32 matmul)."""
+    wl = synth.WORKLOADS[cfg]
+    layers = []
+    for li, ly in enumerate(wl.layers):
+        L = LayerState()
+        L.name, L.n, L.k, L.m, L.cal_rows = ly.name, ly.n, ly.k, wl.m, cal_rows
+        w, b = synth.weights(wl, li, device=dev)
+        x = synth.activations(wl, li, wl.m, device=dev)
+        xcal = synth.activations(wl, li, cal_rows, calibration=True, device=dev)
+        L.bias = b
+        L.wq = torch.empty(ly.n, ly.k, dtype=torch.int8, device=dev)
+        L.sw = torch.empty(ly.n, dtype=torch.float32, device=dev)
+        P.cwac_quantize_rows_sym(w, L.sw, L.wq)
+        L.colsum = torch.empty(ly.n, dtype=torch.int32, device=dev)
+        P.cwac_colsum(L.wq, L.colsum)
+        L.xq = torch.empty(wl.m, ly.k, dtype=torch.int8, device=dev)
+        L.xq_cal = torch.empty(cal_rows, ly.k, dtype=torch.int8, device=dev)
+        if wl.per_token:
+            L.sx_row = torch.empty(wl.m, dtype=torch.float32, device=dev)
+            L.sx_row_cal = torch.empty(cal_rows, dtype=torch.float32, device=dev)
+            P.cwac_quantize_rows_sym(x, L.sx_row, L.xq)
+            P.cwac_quantize_rows_sym(xcal, L.sx_row_cal, L.xq_cal)
+            L.sx, L.zx = 1.0, 0
+        else:
+            mm = torch.empty(2, dtype=torch.float32, device=dev)
+            ws = torch.empty(P.cwac_range_workspace(xcal.numel()), dtype=torch.uint8, device=dev)
+            P.cwac_range_f32(xcal, mm, ws)
+            mn, mx = (float(v) for v in mm.cpu())
+            L.sx, z_u = P.cwac_qparams_from_range(mn, mx, 8)
+            L.zx = z_u - 128
+            P.cwac_quantize_act(x, L.sx, L.zx, L.xq)
+            P.cwac_quantize_act(xcal, L.sx, L.zx, L.xq_cal)
+            L.sx_row = L.sx_row_cal = None
+        L.y_full = xcal @ w.t()
+        if b is not None:
+            L.y_full += b
+        # output quantization parameters: Eq. 2 on the full-precision output range (stand-in for
+        # the compensated output's range, which it approximates by construction of the fit)
+        mm = torch.empty(2, dtype=torch.float32, device=dev)
+        ws = torch.empty(P.cwac_range_workspace(L.y_full.numel()), dtype=torch.uint8, device=dev)
+        P.cwac_range_f32(L.y_full, mm, ws)
+        mn, mx = (float(v) for v in mm.cpu())
+        L.sr, zr_u = P.cwac_qparams_from_range(mn, mx, 8)
+        L.zr = zr_u - 128
+        L.per_token = wl.per_token
+        mode = P.CWAC_EPI_FP_BIAS if wl.per_token else P.CWAC_EPI_INT_OFFSET
+        L.qp = P.make_qparams(mode, wl.per_token, L.sx, L.zx, L.sr, L.zr)
+        L.qp_deq = P.make_qparams(P.CWAC_EPI_FP_BIAS, wl.per_token, L.sx, L.zx, 1.0, 0)
+        f32 = dict(dtype=torch.float32, device=dev)
+        L.deq_mult, L.deq_fb = torch.empty(ly.n, **f32), torch.empty(ly.n, **f32)
+        L.deq_off = torch.empty(ly.n, dtype=torch.int32, device=dev)
+        P.cwac_fold(None, None, L.sw, L.bias, L.colsum, L.qp_deq, L.deq_mult, L.deq_off, L.deq_fb)
+        L.mult, L.fbias = torch.empty(ly.n, **f32), torch.empty(ly.n, **f32)
+        L.offset = torch.empty(ly.n, dtype=torch.int32, device=dev)
+        L.alpha, L.beta = torch.empty(ly.n, **f32), torch.empty(ly.n, **f32)
+        L.stats = torch.empty(P.cwac_stats_bytes(ly.n) // 8 + 2, dtype=torch.float64, device=dev)
+        L.ws = torch.empty(P.cwac_calibrate_stats_workspace(cal_rows, ly.n), dtype=torch.uint8,
+                           device=dev)
+        del w, x, xcal
+        layers.append(L)
+    n_max = max(L.n for L in layers)
+    yq_buf = torch.empty(cal_rows * n_max, dtype=torch.float32, device=dev)
+    out_buf = torch.empty(wl.m * n_max, dtype=torch.int8, device=dev)
+    for L in layers:
+        L.yq = yq_buf[:cal_rows * L.n].view(cal_rows, L.n)
+        L.out = out_buf[:wl.m * L.n].view(wl.m, L.n)
+    torch.cuda.synchronize()
+    return wl, layers
+
+
+def run_step(P, layers, ev=None):
+    """One pass of the hot path.  ev (optional): list that receives per-layer event tuples."""
+    import torch
+    for L in layers:
+        if ev is not None:
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+            e[0].record()
+        P.qlinear_cwac_forward(L.xq_cal, L.wq, None, L.deq_mult, L.deq_off,
+                               L.deq_fb if L.bias is not None else None, L.sx_row_cal,
+                               P.CWAC_OUT_FP32, L.yq)
+        if ev is not None:
+            e[1].record()
+        P.cwac_stats_reset(L.stats, L.n)
+        P.cwac_calibrate_stats(L.y_full, L.yq, L.stats, L.ws)
+        if ev is not None:
+            e[2].record()
+        P.cwac_solve(L.stats, L.n, L.alpha, L.beta)
+        P.cwac_fold(L.alpha, L.beta, L.sw, L.bias, L.colsum, L.qp, L.mult, L.offset, L.fbias)
+        if ev is not None:
+            e[3].record()
+        if L.per_token:
+            P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, L.fbias, L.sx_row,
+                                   P.CWAC_OUT_INT8, L.out)
+        else:
+            P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, None, None,
+                                   P.CWAC_OUT_INT8, L.out)
+        if ev is not None:
+            e[4].record()
+            ev.append(e)
+
+
+def cpu_baseline(synth, cfg: int, sample_rows: int):
+    """The oracle, as it stands, timed on this host on a bounded row sample of the same step."""
+    import numpy as np
+    from oracle import cwac_oracle as orc
+    wl = synth.WORKLOADS[cfg]
+    ops = 0.0
+    t_total = 0.0
+    for li, ly in enumerate(wl.layers):
+        w, b = synth.weights(wl, li)
+        w = w.numpy()
+        b = None if b is None else b.numpy()
+        x = synth.activations(wl, li, sample_rows).numpy()
+        xcal = synth.activations(wl, li, sample_rows, calibration=True).numpy()
+        y_full = (xcal @ w.T + (0 if b is None else b[None, :])).astype(np.float32)  # upstream
+        wq, sw = orc.quantize_rows_sym(w)                                            # setup
+        colsum = orc.colsum_i8(wq)
+        if wl.per_token:
+            xq, sxr = orc.quantize_rows_sym(x)
+            xqc, sxrc = orc.quantize_rows_sym(xcal)
+            sx, zx, deq = np.float32(1.0), 0, sw
+        else:
+            mn, mx = orc.range_f32(xcal)
+            sx, z_u = orc.qparams_asym(mn, mx, 8)
+            zx = z_u - 128
+            xq, xqc = orc.quantize_act_i8(x, sx, zx), orc.quantize_act_i8(xcal, sx, zx)
+            sxr = sxrc = None
+            deq = orc.deq_scale(sw, sx)
+        mn, mx = orc.range_f32(y_full)
+        sr, zr_u = orc.qparams_asym(mn, mx, 8)
+        t0 = time.perf_counter()                                                      # the step
+        acc_c = orc.gemm_i8(xqc, wq)
+        yq = orc.dequant_output(acc_c, colsum, zx, deq, b, sxrc)
+        mom = orc.channel_moments(y_full, yq)
+        alpha, beta, _ = orc.solve(mom)
+        if wl.per_token:
+            mult, fb, off = orc.fold_fp_bias(alpha, beta, sw, b, colsum, True, sx, zx, sr)
+        else:
+            mult, off, _ = orc.fold_int_offset(alpha, beta, sw, b, colsum, sx, zx, sr)
+            fb = None
+        acc = orc.gemm_i8(xq, wq)
+        orc.folded_forward(acc, off, mult, zr_u - 128, fb, sxr)
+        t_total += time.perf_counter() - t0
+        ops += 2.0 * 2.0 * sample_rows * ly.n * ly.k
+    return ops / t_total / 1e12, orc.get_threads(), t_total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the LLM layer)")
+    ap.add_argument("--cal-rows", type=int, default=0, help="calibration rows per step (default: "
+                    "one batch = the workload's token count)")
+    ap.add_argument("--cpu-sample-rows", type=int, default=512)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of "
+              "it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2505_20932_amd as P
+    from paper_2505_20932_amd import synth
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    P.binding.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.config]
+    cal_rows = args.cal_rows or wl.m
+    wl, layers = setup_layers(P, synth, torch, args.config, dev, cal_rows)
+
+    for _ in range(args.warmup):
+        run_step(P, layers)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step(P, layers, events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    gemm_ops = sum(2.0 * (L.m + L.cal_rows) * L.n * L.k for L in layers)      # both GEMMs of a step
+    fwd_ops = sum(2.0 * L.m * L.n * L.k for L in layers)
+    stats_bytes = sum(8.0 * L.cal_rows * L.n for L in layers)
+    ms_step = elapsed / args.steps * 1e3
+    t_cal = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps         # ms per step
+    t_stats = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+    t_fit = sum(e[2].elapsed_time(e[3]) for e in events) / args.steps
+    t_fwd = sum(e[3].elapsed_time(e[4]) for e in events) / args.steps
+    fwd_tops = fwd_ops / (t_fwd * 1e-3) / 1e12
+    stats_gbs = stats_bytes / (t_stats * 1e-3) / 1e9
+    nl = len(layers)
+    result = {
+        "metric": METRIC, "value": round(gemm_ops / (elapsed / args.steps) / 1e12, 2),
+        "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"config {wl.cfg}: {wl.name}, {nl} linear layers, M={wl.m} tokens, "
+                               f"{cal_rows} calibration rows per step, "
+                               + ("per-token" if wl.per_token else "per-tensor") + " activations",
+                   "layers": [f"{L.name} {L.n}x{L.k}" for L in layers]},
+        "roofline": {"bound": "mfma", "achieved": round(fwd_tops / 1e3, 4),
+                     "peak": INT8_MFMA_PEAK_TOPS / 1e3, "unit": "POP/s",
+                     "frac": round(fwd_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                     "kernel": "qlinear_kernel (int8 out, fused CWAC epilogue)",
+                     "launches_per_step": nl, "avg_launch_ms": round(t_fwd / nl, 4),
+                     "ops_per_step": fwd_ops},
+        "roofline_stats": {"bound": "hbm", "achieved": round(stats_gbs, 1), "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": round(stats_gbs / HBM_PEAK_GBS, 4),
+                           "traffic": None, "kernel": "stats_partial_kernel (+merge, commit, reset)",
+                           "avg_launch_ms": round(t_stats / nl, 4), "bytes_per_step": stats_bytes},
+        "phases_ms": {"calibration_forward_fp32": round(t_cal, 4), "statistics": round(t_stats, 4),
+                      "solve_fold": round(t_fit, 4), "forward_int8": round(t_fwd, 4)},
+        "forward_int8_tops": round(fwd_tops, 2),
+        "calibration_forward_tops": round(
+            sum(2.0 * L.cal_rows * L.n * L.k for L in layers) / (t_cal * 1e-3) / 1e12, 2),
+        "stats_gbs": round(stats_gbs, 1),
+    }
+    if not args.no_cpu_baseline:
+        v, cores, secs = cpu_baseline(synth, args.config, args.cpu_sample_rows)
+        result["cpu_baseline"] = {
+            "value": round(v, 5), "unit": "TOPS", "cores": cores, "kind": "oracle",
+            "sample": f"the same step on {args.cpu_sample_rows} inference rows and "
+                      f"{args.cpu_sample_rows} calibration rows of every layer "
+                      f"({secs:.1f} s of oracle time)"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
