@@ -214,6 +214,38 @@ def test_forward_ragged_shapes(orc, m, n, k):
             np.testing.assert_array_equal(got[:, :n], want)
 
 
+@pytest.mark.parametrize("m,n,k", [(256, 256, 128), (300, 520, 384), (700, 1030, 1152),
+                                   (513, 768, 256)])
+def test_forward_large_tile_kernel(orc, m, n, k):
+    """The 256 x 256 direct-to-LDS kernel (forced): edge tiles overlap their neighbours
+    instead of being predicated; N not a multiple of 4 takes the element-wise stores."""
+    g = synth.normal(700 + m, 0, m * k).numpy().reshape(m, k)
+    xq = np.clip(np.rint(g * 60), -128, 127).astype(np.int8)
+    g = synth.normal(700 + m, 1, n * k).numpy().reshape(n, k)
+    wq = np.clip(np.rint(g * 60), -127, 127).astype(np.int8)
+    acc = orc.gemm_i8(xq, wq)
+    mult = (np.abs(synth.normal(700 + m, 2, n).numpy()) * 1e-3 + 1e-4).astype(np.float32)
+    off = np.rint(synth.normal(700 + m, 3, n).numpy() * 500).astype(np.int32)
+    fb = synth.normal(700 + m, 4, n).numpy().astype(np.float32)
+    sxr = (np.abs(synth.normal(700 + m, 5, m).numpy()) + 0.5).astype(np.float32)
+    from types import SimpleNamespace
+    c = SimpleNamespace(xq=xq, wq=wq, n=n)
+    qp = P.make_qparams(z_r=5)
+    for ldo in (None, n + 5):
+        got = _forward(c, P.CWAC_OUT_INT32, tile="fast", ldo=ldo)
+        np.testing.assert_array_equal(got[:, :n], acc)
+        if ldo:
+            assert np.all(got[:, n:] == 77)
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, tile="fast", ldo=ldo)
+        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5))
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qp, tile="fast",
+                       ldo=ldo)
+        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5, fb, sxr))
+        _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)
+        got = _forward(c, P.CWAC_OUT_FP32, mult, off, fbias=fb, sx_row=sxr, tile="fast", ldo=ldo)
+        np.testing.assert_array_equal(got[:, :n], want)
+
+
 def test_forward_extreme_codes(orc):
     """All-extreme operands at the largest supported K: |acc| reaches K * 128 * 127."""
     m, n, k = 64, 96, 11008
