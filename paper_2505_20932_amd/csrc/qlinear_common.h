@@ -1,0 +1,160 @@
+// Pieces shared by the quantized-linear forward kernels: parameter block, workgroup -> tile
+// mapping, and the reference form of the Eq. 10 epilogue on register-resident accumulators.
+#pragma once
+
+#include "cwac_internal.h"
+
+namespace cwac {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+struct FwdParams {
+  const int8_t *x;
+  const int8_t *w;
+  int64_t ldx, ldw, ldo;
+  int64_t m;
+  int n, k;
+  const float *mult;
+  const int32_t *offset;
+  const float *fbias;
+  const float *sx_row;
+  void *out;
+  float lo, hi;
+  int zr;
+  int vec_store;  // output layout allows 4-element vector stores
+  int tiles_m, tiles_n;
+};
+
+// Workgroup id -> output tile.  Consecutive workgroup ids are dealt round-robin
+// to the 8 XCDs (each with its own L2), so ids are first regrouped so that every
+// XCD works on a contiguous range of tiles, and tiles are then walked in bands of
+// GROUP_M tile-rows so that the tiles in flight on one XCD share weight and
+// activation panels in its L2.
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn) {
+  const int total = tiles_m * tiles_n;
+  constexpr int XCDS = 8;
+  const int per = total / XCDS, rem = total - per * XCDS;
+  const int xcd = pid % XCDS, local = pid / XCDS;
+  // ids dealt to xcd: `per` of them, plus one more for the first `rem` xcds
+  const int start = xcd * per + (xcd < rem ? xcd : rem);
+  const int id = start + local;
+  constexpr int GROUP_M = 8;
+  const int band = GROUP_M * tiles_n;
+  const int g = id / band;
+  const int first_m = g * GROUP_M;
+  const int rows = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+  const int in = id - g * band;
+  tm = first_m + in % rows;
+  tn = in / rows;
+}
+
+template <int OUT_KIND, bool INT_ONLY>
+struct Epilogue {
+  // Applies Eq. 10 to 4 consecutive channels nn..nn+3 of row mm and stores them.
+  __device__ static __forceinline__ void run(const FwdParams &p, int64_t mm, int nn,
+                                             const int (&acc)[4], const float (&mu)[4],
+                                             const int (&off)[4], const float (&fb)[4],
+                                             float rs) {
+    if (OUT_KIND == CWAC_OUT_INT32) {
+      int t[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) t[r] = acc[r] + off[r];
+      int32_t *o = static_cast<int32_t *>(p.out) + mm * p.ldo + nn;
+      if (p.vec_store && nn + 3 < p.n) {
+        *reinterpret_cast<int4 *>(o) = make_int4(t[0], t[1], t[2], t[3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < p.n) o[r] = t[r];
+      }
+      return;
+    }
+    float u[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float f = (float)(acc[r] + off[r]);
+      if (!INT_ONLY) {
+        if (p.sx_row) f = f * rs;
+      }
+      float v = f * mu[r];
+      if (!INT_ONLY) {
+        if (p.fbias) v = v + fb[r];
+      }
+      u[r] = v;
+    }
+    if (OUT_KIND == CWAC_OUT_FP32) {
+      float *o = static_cast<float *>(p.out) + mm * p.ldo + nn;
+      if (p.vec_store && nn + 3 < p.n) {
+        *reinterpret_cast<float4 *>(o) = make_float4(u[0], u[1], u[2], u[3]);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < p.n) o[r] = u[r];
+      }
+    } else {
+      int c[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) c[r] = requant_code(u[r], p.lo, p.hi, p.zr);
+      int8_t *o = static_cast<int8_t *>(p.out) + mm * p.ldo + nn;
+      if (p.vec_store && nn + 3 < p.n) {
+        *reinterpret_cast<uint32_t *>(o) = (uint32_t)(c[0] & 0xff) | ((uint32_t)(c[1] & 0xff) << 8) |
+                                           ((uint32_t)(c[2] & 0xff) << 16) | ((uint32_t)c[3] << 24);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < p.n) o[r] = (int8_t)c[r];
+      }
+    }
+  }
+};
+
+// Epilogue over a wave's TN x TM accumulator tiles.  Accumulator element 4*g + r of
+// tile (a, b) belongs to channel n = n0 + a*32 + 8*g + 4*half + r and token
+// m = m0 + b*32 + l32 (n0, m0: first channel / token of the wave tile).
+template <int TM, int TN, int OUT_KIND, bool INT_ONLY>
+__device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[TN][TM], int64_t m0,
+                                               int n0, int l32, int half, int vec_store) {
+  FwdParams q = p;
+  q.vec_store = vec_store;
+#pragma unroll
+  for (int a = 0; a < TN; ++a) {
+    const int nb = n0 + a * 32 + 4 * half;
+    float mu[4][4], fb[4][4];
+    int off[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        int idx = nb + 8 * g + r;
+        if (idx > p.n - 1) idx = p.n - 1;  // clamped read; such channels are never stored
+        off[g][r] = p.offset ? p.offset[idx] : 0;
+        mu[g][r] = (OUT_KIND != CWAC_OUT_INT32) ? p.mult[idx] : 0.0f;
+        fb[g][r] = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.fbias) ? p.fbias[idx] : 0.0f;
+      }
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+      const int64_t mm = m0 + b * 32 + l32;
+      if (mm < p.m) {
+        const float rs = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.sx_row) ? p.sx_row[mm] : 1.0f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int nn = nb + 8 * g;
+          if (nn < p.n) {
+            const int av[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                               acc[a][b][4 * g + 3]};
+            Epilogue<OUT_KIND, INT_ONLY>::run(q, mm, nn, av, mu[g], off[g], fb[g], rs);
+          }
+        }
+      }
+    }
+  }
+}
+
+
+// Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 256, k % 128 == 0.
+cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st);
+constexpr int kFastTile = 256;
+constexpr int kFastKStep = 128;
+
+}  // namespace cwac

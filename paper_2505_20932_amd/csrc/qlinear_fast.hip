@@ -1,0 +1,404 @@
+// Large-problem kernel of the quantized linear layer with the CWAC epilogue (Sec. 3.4,
+// Eq. 10): 256 x 256 output tile, four wavefronts (2 x 2, each 128 x 128 = 4 x 4 MFMA tiles,
+// 256 int32 accumulators per lane), one workgroup per compute unit.
+//
+//   * Panels go global -> LDS directly (global_load_lds_dwordx4, no register staging).  One
+//     wavefront load lands as 1 KiB of contiguous LDS, so the bank swizzle is applied on the
+//     GLOBAL side: lane (row r, slot p) fetches chunk p ^ swz(r) of its row.
+//   * A ring of NSTAGE LDS stages of BK bytes of K; the loads of stage s + NSTAGE are issued as
+//     soon as every wavefront has fetched its last fragments of stage s; one barrier per stage,
+//     NSTAGE - 1 stages of loads in flight behind the MFMAs.
+//   * MFMA operand fragments are double-buffered in registers; the LDS reads of step kk + 1 are
+//     interleaved with the MFMAs of step kk.
+//   * The epilogue parameters of the tile's 256 channels (and the 256 row scales) are staged in
+//     LDS while the first panels are in flight; accumulators START at offset[n], so the integer
+//     offset add of Eq. 10 costs nothing, and rounding uses one fp32 add of 1.5 * 2^23, which
+//     rounds half to even exactly like rint for the clamped (|x| < 2^22) values it sees.
+//
+// Requires m >= 256, n >= 256, k % BK == 0.  Edge tiles are shifted inwards to overlap their
+// neighbours (identical values are written twice) instead of being predicated.
+#include <stdlib.h>
+
+#include "qlinear_common.h"
+
+namespace cwac {
+namespace {
+
+#define CWAC_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define CWAC_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
+  // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14 ; expcnt = 7 (no wait)
+  return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
+}
+
+template <int BK, int NSTAGE>
+struct FastCfg {
+  static constexpr int BM = 256, BN = 256;
+  static constexpr int KK = BK / 32;  // MFMA k-steps per stage
+  static constexpr int X_BYTES = BM * BK, W_BYTES = BN * BK, STAGE = X_BYTES + W_BYTES;
+  static constexpr int RING = NSTAGE * STAGE;
+  static constexpr int PARAM_BYTES = 4 * 256 * 4;  // offset, mult, fbias [256 channels], row scale [256 rows]
+  static constexpr int LDS_BYTES = RING + PARAM_BYTES;
+  static constexpr int CPR = BK / 16;        // 16-byte chunks per row
+  static constexpr int RPL = 64 / CPR;       // rows covered by one wavefront load
+  static constexpr int LOADS = 64 / RPL;     // loads per wavefront, panel and stage
+  static constexpr int LPS = 2 * LOADS;      // loads per wavefront and stage
+  static_assert(BK == 64 || BK == 128, "K step");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one compute unit");
+  static_assert((NSTAGE - 1) * LPS < 64, "vmcnt is a 6-bit counter");
+  // swizzle of the 16-byte chunk position inside a row, a function of the row's low 4 bits
+  __host__ __device__ static constexpr int swz(int r) {
+    return BK == 128 ? ((r >> 1) & 7) : (((r >> 2) & 1) | ((((r >> 1) ^ (r >> 3)) & 1) << 1));
+  }
+};
+
+__device__ __forceinline__ uint32_t pack4(int b0, int b1, int b2, int b3) {
+  const uint32_t t01 = __builtin_amdgcn_perm((uint32_t)b1, (uint32_t)b0, 0x0c0c0400u);
+  const uint32_t t23 = __builtin_amdgcn_perm((uint32_t)b3, (uint32_t)b2, 0x0c0c0400u);
+  return __builtin_amdgcn_perm(t23, t01, 0x05040100u);
+}
+
+// Epilogue (Eq. 10) on the register-resident accumulators, which already hold acc + offset.
+// Element 4*g + r of tile (a, b): channel n = bn0 + wave_n*128 + a*32 + 8*g + 4*half + r,
+// token m = bm0 + wave_m*128 + b*32 + l32.
+//
+// VEC path: a lane's results are 4-channel groups scattered over 32 token rows, which would
+// make every store instruction touch 32 cache lines with a few bytes each.  Instead each
+// wavefront transposes a slab of 128 rows x 128 bytes through its private LDS region (row
+// stride 144 bytes: conflict-free 16-byte accesses) and writes it out as whole 128-byte lines,
+// 8 rows per store instruction.  int8: one slab holds all 128 channels of the wave tile (the
+// two half-waves first swap packed words so that a lane owns 16 consecutive channels);
+// fp32 / int32: one slab per 32-channel MFMA column.
+// Non-VEC path (unaligned output): element-wise stores.
+constexpr int kSlabStride = 144;
+constexpr int kSlabBytes = 128 * kSlabStride;
+
+template <int OUT_KIND>
+__device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int64_t row_bytes, int lane) {
+  const int rd_row = lane >> 3, rd_chunk = lane & 7;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int row = i * 8 + rd_row;
+    const v4i v = *reinterpret_cast<const v4i *>(slab + row * kSlabStride + rd_chunk * 16);
+    *reinterpret_cast<v4i *>(gbase + row * row_bytes + rd_chunk * 16) = v;
+  }
+}
+
+template <int OUT_KIND, bool INT_ONLY, bool VEC>
+__device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4][4], int8_t *smem,
+                                              const float *s_mult, const float *s_fb,
+                                              const float *s_rs, int64_t bm0, int bn0, int wave_m,
+                                              int wave_n, int lane) {
+  constexpr int ESZ = OUT_KIND == CWAC_OUT_INT8 ? 1 : 4;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave = wave_m + 2 * wave_n;
+  int8_t *slab = smem + wave * kSlabBytes;
+  const int64_t row_bytes = p.ldo * ESZ;
+  // first element of the wave tile in the output
+  char *wbase = static_cast<char *>(p.out) + ((bm0 + wave_m * 128) * p.ldo + bn0 + wave_n * 128) * ESZ;
+  float rs[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) rs[b] = s_rs[wave_m * 128 + b * 32 + l32];
+  const bool use_rs = !INT_ONLY && p.sx_row != nullptr;
+  const bool use_fb = !INT_ONLY && p.fbias != nullptr;
+  const float magic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to nearest even at unit steps
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    float mu[4][4], fb[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int cl = wave_n * 128 + a * 32 + 8 * g + 4 * half;  // channel inside the tile
+      if (OUT_KIND != CWAC_OUT_INT32) {
+        const float4 m4 = *reinterpret_cast<const float4 *>(s_mult + cl);
+        mu[g][0] = m4.x; mu[g][1] = m4.y; mu[g][2] = m4.z; mu[g][3] = m4.w;
+        if (!INT_ONLY) {
+          const float4 f4 = *reinterpret_cast<const float4 *>(s_fb + cl);
+          fb[g][0] = f4.x; fb[g][1] = f4.y; fb[g][2] = f4.z; fb[g][3] = f4.w;
+        }
+      }
+    }
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int row = b * 32 + l32;  // row inside the wave tile
+      uint32_t packed[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = a * 32 + 8 * g + 4 * half;  // channel inside the wave tile
+        if (OUT_KIND == CWAC_OUT_INT32) {
+          const v4i t = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                         acc[a][b][4 * g + 3]};
+          if (VEC) {
+            *reinterpret_cast<v4i *>(slab + row * kSlabStride + (8 * g + 4 * half) * 4) = t;
+          } else {
+            int32_t *o = reinterpret_cast<int32_t *>(wbase + row * row_bytes) + col;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = t[r];
+          }
+          continue;
+        }
+        float u[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float f = (float)acc[a][b][4 * g + r];
+          if (use_rs) f = f * rs[b];
+          float v = f * mu[g][r];
+          if (use_fb) v = v + fb[g][r];
+          u[r] = v;
+        }
+        if (OUT_KIND == CWAC_OUT_FP32) {
+          if (VEC) {
+            *reinterpret_cast<float4 *>(slab + row * kSlabStride + (8 * g + 4 * half) * 4) =
+                make_float4(u[0], u[1], u[2], u[3]);
+          } else {
+            float *o = reinterpret_cast<float *>(wbase + row * row_bytes) + col;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = u[r];
+          }
+        } else {
+          int c[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            // clamp(rint(u), lo, hi) == rint(clamp(u, lo, hi)) for integer bounds; the low bits
+            // of (clamped + 1.5 * 2^23) are its rounded value in two's complement
+            const float cl_u = __builtin_amdgcn_fmed3f(u[r], p.lo, p.hi);
+            c[r] = __float_as_int(cl_u + magic) + p.zr;
+          }
+          if (VEC) {
+            packed[g] = pack4(c[0], c[1], c[2], c[3]);
+          } else {
+            int8_t *o = reinterpret_cast<int8_t *>(wbase + row * row_bytes) + col;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (int8_t)c[r];
+          }
+        }
+      }
+      if (OUT_KIND == CWAC_OUT_INT8 && VEC) {
+        // lower half-wave holds channels 8g..8g+3, upper 8g+4..8g+7: after swapping
+        // (upper's g0, lower's g2) and (upper's g1, lower's g3) the lower lane owns
+        // channels 0..15 of this MFMA column and the upper lane 16..31
+        const auto s02 = __builtin_amdgcn_permlane32_swap(packed[0], packed[2], false, false);
+        const auto s13 = __builtin_amdgcn_permlane32_swap(packed[1], packed[3], false, false);
+        const v4i q = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+        *reinterpret_cast<v4i *>(slab + row * kSlabStride + a * 32 + half * 16) = q;
+      }
+    }
+    if (VEC && OUT_KIND != CWAC_OUT_INT8) store_slab<OUT_KIND>(slab, wbase + a * 32 * ESZ, row_bytes, lane);
+  }
+  if (VEC && OUT_KIND == CWAC_OUT_INT8) store_slab<OUT_KIND>(slab, wbase, row_bytes, lane);
+}
+
+template <int BK, int NSTAGE, int OUT_KIND, bool INT_ONLY>
+__global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
+  using C = FastCfg<BK, NSTAGE>;
+  extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+  int32_t *s_off = reinterpret_cast<int32_t *>(smem + C::RING);
+  float *s_mult = reinterpret_cast<float *>(smem + C::RING + 1024);
+  float *s_fb = reinterpret_cast<float *>(smem + C::RING + 2048);
+  float *s_rs = reinterpret_cast<float *>(smem + C::RING + 3072);
+
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  int64_t bm0 = (int64_t)tile_m * C::BM;
+  if (bm0 > p.m - C::BM) bm0 = p.m - C::BM;
+  int bn0 = tile_n * C::BN;
+  if (bn0 > p.n - C::BN) bn0 = p.n - C::BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave & 1, wave_n = wave >> 1;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  // ---- epilogue parameters of this tile: issue their loads first (oldest in the load queue)
+  const int p_off = p.offset ? p.offset[bn0 + tid] : 0;
+  const float p_mult = (OUT_KIND != CWAC_OUT_INT32) ? p.mult[bn0 + tid] : 0.0f;
+  float p_fb = 0.0f, p_rs = 1.0f;
+  if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32) {
+    if (p.fbias) p_fb = p.fbias[bn0 + tid];
+    if (p.sx_row) p_rs = p.sx_row[bm0 + tid];
+  }
+
+  // ---- global -> LDS: wavefront `wave` owns rows [64*wave, 64*wave + 64) of both panels,
+  // LOADS loads of RPL rows each; lane = (row lr, slot pc) inside a load.  Addresses are a
+  // wave-uniform 64-bit base (tile origin + k) plus a per-lane 32-bit offset that never changes,
+  // so the loop body issues the loads without any vector address arithmetic.
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int lr = lane / C::CPR, pc = lane % C::CPR;
+  uint32_t xvo[C::LOADS], wvo[C::LOADS];
+#pragma unroll
+  for (int i = 0; i < C::LOADS; ++i) {
+    const int row = wave * 64 + i * C::RPL + lr;
+    const int chunk = pc ^ C::swz(row);
+    xvo[i] = (uint32_t)row * (uint32_t)p.ldx + chunk * 16;
+    wvo[i] = (uint32_t)row * (uint32_t)p.ldw + chunk * 16;
+  }
+  const int8_t *xtile = p.x + bm0 * p.ldx;
+  const int8_t *wtile = p.w + (int64_t)bn0 * p.ldw;
+
+  auto issue_stage = [&](int buf, int k0) {
+    int8_t *sx = smem + buf * C::STAGE + wave_s * 64 * BK;
+    int8_t *sw = sx + C::X_BYTES;
+    const int8_t *xk = xtile + k0, *wk = wtile + k0;
+#pragma unroll
+    for (int i = 0; i < C::LOADS; ++i)
+      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < C::LOADS; ++i)
+      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wk + wvo[i]), CWAC_LDS_PTR(sw + i * C::RPL * BK), 16, 0, 0);
+  };
+
+  // ---- LDS -> MFMA operand fragments (rows of a 32-row MFMA tile start at multiples of 16)
+  const int swz_l = C::swz(l32);
+  const int x_off = (wave_m * 128 + l32) * BK;
+  const int w_off = C::X_BYTES + (wave_n * 128 + l32) * BK;
+  auto read_frags = [&](int buf, int kk, v4i(&fw)[4], v4i(&fx)[4]) {
+    const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
+  };
+
+  v16i acc[4][4];
+  auto mma = [&](const v4i(&fw)[4], const v4i(&fx)[4]) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
+  };
+  // scheduler hint: the eight LDS reads of the next step go behind the first eight MFMAs of this
+  // one, one by one, so that they land half a step before they are needed
+  auto interleave = [&]() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+  };
+
+  // ---- prologue: fill the ring, stage the parameters, start the accumulators at offset[n]
+  const int stages = p.k / BK;
+#pragma unroll
+  for (int s = 0; s < NSTAGE; ++s)
+    if (s < stages) issue_stage(s, s * BK);
+  s_off[tid] = p_off;
+  s_mult[tid] = p_mult;
+  s_fb[tid] = p_fb;
+  s_rs[tid] = p_rs;
+  if (stages >= NSTAGE)
+    __builtin_amdgcn_s_waitcnt(s_waitcnt_imm((NSTAGE - 1) * C::LPS, 0));  // stage 0 has landed
+  else
+    __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const v4i o = *reinterpret_cast<const v4i *>(s_off + wave_n * 128 + a * 32 + 8 * g + 4 * half);
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[a][b][4 * g + r] = o[r];
+    }
+
+  v4i fwA[4], fxA[4], fwB[4], fxB[4];
+  read_frags(0, 0, fwA, fxA);
+
+  // One stage: KK k-steps; before the MFMAs of the last one, everybody has fetched its last
+  // fragments of this stage (its buffer is free) and the next stage has landed.
+  auto stage_body = [&](int s, int buf, bool issue) {
+#pragma unroll
+    for (int kk = 0; kk + 1 < C::KK; ++kk) {
+      if (kk & 1) {
+        read_frags(buf, kk + 1, fwA, fxA);
+        mma(fwB, fxB);
+      } else {
+        read_frags(buf, kk + 1, fwB, fxB);
+        mma(fwA, fxA);
+      }
+      interleave();
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the MFMAs above on this side of the wait
+    if (issue)
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm((NSTAGE - 2) * C::LPS, 0));
+    else
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (issue) issue_stage(buf, (s + NSTAGE) * BK);
+    // KK is even: the last step's fragments are in B, the next stage's first go to A
+    if (issue || s + 1 < stages) read_frags((buf + 1) % NSTAGE, 0, fwA, fxA);
+    mma(fwB, fxB);
+    if (issue) {
+      // spread the panel loads and the next stage's first fragment reads over the 16 MFMAs
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, C::LPS / 8, 0);
+      }
+    } else {
+      interleave();
+    }
+  };
+
+  int s = 0;
+  for (; s + 2 * NSTAGE <= stages; s += NSTAGE) {
+#pragma unroll
+    for (int j = 0; j < NSTAGE; ++j) stage_body(s + j, j, true);
+  }
+  for (; s + NSTAGE < stages; ++s) stage_body(s, s % NSTAGE, true);
+  for (; s < stages; ++s) stage_body(s, s % NSTAGE, false);
+
+  // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
+  constexpr int ESZ = OUT_KIND == CWAC_OUT_INT8 ? 1 : 4;
+  const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
+  if (vs)
+    fast_epilogue<OUT_KIND, INT_ONLY, true>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+  else
+    fast_epilogue<OUT_KIND, INT_ONLY, false>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+}
+
+template <int BK, int NSTAGE, int OUT_KIND, bool INT_ONLY>
+cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
+  using C = FastCfg<BK, NSTAGE>;
+  static const hipError_t attr = hipFuncSetAttribute(
+      reinterpret_cast<const void *>(&qlinear_fast_kernel<BK, NSTAGE, OUT_KIND, INT_ONLY>),
+      hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+  if (attr != hipSuccess) return CWAC_E_LAUNCH;
+  qlinear_fast_kernel<BK, NSTAGE, OUT_KIND, INT_ONLY><<<grid, 256, C::LDS_BYTES, st>>>(p);
+  return launch_status();
+}
+
+template <int BK, int NSTAGE>
+cwac_status launch_cfg(const FwdParams &p, int out_kind, bool int_only, dim3 grid, hipStream_t st) {
+  if (out_kind == CWAC_OUT_INT8)
+    return int_only ? launch_one<BK, NSTAGE, CWAC_OUT_INT8, true>(p, grid, st)
+                    : launch_one<BK, NSTAGE, CWAC_OUT_INT8, false>(p, grid, st);
+  if (out_kind == CWAC_OUT_FP32) return launch_one<BK, NSTAGE, CWAC_OUT_FP32, false>(p, grid, st);
+  return launch_one<BK, NSTAGE, CWAC_OUT_INT32, false>(p, grid, st);
+}
+
+}  // namespace
+
+cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
+  p.tiles_m = (int)ceil_div(p.m, 256);
+  p.tiles_n = (int)ceil_div(p.n, 256);
+  const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
+  p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
+  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
+  if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
+  const dim3 grid((unsigned)blocks);
+  // Tuning knob: CWAC_FWD_PIPE=128x2 | 64x4 selects the K step and ring depth (same results).
+  const char *e = getenv("CWAC_FWD_PIPE");
+  if (e && e[0] == '6') return launch_cfg<64, 4>(p, out_kind, int_only, grid, st);
+  return launch_cfg<128, 2>(p, out_kind, int_only, grid, st);
+}
+
+}  // namespace cwac

@@ -14,30 +14,10 @@
 // the row-major [M, N] output.
 #include <stdlib.h>
 
-#include "cwac_internal.h"
+#include "qlinear_common.h"
 
 namespace cwac {
 namespace {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-
-struct FwdParams {
-  const int8_t *x;
-  const int8_t *w;
-  int64_t ldx, ldw, ldo;
-  int64_t m;
-  int n, k;
-  const float *mult;
-  const int32_t *offset;
-  const float *fbias;
-  const float *sx_row;
-  void *out;
-  float lo, hi;
-  int zr;
-  int vec_store;  // output layout allows 4-element vector stores
-  int tiles_m, tiles_n;
-};
 
 // LDS tile: ROWS x BK bytes, 16-byte chunks XOR-swizzled inside each row so that
 // the 16 lanes that read the same chunk index of 16 consecutive rows (one MFMA
@@ -60,131 +40,6 @@ struct Tile {
   static_assert((BM * CPR) % NT == 0 && (BN * CPR) % NT == 0, "tile must split evenly over threads");
   static_assert(BK % 32 == 0 && CPR >= 2 && (CPR & (CPR - 1)) == 0, "BK must be a power of two >= 32");
 };
-
-// Workgroup id -> output tile.  Consecutive workgroup ids are dealt round-robin
-// to the 8 XCDs (each with its own L2), so ids are first regrouped so that every
-// XCD works on a contiguous range of tiles, and tiles are then walked in bands of
-// GROUP_M tile-rows so that the tiles in flight on one XCD share weight and
-// activation panels in its L2.
-__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int &tm, int &tn) {
-  const int total = tiles_m * tiles_n;
-  constexpr int XCDS = 8;
-  const int per = total / XCDS, rem = total - per * XCDS;
-  const int xcd = pid % XCDS, local = pid / XCDS;
-  // ids dealt to xcd: `per` of them, plus one more for the first `rem` xcds
-  const int start = xcd * per + (xcd < rem ? xcd : rem);
-  const int id = start + local;
-  constexpr int GROUP_M = 8;
-  const int band = GROUP_M * tiles_n;
-  const int g = id / band;
-  const int first_m = g * GROUP_M;
-  const int rows = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
-  const int in = id - g * band;
-  tm = first_m + in % rows;
-  tn = in / rows;
-}
-
-template <int OUT_KIND, bool INT_ONLY>
-struct Epilogue {
-  // Applies Eq. 10 to 4 consecutive channels nn..nn+3 of row mm and stores them.
-  __device__ static __forceinline__ void run(const FwdParams &p, int64_t mm, int nn,
-                                             const int (&acc)[4], const float (&mu)[4],
-                                             const int (&off)[4], const float (&fb)[4],
-                                             float rs) {
-    if (OUT_KIND == CWAC_OUT_INT32) {
-      int t[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) t[r] = acc[r] + off[r];
-      int32_t *o = static_cast<int32_t *>(p.out) + mm * p.ldo + nn;
-      if (p.vec_store && nn + 3 < p.n) {
-        *reinterpret_cast<int4 *>(o) = make_int4(t[0], t[1], t[2], t[3]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (nn + r < p.n) o[r] = t[r];
-      }
-      return;
-    }
-    float u[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      float f = (float)(acc[r] + off[r]);
-      if (!INT_ONLY) {
-        if (p.sx_row) f = f * rs;
-      }
-      float v = f * mu[r];
-      if (!INT_ONLY) {
-        if (p.fbias) v = v + fb[r];
-      }
-      u[r] = v;
-    }
-    if (OUT_KIND == CWAC_OUT_FP32) {
-      float *o = static_cast<float *>(p.out) + mm * p.ldo + nn;
-      if (p.vec_store && nn + 3 < p.n) {
-        *reinterpret_cast<float4 *>(o) = make_float4(u[0], u[1], u[2], u[3]);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (nn + r < p.n) o[r] = u[r];
-      }
-    } else {
-      int c[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) c[r] = requant_code(u[r], p.lo, p.hi, p.zr);
-      int8_t *o = static_cast<int8_t *>(p.out) + mm * p.ldo + nn;
-      if (p.vec_store && nn + 3 < p.n) {
-        *reinterpret_cast<uint32_t *>(o) = (uint32_t)(c[0] & 0xff) | ((uint32_t)(c[1] & 0xff) << 8) |
-                                           ((uint32_t)(c[2] & 0xff) << 16) | ((uint32_t)c[3] << 24);
-      } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (nn + r < p.n) o[r] = (int8_t)c[r];
-      }
-    }
-  }
-};
-
-// Epilogue over a wave's TN x TM accumulator tiles.  Accumulator element 4*g + r of
-// tile (a, b) belongs to channel n = n0 + a*32 + 8*g + 4*half + r and token
-// m = m0 + b*32 + l32 (n0, m0: first channel / token of the wave tile).
-template <int TM, int TN, int OUT_KIND, bool INT_ONLY>
-__device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[TN][TM], int64_t m0,
-                                               int n0, int l32, int half, int vec_store) {
-  FwdParams q = p;
-  q.vec_store = vec_store;
-#pragma unroll
-  for (int a = 0; a < TN; ++a) {
-    const int nb = n0 + a * 32 + 4 * half;
-    float mu[4][4], fb[4][4];
-    int off[4][4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        int idx = nb + 8 * g + r;
-        if (idx > p.n - 1) idx = p.n - 1;  // clamped read; such channels are never stored
-        off[g][r] = p.offset ? p.offset[idx] : 0;
-        mu[g][r] = (OUT_KIND != CWAC_OUT_INT32) ? p.mult[idx] : 0.0f;
-        fb[g][r] = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.fbias) ? p.fbias[idx] : 0.0f;
-      }
-#pragma unroll
-    for (int b = 0; b < TM; ++b) {
-      const int64_t mm = m0 + b * 32 + l32;
-      if (mm < p.m) {
-        const float rs = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.sx_row) ? p.sx_row[mm] : 1.0f;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int nn = nb + 8 * g;
-          if (nn < p.n) {
-            const int av[4] = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
-                               acc[a][b][4 * g + 3]};
-            Epilogue<OUT_KIND, INT_ONLY>::run(q, mm, nn, av, mu[g], off[g], fb[g], rs);
-          }
-        }
-      }
-    }
-  }
-}
 
 template <int BM, int BN, int BK, int WGM, int WGN, int OUT_KIND, bool INT_ONLY>
 __global__ __launch_bounds__(64 * WGM * WGN) void qlinear_kernel(const FwdParams p) {
@@ -303,160 +158,6 @@ cwac_status launch_tile(FwdParams p, int out_kind, bool int_only, hipStream_t st
 }
 
 
-// ---------------------------------------------------------------------------------------------
-// Large-problem kernel: 256 x 256 output tile, K step 128, four wavefronts (2 x 2, each
-// 128 x 128 = 4 x 4 MFMA tiles, 256 accumulator registers per lane), one workgroup per
-// compute unit.
-//   * Panels go global -> LDS directly (global_load_lds_dwordx4, no register staging): a
-//     wavefront's load covers 8 rows x 128 bytes and lands as 1 KiB of contiguous LDS, so the
-//     bank swizzle is applied on the GLOBAL side: lane (row r, slot p) fetches chunk
-//     p ^ ((r >> 1) & 7) of its row.
-//   * Two LDS stages of 64 KiB; the loads of stage s+2 are issued as soon as every wavefront has
-//     fetched its last fragments of stage s, one barrier per stage.
-//   * MFMA operand fragments are double-buffered in registers, LDS reads for step kk+1 are
-//     interleaved with the MFMAs of step kk.
-// Requires m >= 256, n >= 256, k % 128 == 0.  Edge tiles are shifted inwards to overlap their
-// neighbours (identical values are written twice) instead of being predicated.
-constexpr int FBM = 256, FBN = 256, FBK = 128;
-constexpr int F_X_BYTES = FBM * FBK, F_W_BYTES = FBN * FBK, F_STAGE = F_X_BYTES + F_W_BYTES;
-constexpr int F_LDS_BYTES = 2 * F_STAGE;
-
-#define CWAC_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
-#define CWAC_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
-
-template <int OUT_KIND, bool INT_ONLY>
-__global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
-  extern __shared__ __attribute__((aligned(16))) int8_t smem[];
-
-  int tile_m, tile_n;
-  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
-  int64_t bm0 = (int64_t)tile_m * FBM;
-  if (bm0 > p.m - FBM) bm0 = p.m - FBM;
-  int bn0 = tile_n * FBN;
-  if (bn0 > p.n - FBN) bn0 = p.n - FBN;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave & 1, wave_n = wave >> 1;
-  const int l32 = lane & 31, half = lane >> 5;
-
-  // ---- global -> LDS: wavefront `wave` owns rows [64*wave, 64*wave + 64) of both panels,
-  // 8 loads of 8 rows each; lane = (row lr, slot pc) inside a load.
-  const int lr = lane >> 3, pc = lane & 7;
-  const int ce = pc ^ (lane >> 4);  // chunk for even loads; odd loads (rows +8) use ce ^ 4
-  const int8_t *xrow = p.x + (bm0 + wave * 64 + lr) * p.ldx;
-  const int8_t *wrow = p.w + (int64_t)(bn0 + wave * 64 + lr) * p.ldw;
-  const int8_t *xpe = xrow + ce * 16, *xpo = xrow + (ce ^ 4) * 16;
-  const int8_t *wpe = wrow + ce * 16, *wpo = wrow + (ce ^ 4) * 16;
-  const int64_t xstep = 8 * p.ldx, wstep = 8 * p.ldw;
-
-  auto issue_stage = [&](int buf, int k0) {
-    int8_t *sx = smem + buf * F_STAGE + wave * 64 * FBK;
-    int8_t *sw = sx + F_X_BYTES;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int8_t *g = ((i & 1) ? xpo : xpe) + i * xstep + k0;
-      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(g), CWAC_LDS_PTR(sx + i * 8 * FBK), 16, 0, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int8_t *g = ((i & 1) ? wpo : wpe) + i * wstep + k0;
-      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(g), CWAC_LDS_PTR(sw + i * 8 * FBK), 16, 0, 0);
-    }
-  };
-
-  // ---- LDS -> MFMA operand fragments
-  const int swz = (l32 >> 1) & 7;
-  const int x_off = (wave_m * 128 + l32) * FBK;
-  const int w_off = F_X_BYTES + (wave_n * 128 + l32) * FBK;
-  auto read_frags = [&](int buf, int kk, v4i(&fw)[4], v4i(&fx)[4]) {
-    const int8_t *base = smem + buf * F_STAGE + (((2 * kk + half) ^ swz) << 4);
-#pragma unroll
-    for (int a = 0; a < 4; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * FBK);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * FBK);
-  };
-
-  v16i acc[4][4];
-#pragma unroll
-  for (int a = 0; a < 4; ++a)
-#pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0;
-
-  auto mma = [&](const v4i(&fw)[4], const v4i(&fx)[4]) {
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 4; ++b)
-        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
-  };
-  // ask the scheduler to put the eight LDS reads of the next step behind the first eight
-  // MFMAs of this one, one by one, so that they land half a step before they are needed
-  auto interleave = [&]() {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
-  };
-
-  const int stages = p.k / FBK;
-  v4i fwA[4], fxA[4], fwB[4], fxB[4];
-  issue_stage(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): stage 0 has landed
-  __builtin_amdgcn_s_barrier();
-  if (stages > 1) issue_stage(1, FBK);
-  read_frags(0, 0, fwA, fxA);
-
-  for (int s = 0; s < stages; ++s) {
-    const int buf = s & 1;
-    read_frags(buf, 1, fwB, fxB);
-    mma(fwA, fxA);
-    interleave();
-    read_frags(buf, 2, fwA, fxA);
-    mma(fwB, fxB);
-    interleave();
-    read_frags(buf, 3, fwB, fxB);
-    mma(fwA, fxA);
-    interleave();
-    // every wavefront holds its last fragments of this stage; the next stage has landed
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    __builtin_amdgcn_s_barrier();
-    if (s + 2 < stages) issue_stage(buf, (s + 2) * FBK);
-    if (s + 1 < stages) read_frags(buf ^ 1, 0, fwA, fxA);
-    mma(fwB, fxB);
-  }
-
-  const int vs = p.vec_store && ((bn0 & 3) == 0);
-  epilogue_tiles<4, 4, OUT_KIND, INT_ONLY>(p, acc, bm0 + wave_m * 128, bn0 + wave_n * 128, l32, half, vs);
-}
-
-template <int OUT_KIND, bool INT_ONLY>
-cwac_status launch_fast_one(const FwdParams &p, dim3 grid, hipStream_t st) {
-  static const hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&qlinear_fast_kernel<OUT_KIND, INT_ONLY>),
-      hipFuncAttributeMaxDynamicSharedMemorySize, F_LDS_BYTES);
-  if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<OUT_KIND, INT_ONLY><<<grid, 256, F_LDS_BYTES, st>>>(p);
-  return launch_status();
-}
-
-cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
-  p.tiles_m = (int)ceil_div(p.m, FBM);
-  p.tiles_n = (int)ceil_div(p.n, FBN);
-  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
-  if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
-  const dim3 grid((unsigned)blocks);
-  if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_fast_one<CWAC_OUT_INT8, true>(p, grid, st)
-                    : launch_fast_one<CWAC_OUT_INT8, false>(p, grid, st);
-  if (out_kind == CWAC_OUT_FP32) return launch_fast_one<CWAC_OUT_FP32, false>(p, grid, st);
-  return launch_fast_one<CWAC_OUT_INT32, false>(p, grid, st);
-}
-
 }  // namespace
 }  // namespace cwac
 
@@ -501,7 +202,7 @@ extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, cons
   const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
   const int64_t t128 = ceil_div(m, 128) * ceil_div(n, 128);
   int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
-  const bool fast_ok = m >= FBM && n >= FBN && (k % FBK) == 0;
+  const bool fast_ok = m >= kFastTile && n >= kFastTile && (k % kFastKStep) == 0;
   bool fast = fast_ok && t256 >= 256;
   // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
   // the large-problem kernel where its shape constraints hold (results are identical).
