@@ -94,7 +94,9 @@ cwac_status cwac_colsum(const int8_t *w_q, int64_t ldw, int32_t n, int32_t k, in
  * resume later):
  *   bytes  0..7    int64  n            rows accumulated so far
  *   bytes  8..11   int32  c_out
- *   bytes 12..63   reserved (zero)
+ *   bytes 12..15   reserved (zero)
+ *   bytes 16..19   uint32 internal launch ticket (zero between calls)
+ *   bytes 20..63   reserved (zero)
  *   float  pivot_q[c_out], float pivot_f[c_out]   per-channel shift, fixed by the
  *                                                  first row ever accumulated
  *   double sum[5][c_out]   over all rows so far, with dq = y_quant - pivot_q and

@@ -11,7 +11,8 @@ from typing import Optional
 import torch  # imported first so that the library binds to torch's HIP runtime
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libcwac_hip.so")
+# CWAC_LIB overrides the library path (development builds); the default is the in-tree build
+LIB_PATH = os.environ.get("CWAC_LIB") or os.path.join(_PKG, "libcwac_hip.so")
 
 CWAC_OK = 0
 CWAC_EPI_INT_OFFSET, CWAC_EPI_FP_BIAS = 0, 1

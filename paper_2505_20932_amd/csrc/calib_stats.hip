@@ -3,8 +3,9 @@
 // The pass is a pure streaming read of Y_full and Y_quant (8 bytes per row and
 // channel), so the kernel is shaped for HBM bandwidth: every lane owns 4
 // adjacent channels (one 16-byte load per matrix and row), a wavefront covers
-// 1 KiB of contiguous row, several rows are in flight per lane, and nothing is
-// written but O(channels) partial sums.  Sums are taken of pivot-shifted values
+// 1 KiB of contiguous row and a workgroup up to 4 KiB, 16 loads are in flight
+// per lane, there is no LDS traffic and no barrier, and nothing is written but
+// O(channels) partial sums.  Sums are taken of pivot-shifted values
 // in fp64, so channels whose mean dwarfs their spread lose no precision, and in a
 // fixed order (no floating-point atomics), so results are bit-reproducible.
 #include "cwac_internal.h"
@@ -35,33 +36,36 @@ __host__ __device__ inline StatsView view(void *stats, int c) {
 }
 
 // Row split of one call: the same function sizes the workspace and the launch.
+// The unit of work is a WAVE TASK: one wavefront owns 64*VEC adjacent channels over a block of
+// rows.  Consecutive tasks take adjacent channel groups of the same row block, so the four
+// wavefronts of a workgroup read up to 4 KiB of contiguous row from each matrix.
 struct Split {
-  int col_blocks;      // workgroups along channels
-  int row_blocks;      // workgroups along rows = number of partial sums per channel
+  int col_groups;       // wave tasks along channels
+  int row_blocks;       // wave tasks along rows = number of partial sums per channel
   int64_t rows_per_block;
 };
 
 inline Split make_split(int64_t n_rows, int c_out, int vec) {
   Split s;
-  s.col_blocks = (int)ceil_div(c_out, kWave * vec);
-  const int64_t target_blocks = 2048;  // ~8 workgroups per compute unit
-  int64_t rb = ceil_div(target_blocks, s.col_blocks);
-  const int64_t max_rb = ceil_div(n_rows, 32);  // at least 32 rows per workgroup
+  s.col_groups = (int)ceil_div(c_out, kWave * vec);
+  const int64_t target_tasks = 256 * 4 * 4;  // ~4 wavefronts per SIMD
+  int64_t rb = ceil_div(target_tasks, s.col_groups);
+  const int64_t max_rb = ceil_div(n_rows, 64);  // at least 64 rows per task
   if (rb > max_rb) rb = max_rb;
   if (rb < 1) rb = 1;
-  if (rb > 65535) rb = 65535;
-  s.rows_per_block = ceil_div(ceil_div(n_rows, rb), kWaves) * kWaves;
+  s.rows_per_block = ceil_div(n_rows, rb);
   s.row_blocks = (int)ceil_div(n_rows, s.rows_per_block);
   return s;
 }
 
 template <int VEC>
 struct Ld;
+typedef float vf4 __attribute__((ext_vector_type(4)));
 template <>
 struct Ld<4> {
-  using T = float4;
-  __device__ static void unpack(const float4 &v, float (&o)[4]) {
-    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  using T = vf4;
+  __device__ static void unpack(const vf4 &v, float (&o)[4]) {
+    o[0] = v[0]; o[1] = v[1]; o[2] = v[2]; o[3] = v[3];
   }
 };
 template <>
@@ -70,27 +74,29 @@ struct Ld<1> {
   __device__ static void unpack(const float &v, float (&o)[1]) { o[0] = v; }
 };
 
-// Stage 1.  grid = (col_blocks, row_blocks).  Lane l of every wavefront owns
-// channels c0 + VEC*l .. +VEC-1; wavefront w takes rows r0 + w, r0 + w + 4, ...
-// partial[row_block][stat][channel] receives the workgroup's sums.
+// Stage 1.  One wave task per wavefront (4 per workgroup): lane l owns channels
+// c0 + VEC*l .. +VEC-1 and walks its row block with 2*U to 4*U 16-byte loads in flight.
+// partial[row_block][stat][channel] receives the task's sums; no LDS, no barrier.
 template <int VEC>
-__global__ __launch_bounds__(kThreads) void stats_partial_kernel(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void stats_partial_kernel(
     const float *__restrict__ yf, int64_t ldf, const float *__restrict__ yq, int64_t ldq,
-    int64_t n_rows, int c_out, int64_t rows_per_block, const void *stats,
-    double *__restrict__ partial) {
+    int64_t n_rows, int c_out, int col_groups, int64_t n_tasks, int64_t rows_per_block,
+    const void *stats, double *__restrict__ partial) {
   using V = typename Ld<VEC>::T;
   const int lane = threadIdx.x & (kWave - 1);
-  const int w = threadIdx.x / kWave;
-  const int c = (blockIdx.x * kWave + lane) * VEC;
-  const bool active = c < c_out;  // VEC == 4 requires c_out % 4 == 0, so all-or-nothing
-  const int cc = active ? c : 0;
+  const int64_t task = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+  if (task >= n_tasks) return;
+  const int cg = (int)(task % col_groups);
+  const int64_t rb = task / col_groups;
+  const int c = (cg * kWave + lane) * VEC;
+  if (c >= c_out) return;  // VEC == 4 requires c_out % 4 == 0, so a lane is all in or all out
 
   const StatsView sv = view(const_cast<void *>(stats), c_out);
   const bool first = (*sv.n == 0);
   float pq[VEC], pf[VEC];
   {
-    V vq = first ? *reinterpret_cast<const V *>(yq + cc) : *reinterpret_cast<const V *>(sv.pivot_q + cc);
-    V vf = first ? *reinterpret_cast<const V *>(yf + cc) : *reinterpret_cast<const V *>(sv.pivot_f + cc);
+    V vq = first ? *reinterpret_cast<const V *>(yq + c) : *reinterpret_cast<const V *>(sv.pivot_q + c);
+    V vf = first ? *reinterpret_cast<const V *>(yf + c) : *reinterpret_cast<const V *>(sv.pivot_f + c);
     Ld<VEC>::unpack(vq, pq);
     Ld<VEC>::unpack(vf, pf);
   }
@@ -101,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void stats_partial_kernel(
 #pragma unroll
     for (int s = 0; s < kStats; ++s) acc[j][s] = 0.0;
 
-  const int64_t r_begin = (int64_t)blockIdx.y * rows_per_block;
+  const int64_t r_begin = rb * rows_per_block;
   int64_t r_end = r_begin + rows_per_block;
   if (r_end > n_rows) r_end = n_rows;
 
@@ -115,74 +121,114 @@ __global__ __launch_bounds__(kThreads) void stats_partial_kernel(
       const double df = (double)(f[j] - pf[j]);
       acc[j][0] += dq;
       acc[j][1] += df;
-      acc[j][2] += dq * dq;
-      acc[j][3] += dq * df;
-      acc[j][4] += df * df;
+      acc[j][2] = fma(dq, dq, acc[j][2]);  // explicit fused ops: sums carry no bit-exactness contract
+      acc[j][3] = fma(dq, df, acc[j][3]);
+      acc[j][4] = fma(df, df, acc[j][4]);
     }
   };
 
-  if (active) {
-    constexpr int U = 4;  // rows in flight per lane: 2*U 16-byte loads outstanding
-    int64_t r = r_begin + w;
-    for (; r + (U - 1) * kWaves < r_end; r += U * kWaves) {
-      V vq[U], vf[U];
+  // Software pipeline over batches of U rows: the 2*U loads of the next batch are issued
+  // before the current batch is consumed, so every wavefront always has loads in flight.
+  constexpr int U = 4;
+  const float *pq_row = yq + r_begin * ldq + c;
+  const float *pf_row = yf + r_begin * ldf + c;
+  auto load_batch = [&](V(&vq)[U], V(&vf)[U]) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        vq[u] = *reinterpret_cast<const V *>(yq + (r + u * kWaves) * ldq + c);
-        vf[u] = *reinterpret_cast<const V *>(yf + (r + u * kWaves) * ldf + c);
-      }
+    for (int u = 0; u < U; ++u) {
+      vq[u] = __builtin_nontemporal_load(reinterpret_cast<const V *>(pq_row + u * ldq));
+      vf[u] = __builtin_nontemporal_load(reinterpret_cast<const V *>(pf_row + u * ldf));
+    }
+    pq_row += U * ldq;
+    pf_row += U * ldf;
+  };
+  auto consume_batch = [&](const V(&vq)[U], const V(&vf)[U]) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) consume(vq[u], vf[u]);
-    }
-    for (; r < r_end; r += kWaves) {
-      const V vq = *reinterpret_cast<const V *>(yq + r * ldq + c);
-      const V vf = *reinterpret_cast<const V *>(yf + r * ldf + c);
-      consume(vq, vf);
-    }
+    for (int u = 0; u < U; ++u) consume(vq[u], vf[u]);
+  };
+  const int64_t n_batches = (r_end - r_begin) / U;
+  V aq[U], af[U], bq[U], bf[U];
+  if (n_batches > 0) load_batch(aq, af);
+  int64_t b = 0;
+  for (; b + 2 < n_batches; b += 2) {
+    load_batch(bq, bf);
+    __builtin_amdgcn_sched_barrier(0);
+    consume_batch(aq, af);
+    __builtin_amdgcn_sched_barrier(0);
+    load_batch(aq, af);
+    __builtin_amdgcn_sched_barrier(0);
+    consume_batch(bq, bf);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (b < n_batches) {  // one or two batches left; the first is already in flight
+    if (b + 1 < n_batches) load_batch(bq, bf);
+    consume_batch(aq, af);
+    if (b + 1 < n_batches) consume_batch(bq, bf);
+  }
+  for (int64_t r = r_begin + n_batches * U; r < r_end; ++r) {
+    const V vq = *reinterpret_cast<const V *>(pq_row);
+    const V vf = *reinterpret_cast<const V *>(pf_row);
+    pq_row += ldq;
+    pf_row += ldf;
+    consume(vq, vf);
   }
 
-  // Fixed-order merge of the four wavefronts through LDS.
-  __shared__ double red[kWaves][kStats][kWave * VEC];
 #pragma unroll
-  for (int j = 0; j < VEC; ++j)
+  for (int s = 0; s < kStats; ++s)
 #pragma unroll
-    for (int s = 0; s < kStats; ++s) red[w][s][lane * VEC + j] = acc[j][s];
-  __syncthreads();
-  const int chans = kWave * VEC;
-  for (int i = threadIdx.x; i < kStats * chans; i += kThreads) {
-    const int s = i / chans, j = i - s * chans;
-    const int ch = blockIdx.x * chans + j;
-    if (ch < c_out) {
-      double t = red[0][s][j];
-#pragma unroll
-      for (int ww = 1; ww < kWaves; ++ww) t += red[ww][s][j];
-      partial[((int64_t)blockIdx.y * kStats + s) * c_out + ch] = t;
-    }
-  }
+    for (int j = 0; j < VEC; ++j) partial[(rb * kStats + s) * c_out + c + j] = acc[j][s];
 }
 
-// Stage 2: fixed-order sum over row blocks, added into the state; the first
-// batch also records the pivots (row 0 of that batch).
-__global__ __launch_bounds__(kThreads) void stats_merge_kernel(
+// Stage 2: fixed-order sum over row blocks, added into the state; the first batch also
+// records the pivots (row 0 of that batch).  One workgroup per (statistic, 64 channels):
+// wavefront w sums row blocks w, w+16, ... and the 16 wave sums are combined in order.
+// The last workgroup to finish bumps the row count: every workgroup reads the count before
+// it takes its ticket, so none can see the new value.
+constexpr int kMergeWaves = 16;
+__global__ __launch_bounds__(kMergeWaves *kWave) void stats_merge_kernel(
     const double *__restrict__ partial, int row_blocks, int c_out, const float *__restrict__ yf,
-    const float *__restrict__ yq, void *stats) {
-  const int i = blockIdx.x * kThreads + threadIdx.x;
-  if (i >= kStats * c_out) return;
-  const int s = i / c_out, ch = i - s * c_out;
+    const float *__restrict__ yq, void *stats, int64_t n_rows) {
+  const int groups = (c_out + kWave - 1) / kWave;
+  const int s = blockIdx.x / groups, cg = blockIdx.x - s * groups;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int ch = cg * kWave + lane;
   const StatsView sv = view(stats, c_out);
   const bool first = (*sv.n == 0);
   double t = 0.0;
-  for (int rb = 0; rb < row_blocks; ++rb) t += partial[((int64_t)rb * kStats + s) * c_out + ch];
-  sv.sum[i] = first ? t : sv.sum[i] + t;
-  if (first && s == 0) {
-    sv.pivot_q[ch] = yq[ch];
-    sv.pivot_f[ch] = yf[ch];
+  if (ch < c_out) {
+    const double *src = partial + (int64_t)s * c_out + ch;
+    const int64_t step = (int64_t)kStats * c_out;
+    int rb = w;
+    for (; rb + 3 * kMergeWaves < row_blocks; rb += 4 * kMergeWaves) {
+      const double a0 = src[(int64_t)rb * step], a1 = src[(int64_t)(rb + kMergeWaves) * step],
+                   a2 = src[(int64_t)(rb + 2 * kMergeWaves) * step],
+                   a3 = src[(int64_t)(rb + 3 * kMergeWaves) * step];
+      t += a0; t += a1; t += a2; t += a3;
+    }
+    for (; rb < row_blocks; rb += kMergeWaves) t += src[(int64_t)rb * step];
   }
-}
-
-// Stage 3: bump the row count (its own launch: every workgroup of stage 2 reads it).
-__global__ void stats_commit_kernel(void *stats, int64_t n_rows) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *static_cast<int64_t *>(stats) += n_rows;
+  __shared__ double red[kMergeWaves][kWave];
+  red[w][lane] = t;
+  __syncthreads();
+  if (w == 0 && ch < c_out) {
+    double total = red[0][lane];
+#pragma unroll
+    for (int i = 1; i < kMergeWaves; ++i) total += red[i][lane];
+    const int i = s * c_out + ch;
+    sv.sum[i] = first ? total : sv.sum[i] + total;
+    if (first && s == 0) {
+      sv.pivot_q[ch] = yq[ch];
+      sv.pivot_f[ch] = yf[ch];
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    unsigned *ticket = reinterpret_cast<unsigned *>(static_cast<char *>(stats) + 16);
+    if (atomicAdd(ticket, 1u) == gridDim.x - 1) {
+      *ticket = 0;
+      *sv.n += n_rows;
+    }
+  }
 }
 
 __global__ __launch_bounds__(kThreads) void stats_reset_kernel(void *stats, int c_out,
@@ -298,17 +344,19 @@ extern "C" cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full
                    aligned(y_full, 16) && aligned(y_quant, 16);
   const Split sp = make_split(n_rows, c_out, vec ? 4 : 1);
   double *partial = static_cast<double *>(workspace);
-  const dim3 grid(sp.col_blocks, sp.row_blocks);
+  const int64_t n_tasks = (int64_t)sp.col_groups * sp.row_blocks;
+  const unsigned grid = (unsigned)ceil_div(n_tasks, kWaves);
   hipStream_t st = as_stream(stream);
   if (vec)
     stats_partial_kernel<4><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
-                                                       c_out, sp.rows_per_block, stats, partial);
+                                                       c_out, sp.col_groups, n_tasks,
+                                                       sp.rows_per_block, stats, partial);
   else
     stats_partial_kernel<1><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
-                                                       c_out, sp.rows_per_block, stats, partial);
-  stats_merge_kernel<<<(unsigned)ceil_div((int64_t)kStats * c_out, kThreads), kThreads, 0, st>>>(
-      partial, sp.row_blocks, c_out, y_full, y_quant, stats);
-  stats_commit_kernel<<<1, 64, 0, st>>>(stats, n_rows);
+                                                       c_out, sp.col_groups, n_tasks,
+                                                       sp.rows_per_block, stats, partial);
+  stats_merge_kernel<<<(unsigned)(kStats * ceil_div(c_out, kWave)), kMergeWaves * kWave, 0, st>>>(
+      partial, sp.row_blocks, c_out, y_full, y_quant, stats, n_rows);
   return launch_status();
 }
 
