@@ -135,6 +135,64 @@ def run_step(P, layers, ev=None):
             ev.append(e)
 
 
+def _forward_int8(P, L, mult, offset, fbias):
+    if L.per_token:
+        P.qlinear_cwac_forward(L.xq, L.wq, L.qp, mult, offset, fbias, L.sx_row, P.CWAC_OUT_INT8, L.out)
+    else:
+        P.qlinear_cwac_forward(L.xq, L.wq, L.qp, mult, offset, None, None, P.CWAC_OUT_INT8, L.out)
+
+
+def comparators(P, torch, layers, reps: int = 5):
+    """What the fold buys (Sec. 3.4): the fused CWAC forward against (B0) the same kernel with
+    plain PTQ parameters (alpha = 1, beta = 0) and against (B1 + EPI) a raw int32 GEMM followed
+    by the epilogue as a separate pass over the stored accumulators.  ms per pass over all layers."""
+    dev = layers[0].xq.device
+    n_max, m = max(L.n for L in layers), layers[0].m
+    acc_buf = torch.empty(m * n_max, dtype=torch.int32, device=dev)
+    ptq = []
+    for L in layers:
+        f32 = dict(dtype=torch.float32, device=dev)
+        pm, pf = torch.empty(L.n, **f32), torch.empty(L.n, **f32)
+        po = torch.empty(L.n, dtype=torch.int32, device=dev)
+        P.cwac_fold(None, None, L.sw, L.bias, L.colsum, L.qp, pm, po, pf)
+        ptq.append((pm, po, pf))
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def fused():
+        for L in layers:
+            _forward_int8(P, L, L.mult, L.offset, L.fbias)
+
+    def plain():
+        for L, (pm, po, pf) in zip(layers, ptq):
+            _forward_int8(P, L, pm, po, pf)
+
+    def unfused():
+        for L in layers:
+            acc = acc_buf[:L.m * L.n].view(L.m, L.n)
+            P.qlinear_cwac_forward(L.xq, L.wq, None, None, None, None, None, P.CWAC_OUT_INT32, acc)
+            P.cwac_epilogue_int32(acc, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
+                                  L.sx_row, P.CWAC_OUT_INT8, L.out)
+
+    # interleave the two fused variants so that clock / thermal drift hits both alike
+    t_f1, t_p1, t_f2, t_p2 = timed(fused), timed(plain), timed(fused), timed(plain)
+    t_fused, t_plain = (t_f1 + t_f2) / 2, (t_p1 + t_p2) / 2
+    t_unf = timed(unfused)
+    return {"fused_cwac_ms": round(t_fused, 4), "plain_ptq_same_kernel_ms": round(t_plain, 4),
+            "cwac_overhead_vs_plain_ptq": round(t_fused / t_plain - 1.0, 4),
+            "unfused_gemm_int32_plus_epilogue_pass_ms": round(t_unf, 4),
+            "unfused_over_fused": round(t_unf / t_fused, 3)}
+
+
 def cpu_baseline(synth, cfg: int, sample_rows: int):
     """The oracle, as it stands, timed on this host on a bounded row sample of the same step."""
     import numpy as np
@@ -191,6 +249,9 @@ def main():
                     "one batch = the workload's token count)")
     ap.add_argument("--cpu-sample-rows", type=int, default=512)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe", action="store_true",
+                    help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
+                         "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives or sharding are part of "
@@ -207,6 +268,20 @@ def main():
     wl = synth.WORKLOADS[args.config]
     cal_rows = args.cal_rows or wl.m
     wl, layers = setup_layers(P, synth, torch, args.config, dev, cal_rows)
+
+    if args.probe:
+        # plain copy kernel of known traffic: out = 1 * y + 0 over 2^28 floats (reads 1 GiB, writes 1 GiB)
+        src = torch.empty(1 << 14, 1 << 14, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        one = torch.ones(1 << 14, dtype=torch.float32, device=dev)
+        zero = torch.zeros(1 << 14, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        P.cwac_apply_unfolded(src, one, zero, dst)
+        run_step(P, layers)
+        torch.cuda.synchronize()
+        print(json.dumps({"probe": "copy of 1073741824 bytes, then one step",
+                          "workload": wl.name}))
+        return
 
     for _ in range(args.warmup):
         run_step(P, layers)
@@ -255,6 +330,7 @@ def main():
             sum(2.0 * L.cal_rows * L.n * L.k for L in layers) / (t_cal * 1e-3) / 1e12, 2),
         "stats_gbs": round(stats_gbs, 1),
     }
+    result["epilogue_comparators"] = comparators(P, torch, layers)
     if not args.no_cpu_baseline:
         v, cores, secs = cpu_baseline(synth, args.config, args.cpu_sample_rows)
         result["cpu_baseline"] = {
