@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 METRIC = "W8A8 GEMM+CWAC epilogue TOPS (% int8 MFMA peak); calib stats GB/s (% HBM)"
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --probe`,
+# scaled by what the same counters read for a plain 1 GiB copy (x1.997, x1.000); mean over the
+# workload's launches.  Only the default workload has been profiled.
+PMC_TRAFFIC_BYTES = {5: {"forward_int8": 980e6 + 174e6, "statistics": 1114e6 + 42e6}}
 
 
 class LayerState:
@@ -315,13 +319,16 @@ def main():
                    "layers": [f"{L.name} {L.n}x{L.k}" for L in layers]},
         "roofline": {"bound": "mfma", "achieved": round(fwd_tops / 1e3, 4),
                      "peak": INT8_MFMA_PEAK_TOPS / 1e3, "unit": "POP/s",
-                     "frac": round(fwd_tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                     "frac": round(fwd_tops / INT8_MFMA_PEAK_TOPS, 4),
+                     "traffic": PMC_TRAFFIC_BYTES.get(wl.cfg, {}).get("forward_int8")
+                     if cal_rows == wl.m else None,
                      "kernel": "qlinear_kernel (int8 out, fused CWAC epilogue)",
                      "launches_per_step": nl, "avg_launch_ms": round(t_fwd / nl, 4),
                      "ops_per_step": fwd_ops},
         "roofline_stats": {"bound": "hbm", "achieved": round(stats_gbs, 1), "peak": HBM_PEAK_GBS,
                            "unit": "GB/s", "frac": round(stats_gbs / HBM_PEAK_GBS, 4),
-                           "traffic": None, "kernel": "stats_partial_kernel (+merge, commit, reset)",
+                           "traffic": PMC_TRAFFIC_BYTES.get(wl.cfg, {}).get("statistics")
+                           if cal_rows == wl.m else None, "kernel": "stats_partial_kernel (+merge, commit, reset)",
                            "avg_launch_ms": round(t_stats / nl, 4), "bytes_per_step": stats_bytes},
         "phases_ms": {"calibration_forward_fp32": round(t_cal, 4), "statistics": round(t_stats, 4),
                       "solve_fold": round(t_fit, 4), "forward_int8": round(t_fwd, 4)},
