@@ -48,8 +48,11 @@ struct Split {
 inline Split make_split(int64_t n_rows, int c_out, int vec) {
   Split s;
   s.col_groups = (int)ceil_div(c_out, kWave * vec);
-  const int64_t target_tasks = 256 * 4 * 4;  // ~4 wavefronts per SIMD
-  int64_t rb = ceil_div(target_tasks, s.col_groups);
+  // As many tasks as the chip holds at once: 256 compute units x 4 SIMDs x 3 resident wavefronts
+  // (the kernel's register budget).  All tasks then start together, do equal work and finish
+  // together; a few more than that would leave a second, nearly empty round.
+  const int64_t resident_tasks = 256 * 4 * 3;
+  int64_t rb = resident_tasks / s.col_groups;
   const int64_t max_rb = ceil_div(n_rows, 64);  // at least 64 rows per task
   if (rb > max_rb) rb = max_rb;
   if (rb < 1) rb = 1;
@@ -222,7 +225,8 @@ __global__ __launch_bounds__(kMergeWaves *kWave) void stats_merge_kernel(
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    __threadfence();
+    // no fence needed: this workgroup's read of the count has already returned its value, and
+    // its sums only have to be visible at the end of the kernel
     unsigned *ticket = reinterpret_cast<unsigned *>(static_cast<char *>(stats) + 16);
     if (atomicAdd(ticket, 1u) == gridDim.x - 1) {
       *ticket = 0;
@@ -241,8 +245,14 @@ __global__ __launch_bounds__(kThreads) void stats_reset_kernel(void *stats, int 
   }
 }
 
+__global__ void zero_i32_kernel(int32_t *p) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0;
+}
+
 // Eq. 4-5 from the shifted sums, fp64.
-__global__ __launch_bounds__(1024) void solve_kernel(const void *stats, int c_out, double var_eps,
+// Eq. 4-5 per channel; grid-stride over channels.  With several workgroups the fallback count is
+// added atomically (integer, order-independent) to a counter the host zeroed beforehand.
+__global__ __launch_bounds__(256) void solve_kernel(const void *stats, int c_out, double var_eps,
                                                      float *__restrict__ alpha,
                                                      float *__restrict__ beta,
                                                      double *__restrict__ moments,
@@ -250,7 +260,7 @@ __global__ __launch_bounds__(1024) void solve_kernel(const void *stats, int c_ou
   const StatsView sv = view(const_cast<void *>(stats), c_out);
   const int64_t n = *sv.n;
   int deg = 0;
-  for (int ch = threadIdx.x; ch < c_out; ch += blockDim.x) {
+  for (int ch = blockIdx.x * blockDim.x + threadIdx.x; ch < c_out; ch += gridDim.x * blockDim.x) {
     double mf = 0.0, mq = 0.0, vq = 0.0, cqf = 0.0, vf = 0.0;
     if (n > 0) {
       const double dn = (double)n;
@@ -286,14 +296,15 @@ __global__ __launch_bounds__(1024) void solve_kernel(const void *stats, int c_ou
     }
   }
   if (n_degenerate) {
-    __shared__ int s_deg[1024 / kWave];
+    __shared__ int s_deg[256 / kWave];
     deg = wave_sum(deg);
     if ((threadIdx.x & (kWave - 1)) == 0) s_deg[threadIdx.x / kWave] = deg;
     __syncthreads();
     if (threadIdx.x == 0) {
       int t = 0;
       for (int i = 0; i < (int)(blockDim.x / kWave); ++i) t += s_deg[i];
-      *n_degenerate = t;
+      if (gridDim.x == 1) *n_degenerate = t;
+      else if (t) atomicAdd(n_degenerate, t);
     }
   }
 }
@@ -368,7 +379,9 @@ extern "C" cwac_status cwac_solve(const void *stats, int32_t c_out, double var_e
   if (!aligned(stats, 16) || !aligned(alpha, 4) || !aligned(beta, 4) ||
       (moments && !aligned(moments, 8)))
     return CWAC_E_ALIGN;
-  solve_kernel<<<1, 1024, 0, as_stream(stream)>>>(stats, c_out, var_eps, alpha, beta, moments,
-                                                  n_degenerate);
+  const unsigned blocks = (unsigned)ceil_div(c_out, 256);
+  if (n_degenerate && blocks > 1) zero_i32_kernel<<<1, 64, 0, as_stream(stream)>>>(n_degenerate);
+  solve_kernel<<<blocks, 256, 0, as_stream(stream)>>>(stats, c_out, var_eps, alpha, beta, moments,
+                                                     n_degenerate);
   return launch_status();
 }

@@ -20,8 +20,13 @@ __device__ __forceinline__ double sat_round(double v, double lim, int &nsat) {
   return r;
 }
 
-// One workgroup; channel loop strided over its lanes.  O(channels) work.
-__global__ __launch_bounds__(1024) void fold_kernel(
+__global__ void zero_count_kernel(int32_t *p) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0;
+}
+
+// Grid-stride over channels, O(channels) work.  With several workgroups the saturation count is
+// added atomically (integer, order-independent) to a counter the host zeroed beforehand.
+__global__ __launch_bounds__(256) void fold_kernel(
     const float *__restrict__ alpha, const float *__restrict__ beta,
     const float *__restrict__ sw, const float *__restrict__ bias,
     const int32_t *__restrict__ colsum, int n_out, int mode, int per_token, float sx, int zx,
@@ -29,7 +34,7 @@ __global__ __launch_bounds__(1024) void fold_kernel(
     int32_t *__restrict__ n_saturated) {
   int nsat = 0;
   const double lim = 1073741824.0;  // 2^30
-  for (int c = threadIdx.x; c < n_out; c += blockDim.x) {
+  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n_out; c += gridDim.x * blockDim.x) {
     const double a = alpha ? (double)alpha[c] : 1.0;
     const double b = beta ? (double)beta[c] : 0.0;
     const double w = (double)sw[c];
@@ -56,14 +61,15 @@ __global__ __launch_bounds__(1024) void fold_kernel(
     }
   }
   if (n_saturated) {
-    __shared__ int s_cnt[1024 / kWave];
+    __shared__ int s_cnt[256 / kWave];
     nsat = wave_sum(nsat);
     if ((threadIdx.x & (kWave - 1)) == 0) s_cnt[threadIdx.x / kWave] = nsat;
     __syncthreads();
     if (threadIdx.x == 0) {
       int t = 0;
       for (int i = 0; i < (int)(blockDim.x / kWave); ++i) t += s_cnt[i];
-      *n_saturated = t;
+      if (gridDim.x == 1) *n_saturated = t;
+      else if (t) atomicAdd(n_saturated, t);
     }
   }
 }
@@ -192,7 +198,9 @@ extern "C" cwac_status cwac_fold(const float *alpha, const float *beta, const fl
   if ((alpha == nullptr) != (beta == nullptr)) return CWAC_E_MODE;
   if (qp->mode == CWAC_EPI_FP_BIAS && !fbias) return CWAC_E_NULL;
   if (n_out < 1 || n_out > 65536) return CWAC_E_SHAPE;
-  fold_kernel<<<1, 1024, 0, as_stream(stream)>>>(alpha, beta, s_w, bias, colsum, n_out, qp->mode,
+  const unsigned blocks = (unsigned)ceil_div(n_out, 256);
+  if (n_saturated && blocks > 1) zero_count_kernel<<<1, 64, 0, as_stream(stream)>>>(n_saturated);
+  fold_kernel<<<blocks, 256, 0, as_stream(stream)>>>(alpha, beta, s_w, bias, colsum, n_out, qp->mode,
                                                  qp->act_per_token, qp->s_x, qp->z_x, qp->s_r,
                                                  mult, offset, fbias, n_saturated);
   return launch_status();

@@ -305,6 +305,11 @@ def test_stats_and_solve_config1(orc, case1):
     _check_moments(mom2, c.moments)
     np.testing.assert_allclose(mom2, mom, rtol=1e-9, atol=1e-12)
     _check_fit(a2, b2, c)
+    # degenerate channels spread over several workgroups of the solve kernel are all counted
+    yq_c = c.y_quant.copy()
+    yq_c[:, [3, 400, 1100]] = 0.5
+    a4, _, _, nd4, _ = _stats(yf, dev(yq_c))
+    assert nd4 == 3 and a4[3] == a4[400] == a4[1100] == 1.0
     # bit-reproducible for a given split
     a3, b3, mom3, _, _ = _stats(yf, yq)
     np.testing.assert_array_equal(mom3, mom)
