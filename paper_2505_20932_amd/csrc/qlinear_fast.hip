@@ -18,6 +18,9 @@
 // Requires m >= 256, n >= 256, k % BK == 0.  Edge tiles are shifted inwards to overlap their
 // neighbours (identical values are written twice) instead of being predicated.
 #include <stdlib.h>
+#include <string.h>
+
+#include <type_traits>
 
 #include "qlinear_common.h"
 
@@ -32,7 +35,7 @@ constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
   return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
 }
 
-template <int BK, int NSTAGE>
+template <int BK, int NSTAGE, int NCHUNK>
 struct FastCfg {
   static constexpr int BM = 256, BN = 256;
   static constexpr int KK = BK / 32;  // MFMA k-steps per stage
@@ -44,7 +47,9 @@ struct FastCfg {
   static constexpr int RPL = 64 / CPR;       // rows covered by one wavefront load
   static constexpr int LOADS = 64 / RPL;     // loads per wavefront, panel and stage
   static constexpr int LPS = 2 * LOADS;      // loads per wavefront and stage
+  static constexpr int CHUNK = LPS / NCHUNK;  // loads issued together, once per k-step
   static_assert(BK == 64 || BK == 128, "K step");
+  static_assert(NCHUNK >= 1 && NCHUNK <= KK && LPS % NCHUNK == 0, "load chunks per stage");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one compute unit");
   static_assert((NSTAGE - 1) * LPS < 64, "vmcnt is a 6-bit counter");
   // swizzle of the 16-byte chunk position inside a row, a function of the row's low 4 bits
@@ -188,9 +193,9 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
   if (VEC && OUT_KIND == CWAC_OUT_INT8) store_slab<OUT_KIND>(slab, wbase, row_bytes, lane);
 }
 
-template <int BK, int NSTAGE, int OUT_KIND, bool INT_ONLY>
+template <int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
 __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
-  using C = FastCfg<BK, NSTAGE>;
+  using C = FastCfg<BK, NSTAGE, NCHUNK>;
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   int32_t *s_off = reinterpret_cast<int32_t *>(smem + C::RING);
   float *s_mult = reinterpret_cast<float *>(smem + C::RING + 1024);
@@ -235,16 +240,24 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   const int8_t *xtile = p.x + bm0 * p.ldx;
   const int8_t *wtile = p.w + (int64_t)bn0 * p.ldw;
 
-  auto issue_stage = [&](int buf, int k0) {
+  // chunk c of a stage's 2*LOADS loads (activation loads first, then weight loads)
+  auto issue_chunk = [&](int buf, int k0, int c) {
     int8_t *sx = smem + buf * C::STAGE + wave_s * 64 * BK;
     int8_t *sw = sx + C::X_BYTES;
     const int8_t *xk = xtile + k0, *wk = wtile + k0;
 #pragma unroll
-    for (int i = 0; i < C::LOADS; ++i)
-      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
+    for (int j = 0; j < C::CHUNK; ++j) {
+      const int i = c * C::CHUNK + j;
+      if (i < C::LOADS)
+        __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
+      else
+        __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wk + wvo[i - C::LOADS]),
+                                         CWAC_LDS_PTR(sw + (i - C::LOADS) * C::RPL * BK), 16, 0, 0);
+    }
+  };
+  auto issue_stage = [&](int buf, int k0) {
 #pragma unroll
-    for (int i = 0; i < C::LOADS; ++i)
-      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wk + wvo[i]), CWAC_LDS_PTR(sw + i * C::RPL * BK), 16, 0, 0);
+    for (int c = 0; c < NCHUNK; ++c) issue_chunk(buf, k0, c);
   };
 
   // ---- LDS -> MFMA operand fragments (rows of a 32-row MFMA tile start at multiples of 16)
@@ -267,15 +280,28 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
       for (int b = 0; b < 4; ++b)
         acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
   };
-  // scheduler hint: the eight LDS reads of the next step go behind the first eight MFMAs of this
-  // one, one by one, so that they land half a step before they are needed
-  auto interleave = [&]() {
+  // Scheduler hint for one k-step (16 MFMAs, 8 LDS reads of the next step's fragments and, when
+  // `loads`, one chunk of panel loads): the LDS reads go behind the first eight MFMAs one by one,
+  // so that they land half a step before they are needed; the panel loads are spread evenly
+  // over the second eight, so that their issue never holds up the matrix pipe.
+  auto interleave = [&](bool loads) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    if (loads) {
+      constexpr int PER = C::CHUNK >= 8 ? 1 : 8 / C::CHUNK;          // MFMAs per load group
+      constexpr int GRP = C::CHUNK >= 8 ? C::CHUNK / 8 : 1;          // loads per group
+#pragma unroll
+      for (int i = 0; i < 8 / PER; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, GRP, 0);
+      }
+    } else {
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // one k-step per scheduling region
   };
 
   // ---- prologue: fill the ring, stage the parameters, start the accumulators at offset[n]
@@ -306,11 +332,19 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   v4i fwA[4], fxA[4], fwB[4], fxB[4];
   read_frags(0, 0, fwA, fxA);
 
-  // One stage: KK k-steps; before the MFMAs of the last one, everybody has fetched its last
-  // fragments of this stage (its buffer is free) and the next stage has landed.
-  auto stage_body = [&](int s, int buf, bool issue) {
+  // One stage: KK k-steps.  Before the MFMAs of the last one, everybody has fetched its last
+  // fragments of this stage (its buffer is free) and the next stage has landed.  The loads of
+  // stage s + NSTAGE go into the freed buffer in NCHUNK chunks, one per k-step: chunk 0 in this
+  // stage's last k-step, chunk c in k-step c - 1 of the next stage.
+  // STEADY: 1 <= s and s + NSTAGE < stages, so every chunk exists and the wait count is constant.
+  auto stage_body = [&](int s, int buf, auto steady_tag) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    const bool late_ok = STEADY || (s >= 1 && s - 1 + NSTAGE < stages);  // chunks >= 1 of stage s-1+NSTAGE
+    const bool first_ok = STEADY || (s + NSTAGE < stages);               // chunk 0 of stage s+NSTAGE
 #pragma unroll
     for (int kk = 0; kk + 1 < C::KK; ++kk) {
+      const bool ld = (kk + 1 < NCHUNK) && late_ok;
+      if (ld) issue_chunk((buf + NSTAGE - 1) % NSTAGE, (s - 1 + NSTAGE) * BK, kk + 1);
       if (kk & 1) {
         read_frags(buf, kk + 1, fwA, fxA);
         mma(fwB, fxB);
@@ -318,43 +352,44 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
         read_frags(buf, kk + 1, fwB, fxB);
         mma(fwA, fxA);
       }
-      interleave();
+      interleave(ld);
     }
     __builtin_amdgcn_sched_barrier(0);  // keep the MFMAs above on this side of the wait
-    if (issue)
-      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm((NSTAGE - 2) * C::LPS, 0));
-    else
-      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    // loads issued so far reach stage min(stages, s + NSTAGE) - 1; stage s + 1 must have landed
+    if (STEADY || s == 0) {
+      if (STEADY || stages >= NSTAGE)
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm((NSTAGE - 2) * C::LPS, 0));
+      else
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    } else {
+      const int beyond = (s - 1 + NSTAGE < stages ? s - 1 + NSTAGE : stages - 1) - (s + 1);
+      if (NSTAGE >= 3 && beyond >= NSTAGE - 2)
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm((NSTAGE - 2) * C::LPS, 0));
+      else if (NSTAGE >= 4 && beyond == NSTAGE - 3)
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm((NSTAGE - 3) * C::LPS, 0));
+      else
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    }
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    if (issue) issue_stage(buf, (s + NSTAGE) * BK);
+    if (first_ok) issue_chunk(buf, (s + NSTAGE) * BK, 0);
     // KK is even: the last step's fragments are in B, the next stage's first go to A
-    if (issue || s + 1 < stages) read_frags((buf + 1) % NSTAGE, 0, fwA, fxA);
+    if (STEADY || s + 1 < stages) read_frags((buf + 1) % NSTAGE, 0, fwA, fxA);
     mma(fwB, fxB);
-    if (issue) {
-      // spread the panel loads and the next stage's first fragment reads over the 16 MFMAs
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, C::LPS / 8, 0);
-      }
-    } else {
-      interleave();
-    }
+    interleave(first_ok);
   };
 
   int s = 0;
+  if (stages > 0) stage_body(0, 0, std::false_type{});
+  s = 1;
+  // steady state, unrolled over the ring so that LDS offsets are compile-time constants
+  for (; s % NSTAGE != 0 && s + NSTAGE < stages; ++s) stage_body(s, s % NSTAGE, std::true_type{});
   for (; s + 2 * NSTAGE <= stages; s += NSTAGE) {
 #pragma unroll
-    for (int j = 0; j < NSTAGE; ++j) stage_body(s + j, j, true);
+    for (int j = 0; j < NSTAGE; ++j) stage_body(s + j, j, std::true_type{});
   }
-  for (; s + NSTAGE < stages; ++s) stage_body(s, s % NSTAGE, true);
-  for (; s < stages; ++s) stage_body(s, s % NSTAGE, false);
+  for (; s + NSTAGE < stages; ++s) stage_body(s, s % NSTAGE, std::true_type{});
+  for (; s < stages; ++s) stage_body(s, s % NSTAGE, std::false_type{});
 
   // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
   constexpr int ESZ = OUT_KIND == CWAC_OUT_INT8 ? 1 : 4;
@@ -365,24 +400,24 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
     fast_epilogue<OUT_KIND, INT_ONLY, false>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
 }
 
-template <int BK, int NSTAGE, int OUT_KIND, bool INT_ONLY>
+template <int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
 cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
-  using C = FastCfg<BK, NSTAGE>;
+  using C = FastCfg<BK, NSTAGE, NCHUNK>;
   static const hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&qlinear_fast_kernel<BK, NSTAGE, OUT_KIND, INT_ONLY>),
+      reinterpret_cast<const void *>(&qlinear_fast_kernel<BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY>),
       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<BK, NSTAGE, OUT_KIND, INT_ONLY><<<grid, 256, C::LDS_BYTES, st>>>(p);
+  qlinear_fast_kernel<BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, 256, C::LDS_BYTES, st>>>(p);
   return launch_status();
 }
 
-template <int BK, int NSTAGE>
+template <int BK, int NSTAGE, int NCHUNK>
 cwac_status launch_cfg(const FwdParams &p, int out_kind, bool int_only, dim3 grid, hipStream_t st) {
   if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_one<BK, NSTAGE, CWAC_OUT_INT8, true>(p, grid, st)
-                    : launch_one<BK, NSTAGE, CWAC_OUT_INT8, false>(p, grid, st);
-  if (out_kind == CWAC_OUT_FP32) return launch_one<BK, NSTAGE, CWAC_OUT_FP32, false>(p, grid, st);
-  return launch_one<BK, NSTAGE, CWAC_OUT_INT32, false>(p, grid, st);
+    return int_only ? launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true>(p, grid, st)
+                    : launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false>(p, grid, st);
+  if (out_kind == CWAC_OUT_FP32) return launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false>(p, grid, st);
+  return launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false>(p, grid, st);
 }
 
 }  // namespace
@@ -395,10 +430,12 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
   const dim3 grid((unsigned)blocks);
-  // Tuning knob: CWAC_FWD_PIPE=128x2 | 64x4 selects the K step and ring depth (same results).
+  // Tuning knob: CWAC_FWD_PIPE=128x2 | 128x2x4 | 64x4 selects K step, ring depth and the number of
+  // chunks a stage's loads are issued in (same results).
   const char *e = getenv("CWAC_FWD_PIPE");
-  if (e && e[0] == '6') return launch_cfg<64, 4>(p, out_kind, int_only, grid, st);
-  return launch_cfg<128, 2>(p, out_kind, int_only, grid, st);
+  if (e && e[0] == '6') return launch_cfg<64, 4, 2>(p, out_kind, int_only, grid, st);
+  if (e && e[0] == '1' && e[strlen(e) - 1] == '4') return launch_cfg<128, 2, 4>(p, out_kind, int_only, grid, st);
+  return launch_cfg<128, 2, 2>(p, out_kind, int_only, grid, st);
 }
 
 }  // namespace cwac
