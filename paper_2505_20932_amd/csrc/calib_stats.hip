@@ -3,9 +3,9 @@
 // The pass is a pure streaming read of Y_full and Y_quant (8 bytes per row and
 // channel), so the kernel is shaped for HBM bandwidth: every lane owns 4
 // adjacent channels (one 16-byte load per matrix and row), a wavefront covers
-// 1 KiB of contiguous row and a workgroup up to 4 KiB, 16 loads are in flight
-// per lane, there is no LDS traffic and no barrier, and nothing is written but
-// O(channels) partial sums.  Sums are taken of pivot-shifted values
+// 1 KiB of contiguous row, 16 loads are in flight per lane, the streaming loop
+// touches no LDS and no barrier, and nothing is written but O(channels) partial
+// sums (the four wavefronts of a workgroup add theirs up through LDS first).  Sums are taken of pivot-shifted values
 // in fp64, so channels whose mean dwarfs their spread lose no precision, and in a
 // fixed order (no floating-point atomics), so results are bit-reproducible.
 #include "cwac_internal.h"
@@ -37,11 +37,13 @@ __host__ __device__ inline StatsView view(void *stats, int c) {
 
 // Row split of one call: the same function sizes the workspace and the launch.
 // The unit of work is a WAVE TASK: one wavefront owns 64*VEC adjacent channels over a block of
-// rows.  Consecutive tasks take adjacent channel groups of the same row block, so the four
-// wavefronts of a workgroup read up to 4 KiB of contiguous row from each matrix.
+// rows.  The four wavefronts of a workgroup take four consecutive row blocks of the SAME channel
+// group and add their sums up before writing, so there is one partial sum per channel and
+// workgroup (row group); consecutive workgroups take adjacent channel groups.
 struct Split {
   int col_groups;       // wave tasks along channels
-  int row_blocks;       // wave tasks along rows = number of partial sums per channel
+  int row_blocks;       // wave tasks along rows
+  int row_groups;       // workgroups along rows = number of partial sums per channel
   int64_t rows_per_block;
 };
 
@@ -52,12 +54,13 @@ inline Split make_split(int64_t n_rows, int c_out, int vec) {
   // (the kernel's register budget).  All tasks then start together, do equal work and finish
   // together; a few more than that would leave a second, nearly empty round.
   const int64_t resident_tasks = 256 * 4 * 3;
-  int64_t rb = resident_tasks / s.col_groups;
+  int64_t rb = resident_tasks / s.col_groups / kWaves * kWaves;
   const int64_t max_rb = ceil_div(n_rows, 64);  // at least 64 rows per task
   if (rb > max_rb) rb = max_rb;
   if (rb < 1) rb = 1;
   s.rows_per_block = ceil_div(n_rows, rb);
   s.row_blocks = (int)ceil_div(n_rows, s.rows_per_block);
+  s.row_groups = (int)ceil_div(s.row_blocks, kWaves);
   return s;
 }
 
@@ -77,27 +80,32 @@ struct Ld<1> {
   __device__ static void unpack(const float &v, float (&o)[1]) { o[0] = v; }
 };
 
-// Stage 1.  One wave task per wavefront (4 per workgroup): lane l owns channels
-// c0 + VEC*l .. +VEC-1 and walks its row block with 2*U to 4*U 16-byte loads in flight.
-// partial[row_block][stat][channel] receives the task's sums; no LDS, no barrier.
+// Stage 1.  One wave task per wavefront: lane l owns channels c0 + VEC*l .. +VEC-1 and walks
+// its row block with 2*U to 4*U 16-byte loads in flight.  Workgroup (cg, rg) = channel group cg,
+// row blocks 4*rg .. 4*rg+3; partial[rg][stat][channel] receives the sum of its four tasks,
+// added in wavefront order.
 template <int VEC>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void stats_partial_kernel(
     const float *__restrict__ yf, int64_t ldf, const float *__restrict__ yq, int64_t ldq,
-    int64_t n_rows, int c_out, int col_groups, int64_t n_tasks, int64_t rows_per_block,
+    int64_t n_rows, int c_out, int col_groups, int row_blocks, int64_t rows_per_block,
     const void *stats, double *__restrict__ partial) {
   using V = typename Ld<VEC>::T;
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t task = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
-  if (task >= n_tasks) return;
-  const int cg = (int)(task % col_groups);
-  const int64_t rb = task / col_groups;
+  __shared__ double red[kWaves - 1][kStats * VEC][kWave];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int cg = (int)(blockIdx.x % (unsigned)col_groups);
+  const int rg = (int)(blockIdx.x / (unsigned)col_groups);
+  const int rb = rg * kWaves + wave;
   const int c = (cg * kWave + lane) * VEC;
-  if (c >= c_out) return;  // VEC == 4 requires c_out % 4 == 0, so a lane is all in or all out
+  // VEC == 4 requires c_out % 4 == 0, so a lane is all in or all out
+  const bool lane_in = c < c_out;
+  const bool active = lane_in && rb < row_blocks;
 
   const StatsView sv = view(const_cast<void *>(stats), c_out);
   const bool first = (*sv.n == 0);
   float pq[VEC], pf[VEC];
-  {
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) pq[j] = pf[j] = 0.0f;
+  if (active) {
     V vq = first ? *reinterpret_cast<const V *>(yq + c) : *reinterpret_cast<const V *>(sv.pivot_q + c);
     V vf = first ? *reinterpret_cast<const V *>(yf + c) : *reinterpret_cast<const V *>(sv.pivot_f + c);
     Ld<VEC>::unpack(vq, pq);
@@ -110,8 +118,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
 #pragma unroll
     for (int s = 0; s < kStats; ++s) acc[j][s] = 0.0;
 
-  const int64_t r_begin = rb * rows_per_block;
-  int64_t r_end = r_begin + rows_per_block;
+  const int64_t r_begin = active ? rb * rows_per_block : 0;
+  int64_t r_end = active ? r_begin + rows_per_block : 0;  // inactive tasks walk no rows
   if (r_end > n_rows) r_end = n_rows;
 
   auto consume = [&](const V &vq, const V &vf) {
@@ -175,15 +183,30 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
     consume(vq, vf);
   }
 
+  // wavefronts 1..3 hand their sums to wavefront 0, which adds them in order and writes
+  if (wave > 0) {
 #pragma unroll
-  for (int s = 0; s < kStats; ++s)
+    for (int s = 0; s < kStats; ++s)
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) partial[(rb * kStats + s) * c_out + c + j] = acc[j][s];
+      for (int j = 0; j < VEC; ++j) red[wave - 1][s * VEC + j][lane] = acc[j][s];
+  }
+  __syncthreads();
+  if (wave == 0 && lane_in) {
+#pragma unroll
+    for (int s = 0; s < kStats; ++s)
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        double t = acc[j][s];
+#pragma unroll
+        for (int w = 0; w < kWaves - 1; ++w) t += red[w][s * VEC + j][lane];
+        partial[((int64_t)rg * kStats + s) * c_out + c + j] = t;
+      }
+  }
 }
 
-// Stage 2: fixed-order sum over row blocks, added into the state; the first batch also
+// Stage 2: fixed-order sum over row groups, added into the state; the first batch also
 // records the pivots (row 0 of that batch).  One workgroup per (statistic, 64 channels):
-// wavefront w sums row blocks w, w+16, ... and the 16 wave sums are combined in order.
+// wavefront w sums row groups w, w+16, ... and the 16 wave sums are combined in order.
 // The last workgroup to finish bumps the row count: every workgroup reads the count before
 // it takes its ticket, so none can see the new value.
 constexpr int kMergeWaves = 16;
@@ -333,8 +356,8 @@ extern "C" size_t cwac_calibrate_stats_workspace(int64_t n_rows, int32_t c_out) 
   if (n_rows < 1 || c_out < 1) return 16;
   // sized for the generic (one channel per lane) split, which never needs less
   const Split a = make_split(n_rows, c_out, 1), b = make_split(n_rows, c_out, 4);
-  const int rb = a.row_blocks > b.row_blocks ? a.row_blocks : b.row_blocks;
-  return (size_t)rb * kStats * c_out * sizeof(double);
+  const int rg = a.row_groups > b.row_groups ? a.row_groups : b.row_groups;
+  return (size_t)rg * kStats * c_out * sizeof(double);
 }
 
 extern "C" cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full,
@@ -355,19 +378,20 @@ extern "C" cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full
                    aligned(y_full, 16) && aligned(y_quant, 16);
   const Split sp = make_split(n_rows, c_out, vec ? 4 : 1);
   double *partial = static_cast<double *>(workspace);
-  const int64_t n_tasks = (int64_t)sp.col_groups * sp.row_blocks;
-  const unsigned grid = (unsigned)ceil_div(n_tasks, kWaves);
+  const int64_t blocks = (int64_t)sp.col_groups * sp.row_groups;
+  if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
+  const unsigned grid = (unsigned)blocks;
   hipStream_t st = as_stream(stream);
   if (vec)
     stats_partial_kernel<4><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
-                                                       c_out, sp.col_groups, n_tasks,
+                                                       c_out, sp.col_groups, sp.row_blocks,
                                                        sp.rows_per_block, stats, partial);
   else
     stats_partial_kernel<1><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
-                                                       c_out, sp.col_groups, n_tasks,
+                                                       c_out, sp.col_groups, sp.row_blocks,
                                                        sp.rows_per_block, stats, partial);
   stats_merge_kernel<<<(unsigned)(kStats * ceil_div(c_out, kWave)), kMergeWaves * kWave, 0, st>>>(
-      partial, sp.row_blocks, c_out, y_full, y_quant, stats, n_rows);
+      partial, sp.row_groups, c_out, y_full, y_quant, stats, n_rows);
   return launch_status();
 }
 

@@ -86,7 +86,15 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
   for (int i = 0; i < 16; ++i) {
     const int row = i * 8 + rd_row;
     const v4i v = *reinterpret_cast<const v4i *>(slab + row * kSlabStride + rd_chunk * 16);
-    *reinterpret_cast<v4i *>(gbase + row * row_bytes + rd_chunk * 16) = v;
+    v4i *dst = reinterpret_cast<v4i *>(gbase + row * row_bytes + rd_chunk * 16);
+    // 4-byte outputs (the calibration forward's Y_quant) are far larger than the caches and are
+    // streamed out: written normally they linger as dirty lines whose write-back then competes
+    // with the reads of the statistics pass that follows
+    // (int8 results stay cacheable for the layer that consumes them)
+    if (OUT_KIND != CWAC_OUT_INT8)
+      __builtin_nontemporal_store(v, dst);
+    else
+      *dst = v;
   }
 }
 
