@@ -197,6 +197,49 @@ def comparators(P, torch, layers, reps: int = 5):
             "unfused_over_fused": round(t_unf / t_fused, 3)}
 
 
+def fused_calibration(P, torch, layers, reps: int = 5):
+    """The calibration side of the step (Sec. 3.3) as one call: the statistics taken in the
+    epilogue of the calibration GEMM, so that Y_quant never reaches memory, against the two calls
+    the timed step uses (fp32 forward, then the statistics pass).  ms per pass over all layers;
+    None where a layer's shape is outside the fused kernel's range."""
+    dev = layers[0].xq.device
+    if any(L.cal_rows < 256 or L.n < 256 or L.k % 128 or L.n % 4 for L in layers):
+        return None
+    ws = [torch.empty(P.cwac_calibrate_fused_workspace(L.cal_rows, L.n), dtype=torch.uint8,
+                      device=dev) for L in layers]
+
+    def two_calls():
+        for L in layers:
+            P.qlinear_cwac_forward(L.xq_cal, L.wq, None, L.deq_mult, L.deq_off,
+                                   L.deq_fb if L.bias is not None else None, L.sx_row_cal,
+                                   P.CWAC_OUT_FP32, L.yq)
+            P.cwac_stats_reset(L.stats, L.n)
+            P.cwac_calibrate_stats(L.y_full, L.yq, L.stats, L.ws)
+
+    def fused():
+        for L, w in zip(layers, ws):
+            P.cwac_stats_reset(L.stats, L.n)
+            P.qlinear_cwac_calibrate_fused(L.xq_cal, L.wq, L.deq_mult, L.deq_off,
+                                           L.deq_fb if L.bias is not None else None,
+                                           L.sx_row_cal, L.y_full, L.stats, w)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_a1, t_b1, t_a2, t_b2 = timed(two_calls), timed(fused), timed(two_calls), timed(fused)
+    t_two, t_fused = (t_a1 + t_a2) / 2, (t_b1 + t_b2) / 2
+    return {"forward_fp32_then_statistics_ms": round(t_two, 4), "fused_ms": round(t_fused, 4),
+            "speedup": round(t_two / t_fused, 3)}
+
+
 def cpu_baseline(synth, cfg: int, sample_rows: int):
     """The oracle, as it stands, timed on this host on a bounded row sample of the same step."""
     import numpy as np
@@ -338,6 +381,7 @@ def main():
         "stats_gbs": round(stats_gbs, 1),
     }
     result["epilogue_comparators"] = comparators(P, torch, layers)
+    result["fused_calibration"] = fused_calibration(P, torch, layers)
     if not args.no_cpu_baseline:
         v, cores, secs = cpu_baseline(synth, args.config, args.cpu_sample_rows)
         result["cpu_baseline"] = {

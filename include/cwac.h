@@ -212,6 +212,27 @@ cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w
                                  const float *s_x_row, int32_t out_kind, void *out, int64_t ldo,
                                  void *stream);
 
+/* Calibration forward with the statistics taken in its epilogue (Sec. 3.3: the
+ * sums of Eq. 4-5 over Y_quant = the CWAC_OUT_FP32 output above and the matching
+ * rows of Y_full).  Equivalent to qlinear_cwac_forward(..., CWAC_OUT_FP32, y_quant)
+ * followed by cwac_calibrate_stats(y_full, y_quant, ...), except that Y_quant is
+ * never written to memory (Y_full is read once: 4 bytes per element instead of
+ * 4 written + 8 read); the state differs from the two-call result only by the
+ * order of its fp64 additions.
+ *   x_q, w_q, mult, offset, fbias, s_x_row   as in qlinear_cwac_forward
+ *   y_full     device fp32 [m, n], ld_full; 16-byte aligned, ld_full % 4 == 0
+ *   stats      device, in/out (cwac_stats_bytes(n) bytes)
+ *   workspace  device, >= cwac_calibrate_fused_workspace(m, n) bytes, 16-byte aligned
+ * Shapes: m >= 256, n >= 256, n % 4 == 0, k % 128 == 0; anything else returns
+ * CWAC_E_SHAPE and launches nothing (use the two separate calls). */
+size_t cwac_calibrate_fused_workspace(int64_t m, int32_t n);
+cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                         int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                         const float *mult, const int32_t *offset,
+                                         const float *fbias, const float *s_x_row,
+                                         const float *y_full, int64_t ld_full, void *stats,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Un-fused comparators (what the fold removes; Sec. 3.3 last sentence,       */
 /* Sec. 3.4 first paragraph)                                                  */

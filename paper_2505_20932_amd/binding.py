@@ -22,7 +22,8 @@ EXPORTS = (
     "cwac_status_string", "cwac_range_workspace", "cwac_range_f32", "cwac_qparams_from_range",
     "cwac_quantize_act", "cwac_quantize_rows_sym", "cwac_colsum", "cwac_stats_bytes",
     "cwac_stats_reset", "cwac_calibrate_stats_workspace", "cwac_calibrate_stats", "cwac_solve",
-    "cwac_fold", "qlinear_cwac_forward", "cwac_epilogue_int32", "cwac_apply_unfolded",
+    "cwac_fold", "qlinear_cwac_forward", "cwac_calibrate_fused_workspace",
+    "qlinear_cwac_calibrate_fused", "cwac_epilogue_int32", "cwac_apply_unfolded",
 )
 
 
@@ -65,6 +66,9 @@ def lib() -> C.CDLL:
             "cwac_fold": (i32, [vp, vp, vp, vp, vp, i32, qpp, vp, vp, vp, vp, vp]),
             "qlinear_cwac_forward": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp, vp, vp,
                                            i32, vp, i64, vp]),
+            "cwac_calibrate_fused_workspace": (sz, [i64, i32]),
+            "qlinear_cwac_calibrate_fused": (i32, [vp, i64, vp, i64, i64, i32, i32, vp, vp, vp, vp,
+                                                   vp, i64, vp, vp, sz, vp]),
             "cwac_epilogue_int32": (i32, [vp, i64, i64, i32, qpp, vp, vp, vp, vp, i32, vp, i64, vp]),
             "cwac_apply_unfolded": (i32, [vp, i64, i64, i32, vp, vp, vp, i64, vp]),
         }
@@ -200,6 +204,25 @@ def qlinear_cwac_forward(x_q: torch.Tensor, w_q: torch.Tensor, qp: Optional[cwac
                                       k, C.byref(qp) if qp is not None else None, _ptr(mult),
                                       _ptr(offset), _ptr(fbias), _ptr(s_x_row), out_kind, _ptr(out),
                                       _rowmajor(out), _stream(stream)), "qlinear_cwac_forward")
+
+
+def cwac_calibrate_fused_workspace(m: int, n: int) -> int:
+    return int(lib().cwac_calibrate_fused_workspace(m, n))
+
+
+def qlinear_cwac_calibrate_fused(x_q: torch.Tensor, w_q: torch.Tensor, mult, offset, fbias, s_x_row,
+                                 y_full: torch.Tensor, stats: torch.Tensor,
+                                 workspace: torch.Tensor, stream=None):
+    assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8 and y_full.dtype == torch.float32
+    m, k = x_q.shape
+    n, k2 = w_q.shape
+    assert k == k2 and y_full.shape == (m, n)
+    _check(lib().qlinear_cwac_calibrate_fused(_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q),
+                                              m, n, k, _ptr(mult), _ptr(offset), _ptr(fbias),
+                                              _ptr(s_x_row), _ptr(y_full), _rowmajor(y_full),
+                                              _ptr(stats), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(),
+                                              _stream(stream)), "qlinear_cwac_calibrate_fused")
 
 
 def cwac_epilogue_int32(acc: torch.Tensor, qp, mult, offset, fbias, s_x_row, out_kind: int,

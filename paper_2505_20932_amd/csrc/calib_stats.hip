@@ -15,26 +15,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kStats = 5;  // sum dq, sum df, sum dq*dq, sum dq*df, sum df*df
-constexpr int kHeaderBytes = 64;
-
-struct StatsView {
-  int64_t *n;
-  float *pivot_q;
-  float *pivot_f;
-  double *sum;  // [kStats][c]
-};
-
-__host__ __device__ inline StatsView view(void *stats, int c) {
-  char *b = static_cast<char *>(stats);
-  StatsView v;
-  v.n = reinterpret_cast<int64_t *>(b);
-  v.pivot_q = reinterpret_cast<float *>(b + kHeaderBytes);
-  v.pivot_f = v.pivot_q + c;
-  v.sum = reinterpret_cast<double *>(b + kHeaderBytes + (size_t)8 * c);
-  return v;
-}
-
 // Row split of one call: the same function sizes the workspace and the launch.
 // The unit of work is a WAVE TASK: one wavefront owns 64*VEC adjacent channels over a block of
 // rows.  The four wavefronts of a workgroup take four consecutive row blocks of the SAME channel
@@ -100,7 +80,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
   const bool lane_in = c < c_out;
   const bool active = lane_in && rb < row_blocks;
 
-  const StatsView sv = view(const_cast<void *>(stats), c_out);
+  const StatsView sv = stats_view(const_cast<void *>(stats), c_out);
   const bool first = (*sv.n == 0);
   float pq[VEC], pf[VEC];
 #pragma unroll
@@ -217,7 +197,7 @@ __global__ __launch_bounds__(kMergeWaves *kWave) void stats_merge_kernel(
   const int s = blockIdx.x / groups, cg = blockIdx.x - s * groups;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   const int ch = cg * kWave + lane;
-  const StatsView sv = view(stats, c_out);
+  const StatsView sv = stats_view(stats, c_out);
   const bool first = (*sv.n == 0);
   double t = 0.0;
   if (ch < c_out) {
@@ -280,7 +260,7 @@ __global__ __launch_bounds__(256) void solve_kernel(const void *stats, int c_out
                                                      float *__restrict__ beta,
                                                      double *__restrict__ moments,
                                                      int32_t *__restrict__ n_degenerate) {
-  const StatsView sv = view(const_cast<void *>(stats), c_out);
+  const StatsView sv = stats_view(const_cast<void *>(stats), c_out);
   const int64_t n = *sv.n;
   int deg = 0;
   for (int ch = blockIdx.x * blockDim.x + threadIdx.x; ch < c_out; ch += gridDim.x * blockDim.x) {
@@ -333,13 +313,22 @@ __global__ __launch_bounds__(256) void solve_kernel(const void *stats, int c_out
 }
 
 }  // namespace
+
+cwac_status launch_stats_merge(const double *partial, int row_groups, int c_out,
+                               const float *pivot_f_src, const float *pivot_q_src, void *stats,
+                               int64_t n_rows, hipStream_t st) {
+  stats_merge_kernel<<<(unsigned)(kStats * ceil_div(c_out, kWave)), kMergeWaves * kWave, 0, st>>>(
+      partial, row_groups, c_out, pivot_f_src, pivot_q_src, stats, n_rows);
+  return launch_status();
+}
+
 }  // namespace cwac
 
 using namespace cwac;
 
 extern "C" size_t cwac_stats_bytes(int32_t c_out) {
   if (c_out < 1) return 0;
-  return (size_t)kHeaderBytes + (size_t)8 * c_out + (size_t)kStats * 8 * c_out;
+  return (size_t)kStatsHeaderBytes + (size_t)8 * c_out + (size_t)kStats * 8 * c_out;
 }
 
 extern "C" cwac_status cwac_stats_reset(void *stats, int32_t c_out, void *stream) {
@@ -390,9 +379,7 @@ extern "C" cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full
     stats_partial_kernel<1><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
                                                        c_out, sp.col_groups, sp.row_blocks,
                                                        sp.rows_per_block, stats, partial);
-  stats_merge_kernel<<<(unsigned)(kStats * ceil_div(c_out, kWave)), kMergeWaves * kWave, 0, st>>>(
-      partial, sp.row_groups, c_out, y_full, y_quant, stats, n_rows);
-  return launch_status();
+  return launch_stats_merge(partial, sp.row_groups, c_out, y_full, y_quant, stats, n_rows, st);
 }
 
 extern "C" cwac_status cwac_solve(const void *stats, int32_t c_out, double var_eps, float *alpha,

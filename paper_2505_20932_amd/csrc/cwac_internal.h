@@ -47,4 +47,33 @@ __device__ __forceinline__ int requant_code(float u, float lo, float hi, int zr)
   return static_cast<int>(r) + zr;
 }
 
+// ---- calibration state (layout documented in cwac.h): 64-byte header (int64 row count at
+// byte 0, merge ticket at byte 16), pivot_q[C], pivot_f[C] (fp32), sum[kStats][C] (fp64).
+constexpr int kStats = 5;  // sum dq, sum df, sum dq*dq, sum dq*df, sum df*df
+constexpr int kStatsHeaderBytes = 64;
+
+struct StatsView {
+  int64_t *n;
+  float *pivot_q;
+  float *pivot_f;
+  double *sum;  // [kStats][c]
+};
+
+__host__ __device__ inline StatsView stats_view(void *stats, int c) {
+  char *b = static_cast<char *>(stats);
+  StatsView v;
+  v.n = reinterpret_cast<int64_t *>(b);
+  v.pivot_q = reinterpret_cast<float *>(b + kStatsHeaderBytes);
+  v.pivot_f = v.pivot_q + c;
+  v.sum = reinterpret_cast<double *>(b + kStatsHeaderBytes + (size_t)8 * c);
+  return v;
+}
+
+// Second stage of a statistics pass (calib_stats.hip): adds partial[row_group][kStats][c_out] into
+// the state in a fixed order and bumps its row count by n_rows.  A first batch also records the
+// pivots: pivot_q = pivot_q_src[0..c_out), pivot_f = pivot_f_src[0..c_out).
+cwac_status launch_stats_merge(const double *partial, int row_groups, int c_out,
+                               const float *pivot_f_src, const float *pivot_q_src, void *stats,
+                               int64_t n_rows, hipStream_t st);
+
 }  // namespace cwac

@@ -24,7 +24,18 @@ struct FwdParams {
   int zr;
   int vec_store;  // output layout allows 4-element vector stores
   int tiles_m, tiles_n;
+  // fused calibration statistics (kOutStats): Y_full of the same rows and channels, the
+  // calibration state (read: row count, pivots) and partial[tiles_m][kStats][n] (written)
+  const float *y_full;
+  int64_t ld_full;
+  const void *stats;
+  double *partial;
+  const float *yq_row0;  // Y_quant of row 0 [n]: the pivot of a state's first batch
 };
+
+// Internal output kind of the large-problem kernel: nothing is stored but the per-channel sums
+// of the tile's rows of (Y_full, Y_quant).
+constexpr int kOutStats = 3;
 
 // Workgroup id -> output tile.  Consecutive workgroup ids are dealt round-robin
 // to the 8 XCDs (each with its own L2), so ids are first regrouped so that every
@@ -154,6 +165,9 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 
 // Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 256, k % 128 == 0.
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st);
+// Same kernel with the statistics epilogue; additionally requires n % 4 == 0, ld_full % 4 == 0
+// and a 16-byte aligned y_full.  p.partial receives ceil(m / 256) row groups.
+cwac_status launch_fast_stats(FwdParams p, hipStream_t st);
 constexpr int kFastTile = 256;
 constexpr int kFastKStep = 128;
 

@@ -43,6 +43,12 @@ struct FastCfg {
   static constexpr int RING = NSTAGE * STAGE;
   static constexpr int PARAM_BYTES = 4 * 256 * 4;  // offset, mult, fbias [256 channels], row scale [256 rows]
   static constexpr int LDS_BYTES = RING + PARAM_BYTES;
+  // statistics epilogue: + the two pivots of the 256 channels and the area through which the lower
+  // row half of the tile hands its sums to the upper one ([2 wave columns][4][kStats][32] fp64)
+  static constexpr int STATS_EXCH = RING + PARAM_BYTES + 2 * 256 * 4;
+  static constexpr int STATS_LDS_BYTES = STATS_EXCH + 2 * 4 * kStats * 32 * 8;
+  static_assert(RING >= 4 * 32768, "statistics epilogue: 32 KiB of the ring per wavefront");
+  static_assert(STATS_LDS_BYTES <= 160 * 1024, "LDS budget of one compute unit");
   static constexpr int CPR = BK / 16;        // 16-byte chunks per row
   static constexpr int RPL = 64 / CPR;       // rows covered by one wavefront load
   static constexpr int LOADS = 64 / RPL;     // loads per wavefront, panel and stage
@@ -201,6 +207,164 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
   if (VEC && OUT_KIND == CWAC_OUT_INT8) store_slab<OUT_KIND>(slab, wbase, row_bytes, lane);
 }
 
+// Statistics epilogue (Sec. 3.3, Eq. 4-5 fused into the calibration forward): instead of storing
+// Y_quant, the tile adds up, per channel, the five pivot-shifted sums of (Y_quant, Y_full) over
+// its rows and writes them to partial[tile_m][stat][channel]; Y_quant never reaches memory and
+// Y_full is read once.
+//
+// The accumulators hold a channel's rows spread over 32 lanes, the sums need them in one lane.
+// So each wavefront works in 8 phases of (32 channels) x (64 rows): it writes the phase's Y_quant
+// values to a private LDS slab, Y_full of the same rows and channels arrives in a second slab
+// straight from global memory (global_load_lds, issued two phases ahead), and then lane (c, h)
+// walks rows h, h + 2, ... of channel c in both slabs with fp64 sums.  Slab layout: row-major, 128
+// bytes per row, the 16-byte chunk position XORed with (row & 7): conflict-free for the 16-byte
+// row writes and for the 4-byte column reads (the two half-waves read rows of different parity).
+// Rows below `skip` (an edge tile shifted inwards: rows its upper neighbour already counts)
+// contribute zeros.
+template <bool MASKED>
+__device__ __forceinline__ void stats_column_pass(const int8_t *yq_slab, const int8_t *yf_slab,
+                                                  const int (&o4)[4], int h, float pq, float pf,
+                                                  int row0, int skip, double (&sum)[kStats]) {
+#pragma unroll 8
+  for (int j = 0; j < 32; ++j) {
+    const int off = o4[j & 3] + (j >> 2) * 1024;
+    float q = *reinterpret_cast<const float *>(yq_slab + off) - pq;
+    float f = *reinterpret_cast<const float *>(yf_slab + off) - pf;
+    if (MASKED) {
+      const bool ok = row0 + 2 * j + h >= skip;
+      q = ok ? q : 0.0f;
+      f = ok ? f : 0.0f;
+    }
+    const double dq = (double)q, df = (double)f;
+    sum[0] += dq;
+    sum[1] += df;
+    sum[2] = fma(dq, dq, sum[2]);
+    sum[3] = fma(dq, df, sum[3]);
+    sum[4] = fma(df, df, sum[4]);
+  }
+}
+
+__device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4][4], int8_t *smem,
+                                               const float *s_mult, const float *s_fb,
+                                               const float *s_rs, const float *s_pq,
+                                               const float *s_pf, double *s_exch, int64_t bm0, int bn0,
+                                               int tile_m, int wave_m, int wave_n, int wave_s,
+                                               int lane) {
+  const int l32 = lane & 31, half = lane >> 5;
+  int8_t *wl = smem + (wave_s << 15);  // this wavefront's 32 KiB: Y_quant slab, three Y_full slabs
+  int8_t *yq_slab = wl;
+  const bool use_rs = p.sx_row != nullptr, use_fb = p.fbias != nullptr;
+  // rows of this wave tile that the tile above already counts
+  int64_t skip64 = (int64_t)tile_m * 256 - (bm0 + wave_m * 128);
+  const int skip = skip64 < 0 ? 0 : (skip64 > 128 ? 128 : (int)skip64);
+
+  // Y_full loads: one instruction = 8 rows x 128 bytes; lane (row lr, slot) fetches chunk slot ^ lr
+  const int lr = lane >> 3, slot = lane & 7;
+  const uint32_t yvo = (uint32_t)lr * (uint32_t)(p.ld_full * 4) + (uint32_t)((slot ^ lr) << 4);
+  const char *yf_wave = reinterpret_cast<const char *>(p.y_full + (bm0 + wave_m * 128) * p.ld_full + bn0 +
+                                                       wave_n * 128);
+  auto issue_yf = [&](int phase) {
+    const int a = phase >> 1, hb = phase & 1;
+    const char *g = yf_wave + ((int64_t)hb * 64 * p.ld_full + a * 32) * 4;
+    int8_t *dst = wl + 8192 * (1 + phase % 3);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(g + (int64_t)i * 8 * p.ld_full * 4 + yvo),
+                                       CWAC_LDS_PTR(dst + i * 1024), 16, 0, 0);
+  };
+  float rs[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) rs[b] = s_rs[wave_m * 128 + b * 32 + l32];
+  // column pass: lane (channel c, row parity h); offsets of rows h, 2 + h, 4 + h, 6 + h
+  const int c = l32, h = half;
+  int o4[4];
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const int r = 2 * jj + h;
+    o4[jj] = r * 128 + (((c >> 2) ^ r) << 4) + (c & 3) * 4;
+  }
+  double tot[4][kStats];
+
+  __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));  // only Y_full loads are counted from here on
+  __builtin_amdgcn_sched_barrier(0);
+  issue_yf(0);
+  issue_yf(1);
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    float mu[4][4], fb[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int cl = wave_n * 128 + a * 32 + 8 * g + 4 * half;  // channel inside the tile
+      const float4 m4 = *reinterpret_cast<const float4 *>(s_mult + cl);
+      mu[g][0] = m4.x; mu[g][1] = m4.y; mu[g][2] = m4.z; mu[g][3] = m4.w;
+      const float4 f4 = *reinterpret_cast<const float4 *>(s_fb + cl);
+      fb[g][0] = f4.x; fb[g][1] = f4.y; fb[g][2] = f4.z; fb[g][3] = f4.w;
+    }
+    const float pq = s_pq[wave_n * 128 + a * 32 + c], pf = s_pf[wave_n * 128 + a * 32 + c];
+    double sum[kStats];
+#pragma unroll
+    for (int s = 0; s < kStats; ++s) sum[s] = 0.0;
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+      const int phase = 2 * a + hb;
+      // Y_quant of rows hb*64 .. +63, channels a*32 .. +31 (the arithmetic of the fp32 output mode)
+#pragma unroll
+      for (int bb = 0; bb < 2; ++bb) {
+        const int b = 2 * hb + bb;
+        const int row = bb * 32 + l32;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          float u[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float f = (float)acc[a][b][4 * g + r];
+            if (use_rs) f = f * rs[b];
+            float v = f * mu[g][r];
+            if (use_fb) v = v + fb[g][r];
+            u[r] = v;
+          }
+          *reinterpret_cast<float4 *>(yq_slab + row * 128 + (((2 * g + half) ^ (l32 & 7)) << 4)) =
+              make_float4(u[0], u[1], u[2], u[3]);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (phase + 2 < 8) {
+        issue_yf(phase + 2);
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(16, 0));
+      } else if (phase + 1 < 8) {
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(8, 0));
+      } else {
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+      }
+      asm volatile("" ::: "memory");  // the slab reads below stay below the wait
+      __builtin_amdgcn_sched_barrier(0);
+      const int8_t *yf_slab = wl + 8192 * (1 + phase % 3);
+      if (skip == 0)
+        stats_column_pass<false>(yq_slab, yf_slab, o4, h, pq, pf, hb * 64, skip, sum);
+      else
+        stats_column_pass<true>(yq_slab, yf_slab, o4, h, pq, pf, hb * 64, skip, sum);
+      __builtin_amdgcn_sched_barrier(0);  // the slabs are rewritten next: keep the reads above
+    }
+    // rows of both parities, then the lower wave row hands over to the upper one
+#pragma unroll
+    for (int s = 0; s < kStats; ++s) {
+      sum[s] += __shfl_xor(sum[s], 32, 64);
+      tot[a][s] = sum[s];
+      if (wave_m == 1 && lane < 32) s_exch[((wave_n * 4 + a) * kStats + s) * 32 + c] = sum[s];
+    }
+  }
+  __syncthreads();
+  if (wave_m == 0 && lane < 32) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int s = 0; s < kStats; ++s) {
+        const double t = tot[a][s] + s_exch[((wave_n * 4 + a) * kStats + s) * 32 + c];
+        p.partial[((int64_t)tile_m * kStats + s) * p.n + bn0 + wave_n * 128 + a * 32 + c] = t;
+      }
+  }
+}
+
 template <int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
 __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   using C = FastCfg<BK, NSTAGE, NCHUNK>;
@@ -209,6 +373,8 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   float *s_mult = reinterpret_cast<float *>(smem + C::RING + 1024);
   float *s_fb = reinterpret_cast<float *>(smem + C::RING + 2048);
   float *s_rs = reinterpret_cast<float *>(smem + C::RING + 3072);
+  float *s_pq = reinterpret_cast<float *>(smem + C::RING + 4096);  // statistics epilogue only
+  float *s_pf = reinterpret_cast<float *>(smem + C::RING + 5120);
 
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
@@ -229,6 +395,18 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32) {
     if (p.fbias) p_fb = p.fbias[bn0 + tid];
     if (p.sx_row) p_rs = p.sx_row[bm0 + tid];
+  }
+  // pivots of the shifted sums: the state's, or for the first batch of a state its row 0
+  float p_pq = 0.0f, p_pf = 0.0f;
+  if (OUT_KIND == kOutStats) {
+    const StatsView sv = stats_view(const_cast<void *>(p.stats), p.n);
+    if (*sv.n == 0) {
+      p_pq = p.yq_row0[bn0 + tid];
+      p_pf = p.y_full[bn0 + tid];
+    } else {
+      p_pq = sv.pivot_q[bn0 + tid];
+      p_pf = sv.pivot_f[bn0 + tid];
+    }
   }
 
   // ---- global -> LDS: wavefront `wave` owns rows [64*wave, 64*wave + 64) of both panels,
@@ -321,6 +499,10 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   s_mult[tid] = p_mult;
   s_fb[tid] = p_fb;
   s_rs[tid] = p_rs;
+  if (OUT_KIND == kOutStats) {
+    s_pq[tid] = p_pq;
+    s_pf[tid] = p_pf;
+  }
   if (stages >= NSTAGE)
     __builtin_amdgcn_s_waitcnt(s_waitcnt_imm((NSTAGE - 1) * C::LPS, 0));  // stage 0 has landed
   else
@@ -399,23 +581,31 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   for (; s + NSTAGE < stages; ++s) stage_body(s, s % NSTAGE, std::true_type{});
   for (; s < stages; ++s) stage_body(s, s % NSTAGE, std::false_type{});
 
-  // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
-  constexpr int ESZ = OUT_KIND == CWAC_OUT_INT8 ? 1 : 4;
-  const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
-  if (vs)
-    fast_epilogue<OUT_KIND, INT_ONLY, true>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
-  else
-    fast_epilogue<OUT_KIND, INT_ONLY, false>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+  if constexpr (OUT_KIND == kOutStats) {
+    __builtin_amdgcn_s_barrier();  // every wavefront is done with the ring, which the slabs overlay
+    stats_epilogue(p, acc, smem, s_mult, s_fb, s_rs, s_pq, s_pf,
+                   reinterpret_cast<double *>(smem + C::STATS_EXCH), bm0, bn0, tile_m, wave_m, wave_n,
+                   wave_s, lane);
+  } else {
+    // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
+    constexpr int ESZ = OUT_KIND == CWAC_OUT_INT8 ? 1 : 4;
+    const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
+    if (vs)
+      fast_epilogue<OUT_KIND, INT_ONLY, true>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+    else
+      fast_epilogue<OUT_KIND, INT_ONLY, false>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+  }
 }
 
 template <int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
 cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
   using C = FastCfg<BK, NSTAGE, NCHUNK>;
+  constexpr int LDS = OUT_KIND == kOutStats ? C::STATS_LDS_BYTES : C::LDS_BYTES;
   static const hipError_t attr = hipFuncSetAttribute(
       reinterpret_cast<const void *>(&qlinear_fast_kernel<BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY>),
-      hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+      hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, 256, C::LDS_BYTES, st>>>(p);
+  qlinear_fast_kernel<BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, 256, LDS, st>>>(p);
   return launch_status();
 }
 
@@ -444,6 +634,15 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   if (e && e[0] == '6') return launch_cfg<64, 4, 2>(p, out_kind, int_only, grid, st);
   if (e && e[0] == '1' && e[strlen(e) - 1] == '4') return launch_cfg<128, 2, 4>(p, out_kind, int_only, grid, st);
   return launch_cfg<128, 2, 2>(p, out_kind, int_only, grid, st);
+}
+
+cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {
+  p.tiles_m = (int)ceil_div(p.m, 256);
+  p.tiles_n = (int)ceil_div(p.n, 256);
+  p.vec_store = 0;
+  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
+  if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
+  return launch_one<128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
 }
 
 }  // namespace cwac

@@ -157,6 +157,34 @@ cwac_status launch_tile(FwdParams p, int out_kind, bool int_only, hipStream_t st
   return launch_status();
 }
 
+// Y_quant of token row 0 for every channel (the fp32 output mode's arithmetic on one row): the
+// pivot of a calibration state's first batch.  One wavefront per channel at a time, 16 bytes of
+// K per lane and step; does nothing when the state already holds rows.
+__global__ __launch_bounds__(256) void row0_kernel(const FwdParams p, float *__restrict__ yq_row0) {
+  const StatsView sv = stats_view(const_cast<void *>(p.stats), p.n);
+  if (*sv.n != 0) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int waves = gridDim.x * (blockDim.x / kWave);
+  for (int ch = wave; ch < p.n; ch += waves) {
+    const int8_t *w = p.w + (int64_t)ch * p.ldw;
+    int acc = 0;
+    for (int k0 = lane * 16; k0 < p.k; k0 += kWave * 16) {
+      const v4i xv = *reinterpret_cast<const v4i *>(p.x + k0);
+      const v4i wv = *reinterpret_cast<const v4i *>(w + k0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_sdot4(xv[i], wv[i], acc, false);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) {
+      float f = (float)(acc + (p.offset ? p.offset[ch] : 0));
+      if (p.sx_row) f = f * p.sx_row[0];
+      float v = f * p.mult[ch];
+      if (p.fbias) v = v + p.fbias[ch];
+      yq_row0[ch] = v;
+    }
+  }
+}
 
 }  // namespace
 }  // namespace cwac
@@ -178,7 +206,7 @@ extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, cons
   if (ldx < k || ldw < k || ldo < n) return CWAC_E_SHAPE;
   if (!aligned(x_q, 16) || !aligned(w_q, 16) || (ldx % 16) != 0 || (ldw % 16) != 0)
     return CWAC_E_ALIGN;
-  FwdParams p;
+  FwdParams p = {};
   p.x = x_q; p.w = w_q; p.ldx = ldx; p.ldw = ldw; p.ldo = ldo;
   p.m = m; p.n = n; p.k = k;
   p.mult = mult; p.offset = offset; p.fbias = fbias; p.sx_row = s_x_row; p.out = out;
@@ -219,4 +247,47 @@ extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, cons
   if (tile == 256) return launch_tile<256, 256, 128, 2, 2>(p, out_kind, int_only, st);
   if (tile == 128) return launch_tile<128, 128, 128, 2, 2>(p, out_kind, int_only, st);
   return launch_tile<64, 64, 128, 2, 2>(p, out_kind, int_only, st);
+}
+
+extern "C" size_t cwac_calibrate_fused_workspace(int64_t m, int32_t n) {
+  if (m < 1 || n < 1) return 16;
+  // partial sums [row tiles][kStats][n] fp64, then Y_quant of row 0 [n] fp32
+  return (size_t)ceil_div(m, kFastTile) * kStats * (size_t)n * sizeof(double) + (size_t)n * sizeof(float);
+}
+
+extern "C" cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t ldx,
+                                                    const int8_t *w_q, int64_t ldw, int64_t m,
+                                                    int32_t n, int32_t k, const float *mult,
+                                                    const int32_t *offset, const float *fbias,
+                                                    const float *s_x_row, const float *y_full,
+                                                    int64_t ld_full, void *stats, void *workspace,
+                                                    size_t workspace_bytes, void *stream) {
+  if (!x_q || !w_q || !mult || !y_full || !stats) return CWAC_E_NULL;
+  if (m < kFastTile || m > ((int64_t)1 << 40) || n < kFastTile || n > 65536 || (n % 4) != 0 ||
+      k < kFastKStep || k > 32768 || (k % kFastKStep) != 0)
+    return CWAC_E_SHAPE;
+  if (ldx < k || ldw < k || ld_full < n) return CWAC_E_SHAPE;
+  if (!aligned(x_q, 16) || !aligned(w_q, 16) || (ldx % 16) != 0 || (ldw % 16) != 0 ||
+      !aligned(y_full, 16) || (ld_full % 4) != 0 || !aligned(stats, 16))
+    return CWAC_E_ALIGN;
+  // per-lane byte offsets into a tile of Y_full are kept in 32 bits
+  if (ld_full > ((int64_t)1 << 26)) return CWAC_E_SHAPE;
+  if (!workspace || workspace_bytes < cwac_calibrate_fused_workspace(m, n)) return CWAC_E_WORKSPACE;
+  if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
+  FwdParams p = {};
+  p.x = x_q; p.w = w_q; p.ldx = ldx; p.ldw = ldw;
+  p.m = m; p.n = n; p.k = k;
+  p.mult = mult; p.offset = offset; p.fbias = fbias; p.sx_row = s_x_row;
+  p.y_full = y_full; p.ld_full = ld_full; p.stats = stats;
+  p.partial = static_cast<double *>(workspace);
+  const int row_tiles = (int)ceil_div(m, kFastTile);
+  float *yq_row0 = reinterpret_cast<float *>(p.partial + (size_t)row_tiles * kStats * n);
+  p.yq_row0 = yq_row0;
+  hipStream_t st = as_stream(stream);
+  row0_kernel<<<(unsigned)ceil_div(n, 16), 256, 0, st>>>(p, yq_row0);
+  cwac_status rc = launch_status();
+  if (rc != CWAC_OK) return rc;
+  rc = launch_fast_stats(p, st);
+  if (rc != CWAC_OK) return rc;
+  return launch_stats_merge(p.partial, row_tiles, n, y_full, yq_row0, stats, m, st);
 }
