@@ -240,6 +240,45 @@ def fused_calibration(P, torch, layers, reps: int = 5):
             "speedup": round(t_two / t_fused, 3)}
 
 
+def mfma_ceiling(P, torch, layers, iters: int = 20000, reps: int = 4):
+    """Context for roofline.frac: the rate the int8 matrix cores sustain on THIS device with
+    register-resident operands and no memory traffic (the forward kernel's 4 x 4 MFMA pattern),
+    for constant operands, uniformly random bytes, and operand words sampled from the workload's
+    own quantized weights and activations.  POP/s."""
+    dev = layers[0].xq.device
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    g = torch.Generator(device="cpu").manual_seed(1234)
+
+    def sample(t):
+        words = t.contiguous().view(-1).view(torch.int32).view(-1, 4)      # 16-byte operand chunks
+        idx = torch.randint(0, words.shape[0], (512,), generator=g).to(dev)
+        return words[idx]
+
+    L = layers[0]
+    variants = {
+        "constant_operands": torch.full((1024, 4), 0x01010101, dtype=torch.int32, device=dev),
+        "uniform_random_bytes": torch.randint(-2**31, 2**31 - 1, (1024, 4), generator=g,
+                                              dtype=torch.int64).to(torch.int32).to(dev),
+        "workload_operands": torch.cat([sample(L.wq), sample(L.xq)]).contiguous(),
+    }
+    out = {}
+    for name, ops_buf in variants.items():
+        P.cwac_mfma_probe(ops_buf, iters // 4, cus, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ops = 0.0
+        for _ in range(reps):
+            ops += P.cwac_mfma_probe(ops_buf, iters, cus, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(ops / (e0.elapsed_time(e1) * 1e-3) / 1e15, 3)
+    out["unit"] = "POP/s"
+    out["workgroups"] = cus
+    return out
+
+
 def cpu_baseline(synth, cfg: int, sample_rows: int):
     """The oracle, as it stands, timed on this host on a bounded row sample of the same step."""
     import numpy as np
@@ -382,6 +421,7 @@ def main():
     }
     result["epilogue_comparators"] = comparators(P, torch, layers)
     result["fused_calibration"] = fused_calibration(P, torch, layers)
+    result["mfma_ceiling_probe"] = mfma_ceiling(P, torch, layers)
     if not args.no_cpu_baseline:
         v, cores, secs = cpu_baseline(synth, args.config, args.cpu_sample_rows)
         result["cpu_baseline"] = {

@@ -253,6 +253,23 @@ cwac_status cwac_apply_unfolded(const float *y, int64_t ldy, int64_t rows, int32
                                 const float *alpha, const float *beta, float *out, int64_t ldo,
                                 void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* Diagnostic (measurement aid, not a step of the method)                     */
+/* ------------------------------------------------------------------------- */
+
+/* Runs the forward kernel's matrix-core pattern (per wavefront 4 x 4 int8 MFMA
+ * 32x32x32 tiles, 256 accumulators per lane) with register-resident operands
+ * and no memory traffic, `iters` times: 2 * 32768 * 16 * iters * 4 * workgroups
+ * int8 operations.  Timed by the caller, it gives the rate the matrix cores
+ * sustain on this device for operands of the given CONTENT (the clock a device
+ * holds under its power limit depends on the operands' switching activity).
+ *   operands  device, 16 KiB (1024 x 16 bytes): the first 8 KiB feed the weight
+ *             fragments, the second 8 KiB the activation fragments
+ *   1 <= iters <= 2^24, 1 <= workgroups <= 2^20 (256 threads each)
+ *   sink      device int32[1]; written only if a checksum takes one particular value */
+cwac_status cwac_mfma_probe(const int32_t *operands, int32_t iters, int32_t workgroups,
+                            int32_t *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,6 +24,7 @@ EXPORTS = (
     "cwac_stats_reset", "cwac_calibrate_stats_workspace", "cwac_calibrate_stats", "cwac_solve",
     "cwac_fold", "qlinear_cwac_forward", "cwac_calibrate_fused_workspace",
     "qlinear_cwac_calibrate_fused", "cwac_epilogue_int32", "cwac_apply_unfolded",
+    "cwac_mfma_probe",
 )
 
 
@@ -71,6 +72,7 @@ def lib() -> C.CDLL:
                                                    vp, i64, vp, vp, sz, vp]),
             "cwac_epilogue_int32": (i32, [vp, i64, i64, i32, qpp, vp, vp, vp, vp, i32, vp, i64, vp]),
             "cwac_apply_unfolded": (i32, [vp, i64, i64, i32, vp, vp, vp, i64, vp]),
+            "cwac_mfma_probe": (i32, [vp, i32, i32, vp, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
@@ -240,3 +242,13 @@ def cwac_apply_unfolded(y: torch.Tensor, alpha, beta, out: torch.Tensor, stream=
     _check(lib().cwac_apply_unfolded(_ptr(y), _rowmajor(y), y.shape[0], y.shape[1], _ptr(alpha),
                                      _ptr(beta), _ptr(out), _rowmajor(out), _stream(stream)),
            "cwac_apply_unfolded")
+
+
+# --------------------------------------------------------------------------- diagnostic
+def cwac_mfma_probe(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor,
+                    stream=None) -> float:
+    """Enqueues the register-resident MFMA loop; returns the int8 operations it performs."""
+    assert operands.numel() * operands.element_size() >= 16384 and sink.dtype == torch.int32
+    _check(lib().cwac_mfma_probe(_ptr(operands), iters, workgroups, _ptr(sink), _stream(stream)),
+           "cwac_mfma_probe")
+    return 2.0 * 32768 * 16 * iters * 4 * workgroups

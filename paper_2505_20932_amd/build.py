@@ -12,7 +12,8 @@ CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libcwac_hip.so")
 
-SOURCES = ["status.hip", "quantize.hip", "calib_stats.hip", "fold_epilogue.hip", "qlinear_forward.hip", "qlinear_fast.hip"]
+SOURCES = ["status.hip", "quantize.hip", "calib_stats.hip", "fold_epilogue.hip", "qlinear_forward.hip", "qlinear_fast.hip",
+           "probe.hip"]
 
 # -ffp-contract=off: the epilogue and the fold are defined as sequences of single
 # roundings; packed fp32 instructions are disabled for the device pass.
