@@ -442,3 +442,88 @@ void orc_folded_forward(const int32_t *acc, int64_t rows, int64_t n,
       }
     }
 }
+
+/* ------------------------------------------------------------------ */
+/* Integer-only form of the engine multiplier (Sec. 3.4: after the     */
+/* fold the layer needs "no floating-point computation"; the paper      */
+/* gives no scheme, this is the usual fixed-point one)                  */
+/* ------------------------------------------------------------------ */
+
+/* The real multiplier M' of Eq. 11 (fp64) is replaced by M0 * 2^-shift with
+ * M0 a signed 32-bit integer, 2^30 <= |M0| < 2^31, i.e. M' to 31 significant
+ * bits:  |M'| = mant * 2^e with mant in [0.5, 1);  M0 = sign * rne(mant * 2^31)
+ * (a mantissa that rounds up to 2^31 becomes 2^30 with e + 1);  shift = 31 - e.
+ * Representable range 1 <= shift <= 62: a larger multiplier (|M'| >= 2^30)
+ * is clamped to +-(2^31 - 1) * 2^-1 and counted, a smaller one (and M' = 0)
+ * becomes M0 = 0, shift = 1. */
+static void fixed_point_of(double mreal, int32_t *m0, int32_t *shift, int32_t *n_sat) {
+  *m0 = 0;
+  *shift = 1;
+  if (!(mreal == mreal) || mreal == 0.0) return;
+  int e = 0;
+  const double mant = frexp(fabs(mreal), &e);
+  long long q = llrint(mant * 2147483648.0);
+  if (q == 2147483648LL) {
+    q = 1073741824LL;
+    e += 1;
+  }
+  int sh = 31 - e;
+  if (sh > 62) return;
+  if (sh < 1) {
+    q = 2147483647LL;
+    sh = 1;
+    if (n_sat) ++*n_sat;
+  }
+  *m0 = (int32_t)(mreal < 0.0 ? -q : q);
+  *shift = sh;
+}
+
+/* Eq. 10-11 with the multiplier in fixed point; offset exactly as in
+ * orc_fold_int_offset.  n_saturated counts clamped offsets and clamped
+ * multipliers. */
+void orc_fold_fixed_point(const float *alpha, const float *beta, const float *sw,
+                          const float *bias, const int32_t *colsum, int64_t n,
+                          float sx, int32_t zx, float sr, int32_t *m0,
+                          int32_t *shift, int32_t *offset, int32_t *n_saturated) {
+  int32_t nsat = 0;
+  const double lim = 1073741824.0;
+  for (int64_t c = 0; c < n; ++c) {
+    const double a = alpha ? (double)alpha[c] : 1.0;
+    const double b = beta ? (double)beta[c] : 0.0;
+    const double asx = a * (double)sx;
+    const double den = asx * (double)sw[c];
+    fixed_point_of(den / (double)sr, &m0[c], &shift[c], &nsat);
+    const double unit = (double)sx * (double)sw[c];
+    double bq = 0.0;
+    if (b != 0.0) bq = rint(b / den);
+    double biasq = 0.0;
+    if (bias) biasq = rint((double)bias[c] / unit);
+    const double sum = sat_round(bq + biasq, lim, &nsat);
+    offset[c] = (int32_t)sum - zx * colsum[c];
+  }
+  if (n_saturated) *n_saturated = nsat;
+}
+
+/* Integer-only epilogue of Eq. 10:
+ *   t = acc + offset[n]                               int32
+ *   v = floor((t * M0[n] + 2^(shift[n]-1)) / 2^shift[n])   exact in 64 bits:
+ *       the nearest integer to t * M0 * 2^-shift, ties towards +infinity
+ *   out = clamp(v + Z_r, qmin, qmax) */
+void orc_fixed_point_forward(const int32_t *acc, int64_t rows, int64_t n,
+                             const int32_t *offset, const int32_t *m0,
+                             const int32_t *shift, int32_t zr, int32_t qmin,
+                             int32_t qmax, int8_t *out) {
+  for (int64_t i = 0; i < rows; ++i)
+    for (int64_t c = 0; c < n; ++c) {
+      const int64_t t = (int64_t)acc[i * n + c] + (offset ? offset[c] : 0);
+      const int sh = shift[c];
+      const int64_t prod = t * (int64_t)m0[c] + ((int64_t)1 << (sh - 1));
+      /* floor division by 2^sh without relying on the shift of a negative value */
+      int64_t v = prod / ((int64_t)1 << sh);
+      if (prod % ((int64_t)1 << sh) != 0 && prod < 0) v -= 1;
+      v += zr;
+      if (v < qmin) v = qmin;
+      if (v > qmax) v = qmax;
+      out[i * n + c] = (int8_t)v;
+    }
+}

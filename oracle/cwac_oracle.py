@@ -272,6 +272,35 @@ def fold_fp_bias(alpha, beta, sw, bias, colsum, per_token, sx, zx, sr):
 
 
 # ---------------------------------------------------------------- folded forward
+def fold_fixed_point(alpha, beta, sw, bias, colsum, sx, zx, sr):
+    """Eq. 10-11 with the multiplier as M0 * 2^-shift -> (m0 int32 [N], shift int32 [N],
+    offset int32 [N], n_saturated)."""
+    sw, colsum = _f32(sw), _i32(colsum)
+    alpha, beta, bias = _f32(alpha), _f32(beta), _f32(bias)
+    n = sw.shape[0]
+    m0 = np.empty(n, dtype=np.int32)
+    shift = np.empty(n, dtype=np.int32)
+    offset = np.empty(n, dtype=np.int32)
+    nsat = C.c_int32()
+    lib().orc_fold_fixed_point(_p(alpha, C.c_float), _p(beta, C.c_float), _p(sw, C.c_float),
+                               _p(bias, C.c_float), _p(colsum, C.c_int32), C.c_int64(n),
+                               C.c_float(sx), C.c_int32(zx), C.c_float(sr), _p(m0, C.c_int32),
+                               _p(shift, C.c_int32), _p(offset, C.c_int32), C.byref(nsat))
+    return m0, shift, offset, int(nsat.value)
+
+
+def fixed_point_forward(acc, offset, m0, shift, zr, qmin=-128, qmax=127):
+    """Integer-only epilogue of Eq. 10 on integer accumulators -> int8 [rows, N]."""
+    acc, offset, m0, shift = _i32(acc), _i32(offset), _i32(m0), _i32(shift)
+    rows, n = acc.shape
+    out = np.empty((rows, n), dtype=np.int8)
+    lib().orc_fixed_point_forward(_p(acc, C.c_int32), C.c_int64(rows), C.c_int64(n),
+                                  _p(offset, C.c_int32), _p(m0, C.c_int32), _p(shift, C.c_int32),
+                                  C.c_int32(zr), C.c_int32(qmin), C.c_int32(qmax),
+                                  _p(out, C.c_int8))
+    return out
+
+
 def folded_forward(acc, offset, mult, zr, fbias=None, sx_row=None, qmin=-128, qmax=127,
                    want_f32=False):
     """Eq. 10 epilogue on integer accumulators -> int8 [rows, N]
