@@ -234,6 +234,39 @@ cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t ldx, const i
                                          void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Integer-only engine form (Sec. 3.4: after the fold the layer runs with "no  */
+/* floating-point computation"; the paper names no scheme - this is the usual  */
+/* fixed-point one)                                                            */
+/* ------------------------------------------------------------------------- */
+
+/* cwac_fold in CWAC_EPI_INT_OFFSET form with the multiplier M' of Eq. 11 as
+ * m0[n] * 2^-shift[n]: m0 a signed 32-bit integer with 2^30 <= |m0| < 2^31
+ * (M' rounded to 31 significant bits; the sign is alpha's), 1 <= shift <= 62.
+ * |M'| >= 2^30 is clamped to (2^31 - 1) * 2^-1 and counted in n_saturated with
+ * the clamped offsets; |M'| < 2^-32 gives m0 = 0, shift = 1.  offset[n] is
+ * cwac_fold's.  qp: host, mode CWAC_EPI_INT_OFFSET, act_per_token 0.
+ *   m0, shift, offset   device int32 [n_out];  other arguments as in cwac_fold */
+cwac_status cwac_fold_fixed_point(const float *alpha, const float *beta, const float *s_w,
+                                  const float *bias, const int32_t *colsum, int32_t n_out,
+                                  const cwac_qparams *qp, int32_t *m0, int32_t *shift,
+                                  int32_t *offset, int32_t *n_saturated, void *stream);
+
+/* qlinear_cwac_forward with an epilogue that uses no floating point.  Per element:
+ *   t = acc[m,n] + offset[n]                                    int32
+ *   v = floor((t * m0[n] + 2^(shift[n]-1)) / 2^shift[n])        exact, 64-bit: the nearest
+ *                                       integer to t * m0 * 2^-shift, ties towards +infinity
+ *   out = (int8)(clamp(v, qmin - Z_r, qmax - Z_r) + Z_r)
+ * It differs from the fp32 epilogue by at most one code, and only where the real
+ * value lies within that epilogue's own rounding error of a tie.
+ *   m0, shift  device int32 [n] as produced by cwac_fold_fixed_point (1 <= shift <= 62)
+ *   out        device int8 [m, n], ldo;  other arguments and limits as in qlinear_cwac_forward */
+cwac_status qlinear_cwac_forward_fixed_point(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                             int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                             const cwac_qparams *qp, const int32_t *m0,
+                                             const int32_t *shift, const int32_t *offset,
+                                             int8_t *out, int64_t ldo, void *stream);
+
+/* ------------------------------------------------------------------------- */
 /* Un-fused comparators (what the fold removes; Sec. 3.3 last sentence,       */
 /* Sec. 3.4 first paragraph)                                                  */
 /* ------------------------------------------------------------------------- */

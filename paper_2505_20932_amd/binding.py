@@ -24,7 +24,7 @@ EXPORTS = (
     "cwac_stats_reset", "cwac_calibrate_stats_workspace", "cwac_calibrate_stats", "cwac_solve",
     "cwac_fold", "qlinear_cwac_forward", "cwac_calibrate_fused_workspace",
     "qlinear_cwac_calibrate_fused", "cwac_epilogue_int32", "cwac_apply_unfolded",
-    "cwac_mfma_probe",
+    "cwac_mfma_probe", "cwac_fold_fixed_point", "qlinear_cwac_forward_fixed_point",
 )
 
 
@@ -73,6 +73,9 @@ def lib() -> C.CDLL:
             "cwac_epilogue_int32": (i32, [vp, i64, i64, i32, qpp, vp, vp, vp, vp, i32, vp, i64, vp]),
             "cwac_apply_unfolded": (i32, [vp, i64, i64, i32, vp, vp, vp, i64, vp]),
             "cwac_mfma_probe": (i32, [vp, i32, i32, vp, vp]),
+            "cwac_fold_fixed_point": (i32, [vp, vp, vp, vp, vp, i32, qpp, vp, vp, vp, vp, vp]),
+            "qlinear_cwac_forward_fixed_point": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp,
+                                                       vp, vp, i64, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
@@ -242,6 +245,30 @@ def cwac_apply_unfolded(y: torch.Tensor, alpha, beta, out: torch.Tensor, stream=
     _check(lib().cwac_apply_unfolded(_ptr(y), _rowmajor(y), y.shape[0], y.shape[1], _ptr(alpha),
                                      _ptr(beta), _ptr(out), _rowmajor(out), _stream(stream)),
            "cwac_apply_unfolded")
+
+
+# --------------------------------------------------------------------------- integer-only form
+def cwac_fold_fixed_point(alpha, beta, s_w, bias, colsum, qp: cwac_qparams, m0, shift, offset,
+                          n_saturated=None, stream=None):
+    assert m0.dtype == torch.int32 and shift.dtype == torch.int32 and offset.dtype == torch.int32
+    _check(lib().cwac_fold_fixed_point(_ptr(alpha), _ptr(beta), _ptr(s_w), _ptr(bias),
+                                       _ptr(colsum), s_w.numel(), C.byref(qp), _ptr(m0),
+                                       _ptr(shift), _ptr(offset), _ptr(n_saturated),
+                                       _stream(stream)), "cwac_fold_fixed_point")
+
+
+def qlinear_cwac_forward_fixed_point(x_q: torch.Tensor, w_q: torch.Tensor, qp: cwac_qparams, m0,
+                                     shift, offset, out: torch.Tensor, stream=None):
+    assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8 and out.dtype == torch.int8
+    assert m0.dtype == torch.int32 and shift.dtype == torch.int32
+    m, k = x_q.shape
+    n, k2 = w_q.shape
+    assert k == k2 and out.shape == (m, n)
+    _check(lib().qlinear_cwac_forward_fixed_point(_ptr(x_q), _rowmajor(x_q), _ptr(w_q),
+                                                  _rowmajor(w_q), m, n, k, C.byref(qp), _ptr(m0),
+                                                  _ptr(shift), _ptr(offset), _ptr(out),
+                                                  _rowmajor(out), _stream(stream)),
+           "qlinear_cwac_forward_fixed_point")
 
 
 # --------------------------------------------------------------------------- diagnostic

@@ -74,6 +74,72 @@ __global__ __launch_bounds__(256) void fold_kernel(
   }
 }
 
+// Fixed-point form of a real multiplier: M0 * 2^-shift with 2^30 <= |M0| < 2^31 (31 significant
+// bits), 1 <= shift <= 62; larger multipliers are clamped (counted), smaller ones become 0.
+__device__ inline void fixed_point_of(double mreal, int32_t &m0, int32_t &shift, int &nsat) {
+  m0 = 0;
+  shift = 1;
+  if (!(mreal == mreal) || mreal == 0.0) return;
+  int e = 0;
+  const double mant = frexp(fabs(mreal), &e);
+  long long q = llrint(mant * 2147483648.0);
+  if (q == 2147483648LL) {
+    q = 1073741824LL;
+    e += 1;
+  }
+  int sh = 31 - e;
+  if (sh > 62) return;
+  if (sh < 1) {
+    q = 2147483647LL;
+    sh = 1;
+    ++nsat;
+  }
+  m0 = (int32_t)(mreal < 0.0 ? -q : q);
+  shift = sh;
+}
+
+// Eq. 10-11 with the multiplier in fixed point (integer-only engine form); the offset is the
+// integer-offset fold's.
+__global__ __launch_bounds__(256) void fold_fixed_kernel(
+    const float *__restrict__ alpha, const float *__restrict__ beta,
+    const float *__restrict__ sw, const float *__restrict__ bias,
+    const int32_t *__restrict__ colsum, int n_out, float sx, int zx, float sr,
+    int32_t *__restrict__ m0, int32_t *__restrict__ shift, int32_t *__restrict__ offset,
+    int32_t *__restrict__ n_saturated) {
+  int nsat = 0;
+  const double lim = 1073741824.0;  // 2^30
+  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < n_out; c += gridDim.x * blockDim.x) {
+    const double a = alpha ? (double)alpha[c] : 1.0;
+    const double b = beta ? (double)beta[c] : 0.0;
+    const double w = (double)sw[c];
+    const double asx = a * (double)sx;
+    const double den = asx * w;
+    int32_t q, sh;
+    fixed_point_of(den / (double)sr, q, sh, nsat);
+    m0[c] = q;
+    shift[c] = sh;
+    const double unit = (double)sx * w;
+    double bq = 0.0;
+    if (b != 0.0) bq = rint(b / den);
+    double biasq = 0.0;
+    if (bias) biasq = rint((double)bias[c] / unit);
+    const double sum = sat_round(bq + biasq, lim, nsat);
+    offset[c] = (int32_t)sum - zx * colsum[c];
+  }
+  if (n_saturated) {
+    __shared__ int s_cnt[256 / kWave];
+    nsat = wave_sum(nsat);
+    if ((threadIdx.x & (kWave - 1)) == 0) s_cnt[threadIdx.x / kWave] = nsat;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int i = 0; i < (int)(blockDim.x / kWave); ++i) t += s_cnt[i];
+      if (gridDim.x == 1) *n_saturated = t;
+      else if (t) atomicAdd(n_saturated, t);
+    }
+  }
+}
+
 // Epilogue of Eq. 10 as its own pass: int32 accumulators in, codes (or fp32) out.
 template <int OUT_KIND>
 __global__ __launch_bounds__(kThreads) void epilogue_pass_kernel(
@@ -203,6 +269,25 @@ extern "C" cwac_status cwac_fold(const float *alpha, const float *beta, const fl
   fold_kernel<<<blocks, 256, 0, as_stream(stream)>>>(alpha, beta, s_w, bias, colsum, n_out, qp->mode,
                                                  qp->act_per_token, qp->s_x, qp->z_x, qp->s_r,
                                                  mult, offset, fbias, n_saturated);
+  return launch_status();
+}
+
+extern "C" cwac_status cwac_fold_fixed_point(const float *alpha, const float *beta, const float *s_w,
+                                             const float *bias, const int32_t *colsum,
+                                             int32_t n_out, const cwac_qparams *qp, int32_t *m0,
+                                             int32_t *shift, int32_t *offset,
+                                             int32_t *n_saturated, void *stream) {
+  if (!s_w || !colsum || !m0 || !shift || !offset) return CWAC_E_NULL;
+  cwac_status st = check_qparams(qp);
+  if (st != CWAC_OK) return st;
+  if ((alpha == nullptr) != (beta == nullptr)) return CWAC_E_MODE;
+  if (qp->mode != CWAC_EPI_INT_OFFSET || qp->act_per_token) return CWAC_E_MODE;
+  if (n_out < 1 || n_out > 65536) return CWAC_E_SHAPE;
+  const unsigned blocks = (unsigned)ceil_div(n_out, 256);
+  if (n_saturated && blocks > 1) zero_count_kernel<<<1, 64, 0, as_stream(stream)>>>(n_saturated);
+  fold_fixed_kernel<<<blocks, 256, 0, as_stream(stream)>>>(alpha, beta, s_w, bias, colsum, n_out,
+                                                           qp->s_x, qp->z_x, qp->s_r, m0, shift,
+                                                           offset, n_saturated);
   return launch_status();
 }
 

@@ -31,11 +31,30 @@ struct FwdParams {
   const void *stats;
   double *partial;
   const float *yq_row0;  // Y_quant of row 0 [n]: the pivot of a state's first batch
+  // integer-only epilogue (kOutFixed): multiplier m0[n] * 2^-shift[n], clamp [qlo, qhi] then + zr
+  const int32_t *m0;
+  const int32_t *shift;
+  int qlo, qhi;
 };
 
 // Internal output kind of the large-problem kernel: nothing is stored but the per-channel sums
 // of the tile's rows of (Y_full, Y_quant).
 constexpr int kOutStats = 3;
+// Internal output kind: int8 codes through the integer-only epilogue (no floating point).
+constexpr int kOutFixed = 4;
+
+// Integer-only requantization (fixed-point form of Eq. 10): the nearest integer to
+// t * m0 * 2^-shift, ties towards +infinity, exact in 64 bits (|t|, |m0| < 2^31, 1 <= shift <= 62),
+// saturated to int32, clamped to [qlo, qhi] = [qmin - Z_r, qmax - Z_r], plus Z_r.
+__device__ __forceinline__ int fixed_point_code(int t, int m0, int shift, int qlo, int qhi, int zr) {
+  const int64_t prod = (int64_t)t * (int64_t)m0 + ((int64_t)1 << (shift - 1));
+  const int64_t v = prod >> shift;  // arithmetic shift: floor
+  const int lo32 = (int)v, hi32 = (int)(v >> 32);
+  int r = (hi32 == (lo32 >> 31)) ? lo32 : (hi32 < 0 ? (int)0x80000000 : 0x7fffffff);
+  r = r < qlo ? qlo : r;
+  r = r > qhi ? qhi : r;
+  return r + zr;
+}
 
 // Workgroup id -> output tile.  Consecutive workgroup ids are dealt round-robin
 // to the 8 XCDs (each with its own L2), so ids are first regrouped so that every
@@ -78,6 +97,23 @@ struct Epilogue {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
           if (nn + r < p.n) o[r] = t[r];
+      }
+      return;
+    }
+    if (OUT_KIND == kOutFixed) {
+      int c[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        c[r] = fixed_point_code(acc[r] + off[r], __float_as_int(mu[r]), __float_as_int(fb[r]), p.qlo,
+                                p.qhi, p.zr);
+      int8_t *o = static_cast<int8_t *>(p.out) + mm * p.ldo + nn;
+      if (p.vec_store && nn + 3 < p.n) {
+        *reinterpret_cast<uint32_t *>(o) = (uint32_t)(c[0] & 0xff) | ((uint32_t)(c[1] & 0xff) << 8) |
+                                           ((uint32_t)(c[2] & 0xff) << 16) | ((uint32_t)c[3] << 24);
+      } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < p.n) o[r] = (int8_t)c[r];
       }
       return;
     }
@@ -140,14 +176,20 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
         int idx = nb + 8 * g + r;
         if (idx > p.n - 1) idx = p.n - 1;  // clamped read; such channels are never stored
         off[g][r] = p.offset ? p.offset[idx] : 0;
-        mu[g][r] = (OUT_KIND != CWAC_OUT_INT32) ? p.mult[idx] : 0.0f;
-        fb[g][r] = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.fbias) ? p.fbias[idx] : 0.0f;
+        if (OUT_KIND == kOutFixed) {  // the two float slots carry the integer multiplier and shift
+          mu[g][r] = __int_as_float(p.m0[idx]);
+          fb[g][r] = __int_as_float(p.shift[idx]);
+        } else {
+          mu[g][r] = (OUT_KIND != CWAC_OUT_INT32) ? p.mult[idx] : 0.0f;
+          fb[g][r] = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.fbias) ? p.fbias[idx] : 0.0f;
+        }
       }
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
       const int64_t mm = m0 + b * 32 + l32;
       if (mm < p.m) {
-        const float rs = (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && p.sx_row) ? p.sx_row[mm] : 1.0f;
+        const float rs =
+            (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && OUT_KIND != kOutFixed && p.sx_row) ? p.sx_row[mm] : 1.0f;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int nn = nb + 8 * g;

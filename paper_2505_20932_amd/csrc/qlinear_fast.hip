@@ -97,7 +97,7 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
     // streamed out: written normally they linger as dirty lines whose write-back then competes
     // with the reads of the statistics pass that follows
     // (int8 results stay cacheable for the layer that consumes them)
-    if (OUT_KIND != CWAC_OUT_INT8)
+    if (OUT_KIND != CWAC_OUT_INT8 && OUT_KIND != kOutFixed)
       __builtin_nontemporal_store(v, dst);
     else
       *dst = v;
@@ -109,7 +109,8 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
                                               const float *s_mult, const float *s_fb,
                                               const float *s_rs, int64_t bm0, int bn0, int wave_m,
                                               int wave_n, int lane) {
-  constexpr int ESZ = OUT_KIND == CWAC_OUT_INT8 ? 1 : 4;
+  constexpr bool I8 = OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed;  // packed int8 codes
+  constexpr int ESZ = I8 ? 1 : 4;
   const int l32 = lane & 31, half = lane >> 5;
   const int wave = wave_m + 2 * wave_n;
   int8_t *slab = smem + wave * kSlabBytes;
@@ -131,7 +132,7 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
       if (OUT_KIND != CWAC_OUT_INT32) {
         const float4 m4 = *reinterpret_cast<const float4 *>(s_mult + cl);
         mu[g][0] = m4.x; mu[g][1] = m4.y; mu[g][2] = m4.z; mu[g][3] = m4.w;
-        if (!INT_ONLY) {
+        if (!INT_ONLY || OUT_KIND == kOutFixed) {  // fixed point: the shift travels in this slot
           const float4 f4 = *reinterpret_cast<const float4 *>(s_fb + cl);
           fb[g][0] = f4.x; fb[g][1] = f4.y; fb[g][2] = f4.z; fb[g][3] = f4.w;
         }
@@ -153,6 +154,21 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
             int32_t *o = reinterpret_cast<int32_t *>(wbase + row * row_bytes) + col;
 #pragma unroll
             for (int r = 0; r < 4; ++r) o[r] = t[r];
+          }
+          continue;
+        }
+        if (OUT_KIND == kOutFixed) {
+          int c[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            c[r] = fixed_point_code(acc[a][b][4 * g + r], __float_as_int(mu[g][r]),
+                                    __float_as_int(fb[g][r]), p.qlo, p.qhi, p.zr);
+          if (VEC) {
+            packed[g] = pack4(c[0], c[1], c[2], c[3]);
+          } else {
+            int8_t *o = reinterpret_cast<int8_t *>(wbase + row * row_bytes) + col;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (int8_t)c[r];
           }
           continue;
         }
@@ -192,7 +208,7 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
           }
         }
       }
-      if (OUT_KIND == CWAC_OUT_INT8 && VEC) {
+      if (I8 && VEC) {
         // lower half-wave holds channels 8g..8g+3, upper 8g+4..8g+7: after swapping
         // (upper's g0, lower's g2) and (upper's g1, lower's g3) the lower lane owns
         // channels 0..15 of this MFMA column and the upper lane 16..31
@@ -202,9 +218,9 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
         *reinterpret_cast<v4i *>(slab + row * kSlabStride + a * 32 + half * 16) = q;
       }
     }
-    if (VEC && OUT_KIND != CWAC_OUT_INT8) store_slab<OUT_KIND>(slab, wbase + a * 32 * ESZ, row_bytes, lane);
+    if (VEC && !I8) store_slab<OUT_KIND>(slab, wbase + a * 32 * ESZ, row_bytes, lane);
   }
-  if (VEC && OUT_KIND == CWAC_OUT_INT8) store_slab<OUT_KIND>(slab, wbase, row_bytes, lane);
+  if (VEC && I8) store_slab<OUT_KIND>(slab, wbase, row_bytes, lane);
 }
 
 // Statistics epilogue (Sec. 3.3, Eq. 4-5 fused into the calibration forward): instead of storing
@@ -390,9 +406,14 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
 
   // ---- epilogue parameters of this tile: issue their loads first (oldest in the load queue)
   const int p_off = p.offset ? p.offset[bn0 + tid] : 0;
-  const float p_mult = (OUT_KIND != CWAC_OUT_INT32) ? p.mult[bn0 + tid] : 0.0f;
-  float p_fb = 0.0f, p_rs = 1.0f;
-  if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32) {
+  float p_mult = 0.0f, p_fb = 0.0f, p_rs = 1.0f;
+  if (OUT_KIND == kOutFixed) {  // integer multiplier and shift travel in the two float slots
+    p_mult = __int_as_float(p.m0[bn0 + tid]);
+    p_fb = __int_as_float(p.shift[bn0 + tid]);
+  } else if (OUT_KIND != CWAC_OUT_INT32) {
+    p_mult = p.mult[bn0 + tid];
+  }
+  if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && OUT_KIND != kOutFixed) {
     if (p.fbias) p_fb = p.fbias[bn0 + tid];
     if (p.sx_row) p_rs = p.sx_row[bm0 + tid];
   }
@@ -588,7 +609,7 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
                    wave_s, lane);
   } else {
     // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
-    constexpr int ESZ = OUT_KIND == CWAC_OUT_INT8 ? 1 : 4;
+    constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed) ? 1 : 4;
     const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
     if (vs)
       fast_epilogue<OUT_KIND, INT_ONLY, true>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
@@ -611,6 +632,7 @@ cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
 
 template <int BK, int NSTAGE, int NCHUNK>
 cwac_status launch_cfg(const FwdParams &p, int out_kind, bool int_only, dim3 grid, hipStream_t st) {
+  if (out_kind == kOutFixed) return launch_one<BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
   if (out_kind == CWAC_OUT_INT8)
     return int_only ? launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true>(p, grid, st)
                     : launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false>(p, grid, st);
@@ -623,7 +645,7 @@ cwac_status launch_cfg(const FwdParams &p, int out_kind, bool int_only, dim3 gri
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   p.tiles_m = (int)ceil_div(p.m, 256);
   p.tiles_n = (int)ceil_div(p.n, 256);
-  const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
+  const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;

@@ -144,7 +144,9 @@ cwac_status launch_tile(FwdParams p, int out_kind, bool int_only, hipStream_t st
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
   const dim3 grid((unsigned)blocks), block(64 * WGM * WGN);
-  if (out_kind == CWAC_OUT_INT8) {
+  if (out_kind == kOutFixed) {
+    qlinear_kernel<BM, BN, BK, WGM, WGN, kOutFixed, true><<<grid, block, 0, st>>>(p);
+  } else if (out_kind == CWAC_OUT_INT8) {
     if (int_only)
       qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT8, true><<<grid, block, 0, st>>>(p);
     else
@@ -191,6 +193,34 @@ __global__ __launch_bounds__(256) void row0_kernel(const FwdParams p, float *__r
 
 using namespace cwac;
 
+// Kernel and tile choice shared by the forward entry points.
+static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_only, hipStream_t st) {
+  const int64_t m = p.m;
+  const int n = p.n, k = p.k;
+  // Tile choice: the largest tile that still gives the 256 compute units at least
+  // two workgroups each; small problems fall back to small tiles.
+  const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
+  const int64_t t128 = ceil_div(m, 128) * ceil_div(n, 128);
+  int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
+  const bool fast_ok = m >= kFastTile && n >= kFastTile && (k % kFastKStep) == 0;
+  bool fast = fast_ok && t256 >= 256;
+  // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
+  // the large-problem kernel where its shape constraints hold (results are identical).
+  if (const char *e = getenv("CWAC_FWD_TILE")) {
+    const int v = atoi(e);
+    if (v == 256 || v == 128 || v == 64) {
+      tile = v;
+      fast = false;
+    } else if (e[0] == 'f') {
+      fast = fast_ok;
+    }
+  }
+  if (fast) return launch_fast(p, out_kind, int_only, st);
+  if (tile == 256) return launch_tile<256, 256, 128, 2, 2>(p, out_kind, int_only, st);
+  if (tile == 128) return launch_tile<128, 128, 128, 2, 2>(p, out_kind, int_only, st);
+  return launch_tile<64, 64, 128, 2, 2>(p, out_kind, int_only, st);
+}
+
 extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
                                             int64_t ldw, int64_t m, int32_t n, int32_t k,
                                             const cwac_qparams *qp, const float *mult,
@@ -223,30 +253,7 @@ extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, cons
   if (!aligned(out, esz)) return CWAC_E_ALIGN;
   p.vec_store = ((ldo * esz) % (4 * esz) == 0) && aligned(out, 4 * esz);
   const bool int_only = (out_kind == CWAC_OUT_INT8) && !fbias && !s_x_row;
-  hipStream_t st = as_stream(stream);
-
-  // Tile choice: the largest tile that still gives the 256 compute units at least
-  // two workgroups each; small problems fall back to small tiles.
-  const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
-  const int64_t t128 = ceil_div(m, 128) * ceil_div(n, 128);
-  int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
-  const bool fast_ok = m >= kFastTile && n >= kFastTile && (k % kFastKStep) == 0;
-  bool fast = fast_ok && t256 >= 256;
-  // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
-  // the large-problem kernel where its shape constraints hold (results are identical).
-  if (const char *e = getenv("CWAC_FWD_TILE")) {
-    const int v = atoi(e);
-    if (v == 256 || v == 128 || v == 64) {
-      tile = v;
-      fast = false;
-    } else if (e[0] == 'f') {
-      fast = fast_ok;
-    }
-  }
-  if (fast) return launch_fast(p, out_kind, int_only, st);
-  if (tile == 256) return launch_tile<256, 256, 128, 2, 2>(p, out_kind, int_only, st);
-  if (tile == 128) return launch_tile<128, 128, 128, 2, 2>(p, out_kind, int_only, st);
-  return launch_tile<64, 64, 128, 2, 2>(p, out_kind, int_only, st);
+  return dispatch_forward(p, out_kind, int_only, as_stream(stream));
 }
 
 extern "C" size_t cwac_calibrate_fused_workspace(int64_t m, int32_t n) {
@@ -290,4 +297,30 @@ extern "C" cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t l
   rc = launch_fast_stats(p, st);
   if (rc != CWAC_OK) return rc;
   return launch_stats_merge(p.partial, row_tiles, n, y_full, yq_row0, stats, m, st);
+}
+
+extern "C" cwac_status qlinear_cwac_forward_fixed_point(const int8_t *x_q, int64_t ldx,
+                                                        const int8_t *w_q, int64_t ldw, int64_t m,
+                                                        int32_t n, int32_t k, const cwac_qparams *qp,
+                                                        const int32_t *m0, const int32_t *shift,
+                                                        const int32_t *offset, int8_t *out,
+                                                        int64_t ldo, void *stream) {
+  if (!x_q || !w_q || !out || !qp || !m0 || !shift) return CWAC_E_NULL;
+  if (m < 1 || m > ((int64_t)1 << 40) || n < 1 || k < 16 || k > 32768 || (k % 16) != 0)
+    return CWAC_E_SHAPE;
+  if (ldx < k || ldw < k || ldo < n) return CWAC_E_SHAPE;
+  if (!aligned(x_q, 16) || !aligned(w_q, 16) || (ldx % 16) != 0 || (ldw % 16) != 0)
+    return CWAC_E_ALIGN;
+  if (qp->qmin < -128 || qp->qmax > 127 || qp->qmin > qp->qmax) return CWAC_E_SHAPE;
+  if (qp->z_r < -(1 << 20) || qp->z_r > (1 << 20)) return CWAC_E_SHAPE;
+  FwdParams p = {};
+  p.x = x_q; p.w = w_q; p.ldx = ldx; p.ldw = ldw; p.ldo = ldo;
+  p.m = m; p.n = n; p.k = k;
+  p.offset = offset; p.out = out;
+  p.m0 = m0; p.shift = shift;
+  p.zr = qp->z_r;
+  p.qlo = qp->qmin - qp->z_r;
+  p.qhi = qp->qmax - qp->z_r;
+  p.vec_store = (ldo % 4 == 0) && aligned(out, 4);
+  return dispatch_forward(p, kOutFixed, true, as_stream(stream));
 }
