@@ -80,6 +80,20 @@ cwac_status cwac_quantize_act(const float *x, int64_t ldx, int64_t rows, int32_t
 cwac_status cwac_quantize_rows_sym(const float *x, int64_t ldx, int64_t rows, int32_t k,
                                    float *scale, int8_t *q, int64_t ldq, void *stream);
 
+/* The two quantizers at `bits` bits (2..8) with the codes kept in int8 containers,
+ * for the low-bit settings (W4A4, W6A6): the forward kernels are the same, and
+ * the output range is set by qmin / qmax of cwac_qparams.
+ *   cwac_quantize_act_bits: q = clip(round(x / s) + (z + 2^(bits-1)), 0, 2^bits - 1) - 2^(bits-1),
+ *       z the signed zero-point in [-2^(bits-1), 2^(bits-1) - 1] (Eq. 2's z - 2^(bits-1))
+ *   cwac_quantize_rows_sym_bits: scale[r] = max_k |x[r,k]| / (2^(bits-1) - 1),
+ *       q = clip(round(x / scale[r]), -(2^(bits-1) - 1), 2^(bits-1) - 1)
+ * bits = 8 gives exactly the two functions above; other arguments as there. */
+cwac_status cwac_quantize_act_bits(const float *x, int64_t ldx, int64_t rows, int32_t k, float s,
+                                   int32_t z, int32_t bits, int8_t *q, int64_t ldq, void *stream);
+cwac_status cwac_quantize_rows_sym_bits(const float *x, int64_t ldx, int64_t rows, int32_t k,
+                                        int32_t bits, float *scale, int8_t *q, int64_t ldq,
+                                        void *stream);
+
 /* colsum[n] = sum_k w_q[n, k]: the Z_x W_q term of Eq. 7 is Z_x * colsum[n].
  *   w_q device int8 [n, k]; colsum device int32 [n] */
 cwac_status cwac_colsum(const int8_t *w_q, int64_t ldw, int32_t n, int32_t k, int32_t *colsum,

@@ -130,6 +130,47 @@ void orc_quantize_rows_sym(const float *x, int64_t rows, int64_t k, int64_t ld,
   }
 }
 
+/* The same two quantizers at b bits (2 <= b <= 8) with the codes kept in int8
+ * containers - the low-bit settings of the paper's tables (W4A4, W6A6):
+ * activations: stored value = Eq. 1 code - 2^(b-1), zero-point shifted alike;
+ * weights / per-token activations: symmetric, scale = max|x| / (2^(b-1) - 1),
+ * codes in [-(2^(b-1) - 1), 2^(b-1) - 1]. */
+void orc_quantize_act_bits(const float *x, int64_t count, float s, int32_t z_signed,
+                           int32_t bits, int8_t *q) {
+  const int32_t half = 1 << (bits - 1);
+  const float levels = (float)((1 << bits) - 1);
+  const int32_t z_u = z_signed + half;
+  for (int64_t i = 0; i < count; ++i) {
+    float v = rintf(x[i] / s) + (float)z_u;
+    if (v < 0.0f) v = 0.0f;
+    if (v > levels) v = levels;
+    q[i] = (int8_t)((int32_t)v - half);
+  }
+}
+
+void orc_quantize_rows_sym_bits(const float *x, int64_t rows, int64_t k, int64_t ld,
+                                int32_t bits, float *scale, int8_t *q, int64_t ldq) {
+  const float qmax = (float)((1 << (bits - 1)) - 1);
+  for (int64_t r = 0; r < rows; ++r) {
+    const float *xr = x + r * ld;
+    float amax = 0.0f;
+    for (int64_t j = 0; j < k; ++j) {
+      float a = fabsf(xr[j]);
+      if (a > amax) amax = a;
+    }
+    float s = amax / qmax;
+    const float floor_s = FLT_MIN * 256.0f;
+    if (!(s >= floor_s)) s = floor_s;
+    scale[r] = s;
+    for (int64_t j = 0; j < k; ++j) {
+      float v = rintf(xr[j] / s);
+      if (v < -qmax) v = -qmax;
+      if (v > qmax) v = qmax;
+      q[r * ldq + j] = (int8_t)(int32_t)v;
+    }
+  }
+}
+
 /* ------------------------------------------------------------------ */
 /* Integer product (the W_q x_q term of Eq. 7 / Eq. 10)                */
 /* ------------------------------------------------------------------ */

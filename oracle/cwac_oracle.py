@@ -115,6 +115,27 @@ def quantize_rows_sym(x):
     return q, s
 
 
+def quantize_act_bits(x, s, z_signed, bits):
+    """Eq. 1 at `bits` bits, code - 2^(bits-1) stored in int8."""
+    x = _f32(x)
+    out = np.empty(x.shape, dtype=np.int8)
+    lib().orc_quantize_act_bits(_p(x, C.c_float), C.c_int64(x.size), C.c_float(float(s)),
+                                C.c_int32(int(z_signed)), C.c_int32(int(bits)), _p(out, C.c_int8))
+    return out
+
+
+def quantize_rows_sym_bits(x, bits):
+    """Per-row symmetric quantizer at `bits` bits -> (q int8 [rows,k], scale fp32 [rows])."""
+    x = _f32(x)
+    rows, k = x.shape
+    q = np.empty((rows, k), dtype=np.int8)
+    s = np.empty(rows, dtype=np.float32)
+    lib().orc_quantize_rows_sym_bits(_p(x, C.c_float), C.c_int64(rows), C.c_int64(k),
+                                     C.c_int64(k), C.c_int32(int(bits)), _p(s, C.c_float),
+                                     _p(q, C.c_int8), C.c_int64(k))
+    return q, s
+
+
 # ---------------------------------------------------------------- integer product
 def gemm_i8(xq, wq, rows=None):
     xq, wq = _i8(xq), _i8(wq)

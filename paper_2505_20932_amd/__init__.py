@@ -14,4 +14,5 @@ from .binding import (  # noqa: F401
     cwac_stats_bytes, cwac_stats_reset, make_qparams, qlinear_cwac_forward,
     cwac_calibrate_fused_workspace, qlinear_cwac_calibrate_fused, cwac_mfma_probe,
     cwac_fold_fixed_point, qlinear_cwac_forward_fixed_point,
+    cwac_quantize_act_bits, cwac_quantize_rows_sym_bits,
 )

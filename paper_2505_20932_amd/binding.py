@@ -25,6 +25,7 @@ EXPORTS = (
     "cwac_fold", "qlinear_cwac_forward", "cwac_calibrate_fused_workspace",
     "qlinear_cwac_calibrate_fused", "cwac_epilogue_int32", "cwac_apply_unfolded",
     "cwac_mfma_probe", "cwac_fold_fixed_point", "qlinear_cwac_forward_fixed_point",
+    "cwac_quantize_act_bits", "cwac_quantize_rows_sym_bits",
 )
 
 
@@ -58,6 +59,8 @@ def lib() -> C.CDLL:
             "cwac_qparams_from_range": (i32, [f32, f32, i32, C.POINTER(f32), C.POINTER(i32)]),
             "cwac_quantize_act": (i32, [vp, i64, i64, i32, f32, i32, vp, i64, vp]),
             "cwac_quantize_rows_sym": (i32, [vp, i64, i64, i32, vp, vp, i64, vp]),
+            "cwac_quantize_act_bits": (i32, [vp, i64, i64, i32, f32, i32, i32, vp, i64, vp]),
+            "cwac_quantize_rows_sym_bits": (i32, [vp, i64, i64, i32, i32, vp, vp, i64, vp]),
             "cwac_colsum": (i32, [vp, i64, i32, i32, vp, vp]),
             "cwac_stats_bytes": (sz, [i32]),
             "cwac_stats_reset": (i32, [vp, i32, vp]),
@@ -144,6 +147,23 @@ def cwac_quantize_rows_sym(x: torch.Tensor, scale: torch.Tensor, q: torch.Tensor
     _check(lib().cwac_quantize_rows_sym(_ptr(x), _rowmajor(x), x.shape[0], x.shape[1], _ptr(scale),
                                         _ptr(q), _rowmajor(q), _stream(stream)),
            "cwac_quantize_rows_sym")
+
+
+def cwac_quantize_act_bits(x: torch.Tensor, s: float, z: int, bits: int, q: torch.Tensor,
+                           stream=None):
+    assert x.dtype == torch.float32 and q.dtype == torch.int8 and x.shape == q.shape
+    _check(lib().cwac_quantize_act_bits(_ptr(x), _rowmajor(x), x.shape[0], x.shape[1], s, z, bits,
+                                        _ptr(q), _rowmajor(q), _stream(stream)),
+           "cwac_quantize_act_bits")
+
+
+def cwac_quantize_rows_sym_bits(x: torch.Tensor, bits: int, scale: torch.Tensor, q: torch.Tensor,
+                                stream=None):
+    assert x.dtype == torch.float32 and q.dtype == torch.int8 and scale.dtype == torch.float32
+    assert x.shape == q.shape and scale.numel() == x.shape[0]
+    _check(lib().cwac_quantize_rows_sym_bits(_ptr(x), _rowmajor(x), x.shape[0], x.shape[1], bits,
+                                             _ptr(scale), _ptr(q), _rowmajor(q), _stream(stream)),
+           "cwac_quantize_rows_sym_bits")
 
 
 def cwac_colsum(w_q: torch.Tensor, colsum: torch.Tensor, stream=None):

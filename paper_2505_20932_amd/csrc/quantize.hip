@@ -83,17 +83,22 @@ __global__ __launch_bounds__(kThreads) void range_final_kernel(const float *__re
   }
 }
 
-// ---- Eq. 1, per-tensor parameters, signed 8-bit storage ---------------------
-__device__ __forceinline__ int act_code(float x, float s, float zu) {
-  float v = rintf(__fdiv_rn(x, s)) + zu;
+// ---- Eq. 1, per-tensor parameters, b-bit codes in signed 8-bit storage ------
+// zu = unsigned zero-point, levels = 2^b - 1, half = 2^(b-1)
+struct ActQ {
+  float s, zu, levels;
+  int half;
+};
+__device__ __forceinline__ int act_code(float x, const ActQ &a) {
+  float v = rintf(__fdiv_rn(x, a.s)) + a.zu;
   v = fmaxf(v, 0.0f);
-  v = fminf(v, 255.0f);
-  return static_cast<int>(v) - 128;
+  v = fminf(v, a.levels);
+  return static_cast<int>(v) - a.half;
 }
 
 __global__ __launch_bounds__(kThreads) void quantize_act_vec_kernel(const float *__restrict__ x,
                                                                     int64_t ldx, int64_t rows,
-                                                                    int kv, float s, float zu,
+                                                                    int kv, ActQ a,
                                                                     int8_t *__restrict__ q,
                                                                     int64_t ldq) {
   const int64_t total = rows * kv;
@@ -102,37 +107,36 @@ __global__ __launch_bounds__(kThreads) void quantize_act_vec_kernel(const float 
     const int64_t r = i / kv;
     const int c = static_cast<int>(i - r * kv) * 4;
     const float4 v = *reinterpret_cast<const float4 *>(x + r * ldx + c);
-    const uint32_t b0 = act_code(v.x, s, zu) & 0xff, b1 = act_code(v.y, s, zu) & 0xff,
-                   b2 = act_code(v.z, s, zu) & 0xff, b3 = act_code(v.w, s, zu) & 0xff;
+    const uint32_t b0 = act_code(v.x, a) & 0xff, b1 = act_code(v.y, a) & 0xff,
+                   b2 = act_code(v.z, a) & 0xff, b3 = act_code(v.w, a) & 0xff;
     *reinterpret_cast<uint32_t *>(q + r * ldq + c) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
   }
 }
 
 __global__ __launch_bounds__(kThreads) void quantize_act_kernel(const float *__restrict__ x,
                                                                 int64_t ldx, int64_t rows, int k,
-                                                                float s, float zu,
-                                                                int8_t *__restrict__ q,
+                                                                ActQ a, int8_t *__restrict__ q,
                                                                 int64_t ldq) {
   const int64_t total = rows * k;
   for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total;
        i += (int64_t)gridDim.x * kThreads) {
     const int64_t r = i / k;
     const int64_t c = i - r * k;
-    q[r * ldq + c] = static_cast<int8_t>(act_code(x[r * ldx + c], s, zu));
+    q[r * ldq + c] = static_cast<int8_t>(act_code(x[r * ldx + c], a));
   }
 }
 
 // ---- symmetric per-row quantizer: one workgroup per row ---------------------
-__device__ __forceinline__ int sym_code(float x, float s) {
+__device__ __forceinline__ int sym_code(float x, float s, float qmax) {
   float v = rintf(__fdiv_rn(x, s));
-  v = fmaxf(v, -127.0f);
-  v = fminf(v, 127.0f);
+  v = fmaxf(v, -qmax);
+  v = fminf(v, qmax);
   return static_cast<int>(v);
 }
 
 __global__ __launch_bounds__(kThreads) void quantize_rows_sym_kernel(
-    const float *__restrict__ x, int64_t ldx, int k, int vec_ok, float *__restrict__ scale,
-    int8_t *__restrict__ q, int64_t ldq) {
+    const float *__restrict__ x, int64_t ldx, int k, int vec_ok, float qmax,
+    float *__restrict__ scale, int8_t *__restrict__ q, int64_t ldq) {
   const int64_t row = blockIdx.x;
   const float *xr = x + row * ldx;
   int8_t *qr = q + row * ldq;
@@ -151,20 +155,20 @@ __global__ __launch_bounds__(kThreads) void quantize_rows_sym_kernel(
   __syncthreads();
   amax = s_max[0];
   for (int i = 1; i < kThreads / kWave; ++i) amax = fmaxf(amax, s_max[i]);
-  float s = __fdiv_rn(amax, 127.0f);
+  float s = __fdiv_rn(amax, qmax);
   const float floor_s = FLT_MIN * 256.0f;
   if (!(s >= floor_s)) s = floor_s;
   if (threadIdx.x == 0) scale[row] = s;
   if (vec_ok) {
     for (int c = threadIdx.x * 4; c < k; c += kThreads * 4) {
       const float4 v = *reinterpret_cast<const float4 *>(xr + c);
-      const uint32_t b0 = sym_code(v.x, s) & 0xff, b1 = sym_code(v.y, s) & 0xff,
-                     b2 = sym_code(v.z, s) & 0xff, b3 = sym_code(v.w, s) & 0xff;
+      const uint32_t b0 = sym_code(v.x, s, qmax) & 0xff, b1 = sym_code(v.y, s, qmax) & 0xff,
+                     b2 = sym_code(v.z, s, qmax) & 0xff, b3 = sym_code(v.w, s, qmax) & 0xff;
       *reinterpret_cast<uint32_t *>(qr + c) = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
     }
   } else {
     for (int c = threadIdx.x; c < k; c += kThreads)
-      qr[c] = static_cast<int8_t>(sym_code(xr[c], s));
+      qr[c] = static_cast<int8_t>(sym_code(xr[c], s, qmax));
   }
 }
 
@@ -238,41 +242,60 @@ extern "C" cwac_status cwac_qparams_from_range(float mn, float mx, int32_t bits,
   return CWAC_OK;
 }
 
-extern "C" cwac_status cwac_quantize_act(const float *x, int64_t ldx, int64_t rows, int32_t k,
-                                         float s, int32_t z, int8_t *q, int64_t ldq,
-                                         void *stream) {
+extern "C" cwac_status cwac_quantize_act_bits(const float *x, int64_t ldx, int64_t rows, int32_t k,
+                                              float s, int32_t z, int32_t bits, int8_t *q,
+                                              int64_t ldq, void *stream) {
   if (!x || !q) return CWAC_E_NULL;
-  if (rows < 0 || k < 1 || ldx < k || ldq < k || !(s > 0.0f) || z < -128 || z > 127)
+  if (bits < 2 || bits > 8) return CWAC_E_SHAPE;
+  const int half = 1 << (bits - 1);
+  if (rows < 0 || k < 1 || ldx < k || ldq < k || !(s > 0.0f) || z < -half || z > half - 1)
     return CWAC_E_SHAPE;
   if (!aligned(x, 4)) return CWAC_E_ALIGN;
   if (rows == 0) return CWAC_OK;
-  const float zu = (float)(z + 128);
+  ActQ a;
+  a.s = s;
+  a.zu = (float)(z + half);
+  a.levels = (float)((1 << bits) - 1);
+  a.half = half;
   const bool vec = (k % 4 == 0) && (ldx % 4 == 0) && (ldq % 4 == 0) && aligned(x, 16) &&
                    aligned(q, 4);
   const int64_t work = vec ? rows * (k / 4) : rows * (int64_t)k;
   const int64_t want = ceil_div(work, kThreads);
   const int blocks = (int)(want < 65536 ? want : 65536);
   if (vec)
-    quantize_act_vec_kernel<<<blocks, kThreads, 0, as_stream(stream)>>>(x, ldx, rows, k / 4, s,
-                                                                         zu, q, ldq);
+    quantize_act_vec_kernel<<<blocks, kThreads, 0, as_stream(stream)>>>(x, ldx, rows, k / 4, a, q,
+                                                                         ldq);
   else
-    quantize_act_kernel<<<blocks, kThreads, 0, as_stream(stream)>>>(x, ldx, rows, k, s, zu, q,
-                                                                     ldq);
+    quantize_act_kernel<<<blocks, kThreads, 0, as_stream(stream)>>>(x, ldx, rows, k, a, q, ldq);
+  return launch_status();
+}
+
+extern "C" cwac_status cwac_quantize_act(const float *x, int64_t ldx, int64_t rows, int32_t k,
+                                         float s, int32_t z, int8_t *q, int64_t ldq,
+                                         void *stream) {
+  return cwac_quantize_act_bits(x, ldx, rows, k, s, z, 8, q, ldq, stream);
+}
+
+extern "C" cwac_status cwac_quantize_rows_sym_bits(const float *x, int64_t ldx, int64_t rows,
+                                                   int32_t k, int32_t bits, float *scale,
+                                                   int8_t *q, int64_t ldq, void *stream) {
+  if (!x || !q || !scale) return CWAC_E_NULL;
+  if (bits < 2 || bits > 8) return CWAC_E_SHAPE;
+  if (rows < 0 || rows > 0x7fffffff || k < 1 || ldx < k || ldq < k) return CWAC_E_SHAPE;
+  if (!aligned(x, 4) || !aligned(scale, 4)) return CWAC_E_ALIGN;
+  if (rows == 0) return CWAC_OK;
+  const int vec = (k % 4 == 0) && (ldx % 4 == 0) && (ldq % 4 == 0) && aligned(x, 16) &&
+                  aligned(q, 4);
+  const float qmax = (float)((1 << (bits - 1)) - 1);
+  quantize_rows_sym_kernel<<<(unsigned)rows, kThreads, 0, as_stream(stream)>>>(x, ldx, k, vec, qmax,
+                                                                                scale, q, ldq);
   return launch_status();
 }
 
 extern "C" cwac_status cwac_quantize_rows_sym(const float *x, int64_t ldx, int64_t rows,
                                               int32_t k, float *scale, int8_t *q, int64_t ldq,
                                               void *stream) {
-  if (!x || !q || !scale) return CWAC_E_NULL;
-  if (rows < 0 || rows > 0x7fffffff || k < 1 || ldx < k || ldq < k) return CWAC_E_SHAPE;
-  if (!aligned(x, 4) || !aligned(scale, 4)) return CWAC_E_ALIGN;
-  if (rows == 0) return CWAC_OK;
-  const int vec = (k % 4 == 0) && (ldx % 4 == 0) && (ldq % 4 == 0) && aligned(x, 16) &&
-                  aligned(q, 4);
-  quantize_rows_sym_kernel<<<(unsigned)rows, kThreads, 0, as_stream(stream)>>>(x, ldx, k, vec,
-                                                                                scale, q, ldq);
-  return launch_status();
+  return cwac_quantize_rows_sym_bits(x, ldx, rows, k, 8, scale, q, ldq, stream);
 }
 
 extern "C" cwac_status cwac_colsum(const int8_t *w_q, int64_t ldw, int32_t n, int32_t k,
