@@ -475,6 +475,19 @@ def main():
             sum(2.0 * L.cal_rows * L.n * L.k for L in layers) / (t_cal * 1e-3) / 1e12, 2),
         "stats_gbs": round(stats_gbs, 1),
     }
+    # the same step captured once in a HIP graph and replayed (what a launch-bound caller would do)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run_step(P, layers)
+    g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        g.replay()
+    torch.cuda.synchronize()
+    t_graph = (time.perf_counter() - t0) / args.steps
+    result["graph_replay"] = {"ms_per_step": round(t_graph * 1e3, 4),
+                              "tops": round(gemm_ops / t_graph / 1e12, 2)}
     result["epilogue_comparators"] = comparators(P, torch, layers)
     result["fused_calibration"] = fused_calibration(P, torch, layers, args.steps)
     result["mfma_ceiling_probe"] = mfma_ceiling(P, torch, layers)
