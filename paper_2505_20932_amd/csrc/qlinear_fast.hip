@@ -650,11 +650,9 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
   const dim3 grid((unsigned)blocks);
-  // Tuning knob: CWAC_FWD_PIPE=128x2 | 128x2x4 | 64x4 selects K step, ring depth and the number of
-  // chunks a stage's loads are issued in (same results).
+  // Tuning knob: CWAC_FWD_PIPE=128x2 | 64x4 selects K step and ring depth (same results).
   const char *e = getenv("CWAC_FWD_PIPE");
   if (e && e[0] == '6') return launch_cfg<64, 4, 2>(p, out_kind, int_only, grid, st);
-  if (e && e[0] == '1' && e[strlen(e) - 1] == '4') return launch_cfg<128, 2, 4>(p, out_kind, int_only, grid, st);
   return launch_cfg<128, 2, 2>(p, out_kind, int_only, grid, st);
 }
 

@@ -87,6 +87,48 @@ def test_argument_errors_launch_nothing(lib):
     assert lib.cwac_calibrate_stats(a, 2, a, 4, 8, 4, a, a, 1 << 20, null) == -2  # ld < c_out
 
 
+def test_argument_errors_of_the_widened_entry_points(lib):
+    qp = binding.make_qparams()
+    null = None
+    a = C.c_void_p(4096)
+    big = 1 << 30
+    # fused calibration: NULLs, shapes outside the large-tile kernel, alignment, workspace
+    f = lib.qlinear_cwac_calibrate_fused
+    assert f(null, 128, a, 128, 256, 256, 128, a, null, null, null, a, 256, a, a, big, null) == -1
+    assert f(a, 128, a, 128, 255, 256, 128, a, null, null, null, a, 256, a, a, big, null) == -2
+    assert f(a, 128, a, 128, 256, 258, 128, a, null, null, null, a, 260, a, a, big, null) == -2  # n % 4
+    assert f(a, 192, a, 192, 256, 256, 192, a, null, null, null, a, 256, a, a, big, null) == -2  # k % 128
+    assert f(a, 128, a, 128, 256, 256, 128, a, null, null, null, a, 258, a, a, big, null) == -3  # ld_full % 4
+    assert f(a, 128, a, 128, 256, 256, 128, a, null, null, null, a, 256, a, a, 64, null) == -5
+    assert P.cwac_calibrate_fused_workspace(16384, 4096) == 64 * 5 * 4096 * 8 + 4096 * 4
+    # integer-only form
+    g = lib.cwac_fold_fixed_point
+    assert g(null, null, null, null, null, 4, C.byref(qp), null, null, null, null, null) == -1
+    per_token = binding.make_qparams(mode=1, act_per_token=True)
+    assert g(null, null, a, null, a, 4, C.byref(per_token), a, a, a, null, null) == -4
+    h = lib.qlinear_cwac_forward_fixed_point
+    assert h(a, 32, a, 32, 4, 4, 32, C.byref(qp), null, a, null, a, 4, null) == -1   # no multiplier
+    assert h(a, 24, a, 24, 4, 4, 24, C.byref(qp), a, a, null, a, 4, null) == -2      # k % 16
+    assert h(a, 32, a, 32, 4, 4, 32, C.byref(qp), a, a, null, a, 2, null) == -2      # ldo < n
+    # b-bit quantizers
+    q = lib.cwac_quantize_act_bits
+    assert q(a, 8, 4, 8, 1.0, 0, 9, a, 8, null) == -2          # bits out of range
+    assert q(a, 8, 4, 8, 1.0, 8, 4, a, 8, null) == -2          # zero-point outside the 4-bit range
+    assert q(a, 8, 0, 8, 1.0, 0, 4, a, 8, null) == 0           # no rows: no-op
+    assert lib.cwac_quantize_rows_sym_bits(a, 8, 4, 8, 1, a, a, 8, null) == -2
+    # diagnostic
+    assert lib.cwac_mfma_probe(null, 10, 1, a, null) == -1
+    assert lib.cwac_mfma_probe(a, 0, 1, a, null) == -2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
 def test_eq2_host_function_matches_oracle(orc, lib):
     x = synth.normal(5, 0, 1000).numpy()
     cases = [(-64.0, 191.0), (float(x.min()), float(x.max())), (0.0, 0.0), (-1e-3, 7.5),
