@@ -389,7 +389,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default: the LLM layer)")
     ap.add_argument("--cal-rows", type=int, default=0, help="calibration rows per step (default: "
                     "one batch = the workload's token count)")
-    ap.add_argument("--cpu-sample-rows", type=int, default=512)
+    ap.add_argument("--cpu-sample-rows", type=int, default=1536)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
