@@ -291,7 +291,7 @@ extern "C" cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t l
   float *yq_row0 = reinterpret_cast<float *>(p.partial + (size_t)row_tiles * kStats * n);
   p.yq_row0 = yq_row0;
   hipStream_t st = as_stream(stream);
-  row0_kernel<<<(unsigned)ceil_div(n, 16), 256, 0, st>>>(p, yq_row0);
+  row0_kernel<<<(unsigned)ceil_div(n, 4), 256, 0, st>>>(p, yq_row0);  // one channel per wavefront
   cwac_status rc = launch_status();
   if (rc != CWAC_OK) return rc;
   rc = launch_fast_stats(p, st);
