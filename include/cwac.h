@@ -301,6 +301,69 @@ cwac_status cwac_apply_unfolded(const float *y, int64_t ldy, int64_t rows, int32
                                 void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Weight-only INT4 linear layer with the compensation in its epilogue -       */
+/* the LLM setting of Sec. 4.4 (group-wise asymmetric 4-bit weights, group     */
+/* size 128, 16-bit floating-point activations) with the CWAC of Sec. 3.3      */
+/* folded as in Sec. 3.4                                                       */
+/* ------------------------------------------------------------------------- */
+
+/* binary16 values cross this interface as their bit patterns (uint16_t). */
+enum { CWAC_W4_GROUP = 128 };
+enum { CWAC_OUT_FP16 = 3 };
+
+/* Eq. 1-2 with b = 4 on every group of 128 consecutive input channels of one
+ * output channel.  s = (max - min) / 15 in fp32, STORED as binary16 (nearest
+ * even; floored at 2^-14, capped at 65504); z = clip(round(-min / s), 0, 15) and
+ * c = clip(round(w / s) + z, 0, 15) against the stored scale (fp32 division).
+ *   w       device fp32 [n, k], ldw;  n >= 1, k % 128 == 0, ldw % 2 == 0, w 8-byte aligned
+ *   codes   device uint8 [n, k] (one code per byte, pitch k)
+ *   scales  device uint16 [n, k / 128] binary16 bit patterns
+ *   zeros   device uint8 [n, k / 128] */
+cwac_status cwac_w4_quantize_groupwise(const float *w, int64_t ldw, int32_t n, int32_t k,
+                                       uint8_t *codes, uint16_t *scales, uint8_t *zeros,
+                                       void *stream);
+
+/* Re-orders the quantized weights into the layout the forward kernel streams
+ * (done once per layer, offline in an engine).  An activation re-ordering
+ * ("act-order") is a fixed permutation of the k axis applied to the weight
+ * columns and activation channels beforehand; here groups are contiguous in k.
+ *   packed_w   device, cwac_w4_packed_w_bytes(n, k) = n * k / 2 bytes, 16-byte aligned:
+ *              1 KiB blocks indexed [n / 32][k / 64]; in a block, 16 bytes per lane
+ *              (lane = 32 * h + n % 32, h = 0, 1); dword j of a lane holds the 8 codes of
+ *              input channels 64 * block + 16 * j + 8 * h + e, e = 0..7, code e in bits
+ *              4 * p(e) .. 4 * p(e) + 3 with p = (0, 4, 1, 5, 2, 6, 3, 7)
+ *   packed_sz  device uint32 [k / 128][n]: scale bits | zero << 16
+ *   n % 32 == 0, k % 128 == 0 */
+size_t cwac_w4_packed_w_bytes(int32_t n, int32_t k);
+cwac_status cwac_w4_pack(const uint8_t *codes, const uint16_t *scales, const uint8_t *zeros,
+                         int32_t n, int32_t k, void *packed_w, uint32_t *packed_sz, void *stream);
+
+/* Fold of the compensation into the weight-only layer's epilogue (the analogue of
+ * Eq. 10-11 where nothing is requantized): the multiplier is alpha itself and the
+ * constant is alpha * bias + beta, evaluated in fp64 and rounded once to fp32.
+ * alpha == NULL and beta == NULL: mult = 1, fbias = bias (0 without bias).
+ *   alpha, beta, bias (nullable)  device fp32 [n_out];  mult, fbias  device fp32 [n_out] */
+cwac_status cwac_fold_weight_only(const float *alpha, const float *beta, const float *bias,
+                                  int32_t n_out, float *mult, float *fbias, void *stream);
+
+/* out = epilogue(x * Wd^T) with Wd[n, k] = RN16(s[n, g] * (c[n, k] - z[n, g])), g = k / 128,
+ * dequantized in registers (one binary16 rounding), binary16 x binary16 -> fp32 on
+ * the matrix cores.  Per output element:
+ *   acc = sum_k x[m, k] * Wd[n, k]      fp32 accumulation (order unspecified)
+ *   u   = acc * mult[n]                 only if mult != NULL
+ *   u   = u + fbias[n]                  only if fbias != NULL     (single fp32 operations)
+ *   CWAC_OUT_FP16: out = RN16(u);   CWAC_OUT_FP32: out = u  (calibration forward: Y_quant)
+ *   x          device binary16 [m, k], ldx; 16-byte aligned, ldx % 8 == 0
+ *   packed_w, packed_sz   as produced by cwac_w4_pack
+ *   m >= 1, n >= 256, n % 32 == 0, 128 <= k <= 32768, k % 128 == 0
+ *   mult, fbias  device fp32 [n] or NULL
+ *   out        device [m, n], ldo; 16-byte aligned, ldo * sizeof(element) % 16 == 0 */
+cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const void *packed_w,
+                                       const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
+                                       const float *mult, const float *fbias, int32_t out_kind,
+                                       void *out, int64_t ldo, void *stream);
+
+/* ------------------------------------------------------------------------- */
 /* Diagnostic (measurement aid, not a step of the method)                     */
 /* ------------------------------------------------------------------------- */
 

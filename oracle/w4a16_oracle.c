@@ -26,6 +26,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -127,6 +128,7 @@ void w4o_quantize_groupwise(const float *w, int64_t n, int64_t k, int64_t ld, in
 void w4o_dequant(const uint8_t *codes, const uint16_t *scales, const uint8_t *zeros, int64_t n,
                  int64_t k, int64_t group, float *wd) {
   const int64_t groups = k / group;
+#pragma omp parallel for schedule(static)
   for (int64_t r = 0; r < n; ++r)
     for (int64_t i = 0; i < k; ++i) {
       const int64_t g = i / group;
@@ -149,19 +151,25 @@ void w4o_dequant(const uint8_t *codes, const uint16_t *scales, const uint8_t *ze
 void w4o_product(const uint16_t *x, const float *wd, int64_t m, int64_t n, int64_t k,
                  const int64_t *rows, int64_t n_rows, double *acc, double *mag) {
   const int64_t cnt = rows ? n_rows : m;
-#pragma omp parallel for schedule(static)
-  for (int64_t i = 0; i < cnt; ++i) {
-    const int64_t r = rows ? rows[i] : i;
-    for (int64_t c = 0; c < n; ++c) {
-      double s = 0.0, a = 0.0;
-      for (int64_t j = 0; j < k; ++j) {
-        const double p = (double)w4o_f16_to_f32(x[r * k + j]) * (double)wd[c * k + j];
-        s += p;
-        a += fabs(p);
+#pragma omp parallel
+  {
+    double *xr = (double *)malloc((size_t)k * sizeof(double)); /* one activation row, converted once */
+#pragma omp for schedule(static)
+    for (int64_t i = 0; i < cnt; ++i) {
+      const int64_t r = rows ? rows[i] : i;
+      for (int64_t j = 0; j < k; ++j) xr[j] = (double)w4o_f16_to_f32(x[r * k + j]);
+      for (int64_t c = 0; c < n; ++c) {
+        double s = 0.0, a = 0.0;
+        for (int64_t j = 0; j < k; ++j) {
+          const double p = xr[j] * (double)wd[c * k + j];
+          s += p;
+          a += fabs(p);
+        }
+        acc[i * n + c] = s;
+        if (mag) mag[i * n + c] = a;
       }
-      acc[i * n + c] = s;
-      if (mag) mag[i * n + c] = a;
     }
+    free(xr);
   }
 }
 

@@ -16,7 +16,8 @@ LIB_PATH = os.environ.get("CWAC_LIB") or os.path.join(_PKG, "libcwac_hip.so")
 
 CWAC_OK = 0
 CWAC_EPI_INT_OFFSET, CWAC_EPI_FP_BIAS = 0, 1
-CWAC_OUT_INT8, CWAC_OUT_FP32, CWAC_OUT_INT32 = 0, 1, 2
+CWAC_OUT_INT8, CWAC_OUT_FP32, CWAC_OUT_INT32, CWAC_OUT_FP16 = 0, 1, 2, 3
+CWAC_W4_GROUP = 128
 
 EXPORTS = (
     "cwac_status_string", "cwac_range_workspace", "cwac_range_f32", "cwac_qparams_from_range",
@@ -26,6 +27,8 @@ EXPORTS = (
     "qlinear_cwac_calibrate_fused", "cwac_epilogue_int32", "cwac_apply_unfolded",
     "cwac_mfma_probe", "cwac_fold_fixed_point", "qlinear_cwac_forward_fixed_point",
     "cwac_quantize_act_bits", "cwac_quantize_rows_sym_bits",
+    "cwac_w4_quantize_groupwise", "cwac_w4_packed_w_bytes", "cwac_w4_pack",
+    "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward",
 )
 
 
@@ -79,6 +82,12 @@ def lib() -> C.CDLL:
             "cwac_fold_fixed_point": (i32, [vp, vp, vp, vp, vp, i32, qpp, vp, vp, vp, vp, vp]),
             "qlinear_cwac_forward_fixed_point": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp,
                                                        vp, vp, i64, vp]),
+            "cwac_w4_quantize_groupwise": (i32, [vp, i64, i32, i32, vp, vp, vp, vp]),
+            "cwac_w4_packed_w_bytes": (sz, [i32, i32]),
+            "cwac_w4_pack": (i32, [vp, vp, vp, i32, i32, vp, vp, vp]),
+            "cwac_fold_weight_only": (i32, [vp, vp, vp, i32, vp, vp, vp]),
+            "qlinear_w4a16_cwac_forward": (i32, [vp, i64, vp, vp, i64, i32, i32, vp, vp, i32, vp,
+                                                 i64, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
@@ -289,6 +298,54 @@ def qlinear_cwac_forward_fixed_point(x_q: torch.Tensor, w_q: torch.Tensor, qp: c
                                                   _ptr(shift), _ptr(offset), _ptr(out),
                                                   _rowmajor(out), _stream(stream)),
            "qlinear_cwac_forward_fixed_point")
+
+
+# --------------------------------------------------------------------------- weight-only INT4
+def cwac_w4_quantize_groupwise(w: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor,
+                               zeros: torch.Tensor, stream=None):
+    """scales: float16 [n, k/128] (the library sees the bit patterns)."""
+    assert w.dtype == torch.float32 and codes.dtype == torch.uint8 and zeros.dtype == torch.uint8
+    assert scales.dtype == torch.float16 and codes.is_contiguous() and codes.shape == w.shape
+    n, k = w.shape
+    assert scales.shape == (n, k // CWAC_W4_GROUP) and zeros.shape == scales.shape
+    assert scales.is_contiguous() and zeros.is_contiguous()
+    _check(lib().cwac_w4_quantize_groupwise(_ptr(w), _rowmajor(w), n, k, _ptr(codes), _ptr(scales),
+                                            _ptr(zeros), _stream(stream)),
+           "cwac_w4_quantize_groupwise")
+
+
+def cwac_w4_packed_w_bytes(n: int, k: int) -> int:
+    return int(lib().cwac_w4_packed_w_bytes(n, k))
+
+
+def cwac_w4_pack(codes: torch.Tensor, scales: torch.Tensor, zeros: torch.Tensor,
+                 packed_w: torch.Tensor, packed_sz: torch.Tensor, stream=None):
+    assert codes.dtype == torch.uint8 and codes.is_contiguous() and zeros.dtype == torch.uint8
+    assert scales.dtype == torch.float16 and scales.is_contiguous() and zeros.is_contiguous()
+    n, k = codes.shape
+    assert packed_w.numel() * packed_w.element_size() >= cwac_w4_packed_w_bytes(n, k)
+    assert packed_sz.dtype in (torch.int32, torch.uint32) and packed_sz.numel() >= n * (k // CWAC_W4_GROUP)
+    _check(lib().cwac_w4_pack(_ptr(codes), _ptr(scales), _ptr(zeros), n, k, _ptr(packed_w),
+                              _ptr(packed_sz), _stream(stream)), "cwac_w4_pack")
+
+
+def cwac_fold_weight_only(alpha, beta, bias, mult: torch.Tensor, fbias: torch.Tensor, stream=None):
+    assert mult.dtype == torch.float32 and fbias.dtype == torch.float32
+    _check(lib().cwac_fold_weight_only(_ptr(alpha), _ptr(beta), _ptr(bias), mult.numel(), _ptr(mult),
+                                       _ptr(fbias), _stream(stream)), "cwac_fold_weight_only")
+
+
+def qlinear_w4a16_cwac_forward(x: torch.Tensor, packed_w: torch.Tensor, packed_sz: torch.Tensor,
+                               n: int, mult, fbias, out: torch.Tensor, stream=None):
+    """x float16 [m, k]; out float16 (CWAC_OUT_FP16) or float32 (CWAC_OUT_FP32) [m, n]."""
+    assert x.dtype == torch.float16 and out.dtype in (torch.float16, torch.float32)
+    m, k = x.shape
+    assert out.shape == (m, n)
+    kind = CWAC_OUT_FP16 if out.dtype == torch.float16 else CWAC_OUT_FP32
+    _check(lib().qlinear_w4a16_cwac_forward(_ptr(x), _rowmajor(x), _ptr(packed_w), _ptr(packed_sz),
+                                            m, n, k, _ptr(mult), _ptr(fbias), kind, _ptr(out),
+                                            _rowmajor(out), _stream(stream)),
+           "qlinear_w4a16_cwac_forward")
 
 
 # --------------------------------------------------------------------------- diagnostic

@@ -1,0 +1,509 @@
+// Weight-only INT4 linear layer with the CWAC epilogue (LLM setting of Sec. 4.4: group-wise
+// asymmetric 4-bit weights, group size 128, binary16 activations; compensation of Sec. 3.3
+// folded into the epilogue as in Sec. 3.4), plus its quantizer, weight re-ordering and fold.
+//
+// Forward kernel: 256 x 256 output tile, four wavefronts (2 x 2, each 128 x 128 = 4 x 4 tiles of
+// v_mfma_f32_32x32x16_f16, 256 fp32 accumulators per lane), one workgroup per compute unit.
+//   * Activation panels go global -> LDS directly (global_load_lds_dwordx4); one K stage is one
+//     quantization group (128 channels = 256 bytes per row, 64 KiB per stage, two stages).  The
+//     bank swizzle (16-byte chunk position XOR row & 15) is applied on the global-address side.
+//   * Weights never touch LDS: they were re-ordered once into the order in which a wavefront's
+//     lanes consume them, so each wavefront streams its own 4-bit codes with contiguous 1 KiB
+//     loads straight into registers, one stage ahead, together with the group's scale and
+//     zero-point, and expands them to binary16 MFMA operands right before use:
+//     (code | 0x6400) is the binary16 number 1024 + code, so (1024 + c) - (1024 + z) and
+//     fma(1024 + 16 c, 1/16, -(64 + z)) give c - z exactly with one packed instruction each,
+//     and one packed multiply by the scale is the single rounding of RN16(s * (c - z)).
+//   * Epilogue in registers: acc * mult[n] + fbias[n] (two fp32 operations), conversion to
+//     binary16, transposition through a wave-private LDS slab, whole 128-byte line stores.
+#include <hip/hip_runtime.h>
+
+#include "qlinear_common.h"
+
+namespace cwac {
+namespace {
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+#define CWAC_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+#define CWAC_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
+
+constexpr int wait_imm(int vmcnt, int lgkmcnt) {
+  // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14 ; expcnt = 7 (no wait)
+  return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
+}
+
+constexpr int kGroup = CWAC_W4_GROUP;  // input channels per scale / zero-point = per K stage
+constexpr int kThreads = 256;
+
+// ------------------------------------------------------------------------------------------
+// Quantizer (Eq. 1-2, b = 4, per group): one wavefront per (output channel, group), two
+// weights per lane.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void w4_quantize_kernel(const float *__restrict__ w, int64_t ldw,
+                                                               int n, int groups,
+                                                               uint8_t *__restrict__ codes,
+                                                               uint16_t *__restrict__ scales,
+                                                               uint8_t *__restrict__ zeros) {
+  const int lane = threadIdx.x & 63;
+  const int64_t task = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+  if (task >= (int64_t)n * groups) return;
+  const int r = (int)(task / groups), g = (int)(task - (int64_t)r * groups);
+  const float2 v = *reinterpret_cast<const float2 *>(w + (int64_t)r * ldw + g * kGroup + 2 * lane);
+  const float mn = wave_min(fminf(v.x, v.y)), mx = wave_max(fmaxf(v.x, v.y));
+  const _Float16 sh = (_Float16)__fdiv_rn(mx - mn, 15.0f);  // round to nearest even
+  uint16_t sb = __builtin_bit_cast(uint16_t, sh);
+  if (sb < 0x0400u) sb = 0x0400u;   // zero or subnormal: 2^-14
+  if (sb >= 0x7c00u) sb = 0x7bffu;  // never infinite
+  const float s = (float)__builtin_bit_cast(_Float16, sb);
+  float zf = rintf(__fdiv_rn(-mn, s));
+  zf = fminf(fmaxf(zf, 0.0f), 15.0f);
+  float c0 = rintf(__fdiv_rn(v.x, s)) + zf, c1 = rintf(__fdiv_rn(v.y, s)) + zf;
+  c0 = fminf(fmaxf(c0, 0.0f), 15.0f);
+  c1 = fminf(fmaxf(c1, 0.0f), 15.0f);
+  const int64_t kk = (int64_t)groups * kGroup;
+  *reinterpret_cast<uint16_t *>(codes + (int64_t)r * kk + g * kGroup + 2 * lane) =
+      (uint16_t)((uint32_t)c0 | ((uint32_t)c1 << 8));
+  if (lane == 0) {
+    scales[(int64_t)r * groups + g] = sb;
+    zeros[(int64_t)r * groups + g] = (uint8_t)zf;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Re-ordering into the forward kernel's streaming layout: one thread per output dword.
+// dword index = (((n / 32) * (k / 64) + kb) * 64 + lane) * 4 + j, lane = 32 * h + n % 32; it
+// holds the codes of input channels 64 * kb + 16 * j + 8 * h + e (e = 0..7) at nibble p(e).
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void w4_pack_kernel(const uint8_t *__restrict__ codes, int n, int k,
+                                                           uint32_t *__restrict__ packed) {
+  const int64_t total = (int64_t)n * (k / 8);
+  for (int64_t d = (int64_t)blockIdx.x * kThreads + threadIdx.x; d < total;
+       d += (int64_t)gridDim.x * kThreads) {
+    const int j = (int)(d & 3), lane = (int)((d >> 2) & 63);
+    const int64_t blk = d >> 8;
+    const int kb64 = k / 64;
+    const int nb = (int)(blk / kb64), kb = (int)(blk - (int64_t)nb * kb64);
+    const int row = nb * 32 + (lane & 31), h = lane >> 5;
+    const uint8_t *src = codes + (int64_t)row * k + kb * 64 + j * 16 + h * 8;
+    const uint2 raw = *reinterpret_cast<const uint2 *>(src);  // 8 codes, 8-byte aligned
+    uint32_t word = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t c = ((e < 4 ? raw.x : raw.y) >> (8 * (e & 3))) & 15u;
+      const int p = (e >> 1) + 4 * (e & 1);  // (0, 4, 1, 5, 2, 6, 3, 7)
+      word |= c << (4 * p);
+    }
+    packed[d] = word;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void w4_pack_sz_kernel(const uint16_t *__restrict__ scales,
+                                                              const uint8_t *__restrict__ zeros, int n,
+                                                              int groups, uint32_t *__restrict__ sz) {
+  const int64_t total = (int64_t)n * groups;
+  for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * kThreads) {
+    const int g = (int)(i / n), r = (int)(i - (int64_t)g * n);
+    sz[i] = (uint32_t)scales[(int64_t)r * groups + g] | ((uint32_t)zeros[(int64_t)r * groups + g] << 16);
+  }
+}
+
+// Fold (Sec. 3.4 for a layer without requantization): mult = alpha, fbias = alpha * b + beta.
+__global__ __launch_bounds__(kThreads) void fold_weight_only_kernel(const float *__restrict__ alpha,
+                                                                    const float *__restrict__ beta,
+                                                                    const float *__restrict__ bias, int n,
+                                                                    float *__restrict__ mult,
+                                                                    float *__restrict__ fbias) {
+  const int c = blockIdx.x * kThreads + threadIdx.x;
+  if (c >= n) return;
+  const double a = alpha ? (double)alpha[c] : 1.0;
+  const double be = beta ? (double)beta[c] : 0.0;
+  const double b = bias ? (double)bias[c] : 0.0;
+  mult[c] = (float)a;
+  fbias[c] = (float)(__dadd_rn(__dmul_rn(a, b), be));
+}
+
+// ------------------------------------------------------------------------------------------
+// Forward
+// ------------------------------------------------------------------------------------------
+struct W4Params {
+  const char *x;  // binary16 [m, k]
+  int64_t ldx_bytes;
+  const u4 *wp;
+  const uint32_t *sz;
+  int64_t m;
+  int n, k;
+  const float *mult;
+  const float *fbias;
+  char *out;
+  int64_t ldo;
+  int tiles_m, tiles_n;
+};
+
+constexpr int kStageBytes = 256 * 256;  // 256 rows x 128 binary16
+constexpr int kRing = 2 * kStageBytes;
+constexpr int kW4Lds = kRing + 2 * 256 * 4;
+constexpr int kXLoads = 16;  // global_load_lds per wavefront and stage (4 rows x 256 bytes each)
+
+constexpr int kSlabStride = 144;
+constexpr int kSlabBytes = 128 * kSlabStride;
+
+__device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+
+// Scale and zero-point of one weight row in the three forms the expansion needs.
+struct GroupConst {
+  h2 s, zlo, zhi;  // (s, s), (1024 + z) twice, (64 + z) twice
+};
+__device__ __forceinline__ GroupConst group_const(uint32_t sz) {
+  GroupConst g;
+  const uint32_t z = sz >> 16;
+  g.s = as_h2((sz & 0xffffu) * 0x00010001u);
+  g.zlo = as_h2(0x64006400u + z * 0x00010001u);  // 1024 + z: one unit per mantissa step
+  g.zhi = as_h2(0x54005400u + z * 0x00100010u);  // 64 + z: sixteen mantissa steps per unit
+  return g;
+}
+
+// Eight codes (one dword in the packed order) -> the MFMA operand of 8 consecutive input channels.
+__device__ __forceinline__ h8 expand8(uint32_t w, const GroupConst &g) {
+  const uint32_t w8 = w >> 8;
+  const h2 t0 = as_h2((w & 0x000f000fu) | 0x64006400u);   // 1024 + c      channels 0, 1
+  const h2 t1 = as_h2((w & 0x00f000f0u) | 0x64006400u);   // 1024 + 16 c   channels 2, 3
+  const h2 t2 = as_h2((w8 & 0x000f000fu) | 0x64006400u);  //               channels 4, 5
+  const h2 t3 = as_h2((w8 & 0x00f000f0u) | 0x64006400u);  //               channels 6, 7
+  const h2 sixteenth = {(_Float16)0.0625f, (_Float16)0.0625f};
+  const h2 d0 = t0 - g.zlo;                                        // c - z, exact
+  const h2 d1 = __builtin_elementwise_fma(t1, sixteenth, -g.zhi);  // c - z, exact
+  const h2 d2 = t2 - g.zlo;
+  const h2 d3 = __builtin_elementwise_fma(t3, sixteenth, -g.zhi);
+  const h2 r0 = d0 * g.s, r1 = d1 * g.s, r2 = d2 * g.s, r3 = d3 * g.s;  // the one rounding
+  return h8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
+}
+
+template <int OUT_KIND>
+__device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int64_t row_bytes,
+                                           int64_t rows_left, int lane) {
+  const int rd_row = lane >> 3, rd_chunk = lane & 7;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int row = i * 8 + rd_row;
+    const u4 v = *reinterpret_cast<const u4 *>(slab + row * kSlabStride + rd_chunk * 16);
+    u4 *dst = reinterpret_cast<u4 *>(gbase + row * row_bytes + rd_chunk * 16);
+    if (row < rows_left) {
+      // fp32 results (the calibration forward's Y_quant) are far larger than the caches and are
+      // streamed out; binary16 results stay cacheable for the layer that consumes them
+      if (OUT_KIND == CWAC_OUT_FP32)
+        __builtin_nontemporal_store(v, dst);
+      else
+        *dst = v;
+    }
+  }
+}
+
+// Accumulator element 4*g + r of tile (a, b): channel n = bn0 + wave_n*128 + a*32 + 8*g + 4*half + r,
+// token m = bm0 + wave_m*128 + b*32 + l32.
+template <int OUT_KIND>
+__device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[4][4], int8_t *smem,
+                                            const float *s_mult, const float *s_fb, int64_t bm0, int bn0,
+                                            int wave_m, int wave_n, int lane) {
+  constexpr int ESZ = OUT_KIND == CWAC_OUT_FP16 ? 2 : 4;
+  constexpr int APS = OUT_KIND == CWAC_OUT_FP16 ? 2 : 1;  // MFMA columns per 128-byte slab row
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave = wave_m + 2 * wave_n;
+  int8_t *slab = smem + wave * kSlabBytes;
+  const int64_t row_bytes = p.ldo * ESZ;
+  const int64_t wrow0 = bm0 + wave_m * 128;
+  char *wbase = p.out + (wrow0 * p.ldo + bn0 + wave_n * 128) * ESZ;
+  const int64_t rows_left = p.m - wrow0;
+  const bool use_mult = p.mult != nullptr, use_fb = p.fbias != nullptr;
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    float mu[4][4], fb[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int cl = wave_n * 128 + a * 32 + 8 * g + 4 * half;  // channel inside the tile
+      const float4 m4 = *reinterpret_cast<const float4 *>(s_mult + cl);
+      mu[g][0] = m4.x; mu[g][1] = m4.y; mu[g][2] = m4.z; mu[g][3] = m4.w;
+      const float4 f4 = *reinterpret_cast<const float4 *>(s_fb + cl);
+      fb[g][0] = f4.x; fb[g][1] = f4.y; fb[g][2] = f4.z; fb[g][3] = f4.w;
+    }
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int row = b * 32 + l32;  // row inside the wave tile
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float u[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float v = acc[a][b][4 * g + r];
+          if (use_mult) v = v * mu[g][r];
+          if (use_fb) v = v + fb[g][r];
+          u[r] = v;
+        }
+        const int col = (a % APS) * 32 + 8 * g + 4 * half;  // channel inside the slab row
+        if (OUT_KIND == CWAC_OUT_FP16) {
+          const h2 lo = {(_Float16)u[0], (_Float16)u[1]}, hi = {(_Float16)u[2], (_Float16)u[3]};
+          *reinterpret_cast<uint2 *>(slab + row * kSlabStride + col * 2) =
+              make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+        } else {
+          *reinterpret_cast<float4 *>(slab + row * kSlabStride + col * 4) = make_float4(u[0], u[1], u[2], u[3]);
+        }
+      }
+    }
+    if (a % APS == APS - 1)
+      store_slab<OUT_KIND>(slab, wbase + (a / APS) * 128, row_bytes, rows_left, lane);
+  }
+}
+
+template <int OUT_KIND>
+__global__ __launch_bounds__(kThreads) void w4a16_kernel(const W4Params p) {
+  extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+  float *s_mult = reinterpret_cast<float *>(smem + kRing);
+  float *s_fb = reinterpret_cast<float *>(smem + kRing + 1024);
+
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int64_t bm0 = (int64_t)tile_m * 256;  // row edges: clamped loads, predicated stores
+  int bn0 = tile_n * 256;
+  if (bn0 > p.n - 256) bn0 = p.n - 256;  // channel edge: tile shifted inwards (n % 32 == 0)
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave & 1, wave_n = wave >> 1;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+
+  const float p_mult = p.mult ? p.mult[bn0 + tid] : 1.0f;
+  const float p_fb = p.fbias ? p.fbias[bn0 + tid] : 0.0f;
+
+  // ---- activations, global -> LDS: wavefront `wave` owns rows [64*wave, 64*wave + 64), 16 loads
+  // of 4 rows; lane = (row lr, slot pc) fetches 16-byte chunk pc ^ (row & 15) of its row
+  const int lr = lane >> 4, pc = lane & 15;
+  uint32_t xvo[kXLoads];
+#pragma unroll
+  for (int i = 0; i < kXLoads; ++i) {
+    const int row = wave * 64 + i * 4 + lr;
+    int64_t grow = bm0 + row;
+    if (grow > p.m - 1) grow = p.m - 1;
+    xvo[i] = (uint32_t)((grow - bm0) * p.ldx_bytes) + (uint32_t)((pc ^ (row & 15)) << 4);
+  }
+  const char *xtile = p.x + bm0 * p.ldx_bytes;
+  auto issue_x = [&](int buf, int stage, int first, int count) {
+    int8_t *sx = smem + buf * kStageBytes + wave_s * 64 * 256;
+    const char *xk = xtile + (int64_t)stage * 256;
+#pragma unroll
+    for (int i = first; i < first + count; ++i)
+      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * 1024), 16, 0, 0);
+  };
+
+  // ---- weights, global -> registers: per MFMA row block a, 2 x 16 bytes per lane and stage
+  const int kb64 = p.k / 64;
+  const u4 *wrow[4];
+  const uint32_t *szrow[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int nb = (bn0 + wave_n * 128 + a * 32) >> 5;
+    wrow[a] = p.wp + (int64_t)nb * kb64 * 64 + lane;
+    szrow[a] = p.sz + bn0 + wave_n * 128 + a * 32 + l32;
+  }
+  struct RawW {
+    u4 c[4][2];
+    uint32_t sz[4];
+  };
+  auto issue_w = [&](RawW &r, int stage) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      r.c[a][0] = wrow[a][(int64_t)(2 * stage) * 64];
+      r.c[a][1] = wrow[a][(int64_t)(2 * stage + 1) * 64];
+      r.sz[a] = szrow[a][(int64_t)stage * p.n];
+    }
+  };
+
+  // ---- LDS -> activation operand fragments
+  const int x_off = (wave_m * 128 + l32) * 256;
+  const int swz_l = l32 & 15;
+  auto read_x = [&](int buf, int kk, h8(&fx)[4]) {
+    const int8_t *base = smem + buf * kStageBytes + x_off + (((2 * kk + half) ^ swz_l) << 4);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) fx[b] = *reinterpret_cast<const h8 *>(base + b * 32 * 256);
+  };
+  auto expand_w = [&](const RawW &r, const GroupConst (&gc)[4], int kk, h8(&fw)[4]) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a) fw[a] = expand8(r.c[a][kk >> 2][kk & 3], gc[a]);
+  };
+
+  v16f acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+  auto mma = [&](const h8(&fw)[4], const h8(&fx)[4]) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[a], fx[b], acc[a][b], 0, 0, 0);
+  };
+
+  // ---- prologue.  Load order: X(0), W(0), X(1); waiting for all but the last 16 leaves X(1) in flight.
+  const int stages = p.k / kGroup;
+  RawW rawA, rawB;
+  issue_x(0, 0, 0, kXLoads);
+  issue_w(rawA, 0);
+  if (stages > 1) issue_x(1, 1, 0, kXLoads);
+  s_mult[tid] = p_mult;
+  s_fb[tid] = p_fb;
+  if (stages > 1)
+    __builtin_amdgcn_s_waitcnt(wait_imm(kXLoads, 0));
+  else
+    __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
+  __builtin_amdgcn_s_barrier();
+
+  h8 fxA[4], fxB[4], fwA[4], fwB[4];
+
+  // One stage = one group.  `cur` holds this stage's codes (landed), `nxt` receives the next
+  // stage's.  Before the MFMAs of the last k-step every wavefront has fetched its last fragments
+  // of this stage (its buffer is free for stage s + 2) and stage s + 1 has landed.
+  auto stage_body = [&](int s, int buf, RawW &cur, RawW &nxt) {
+    GroupConst gc[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) gc[a] = group_const(cur.sz[a]);
+    if (s + 1 < stages) issue_w(nxt, s + 1);
+    read_x(buf, 0, fxA);
+    expand_w(cur, gc, 0, fwA);
+#pragma unroll
+    for (int kk = 0; kk < 7; ++kk) {
+      if (kk & 1) {
+        read_x(buf, kk + 1, fxA);
+        expand_w(cur, gc, kk + 1, fwA);
+        mma(fwB, fxB);
+      } else {
+        read_x(buf, kk + 1, fxB);
+        expand_w(cur, gc, kk + 1, fwB);
+        mma(fwA, fxA);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));  // X(s + 1) and W(s + 1) have landed; fragments read
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (s + 2 < stages) issue_x(buf, s + 2, 0, kXLoads);
+    mma(fwB, fxB);  // k-step 7
+  };
+
+  int s = 0;
+  for (; s + 2 <= stages; s += 2) {
+    stage_body(s, 0, rawA, rawB);
+    stage_body(s + 1, 1, rawB, rawA);
+  }
+  if (s < stages) stage_body(s, 0, rawA, rawB);
+
+  w4_epilogue<OUT_KIND>(p, acc, smem, s_mult, s_fb, bm0, bn0, wave_m, wave_n, lane);
+}
+
+template <int OUT_KIND>
+cwac_status launch_w4(const W4Params &p, hipStream_t st) {
+  static const hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a16_kernel<OUT_KIND>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kW4Lds);
+  if (attr != hipSuccess) return CWAC_E_LAUNCH;
+  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
+  if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
+  w4a16_kernel<OUT_KIND><<<dim3((unsigned)blocks), kThreads, kW4Lds, st>>>(p);
+  return launch_status();
+}
+
+int grid_for(int64_t items) {
+  const int64_t b = ceil_div(items, kThreads);
+  return (int)(b < 1 ? 1 : (b > 65536 ? 65536 : b));
+}
+
+}  // namespace
+}  // namespace cwac
+
+using namespace cwac;
+
+extern "C" {
+
+cwac_status cwac_w4_quantize_groupwise(const float *w, int64_t ldw, int32_t n, int32_t k, uint8_t *codes,
+                                       uint16_t *scales, uint8_t *zeros, void *stream) {
+  if (!w || !codes || !scales || !zeros) return CWAC_E_NULL;
+  if (n < 1 || k < kGroup || k % kGroup != 0 || ldw < k) return CWAC_E_SHAPE;
+  if (!aligned(w, 8) || ldw % 2 != 0 || !aligned(codes, 2)) return CWAC_E_ALIGN;
+  const int groups = k / kGroup;
+  const int64_t tasks = (int64_t)n * groups;
+  const int64_t blocks = ceil_div(tasks, kThreads / 64);
+  if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
+  w4_quantize_kernel<<<dim3((unsigned)blocks), kThreads, 0, as_stream(stream)>>>(w, ldw, n, groups, codes,
+                                                                                 scales, zeros);
+  return launch_status();
+}
+
+size_t cwac_w4_packed_w_bytes(int32_t n, int32_t k) {
+  if (n < 1 || k < 1) return 0;
+  return (size_t)n * (size_t)k / 2;
+}
+
+cwac_status cwac_w4_pack(const uint8_t *codes, const uint16_t *scales, const uint8_t *zeros, int32_t n,
+                         int32_t k, void *packed_w, uint32_t *packed_sz, void *stream) {
+  if (!codes || !scales || !zeros || !packed_w || !packed_sz) return CWAC_E_NULL;
+  if (n < 32 || n % 32 != 0 || k < kGroup || k % kGroup != 0) return CWAC_E_SHAPE;
+  if (!aligned(codes, 8) || !aligned(packed_w, 16) || !aligned(packed_sz, 4)) return CWAC_E_ALIGN;
+  hipStream_t st = as_stream(stream);
+  w4_pack_kernel<<<grid_for((int64_t)n * (k / 8)), kThreads, 0, st>>>(codes, n, k,
+                                                                      static_cast<uint32_t *>(packed_w));
+  if (launch_status() != CWAC_OK) return CWAC_E_LAUNCH;
+  w4_pack_sz_kernel<<<grid_for((int64_t)n * (k / kGroup)), kThreads, 0, st>>>(scales, zeros, n, k / kGroup,
+                                                                              packed_sz);
+  return launch_status();
+}
+
+cwac_status cwac_fold_weight_only(const float *alpha, const float *beta, const float *bias, int32_t n_out,
+                                  float *mult, float *fbias, void *stream) {
+  if (!mult || !fbias) return CWAC_E_NULL;
+  if ((alpha == nullptr) != (beta == nullptr)) return CWAC_E_MODE;
+  if (n_out < 1) return CWAC_E_SHAPE;
+  fold_weight_only_kernel<<<grid_for(n_out), kThreads, 0, as_stream(stream)>>>(alpha, beta, bias, n_out, mult,
+                                                                                fbias);
+  return launch_status();
+}
+
+cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const void *packed_w,
+                                       const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
+                                       const float *mult, const float *fbias, int32_t out_kind, void *out,
+                                       int64_t ldo, void *stream) {
+  if (!x || !packed_w || !packed_sz || !out) return CWAC_E_NULL;
+  if (out_kind != CWAC_OUT_FP16 && out_kind != CWAC_OUT_FP32) return CWAC_E_MODE;
+  if (m < 1 || n < 256 || n % 32 != 0 || k < kGroup || k > 32768 || k % kGroup != 0 || ldx < k || ldo < n)
+    return CWAC_E_SHAPE;
+  const int64_t esz = out_kind == CWAC_OUT_FP16 ? 2 : 4;
+  if (!aligned(x, 16) || ldx % 8 != 0 || !aligned(packed_w, 16) || !aligned(packed_sz, 4) ||
+      !aligned(out, 16) || (ldo * esz) % 16 != 0)
+    return CWAC_E_ALIGN;
+  if (ceil_div(m, 256) > 0x7fffff) return CWAC_E_SHAPE;
+  // per-lane activation offsets inside a tile are 32-bit
+  if (255 * ldx * 2 + 32768 * 2 > 0xffffffffLL) return CWAC_E_SHAPE;
+  W4Params p;
+  p.x = reinterpret_cast<const char *>(x);
+  p.ldx_bytes = ldx * 2;
+  p.wp = static_cast<const u4 *>(packed_w);
+  p.sz = packed_sz;
+  p.m = m;
+  p.n = n;
+  p.k = k;
+  p.mult = mult;
+  p.fbias = fbias;
+  p.out = static_cast<char *>(out);
+  p.ldo = ldo;
+  p.tiles_m = (int)ceil_div(m, 256);
+  p.tiles_n = (int)ceil_div(n, 256);
+  return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16>(p, as_stream(stream))
+                                   : launch_w4<CWAC_OUT_FP32>(p, as_stream(stream));
+}
+
+}  // extern "C"
