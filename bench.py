@@ -24,6 +24,7 @@ if ROOT not in sys.path:
 
 METRIC = "W8A8 GEMM+CWAC epilogue TOPS (% int8 MFMA peak); calib stats GB/s (% HBM)"
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8, published
+FP16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X dense fp16, published
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --probe`,
 # scaled by what the same counters read for a plain 1 GiB copy (x1.997, x1.000); mean over the
@@ -335,6 +336,130 @@ def mfma_ceiling(P, torch, layers, iters: int = 20000, reps: int = 4):
     return out
 
 
+def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: int):
+    """The paper's LLM setting on the same layer shapes: INT4 group-128 weights, fp16 activations,
+    CWAC in the epilogue.  A step = calibration forward (fp32 out) -> statistics -> fit -> fold ->
+    compensated fp16 forward, for every layer; the fp16 forward is the kernel the roofline is for."""
+    import numpy as np
+    wl = synth.WORKLOADS[cfg]
+    m = wl.m
+    layers = []
+    for li, ly in enumerate(wl.layers):
+        L = LayerState()
+        L.n, L.k = ly.n, ly.k
+        w = synth.weights(wl, li, device=dev)[0]
+        L.x = synth.activations(wl, li, m, device=dev).to(torch.float16)
+        L.xcal = synth.activations(wl, li, m, calibration=True, device=dev).to(torch.float16)
+        L.y_full = L.xcal.float() @ w.t()                      # upstream full-precision layer
+        L.wh = w.to(torch.float16)                             # comparator only: dense fp16 weights
+        codes = torch.empty(ly.n, ly.k, dtype=torch.uint8, device=dev)
+        sc = torch.empty(ly.n, ly.k // 128, dtype=torch.float16, device=dev)
+        ze = torch.empty(ly.n, ly.k // 128, dtype=torch.uint8, device=dev)
+        P.cwac_w4_quantize_groupwise(w, codes, sc, ze)
+        L.pw = torch.empty(P.cwac_w4_packed_w_bytes(ly.n, ly.k), dtype=torch.uint8, device=dev)
+        L.psz = torch.empty((ly.k // 128) * ly.n, dtype=torch.int32, device=dev)
+        P.cwac_w4_pack(codes, sc, ze, L.pw, L.psz)
+        f32 = dict(dtype=torch.float32, device=dev)
+        L.alpha, L.beta = torch.empty(ly.n, **f32), torch.empty(ly.n, **f32)
+        L.mult, L.fbias = torch.empty(ly.n, **f32), torch.empty(ly.n, **f32)
+        L.stats = torch.empty(P.cwac_stats_bytes(ly.n) // 8 + 2, dtype=torch.float64, device=dev)
+        L.ws = torch.empty(P.cwac_calibrate_stats_workspace(m, ly.n), dtype=torch.uint8, device=dev)
+        del w, codes, sc, ze
+        layers.append(L)
+    n_max = max(L.n for L in layers)
+    yq_buf = torch.empty(m * n_max, dtype=torch.float32, device=dev)
+    out_buf = torch.empty(m * n_max, dtype=torch.float16, device=dev)
+    for L in layers:
+        L.yq = yq_buf[:m * L.n].view(m, L.n)
+        L.out = out_buf[:m * L.n].view(m, L.n)
+
+    def step(ev=None):
+        for L in layers:
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if ev is not None else None
+            if e:
+                e[0].record()
+            P.qlinear_w4a16_cwac_forward(L.xcal, L.pw, L.psz, L.n, None, None, L.yq)
+            if e:
+                e[1].record()
+            P.cwac_stats_reset(L.stats, L.n)
+            P.cwac_calibrate_stats(L.y_full, L.yq, L.stats, L.ws)
+            P.cwac_solve(L.stats, L.n, L.alpha, L.beta)
+            P.cwac_fold_weight_only(L.alpha, L.beta, None, L.mult, L.fbias)
+            if e:
+                e[2].record()
+            P.qlinear_w4a16_cwac_forward(L.x, L.pw, L.psz, L.n, L.mult, L.fbias, L.out)
+            if e:
+                e[3].record()
+                ev.append(e)
+
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    ev = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(ev)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / steps
+    fwd_flops = sum(2.0 * m * L.n * L.k for L in layers)
+    t_cal = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    t_fit = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    t_fwd = sum(e[2].elapsed_time(e[3]) for e in ev) / steps
+    # comparator: the vendor library's dense fp16 GEMM on the same activations and un-quantized
+    # fp16 weights (no 4-bit expansion, no epilogue vectors, 4x the weight bytes)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for L in layers:
+        torch.matmul(L.x, L.wh.t(), out=L.out)
+    e0.record()
+    for _ in range(steps):
+        for L in layers:
+            torch.matmul(L.x, L.wh.t(), out=L.out)
+    e1.record()
+    torch.cuda.synchronize()
+    t_dense = e0.elapsed_time(e1) / steps
+    tf = fwd_flops / (t_fwd * 1e-3) / 1e12
+    res = {
+        "workload": f"config {wl.cfg} layer shapes, INT4 group-128 asymmetric weights, fp16 "
+                    f"activations, M={m} tokens, {m} calibration rows per step",
+        "dtype": "f16", "ms_per_step": round(t_step * 1e3, 4),
+        "value": round(2.0 * fwd_flops / t_step / 1e12, 2), "unit": "TFLOP/s",
+        "roofline": {"bound": "mfma", "achieved": round(tf / 1e3, 4),
+                     "peak": FP16_MFMA_PEAK_TFLOPS / 1e3, "unit": "PFLOP/s",
+                     "frac": round(tf / FP16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "w4a16_kernel (fp16 out, fused CWAC epilogue)",
+                     "launches_per_step": len(layers), "avg_launch_ms": round(t_fwd / len(layers), 4),
+                     "flops_per_step": fwd_flops},
+        "phases_ms": {"calibration_forward_fp32": round(t_cal, 4),
+                      "statistics_solve_fold": round(t_fit, 4), "forward_fp16": round(t_fwd, 4)},
+        "calibration_forward_tflops": round(fwd_flops / (t_cal * 1e-3) / 1e12, 2),
+        "dense_fp16_library_gemm_tflops": round(fwd_flops / (t_dense * 1e-3) / 1e12, 2),
+    }
+    if cpu_rows > 0:
+        from oracle import cwac_oracle as orc
+        from oracle import w4a16_oracle as w4
+        flops, secs = 0.0, 0.0
+        for li, ly in enumerate(wl.layers):
+            w = synth.weights(wl, li)[0].numpy()
+            x16 = synth.activations(wl, li, cpu_rows).numpy().astype(np.float16)
+            xc16 = synth.activations(wl, li, cpu_rows, calibration=True).numpy().astype(np.float16)
+            y_full = (xc16.astype(np.float32) @ w.T).astype(np.float32)        # upstream
+            codes, sc, ze = w4.quantize_groupwise(w)                             # setup
+            t0 = time.perf_counter()                                             # the step
+            wd = w4.dequant(codes, sc, ze)
+            acc_c, _ = w4.product(xc16, wd)
+            alpha, beta = orc.fit(y_full, acc_c.astype(np.float32))
+            mult, fb = w4.fold(alpha, beta, None, ly.n)
+            acc, _ = w4.product(x16, wd)
+            w4.folded_real(acc, mult, fb)
+            secs += time.perf_counter() - t0
+            flops += 2.0 * 2.0 * cpu_rows * ly.n * ly.k
+        res["cpu_baseline"] = {"value": round(flops / secs / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": orc.get_threads(), "kind": "oracle",
+                               "sample": f"the same step on {cpu_rows} inference rows and {cpu_rows} "
+                                         f"calibration rows of every layer ({secs:.1f} s of oracle time)"}
+    return res
+
+
 def cpu_baseline(synth, cfg: int, sample_rows: int):
     """The oracle, as it stands, timed on this host on a bounded row sample of the same step."""
     import numpy as np
@@ -391,6 +516,8 @@ def main():
                     "one batch = the workload's token count)")
     ap.add_argument("--cpu-sample-rows", type=int, default=1536)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-weight-only", action="store_true",
+                    help="skip the INT4 weight-only section (reported for the LLM workload only)")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -498,6 +625,12 @@ def main():
             "sample": f"the same step on {args.cpu_sample_rows} inference rows and "
                       f"{args.cpu_sample_rows} calibration rows of every layer "
                       f"({secs:.1f} s of oracle time)"}
+    if args.config == 5 and not args.no_weight_only:
+        del layers
+        torch.cuda.empty_cache()
+        result["weight_only_int4"] = weight_only_int4(
+            P, synth, torch, args.config, dev, args.steps,
+            0 if args.no_cpu_baseline else max(32, args.cpu_sample_rows // 8))
     print(json.dumps(result))
 
 

@@ -350,8 +350,8 @@ cwac_status cwac_fold_weight_only(const float *alpha, const float *beta, const f
  * dequantized in registers (one binary16 rounding), binary16 x binary16 -> fp32 on
  * the matrix cores.  Per output element:
  *   acc = sum_k x[m, k] * Wd[n, k]      fp32 accumulation (order unspecified)
- *   u   = acc * mult[n]                 only if mult != NULL
- *   u   = u + fbias[n]                  only if fbias != NULL     (single fp32 operations)
+ *   u   = acc * mult[n]                 mult == NULL: multiplier 1
+ *   u   = u + fbias[n]                  fbias == NULL: constant +0  (single fp32 operations)
  *   CWAC_OUT_FP16: out = RN16(u);   CWAC_OUT_FP32: out = u  (calibration forward: Y_quant)
  *   x          device binary16 [m, k], ldx; 16-byte aligned, ldx % 8 == 0
  *   packed_w, packed_sz   as produced by cwac_w4_pack

@@ -212,7 +212,9 @@ void w4o_folded_real(const double *acc, int64_t rows, int64_t n, const float *mu
 }
 
 /* The engine's epilogue applied to an fp32 accumulator value, as defined:
- * u = fl32(fl32(acc * mult[n]) + fbias[n]); out32 = u, out16 = RN16(u).
+ * u = fl32(fl32(acc * mult[n]) + fbias[n]); out32 = u, out16 = RN16(u); a
+ * missing multiplier is 1 and a missing constant is +0 (both operations are
+ * always carried out, so a result of -0 becomes +0).
  * Used where the accumulator itself is exact in fp32 (integer-valued cases),
  * which makes the whole layer output reproducible bit for bit. */
 void w4o_epilogue_f32(const float *acc, int64_t rows, int64_t n, const float *mult,

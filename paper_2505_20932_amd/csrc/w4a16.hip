@@ -2,8 +2,12 @@
 // asymmetric 4-bit weights, group size 128, binary16 activations; compensation of Sec. 3.3
 // folded into the epilogue as in Sec. 3.4), plus its quantizer, weight re-ordering and fold.
 //
-// Forward kernel: 256 x 256 output tile, four wavefronts (2 x 2, each 128 x 128 = 4 x 4 tiles of
-// v_mfma_f32_32x32x16_f16, 256 fp32 accumulators per lane), one workgroup per compute unit.
+// Forward kernel: 256 x 256 output tile, eight wavefronts (2 x 4, each 128 tokens x 64 channels =
+// 4 x 2 tiles of v_mfma_f32_32x32x16_f16, 128 fp32 accumulators per lane), one workgroup per
+// compute unit, two wavefronts per SIMD.  Measured on this device with register-resident operands:
+// beside one such MFMA (32 cycles of the matrix pipe) a SIMD issues about five vector ALU
+// instructions per wavefront for free when two wavefronts share it, but only about three when one
+// wavefront has it alone - and the weight expansion needs five per MFMA.
 //   * Activation panels go global -> LDS directly (global_load_lds_dwordx4); one K stage is one
 //     quantization group (128 channels = 256 bytes per row, 64 KiB per stage, two stages).  The
 //     bank swizzle (16-byte chunk position XOR row & 15) is applied on the global-address side.
@@ -27,6 +31,8 @@ typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) u4 GU4;        // in global memory (not a generic address)
+typedef __attribute__((address_space(1))) uint32_t GU32;
 
 #define CWAC_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define CWAC_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -144,13 +150,16 @@ struct W4Params {
   int tiles_m, tiles_n;
 };
 
-constexpr int kStageBytes = 256 * 256;  // 256 rows x 128 binary16
+constexpr int kFwdThreads = 512;         // 8 wavefronts: 2 per SIMD
+constexpr int kTA = 2, kTB = 4;          // MFMA tiles per wavefront: 64 channels x 128 tokens
+constexpr int kStageBytes = 256 * 256;   // 256 rows x 128 binary16
 constexpr int kRing = 2 * kStageBytes;
-constexpr int kW4Lds = kRing + 2 * 256 * 4;
-constexpr int kXLoads = 16;  // global_load_lds per wavefront and stage (4 rows x 256 bytes each)
-
+constexpr int kXLoads = 8;  // global_load_lds per wavefront and stage (4 rows x 256 bytes each)
 constexpr int kSlabStride = 144;
 constexpr int kSlabBytes = 128 * kSlabStride;
+constexpr int kParams = 8 * kSlabBytes;  // epilogue parameters sit behind the ring and the slabs
+constexpr int kW4Lds = kParams + 2 * 256 * 4;
+static_assert(kParams >= kRing && kW4Lds <= 160 * 1024, "LDS budget of one compute unit");
 
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 
@@ -203,10 +212,12 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
   }
 }
 
-// Accumulator element 4*g + r of tile (a, b): channel n = bn0 + wave_n*128 + a*32 + 8*g + 4*half + r,
-// token m = bm0 + wave_m*128 + b*32 + l32.
+// Accumulator element 4*g + r of tile (a, b): channel n = bn0 + wave_n*64 + a*32 + 8*g + 4*half + r,
+// token m = bm0 + wave_m*128 + b*32 + l32.  Each wavefront transposes its 128 rows x 128 bytes
+// through a private LDS slab (row stride 144 bytes) and writes whole 128-byte lines: binary16
+// output = all 64 channels of the wave tile in one slab, fp32 output = one slab per MFMA column.
 template <int OUT_KIND>
-__device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[4][4], int8_t *smem,
+__device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[kTA][kTB], int8_t *smem,
                                             const float *s_mult, const float *s_fb, int64_t bm0, int bn0,
                                             int wave_m, int wave_n, int lane) {
   constexpr int ESZ = OUT_KIND == CWAC_OUT_FP16 ? 2 : 4;
@@ -216,32 +227,29 @@ __device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[4][4]
   int8_t *slab = smem + wave * kSlabBytes;
   const int64_t row_bytes = p.ldo * ESZ;
   const int64_t wrow0 = bm0 + wave_m * 128;
-  char *wbase = p.out + (wrow0 * p.ldo + bn0 + wave_n * 128) * ESZ;
+  char *wbase = p.out + (wrow0 * p.ldo + bn0 + wave_n * 64) * ESZ;
   const int64_t rows_left = p.m - wrow0;
-  const bool use_mult = p.mult != nullptr, use_fb = p.fbias != nullptr;
 #pragma unroll
-  for (int a = 0; a < 4; ++a) {
+  for (int a = 0; a < kTA; ++a) {
     float mu[4][4], fb[4][4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const int cl = wave_n * 128 + a * 32 + 8 * g + 4 * half;  // channel inside the tile
+      const int cl = wave_n * 64 + a * 32 + 8 * g + 4 * half;  // channel inside the tile
       const float4 m4 = *reinterpret_cast<const float4 *>(s_mult + cl);
       mu[g][0] = m4.x; mu[g][1] = m4.y; mu[g][2] = m4.z; mu[g][3] = m4.w;
       const float4 f4 = *reinterpret_cast<const float4 *>(s_fb + cl);
       fb[g][0] = f4.x; fb[g][1] = f4.y; fb[g][2] = f4.z; fb[g][3] = f4.w;
     }
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < kTB; ++b) {
       const int row = b * 32 + l32;  // row inside the wave tile
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         float u[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float v = acc[a][b][4 * g + r];
-          if (use_mult) v = v * mu[g][r];
-          if (use_fb) v = v + fb[g][r];
-          u[r] = v;
+          const float v = acc[a][b][4 * g + r] * mu[g][r];  // mult == NULL: 1
+          u[r] = v + fb[g][r];                              // fbias == NULL: +0
         }
         const int col = (a % APS) * 32 + 8 * g + 4 * half;  // channel inside the slab row
         if (OUT_KIND == CWAC_OUT_FP16) {
@@ -259,10 +267,10 @@ __device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[4][4]
 }
 
 template <int OUT_KIND>
-__global__ __launch_bounds__(kThreads) void w4a16_kernel(const W4Params p) {
+__global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
-  float *s_mult = reinterpret_cast<float *>(smem + kRing);
-  float *s_fb = reinterpret_cast<float *>(smem + kRing + 1024);
+  float *s_mult = reinterpret_cast<float *>(smem + kParams);
+  float *s_fb = reinterpret_cast<float *>(smem + kParams + 1024);
 
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
@@ -272,112 +280,141 @@ __global__ __launch_bounds__(kThreads) void w4a16_kernel(const W4Params p) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave & 1, wave_n = wave >> 1;
+  const int wave_m = wave & 1, wave_n = wave >> 1;  // 2 x 4 wavefronts of 128 tokens x 64 channels
   const int l32 = lane & 31, half = lane >> 5;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
 
-  const float p_mult = p.mult ? p.mult[bn0 + tid] : 1.0f;
-  const float p_fb = p.fbias ? p.fbias[bn0 + tid] : 0.0f;
+  float p_mult = 1.0f, p_fb = 0.0f;
+  if (tid < 256) {
+    if (p.mult) p_mult = p.mult[bn0 + tid];
+    if (p.fbias) p_fb = p.fbias[bn0 + tid];
+  }
 
-  // ---- activations, global -> LDS: wavefront `wave` owns rows [64*wave, 64*wave + 64), 16 loads
+  // ---- activations, global -> LDS: wavefront `wave` owns rows [32*wave, 32*wave + 32), 8 loads
   // of 4 rows; lane = (row lr, slot pc) fetches 16-byte chunk pc ^ (row & 15) of its row
   const int lr = lane >> 4, pc = lane & 15;
   uint32_t xvo[kXLoads];
 #pragma unroll
   for (int i = 0; i < kXLoads; ++i) {
-    const int row = wave * 64 + i * 4 + lr;
+    const int row = wave * 32 + i * 4 + lr;
     int64_t grow = bm0 + row;
     if (grow > p.m - 1) grow = p.m - 1;
     xvo[i] = (uint32_t)((grow - bm0) * p.ldx_bytes) + (uint32_t)((pc ^ (row & 15)) << 4);
   }
   const char *xtile = p.x + bm0 * p.ldx_bytes;
-  auto issue_x = [&](int buf, int stage, int first, int count) {
-    int8_t *sx = smem + buf * kStageBytes + wave_s * 64 * 256;
-    const char *xk = xtile + (int64_t)stage * 256;
+  // a wave-uniform 64-bit address that the compiler must keep in scalar registers, so that loads
+  // take the (scalar base + 32-bit lane offset) form and need no vector address arithmetic
+  auto uniform = [](const char *q) {
+    const uint64_t v = reinterpret_cast<uint64_t>(q);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+  };
+  auto issue_x = [&](int buf, int stage) {
+    int8_t *sx = smem + buf * kStageBytes + wave_s * 32 * 256;
+    const char *xk = uniform(xtile + (int64_t)stage * 256);
 #pragma unroll
-    for (int i = first; i < first + count; ++i)
+    for (int i = 0; i < kXLoads; ++i)
       __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * 1024), 16, 0, 0);
   };
 
   // ---- weights, global -> registers: per MFMA row block a, 2 x 16 bytes per lane and stage
   const int kb64 = p.k / 64;
-  const u4 *wrow[4];
-  const uint32_t *szrow[4];
-#pragma unroll
-  for (int a = 0; a < 4; ++a) {
-    const int nb = (bn0 + wave_n * 128 + a * 32) >> 5;
-    wrow[a] = p.wp + (int64_t)nb * kb64 * 64 + lane;
-    szrow[a] = p.sz + bn0 + wave_n * 128 + a * 32 + l32;
-  }
+  const int n0w = bn0 + wave_s / 2 * 64;  // first channel of this wavefront
+  const uint32_t w_lane = (uint32_t)lane * 16u, sz_lane = (uint32_t)l32 * 4u;
   struct RawW {
-    u4 c[4][2];
-    uint32_t sz[4];
+    u4 c[kTA][2];
+    uint32_t sz[kTA];
   };
   auto issue_w = [&](RawW &r, int stage) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-      r.c[a][0] = wrow[a][(int64_t)(2 * stage) * 64];
-      r.c[a][1] = wrow[a][(int64_t)(2 * stage + 1) * 64];
-      r.sz[a] = szrow[a][(int64_t)stage * p.n];
+    for (int a = 0; a < kTA; ++a) {
+      const int nb = (n0w + a * 32) >> 5;
+      const char *wb = uniform(reinterpret_cast<const char *>(p.wp) +
+                               ((int64_t)nb * kb64 + 2 * stage) * 1024);
+      r.c[a][0] = *reinterpret_cast<const GU4 *>(CWAC_GLOBAL_PTR(wb + w_lane));
+      r.c[a][1] = *reinterpret_cast<const GU4 *>(CWAC_GLOBAL_PTR(wb + 1024 + w_lane));
+      const char *sb = uniform(reinterpret_cast<const char *>(p.sz) +
+                               ((int64_t)stage * p.n + n0w + a * 32) * 4);
+      r.sz[a] = *reinterpret_cast<const GU32 *>(CWAC_GLOBAL_PTR(sb + sz_lane));
     }
   };
+  constexpr int kWLoads = 3 * kTA;
 
   // ---- LDS -> activation operand fragments
   const int x_off = (wave_m * 128 + l32) * 256;
   const int swz_l = l32 & 15;
-  auto read_x = [&](int buf, int kk, h8(&fx)[4]) {
+  auto read_x = [&](int buf, int kk, h8(&fx)[kTB]) {
     const int8_t *base = smem + buf * kStageBytes + x_off + (((2 * kk + half) ^ swz_l) << 4);
 #pragma unroll
-    for (int b = 0; b < 4; ++b) fx[b] = *reinterpret_cast<const h8 *>(base + b * 32 * 256);
+    for (int b = 0; b < kTB; ++b) fx[b] = *reinterpret_cast<const h8 *>(base + b * 32 * 256);
   };
-  auto expand_w = [&](const RawW &r, const GroupConst (&gc)[4], int kk, h8(&fw)[4]) {
+  auto expand_w = [&](const RawW &r, const GroupConst (&gc)[kTA], int kk, h8(&fw)[kTA]) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a) fw[a] = expand8(r.c[a][kk >> 2][kk & 3], gc[a]);
+    for (int a = 0; a < kTA; ++a) fw[a] = expand8(r.c[a][kk >> 2][kk & 3], gc[a]);
   };
 
-  v16f acc[4][4];
+  v16f acc[kTA][kTB];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < kTA; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
+    for (int b = 0; b < kTB; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
-  auto mma = [&](const h8(&fw)[4], const h8(&fx)[4]) {
+  auto mma = [&](const h8(&fw)[kTA], const h8(&fx)[kTB]) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < kTA; ++a)
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
+      for (int b = 0; b < kTB; ++b)
         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[a], fx[b], acc[a][b], 0, 0, 0);
   };
+  // Scheduler hint for one k-step: first the LDS reads of the next step's activation fragments,
+  // then 8 MFMAs; the expansion of the next step's weight fragments (about
+  // 35 vector ALU operations) spread evenly behind all of them; `vmem` loads spread likewise.
+  auto interleave = [&](int vmem) {
+    __builtin_amdgcn_sched_group_barrier(0x100, kTB, 0);  // the next step's LDS reads go first
+#pragma unroll
+    for (int i = 0; i < kTA * kTB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < vmem) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // one k-step per scheduling region
+  };
 
-  // ---- prologue.  Load order: X(0), W(0), X(1); waiting for all but the last 16 leaves X(1) in flight.
+  // ---- prologue.  Load order: X(0), W(0), X(1); waiting for all but the last 8 leaves X(1) in flight.
   const int stages = p.k / kGroup;
   RawW rawA, rawB;
-  issue_x(0, 0, 0, kXLoads);
+  GroupConst gc[kTA];
+  h8 fxA[kTB], fxB[kTB], fwA[kTA], fwB[kTA];
+  issue_x(0, 0);
   issue_w(rawA, 0);
-  if (stages > 1) issue_x(1, 1, 0, kXLoads);
-  s_mult[tid] = p_mult;
-  s_fb[tid] = p_fb;
+  if (stages > 1) issue_x(1, 1);
+  if (tid < 256) {
+    s_mult[tid] = p_mult;
+    s_fb[tid] = p_fb;
+  }
   if (stages > 1)
     __builtin_amdgcn_s_waitcnt(wait_imm(kXLoads, 0));
   else
     __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));
   __builtin_amdgcn_s_barrier();
-
-  h8 fxA[4], fxB[4], fwA[4], fwB[4];
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int a = 0; a < kTA; ++a) gc[a] = group_const(rawA.sz[a]);
+  read_x(0, 0, fxA);
+  expand_w(rawA, gc, 0, fwA);
 
   // One stage = one group.  `cur` holds this stage's codes (landed), `nxt` receives the next
-  // stage's.  Before the MFMAs of the last k-step every wavefront has fetched its last fragments
-  // of this stage (its buffer is free for stage s + 2) and stage s + 1 has landed.
+  // stage's during k-step 0.  Every k-step fetches and expands the fragments of the following
+  // one while its own MFMAs run.  Before the MFMAs of the last k-step every wavefront has fetched
+  // its last fragments of this stage (its buffer is free for stage s + 2) and stage s + 1 has
+  // landed; that k-step prepares the first fragments of the next stage.
   auto stage_body = [&](int s, int buf, RawW &cur, RawW &nxt) {
-    GroupConst gc[4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a) gc[a] = group_const(cur.sz[a]);
-    if (s + 1 < stages) issue_w(nxt, s + 1);
-    read_x(buf, 0, fxA);
-    expand_w(cur, gc, 0, fwA);
+    const bool more = s + 1 < stages;
 #pragma unroll
     for (int kk = 0; kk < 7; ++kk) {
+      if (kk == 0 && more) issue_w(nxt, s + 1);
       if (kk & 1) {
         read_x(buf, kk + 1, fxA);
         expand_w(cur, gc, kk + 1, fwA);
@@ -387,13 +424,20 @@ __global__ __launch_bounds__(kThreads) void w4a16_kernel(const W4Params p) {
         expand_w(cur, gc, kk + 1, fwB);
         mma(fwA, fxA);
       }
+      interleave(kk == 0 ? kWLoads : 0);
     }
-    __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(wait_imm(0, 0));  // X(s + 1) and W(s + 1) have landed; fragments read
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    if (s + 2 < stages) issue_x(buf, s + 2, 0, kXLoads);
+    if (s + 2 < stages) issue_x(buf, s + 2);
+    if (more) {
+#pragma unroll
+      for (int a = 0; a < kTA; ++a) gc[a] = group_const(nxt.sz[a]);  // this stage's are dead by now
+      read_x(buf ^ 1, 0, fxA);
+      expand_w(nxt, gc, 0, fwA);
+    }
     mma(fwB, fxB);  // k-step 7
+    interleave(kXLoads);
   };
 
   int s = 0;
@@ -403,6 +447,7 @@ __global__ __launch_bounds__(kThreads) void w4a16_kernel(const W4Params p) {
   }
   if (s < stages) stage_body(s, 0, rawA, rawB);
 
+  // every wavefront is past its last LDS read of the ring (the barrier of the last stage)
   w4_epilogue<OUT_KIND>(p, acc, smem, s_mult, s_fb, bm0, bn0, wave_m, wave_n, lane);
 }
 
@@ -414,7 +459,7 @@ cwac_status launch_w4(const W4Params &p, hipStream_t st) {
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  w4a16_kernel<OUT_KIND><<<dim3((unsigned)blocks), kThreads, kW4Lds, st>>>(p);
+  w4a16_kernel<OUT_KIND><<<dim3((unsigned)blocks), kFwdThreads, kW4Lds, st>>>(p);
   return launch_status();
 }
 

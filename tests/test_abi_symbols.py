@@ -121,6 +121,33 @@ def test_argument_errors_of_the_widened_entry_points(lib):
     assert lib.cwac_mfma_probe(a, 0, 1, a, null) == -2
 
 
+def test_argument_errors_of_the_weight_only_entry_points(lib):
+    null = None
+    a = C.c_void_p(4096)
+    q = lib.cwac_w4_quantize_groupwise
+    assert q(null, 128, 4, 128, a, a, a, null) == -1
+    assert q(a, 192, 4, 192, a, a, a, null) == -2            # k % 128
+    assert q(a, 64, 4, 128, a, a, a, null) == -2             # ldw < k
+    assert q(C.c_void_p(4100), 128, 4, 128, a, a, a, null) == -3
+    pk = lib.cwac_w4_pack
+    assert pk(a, a, a, 48, 128, a, a, null) == -2            # n % 32
+    assert pk(a, a, a, 64, 128, null, a, null) == -1
+    assert pk(a, a, a, 64, 128, C.c_void_p(4104), a, null) == -3
+    assert P.cwac_w4_packed_w_bytes(4096, 11008) == 4096 * 11008 // 2
+    fo = lib.cwac_fold_weight_only
+    assert fo(a, null, null, 8, a, a, null) == -4            # alpha without beta
+    assert fo(null, null, null, 8, null, a, null) == -1
+    f = lib.qlinear_w4a16_cwac_forward
+    assert f(null, 128, a, a, 1, 256, 128, null, null, 3, a, 256, null) == -1
+    assert f(a, 128, a, a, 1, 128, 128, null, null, 3, a, 128, null) == -2     # n < 256
+    assert f(a, 128, a, a, 1, 272, 128, null, null, 3, a, 272, null) == -2     # n % 32
+    assert f(a, 192, a, a, 1, 256, 192, null, null, 3, a, 256, null) == -2     # k % 128
+    assert f(a, 128, a, a, 1, 256, 128, null, null, 0, a, 256, null) == -4     # int8 output: not this layer
+    assert f(a, 132, a, a, 2, 256, 128, null, null, 3, a, 256, null) == -3     # ldx % 8
+    assert f(a, 128, a, a, 2, 256, 128, null, null, 3, a, 260, null) == -3     # output pitch not 16-byte
+    assert f(a, 128, a, a, 0, 256, 128, null, null, 3, a, 256, null) == -2     # no rows
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
