@@ -15,7 +15,12 @@
 //     offset add of Eq. 10 costs nothing, and rounding uses one fp32 add of 1.5 * 2^23, which
 //     rounds half to even exactly like rint for the clamped (|x| < 2^22) values it sees.
 //
-// Requires m >= 256, n >= 256, k % BK == 0.  Edge tiles are shifted inwards to overlap their
+//   * A second shape of the same kernel for layers with a short K loop (ViT / Swin linears): a
+//     128-token x 256-channel tile (wave tile 64 x 128), 64-byte K steps, three stages, at most 256
+//     registers per lane, so that TWO workgroups share a compute unit and one's prologue and
+//     epilogue run under the other's main loop.
+//
+// Requires m >= 256, n >= 256, k % 128 == 0.  Edge tiles are shifted inwards to overlap their
 // neighbours (identical values are written twice) instead of being predicated.
 #include <stdlib.h>
 #include <string.h>
@@ -35,9 +40,10 @@ constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
   return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
 }
 
-template <int BK, int NSTAGE, int NCHUNK>
+template <int BM_, int BK, int NSTAGE, int NCHUNK>
 struct FastCfg {
-  static constexpr int BM = 256, BN = 256;
+  static constexpr int BM = BM_, BN = 256;
+  static constexpr int TB = BM / 64;  // 32-token MFMA tiles per wavefront (2 wavefronts along m)
   static constexpr int KK = BK / 32;  // MFMA k-steps per stage
   static constexpr int X_BYTES = BM * BK, W_BYTES = BN * BK, STAGE = X_BYTES + W_BYTES;
   static constexpr int RING = NSTAGE * STAGE;
@@ -47,13 +53,14 @@ struct FastCfg {
   // row half of the tile hands its sums to the upper one ([2 wave columns][4][kStats][32] fp64)
   static constexpr int STATS_EXCH = RING + PARAM_BYTES + 2 * 256 * 4;
   static constexpr int STATS_LDS_BYTES = STATS_EXCH + 2 * 4 * kStats * 32 * 8;
-  static_assert(RING >= 4 * 32768, "statistics epilogue: 32 KiB of the ring per wavefront");
-  static_assert(STATS_LDS_BYTES <= 160 * 1024, "LDS budget of one compute unit");
   static constexpr int CPR = BK / 16;        // 16-byte chunks per row
   static constexpr int RPL = 64 / CPR;       // rows covered by one wavefront load
-  static constexpr int LOADS = 64 / RPL;     // loads per wavefront, panel and stage
-  static constexpr int LPS = 2 * LOADS;      // loads per wavefront and stage
+  static constexpr int XROWS = BM / 4;       // activation rows each wavefront loads per stage
+  static constexpr int LOADS_X = XROWS / RPL;  // loads per wavefront and stage, activation panel
+  static constexpr int LOADS_W = 64 / RPL;     // ... weight panel (64 rows per wavefront)
+  static constexpr int LPS = LOADS_X + LOADS_W;  // loads per wavefront and stage
   static constexpr int CHUNK = LPS / NCHUNK;  // loads issued together, once per k-step
+  static_assert(BM == 256 || BM == 128, "token rows per tile");
   static_assert(BK == 64 || BK == 128, "K step");
   static_assert(NCHUNK >= 1 && NCHUNK <= KK && LPS % NCHUNK == 0, "load chunks per stage");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one compute unit");
@@ -83,13 +90,12 @@ __device__ __forceinline__ uint32_t pack4(int b0, int b1, int b2, int b3) {
 // fp32 / int32: one slab per 32-channel MFMA column.
 // Non-VEC path (unaligned output): element-wise stores.
 constexpr int kSlabStride = 144;
-constexpr int kSlabBytes = 128 * kSlabStride;
 
-template <int OUT_KIND>
+template <int OUT_KIND, int ROWS>
 __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int64_t row_bytes, int lane) {
   const int rd_row = lane >> 3, rd_chunk = lane & 7;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
+  for (int i = 0; i < ROWS / 8; ++i) {
     const int row = i * 8 + rd_row;
     const v4i v = *reinterpret_cast<const v4i *>(slab + row * kSlabStride + rd_chunk * 16);
     v4i *dst = reinterpret_cast<v4i *>(gbase + row * row_bytes + rd_chunk * 16);
@@ -104,8 +110,8 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
   }
 }
 
-template <int OUT_KIND, bool INT_ONLY, bool VEC>
-__device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4][4], int8_t *smem,
+template <int OUT_KIND, bool INT_ONLY, bool VEC, int TB>
+__device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4][TB], int8_t *smem,
                                               const float *s_mult, const float *s_fb,
                                               const float *s_rs, int64_t bm0, int bn0, int wave_m,
                                               int wave_n, int lane) {
@@ -113,13 +119,14 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
   constexpr int ESZ = I8 ? 1 : 4;
   const int l32 = lane & 31, half = lane >> 5;
   const int wave = wave_m + 2 * wave_n;
-  int8_t *slab = smem + wave * kSlabBytes;
+  constexpr int WROWS = 32 * TB;  // token rows of the wave tile = rows of a slab
+  int8_t *slab = smem + wave * (WROWS * kSlabStride);
   const int64_t row_bytes = p.ldo * ESZ;
   // first element of the wave tile in the output
-  char *wbase = static_cast<char *>(p.out) + ((bm0 + wave_m * 128) * p.ldo + bn0 + wave_n * 128) * ESZ;
-  float rs[4];
+  char *wbase = static_cast<char *>(p.out) + ((bm0 + wave_m * WROWS) * p.ldo + bn0 + wave_n * 128) * ESZ;
+  float rs[TB];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) rs[b] = s_rs[wave_m * 128 + b * 32 + l32];
+  for (int b = 0; b < TB; ++b) rs[b] = s_rs[wave_m * WROWS + b * 32 + l32];
   const bool use_rs = !INT_ONLY && p.sx_row != nullptr;
   const bool use_fb = !INT_ONLY && p.fbias != nullptr;
   const float magic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to nearest even at unit steps
@@ -139,7 +146,7 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
       }
     }
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < TB; ++b) {
       const int row = b * 32 + l32;  // row inside the wave tile
       uint32_t packed[4];
 #pragma unroll
@@ -218,9 +225,9 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
         *reinterpret_cast<v4i *>(slab + row * kSlabStride + a * 32 + half * 16) = q;
       }
     }
-    if (VEC && !I8) store_slab<OUT_KIND>(slab, wbase + a * 32 * ESZ, row_bytes, lane);
+    if (VEC && !I8) store_slab<OUT_KIND, WROWS>(slab, wbase + a * 32 * ESZ, row_bytes, lane);
   }
-  if (VEC && I8) store_slab<OUT_KIND>(slab, wbase, row_bytes, lane);
+  if (VEC && I8) store_slab<OUT_KIND, WROWS>(slab, wbase, row_bytes, lane);
 }
 
 // Statistics epilogue (Sec. 3.3, Eq. 4-5 fused into the calibration forward): instead of storing
@@ -381,9 +388,12 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
   }
 }
 
-template <int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
-__global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
-  using C = FastCfg<BK, NSTAGE, NCHUNK>;
+template <int BM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
+__global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(const FwdParams p) {
+  using C = FastCfg<BM, BK, NSTAGE, NCHUNK>;
+  constexpr int TB = C::TB;
+  static_assert(OUT_KIND != kOutStats || (BM == 256 && C::RING >= 4 * 32768 && C::STATS_LDS_BYTES <= 160 * 1024),
+                "statistics epilogue: full-height tile, 32 KiB of the ring per wavefront");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   int32_t *s_off = reinterpret_cast<int32_t *>(smem + C::RING);
   float *s_mult = reinterpret_cast<float *>(smem + C::RING + 1024);
@@ -415,7 +425,7 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   }
   if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && OUT_KIND != kOutFixed) {
     if (p.fbias) p_fb = p.fbias[bn0 + tid];
-    if (p.sx_row) p_rs = p.sx_row[bm0 + tid];
+    if (p.sx_row && tid < BM) p_rs = p.sx_row[bm0 + tid];
   }
   // pivots of the shifted sums: the state's, or for the first batch of a state its row 0
   float p_pq = 0.0f, p_pf = 0.0f;
@@ -430,36 +440,39 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
     }
   }
 
-  // ---- global -> LDS: wavefront `wave` owns rows [64*wave, 64*wave + 64) of both panels,
-  // LOADS loads of RPL rows each; lane = (row lr, slot pc) inside a load.  Addresses are a
+  // ---- global -> LDS: wavefront `wave` owns a quarter of the rows of both panels (XROWS
+  // activation rows, 64 weight rows), loads of RPL rows each; lane = (row lr, slot pc) inside a load.  Addresses are a
   // wave-uniform 64-bit base (tile origin + k) plus a per-lane 32-bit offset that never changes,
   // so the loop body issues the loads without any vector address arithmetic.
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int lr = lane / C::CPR, pc = lane % C::CPR;
-  uint32_t xvo[C::LOADS], wvo[C::LOADS];
+  uint32_t xvo[C::LOADS_X], wvo[C::LOADS_W];
 #pragma unroll
-  for (int i = 0; i < C::LOADS; ++i) {
+  for (int i = 0; i < C::LOADS_X; ++i) {
+    const int row = wave * C::XROWS + i * C::RPL + lr;
+    xvo[i] = (uint32_t)row * (uint32_t)p.ldx + (pc ^ C::swz(row)) * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < C::LOADS_W; ++i) {
     const int row = wave * 64 + i * C::RPL + lr;
-    const int chunk = pc ^ C::swz(row);
-    xvo[i] = (uint32_t)row * (uint32_t)p.ldx + chunk * 16;
-    wvo[i] = (uint32_t)row * (uint32_t)p.ldw + chunk * 16;
+    wvo[i] = (uint32_t)row * (uint32_t)p.ldw + (pc ^ C::swz(row)) * 16;
   }
   const int8_t *xtile = p.x + bm0 * p.ldx;
   const int8_t *wtile = p.w + (int64_t)bn0 * p.ldw;
 
   // chunk c of a stage's 2*LOADS loads (activation loads first, then weight loads)
   auto issue_chunk = [&](int buf, int k0, int c) {
-    int8_t *sx = smem + buf * C::STAGE + wave_s * 64 * BK;
-    int8_t *sw = sx + C::X_BYTES;
+    int8_t *sx = smem + buf * C::STAGE + wave_s * C::XROWS * BK;
+    int8_t *sw = smem + buf * C::STAGE + C::X_BYTES + wave_s * 64 * BK;
     const int8_t *xk = xtile + k0, *wk = wtile + k0;
 #pragma unroll
     for (int j = 0; j < C::CHUNK; ++j) {
       const int i = c * C::CHUNK + j;
-      if (i < C::LOADS)
+      if (i < C::LOADS_X)
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
       else
-        __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wk + wvo[i - C::LOADS]),
-                                         CWAC_LDS_PTR(sw + (i - C::LOADS) * C::RPL * BK), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wk + wvo[i - C::LOADS_X]),
+                                         CWAC_LDS_PTR(sw + (i - C::LOADS_X) * C::RPL * BK), 16, 0, 0);
     }
   };
   auto issue_stage = [&](int buf, int k0) {
@@ -469,44 +482,44 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
 
   // ---- LDS -> MFMA operand fragments (rows of a 32-row MFMA tile start at multiples of 16)
   const int swz_l = C::swz(l32);
-  const int x_off = (wave_m * 128 + l32) * BK;
+  const int x_off = (wave_m * (BM / 2) + l32) * BK;
   const int w_off = C::X_BYTES + (wave_n * 128 + l32) * BK;
-  auto read_frags = [&](int buf, int kk, v4i(&fw)[4], v4i(&fx)[4]) {
+  auto read_frags = [&](int buf, int kk, v4i(&fw)[4], v4i(&fx)[TB]) {
     const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
 #pragma unroll
     for (int a = 0; a < 4; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
 #pragma unroll
-    for (int b = 0; b < 4; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
+    for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
   };
 
-  v16i acc[4][4];
-  auto mma = [&](const v4i(&fw)[4], const v4i(&fx)[4]) {
+  v16i acc[4][TB];
+  auto mma = [&](const v4i(&fw)[4], const v4i(&fx)[TB]) {
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
+      for (int b = 0; b < TB; ++b)
         acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
   };
-  // Scheduler hint for one k-step (16 MFMAs, 8 LDS reads of the next step's fragments and, when
-  // `loads`, one chunk of panel loads): the LDS reads go behind the first eight MFMAs one by one,
-  // so that they land half a step before they are needed; the panel loads are spread evenly
-  // over the second eight, so that their issue never holds up the matrix pipe.
+  // Scheduler hint for one k-step (4 * TB MFMAs, 4 + TB LDS reads of the next step's fragments and,
+  // when `loads`, one chunk of panel loads): the LDS reads go behind the first MFMAs one by one,
+  // so that they land well before they are needed; the panel loads are spread over the remaining
+  // MFMAs, so that their issue never holds up the matrix pipe.
   auto interleave = [&](bool loads) {
+    constexpr int READS = 4 + TB, REST = 4 * TB - READS;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < READS; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     if (loads) {
-      constexpr int PER = C::CHUNK >= 8 ? 1 : 8 / C::CHUNK;          // MFMAs per load group
-      constexpr int GRP = C::CHUNK >= 8 ? C::CHUNK / 8 : 1;          // loads per group
+      constexpr int GRP = (C::CHUNK + REST - 1) / REST;  // loads behind each remaining MFMA
 #pragma unroll
-      for (int i = 0; i < 8 / PER; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+      for (int i = 0; i < REST; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, GRP, 0);
       }
     } else {
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
     }
     __builtin_amdgcn_sched_barrier(0);  // one k-step per scheduling region
   };
@@ -519,7 +532,7 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
   s_off[tid] = p_off;
   s_mult[tid] = p_mult;
   s_fb[tid] = p_fb;
-  s_rs[tid] = p_rs;
+  if (tid < BM) s_rs[tid] = p_rs;
   if (OUT_KIND == kOutStats) {
     s_pq[tid] = p_pq;
     s_pf[tid] = p_pf;
@@ -535,12 +548,12 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
     for (int g = 0; g < 4; ++g) {
       const v4i o = *reinterpret_cast<const v4i *>(s_off + wave_n * 128 + a * 32 + 8 * g + 4 * half);
 #pragma unroll
-      for (int b = 0; b < 4; ++b)
+      for (int b = 0; b < TB; ++b)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[a][b][4 * g + r] = o[r];
     }
 
-  v4i fwA[4], fxA[4], fwB[4], fxB[4];
+  v4i fwA[4], fxA[TB], fwB[4], fxB[TB];
   read_frags(0, 0, fwA, fxA);
 
   // One stage: KK k-steps.  Before the MFMAs of the last one, everybody has fetched its last
@@ -612,48 +625,60 @@ __global__ __launch_bounds__(256) void qlinear_fast_kernel(const FwdParams p) {
     constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed) ? 1 : 4;
     const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
     if (vs)
-      fast_epilogue<OUT_KIND, INT_ONLY, true>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      fast_epilogue<OUT_KIND, INT_ONLY, true, TB>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
     else
-      fast_epilogue<OUT_KIND, INT_ONLY, false>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      fast_epilogue<OUT_KIND, INT_ONLY, false, TB>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
   }
 }
 
-template <int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
+template <int BM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
 cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
-  using C = FastCfg<BK, NSTAGE, NCHUNK>;
+  using C = FastCfg<BM, BK, NSTAGE, NCHUNK>;
   constexpr int LDS = OUT_KIND == kOutStats ? C::STATS_LDS_BYTES : C::LDS_BYTES;
   static const hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&qlinear_fast_kernel<BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY>),
+      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY>),
       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, 256, LDS, st>>>(p);
+  qlinear_fast_kernel<BM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, 256, LDS, st>>>(p);
   return launch_status();
 }
 
-template <int BK, int NSTAGE, int NCHUNK>
-cwac_status launch_cfg(const FwdParams &p, int out_kind, bool int_only, dim3 grid, hipStream_t st) {
-  if (out_kind == kOutFixed) return launch_one<BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
+template <int BM, int BK, int NSTAGE, int NCHUNK>
+cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
+  p.tiles_m = (int)ceil_div(p.m, BM);
+  p.tiles_n = (int)ceil_div(p.n, 256);
+  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
+  if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
+  const dim3 grid((unsigned)blocks);
+  if (out_kind == kOutFixed) return launch_one<BM, BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
   if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true>(p, grid, st)
-                    : launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false>(p, grid, st);
-  if (out_kind == CWAC_OUT_FP32) return launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false>(p, grid, st);
-  return launch_one<BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false>(p, grid, st);
+    return int_only ? launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true>(p, grid, st)
+                    : launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false>(p, grid, st);
+  if (out_kind == CWAC_OUT_FP32) return launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false>(p, grid, st);
+  return launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false>(p, grid, st);
 }
 
 }  // namespace
 
+bool fast_prefers_half_tile(int64_t m, int n, int k) {
+  // Measured on the ViT / Swin / LLM layer shapes: with two 128-token workgroups per compute unit
+  // one workgroup's prologue and epilogue overlap the other's main loop (about 8 us of fixed cost
+  // per tile instead of 12), but the main loop moves 1.5x the panel bytes per MAC and runs ~25 %
+  // slower; the fixed cost dominates up to K of about 1500.
+  return k <= 1536 && ceil_div(m, 128) * ceil_div(n, 256) >= 256;
+}
+
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
-  p.tiles_m = (int)ceil_div(p.m, 256);
-  p.tiles_n = (int)ceil_div(p.n, 256);
   const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
-  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
-  if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  const dim3 grid((unsigned)blocks);
-  // Tuning knob: CWAC_FWD_PIPE=128x2 | 64x4 selects K step and ring depth (same results).
+  // Tuning knob (same results): CWAC_FWD_PIPE=128x2 | 64x4 selects K step and ring depth of the
+  // 256-token tile; "duo" the 128-token tile, two workgroups per compute unit.
   const char *e = getenv("CWAC_FWD_PIPE");
-  if (e && e[0] == '6') return launch_cfg<64, 4, 2>(p, out_kind, int_only, grid, st);
-  return launch_cfg<128, 2, 2>(p, out_kind, int_only, grid, st);
+  if (e && e[0] == 'd') return launch_cfg<128, 64, 3, 2>(p, out_kind, int_only, st);
+  if (e && e[0] == '6') return launch_cfg<256, 64, 4, 2>(p, out_kind, int_only, st);
+  if (e && e[0] == '1') return launch_cfg<256, 128, 2, 2>(p, out_kind, int_only, st);
+  if (fast_prefers_half_tile(p.m, p.n, p.k)) return launch_cfg<128, 64, 3, 2>(p, out_kind, int_only, st);
+  return launch_cfg<256, 128, 2, 2>(p, out_kind, int_only, st);
 }
 
 cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {
@@ -662,7 +687,7 @@ cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {
   p.vec_store = 0;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  return launch_one<128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
+  return launch_one<256, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
 }
 
 }  // namespace cwac

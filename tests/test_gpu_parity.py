@@ -119,7 +119,7 @@ def test_quantize_rows_sym_and_colsum(orc, case1, case5s):
 
 # --------------------------------------------------------------------------- forward
 def _forward(c, out_kind, mult=None, offset=None, fbias=None, sx_row=None, qp=None, tile=None,
-             xq=None, ldo=None):
+             xq=None, ldo=None, pipe=None):
     xq = c.xq if xq is None else xq
     m = xq.shape[0]
     dt = {0: torch.int8, 1: torch.float32, 2: torch.int32}[out_kind]
@@ -131,11 +131,14 @@ def _forward(c, out_kind, mult=None, offset=None, fbias=None, sx_row=None, qp=No
         view = out[:, :c.n]
     if tile is not None:
         os.environ["CWAC_FWD_TILE"] = str(tile)
+    if pipe:
+        os.environ["CWAC_FWD_PIPE"] = pipe
     try:
         P.qlinear_cwac_forward(dev(xq), dev(c.wq), qp, dev(mult), dev(offset), dev(fbias),
                                dev(sx_row), out_kind, view)
     finally:
         os.environ.pop("CWAC_FWD_TILE", None)
+        os.environ.pop("CWAC_FWD_PIPE", None)
     return host(out)
 
 
@@ -214,11 +217,15 @@ def test_forward_ragged_shapes(orc, m, n, k):
             np.testing.assert_array_equal(got[:, :n], want)
 
 
+@pytest.mark.parametrize("pipe", ["128x2", "64x4", "duo"])
 @pytest.mark.parametrize("m,n,k", [(256, 256, 128), (300, 520, 384), (700, 1030, 1152),
                                    (513, 768, 256)])
-def test_forward_large_tile_kernel(orc, m, n, k):
-    """The 256 x 256 direct-to-LDS kernel (forced): edge tiles overlap their neighbours
-    instead of being predicated; N not a multiple of 4 takes the element-wise stores."""
+def test_forward_large_tile_kernel(orc, m, n, k, pipe):
+    """The direct-to-LDS kernel (forced) in its three pipeline shapes - 256-token tiles with a
+    128-byte or 64-byte K step, 128-token tiles with two workgroups per compute unit: edge tiles
+    overlap their neighbours instead of being predicated; N not a multiple of 4 takes the
+    element-wise stores."""
+    print(f"large-tile kernel {pipe}: {m} x {n} x {k}", flush=True)
     g = synth.normal(700 + m, 0, m * k).numpy().reshape(m, k)
     xq = np.clip(np.rint(g * 60), -128, 127).astype(np.int8)
     g = synth.normal(700 + m, 1, n * k).numpy().reshape(n, k)
@@ -232,17 +239,17 @@ def test_forward_large_tile_kernel(orc, m, n, k):
     c = SimpleNamespace(xq=xq, wq=wq, n=n)
     qp = P.make_qparams(z_r=5)
     for ldo in (None, n + 5):
-        got = _forward(c, P.CWAC_OUT_INT32, tile="fast", ldo=ldo)
+        got = _forward(c, P.CWAC_OUT_INT32, tile="fast", ldo=ldo, pipe=pipe)
         np.testing.assert_array_equal(got[:, :n], acc)
         if ldo:
             assert np.all(got[:, n:] == 77)
-        got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, tile="fast", ldo=ldo)
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, tile="fast", ldo=ldo, pipe=pipe)
         np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5))
         got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qp, tile="fast",
-                       ldo=ldo)
+                       ldo=ldo, pipe=pipe)
         np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5, fb, sxr))
         _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)
-        got = _forward(c, P.CWAC_OUT_FP32, mult, off, fbias=fb, sx_row=sxr, tile="fast", ldo=ldo)
+        got = _forward(c, P.CWAC_OUT_FP32, mult, off, fbias=fb, sx_row=sxr, tile="fast", ldo=ldo, pipe=pipe)
         np.testing.assert_array_equal(got[:, :n], want)
 
 
