@@ -202,6 +202,40 @@ void orc_colsum_i8(const int8_t *wq, int64_t n, int64_t k, int32_t *colsum) {
   }
 }
 
+/* Quantized convolution (Sec. 3.3: a CWAC module follows every quantized
+ * convolutional layer of a CNN; Sec. 3.4: the fold extends to it): the integer
+ * product of Eq. 7 with the sum running over the receptive field,
+ *   acc[b, oh, ow, n] = sum_{kh, kw, c} x_q[b, oh*stride + kh - pad, ow*stride + kw - pad, c]
+ *                                      * w_q[n, kh, kw, c],
+ * where a position outside the image holds the code of the real value zero,
+ * i.e. the zero-point Z_x (so that (x_q - Z_x) vanishes there and the zero-point
+ * term of Eq. 7 stays Z_x * sum_{kh,kw,c} w_q[n, kh, kw, c]).
+ *   x_q  [batch, h, w, c_in]      channels last
+ *   w_q  [c_out, kh, kw, c_in]
+ *   acc  [batch * oh * ow, c_out] with oh = (h + 2 pad - kh) / stride + 1, likewise ow */
+void orc_conv2d_i8(const int8_t *xq, const int8_t *wq, int64_t batch, int64_t h, int64_t w,
+                   int64_t c_in, int64_t c_out, int64_t kh, int64_t kw, int64_t stride,
+                   int64_t pad, int32_t zx, int32_t *acc) {
+  const int64_t oh = (h + 2 * pad - kh) / stride + 1, ow = (w + 2 * pad - kw) / stride + 1;
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < batch * oh * ow; ++m) {
+    const int64_t b = m / (oh * ow), y = (m / ow) % oh, x = m % ow;
+    for (int64_t n = 0; n < c_out; ++n) {
+      int32_t s = 0;
+      for (int64_t i = 0; i < kh; ++i)
+        for (int64_t j = 0; j < kw; ++j) {
+          const int64_t iy = y * stride + i - pad, ix = x * stride + j - pad;
+          const int inside = iy >= 0 && iy < h && ix >= 0 && ix < w;
+          for (int64_t c = 0; c < c_in; ++c) {
+            const int32_t xv = inside ? (int32_t)xq[((b * h + iy) * w + ix) * c_in + c] : zx;
+            s += xv * (int32_t)wq[((n * kh + i) * kw + j) * c_in + c];
+          }
+        }
+      acc[m * c_out + n] = s;
+    }
+  }
+}
+
 /* Right-hand side of Eq. 6 without the scales, written directly:
  * sum_k (w_q[n,k] - Z_W[n]) * (x_q[m,k] - Z_x), in 64-bit integers. */
 void orc_product_zp_direct(const int8_t *xq, const int8_t *wq, int64_t m,

@@ -154,6 +154,22 @@ def gemm_i8(xq, wq, rows=None):
     return acc
 
 
+def conv2d_i8(xq, wq, stride=1, pad=0, zx=0):
+    """Integer product of a quantized convolution: x_q [B,H,W,C_in], w_q [C_out,KH,KW,C_in]
+    -> acc int32 [B*OH*OW, C_out]; positions outside the image hold the zero-point."""
+    xq, wq = _i8(xq), _i8(wq)
+    b, h, w, c_in = xq.shape
+    c_out, kh, kw, c2 = wq.shape
+    assert c2 == c_in
+    oh, ow = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad - kw) // stride + 1
+    acc = np.empty((b * oh * ow, c_out), dtype=np.int32)
+    lib().orc_conv2d_i8(_p(xq, C.c_int8), _p(wq, C.c_int8), C.c_int64(b), C.c_int64(h),
+                        C.c_int64(w), C.c_int64(c_in), C.c_int64(c_out), C.c_int64(kh),
+                        C.c_int64(kw), C.c_int64(stride), C.c_int64(pad), C.c_int32(int(zx)),
+                        _p(acc, C.c_int32))
+    return acc
+
+
 def colsum_i8(wq):
     wq = _i8(wq)
     n, k = wq.shape
