@@ -226,6 +226,27 @@ cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w
                                  const float *s_x_row, int32_t out_kind, void *out, int64_t ldo,
                                  void *stream);
 
+/* Quantized convolutional layer with the compensation in its epilogue: the CWAC
+ * module that follows every quantized convolutional layer of a CNN (Sec. 3.3)
+ * folds into it as into a linear layer (Sec. 3.4).  Implicit GEMM: row m = (b, oh,
+ * ow), column n = output channel, the sum of Eq. 7 runs over the receptive field
+ *   acc[m, n] = sum_{i, j, c} x_q[b, oh*stride + i - pad, ow*stride + j - pad, c] * w_q[n, i, j, c]
+ * and a position outside the image holds the zero-point Z_x = qp->z_x (the code of
+ * the real value 0), so the zero-point term stays Z_x * sum_{i,j,c} w_q[n, i, j, c]:
+ * cwac_colsum and cwac_fold apply unchanged to w_q seen as [c_out, kh*kw*c_in].
+ * Epilogue and out_kind exactly as in qlinear_cwac_forward (no per-row scales).
+ *   x_q   device int8 [batch, h, w, c_in], channels last, contiguous, 16-byte aligned
+ *   w_q   device int8 [c_out, kh, kw, c_in], contiguous, 16-byte aligned
+ *   c_in % 16 == 0, kh * kw * c_in <= 32768, 1 <= kh, kw, stride <= 16, 0 <= pad < min(kh, kw)
+ *   qp    host, required (z_x; z_r, qmin, qmax for CWAC_OUT_INT8); act_per_token must be 0
+ *   out   device [batch * oh * ow, c_out] (= channels-last [batch, oh, ow, c_out]), ldo >= c_out,
+ *         oh = (h + 2 pad - kh) / stride + 1, ow likewise */
+cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q, int32_t batch, int32_t h,
+                                 int32_t w, int32_t c_in, int32_t c_out, int32_t kh, int32_t kw,
+                                 int32_t stride, int32_t pad, const cwac_qparams *qp,
+                                 const float *mult, const int32_t *offset, const float *fbias,
+                                 int32_t out_kind, void *out, int64_t ldo, void *stream);
+
 /* Calibration forward with the statistics taken in its epilogue (Sec. 3.3: the
  * sums of Eq. 4-5 over Y_quant = the CWAC_OUT_FP32 output above and the matching
  * rows of Y_full).  Equivalent to qlinear_cwac_forward(..., CWAC_OUT_FP32, y_quant)

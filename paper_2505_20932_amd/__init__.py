@@ -16,5 +16,5 @@ from .binding import (  # noqa: F401
     cwac_fold_fixed_point, qlinear_cwac_forward_fixed_point,
     cwac_quantize_act_bits, cwac_quantize_rows_sym_bits,
     CWAC_OUT_FP16, CWAC_W4_GROUP, cwac_w4_quantize_groupwise, cwac_w4_packed_w_bytes, cwac_w4_pack,
-    cwac_fold_weight_only, qlinear_w4a16_cwac_forward,
+    cwac_fold_weight_only, qlinear_w4a16_cwac_forward, qconv2d_cwac_forward,
 )

@@ -28,7 +28,7 @@ EXPORTS = (
     "cwac_mfma_probe", "cwac_fold_fixed_point", "qlinear_cwac_forward_fixed_point",
     "cwac_quantize_act_bits", "cwac_quantize_rows_sym_bits",
     "cwac_w4_quantize_groupwise", "cwac_w4_packed_w_bytes", "cwac_w4_pack",
-    "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward",
+    "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward", "qconv2d_cwac_forward",
 )
 
 
@@ -82,6 +82,8 @@ def lib() -> C.CDLL:
             "cwac_fold_fixed_point": (i32, [vp, vp, vp, vp, vp, i32, qpp, vp, vp, vp, vp, vp]),
             "qlinear_cwac_forward_fixed_point": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp,
                                                        vp, vp, i64, vp]),
+            "qconv2d_cwac_forward": (i32, [vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, i32, qpp,
+                                           vp, vp, vp, i32, vp, i64, vp]),
             "cwac_w4_quantize_groupwise": (i32, [vp, i64, i32, i32, vp, vp, vp, vp]),
             "cwac_w4_packed_w_bytes": (sz, [i32, i32]),
             "cwac_w4_pack": (i32, [vp, vp, vp, i32, i32, vp, vp, vp]),
@@ -298,6 +300,22 @@ def qlinear_cwac_forward_fixed_point(x_q: torch.Tensor, w_q: torch.Tensor, qp: c
                                                   _ptr(shift), _ptr(offset), _ptr(out),
                                                   _rowmajor(out), _stream(stream)),
            "qlinear_cwac_forward_fixed_point")
+
+
+def qconv2d_cwac_forward(x_q: torch.Tensor, w_q: torch.Tensor, stride: int, pad: int,
+                         qp: cwac_qparams, mult, offset, fbias, out_kind: int, out: torch.Tensor,
+                         stream=None):
+    """x_q int8 [B, H, W, C_in] (channels last), w_q int8 [C_out, KH, KW, C_in];
+    out [B*OH*OW, C_out] int8 / float32 / int32 per out_kind."""
+    assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8
+    assert x_q.is_contiguous() and w_q.is_contiguous() and x_q.dim() == 4 and w_q.dim() == 4
+    b, h, w, c_in = x_q.shape
+    c_out, kh, kw, c2 = w_q.shape
+    assert c2 == c_in and out.shape[1] == c_out
+    _check(lib().qconv2d_cwac_forward(_ptr(x_q), _ptr(w_q), b, h, w, c_in, c_out, kh, kw, stride,
+                                      pad, C.byref(qp), _ptr(mult), _ptr(offset), _ptr(fbias),
+                                      out_kind, _ptr(out), _rowmajor(out), _stream(stream)),
+           "qconv2d_cwac_forward")
 
 
 # --------------------------------------------------------------------------- weight-only INT4

@@ -35,6 +35,11 @@ struct FwdParams {
   const int32_t *m0;
   const int32_t *shift;
   int qlo, qhi;
+  // convolution as an implicit GEMM (generic kernel, CONV instantiation): x is the image tensor
+  // [batch, cv_h, cv_w, cv_cin] (channels last), row m = (b, oh, ow), k = (kh * cv_kw + kw) * cv_cin + c;
+  // positions outside the image read cv_pad4 (the zero-point code in all four bytes)
+  int cv_h, cv_w, cv_cin, cv_kw, cv_stride, cv_pad, cv_oh, cv_ow;
+  int cv_pad4;
 };
 
 // Internal output kind of the large-problem kernel: nothing is stored but the per-channel sums

@@ -41,7 +41,10 @@ struct Tile {
   static_assert(BK % 32 == 0 && CPR >= 2 && (CPR & (CPR - 1)) == 0, "BK must be a power of two >= 32");
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN, int OUT_KIND, bool INT_ONLY>
+// CONV: the activation operand is gathered from an image tensor (implicit GEMM): the CWAC module
+// that follows a quantized convolutional layer (Sec. 3.3) folds into it exactly as into a linear
+// layer (Sec. 3.4), the sum of Eq. 7 running over the receptive field.
+template <int BM, int BN, int BK, int WGM, int WGN, int OUT_KIND, bool INT_ONLY, bool CONV>
 __global__ __launch_bounds__(64 * WGM * WGN) void qlinear_kernel(const FwdParams p) {
   using T = Tile<BM, BN, BK, WGM, WGN>;
   constexpr int NT = T::NT, TM = T::TM, TN = T::TN, CPR = T::CPR;
@@ -65,11 +68,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qlinear_kernel(const FwdParams
   constexpr int RSTEP = NT / CPR;  // rows between a thread's successive chunks
   const int8_t *xg[T::XCH];
   const int8_t *wg[T::WCH];
+  int ih0[T::XCH], iw0[T::XCH];  // CONV: top-left input position of the row's receptive field
 #pragma unroll
   for (int i = 0; i < T::XCH; ++i) {
     int64_t r = bm0 + ld_r + i * RSTEP;
     if (r > p.m - 1) r = p.m - 1;  // rows past the edge re-read the last row; never stored
-    xg[i] = p.x + r * p.ldx + ld_c * 16;
+    if (CONV) {
+      const int per = p.cv_oh * p.cv_ow;
+      const int64_t b = r / per;
+      const int rem = (int)(r - b * per);
+      const int y = rem / p.cv_ow, x = rem - y * p.cv_ow;
+      ih0[i] = y * p.cv_stride - p.cv_pad;
+      iw0[i] = x * p.cv_stride - p.cv_pad;
+      xg[i] = p.x + b * ((int64_t)p.cv_h * p.cv_w * p.cv_cin);
+    } else {
+      xg[i] = p.x + r * p.ldx + ld_c * 16;
+    }
   }
 #pragma unroll
   for (int i = 0; i < T::WCH; ++i) {
@@ -81,9 +95,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qlinear_kernel(const FwdParams
 
   auto load_stage = [&](int k0) {
     const bool in_k = (k0 + ld_c * 16) < p.k;  // k % 16 == 0: a chunk is all in or all out
+    if (CONV) {
+      // c_in % 16 == 0: the 16 channels of a chunk belong to one filter tap
+      const int kc = k0 + ld_c * 16;
+      const int tap = kc / p.cv_cin, c = kc - tap * p.cv_cin;
+      const int kh = tap / p.cv_kw, kw = tap - kh * p.cv_kw;
+      const v4i pad = {p.cv_pad4, p.cv_pad4, p.cv_pad4, p.cv_pad4};
 #pragma unroll
-    for (int i = 0; i < T::XCH; ++i)
-      xr[i] = in_k ? *reinterpret_cast<const v4i *>(xg[i] + k0) : v4i{0, 0, 0, 0};
+      for (int i = 0; i < T::XCH; ++i) {
+        const int ih = ih0[i] + kh, iw = iw0[i] + kw;
+        const bool inside = in_k && (unsigned)ih < (unsigned)p.cv_h && (unsigned)iw < (unsigned)p.cv_w;
+        const int64_t pos = ((int64_t)ih * p.cv_w + iw) * p.cv_cin + c;
+        xr[i] = inside ? *reinterpret_cast<const v4i *>(xg[i] + pos) : pad;  // beyond k: weights are 0
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < T::XCH; ++i)
+        xr[i] = in_k ? *reinterpret_cast<const v4i *>(xg[i] + k0) : v4i{0, 0, 0, 0};
+    }
 #pragma unroll
     for (int i = 0; i < T::WCH; ++i)
       wr[i] = in_k ? *reinterpret_cast<const v4i *>(wg[i] + k0) : v4i{0, 0, 0, 0};
@@ -137,7 +166,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void qlinear_kernel(const FwdParams
                                              p.vec_store);
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN>
+template <int BM, int BN, int BK, int WGM, int WGN, bool CONV = false>
 cwac_status launch_tile(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   p.tiles_m = (int)ceil_div(p.m, BM);
   p.tiles_n = (int)ceil_div(p.n, BN);
@@ -145,16 +174,17 @@ cwac_status launch_tile(FwdParams p, int out_kind, bool int_only, hipStream_t st
   if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
   const dim3 grid((unsigned)blocks), block(64 * WGM * WGN);
   if (out_kind == kOutFixed) {
-    qlinear_kernel<BM, BN, BK, WGM, WGN, kOutFixed, true><<<grid, block, 0, st>>>(p);
+    if (CONV) return CWAC_E_MODE;
+    qlinear_kernel<BM, BN, BK, WGM, WGN, kOutFixed, true, false><<<grid, block, 0, st>>>(p);
   } else if (out_kind == CWAC_OUT_INT8) {
     if (int_only)
-      qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT8, true><<<grid, block, 0, st>>>(p);
+      qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT8, true, CONV><<<grid, block, 0, st>>>(p);
     else
-      qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT8, false><<<grid, block, 0, st>>>(p);
+      qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT8, false, CONV><<<grid, block, 0, st>>>(p);
   } else if (out_kind == CWAC_OUT_FP32) {
-    qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_FP32, false><<<grid, block, 0, st>>>(p);
+    qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_FP32, false, CONV><<<grid, block, 0, st>>>(p);
   } else {
-    qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT32, false><<<grid, block, 0, st>>>(p);
+    qlinear_kernel<BM, BN, BK, WGM, WGN, CWAC_OUT_INT32, false, CONV><<<grid, block, 0, st>>>(p);
   }
   return launch_status();
 }
@@ -255,6 +285,63 @@ extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, cons
   p.vec_store = ((ldo * esz) % (4 * esz) == 0) && aligned(out, 4 * esz);
   const bool int_only = (out_kind == CWAC_OUT_INT8) && !fbias && !s_x_row;
   return dispatch_forward(p, out_kind, int_only, as_stream(stream));
+}
+
+extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q, int32_t batch,
+                                            int32_t h, int32_t w, int32_t c_in, int32_t c_out,
+                                            int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                            const cwac_qparams *qp, const float *mult,
+                                            const int32_t *offset, const float *fbias,
+                                            int32_t out_kind, void *out, int64_t ldo, void *stream) {
+  if (!x_q || !w_q || !out || !qp) return CWAC_E_NULL;
+  if (out_kind != CWAC_OUT_INT8 && out_kind != CWAC_OUT_FP32 && out_kind != CWAC_OUT_INT32)
+    return CWAC_E_MODE;
+  if (out_kind != CWAC_OUT_INT32 && !mult) return CWAC_E_NULL;
+  if (qp->act_per_token) return CWAC_E_MODE;  // a convolution's rows share activations: per-tensor only
+  if (batch < 1 || h < 1 || w < 1 || c_in < 16 || (c_in % 16) != 0 || c_out < 1 || kh < 1 || kw < 1 ||
+      kh > 16 || kw > 16 || stride < 1 || stride > 16 || pad < 0 || pad >= kh || pad >= kw ||
+      h > 32768 || w > 32768)
+    return CWAC_E_SHAPE;
+  if (h + 2 * pad < kh || w + 2 * pad < kw) return CWAC_E_SHAPE;
+  const int64_t k = (int64_t)kh * kw * c_in;
+  if (k > 32768) return CWAC_E_SHAPE;
+  if (qp->z_x < -128 || qp->z_x > 127) return CWAC_E_SHAPE;
+  const int oh = (h + 2 * pad - kh) / stride + 1, ow = (w + 2 * pad - kw) / stride + 1;
+  const int64_t m = (int64_t)batch * oh * ow;
+  if (m > ((int64_t)1 << 40) || (int64_t)oh * ow > 0x7fffffff || ldo < c_out) return CWAC_E_SHAPE;
+  if (!aligned(x_q, 16) || !aligned(w_q, 16)) return CWAC_E_ALIGN;
+  FwdParams p = {};
+  p.x = x_q; p.w = w_q; p.ldx = 0; p.ldw = k; p.ldo = ldo;
+  p.m = m; p.n = c_out; p.k = (int)k;
+  p.mult = mult; p.offset = offset; p.fbias = fbias; p.sx_row = nullptr; p.out = out;
+  p.cv_h = h; p.cv_w = w; p.cv_cin = c_in; p.cv_kw = kw; p.cv_stride = stride; p.cv_pad = pad;
+  p.cv_oh = oh; p.cv_ow = ow;
+  p.cv_pad4 = (int)(0x01010101u * (uint32_t)(uint8_t)(int8_t)qp->z_x);
+  if (out_kind == CWAC_OUT_INT8) {
+    if (qp->qmin < -128 || qp->qmax > 127 || qp->qmin > qp->qmax) return CWAC_E_SHAPE;
+    if (qp->z_r < -(1 << 20) || qp->z_r > (1 << 20)) return CWAC_E_SHAPE;
+    p.zr = qp->z_r;
+    p.lo = (float)(qp->qmin - qp->z_r);
+    p.hi = (float)(qp->qmax - qp->z_r);
+  }
+  const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
+  if (!aligned(out, esz)) return CWAC_E_ALIGN;
+  p.vec_store = ((ldo * esz) % (4 * esz) == 0) && aligned(out, 4 * esz);
+  const bool int_only = (out_kind == CWAC_OUT_INT8) && !fbias;
+  const int64_t t256 = ceil_div(m, 256) * ceil_div(c_out, 256);
+  const int64_t t128 = ceil_div(m, 128) * ceil_div(c_out, 128);
+  int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
+  // narrow layers: a tile much wider than the layer would multiply mostly padding
+  if (c_out <= 160 && tile > 128) tile = 128;
+  if (c_out <= 80 && tile > 64) tile = 64;
+  if (const char *e = getenv("CWAC_FWD_TILE")) {  // testing / tuning knob, as for the linear layer
+    const int v = atoi(e);
+    if (v == 256 || v == 128 || v == 64) tile = v;
+  }
+  hipStream_t st = as_stream(stream);
+  if (tile == 256) return launch_tile<256, 256, 128, 2, 2, true>(p, out_kind, int_only, st);
+  if (tile == 128) return launch_tile<128, 128, 128, 2, 2, true>(p, out_kind, int_only, st);
+  return launch_tile<64, 64, 128, 2, 2, true>(p, out_kind, int_only, st);
 }
 
 extern "C" size_t cwac_calibrate_fused_workspace(int64_t m, int32_t n) {

@@ -148,6 +148,26 @@ def test_argument_errors_of_the_weight_only_entry_points(lib):
     assert f(a, 128, a, a, 0, 256, 128, null, null, 3, a, 256, null) == -2     # no rows
 
 
+def test_argument_errors_of_the_convolution_entry_point(lib):
+    qp = binding.make_qparams(z_x=3)
+    null = None
+    a = C.c_void_p(4096)
+    f = lib.qconv2d_cwac_forward
+    ok_tail = (C.byref(qp), a, a, null, 0, a, 64, null)
+    assert f(null, a, 1, 8, 8, 16, 64, 3, 3, 1, 1, *ok_tail) == -1
+    assert f(a, a, 1, 8, 8, 24, 64, 3, 3, 1, 1, *ok_tail) == -2          # c_in % 16
+    assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 1, 3, *ok_tail) == -2          # pad >= kernel
+    assert f(a, a, 1, 2, 2, 16, 64, 5, 5, 1, 1, *ok_tail) == -2          # image smaller than the window
+    assert f(a, a, 1, 8, 8, 4096, 64, 3, 3, 1, 1, *ok_tail) == -2        # kh * kw * c_in > 32768
+    assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 0, 1, *ok_tail) == -2          # stride 0
+    assert f(C.c_void_p(4100), a, 1, 8, 8, 16, 64, 3, 3, 1, 1, *ok_tail) == -3
+    assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 1, 1, C.byref(qp), a, a, null, 7, a, 64, null) == -4
+    assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 1, 1, C.byref(qp), a, a, null, 0, a, 32, null) == -2   # ldo < c_out
+    per_token = binding.make_qparams(mode=1, act_per_token=True)
+    assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 1, 1, C.byref(per_token), a, a, a, 0, a, 64, null) == -4
+    assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 1, 1, null, a, a, null, 0, a, 64, null) == -1          # qp required
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
