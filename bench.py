@@ -29,7 +29,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --probe`,
 # scaled by what the same counters read for a plain 1 GiB copy (x1.997, x1.000); mean over the
 # workload's launches.  Only the default workload has been profiled.
-PMC_TRAFFIC_BYTES = {5: {"forward_int8": 984e6 + 144e6, "statistics": 1113e6 + 8e6}}
+PMC_TRAFFIC_BYTES = {5: {"forward_int8": 984e6 + 144e6, "statistics": 1113e6 + 8e6,
+                         "forward_w4a16": 1532e6 + 331e6}}
 
 
 class LayerState:
@@ -336,11 +337,9 @@ def mfma_ceiling(P, torch, layers, iters: int = 20000, reps: int = 4):
     return out
 
 
-def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: int):
-    """The paper's LLM setting on the same layer shapes: INT4 group-128 weights, fp16 activations,
-    CWAC in the epilogue.  A step = calibration forward (fp32 out) -> statistics -> fit -> fold ->
-    compensated fp16 forward, for every layer; the fp16 forward is the kernel the roofline is for."""
-    import numpy as np
+def setup_weight_only(P, synth, torch, cfg: int, dev: str):
+    """Device-resident inputs of the weight-only step: INT4 group-128 weights in the kernel's
+    streaming layout, fp16 activations, the upstream fp32 layer output."""
     wl = synth.WORKLOADS[cfg]
     m = wl.m
     layers = []
@@ -372,25 +371,43 @@ def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: 
     for L in layers:
         L.yq = yq_buf[:m * L.n].view(m, L.n)
         L.out = out_buf[:m * L.n].view(m, L.n)
+    torch.cuda.synchronize()
+    return layers
+
+
+def run_step_weight_only(P, layers, ev=None):
+    """fp32 calibration forward -> statistics -> fit -> fold -> compensated fp16 forward, per layer."""
+    import torch
+    for L in layers:
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if ev is not None else None
+        if e:
+            e[0].record()
+        P.qlinear_w4a16_cwac_forward(L.xcal, L.pw, L.psz, L.n, None, None, L.yq)
+        if e:
+            e[1].record()
+        P.cwac_stats_reset(L.stats, L.n)
+        P.cwac_calibrate_stats(L.y_full, L.yq, L.stats, L.ws)
+        P.cwac_solve(L.stats, L.n, L.alpha, L.beta)
+        P.cwac_fold_weight_only(L.alpha, L.beta, None, L.mult, L.fbias)
+        if e:
+            e[2].record()
+        P.qlinear_w4a16_cwac_forward(L.x, L.pw, L.psz, L.n, L.mult, L.fbias, L.out)
+        if e:
+            e[3].record()
+            ev.append(e)
+
+
+def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: int):
+    """The paper's LLM setting on the same layer shapes: INT4 group-128 weights, fp16 activations,
+    CWAC in the epilogue.  A step = calibration forward (fp32 out) -> statistics -> fit -> fold ->
+    compensated fp16 forward, for every layer; the fp16 forward is the kernel the roofline is for."""
+    import numpy as np
+    wl = synth.WORKLOADS[cfg]
+    m = wl.m
+    layers = setup_weight_only(P, synth, torch, cfg, dev)
 
     def step(ev=None):
-        for L in layers:
-            e = [torch.cuda.Event(enable_timing=True) for _ in range(4)] if ev is not None else None
-            if e:
-                e[0].record()
-            P.qlinear_w4a16_cwac_forward(L.xcal, L.pw, L.psz, L.n, None, None, L.yq)
-            if e:
-                e[1].record()
-            P.cwac_stats_reset(L.stats, L.n)
-            P.cwac_calibrate_stats(L.y_full, L.yq, L.stats, L.ws)
-            P.cwac_solve(L.stats, L.n, L.alpha, L.beta)
-            P.cwac_fold_weight_only(L.alpha, L.beta, None, L.mult, L.fbias)
-            if e:
-                e[2].record()
-            P.qlinear_w4a16_cwac_forward(L.x, L.pw, L.psz, L.n, L.mult, L.fbias, L.out)
-            if e:
-                e[3].record()
-                ev.append(e)
+        run_step_weight_only(P, layers, ev)
 
     for _ in range(2):
         step()
@@ -425,7 +442,8 @@ def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: 
         "value": round(2.0 * fwd_flops / t_step / 1e12, 2), "unit": "TFLOP/s",
         "roofline": {"bound": "mfma", "achieved": round(tf / 1e3, 4),
                      "peak": FP16_MFMA_PEAK_TFLOPS / 1e3, "unit": "PFLOP/s",
-                     "frac": round(tf / FP16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(tf / FP16_MFMA_PEAK_TFLOPS, 4),
+                     "traffic": PMC_TRAFFIC_BYTES.get(wl.cfg, {}).get("forward_w4a16"),
                      "kernel": "w4a16_kernel (fp16 out, fused CWAC epilogue)",
                      "launches_per_step": len(layers), "avg_launch_ms": round(t_fwd / len(layers), 4),
                      "flops_per_step": fwd_flops},
@@ -548,7 +566,12 @@ def main():
         P.cwac_apply_unfolded(src, one, zero, dst)
         run_step(P, layers)
         torch.cuda.synchronize()
-        print(json.dumps({"probe": "copy of 1073741824 bytes, then one step",
+        if args.config == 5 and not args.no_weight_only:
+            del layers, src, dst
+            torch.cuda.empty_cache()
+            run_step_weight_only(P, setup_weight_only(P, synth, torch, args.config, dev))
+            torch.cuda.synchronize()
+        print(json.dumps({"probe": "copy of 1073741824 bytes, then one step (and one weight-only step)",
                           "workload": wl.name}))
         return
 
