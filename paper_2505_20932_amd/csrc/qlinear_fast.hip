@@ -59,10 +59,12 @@ struct FastCfg {
   static constexpr int LOADS_X = XROWS / RPL;  // loads per wavefront and stage, activation panel
   static constexpr int LOADS_W = 64 / RPL;     // ... weight panel (64 rows per wavefront)
   static constexpr int LPS = LOADS_X + LOADS_W;  // loads per wavefront and stage
-  static constexpr int CHUNK = LPS / NCHUNK;  // loads issued together, once per k-step
+  static constexpr int CHUNK = (LPS + NCHUNK - 1) / NCHUNK;  // most loads issued in one k-step
+  // chunk c of a stage's loads = loads [chunk_begin(c), chunk_begin(c + 1))
+  __host__ __device__ static constexpr int chunk_begin(int c) { return c * LPS / NCHUNK; }
   static_assert(BM == 256 || BM == 128, "token rows per tile");
   static_assert(BK == 64 || BK == 128, "K step");
-  static_assert(NCHUNK >= 1 && NCHUNK <= KK && LPS % NCHUNK == 0, "load chunks per stage");
+  static_assert(NCHUNK >= 1 && NCHUNK <= KK && NCHUNK <= LPS, "load chunks per stage");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one compute unit");
   static_assert((NSTAGE - 1) * LPS < 64, "vmcnt is a 6-bit counter");
   // swizzle of the 16-byte chunk position inside a row, a function of the row's low 4 bits
@@ -467,7 +469,8 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(co
     const int8_t *xk = xtile + k0, *wk = wtile + k0;
 #pragma unroll
     for (int j = 0; j < C::CHUNK; ++j) {
-      const int i = c * C::CHUNK + j;
+      const int i = C::chunk_begin(c) + j;
+      if (i >= C::chunk_begin(c + 1)) break;
       if (i < C::LOADS_X)
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
       else
