@@ -88,3 +88,59 @@ def test_step_replays_from_a_graph(orc):
     acc = orc.gemm_i8(xq.cpu().numpy(), wq.cpu().numpy())
     np.testing.assert_array_equal(out.cpu().numpy(),
                                   orc.folded_forward(acc, off.cpu().numpy(), mult.cpu().numpy(), zr))
+
+
+def test_weight_only_and_convolution_replay_from_a_graph():
+    """The weight-only INT4 entry points and the convolution launch only kernels too."""
+    f32 = dict(dtype=torch.float32, device=DEV)
+    m, n, k = 300, 512, 384
+    w = synth.normal(3, 0, n * k, device=DEV).view(n, k) * 0.02
+    x = torch.empty(m, k, dtype=torch.float16, device=DEV)
+    codes = torch.empty(n, k, dtype=torch.uint8, device=DEV)
+    sc = torch.empty(n, k // 128, dtype=torch.float16, device=DEV)
+    ze = torch.empty(n, k // 128, dtype=torch.uint8, device=DEV)
+    pw = torch.empty(P.cwac_w4_packed_w_bytes(n, k), dtype=torch.uint8, device=DEV)
+    psz = torch.empty((k // 128) * n, dtype=torch.int32, device=DEV)
+    alpha, beta = torch.empty(n, **f32), torch.empty(n, **f32)
+    mult, fb = torch.empty(n, **f32), torch.empty(n, **f32)
+    out = torch.empty(m, n, dtype=torch.float16, device=DEV)
+    # convolution: 2 images of 12 x 12 x 32 -> 48 channels, 3 x 3, padding 1
+    xc = torch.empty(2, 12, 12, 32, dtype=torch.int8, device=DEV)
+    wc = torch.randint(-100, 101, (48, 3, 3, 32), dtype=torch.int8, device=DEV,
+                       generator=torch.Generator(device=DEV).manual_seed(9))
+    cm = torch.full((48,), 3e-4, **f32)
+    co = torch.arange(48, dtype=torch.int32, device=DEV) * 7 - 100
+    outc = torch.empty(2 * 12 * 12, 48, dtype=torch.int8, device=DEV)
+    qp = P.make_qparams(z_x=-4, z_r=3)
+
+    def step():
+        P.cwac_w4_quantize_groupwise(w, codes, sc, ze)
+        P.cwac_w4_pack(codes, sc, ze, pw, psz)
+        P.cwac_fold_weight_only(alpha, beta, None, mult, fb)
+        P.qlinear_w4a16_cwac_forward(x, pw, psz, n, mult, fb, out)
+        P.qconv2d_cwac_forward(xc, wc, 1, 1, qp, cm, co, None, P.CWAC_OUT_INT8, outc)
+
+    def load(seed):
+        x.copy_(synth.normal(seed, 0, m * k, device=DEV).view(m, k))
+        alpha.copy_(1.0 + 0.1 * synth.normal(seed, 1, n, device=DEV))
+        beta.copy_(0.05 * synth.normal(seed, 2, n, device=DEV))
+        xc.copy_((synth.normal(seed, 3, xc.numel(), device=DEV) * 40).clamp(-128, 127).view(xc.shape))
+
+    load(1)
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for seed in (2, 3, 4):
+        load(seed)
+        step()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (out, outc, mult, fb)]
+        for t in (out, outc, mult, fb, pw):
+            t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(want, (out, outc, mult, fb)):
+            assert torch.equal(a, b), f"replay {seed} differs from the eager step"
