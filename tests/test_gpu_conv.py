@@ -78,6 +78,19 @@ def test_conv_all_modes(orc, shape, tile):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("kh,kw,pad", [(1, 7, 0), (7, 1, 0), (3, 5, 2), (5, 3, 1)])
+def test_conv_rectangular_filters(orc, kh, kw, pad):
+    b, h, w, c, n = 3, 17, 19, 32, 72
+    xq = np.clip(np.rint(synth.normal(60 + kh, 0, b * h * w * c).numpy() * 50), -128, 127).astype(np.int8)
+    xq = xq.reshape(b, h, w, c)
+    wq = np.clip(np.rint(synth.normal(60 + kh, 1, n * kh * kw * c).numpy() * 50), -127, 127).astype(np.int8)
+    wq = wq.reshape(n, kh, kw, c)
+    qp = P.make_qparams(z_x=9)
+    for stride in (1, 2):
+        got = _conv(xq, wq, stride, pad, qp, P.CWAC_OUT_INT32)
+        np.testing.assert_array_equal(got, orc.conv2d_i8(xq, wq, stride, pad, 9))
+
+
 def test_conv_pointwise_equals_linear(orc):
     """A 1x1 stride-1 convolution is the linear layer on the flattened positions."""
     b, h, w, c, n = 4, 16, 16, 256, 512

@@ -163,6 +163,19 @@ def test_forward_exact_operands(w4, m, n, k):
     np.testing.assert_array_equal(_forward(x16, pw, psz, n, None, fbias, torch.float32).cpu().numpy(), o32b)
 
 
+def test_forward_longest_k(w4):
+    """The largest supported K (256 quantization groups): every partial sum still exact in fp32."""
+    m, n, k = 40, 256, 32768
+    x16, codes, scales, zeros = _exact_case(77, m, n, k)
+    scales[:] = np.float16(0.5)
+    wd = w4.dequant(codes, scales, zeros)
+    acc, _ = w4.product(x16, wd)
+    assert np.abs(acc).max() < 2 ** 23
+    pw, psz = _pack(codes, scales, zeros)
+    out = _forward(x16, pw, psz, n, None, None, torch.float32)
+    np.testing.assert_array_equal(out.cpu().numpy(), acc.astype(np.float32))
+
+
 def test_forward_padded_activation_pitch(w4):
     m, n, k = 260, 256, 256
     x16, codes, scales, zeros = _exact_case(9, m, n, k)

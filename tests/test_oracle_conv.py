@@ -42,6 +42,16 @@ def test_against_numpy_windows(orc, h, w, c, n, k, stride, pad, zx):
     np.testing.assert_array_equal(got.astype(np.int64), _windows_product(xq, wq, stride, pad, zx))
 
 
+def test_rectangular_filters(orc):
+    """kh != kw: the two filter axes are not interchangeable."""
+    rng = np.random.default_rng(8)
+    xq = rng.integers(-128, 128, (2, 9, 10, 16), dtype=np.int64).astype(np.int8)
+    for kh, kw, pad in [(1, 3, 0), (3, 1, 0), (5, 3, 1), (1, 7, 0)]:
+        wq = rng.integers(-127, 128, (3, kh, kw, 16), dtype=np.int64).astype(np.int8)
+        got = orc.conv2d_i8(xq, wq, 1, pad, 4)
+        np.testing.assert_array_equal(got.astype(np.int64), _windows_product(xq, wq, 1, pad, 4))
+
+
 def test_pointwise_convolution_is_the_linear_layer(orc):
     rng = np.random.default_rng(3)
     xq = rng.integers(-128, 128, (3, 5, 6, 32), dtype=np.int64).astype(np.int8)
