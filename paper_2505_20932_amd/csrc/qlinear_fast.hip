@@ -664,11 +664,17 @@ cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st)
 }  // namespace
 
 bool fast_prefers_half_tile(int64_t m, int n, int k) {
-  // Measured on the ViT / Swin / LLM layer shapes: with two 128-token workgroups per compute unit
-  // one workgroup's prologue and epilogue overlap the other's main loop (about 8 us of fixed cost
-  // per tile instead of 12), but the main loop moves 1.5x the panel bytes per MAC and runs ~25 %
-  // slower; the fixed cost dominates up to K of about 1500.
-  return k <= 1536 && ceil_div(m, 128) * ceil_div(n, 256) >= 256;
+  // Cost model fitted to measurements on ViT / Swin / LLM layer shapes (microseconds per compute
+  // unit): a 256-token tile costs 12 + 0.0104 k; two 128-token workgroups sharing a compute unit
+  // overlap each other's prologue and epilogue but move 1.5x the panel bytes per MAC: the pair
+  // costs 8 + 0.0133 k, a lone one 10 + 0.00665 k.  Tiles run in rounds of 256 (512) at a time.
+  const int64_t t_full = ceil_div(m, 256) * ceil_div(n, 256), t_half = ceil_div(m, 128) * ceil_div(n, 256);
+  if (t_half < 160) return false;
+  const double cost_full = (double)ceil_div(t_full, 256) * (12.0 + 0.0104 * k);
+  const int64_t rest = t_half % 512;
+  const double cost_half = (double)(t_half / 512) * (8.0 + 0.0133 * k) +
+                           (rest == 0 ? 0.0 : rest <= 256 ? 10.0 + 0.00665 * k : 8.0 + 0.0133 * k);
+  return cost_half < cost_full;
 }
 
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
