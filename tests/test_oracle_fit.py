@@ -130,3 +130,24 @@ def test_parameter_count_matches_printed_delta(orc):
     for _, blocks, chans, printed in rows:
         mb = int(blocks) * int(chans) * bytes_per_channel / 1e6
         assert round(mb, 1) == float(printed), (mb, printed)
+
+
+def test_fit_error_shrinks_with_the_calibration_set(orc):
+    """Synthetic analogue of the paper's calibration-set-size ablation (Sec. 4.5): for
+    Y_full = a * Y_quant + d + noise the closed-form estimate approaches (a, d) like 1/sqrt(N),
+    the textbook rate of a least-squares slope."""
+    c = 64
+    a = (0.8 + 0.4 * np.abs(synth.normal(55, 0, c).numpy())).astype(np.float64)
+    d = synth.normal(55, 1, c).numpy().astype(np.float64) * 0.3
+    errs = []
+    for n_rows in (32, 128, 512, 2048, 8192):
+        yq = synth.normal(56, n_rows, n_rows * c).numpy().reshape(n_rows, c).astype(np.float32)
+        noise = synth.normal(57, n_rows, n_rows * c).numpy().reshape(n_rows, c) * 0.1
+        yf = (a[None, :] * yq + d[None, :] + noise).astype(np.float32)
+        alpha, beta = orc.fit(yf, yq)
+        errs.append(float(np.sqrt(np.mean((alpha - a) ** 2 + (beta - d) ** 2))))
+    # every 4x in rows roughly halves the error; 256x in rows: 16x, within a factor of 2
+    assert all(e1 < 0.8 * e0 for e0, e1 in zip(errs, errs[1:])), errs
+    assert 8.0 < errs[0] / errs[-1] < 32.0, errs
+    # standard error of the slope: sigma_noise / (sigma_q * sqrt(N)); of the intercept about the same
+    assert errs[-1] < 3.0 * 0.1 * np.sqrt(2.0 / 8192)
