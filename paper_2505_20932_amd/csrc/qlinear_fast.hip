@@ -1,6 +1,8 @@
 // Large-problem kernel of the quantized linear layer with the CWAC epilogue (Sec. 3.4,
-// Eq. 10): 256 x 256 output tile, four wavefronts (2 x 2, each 128 x 128 = 4 x 4 MFMA tiles,
-// 256 int32 accumulators per lane), one workgroup per compute unit.
+// Eq. 10): 256 x 256 output tile, one workgroup per compute unit, of eight wavefronts (4 x 2,
+// each 64 x 128 = 2 x 4 MFMA tiles, 128 int32 accumulators per lane, two wavefronts per SIMD so
+// that one's load issue and LDS reads run under the other's MFMAs) or of four wavefronts (2 x 2,
+// each 128 x 128, 256 accumulators per lane; the shape the statistics epilogue uses).
 //
 //   * Panels go global -> LDS directly (global_load_lds_dwordx4, no register staging).  One
 //     wavefront load lands as 1 KiB of contiguous LDS, so the bank swizzle is applied on the
@@ -40,10 +42,12 @@ constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
   return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
 }
 
-template <int BM_, int BK, int NSTAGE, int NCHUNK>
+template <int BM_, int WM_, int BK, int NSTAGE, int NCHUNK>
 struct FastCfg {
   static constexpr int BM = BM_, BN = 256;
-  static constexpr int TB = BM / 64;  // 32-token MFMA tiles per wavefront (2 wavefronts along m)
+  static constexpr int WM = WM_;                 // wavefronts along m (always 2 along n)
+  static constexpr int NWAVES = 2 * WM, NT = 64 * NWAVES;
+  static constexpr int TB = BM / (32 * WM);      // 32-token MFMA tiles per wavefront
   static constexpr int KK = BK / 32;  // MFMA k-steps per stage
   static constexpr int X_BYTES = BM * BK, W_BYTES = BN * BK, STAGE = X_BYTES + W_BYTES;
   static constexpr int RING = NSTAGE * STAGE;
@@ -55,14 +59,16 @@ struct FastCfg {
   static constexpr int STATS_LDS_BYTES = STATS_EXCH + 2 * 4 * kStats * 32 * 8;
   static constexpr int CPR = BK / 16;        // 16-byte chunks per row
   static constexpr int RPL = 64 / CPR;       // rows covered by one wavefront load
-  static constexpr int XROWS = BM / 4;       // activation rows each wavefront loads per stage
+  static constexpr int XROWS = BM / NWAVES;   // activation rows each wavefront loads per stage
+  static constexpr int WLROWS = BN / NWAVES;  // weight rows each wavefront loads per stage
   static constexpr int LOADS_X = XROWS / RPL;  // loads per wavefront and stage, activation panel
-  static constexpr int LOADS_W = 64 / RPL;     // ... weight panel (64 rows per wavefront)
+  static constexpr int LOADS_W = WLROWS / RPL;  // ... weight panel
   static constexpr int LPS = LOADS_X + LOADS_W;  // loads per wavefront and stage
   static constexpr int CHUNK = (LPS + NCHUNK - 1) / NCHUNK;  // most loads issued in one k-step
   // chunk c of a stage's loads = loads [chunk_begin(c), chunk_begin(c + 1))
   __host__ __device__ static constexpr int chunk_begin(int c) { return c * LPS / NCHUNK; }
-  static_assert(BM == 256 || BM == 128, "token rows per tile");
+  static_assert((BM == 256 || BM == 128) && (WM == 2 || WM == 4) && (TB == 4 || TB == 2), "tile and wave grid");
+  static_assert(XROWS % RPL == 0 && WLROWS % RPL == 0, "whole loads per wavefront");
   static_assert(BK == 64 || BK == 128, "K step");
   static_assert(NCHUNK >= 1 && NCHUNK <= KK && NCHUNK <= LPS, "load chunks per stage");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of one compute unit");
@@ -112,7 +118,7 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
   }
 }
 
-template <int OUT_KIND, bool INT_ONLY, bool VEC, int TB>
+template <int OUT_KIND, bool INT_ONLY, bool VEC, int TB, int WM>
 __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4][TB], int8_t *smem,
                                               const float *s_mult, const float *s_fb,
                                               const float *s_rs, int64_t bm0, int bn0, int wave_m,
@@ -120,7 +126,7 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
   constexpr bool I8 = OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed;  // packed int8 codes
   constexpr int ESZ = I8 ? 1 : 4;
   const int l32 = lane & 31, half = lane >> 5;
-  const int wave = wave_m + 2 * wave_n;
+  const int wave = wave_m + WM * wave_n;
   constexpr int WROWS = 32 * TB;  // token rows of the wave tile = rows of a slab
   int8_t *slab = smem + wave * (WROWS * kSlabStride);
   const int64_t row_bytes = p.ldo * ESZ;
@@ -390,12 +396,13 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
   }
 }
 
-template <int BM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
-__global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(const FwdParams p) {
-  using C = FastCfg<BM, BK, NSTAGE, NCHUNK>;
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
+__global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(const FwdParams p) {
+  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK>;
   constexpr int TB = C::TB;
-  static_assert(OUT_KIND != kOutStats || (BM == 256 && C::RING >= 4 * 32768 && C::STATS_LDS_BYTES <= 160 * 1024),
-                "statistics epilogue: full-height tile, 32 KiB of the ring per wavefront");
+  static_assert(OUT_KIND != kOutStats ||
+                    (BM == 256 && WM == 2 && C::RING >= 4 * 32768 && C::STATS_LDS_BYTES <= 160 * 1024),
+                "statistics epilogue: full-height tile, four wavefronts, 32 KiB of the ring per wavefront");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   int32_t *s_off = reinterpret_cast<int32_t *>(smem + C::RING);
   float *s_mult = reinterpret_cast<float *>(smem + C::RING + 1024);
@@ -413,20 +420,22 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(co
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave & 1, wave_n = wave >> 1;
+  const int wave_m = wave % WM, wave_n = wave / WM;
   const int l32 = lane & 31, half = lane >> 5;
 
-  // ---- epilogue parameters of this tile: issue their loads first (oldest in the load queue)
-  const int p_off = p.offset ? p.offset[bn0 + tid] : 0;
+  // ---- epilogue parameters of this tile: issue their loads first (oldest in the load queue);
+  // thread t < 256 stages channel t (and row t)
+  const int ptid = tid < 256 ? tid : 255;
+  const int p_off = p.offset ? p.offset[bn0 + ptid] : 0;
   float p_mult = 0.0f, p_fb = 0.0f, p_rs = 1.0f;
   if (OUT_KIND == kOutFixed) {  // integer multiplier and shift travel in the two float slots
-    p_mult = __int_as_float(p.m0[bn0 + tid]);
-    p_fb = __int_as_float(p.shift[bn0 + tid]);
+    p_mult = __int_as_float(p.m0[bn0 + ptid]);
+    p_fb = __int_as_float(p.shift[bn0 + ptid]);
   } else if (OUT_KIND != CWAC_OUT_INT32) {
-    p_mult = p.mult[bn0 + tid];
+    p_mult = p.mult[bn0 + ptid];
   }
   if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && OUT_KIND != kOutFixed) {
-    if (p.fbias) p_fb = p.fbias[bn0 + tid];
+    if (p.fbias) p_fb = p.fbias[bn0 + ptid];
     if (p.sx_row && tid < BM) p_rs = p.sx_row[bm0 + tid];
   }
   // pivots of the shifted sums: the state's, or for the first batch of a state its row 0
@@ -456,7 +465,7 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(co
   }
 #pragma unroll
   for (int i = 0; i < C::LOADS_W; ++i) {
-    const int row = wave * 64 + i * C::RPL + lr;
+    const int row = wave * C::WLROWS + i * C::RPL + lr;
     wvo[i] = (uint32_t)row * (uint32_t)p.ldw + (pc ^ C::swz(row)) * 16;
   }
   const int8_t *xtile = p.x + bm0 * p.ldx;
@@ -465,7 +474,7 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(co
   // chunk c of a stage's 2*LOADS loads (activation loads first, then weight loads)
   auto issue_chunk = [&](int buf, int k0, int c) {
     int8_t *sx = smem + buf * C::STAGE + wave_s * C::XROWS * BK;
-    int8_t *sw = smem + buf * C::STAGE + C::X_BYTES + wave_s * 64 * BK;
+    int8_t *sw = smem + buf * C::STAGE + C::X_BYTES + wave_s * C::WLROWS * BK;
     const int8_t *xk = xtile + k0, *wk = wtile + k0;
 #pragma unroll
     for (int j = 0; j < C::CHUNK; ++j) {
@@ -485,7 +494,7 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(co
 
   // ---- LDS -> MFMA operand fragments (rows of a 32-row MFMA tile start at multiples of 16)
   const int swz_l = C::swz(l32);
-  const int x_off = (wave_m * (BM / 2) + l32) * BK;
+  const int x_off = (wave_m * 32 * TB + l32) * BK;
   const int w_off = C::X_BYTES + (wave_n * 128 + l32) * BK;
   auto read_frags = [&](int buf, int kk, v4i(&fw)[4], v4i(&fx)[TB]) {
     const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
@@ -532,9 +541,11 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(co
 #pragma unroll
   for (int s = 0; s < NSTAGE; ++s)
     if (s < stages) issue_stage(s, s * BK);
-  s_off[tid] = p_off;
-  s_mult[tid] = p_mult;
-  s_fb[tid] = p_fb;
+  if (tid < 256) {
+    s_off[tid] = p_off;
+    s_mult[tid] = p_mult;
+    s_fb[tid] = p_fb;
+  }
   if (tid < BM) s_rs[tid] = p_rs;
   if (OUT_KIND == kOutStats) {
     s_pq[tid] = p_pq;
@@ -628,66 +639,75 @@ __global__ __launch_bounds__(256, BM == 128 ? 2 : 1) void qlinear_fast_kernel(co
     constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed) ? 1 : 4;
     const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
     if (vs)
-      fast_epilogue<OUT_KIND, INT_ONLY, true, TB>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
     else
-      fast_epilogue<OUT_KIND, INT_ONLY, false, TB>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      fast_epilogue<OUT_KIND, INT_ONLY, false, TB, WM>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
   }
 }
 
-template <int BM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
 cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
-  using C = FastCfg<BM, BK, NSTAGE, NCHUNK>;
+  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK>;
   constexpr int LDS = OUT_KIND == kOutStats ? C::STATS_LDS_BYTES : C::LDS_BYTES;
   static const hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY>),
+      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY>),
       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<BM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, 256, LDS, st>>>(p);
+  qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, C::NT, LDS, st>>>(p);
   return launch_status();
 }
 
-template <int BM, int BK, int NSTAGE, int NCHUNK>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK>
 cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   p.tiles_m = (int)ceil_div(p.m, BM);
   p.tiles_n = (int)ceil_div(p.n, 256);
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
   const dim3 grid((unsigned)blocks);
-  if (out_kind == kOutFixed) return launch_one<BM, BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
+  if (out_kind == kOutFixed) return launch_one<BM, WM, BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
   if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true>(p, grid, st)
-                    : launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false>(p, grid, st);
-  if (out_kind == CWAC_OUT_FP32) return launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false>(p, grid, st);
-  return launch_one<BM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false>(p, grid, st);
+    return int_only ? launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true>(p, grid, st)
+                    : launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false>(p, grid, st);
+  if (out_kind == CWAC_OUT_FP32) return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false>(p, grid, st);
+  return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false>(p, grid, st);
 }
 
 }  // namespace
 
-bool fast_prefers_half_tile(int64_t m, int n, int k) {
-  // Cost model fitted to measurements on ViT / Swin / LLM layer shapes (microseconds per compute
-  // unit): a 256-token tile costs 12 + 0.0104 k; two 128-token workgroups sharing a compute unit
-  // overlap each other's prologue and epilogue but move 1.5x the panel bytes per MAC: the pair
-  // costs 8 + 0.0133 k, a lone one 10 + 0.00665 k.  Tiles run in rounds of 256 (512) at a time.
+bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes) {
+  // Cost model fitted to a sweep of 140 layer shapes per output width (microseconds per compute
+  // unit).  A 256-token tile (eight wavefronts) costs a + b k.  Two 128-token workgroups sharing a
+  // compute unit overlap each other's prologue and epilogue but move 1.5x the panel bytes per MAC:
+  // the pair costs c + d k, a lone one e + f k.  Tiles run in rounds of 256 (512) at a time.
+  // The constants grow with the width of the output element (more bytes for the epilogue to store).
+  const bool wide = out_bytes > 1;
+  const double a = wide ? 10.7 : 6.05, b = wide ? 0.01112 : 0.01136;
+  const double c = wide ? 7.56 : 4.18, d = 0.01559;
+  const double e = wide ? 9.71 : 5.64, f = wide ? 0.00411 : 0.00524;
   const int64_t t_full = ceil_div(m, 256) * ceil_div(n, 256), t_half = ceil_div(m, 128) * ceil_div(n, 256);
   if (t_half < 160) return false;
-  const double cost_full = (double)ceil_div(t_full, 256) * (12.0 + 0.0104 * k);
+  const double cost_full = (double)ceil_div(t_full, 256) * (a + b * k);
   const int64_t rest = t_half % 512;
-  const double cost_half = (double)(t_half / 512) * (8.0 + 0.0133 * k) +
-                           (rest == 0 ? 0.0 : rest <= 256 ? 10.0 + 0.00665 * k : 8.0 + 0.0133 * k);
+  const double cost_half =
+      (double)(t_half / 512) * (c + d * k) + (rest == 0 ? 0.0 : rest <= 256 ? e + f * k : c + d * k);
   return cost_half < cost_full;
 }
 
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
-  // Tuning knob (same results): CWAC_FWD_PIPE=128x2 | 64x4 selects K step and ring depth of the
-  // 256-token tile; "duo" the 128-token tile, two workgroups per compute unit.
+  // Tuning knob (same results): CWAC_FWD_PIPE=8w is the 256-token tile with eight wavefronts (the
+  // default for large layers), 128x2 | 64x4 the same tile with four wavefronts and that K step
+  // and ring depth; "duo" the 128-token tile, two workgroups of four wavefronts per compute unit.
   const char *e = getenv("CWAC_FWD_PIPE");
-  if (e && e[0] == 'd') return launch_cfg<128, 64, 3, 2>(p, out_kind, int_only, st);
-  if (e && e[0] == '6') return launch_cfg<256, 64, 4, 2>(p, out_kind, int_only, st);
-  if (e && e[0] == '1') return launch_cfg<256, 128, 2, 2>(p, out_kind, int_only, st);
-  if (fast_prefers_half_tile(p.m, p.n, p.k)) return launch_cfg<128, 64, 3, 2>(p, out_kind, int_only, st);
-  return launch_cfg<256, 128, 2, 2>(p, out_kind, int_only, st);
+  if (e && e[0] == 'd') return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
+  if (e && e[0] == '6') return launch_cfg<256, 2, 64, 4, 2>(p, out_kind, int_only, st);
+  if (e && e[0] == '8') return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
+  if (e && e[0] == '1') return launch_cfg<256, 2, 128, 2, 2>(p, out_kind, int_only, st);
+  const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
+  if (fast_prefers_half_tile(p.m, p.n, p.k, out_bytes))
+    return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
+  return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
 }
 
 cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {
@@ -696,7 +716,7 @@ cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {
   p.vec_store = 0;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  return launch_one<256, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
+  return launch_one<256, 2, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
 }
 
 }  // namespace cwac

@@ -234,7 +234,8 @@ static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_o
   int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
   const bool fast_ok = m >= kFastTile && n >= kFastTile && (k % kFastKStep) == 0;
   // the large-problem kernel wants most compute units busy: 160 full tiles, or 256 half tiles
-  bool fast = fast_ok && (t256 >= 160 || fast_prefers_half_tile(m, n, k));
+  const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
+  bool fast = fast_ok && (t256 >= 160 || fast_prefers_half_tile(m, n, k, out_bytes));
   // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
   // the large-problem kernel where its shape constraints hold (results are identical).
   if (const char *e = getenv("CWAC_FWD_TILE")) {
