@@ -53,10 +53,8 @@ struct FastCfg {
   static constexpr int RING = NSTAGE * STAGE;
   static constexpr int PARAM_BYTES = 4 * 256 * 4;  // offset, mult, fbias [256 channels], row scale [256 rows]
   static constexpr int LDS_BYTES = RING + PARAM_BYTES;
-  // statistics epilogue: + the two pivots of the 256 channels and the area through which the lower
-  // row half of the tile hands its sums to the upper one ([2 wave columns][4][kStats][32] fp64)
-  static constexpr int STATS_EXCH = RING + PARAM_BYTES + 2 * 256 * 4;
-  static constexpr int STATS_LDS_BYTES = STATS_EXCH + 2 * 4 * kStats * 32 * 8;
+  // statistics epilogue: + the two pivots of the 256 channels
+  static constexpr int STATS_LDS_BYTES = RING + PARAM_BYTES + 2 * 256 * 4;
   static constexpr int CPR = BK / 16;        // 16-byte chunks per row
   static constexpr int RPL = 64 / CPR;       // rows covered by one wavefront load
   static constexpr int XROWS = BM / NWAVES;   // activation rows each wavefront loads per stage
@@ -244,20 +242,21 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
 // Y_full is read once.
 //
 // The accumulators hold a channel's rows spread over 32 lanes, the sums need them in one lane.
-// So each wavefront works in 8 phases of (32 channels) x (64 rows): it writes the phase's Y_quant
-// values to a private LDS slab, Y_full of the same rows and channels arrives in a second slab
-// straight from global memory (global_load_lds, issued two phases ahead), and then lane (c, h)
-// walks rows h, h + 2, ... of channel c in both slabs with fp64 sums.  Slab layout: row-major, 128
-// bytes per row, the 16-byte chunk position XORed with (row & 7): conflict-free for the 16-byte
-// row writes and for the 4-byte column reads (the two half-waves read rows of different parity).
-// Rows below `skip` (an edge tile shifted inwards: rows its upper neighbour already counts)
-// contribute zeros.
-template <bool MASKED>
+// So each wavefront works in 8 phases of (32 channels) x (PR = 16 * TB rows, half its wave tile):
+// it writes the phase's Y_quant values to a private LDS slab, Y_full of the same rows and
+// channels arrives in a second slab straight from global memory (global_load_lds, issued two
+// phases ahead), and then lane (c, h) walks rows h, h + 2, ... of channel c in both slabs with
+// fp64 sums.  Slab layout: row-major, 128 bytes per row, the 16-byte chunk position XORed with
+// (row & 7): conflict-free for the 16-byte row writes and for the 4-byte column reads (the two
+// half-waves read rows of different parity).  A wavefront owns four slabs (Y_quant, three of
+// Y_full) of PR * 128 bytes in the ring, which the main loop has left.  Rows below `skip` (an edge
+// tile shifted inwards: rows its upper neighbour already counts) contribute zeros.
+template <bool MASKED, int PR>
 __device__ __forceinline__ void stats_column_pass(const int8_t *yq_slab, const int8_t *yf_slab,
                                                   const int (&o4)[4], int h, float pq, float pf,
                                                   int row0, int skip, double (&sum)[kStats]) {
 #pragma unroll 8
-  for (int j = 0; j < 32; ++j) {
+  for (int j = 0; j < PR / 2; ++j) {
     const int off = o4[j & 3] + (j >> 2) * 1024;
     float q = *reinterpret_cast<const float *>(yq_slab + off) - pq;
     float f = *reinterpret_cast<const float *>(yf_slab + off) - pf;
@@ -275,37 +274,42 @@ __device__ __forceinline__ void stats_column_pass(const int8_t *yq_slab, const i
   }
 }
 
-__device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4][4], int8_t *smem,
+template <int TB, int WM>
+__device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4][TB], int8_t *smem,
                                                const float *s_mult, const float *s_fb,
                                                const float *s_rs, const float *s_pq,
-                                               const float *s_pf, double *s_exch, int64_t bm0, int bn0,
-                                               int tile_m, int wave_m, int wave_n, int wave_s,
-                                               int lane) {
+                                               const float *s_pf, int64_t bm0, int bn0, int tile_m,
+                                               int wave_m, int wave_n, int wave_s, int lane) {
+  constexpr int WROWS = 32 * TB;    // token rows of the wave tile
+  constexpr int PR = WROWS / 2;     // rows per phase
+  constexpr int SLAB = PR * 128;    // bytes per slab
+  constexpr int YL = PR / 8;        // Y_full loads per phase (8 rows x 128 bytes each)
+  static_assert(2 * WM * 4 * SLAB <= 131072, "the slabs of all wavefronts fit the ring");
   const int l32 = lane & 31, half = lane >> 5;
-  int8_t *wl = smem + (wave_s << 15);  // this wavefront's 32 KiB: Y_quant slab, three Y_full slabs
+  int8_t *wl = smem + wave_s * (4 * SLAB);  // this wavefront's slabs: Y_quant, three of Y_full
   int8_t *yq_slab = wl;
   const bool use_rs = p.sx_row != nullptr, use_fb = p.fbias != nullptr;
   // rows of this wave tile that the tile above already counts
-  int64_t skip64 = (int64_t)tile_m * 256 - (bm0 + wave_m * 128);
-  const int skip = skip64 < 0 ? 0 : (skip64 > 128 ? 128 : (int)skip64);
+  int64_t skip64 = (int64_t)tile_m * 256 - (bm0 + wave_m * WROWS);
+  const int skip = skip64 < 0 ? 0 : (skip64 > WROWS ? WROWS : (int)skip64);
 
   // Y_full loads: one instruction = 8 rows x 128 bytes; lane (row lr, slot) fetches chunk slot ^ lr
   const int lr = lane >> 3, slot = lane & 7;
   const uint32_t yvo = (uint32_t)lr * (uint32_t)(p.ld_full * 4) + (uint32_t)((slot ^ lr) << 4);
-  const char *yf_wave = reinterpret_cast<const char *>(p.y_full + (bm0 + wave_m * 128) * p.ld_full + bn0 +
+  const char *yf_wave = reinterpret_cast<const char *>(p.y_full + (bm0 + wave_m * WROWS) * p.ld_full + bn0 +
                                                        wave_n * 128);
   auto issue_yf = [&](int phase) {
     const int a = phase >> 1, hb = phase & 1;
-    const char *g = yf_wave + ((int64_t)hb * 64 * p.ld_full + a * 32) * 4;
-    int8_t *dst = wl + 8192 * (1 + phase % 3);
+    const char *g = yf_wave + ((int64_t)hb * PR * p.ld_full + a * 32) * 4;
+    int8_t *dst = wl + SLAB * (1 + phase % 3);
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < YL; ++i)
       __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(g + (int64_t)i * 8 * p.ld_full * 4 + yvo),
                                        CWAC_LDS_PTR(dst + i * 1024), 16, 0, 0);
   };
-  float rs[4];
+  float rs[TB];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) rs[b] = s_rs[wave_m * 128 + b * 32 + l32];
+  for (int b = 0; b < TB; ++b) rs[b] = s_rs[wave_m * WROWS + b * 32 + l32];
   // column pass: lane (channel c, row parity h); offsets of rows h, 2 + h, 4 + h, 6 + h
   const int c = l32, h = half;
   int o4[4];
@@ -338,10 +342,10 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
 #pragma unroll
     for (int hb = 0; hb < 2; ++hb) {
       const int phase = 2 * a + hb;
-      // Y_quant of rows hb*64 .. +63, channels a*32 .. +31 (the arithmetic of the fp32 output mode)
+      // Y_quant of rows hb*PR .. +PR-1, channels a*32 .. +31 (the arithmetic of the fp32 output mode)
 #pragma unroll
-      for (int bb = 0; bb < 2; ++bb) {
-        const int b = 2 * hb + bb;
+      for (int bb = 0; bb < TB / 2; ++bb) {
+        const int b = (TB / 2) * hb + bb;
         const int row = bb * 32 + l32;
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -361,28 +365,35 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
       __builtin_amdgcn_sched_barrier(0);
       if (phase + 2 < 8) {
         issue_yf(phase + 2);
-        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(16, 0));
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(2 * YL, 0));
       } else if (phase + 1 < 8) {
-        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(8, 0));
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(YL, 0));
       } else {
         __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
       }
       asm volatile("" ::: "memory");  // the slab reads below stay below the wait
       __builtin_amdgcn_sched_barrier(0);
-      const int8_t *yf_slab = wl + 8192 * (1 + phase % 3);
+      const int8_t *yf_slab = wl + SLAB * (1 + phase % 3);
       if (skip == 0)
-        stats_column_pass<false>(yq_slab, yf_slab, o4, h, pq, pf, hb * 64, skip, sum);
+        stats_column_pass<false, PR>(yq_slab, yf_slab, o4, h, pq, pf, hb * PR, skip, sum);
       else
-        stats_column_pass<true>(yq_slab, yf_slab, o4, h, pq, pf, hb * 64, skip, sum);
+        stats_column_pass<true, PR>(yq_slab, yf_slab, o4, h, pq, pf, hb * PR, skip, sum);
       __builtin_amdgcn_sched_barrier(0);  // the slabs are rewritten next: keep the reads above
     }
-    // rows of both parities, then the lower wave row hands over to the upper one
+    // rows of both parities
 #pragma unroll
-    for (int s = 0; s < kStats; ++s) {
-      sum[s] += __shfl_xor(sum[s], 32, 64);
-      tot[a][s] = sum[s];
-      if (wave_m == 1 && lane < 32) s_exch[((wave_n * 4 + a) * kStats + s) * 32 + c] = sum[s];
-    }
+    for (int s = 0; s < kStats; ++s) tot[a][s] = sum[s] + __shfl_xor(sum[s], 32, 64);
+  }
+  // The lower wave rows hand their sums to the top one through LDS (over the slabs, once every
+  // wavefront has left them): exch[wave row - 1][wave column][a][stat][channel], fp64.
+  double *exch = reinterpret_cast<double *>(smem);
+  __syncthreads();
+  if (wave_m > 0 && lane < 32) {
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int s = 0; s < kStats; ++s)
+        exch[((((wave_m - 1) * 2 + wave_n) * 4 + a) * kStats + s) * 32 + c] = tot[a][s];
   }
   __syncthreads();
   if (wave_m == 0 && lane < 32) {
@@ -390,7 +401,9 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
     for (int a = 0; a < 4; ++a)
 #pragma unroll
       for (int s = 0; s < kStats; ++s) {
-        const double t = tot[a][s] + s_exch[((wave_n * 4 + a) * kStats + s) * 32 + c];
+        double t = tot[a][s];
+#pragma unroll
+        for (int r = 1; r < WM; ++r) t += exch[((((r - 1) * 2 + wave_n) * 4 + a) * kStats + s) * 32 + c];
         p.partial[((int64_t)tile_m * kStats + s) * p.n + bn0 + wave_n * 128 + a * 32 + c] = t;
       }
   }
@@ -400,9 +413,8 @@ template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT
 __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(const FwdParams p) {
   using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK>;
   constexpr int TB = C::TB;
-  static_assert(OUT_KIND != kOutStats ||
-                    (BM == 256 && WM == 2 && C::RING >= 4 * 32768 && C::STATS_LDS_BYTES <= 160 * 1024),
-                "statistics epilogue: full-height tile, four wavefronts, 32 KiB of the ring per wavefront");
+  static_assert(OUT_KIND != kOutStats || (BM == 256 && C::RING >= 131072 && C::STATS_LDS_BYTES <= 160 * 1024),
+                "statistics epilogue: full-height tile, 128 KiB of ring for the slabs");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   int32_t *s_off = reinterpret_cast<int32_t *>(smem + C::RING);
   float *s_mult = reinterpret_cast<float *>(smem + C::RING + 1024);
@@ -443,11 +455,11 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
   if (OUT_KIND == kOutStats) {
     const StatsView sv = stats_view(const_cast<void *>(p.stats), p.n);
     if (*sv.n == 0) {
-      p_pq = p.yq_row0[bn0 + tid];
-      p_pf = p.y_full[bn0 + tid];
+      p_pq = p.yq_row0[bn0 + ptid];
+      p_pf = p.y_full[bn0 + ptid];
     } else {
-      p_pq = sv.pivot_q[bn0 + tid];
-      p_pf = sv.pivot_f[bn0 + tid];
+      p_pq = sv.pivot_q[bn0 + ptid];
+      p_pf = sv.pivot_f[bn0 + ptid];
     }
   }
 
@@ -547,7 +559,7 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
     s_fb[tid] = p_fb;
   }
   if (tid < BM) s_rs[tid] = p_rs;
-  if (OUT_KIND == kOutStats) {
+  if (OUT_KIND == kOutStats && tid < 256) {
     s_pq[tid] = p_pq;
     s_pf[tid] = p_pf;
   }
@@ -631,9 +643,8 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
 
   if constexpr (OUT_KIND == kOutStats) {
     __builtin_amdgcn_s_barrier();  // every wavefront is done with the ring, which the slabs overlay
-    stats_epilogue(p, acc, smem, s_mult, s_fb, s_rs, s_pq, s_pf,
-                   reinterpret_cast<double *>(smem + C::STATS_EXCH), bm0, bn0, tile_m, wave_m, wave_n,
-                   wave_s, lane);
+    stats_epilogue<TB, WM>(p, acc, smem, s_mult, s_fb, s_rs, s_pq, s_pf, bm0, bn0, tile_m, wave_m, wave_n,
+                           wave_s, lane);
   } else {
     // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
     constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed) ? 1 : 4;
@@ -716,7 +727,11 @@ cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {
   p.vec_store = 0;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  return launch_one<256, 2, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
+  // Tuning knob: CWAC_STATS_PIPE=4w keeps four wavefronts per tile (the fp64 sums then add up in
+  // another order).
+  const char *e = getenv("CWAC_STATS_PIPE");
+  if (e && e[0] == '4') return launch_one<256, 2, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
+  return launch_one<256, 4, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
 }
 
 }  // namespace cwac

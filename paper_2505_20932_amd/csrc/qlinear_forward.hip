@@ -329,6 +329,12 @@ extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q
   if (!aligned(out, esz)) return CWAC_E_ALIGN;
   p.vec_store = ((ldo * esz) % (4 * esz) == 0) && aligned(out, 4 * esz);
   const bool int_only = (out_kind == CWAC_OUT_INT8) && !fbias;
+  hipStream_t st = as_stream(stream);
+  if (kh == 1 && kw == 1 && stride == 1 && pad == 0) {
+    // a pointwise convolution is the linear layer on the [batch * h * w, c_in] matrix
+    p.ldx = c_in;
+    return dispatch_forward(p, out_kind, int_only, st);
+  }
   const int64_t t256 = ceil_div(m, 256) * ceil_div(c_out, 256);
   const int64_t t128 = ceil_div(m, 128) * ceil_div(c_out, 128);
   int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
@@ -339,7 +345,6 @@ extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q
     const int v = atoi(e);
     if (v == 256 || v == 128 || v == 64) tile = v;
   }
-  hipStream_t st = as_stream(stream);
   if (tile == 256) return launch_tile<256, 256, 128, 2, 2, true>(p, out_kind, int_only, st);
   if (tile == 128) return launch_tile<128, 128, 128, 2, 2, true>(p, out_kind, int_only, st);
   return launch_tile<64, 64, 128, 2, 2, true>(p, out_kind, int_only, st);

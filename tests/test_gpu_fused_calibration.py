@@ -87,8 +87,14 @@ def _two_calls(xq, wq, mult, off, fb, sxr, yf, st):
     (700, 1028, 1152, False, True),     # several tiles, ragged tail of 188 rows / 4 channels
     (513, 768, 256, True, False),       # a last row tile that keeps a single row
 ])
-def test_fused_calibration_against_oracle(orc, m, n, k, per_token, bias):
-    print(f"fused calibration {m} x {n} x {k} per_token={per_token} bias={bias}", flush=True)
+@pytest.mark.parametrize("pipe", [None, "4w"])
+def test_fused_calibration_against_oracle(orc, monkeypatch, m, n, k, per_token, bias, pipe):
+    """`pipe`: the default tile of eight wavefronts, or the four-wavefront shape of the same kernel."""
+    print(f"fused calibration {m} x {n} x {k} per_token={per_token} bias={bias} pipe={pipe}", flush=True)
+    if pipe:
+        monkeypatch.setenv("CWAC_STATS_PIPE", pipe)
+    else:
+        monkeypatch.delenv("CWAC_STATS_PIPE", raising=False)
     xq, wq, mult, off, fb, sxr, yq, yf = _inputs(orc, 4100 + m, m, n, k, per_token, bias)
     ref = orc.channel_moments(yf, yq)
     a0, b0, _ = orc.solve(ref)
