@@ -37,6 +37,16 @@ namespace {
 #define CWAC_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 #define CWAC_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
+// Convolution: the 16 bytes a load fetches for a filter tap outside the image.  Row c holds the
+// code c sixteen times; a direct-to-LDS load cannot substitute a value, so it is pointed here.
+struct PadCodes {
+  uint8_t v[256 * 16];
+  constexpr PadCodes() : v() {
+    for (int i = 0; i < 256 * 16; ++i) v[i] = (uint8_t)(i >> 4);
+  }
+};
+__device__ __attribute__((aligned(16))) const PadCodes kPadCodes{};
+
 constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
   // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14 ; expcnt = 7 (no wait)
   return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
@@ -409,7 +419,7 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
   }
 }
 
-template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false>
 __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(const FwdParams p) {
   using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK>;
   constexpr int TB = C::TB;
@@ -470,29 +480,72 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int lr = lane / C::CPR, pc = lane % C::CPR;
   uint32_t xvo[C::LOADS_X], wvo[C::LOADS_W];
+  // Convolution (implicit GEMM; c_in % BK == 0, so a stage lies inside ONE filter tap and the tap
+  // is wave-uniform): row m = (b, oy, ox) reads the image at (oy * stride - pad + kh, ox * stride -
+  // pad + kw).  Per load: xvo = byte offset of tap (0, 0), channel chunk included (it may lie
+  // before the image: only taps inside it are dereferenced); xin = bit kh set where row kh of the
+  // filter falls inside the image, bit 16 + kw likewise for its columns.
+  uint32_t xin[C::LOADS_X];
 #pragma unroll
   for (int i = 0; i < C::LOADS_X; ++i) {
     const int row = wave * C::XROWS + i * C::RPL + lr;
-    xvo[i] = (uint32_t)row * (uint32_t)p.ldx + (pc ^ C::swz(row)) * 16;
+    if (CONV) {
+      const int r = (int)bm0 + row, plane = p.cv_oh * p.cv_ow;
+      const int b = r / plane, rem = r - b * plane;
+      const int oy = rem / p.cv_ow, ox = rem - oy * p.cv_ow;
+      const int iy0 = oy * p.cv_stride - p.cv_pad, ix0 = ox * p.cv_stride - p.cv_pad;
+      xvo[i] = (uint32_t)(((b * p.cv_h + iy0) * p.cv_w + ix0) * p.cv_cin + (pc ^ C::swz(row)) * 16);
+      // taps kh with 0 <= iy0 + kh < h: kh in [max(0, -iy0), min(15, h - 1 - iy0)] (never empty)
+      auto span = [](int lo, int hi) {
+        lo = lo < 0 ? 0 : lo;
+        hi = hi > 15 ? 15 : hi;
+        return ((2u << hi) - 1u) & ~((1u << lo) - 1u);
+      };
+      xin[i] = span(-iy0, p.cv_h - 1 - iy0) | (span(-ix0, p.cv_w - 1 - ix0) << 16);
+    } else {
+      xvo[i] = (uint32_t)row * (uint32_t)p.ldx + (pc ^ C::swz(row)) * 16;
+    }
   }
 #pragma unroll
   for (int i = 0; i < C::LOADS_W; ++i) {
     const int row = wave * C::WLROWS + i * C::RPL + lr;
     wvo[i] = (uint32_t)row * (uint32_t)p.ldw + (pc ^ C::swz(row)) * 16;
   }
-  const int8_t *xtile = p.x + bm0 * p.ldx;
+  const int8_t *xtile = CONV ? p.x : p.x + bm0 * p.ldx;
   const int8_t *wtile = p.w + (int64_t)bn0 * p.ldw;
+  // convolution: the tap of the stage whose loads are being issued (wave-uniform; stages are
+  // loaded in order, so it steps forward at the first chunk of every stage after stage 0)
+  int tap_c = 0, tap_kw = 0, tap_kh = 0;
+  int tap_off = 0;           // byte offset of the tap and channel block from tap (0, 0), channel 0
+  uint32_t tap_sel = 0x10001u;  // bit kh | bit 16 + kw
+  const int8_t *pad = reinterpret_cast<const int8_t *>(kPadCodes.v) + (p.cv_pad4 & 255) * 16;
 
   // chunk c of a stage's 2*LOADS loads (activation loads first, then weight loads)
   auto issue_chunk = [&](int buf, int k0, int c) {
     int8_t *sx = smem + buf * C::STAGE + wave_s * C::XROWS * BK;
     int8_t *sw = smem + buf * C::STAGE + C::X_BYTES + wave_s * C::WLROWS * BK;
     const int8_t *xk = xtile + k0, *wk = wtile + k0;
+    if (CONV && c == 0 && k0 != 0) {
+      tap_c += BK;
+      if (tap_c >= p.cv_cin) {
+        tap_c = 0;
+        if (++tap_kw == p.cv_kw) {
+          tap_kw = 0;
+          ++tap_kh;
+        }
+      }
+      tap_off = (tap_kh * p.cv_w + tap_kw) * p.cv_cin + tap_c;
+      tap_sel = (1u << tap_kh) | (0x10000u << tap_kw);
+    }
 #pragma unroll
     for (int j = 0; j < C::CHUNK; ++j) {
       const int i = C::chunk_begin(c) + j;
       if (i >= C::chunk_begin(c + 1)) break;
-      if (i < C::LOADS_X)
+      if (i < C::LOADS_X && CONV) {
+        const bool inside = (xin[i] & tap_sel) == tap_sel;
+        const int8_t *src = inside ? xtile + (uint32_t)(xvo[i] + (uint32_t)tap_off) : pad;
+        __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(src), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
+      } else if (i < C::LOADS_X)
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
       else
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wk + wvo[i - C::LOADS_X]),
@@ -656,31 +709,34 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
   }
 }
 
-template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false>
 cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
   using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK>;
   constexpr int LDS = OUT_KIND == kOutStats ? C::STATS_LDS_BYTES : C::LDS_BYTES;
   static const hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY>),
+      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV>),
       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY><<<grid, C::NT, LDS, st>>>(p);
+  qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV><<<grid, C::NT, LDS, st>>>(p);
   return launch_status();
 }
 
-template <int BM, int WM, int BK, int NSTAGE, int NCHUNK>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, bool CONV = false>
 cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   p.tiles_m = (int)ceil_div(p.m, BM);
   p.tiles_n = (int)ceil_div(p.n, 256);
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
   const dim3 grid((unsigned)blocks);
-  if (out_kind == kOutFixed) return launch_one<BM, WM, BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
+  if constexpr (!CONV) {
+    if (out_kind == kOutFixed) return launch_one<BM, WM, BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
+  }
   if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true>(p, grid, st)
-                    : launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false>(p, grid, st);
-  if (out_kind == CWAC_OUT_FP32) return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false>(p, grid, st);
-  return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false>(p, grid, st);
+    return int_only ? launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true, CONV>(p, grid, st)
+                    : launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false, CONV>(p, grid, st);
+  if (out_kind == CWAC_OUT_FP32)
+    return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false, CONV>(p, grid, st);
+  return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false, CONV>(p, grid, st);
 }
 
 }  // namespace
@@ -719,6 +775,25 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   if (fast_prefers_half_tile(p.m, p.n, p.k, out_bytes))
     return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
   return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
+}
+
+bool fast_conv_ok(const FwdParams &p, int64_t image_bytes) {
+  return p.m >= kFastTile && p.m < ((int64_t)1 << 31) && p.n >= kFastTile && (p.k % kFastKStep) == 0 &&
+         (p.cv_cin % 64) == 0 && image_bytes < ((int64_t)1 << 31);
+}
+
+cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
+  const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
+  p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
+  // a stage must lie inside one filter tap: the 256-token tile steps K by 128, the 128-token tile by 64
+  const bool full_ok = (p.cv_cin % 128) == 0;
+  const char *e = getenv("CWAC_FWD_PIPE");  // tuning knob (same results): "8w" | "duo"
+  bool half = !full_ok || fast_prefers_half_tile(p.m, p.n, p.k, (int)esz) ||
+              ceil_div(p.m, 256) * ceil_div(p.n, 256) < 160;
+  if (e && e[0] == 'd') half = true;
+  if (e && e[0] == '8' && full_ok) half = false;
+  if (half) return launch_cfg<128, 2, 64, 3, 2, true>(p, out_kind, int_only, st);
+  return launch_cfg<256, 4, 128, 2, 2, true>(p, out_kind, int_only, st);
 }
 
 cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {

@@ -341,10 +341,22 @@ extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q
   // narrow layers: a tile much wider than the layer would multiply mostly padding
   if (c_out <= 160 && tile > 128) tile = 128;
   if (c_out <= 80 && tile > 64) tile = 64;
+  // the direct-to-LDS kernel where its shape constraints hold and its 128 x 256 tiles occupy at
+  // least a quarter of the compute units (measured on ResNet-50 layer shapes: ahead of the generic
+  // kernel's small tiles from there on)
+  const int64_t image_bytes = (int64_t)batch * h * w * c_in;
+  const bool fast_ok = fast_conv_ok(p, image_bytes);
+  bool fast = fast_ok && ceil_div(m, 128) * ceil_div(c_out, 256) >= 64;
   if (const char *e = getenv("CWAC_FWD_TILE")) {  // testing / tuning knob, as for the linear layer
     const int v = atoi(e);
-    if (v == 256 || v == 128 || v == 64) tile = v;
+    if (v == 256 || v == 128 || v == 64) {
+      tile = v;
+      fast = false;
+    } else if (e[0] == 'f') {
+      fast = fast_ok;
+    }
   }
+  if (fast) return launch_fast_conv(p, out_kind, int_only, st);
   if (tile == 256) return launch_tile<256, 256, 128, 2, 2, true>(p, out_kind, int_only, st);
   if (tile == 128) return launch_tile<128, 128, 128, 2, 2, true>(p, out_kind, int_only, st);
   return launch_tile<64, 64, 128, 2, 2, true>(p, out_kind, int_only, st);

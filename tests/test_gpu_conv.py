@@ -18,7 +18,8 @@ def dev(a):
     return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def _conv(xq, wq, stride, pad, qp, out_kind, mult=None, offset=None, fbias=None, tile=None, ldo=None):
+def _conv(xq, wq, stride, pad, qp, out_kind, mult=None, offset=None, fbias=None, tile=None, ldo=None,
+          pipe=None):
     b, h, w, _ = xq.shape
     n, kh, kw, _ = wq.shape
     oh, ow = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad - kw) // stride + 1
@@ -27,11 +28,14 @@ def _conv(xq, wq, stride, pad, qp, out_kind, mult=None, offset=None, fbias=None,
     view = full[:, :n]
     if tile is not None:
         os.environ["CWAC_FWD_TILE"] = str(tile)
+    if pipe is not None:
+        os.environ["CWAC_FWD_PIPE"] = pipe
     try:
         P.qconv2d_cwac_forward(dev(xq), dev(wq), stride, pad, qp, dev(mult), dev(offset), dev(fbias),
                                out_kind, view)
     finally:
         os.environ.pop("CWAC_FWD_TILE", None)
+        os.environ.pop("CWAC_FWD_PIPE", None)
     torch.cuda.synchronize()
     got = full.cpu().numpy()
     if ldo:
@@ -76,6 +80,47 @@ def test_conv_all_modes(orc, shape, tile):
     _, want = orc.folded_forward(acc, off, mult, 0, fb, want_f32=True)
     got = _conv(xq, wq, stride, pad, qp, P.CWAC_OUT_FP32, mult, off, fbias=fb, tile=tile, ldo=ldo)
     np.testing.assert_array_equal(got, want)
+
+
+FAST_SHAPES = [  # batch, h, w, c_in, c_out, kh, kw, stride, pad, pipes
+    (2, 14, 14, 128, 256, 3, 3, 1, 1, ("8w", "duo")),     # ResNet-style 3x3, two row tiles that overlap
+    (5, 12, 11, 64, 300, 4, 4, 1, 2, ("duo",)),           # 64 channels: one K step per tap; ragged channel edge
+    (2, 23, 21, 128, 256, 7, 7, 2, 3, ("8w", "duo")),     # 7x7 / 2 with padding 3: most taps of the border rows are outside
+    (3, 10, 16, 256, 260, 3, 5, 1, 2, ("8w", "duo")),     # rectangular filter, two K steps per tap
+    (24, 9, 7, 128, 256, 3, 3, 2, 0, ("8w",)),            # stride 2 without padding
+]
+
+
+@pytest.mark.parametrize("shape", FAST_SHAPES)
+def test_conv_direct_to_lds_kernel(orc, shape):
+    """The large-layer kernel (forced) as an implicit-GEMM convolution, in both tile shapes: padding
+    taps come from a table of constant codes, every stage of K lies inside one filter tap."""
+    b, h, w, c, n, kh, kw, stride, pad, pipes = shape
+    seed = 900 + h * 31 + c + kh
+    xq = np.clip(np.rint(synth.normal(seed, 0, b * h * w * c).numpy() * 50), -128, 127).astype(np.int8)
+    xq = xq.reshape(b, h, w, c)
+    wq = np.clip(np.rint(synth.normal(seed, 1, n * kh * kw * c).numpy() * 50), -127, 127).astype(np.int8)
+    wq = wq.reshape(n, kh, kw, c)
+    zx, zr = 9, -3
+    acc = orc.conv2d_i8(xq, wq, stride, pad, zx)
+    assert acc.shape[0] >= 256
+    colsum = orc.colsum_i8(wq.reshape(n, -1))
+    mult = (np.abs(synth.normal(seed, 2, n).numpy()) * 3e-4 + 1e-5).astype(np.float32)
+    off = (np.rint(synth.normal(seed, 3, n).numpy() * 300).astype(np.int64) - zx * colsum).astype(np.int32)
+    fb = synth.normal(seed, 4, n).numpy().astype(np.float32)
+    qp = P.make_qparams(z_x=zx, z_r=zr)
+    for pipe in pipes:
+        print(f"conv {shape[:9]} direct-to-LDS kernel, pipe {pipe}", flush=True)
+        kw_ = dict(tile="fast", pipe=pipe, ldo=n + 16 if pipe == "duo" else None)
+        got = _conv(xq, wq, stride, pad, qp, P.CWAC_OUT_INT32, **kw_)
+        np.testing.assert_array_equal(got, acc)
+        got = _conv(xq, wq, stride, pad, qp, P.CWAC_OUT_INT8, mult, off, **kw_)
+        np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, zr))
+        got = _conv(xq, wq, stride, pad, qp, P.CWAC_OUT_INT8, mult, off, fbias=fb, **kw_)
+        np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, zr, fb))
+        _, want = orc.folded_forward(acc, off, mult, 0, fb, want_f32=True)
+        got = _conv(xq, wq, stride, pad, qp, P.CWAC_OUT_FP32, mult, off, fbias=fb, **kw_)
+        np.testing.assert_array_equal(got, want)
 
 
 @pytest.mark.parametrize("kh,kw,pad", [(1, 7, 0), (7, 1, 0), (3, 5, 2), (5, 3, 1)])
@@ -170,10 +215,12 @@ def test_conv_calibration_pipeline(orc):
     np.testing.assert_array_equal(out.cpu().numpy(), want)
 
 
-def test_conv_large_layer_sampled(orc):
-    """A ResNet-50-sized 3x3 layer at batch 64 (M = 12544, K = 2304) in the automatic tile choice;
-    the oracle checks whole images (first, last) position by position."""
-    b, h, w, c, n, k = 64, 14, 14, 256, 256, 3
+@pytest.mark.parametrize("b", [64, 128])
+def test_conv_large_layer_sampled(orc, b):
+    """A ResNet-50-sized 3x3 layer at batch 64 and 128 (M = 12544 / 25088, K = 2304) in the automatic
+    kernel choice (the generic kernel / the direct-to-LDS kernel); the oracle checks whole images
+    (first, last) position by position."""
+    h, w, c, n, k = 14, 14, 256, 256, 3
     xq = torch.randint(-128, 128, (b, h, w, c), dtype=torch.int8, device=DEV,
                        generator=torch.Generator(device=DEV).manual_seed(5))
     wq = torch.randint(-127, 128, (n, k, k, c), dtype=torch.int8, device=DEV,
