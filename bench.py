@@ -478,6 +478,172 @@ def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: 
     return res
 
 
+# ResNet-50 bottleneck convolutions (stages 2-5; H = W of the layer's input at 224 x 224 images):
+# name, H, C_in, C_out, filter, stride, padding
+RESNET50_CONVS = (
+    ("s2 1x1 256->64", 56, 256, 64, 1, 1, 0), ("s2 3x3 64->64", 56, 64, 64, 3, 1, 1),
+    ("s2 1x1 64->256", 56, 64, 256, 1, 1, 0),
+    ("s3 1x1 512->128", 28, 512, 128, 1, 1, 0), ("s3 3x3 128->128", 28, 128, 128, 3, 1, 1),
+    ("s3 1x1 128->512", 28, 128, 512, 1, 1, 0),
+    ("s4 1x1 1024->256", 14, 1024, 256, 1, 1, 0), ("s4 3x3 256->256", 14, 256, 256, 3, 1, 1),
+    ("s4 1x1 256->1024", 14, 256, 1024, 1, 1, 0),
+    ("s5 1x1 2048->512", 7, 2048, 512, 1, 1, 0), ("s5 3x3 512->512", 7, 512, 512, 3, 1, 1),
+    ("s5 1x1 512->2048", 7, 512, 2048, 1, 1, 0),
+    ("s3 3x3/2 128->128", 56, 128, 128, 3, 2, 1), ("s4 3x3/2 256->256", 28, 256, 256, 3, 2, 1),
+    ("s5 3x3/2 512->512", 14, 512, 512, 3, 2, 1),
+)
+
+
+def conv_section(P, synth, torch, dev: str, batch: int, steps: int, cpu_batch: int):
+    """Quantized convolutional layers with the CWAC epilogue (Sec. 3.3-3.4 applied to a CNN): the 15
+    distinct bottleneck convolutions of ResNet-50 on synthetic post-ReLU images.  A step = for every
+    layer: calibration forward (fp32 out) -> statistics -> fit -> fold -> compensated int8 forward;
+    the int8 forward is the kernel the roofline is for.  Y_full comes from torch's fp32 convolution
+    (upstream of the path, set-up)."""
+    import numpy as np
+    import torch.nn.functional as F
+    f32 = dict(dtype=torch.float32, device=dev)
+    layers = []
+    for li, (name, h, c, n, k, stride, pad) in enumerate(RESNET50_CONVS):
+        L = LayerState()
+        L.name, L.h, L.c, L.n, L.kf, L.stride, L.pad = name, h, c, n, k, stride, pad
+        L.oh = (h + 2 * pad - k) // stride + 1
+        L.m, L.k = batch * L.oh * L.oh, k * k * c
+        seed = 7000 + li
+        xf = torch.relu(synth.normal(seed, 0, batch * h * h * c, device=dev)).view(batch, h, h, c)
+        xf[..., 3::37] *= 6.0                                     # a few strong channels
+        wf = (synth.normal(seed, 1, n * k * k * c, device=dev) * (2.0 / L.k) ** 0.5).view(n, L.k)
+        L.bias = synth.normal(seed, 2, n, device=dev) * 0.05
+        L.wq = torch.empty(n, L.k, dtype=torch.int8, device=dev)
+        L.sw = torch.empty(n, **f32)
+        P.cwac_quantize_rows_sym(wf, L.sw, L.wq)
+        L.colsum = torch.empty(n, dtype=torch.int32, device=dev)
+        P.cwac_colsum(L.wq, L.colsum)
+        mm = torch.empty(2, **f32)
+        ws = torch.empty(P.cwac_range_workspace(xf.numel()), dtype=torch.uint8, device=dev)
+        P.cwac_range_f32(xf, mm, ws)
+        mn, mx = (float(v) for v in mm.cpu())
+        L.sx, z_u = P.cwac_qparams_from_range(mn, mx, 8)
+        L.zx = z_u - 128
+        L.xq = torch.empty(batch, h, h, c, dtype=torch.int8, device=dev)
+        P.cwac_quantize_act(xf.view(-1, c), L.sx, L.zx, L.xq.view(-1, c))
+        w4 = wf.view(n, k, k, c).permute(0, 3, 1, 2).contiguous()
+        L.y_full = (F.conv2d(xf.permute(0, 3, 1, 2), w4, L.bias, stride=stride, padding=pad)
+                    .permute(0, 2, 3, 1).reshape(L.m, n).contiguous())
+        ws = torch.empty(P.cwac_range_workspace(L.y_full.numel()), dtype=torch.uint8, device=dev)
+        P.cwac_range_f32(L.y_full, mm, ws)
+        mn, mx = (float(v) for v in mm.cpu())
+        L.sr, zr_u = P.cwac_qparams_from_range(mn, mx, 8)
+        L.zr = zr_u - 128
+        L.qp = P.make_qparams(P.CWAC_EPI_INT_OFFSET, False, L.sx, L.zx, L.sr, L.zr)
+        L.qp_deq = P.make_qparams(P.CWAC_EPI_FP_BIAS, False, L.sx, L.zx, 1.0, 0)
+        L.deq_mult, L.deq_fb = torch.empty(n, **f32), torch.empty(n, **f32)
+        L.deq_off = torch.empty(n, dtype=torch.int32, device=dev)
+        P.cwac_fold(None, None, L.sw, L.bias, L.colsum, L.qp_deq, L.deq_mult, L.deq_off, L.deq_fb)
+        L.mult, L.offset = torch.empty(n, **f32), torch.empty(n, dtype=torch.int32, device=dev)
+        L.alpha, L.beta = torch.empty(n, **f32), torch.empty(n, **f32)
+        L.stats = torch.empty(P.cwac_stats_bytes(n) // 8 + 2, dtype=torch.float64, device=dev)
+        L.ws = torch.empty(P.cwac_calibrate_stats_workspace(L.m, n), dtype=torch.uint8, device=dev)
+        L.wq4 = L.wq.view(n, k, k, c)
+        L.xf_cpu = xf[:cpu_batch].cpu().numpy() if cpu_batch else None
+        L.wf_cpu = wf.cpu().numpy() if cpu_batch else None
+        del xf, wf, w4
+        layers.append(L)
+    mn_max = max(L.m * L.n for L in layers)
+    yq_buf = torch.empty(mn_max, **f32)
+    out_buf = torch.empty(mn_max, dtype=torch.int8, device=dev)
+    for L in layers:
+        L.yq, L.out = yq_buf[:L.m * L.n].view(L.m, L.n), out_buf[:L.m * L.n].view(L.m, L.n)
+    torch.cuda.synchronize()
+
+    def step(ev=None):
+        for L in layers:
+            if ev is not None:
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+                e[0].record()
+            P.qconv2d_cwac_forward(L.xq, L.wq4, L.stride, L.pad, L.qp_deq, L.deq_mult, L.deq_off, L.deq_fb,
+                                   P.CWAC_OUT_FP32, L.yq)
+            if ev is not None:
+                e[1].record()
+            P.cwac_stats_reset(L.stats, L.n)
+            P.cwac_calibrate_stats(L.y_full, L.yq, L.stats, L.ws)
+            P.cwac_solve(L.stats, L.n, L.alpha, L.beta)
+            P.cwac_fold(L.alpha, L.beta, L.sw, L.bias, L.colsum, L.qp, L.mult, L.offset)
+            if ev is not None:
+                e[2].record()
+            P.qconv2d_cwac_forward(L.xq, L.wq4, L.stride, L.pad, L.qp, L.mult, L.offset, None,
+                                   P.CWAC_OUT_INT8, L.out)
+            if ev is not None:
+                e[3].record()
+                ev.append(e)
+
+    for _ in range(2):
+        step()
+    torch.cuda.synchronize()
+    ev = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(ev)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / steps
+    nl = len(layers)
+    fwd_ops = sum(2.0 * L.m * L.n * L.k for L in layers)
+    t_cal = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    t_fit = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    t_fwd = sum(e[2].elapsed_time(e[3]) for e in ev) / steps
+    per_layer = []
+    for i, L in enumerate(layers):
+        us = sum(ev[s * nl + i][2].elapsed_time(ev[s * nl + i][3]) for s in range(steps)) / steps * 1e3
+        nbytes = L.xq.numel() + L.wq.numel() + L.m * L.n        # image + filter + int8 output, each once
+        per_layer.append({"layer": L.name, "m": L.m, "n": L.n, "k": L.k, "us": round(us, 1),
+                          "tops": round(2.0 * L.m * L.n * L.k / us / 1e6, 1),
+                          "algorithmic_gbs": round(nbytes / us / 1e3, 1)})
+    tops = fwd_ops / (t_fwd * 1e-3) / 1e12
+    res = {
+        "metric": "int8 convolution + CWAC epilogue TOPS (% int8 MFMA peak)",
+        "value": round(2.0 * fwd_ops / t_step / 1e12, 2), "unit": "TOPS", "n_gpus": 1, "steps": steps,
+        "warmup": 2, "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"ResNet-50 bottleneck convolutions (15 distinct layers of stages 2-5), "
+                               f"batch {batch}, channels-last int8 images, per-tensor activations"},
+        "roofline": {"bound": "mfma", "achieved": round(tops / 1e3, 4), "peak": INT8_MFMA_PEAK_TOPS / 1e3,
+                     "unit": "POP/s", "frac": round(tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
+                     "kernel": "qlinear_fast_kernel / qlinear_kernel, convolution instantiations "
+                               "(int8 out, fused CWAC epilogue)",
+                     "launches_per_step": nl, "avg_launch_ms": round(t_fwd / nl, 4),
+                     "ops_per_step": fwd_ops},
+        "phases_ms": {"calibration_forward_fp32": round(t_cal, 4),
+                      "statistics_solve_fold": round(t_fit, 4), "forward_int8": round(t_fwd, 4)},
+        "layers": per_layer,
+    }
+    if cpu_batch > 0:
+        from oracle import cwac_oracle as orc
+        ops, secs = 0.0, 0.0
+        for L in layers:
+            xf, wf = L.xf_cpu, L.wf_cpu
+            bias = L.bias.cpu().numpy()
+            wq, sw = orc.quantize_rows_sym(wf)                       # set-up
+            colsum = orc.colsum_i8(wq)
+            xq = orc.quantize_act_i8(xf, L.sx, L.zx)
+            y_full = L.y_full[:cpu_batch * L.oh * L.oh].cpu().numpy()
+            wq4 = wq.reshape(L.n, L.kf, L.kf, L.c)
+            t0 = time.perf_counter()                                 # the step
+            acc = orc.conv2d_i8(xq, wq4, L.stride, L.pad, L.zx)
+            y_quant = orc.dequant_output(acc, colsum, L.zx, orc.deq_scale(sw, L.sx), bias)
+            alpha, beta = orc.fit(y_full, y_quant)[:2]
+            mult, offset, _ = orc.fold_int_offset(alpha, beta, sw, bias, colsum, L.sx, L.zx, L.sr)
+            acc = orc.conv2d_i8(xq, wq4, L.stride, L.pad, L.zx)
+            orc.folded_forward(acc, offset, mult, L.zr)
+            secs += time.perf_counter() - t0
+            ops += 2.0 * 2.0 * cpu_batch * L.oh * L.oh * L.n * L.k
+        res["cpu_baseline"] = {"value": round(ops / secs / 1e12, 5), "unit": "TOPS",
+                               "cores": orc.get_threads(), "kind": "oracle",
+                               "sample": f"the same step on {cpu_batch} images of every layer "
+                                         f"({secs:.1f} s of oracle time)"}
+    return res
+
+
+
 def cpu_baseline(synth, cfg: int, sample_rows: int):
     """The oracle, as it stands, timed on this host on a bounded row sample of the same step."""
     import numpy as np
@@ -536,6 +702,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-weight-only", action="store_true",
                     help="skip the INT4 weight-only section (reported for the LLM workload only)")
+    ap.add_argument("--conv", action="store_true",
+                    help="the convolutional-layer section instead: ResNet-50 bottleneck convolutions "
+                         "(its own JSON line)")
+    ap.add_argument("--conv-batch", type=int, default=128)
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -552,6 +722,10 @@ def main():
     P.binding.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.conv:
+        print(json.dumps(conv_section(P, synth, torch, dev, args.conv_batch, args.steps,
+                                      0 if args.no_cpu_baseline else 8)))
+        return
     wl = synth.WORKLOADS[args.config]
     cal_rows = args.cal_rows or wl.m
     wl, layers = setup_layers(P, synth, torch, args.config, dev, cal_rows)

@@ -210,7 +210,8 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 }
 
 
-// Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 256, k % 128 == 0.
+// Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 256, k % 64 == 0 (its 256-token
+// tile: k % 128 == 0).
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st);
 // True where that kernel would take its 128-token tile shape (two workgroups per compute unit).
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);

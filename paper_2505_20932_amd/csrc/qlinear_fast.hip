@@ -22,7 +22,7 @@
 //     registers per lane, so that TWO workgroups share a compute unit and one's prologue and
 //     epilogue run under the other's main loop.
 //
-// Requires m >= 256, n >= 256, k % 128 == 0.  Edge tiles are shifted inwards to overlap their
+// Requires m >= 256, n >= 256, k % 128 == 0 (the 128-token shape: k % 64 == 0).  Edge tiles are shifted inwards to overlap their
 // neighbours (identical values are written twice) instead of being predicated.
 #include <stdlib.h>
 #include <string.h>
@@ -767,6 +767,7 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   // default for large layers), 128x2 | 64x4 the same tile with four wavefronts and that K step
   // and ring depth; "duo" the 128-token tile, two workgroups of four wavefronts per compute unit.
   const char *e = getenv("CWAC_FWD_PIPE");
+  if ((p.k % 128) != 0) e = "duo";  // K a multiple of 64 only: the tile that steps K by 64
   if (e && e[0] == 'd') return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
   if (e && e[0] == '6') return launch_cfg<256, 2, 64, 4, 2>(p, out_kind, int_only, st);
   if (e && e[0] == '8') return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);

@@ -232,10 +232,17 @@ static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_o
   const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
   const int64_t t128 = ceil_div(m, 128) * ceil_div(n, 128);
   int tile = t256 >= 512 ? 256 : (t128 >= 512 ? 128 : 64);
-  const bool fast_ok = m >= kFastTile && n >= kFastTile && (k % kFastKStep) == 0;
-  // the large-problem kernel wants most compute units busy: 160 full tiles, or 256 half tiles
+  // narrow layers: a tile much wider than the layer would multiply mostly padding
+  if (n <= 160 && tile > 128) tile = 128;
+  if (n <= 80 && tile > 64) tile = 64;
+  // the large-problem kernel: K a multiple of 128, or of 64 (then only its 128-token tile, which
+  // steps K by 64)
+  const bool fast_ok = m >= kFastTile && n >= kFastTile && (k % 64) == 0;
+  // it wants most compute units busy: 160 full tiles, or 256 half tiles
   const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
-  bool fast = fast_ok && (t256 >= 160 || fast_prefers_half_tile(m, n, k, out_bytes));
+  bool fast = fast_ok && (k % kFastKStep) == 0 &&
+              (t256 >= 160 || fast_prefers_half_tile(m, n, k, out_bytes));
+  if (fast_ok && (k % kFastKStep) != 0) fast = ceil_div(m, 128) * ceil_div(n, 256) >= 160;
   // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
   // the large-problem kernel where its shape constraints hold (results are identical).
   if (const char *e = getenv("CWAC_FWD_TILE")) {
