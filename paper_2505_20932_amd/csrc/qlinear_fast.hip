@@ -52,11 +52,11 @@ constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
   return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
 }
 
-template <int BM_, int WM_, int BK, int NSTAGE, int NCHUNK>
+template <int BM_, int WM_, int BK, int NSTAGE, int NCHUNK, int BN_ = 256>
 struct FastCfg {
-  static constexpr int BM = BM_, BN = 256;
-  static constexpr int WM = WM_;                 // wavefronts along m (always 2 along n)
-  static constexpr int NWAVES = 2 * WM, NT = 64 * NWAVES;
+  static constexpr int BM = BM_, BN = BN_;
+  static constexpr int WM = WM_, WN = BN / 128;  // wavefronts along m and n (a wave tile spans 128 channels)
+  static constexpr int NWAVES = WN * WM, NT = 64 * NWAVES;
   static constexpr int TB = BM / (32 * WM);      // 32-token MFMA tiles per wavefront
   static constexpr int KK = BK / 32;  // MFMA k-steps per stage
   static constexpr int X_BYTES = BM * BK, W_BYTES = BN * BK, STAGE = X_BYTES + W_BYTES;
@@ -75,7 +75,9 @@ struct FastCfg {
   static constexpr int CHUNK = (LPS + NCHUNK - 1) / NCHUNK;  // most loads issued in one k-step
   // chunk c of a stage's loads = loads [chunk_begin(c), chunk_begin(c + 1))
   __host__ __device__ static constexpr int chunk_begin(int c) { return c * LPS / NCHUNK; }
-  static_assert((BM == 256 || BM == 128) && (WM == 2 || WM == 4) && (TB == 4 || TB == 2), "tile and wave grid");
+  static_assert((BM == 256 || BM == 128) && (BN == 256 || BN == 128) && (WM == 2 || WM == 4) &&
+                    (TB == 4 || TB == 2),
+                "tile and wave grid");
   static_assert(XROWS % RPL == 0 && WLROWS % RPL == 0, "whole loads per wavefront");
   static_assert(BK == 64 || BK == 128, "K step");
   static_assert(NCHUNK >= 1 && NCHUNK <= KK && NCHUNK <= LPS, "load chunks per stage");
@@ -419,11 +421,14 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
   }
 }
 
-template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false>
-__global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(const FwdParams p) {
-  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK>;
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false,
+          int BN = 256>
+__global__ __launch_bounds__(64 * (BN / 128) * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(
+    const FwdParams p) {
+  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN>;
   constexpr int TB = C::TB;
-  static_assert(OUT_KIND != kOutStats || (BM == 256 && C::RING >= 131072 && C::STATS_LDS_BYTES <= 160 * 1024),
+  static_assert(OUT_KIND != kOutStats ||
+                    (BM == 256 && BN == 256 && C::RING >= 131072 && C::STATS_LDS_BYTES <= 160 * 1024),
                 "statistics epilogue: full-height tile, 128 KiB of ring for the slabs");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   int32_t *s_off = reinterpret_cast<int32_t *>(smem + C::RING);
@@ -446,8 +451,8 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
   const int l32 = lane & 31, half = lane >> 5;
 
   // ---- epilogue parameters of this tile: issue their loads first (oldest in the load queue);
-  // thread t < 256 stages channel t (and row t)
-  const int ptid = tid < 256 ? tid : 255;
+  // thread t < BN stages channel t (and thread t < BM row t)
+  const int ptid = tid < BN ? tid : BN - 1;
   const int p_off = p.offset ? p.offset[bn0 + ptid] : 0;
   float p_mult = 0.0f, p_fb = 0.0f, p_rs = 1.0f;
   if (OUT_KIND == kOutFixed) {  // integer multiplier and shift travel in the two float slots
@@ -606,13 +611,13 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
 #pragma unroll
   for (int s = 0; s < NSTAGE; ++s)
     if (s < stages) issue_stage(s, s * BK);
-  if (tid < 256) {
+  if (tid < BN) {
     s_off[tid] = p_off;
     s_mult[tid] = p_mult;
     s_fb[tid] = p_fb;
   }
   if (tid < BM) s_rs[tid] = p_rs;
-  if (OUT_KIND == kOutStats && tid < 256) {
+  if (OUT_KIND == kOutStats && tid < BN) {
     s_pq[tid] = p_pq;
     s_pf[tid] = p_pf;
   }
@@ -709,34 +714,36 @@ __global__ __launch_bounds__(64 * 2 * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void ql
   }
 }
 
-template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false,
+          int BN = 256>
 cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
-  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK>;
+  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN>;
   constexpr int LDS = OUT_KIND == kOutStats ? C::STATS_LDS_BYTES : C::LDS_BYTES;
   static const hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV>),
+      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV, BN>),
       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV><<<grid, C::NT, LDS, st>>>(p);
+  qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV, BN><<<grid, C::NT, LDS, st>>>(p);
   return launch_status();
 }
 
-template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, bool CONV = false>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, bool CONV = false, int BN = 256>
 cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   p.tiles_m = (int)ceil_div(p.m, BM);
-  p.tiles_n = (int)ceil_div(p.n, 256);
+  p.tiles_n = (int)ceil_div(p.n, BN);
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
   const dim3 grid((unsigned)blocks);
   if constexpr (!CONV) {
-    if (out_kind == kOutFixed) return launch_one<BM, WM, BK, NSTAGE, NCHUNK, kOutFixed, true>(p, grid, st);
+    if (out_kind == kOutFixed)
+      return launch_one<BM, WM, BK, NSTAGE, NCHUNK, kOutFixed, true, false, BN>(p, grid, st);
   }
   if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true, CONV>(p, grid, st)
-                    : launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false, CONV>(p, grid, st);
+    return int_only ? launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true, CONV, BN>(p, grid, st)
+                    : launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false, CONV, BN>(p, grid, st);
   if (out_kind == CWAC_OUT_FP32)
-    return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false, CONV>(p, grid, st);
-  return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false, CONV>(p, grid, st);
+    return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false, CONV, BN>(p, grid, st);
+  return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false, CONV, BN>(p, grid, st);
 }
 
 }  // namespace
@@ -766,6 +773,9 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   // Tuning knob (same results): CWAC_FWD_PIPE=8w is the 256-token tile with eight wavefronts (the
   // default for large layers), 128x2 | 64x4 the same tile with four wavefronts and that K step
   // and ring depth; "duo" the 128-token tile, two workgroups of four wavefronts per compute unit.
+  // layers narrower than 256 channels: 256 tokens x 128 channels, four wavefronts (4 x 1), 64-byte K
+  // steps, two workgroups per compute unit
+  if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, false, 128>(p, out_kind, int_only, st);
   const char *e = getenv("CWAC_FWD_PIPE");
   if ((p.k % 128) != 0) e = "duo";  // K a multiple of 64 only: the tile that steps K by 64
   if (e && e[0] == 'd') return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
@@ -779,13 +789,14 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
 }
 
 bool fast_conv_ok(const FwdParams &p, int64_t image_bytes) {
-  return p.m >= kFastTile && p.m < ((int64_t)1 << 31) && p.n >= kFastTile && (p.k % kFastKStep) == 0 &&
+  return p.m >= kFastTile && p.m < ((int64_t)1 << 31) && p.n >= 128 && (p.k % kFastKStep) == 0 &&
          (p.cv_cin % 64) == 0 && image_bytes < ((int64_t)1 << 31);
 }
 
 cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
+  if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, true, 128>(p, out_kind, int_only, st);
   // a stage must lie inside one filter tap: the 256-token tile steps K by 128, the 128-token tile by 64
   const bool full_ok = (p.cv_cin % 128) == 0;
   const char *e = getenv("CWAC_FWD_PIPE");  // tuning knob (same results): "8w" | "duo"

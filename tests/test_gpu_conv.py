@@ -88,6 +88,8 @@ FAST_SHAPES = [  # batch, h, w, c_in, c_out, kh, kw, stride, pad, pipes
     (2, 23, 21, 128, 256, 7, 7, 2, 3, ("8w", "duo")),     # 7x7 / 2 with padding 3: most taps of the border rows are outside
     (3, 10, 16, 256, 260, 3, 5, 1, 2, ("8w", "duo")),     # rectangular filter, two K steps per tap
     (24, 9, 7, 128, 256, 3, 3, 2, 0, ("8w",)),            # stride 2 without padding
+    (2, 14, 14, 128, 128, 3, 3, 1, 1, ("duo",)),          # fewer than 256 output channels: the 256 x 128 tile
+    (3, 11, 13, 64, 176, 2, 2, 1, 1, ("duo",)),           # ... with overlapping channel tiles, 64 channels per tap
 ]
 
 
@@ -215,12 +217,12 @@ def test_conv_calibration_pipeline(orc):
     np.testing.assert_array_equal(out.cpu().numpy(), want)
 
 
-@pytest.mark.parametrize("b", [64, 128])
-def test_conv_large_layer_sampled(orc, b):
-    """A ResNet-50-sized 3x3 layer at batch 64 and 128 (M = 12544 / 25088, K = 2304) in the automatic
-    kernel choice (the generic kernel / the direct-to-LDS kernel); the oracle checks whole images
-    (first, last) position by position."""
-    h, w, c, n, k = 14, 14, 256, 256, 3
+@pytest.mark.parametrize("b,h,c,n", [(64, 14, 256, 256), (128, 14, 256, 256), (32, 28, 128, 128)])
+def test_conv_large_layer_sampled(orc, b, h, c, n):
+    """ResNet-50-sized 3x3 layers (M = 12544 / 25088, K = 2304; M = 25088, N = 128, K = 1152) in the
+    automatic kernel choice (the generic kernel / the direct-to-LDS kernel in its 128 x 256 and
+    256 x 128 tiles); the oracle checks whole images (first, last) position by position."""
+    w, k = h, 3
     xq = torch.randint(-128, 128, (b, h, w, c), dtype=torch.int8, device=DEV,
                        generator=torch.Generator(device=DEV).manual_seed(5))
     wq = torch.randint(-127, 128, (n, k, k, c), dtype=torch.int8, device=DEV,
