@@ -452,6 +452,38 @@ def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: 
         "calibration_forward_tflops": round(fwd_flops / (t_cal * 1e-3) / 1e12, 2),
         "dense_fp16_library_gemm_tflops": round(fwd_flops / (t_dense * 1e-3) / 1e12, 2),
     }
+    # decode-sized batches (8 tokens): the layer is a stream of 4-bit weights; 20 passes over the
+    # five layers replayed from a HIP graph (a launch from Python costs as much as the kernel)
+    sm = 8
+    outs = [torch.empty(sm, L.n, dtype=torch.float16, device=dev) for L in layers]
+
+    def small_pass():
+        for L, o in zip(layers, outs):
+            P.qlinear_w4a16_cwac_forward(L.x[:sm], L.pw, L.psz, L.n, L.mult, L.fbias, o)
+
+    small_pass()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(20):
+                small_pass()
+    g.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    t_small = e0.elapsed_time(e1) / 20                      # ms per pass over the layers
+    small_bytes = sum(L.n * L.k / 2 + L.n * (L.k // 128) * 4 + sm * L.k * 2 + sm * L.n * 2 for L in layers)
+    gbs = small_bytes / (t_small * 1e-3) / 1e9
+    res["small_batch"] = {
+        "tokens": sm, "us_per_layer": round(t_small * 1e3 / len(layers), 2),
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "w4a16_small_m_kernel (fp16 out, fused CWAC epilogue)",
+                     "bytes_per_pass": small_bytes}}
     if cpu_rows > 0:
         from oracle import cwac_oracle as orc
         from oracle import w4a16_oracle as w4

@@ -22,6 +22,8 @@
 //     binary16, transposition through a wave-private LDS slab, whole 128-byte line stores.
 #include <hip/hip_runtime.h>
 
+#include <stdlib.h>
+
 #include "qlinear_common.h"
 
 namespace cwac {
@@ -463,6 +465,122 @@ cwac_status launch_w4(const W4Params &p, hipStream_t st) {
   return launch_status();
 }
 
+// ------------------------------------------------------------------------------------------
+// Small batches (m <= 32 tokens: the decode step of an LLM).  The layer is then bound by the
+// stream of 4-bit weights, not by the matrix cores: one workgroup of NW (4 or 8) wavefronts owns 32 output
+// channels (one row of 1 KiB blocks of the packed layout) over the whole of K, each wavefront a
+// contiguous quarter of the groups; the codes arrive with the same contiguous 16-byte-per-lane loads
+// as in the tiled kernel, are expanded in registers and meet the activations (read straight from
+// memory: m rows of K binary16 values stay in the caches) in one 32 x 32 MFMA tile per 16 input
+// channels, rows beyond m idle.  The four partial tiles are added in wavefront order through LDS
+// (deterministic), then the epilogue of the tiled kernel.  No workspace, no atomics.
+// ------------------------------------------------------------------------------------------
+constexpr int kSmallM = 32;
+
+template <int OUT_KIND, int NW>
+__global__ __launch_bounds__(64 * NW) void w4a16_small_m_kernel(const W4Params p) {
+  __shared__ float s_part[NW - 1][16][64];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, half = lane >> 5;
+  const int nb = blockIdx.x, n0 = nb * 32;
+  const int groups = p.k / kGroup, kb64 = p.k / 64;
+  const int g_begin = wave * groups / NW, g_end = (wave + 1) * groups / NW;
+  const bool row_ok = l32 < p.m;
+
+  const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)nb * kb64 * 1024 + lane * 16;
+  // activations through a buffer descriptor that ends with row m - 1: the lanes of rows beyond m
+  // read zeros without touching memory, and the loads need no branches
+  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char *>(p.x), 0, (int)((p.m - 1) * p.ldx_bytes + (int64_t)p.k * 2), 0x00020000);
+  const uint32_t xvo = (uint32_t)l32 * (uint32_t)p.ldx_bytes + (uint32_t)half * 16u;
+  struct Raw {
+    u4 c[2];
+    uint32_t sz;
+    h8 x[8];
+  };
+  auto fetch = [&](Raw &r, int g) {
+    r.c[0] = *reinterpret_cast<const GU4 *>(CWAC_GLOBAL_PTR(wrow + (int64_t)(2 * g) * 1024));
+    r.c[1] = *reinterpret_cast<const GU4 *>(CWAC_GLOBAL_PTR(wrow + (int64_t)(2 * g + 1) * 1024));
+    r.sz = p.sz[(int64_t)g * p.n + n0 + l32];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      r.x[kk] = __builtin_bit_cast(h8, __builtin_amdgcn_raw_buffer_load_b128(xres, xvo + g * 256 + kk * 32, 0, 0));
+  };
+  // two accumulators (even / odd k-steps): consecutive MFMAs do not wait for each other
+  v16f acc, acc1;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = acc1[i] = 0.0f;
+  auto consume = [&](const Raw &r) {
+    const GroupConst gc = group_const(r.sz);
+#pragma unroll
+    for (int kk = 0; kk < 8; kk += 2) {
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand8(r.c[kk >> 2][kk & 3], gc), r.x[kk], acc, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand8(r.c[(kk + 1) >> 2][(kk + 1) & 3], gc), r.x[kk + 1],
+                                                    acc1, 0, 0, 0);
+    }
+  };
+  // two groups in flight: the loads of group g + 1 are issued before group g is consumed.  (A
+  // deeper ring does not pay: the kernel is bound by the expansion arithmetic, about 140 vector
+  // instructions per group and wavefront, not by the latency of the stream.)
+  Raw ra, rb;
+  int g = g_begin;
+  if (g < g_end) fetch(ra, g);
+  for (; g + 2 <= g_end; g += 2) {
+    fetch(rb, g + 1);
+    consume(ra);
+    if (g + 2 < g_end) fetch(ra, g + 2);
+    consume(rb);
+  }
+  if (g < g_end) consume(ra);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] += acc1[i];
+
+  if (wave > 0) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s_part[wave - 1][i][lane] = acc[i];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int w = 0; w < NW - 1; ++w)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] += s_part[w][i][lane];
+  if (!row_ok) return;
+  constexpr int ESZ = OUT_KIND == CWAC_OUT_FP16 ? 2 : 4;
+  char *orow = p.out + ((int64_t)l32 * p.ldo + n0) * ESZ;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int ch = 8 * q + 4 * half;  // channel inside the block: accumulator elements 4q .. 4q + 3
+    float u[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float v = acc[4 * q + r] * (p.mult ? p.mult[n0 + ch + r] : 1.0f);
+      u[r] = v + (p.fbias ? p.fbias[n0 + ch + r] : 0.0f);
+    }
+    if (OUT_KIND == CWAC_OUT_FP16) {
+      const h2 lo = {(_Float16)u[0], (_Float16)u[1]}, hi = {(_Float16)u[2], (_Float16)u[3]};
+      *reinterpret_cast<uint2 *>(orow + ch * 2) =
+          make_uint2(__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi));
+    } else {
+      *reinterpret_cast<float4 *>(orow + ch * 4) = make_float4(u[0], u[1], u[2], u[3]);
+    }
+  }
+}
+
+template <int OUT_KIND>
+cwac_status launch_w4_small(const W4Params &p, hipStream_t st) {
+  // four wavefronts per workgroup; eight where there are fewer workgroups than compute units
+  const char *e = getenv("CWAC_W4_WAVES");  // tuning knob
+  const int nw = e ? atoi(e) : (p.n / 32 < 256 ? 8 : 4);
+  if (nw == 4)
+    w4a16_small_m_kernel<OUT_KIND, 4><<<dim3((unsigned)(p.n / 32)), 256, 0, st>>>(p);
+  else
+    w4a16_small_m_kernel<OUT_KIND, 8><<<dim3((unsigned)(p.n / 32)), 512, 0, st>>>(p);
+  return launch_status();
+}
+
+
 int grid_for(int64_t items) {
   const int64_t b = ceil_div(items, kThreads);
   return (int)(b < 1 ? 1 : (b > 65536 ? 65536 : b));
@@ -547,6 +665,12 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
   p.ldo = ldo;
   p.tiles_m = (int)ceil_div(m, 256);
   p.tiles_n = (int)ceil_div(n, 256);
+  // Tuning / testing knob (results agree to the rounding of the fp32 sums): CWAC_W4_PIPE=tile keeps
+  // the 256-token tiles for small batches too.
+  const char *e = getenv("CWAC_W4_PIPE");
+  if (m <= kSmallM && !(e && e[0] == 't'))
+    return out_kind == CWAC_OUT_FP16 ? launch_w4_small<CWAC_OUT_FP16>(p, as_stream(stream))
+                                     : launch_w4_small<CWAC_OUT_FP32>(p, as_stream(stream));
   return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16>(p, as_stream(stream))
                                    : launch_w4<CWAC_OUT_FP32>(p, as_stream(stream));
 }

@@ -8,6 +8,8 @@ so it is checked two ways: on operands whose every partial sum is exactly repres
 workload-like operands against the exact fp64 product within
     8 * sqrt(K) * 2^-24 * sum_k |x w|        (fp32 summation, probabilistic bound with margin)
 plus the roundings of the two epilogue operations and of the binary16 store."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -39,14 +41,19 @@ def _pack(codes, scales, zeros):
     return pw, psz
 
 
-def _forward(x16, pw, psz, n, mult, fbias, dtype, ldo=None):
+def _forward(x16, pw, psz, n, mult, fbias, dtype, ldo=None, pipe=None):
     m = x16.shape[0]
     if ldo is None:
         out = torch.empty(m, n, dtype=dtype, device=DEV)
     else:
         full = torch.full((m, ldo), 7.0, dtype=dtype, device=DEV)
         out = full[:, :n]
-    P.qlinear_w4a16_cwac_forward(_dev(x16), pw, psz, n, _dev(mult), _dev(fbias), out)
+    if pipe:
+        os.environ["CWAC_W4_PIPE"] = pipe
+    try:
+        P.qlinear_w4a16_cwac_forward(_dev(x16), pw, psz, n, _dev(mult), _dev(fbias), out)
+    finally:
+        os.environ.pop("CWAC_W4_PIPE", None)
     torch.cuda.synchronize()
     if ldo is not None:
         assert (full[:, n:] == 7.0).all(), "wrote outside the output columns"
@@ -161,6 +168,74 @@ def test_forward_exact_operands(w4, m, n, k):
     np.testing.assert_array_equal(_forward(x16, pw, psz, n, mult, None, torch.float32).cpu().numpy(), o32m)
     o32b, _ = w4.epilogue_f32(acc32, None, fbias)
     np.testing.assert_array_equal(_forward(x16, pw, psz, n, None, fbias, torch.float32).cpu().numpy(), o32b)
+
+
+@pytest.mark.parametrize("n,k", [(256, 128), (320, 384), (512, 1024), (288, 640)])
+@pytest.mark.parametrize("m", [1, 5, 17, 32])
+def test_small_batch_exact_operands(w4, m, n, k):
+    """Batches of at most 32 tokens take the weight-streaming kernel (one workgroup per 32 channels,
+    K split over its four wavefronts - here 1, 3, 8 and 5 groups); `tile` forces the tiled kernel.
+    Exact operands: both give the oracle's bits."""
+    print(f"w4a16 small batch {m} x {n} x {k}", flush=True)
+    x16, codes, scales, zeros = _exact_case(300 + m + n + k, m, n, k)
+    wd = w4.dequant(codes, scales, zeros)
+    acc, _ = w4.product(x16, wd)
+    acc32 = acc.astype(np.float32)
+    assert np.array_equal(acc32.astype(np.float64), acc)
+    pw, psz = _pack(codes, scales, zeros)
+    rng = np.random.default_rng(6)
+    mult = (1 + 0.25 * rng.standard_normal(n)).astype(np.float32)
+    fbias = rng.standard_normal(n).astype(np.float32)
+    o32, o16 = w4.epilogue_f32(acc32, mult, fbias)
+    o32m, _ = w4.epilogue_f32(acc32, mult, None)
+    o32b, _ = w4.epilogue_f32(acc32, None, fbias)
+    for pipe in (None, "tile"):
+        out = _forward(x16, pw, psz, n, None, None, torch.float32, pipe=pipe)
+        np.testing.assert_array_equal(out.cpu().numpy(), acc32)
+        out = _forward(x16, pw, psz, n, mult, fbias, torch.float32, ldo=n + 12, pipe=pipe)
+        np.testing.assert_array_equal(out.cpu().numpy(), o32)
+        outh = _forward(x16, pw, psz, n, mult, fbias, torch.float16, ldo=n + 24, pipe=pipe)
+        np.testing.assert_array_equal(outh.cpu().numpy().view(np.uint16), o16.view(np.uint16))
+        np.testing.assert_array_equal(
+            _forward(x16, pw, psz, n, mult, None, torch.float32, pipe=pipe).cpu().numpy(), o32m)
+        np.testing.assert_array_equal(
+            _forward(x16, pw, psz, n, None, fbias, torch.float32, pipe=pipe).cpu().numpy(), o32b)
+
+
+def test_small_batch_padded_activation_pitch(w4):
+    m, n, k = 9, 256, 512
+    x16, codes, scales, zeros = _exact_case(19, m, n, k)
+    acc, _ = w4.product(x16, w4.dequant(codes, scales, zeros))
+    pw, psz = _pack(codes, scales, zeros)
+    xp = torch.zeros(m, k + 40, dtype=torch.float16, device=DEV)
+    xp[:, :k] = _dev(x16)
+    out = torch.empty(m, n, dtype=torch.float32, device=DEV)
+    P.qlinear_w4a16_cwac_forward(xp[:, :k], pw, psz, n, None, None, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), acc.astype(np.float32))
+
+
+@pytest.mark.parametrize("m,n,k", [(8, 512, 4096), (32, 12288, 4096), (16, 4096, 11008)])
+def test_small_batch_workload_like(w4, m, n, k):
+    """Decode-sized batches on LLM-like operands, up to the largest layer shapes of workload 5:
+    every output inside the rounding bound of an fp32 summation of the exact products."""
+    print(f"w4a16 small batch, workload-like {m} x {n} x {k}", flush=True)
+    w, x16 = _llm_like(60 + k + m, m, n, k)
+    codes, scales, zeros = w4.quantize_groupwise(w)
+    wd = w4.dequant(codes, scales, zeros)
+    acc, mag = w4.product(x16, wd)
+    pw, psz = _pack(codes, scales, zeros)
+    alpha = (1 + 0.05 * synth.normal(8, 0, n).numpy()).astype(np.float32)
+    beta = (0.02 * synth.normal(8, 1, n).numpy()).astype(np.float32)
+    mult, fbias = w4.fold(alpha, beta, None, n)
+    ref = w4.folded_real(acc, mult, fbias)
+    for dtype in (torch.float32, torch.float16):
+        out = _forward(x16, pw, psz, n, mult, fbias, dtype).cpu().numpy().astype(np.float64)
+        err = np.abs(out - ref)
+        tol = _tolerance(mag, ref, k, mult, fbias, dtype == torch.float16)
+        assert (err <= tol).all(), float((err / tol).max())
+    out = _forward(x16, pw, psz, n, None, None, torch.float32).cpu().numpy().astype(np.float64)
+    assert (np.abs(out - acc) <= 0.25 * _tolerance(mag, acc, k, None, None, False)).all()
 
 
 def test_forward_longest_k(w4):
