@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --probe`,
 # scaled by what the same counters read for a plain 1 GiB copy (x1.997, x1.000); mean over the
 # workload's launches.  Only the default workload has been profiled.
-PMC_TRAFFIC_BYTES = {5: {"forward_int8": 984e6 + 144e6, "statistics": 1113e6 + 8e6,
-                         "forward_w4a16": 1532e6 + 331e6}}
+PMC_TRAFFIC_BYTES = {5: {"forward_int8": 979e6 + 139e6, "statistics": 1113e6 + 8e6,
+                         "forward_w4a16": 1535e6 + 331e6}}
 
 
 class LayerState:
