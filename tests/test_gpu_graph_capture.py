@@ -112,19 +112,31 @@ def test_weight_only_and_convolution_replay_from_a_graph():
     co = torch.arange(48, dtype=torch.int32, device=DEV) * 7 - 100
     outc = torch.empty(2 * 12 * 12, 48, dtype=torch.int8, device=DEV)
     qp = P.make_qparams(z_x=-4, z_r=3)
+    # the same weight-only layer at a decode-sized batch (the weight-streaming kernel) ...
+    out8 = torch.empty(8, n, dtype=torch.float16, device=DEV)
+    # ... and a convolution wide enough for the direct-to-LDS kernel: 4 images of 14 x 14 x 128 -> 256
+    xw = torch.empty(4, 14, 14, 128, dtype=torch.int8, device=DEV)
+    ww = torch.randint(-100, 101, (256, 3, 3, 128), dtype=torch.int8, device=DEV,
+                       generator=torch.Generator(device=DEV).manual_seed(10))
+    wm = torch.full((256,), 1e-4, **f32)
+    wo = torch.arange(256, dtype=torch.int32, device=DEV) * 5 - 600
+    outw = torch.empty(4 * 14 * 14, 256, dtype=torch.int8, device=DEV)
 
     def step():
         P.cwac_w4_quantize_groupwise(w, codes, sc, ze)
         P.cwac_w4_pack(codes, sc, ze, pw, psz)
         P.cwac_fold_weight_only(alpha, beta, None, mult, fb)
         P.qlinear_w4a16_cwac_forward(x, pw, psz, n, mult, fb, out)
+        P.qlinear_w4a16_cwac_forward(x[:8], pw, psz, n, mult, fb, out8)
         P.qconv2d_cwac_forward(xc, wc, 1, 1, qp, cm, co, None, P.CWAC_OUT_INT8, outc)
+        P.qconv2d_cwac_forward(xw, ww, 1, 1, qp, wm, wo, None, P.CWAC_OUT_INT8, outw)
 
     def load(seed):
         x.copy_(synth.normal(seed, 0, m * k, device=DEV).view(m, k))
         alpha.copy_(1.0 + 0.1 * synth.normal(seed, 1, n, device=DEV))
         beta.copy_(0.05 * synth.normal(seed, 2, n, device=DEV))
         xc.copy_((synth.normal(seed, 3, xc.numel(), device=DEV) * 40).clamp(-128, 127).view(xc.shape))
+        xw.copy_((synth.normal(seed, 4, xw.numel(), device=DEV) * 40).clamp(-128, 127).view(xw.shape))
 
     load(1)
     step()
@@ -136,11 +148,11 @@ def test_weight_only_and_convolution_replay_from_a_graph():
         load(seed)
         step()
         torch.cuda.synchronize()
-        want = [t.clone() for t in (out, outc, mult, fb)]
-        for t in (out, outc, mult, fb, pw):
+        want = [t.clone() for t in (out, outc, mult, fb, out8, outw)]
+        for t in (out, outc, mult, fb, pw, out8, outw):
             t.zero_()
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        for a, b in zip(want, (out, outc, mult, fb)):
+        for a, b in zip(want, (out, outc, mult, fb, out8, outw)):
             assert torch.equal(a, b), f"replay {seed} differs from the eager step"
