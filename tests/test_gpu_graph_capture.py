@@ -90,8 +90,10 @@ def test_step_replays_from_a_graph(orc):
                                   orc.folded_forward(acc, off.cpu().numpy(), mult.cpu().numpy(), zr))
 
 
-def test_weight_only_and_convolution_replay_from_a_graph():
+def test_weight_only_and_convolution_replay_from_a_graph(monkeypatch):
     """The weight-only INT4 entry points and the convolution launch only kernels too."""
+    # the wide convolution below is too small for the dispatcher to pick the direct-to-LDS kernel
+    monkeypatch.setenv("CWAC_FWD_TILE", "fast")
     f32 = dict(dtype=torch.float32, device=DEV)
     m, n, k = 300, 512, 384
     w = synth.normal(3, 0, n * k, device=DEV).view(n, k) * 0.02
