@@ -210,13 +210,13 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 }
 
 
-// Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 128, k % 64 == 0 (its 256 x 256
+// Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 64, k % 64 == 0 (its 256 x 256
 // tile: n >= 256 and k % 128 == 0).
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st);
 // True where that kernel would take its 128-token tile shape (two workgroups per compute unit).
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);
 // The same kernel as an implicit-GEMM convolution (p.cv_* set, p.ldx unused).  fast_conv_ok: its shape
-// constraints (m >= 256, n >= 128, c_in % 64 == 0, k % 128 == 0, image below 2 GiB).
+// constraints (m >= 256, n >= 64, c_in % 64 == 0, image below 2 GiB).
 bool fast_conv_ok(const FwdParams &p, int64_t image_bytes);
 cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, hipStream_t st);
 // Same kernel with the statistics epilogue; additionally requires n % 4 == 0, ld_full % 4 == 0

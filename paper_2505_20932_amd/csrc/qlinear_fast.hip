@@ -55,7 +55,8 @@ constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
 template <int BM_, int WM_, int BK, int NSTAGE, int NCHUNK, int BN_ = 256>
 struct FastCfg {
   static constexpr int BM = BM_, BN = BN_;
-  static constexpr int WM = WM_, WN = BN / 128;  // wavefronts along m and n (a wave tile spans 128 channels)
+  static constexpr int TA = BN >= 128 ? 4 : BN / 32;  // 32-channel MFMA tiles per wavefront
+  static constexpr int WM = WM_, WN = BN / (32 * TA);  // wavefronts along m and n
   static constexpr int NWAVES = WN * WM, NT = 64 * NWAVES;
   static constexpr int TB = BM / (32 * WM);      // 32-token MFMA tiles per wavefront
   static constexpr int KK = BK / 32;  // MFMA k-steps per stage
@@ -75,7 +76,7 @@ struct FastCfg {
   static constexpr int CHUNK = (LPS + NCHUNK - 1) / NCHUNK;  // most loads issued in one k-step
   // chunk c of a stage's loads = loads [chunk_begin(c), chunk_begin(c + 1))
   __host__ __device__ static constexpr int chunk_begin(int c) { return c * LPS / NCHUNK; }
-  static_assert((BM == 256 || BM == 128) && (BN == 256 || BN == 128) && (WM == 2 || WM == 4) &&
+  static_assert((BM == 256 || BM == 128) && (BN == 256 || BN == 128 || BN == 64) && (WM == 2 || WM == 4) &&
                     (TB == 4 || TB == 2),
                 "tile and wave grid");
   static_assert(XROWS % RPL == 0 && WLROWS % RPL == 0, "whole loads per wavefront");
@@ -109,12 +110,13 @@ __device__ __forceinline__ uint32_t pack4(int b0, int b1, int b2, int b3) {
 // Non-VEC path (unaligned output): element-wise stores.
 constexpr int kSlabStride = 144;
 
-template <int OUT_KIND, int ROWS>
+template <int OUT_KIND, int ROWS, int ROW_BYTES = 128>
 __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int64_t row_bytes, int lane) {
-  const int rd_row = lane >> 3, rd_chunk = lane & 7;
+  constexpr int CPR = ROW_BYTES / 16, RPP = 64 / CPR;  // 16-byte chunks per row, rows per store instruction
+  const int rd_row = lane / CPR, rd_chunk = lane % CPR;
 #pragma unroll
-  for (int i = 0; i < ROWS / 8; ++i) {
-    const int row = i * 8 + rd_row;
+  for (int i = 0; i < ROWS / RPP; ++i) {
+    const int row = i * RPP + rd_row;
     const v4i v = *reinterpret_cast<const v4i *>(slab + row * kSlabStride + rd_chunk * 16);
     v4i *dst = reinterpret_cast<v4i *>(gbase + row * row_bytes + rd_chunk * 16);
     // 4-byte outputs (the calibration forward's Y_quant) are far larger than the caches and are
@@ -128,8 +130,8 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
   }
 }
 
-template <int OUT_KIND, bool INT_ONLY, bool VEC, int TB, int WM>
-__device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4][TB], int8_t *smem,
+template <int OUT_KIND, bool INT_ONLY, bool VEC, int TB, int WM, int TA>
+__device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[TA][TB], int8_t *smem,
                                               const float *s_mult, const float *s_fb,
                                               const float *s_rs, int64_t bm0, int bn0, int wave_m,
                                               int wave_n, int lane) {
@@ -141,7 +143,7 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
   int8_t *slab = smem + wave * (WROWS * kSlabStride);
   const int64_t row_bytes = p.ldo * ESZ;
   // first element of the wave tile in the output
-  char *wbase = static_cast<char *>(p.out) + ((bm0 + wave_m * WROWS) * p.ldo + bn0 + wave_n * 128) * ESZ;
+  char *wbase = static_cast<char *>(p.out) + ((bm0 + wave_m * WROWS) * p.ldo + bn0 + wave_n * (32 * TA)) * ESZ;
   float rs[TB];
 #pragma unroll
   for (int b = 0; b < TB; ++b) rs[b] = s_rs[wave_m * WROWS + b * 32 + l32];
@@ -149,11 +151,11 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
   const bool use_fb = !INT_ONLY && p.fbias != nullptr;
   const float magic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to nearest even at unit steps
 #pragma unroll
-  for (int a = 0; a < 4; ++a) {
+  for (int a = 0; a < TA; ++a) {
     float mu[4][4], fb[4][4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const int cl = wave_n * 128 + a * 32 + 8 * g + 4 * half;  // channel inside the tile
+      const int cl = wave_n * (32 * TA) + a * 32 + 8 * g + 4 * half;  // channel inside the tile
       if (OUT_KIND != CWAC_OUT_INT32) {
         const float4 m4 = *reinterpret_cast<const float4 *>(s_mult + cl);
         mu[g][0] = m4.x; mu[g][1] = m4.y; mu[g][2] = m4.z; mu[g][3] = m4.w;
@@ -245,7 +247,7 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[4]
     }
     if (VEC && !I8) store_slab<OUT_KIND, WROWS>(slab, wbase + a * 32 * ESZ, row_bytes, lane);
   }
-  if (VEC && I8) store_slab<OUT_KIND, WROWS>(slab, wbase, row_bytes, lane);
+  if (VEC && I8) store_slab<OUT_KIND, WROWS, 32 * TA>(slab, wbase, row_bytes, lane);
 }
 
 // Statistics epilogue (Sec. 3.3, Eq. 4-5 fused into the calibration forward): instead of storing
@@ -423,10 +425,10 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
 
 template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false,
           int BN = 256>
-__global__ __launch_bounds__(64 * (BN / 128) * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(
+__global__ __launch_bounds__(64 * (BN >= 128 ? BN / 128 : 1) * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(
     const FwdParams p) {
   using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN>;
-  constexpr int TB = C::TB;
+  constexpr int TB = C::TB, TA = C::TA;
   static_assert(OUT_KIND != kOutStats ||
                     (BM == 256 && BN == 256 && C::RING >= 131072 && C::STATS_LDS_BYTES <= 160 * 1024),
                 "statistics epilogue: full-height tile, 128 KiB of ring for the slabs");
@@ -565,45 +567,57 @@ __global__ __launch_bounds__(64 * (BN / 128) * WM, (BM / (32 * WM)) == 2 ? 2 : 1
   // ---- LDS -> MFMA operand fragments (rows of a 32-row MFMA tile start at multiples of 16)
   const int swz_l = C::swz(l32);
   const int x_off = (wave_m * 32 * TB + l32) * BK;
-  const int w_off = C::X_BYTES + (wave_n * 128 + l32) * BK;
-  auto read_frags = [&](int buf, int kk, v4i(&fw)[4], v4i(&fx)[TB]) {
+  const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
+  auto read_frags = [&](int buf, int kk, v4i(&fw)[TA], v4i(&fx)[TB]) {
     const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
+    for (int a = 0; a < TA; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
 #pragma unroll
     for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
   };
 
-  v16i acc[4][TB];
-  auto mma = [&](const v4i(&fw)[4], const v4i(&fx)[TB]) {
+  v16i acc[TA][TB];
+  auto mma = [&](const v4i(&fw)[TA], const v4i(&fx)[TB]) {
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < TA; ++a)
 #pragma unroll
       for (int b = 0; b < TB; ++b)
         acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
   };
-  // Scheduler hint for one k-step (4 * TB MFMAs, 4 + TB LDS reads of the next step's fragments and,
+  // Scheduler hint for one k-step (TA * TB MFMAs, TA + TB LDS reads of the next step's fragments and,
   // when `loads`, one chunk of panel loads): the LDS reads go behind the first MFMAs one by one,
   // so that they land well before they are needed; the panel loads are spread over the remaining
-  // MFMAs, so that their issue never holds up the matrix pipe.
+  // MFMAs, so that their issue never holds up the matrix pipe.  (The 64 x 64 wave tile has as many
+  // reads as MFMAs: there the loads follow the reads, one group behind every MFMA.)
   auto interleave = [&](bool loads) {
-    constexpr int READS = 4 + TB, REST = 4 * TB - READS;
+    constexpr int READS = TA + TB, REST = TA * TB - READS;
+    if constexpr (REST <= 0) {
+      constexpr int GRP = (C::CHUNK + TA * TB - 1) / (TA * TB);
 #pragma unroll
-    for (int i = 0; i < READS; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    if (loads) {
-      constexpr int GRP = (C::CHUNK + REST - 1) / REST;  // loads behind each remaining MFMA
-#pragma unroll
-      for (int i = 0; i < REST; ++i) {
+      for (int i = 0; i < TA * TB; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, GRP, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (READS + TA * TB - 1) / (TA * TB), 0);
+        if (loads) __builtin_amdgcn_sched_group_barrier(0x020, GRP, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
     } else {
-      __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+#pragma unroll
+      for (int i = 0; i < READS; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      if (loads) {
+        constexpr int GRP = (C::CHUNK + REST - 1) / REST;  // loads behind each remaining MFMA
+#pragma unroll
+        for (int i = 0; i < REST; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, GRP, 0);
+        }
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // one k-step per scheduling region
     }
-    __builtin_amdgcn_sched_barrier(0);  // one k-step per scheduling region
   };
 
   // ---- prologue: fill the ring, stage the parameters, start the accumulators at offset[n]
@@ -627,17 +641,17 @@ __global__ __launch_bounds__(64 * (BN / 128) * WM, (BM / (32 * WM)) == 2 ? 2 : 1
     __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
   __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < TA; ++a)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      const v4i o = *reinterpret_cast<const v4i *>(s_off + wave_n * 128 + a * 32 + 8 * g + 4 * half);
+      const v4i o = *reinterpret_cast<const v4i *>(s_off + wave_n * (32 * TA) + a * 32 + 8 * g + 4 * half);
 #pragma unroll
       for (int b = 0; b < TB; ++b)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[a][b][4 * g + r] = o[r];
     }
 
-  v4i fwA[4], fxA[TB], fwB[4], fxB[TB];
+  v4i fwA[TA], fxA[TB], fwB[TA], fxB[TB];
   read_frags(0, 0, fwA, fxA);
 
   // One stage: KK k-steps.  Before the MFMAs of the last one, everybody has fetched its last
@@ -708,9 +722,9 @@ __global__ __launch_bounds__(64 * (BN / 128) * WM, (BM / (32 * WM)) == 2 ? 2 : 1
     constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed) ? 1 : 4;
     const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
     if (vs)
-      fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
     else
-      fast_epilogue<OUT_KIND, INT_ONLY, false, TB, WM>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      fast_epilogue<OUT_KIND, INT_ONLY, false, TB, WM, TA>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
   }
 }
 
@@ -773,8 +787,9 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   // Tuning knob (same results): CWAC_FWD_PIPE=8w is the 256-token tile with eight wavefronts (the
   // default for large layers), 128x2 | 64x4 the same tile with four wavefronts and that K step
   // and ring depth; "duo" the 128-token tile, two workgroups of four wavefronts per compute unit.
-  // layers narrower than 256 channels: 256 tokens x 128 channels, four wavefronts (4 x 1), 64-byte K
-  // steps, two workgroups per compute unit
+  // layers narrower than 256 channels: 256 tokens x 128 (64) channels, four wavefronts (4 x 1) of
+  // 64 x 128 (64 x 64), 64-byte K steps, two workgroups per compute unit
+  if (p.n < 128) return launch_cfg<256, 4, 64, 3, 2, false, 64>(p, out_kind, int_only, st);
   if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, false, 128>(p, out_kind, int_only, st);
   const char *e = getenv("CWAC_FWD_PIPE");
   if ((p.k % 128) != 0) e = "duo";  // K a multiple of 64 only: the tile that steps K by 64
@@ -789,13 +804,14 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
 }
 
 bool fast_conv_ok(const FwdParams &p, int64_t image_bytes) {
-  return p.m >= kFastTile && p.m < ((int64_t)1 << 31) && p.n >= 128 && (p.k % kFastKStep) == 0 &&
+  return p.m >= kFastTile && p.m < ((int64_t)1 << 31) && p.n >= 64 && (p.k % 64) == 0 &&
          (p.cv_cin % 64) == 0 && image_bytes < ((int64_t)1 << 31);
 }
 
 cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
+  if (p.n < 128) return launch_cfg<256, 4, 64, 3, 2, true, 64>(p, out_kind, int_only, st);
   if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, true, 128>(p, out_kind, int_only, st);
   // a stage must lie inside one filter tap: the 256-token tile steps K by 128, the 128-token tile by 64
   const bool full_ok = (p.cv_cin % 128) == 0;

@@ -236,14 +236,14 @@ static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_o
   if (n <= 160 && tile > 128) tile = 128;
   if (n <= 80 && tile > 64) tile = 64;
   // the large-problem kernel: K a multiple of 128, or of 64 (then only its 128-token tile, which
-  // steps K by 64); 128 <= N < 256: its 256 x 128 tile
-  const bool fast_ok = m >= kFastTile && n >= 128 && (k % 64) == 0;
+  // steps K by 64); 64 <= N < 256: its 256 x 128 or 256 x 64 tile
+  const bool fast_ok = m >= kFastTile && n >= 64 && (k % 64) == 0;
   // it wants most compute units busy: 160 full tiles, or 256 half tiles
   const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   bool fast = fast_ok && n >= kFastTile && (k % kFastKStep) == 0 &&
               (t256 >= 160 || fast_prefers_half_tile(m, n, k, out_bytes));
   if (fast_ok && n >= kFastTile && (k % kFastKStep) != 0) fast = ceil_div(m, 128) * ceil_div(n, 256) >= 160;
-  if (fast_ok && n < kFastTile) fast = ceil_div(m, 256) * ceil_div(n, 128) >= 160;
+  if (fast_ok && n < kFastTile) fast = ceil_div(m, 256) * ceil_div(n, n < 128 ? 64 : 128) >= 160;
   // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
   // the large-problem kernel where its shape constraints hold (results are identical).
   if (const char *e = getenv("CWAC_FWD_TILE")) {
@@ -355,7 +355,7 @@ extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q
   const int64_t image_bytes = (int64_t)batch * h * w * c_in;
   const bool fast_ok = fast_conv_ok(p, image_bytes);
   bool fast = fast_ok && (c_out >= 256 ? ceil_div(m, 128) * ceil_div(c_out, 256)
-                                      : ceil_div(m, 256) * ceil_div(c_out, 128)) >= 64;
+                                      : ceil_div(m, 256) * ceil_div(c_out, c_out < 128 ? 64 : 128)) >= 64;
   if (const char *e = getenv("CWAC_FWD_TILE")) {  // testing / tuning knob, as for the linear layer
     const int v = atoi(e);
     if (v == 256 || v == 128 || v == 64) {

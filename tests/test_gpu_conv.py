@@ -90,6 +90,8 @@ FAST_SHAPES = [  # batch, h, w, c_in, c_out, kh, kw, stride, pad, pipes
     (24, 9, 7, 128, 256, 3, 3, 2, 0, ("8w",)),            # stride 2 without padding
     (2, 14, 14, 128, 128, 3, 3, 1, 1, ("duo",)),          # fewer than 256 output channels: the 256 x 128 tile
     (3, 11, 13, 64, 176, 2, 2, 1, 1, ("duo",)),           # ... with overlapping channel tiles, 64 channels per tap
+    (4, 14, 14, 64, 64, 3, 3, 1, 1, ("duo",)),            # 64 output channels: the 256 x 64 tile; K = 576
+    (8, 12, 12, 128, 96, 3, 3, 2, 1, ("duo",)),           # ... overlapping 64-channel tiles, stride 2
 ]
 
 
@@ -217,11 +219,13 @@ def test_conv_calibration_pipeline(orc):
     np.testing.assert_array_equal(out.cpu().numpy(), want)
 
 
-@pytest.mark.parametrize("b,h,c,n", [(64, 14, 256, 256), (128, 14, 256, 256), (32, 28, 128, 128)])
+@pytest.mark.parametrize("b,h,c,n", [(64, 14, 256, 256), (128, 14, 256, 256), (32, 28, 128, 128),
+                                     (8, 56, 64, 64)])
 def test_conv_large_layer_sampled(orc, b, h, c, n):
-    """ResNet-50-sized 3x3 layers (M = 12544 / 25088, K = 2304; M = 25088, N = 128, K = 1152) in the
-    automatic kernel choice (the generic kernel / the direct-to-LDS kernel in its 128 x 256 and
-    256 x 128 tiles); the oracle checks whole images (first, last) position by position."""
+    """ResNet-50-sized 3x3 layers (M = 12544 / 25088, K = 2304; M = 25088, N = 128, K = 1152; M = 25088,
+    N = 64, K = 576) in the automatic kernel choice (the generic kernel / the direct-to-LDS kernel in
+    its 128 x 256, 256 x 128 and 256 x 64 tiles); the oracle checks whole images (first, last)
+    position by position."""
     w, k = h, 3
     xq = torch.randint(-128, 128, (b, h, w, c), dtype=torch.int8, device=DEV,
                        generator=torch.Generator(device=DEV).manual_seed(5))

@@ -223,7 +223,9 @@ def test_forward_ragged_shapes(orc, m, n, k):
                                    # K a multiple of 64 only: every pipe falls to the 64-byte K step
                                    (300, 520, 64), (520, 300, 192), (700, 256, 320),
                                    # fewer than 256 channels: the 256 x 128 tile, whatever the pipe
-                                   (300, 128, 128), (520, 200, 192), (700, 255, 320)])
+                                   (300, 128, 128), (520, 200, 192), (700, 255, 320),
+                                   # fewer than 128: the 256 x 64 tile (64 x 64 wave tiles)
+                                   (300, 64, 128), (520, 100, 192), (700, 127, 320)])
 def test_forward_large_tile_kernel(orc, m, n, k, pipe):
     """The direct-to-LDS kernel (forced) in its three pipeline shapes - 256-token tiles with a
     128-byte or 64-byte K step, 128-token tiles with two workgroups per compute unit: edge tiles
