@@ -215,6 +215,8 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st);
 // True where that kernel would take its 128-token tile shape (two workgroups per compute unit).
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);
+// True where it would take 128 x 128 tiles (layers with few tiles and a long K loop).
+bool fast_prefers_quarter_tile(int64_t m, int n);
 // The same kernel as an implicit-GEMM convolution (p.cv_* set, p.ldx unused).  fast_conv_ok: its shape
 // constraints (m >= 256, n >= 64, c_in % 64 == 0, image below 2 GiB).
 bool fast_conv_ok(const FwdParams &p, int64_t image_bytes);

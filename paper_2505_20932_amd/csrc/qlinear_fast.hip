@@ -52,10 +52,10 @@ constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
   return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
 }
 
-template <int BM_, int WM_, int BK, int NSTAGE, int NCHUNK, int BN_ = 256>
+template <int BM_, int WM_, int BK, int NSTAGE, int NCHUNK, int BN_ = 256, int TA_ = 0>
 struct FastCfg {
   static constexpr int BM = BM_, BN = BN_;
-  static constexpr int TA = BN >= 128 ? 4 : BN / 32;  // 32-channel MFMA tiles per wavefront
+  static constexpr int TA = TA_ ? TA_ : (BN >= 128 ? 4 : BN / 32);  // 32-channel MFMA tiles per wavefront
   static constexpr int WM = WM_, WN = BN / (32 * TA);  // wavefronts along m and n
   static constexpr int NWAVES = WN * WM, NT = 64 * NWAVES;
   static constexpr int TB = BM / (32 * WM);      // 32-token MFMA tiles per wavefront
@@ -424,10 +424,10 @@ __device__ __forceinline__ void stats_epilogue(const FwdParams &p, v16i (&acc)[4
 }
 
 template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false,
-          int BN = 256>
-__global__ __launch_bounds__(64 * (BN >= 128 ? BN / 128 : 1) * WM, (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(
+          int BN = 256, int TA_ = 0>
+__global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT), (BM / (32 * WM)) == 2 ? 2 : 1) void qlinear_fast_kernel(
     const FwdParams p) {
-  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN>;
+  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>;
   constexpr int TB = C::TB, TA = C::TA;
   static_assert(OUT_KIND != kOutStats ||
                     (BM == 256 && BN == 256 && C::RING >= 131072 && C::STATS_LDS_BYTES <= 160 * 1024),
@@ -729,19 +729,19 @@ __global__ __launch_bounds__(64 * (BN >= 128 ? BN / 128 : 1) * WM, (BM / (32 * W
 }
 
 template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false,
-          int BN = 256>
+          int BN = 256, int TA = 0>
 cwac_status launch_one(const FwdParams &p, dim3 grid, hipStream_t st) {
-  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN>;
+  using C = FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA>;
   constexpr int LDS = OUT_KIND == kOutStats ? C::STATS_LDS_BYTES : C::LDS_BYTES;
   static const hipError_t attr = hipFuncSetAttribute(
-      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV, BN>),
+      reinterpret_cast<const void *>(&qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV, BN, TA>),
       hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV, BN><<<grid, C::NT, LDS, st>>>(p);
+  qlinear_fast_kernel<BM, WM, BK, NSTAGE, NCHUNK, OUT_KIND, INT_ONLY, CONV, BN, TA><<<grid, C::NT, LDS, st>>>(p);
   return launch_status();
 }
 
-template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, bool CONV = false, int BN = 256>
+template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, bool CONV = false, int BN = 256, int TA = 0>
 cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   p.tiles_m = (int)ceil_div(p.m, BM);
   p.tiles_n = (int)ceil_div(p.n, BN);
@@ -750,14 +750,14 @@ cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st)
   const dim3 grid((unsigned)blocks);
   if constexpr (!CONV) {
     if (out_kind == kOutFixed)
-      return launch_one<BM, WM, BK, NSTAGE, NCHUNK, kOutFixed, true, false, BN>(p, grid, st);
+      return launch_one<BM, WM, BK, NSTAGE, NCHUNK, kOutFixed, true, false, BN, TA>(p, grid, st);
   }
   if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true, CONV, BN>(p, grid, st)
-                    : launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false, CONV, BN>(p, grid, st);
+    return int_only ? launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, true, CONV, BN, TA>(p, grid, st)
+                    : launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT8, false, CONV, BN, TA>(p, grid, st);
   if (out_kind == CWAC_OUT_FP32)
-    return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false, CONV, BN>(p, grid, st);
-  return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false, CONV, BN>(p, grid, st);
+    return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_FP32, false, CONV, BN, TA>(p, grid, st);
+  return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false, CONV, BN, TA>(p, grid, st);
 }
 
 }  // namespace
@@ -781,6 +781,15 @@ bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes) {
   return cost_half < cost_full;
 }
 
+bool fast_prefers_quarter_tile(int64_t m, int n) {
+  // Layers with too few 128 x 256 tiles to occupy the chip: a tile's duration is the K loop of one
+  // wavefront, so 128 x 128 tiles of four 64 x 64 wavefronts (half the MFMAs per wavefront and K step,
+  // twice the tiles) finish sooner.  Thresholds from measurements on LLM layer shapes at 256-2048
+  // tokens and ResNet-50 stage 5: ahead from 96 such tiles on, until 160 half tiles exist.
+  const int64_t t_half = ceil_div(m, 128) * ceil_div(n, 256), t_q = ceil_div(m, 128) * ceil_div(n, 128);
+  return n >= 128 && t_half < 160 && t_q >= 96;
+}
+
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
   const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
@@ -792,6 +801,8 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st
   if (p.n < 128) return launch_cfg<256, 4, 64, 3, 2, false, 64>(p, out_kind, int_only, st);
   if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, false, 128>(p, out_kind, int_only, st);
   const char *e = getenv("CWAC_FWD_PIPE");
+  if ((e && e[0] == 'q') || (!e && fast_prefers_quarter_tile(p.m, p.n)))
+    return launch_cfg<128, 2, 64, 3, 2, false, 128, 2>(p, out_kind, int_only, st);
   if ((p.k % 128) != 0) e = "duo";  // K a multiple of 64 only: the tile that steps K by 64
   if (e && e[0] == 'd') return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
   if (e && e[0] == '6') return launch_cfg<256, 2, 64, 4, 2>(p, out_kind, int_only, st);
@@ -815,7 +826,9 @@ cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, hipStream
   if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, true, 128>(p, out_kind, int_only, st);
   // a stage must lie inside one filter tap: the 256-token tile steps K by 128, the 128-token tile by 64
   const bool full_ok = (p.cv_cin % 128) == 0;
-  const char *e = getenv("CWAC_FWD_PIPE");  // tuning knob (same results): "8w" | "duo"
+  const char *e = getenv("CWAC_FWD_PIPE");  // tuning knob (same results): "8w" | "duo" | "q"
+  if ((e && e[0] == 'q') || (!e && fast_prefers_quarter_tile(p.m, p.n)))
+    return launch_cfg<128, 2, 64, 3, 2, true, 128, 2>(p, out_kind, int_only, st);
   bool half = !full_ok || fast_prefers_half_tile(p.m, p.n, p.k, (int)esz) ||
               ceil_div(p.m, 256) * ceil_div(p.n, 256) < 160;
   if (e && e[0] == 'd') half = true;

@@ -244,6 +244,7 @@ static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_o
               (t256 >= 160 || fast_prefers_half_tile(m, n, k, out_bytes));
   if (fast_ok && n >= kFastTile && (k % kFastKStep) != 0) fast = ceil_div(m, 128) * ceil_div(n, 256) >= 160;
   if (fast_ok && n < kFastTile) fast = ceil_div(m, 256) * ceil_div(n, n < 128 ? 64 : 128) >= 160;
+  if (fast_ok && n >= kFastTile && fast_prefers_quarter_tile(m, n)) fast = true;
   // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
   // the large-problem kernel where its shape constraints hold (results are identical).
   if (const char *e = getenv("CWAC_FWD_TILE")) {
@@ -356,6 +357,7 @@ extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q
   const bool fast_ok = fast_conv_ok(p, image_bytes);
   bool fast = fast_ok && (c_out >= 256 ? ceil_div(m, 128) * ceil_div(c_out, 256)
                                       : ceil_div(m, 256) * ceil_div(c_out, c_out < 128 ? 64 : 128)) >= 64;
+  if (fast_ok && c_out >= 256 && fast_prefers_quarter_tile(m, c_out)) fast = true;
   if (const char *e = getenv("CWAC_FWD_TILE")) {  // testing / tuning knob, as for the linear layer
     const int v = atoi(e);
     if (v == 256 || v == 128 || v == 64) {

@@ -83,9 +83,9 @@ def test_conv_all_modes(orc, shape, tile):
 
 
 FAST_SHAPES = [  # batch, h, w, c_in, c_out, kh, kw, stride, pad, pipes
-    (2, 14, 14, 128, 256, 3, 3, 1, 1, ("8w", "duo")),     # ResNet-style 3x3, two row tiles that overlap
+    (2, 14, 14, 128, 256, 3, 3, 1, 1, ("8w", "duo", "q")),  # ResNet-style 3x3, row tiles that overlap
     (5, 12, 11, 64, 300, 4, 4, 1, 2, ("duo",)),           # 64 channels: one K step per tap; ragged channel edge
-    (2, 23, 21, 128, 256, 7, 7, 2, 3, ("8w", "duo")),     # 7x7 / 2 with padding 3: most taps of the border rows are outside
+    (2, 23, 21, 128, 256, 7, 7, 2, 3, ("8w", "duo", "q")),  # 7x7 / 2 with padding 3: most taps of the border rows are outside
     (3, 10, 16, 256, 260, 3, 5, 1, 2, ("8w", "duo")),     # rectangular filter, two K steps per tap
     (24, 9, 7, 128, 256, 3, 3, 2, 0, ("8w",)),            # stride 2 without padding
     (2, 14, 14, 128, 128, 3, 3, 1, 1, ("duo",)),          # fewer than 256 output channels: the 256 x 128 tile

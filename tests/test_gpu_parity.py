@@ -217,7 +217,7 @@ def test_forward_ragged_shapes(orc, m, n, k):
             np.testing.assert_array_equal(got[:, :n], want)
 
 
-@pytest.mark.parametrize("pipe", ["128x2", "64x4", "duo", "8w"])
+@pytest.mark.parametrize("pipe", ["128x2", "64x4", "duo", "8w", "q"])
 @pytest.mark.parametrize("m,n,k", [(256, 256, 128), (300, 520, 384), (700, 1030, 1152),
                                    (513, 768, 256),
                                    # K a multiple of 64 only: every pipe falls to the 64-byte K step
