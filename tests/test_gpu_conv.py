@@ -220,12 +220,12 @@ def test_conv_calibration_pipeline(orc):
 
 
 @pytest.mark.parametrize("b,h,c,n", [(64, 14, 256, 256), (128, 14, 256, 256), (32, 28, 128, 128),
-                                     (8, 56, 64, 64)])
+                                     (8, 56, 64, 64), (128, 7, 512, 512)])
 def test_conv_large_layer_sampled(orc, b, h, c, n):
     """ResNet-50-sized 3x3 layers (M = 12544 / 25088, K = 2304; M = 25088, N = 128, K = 1152; M = 25088,
-    N = 64, K = 576) in the automatic kernel choice (the generic kernel / the direct-to-LDS kernel in
-    its 128 x 256, 256 x 128 and 256 x 64 tiles); the oracle checks whole images (first, last)
-    position by position."""
+    N = 64, K = 576; M = 6272, N = 512, K = 4608) in the automatic kernel choice (the generic kernel / the
+    direct-to-LDS kernel in its 128 x 256, 256 x 128, 256 x 64 and 128 x 128 tiles); the oracle checks whole
+    images (first, last) position by position."""
     w, k = h, 3
     xq = torch.randint(-128, 128, (b, h, w, c), dtype=torch.int8, device=DEV,
                        generator=torch.Generator(device=DEV).manual_seed(5))

@@ -29,9 +29,20 @@ def _dev(a):
 
 @pytest.mark.parametrize("cfg,layer", LAYERS)
 def test_full_size_forward(orc, cfg, layer):
+    _check_forward(orc, cfg, layer, synth.WORKLOADS[cfg].m)
+
+
+@pytest.mark.parametrize("layer,m", [(0, 512), (1, 1024), (4, 1024), (1, 256)])
+def test_llm_layers_few_tokens(orc, layer, m):
+    """Workload 5's layer shapes at 256-1024 tokens: few tiles and a long K loop, where the automatic
+    choice takes the 128 x 128 tile of the direct-to-LDS kernel (or small generic tiles)."""
+    _check_forward(orc, 5, layer, m)
+
+
+def _check_forward(orc, cfg, layer, m):
     wl = synth.WORKLOADS[cfg]
     ly = wl.layers[layer]
-    m, n, k = wl.m, ly.n, ly.k
+    n, k = ly.n, ly.k
     print(f"config {cfg} layer {ly.name}: {m} x {n} x {k}", flush=True)
     w_t, b_t = synth.weights(wl, layer)
     x_t = synth.activations(wl, layer, m)
