@@ -501,7 +501,9 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
       const int b = r / plane, rem = r - b * plane;
       const int oy = rem / p.cv_ow, ox = rem - oy * p.cv_ow;
       const int iy0 = oy * p.cv_stride - p.cv_pad, ix0 = ox * p.cv_stride - p.cv_pad;
-      xvo[i] = (uint32_t)(((b * p.cv_h + iy0) * p.cv_w + ix0) * p.cv_cin + (pc ^ C::swz(row)) * 16);
+      // (mod 2^32: the sum with the tap offset is the true offset, below 2^31, for every tap inside)
+      xvo[i] = ((uint32_t)(b * p.cv_h + iy0) * (uint32_t)p.cv_w + (uint32_t)ix0) * (uint32_t)p.cv_cin +
+               (uint32_t)((pc ^ C::swz(row)) * 16);
       // taps kh with 0 <= iy0 + kh < h: kh in [max(0, -iy0), min(15, h - 1 - iy0)] (never empty)
       auto span = [](int lo, int hi) {
         lo = lo < 0 ? 0 : lo;
@@ -523,7 +525,7 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
   // convolution: the tap of the stage whose loads are being issued (wave-uniform; stages are
   // loaded in order, so it steps forward at the first chunk of every stage after stage 0)
   int tap_c = 0, tap_kw = 0, tap_kh = 0;
-  int tap_off = 0;           // byte offset of the tap and channel block from tap (0, 0), channel 0
+  uint32_t tap_off = 0;      // byte offset of the tap and channel block from tap (0, 0), channel 0 (mod 2^32)
   uint32_t tap_sel = 0x10001u;  // bit kh | bit 16 + kw
   const int8_t *pad = reinterpret_cast<const int8_t *>(kPadCodes.v) + (p.cv_pad4 & 255) * 16;
 
@@ -541,7 +543,7 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
           ++tap_kh;
         }
       }
-      tap_off = (tap_kh * p.cv_w + tap_kw) * p.cv_cin + tap_c;
+      tap_off = ((uint32_t)tap_kh * (uint32_t)p.cv_w + (uint32_t)tap_kw) * (uint32_t)p.cv_cin + (uint32_t)tap_c;
       tap_sel = (1u << tap_kh) | (0x10000u << tap_kw);
     }
 #pragma unroll
@@ -550,7 +552,7 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
       if (i >= C::chunk_begin(c + 1)) break;
       if (i < C::LOADS_X && CONV) {
         const bool inside = (xin[i] & tap_sel) == tap_sel;
-        const int8_t *src = inside ? xtile + (uint32_t)(xvo[i] + (uint32_t)tap_off) : pad;
+        const int8_t *src = inside ? xtile + (uint32_t)(xvo[i] + tap_off) : pad;
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(src), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
       } else if (i < C::LOADS_X)
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
