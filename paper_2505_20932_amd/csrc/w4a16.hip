@@ -497,7 +497,7 @@ cwac_status launch_w4(const W4Params &p, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Small batches (m <= 32 tokens: the decode step of an LLM).  The layer is then bound by the
+// Small batches (32 tokens per launch: the decode step of an LLM).  The layer is then bound by the
 // stream of 4-bit weights, not by the matrix cores: one workgroup of NW (4 or 8) wavefronts owns 32 output
 // channels (one row of 1 KiB blocks of the packed layout) over the whole of K, each wavefront a
 // contiguous quarter of the groups; the codes arrive with the same contiguous 16-byte-per-lane loads
@@ -507,6 +507,7 @@ cwac_status launch_w4(const W4Params &p, hipStream_t st) {
 // (deterministic), then the epilogue of the tiled kernel.  No workspace, no atomics.
 // ------------------------------------------------------------------------------------------
 constexpr int kSmallM = 32;
+constexpr int kSmallPasses = 4;  // batches of up to 128 rows take this kernel, 32 rows per launch
 
 template <int OUT_KIND, int NW>
 __global__ __launch_bounds__(64 * NW) void w4a16_small_m_kernel(const W4Params p) {
@@ -700,9 +701,21 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
   // Tuning / testing knob (results agree to the rounding of the fp32 sums): CWAC_W4_PIPE=tile keeps
   // the 256-token tiles for small batches too.
   const char *e = getenv("CWAC_W4_PIPE");
-  if (m <= kSmallM && !(e && e[0] == 't'))
-    return out_kind == CWAC_OUT_FP16 ? launch_w4_small<CWAC_OUT_FP16>(p, as_stream(stream))
-                                     : launch_w4_small<CWAC_OUT_FP32>(p, as_stream(stream));
+  if (m <= kSmallPasses * kSmallM && !(e && e[0] == 't')) {
+    // up to four passes of the weight-streaming kernel over blocks of 32 rows: the packed weights
+    // of a layer stay in the last-level cache between passes, and a 256-token tile would leave
+    // most of the chip idle at these sizes (one row of tiles, each as long as its K loop)
+    for (int64_t r0 = 0; r0 < m; r0 += kSmallM) {
+      W4Params q = p;
+      q.x = p.x + r0 * p.ldx_bytes;
+      q.out = p.out + r0 * ldo * esz;
+      q.m = m - r0 < kSmallM ? m - r0 : kSmallM;
+      const cwac_status s = out_kind == CWAC_OUT_FP16 ? launch_w4_small<CWAC_OUT_FP16>(q, as_stream(stream))
+                                                      : launch_w4_small<CWAC_OUT_FP32>(q, as_stream(stream));
+      if (s != CWAC_OK) return s;
+    }
+    return CWAC_OK;
+  }
   return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16>(p, as_stream(stream))
                                    : launch_w4<CWAC_OUT_FP32>(p, as_stream(stream));
 }

@@ -215,7 +215,7 @@ def test_small_batch_padded_activation_pitch(w4):
     np.testing.assert_array_equal(out.cpu().numpy(), acc.astype(np.float32))
 
 
-@pytest.mark.parametrize("m,n,k", [(8, 512, 4096), (32, 12288, 4096), (16, 4096, 11008)])
+@pytest.mark.parametrize("m,n,k", [(8, 512, 4096), (32, 12288, 4096), (16, 4096, 11008), (100, 512, 4096)])
 def test_small_batch_workload_like(w4, m, n, k):
     """Decode-sized batches on LLM-like operands, up to the largest layer shapes of workload 5:
     every output inside the rounding bound of an fp32 summation of the exact products."""
