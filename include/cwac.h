@@ -380,9 +380,9 @@ cwac_status cwac_fold_weight_only(const float *alpha, const float *beta, const f
  *   mult, fbias  device fp32 [n] or NULL
  *   out        device [m, n], ldo; 16-byte aligned, ldo * sizeof(element) % 16 == 0
  * Batches of at most 128 rows (decoding steps) take a kernel that streams the packed
- * weights once per 32 rows, 32 output channels per workgroup; larger batches 256 x 256
- * tiles.  Both compute the sum above; they differ in the order of the fp32 accumulation
- * only. */
+ * weights once per 32 rows, 32 output channels per workgroup; larger batches tiles of
+ * 256 channels x 128 tokens while those fit the chip in one round, else x 256 tokens.
+ * All compute the sum above; they differ in the order of the fp32 accumulation only. */
 cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const void *packed_w,
                                        const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
                                        const float *mult, const float *fbias, int32_t out_kind,

@@ -20,6 +20,9 @@
 //     and one packed multiply by the scale is the single rounding of RN16(s * (c - z)).
 //   * Epilogue in registers: acc * mult[n] + fbias[n] (two fp32 operations), conversion to
 //     binary16, transposition through a wave-private LDS slab, whole 128-byte line stores.
+// The same kernel with 128-token tiles (two token blocks per wavefront) serves batches whose
+// 128-token tiles fit the chip in one round; batches of up to 128 tokens take the
+// weight-streaming kernel further down.
 #include <hip/hip_runtime.h>
 
 #include <stdlib.h>
@@ -152,16 +155,26 @@ struct W4Params {
   int tiles_m, tiles_n;
 };
 
-constexpr int kFwdThreads = 512;         // 8 wavefronts: 2 per SIMD
-constexpr int kTA = 2, kTB = 4;          // MFMA tiles per wavefront: 64 channels x 128 tokens
-constexpr int kStageBytes = 256 * 256;   // 256 rows x 128 binary16
-constexpr int kRing = 2 * kStageBytes;
-constexpr int kXLoads = 8;  // global_load_lds per wavefront and stage (4 rows x 256 bytes each)
+constexpr int kFwdThreads = 512;  // 8 wavefronts: 2 per SIMD
+constexpr int kTA = 2;            // MFMA row blocks per wavefront: 64 channels
 constexpr int kSlabStride = 144;
-constexpr int kSlabBytes = 128 * kSlabStride;
-constexpr int kParams = 8 * kSlabBytes;  // epilogue parameters sit behind the ring and the slabs
-constexpr int kW4Lds = kParams + 2 * 256 * 4;
-static_assert(kParams >= kRing && kW4Lds <= 160 * 1024, "LDS budget of one compute unit");
+// Tile of 256 channels x (64 * TB) tokens: 2 x 4 wavefronts of TB token blocks x kTA channel
+// blocks of 32.  TB = 4 is the tile of large batches; TB = 2 halves it for batches of a few hundred
+// tokens, where one row of 256-token tiles would leave most compute units idle.
+template <int TB>
+struct W4Cfg {
+  static constexpr int BM = 64 * TB;
+  static constexpr int STAGE_BYTES = BM * 256;  // BM rows x 128 binary16
+  static constexpr int RING = 2 * STAGE_BYTES;
+  static constexpr int XROWS = BM / 8;          // activation rows one wavefront fetches per stage
+  static constexpr int XLOADS = XROWS / 4;      // global_load_lds per wavefront and stage (4 rows x 256 bytes each)
+  static constexpr int SLAB_ROWS = 32 * TB;
+  static constexpr int SLAB_BYTES = SLAB_ROWS * kSlabStride;
+  // epilogue parameters sit behind the ring and the slabs
+  static constexpr int PARAMS = 8 * SLAB_BYTES > RING ? 8 * SLAB_BYTES : RING;
+  static constexpr int LDS = PARAMS + 2 * 256 * 4;
+  static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
+};
 
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 
@@ -225,12 +238,12 @@ __device__ __forceinline__ h8 expand8(uint32_t w, const GroupConst &g, const Exp
   return h8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
 }
 
-template <int OUT_KIND>
+template <int OUT_KIND, int ROWS>
 __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int64_t row_bytes,
                                            int64_t rows_left, int lane) {
   const int rd_row = lane >> 3, rd_chunk = lane & 7;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
+  for (int i = 0; i < ROWS / 8; ++i) {
     const int row = i * 8 + rd_row;
     const u4 v = *reinterpret_cast<const u4 *>(slab + row * kSlabStride + rd_chunk * 16);
     u4 *dst = reinterpret_cast<u4 *>(gbase + row * row_bytes + rd_chunk * 16);
@@ -246,20 +259,20 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
 }
 
 // Accumulator element 4*g + r of tile (a, b): channel n = bn0 + wave_n*64 + a*32 + 8*g + 4*half + r,
-// token m = bm0 + wave_m*128 + b*32 + l32.  Each wavefront transposes its 128 rows x 128 bytes
+// token m = bm0 + wave_m*32*TB + b*32 + l32.  Each wavefront transposes its 32*TB rows x 128 bytes
 // through a private LDS slab (row stride 144 bytes) and writes whole 128-byte lines: binary16
 // output = all 64 channels of the wave tile in one slab, fp32 output = one slab per MFMA column.
-template <int OUT_KIND>
-__device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[kTA][kTB], int8_t *smem,
+template <int OUT_KIND, int TB>
+__device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[kTA][TB], int8_t *smem,
                                             const float *s_mult, const float *s_fb, int64_t bm0, int bn0,
                                             int wave_m, int wave_n, int lane) {
   constexpr int ESZ = OUT_KIND == CWAC_OUT_FP16 ? 2 : 4;
   constexpr int APS = OUT_KIND == CWAC_OUT_FP16 ? 2 : 1;  // MFMA columns per 128-byte slab row
   const int l32 = lane & 31, half = lane >> 5;
   const int wave = wave_m + 2 * wave_n;
-  int8_t *slab = smem + wave * kSlabBytes;
+  int8_t *slab = smem + wave * W4Cfg<TB>::SLAB_BYTES;
   const int64_t row_bytes = p.ldo * ESZ;
-  const int64_t wrow0 = bm0 + wave_m * 128;
+  const int64_t wrow0 = bm0 + wave_m * 32 * TB;
   char *wbase = p.out + (wrow0 * p.ldo + bn0 + wave_n * 64) * ESZ;
   const int64_t rows_left = p.m - wrow0;
 #pragma unroll
@@ -274,7 +287,7 @@ __device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[kTA][
       fb[g][0] = f4.x; fb[g][1] = f4.y; fb[g][2] = f4.z; fb[g][3] = f4.w;
     }
 #pragma unroll
-    for (int b = 0; b < kTB; ++b) {
+    for (int b = 0; b < TB; ++b) {
       const int row = b * 32 + l32;  // row inside the wave tile
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -295,25 +308,27 @@ __device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[kTA][
       }
     }
     if (a % APS == APS - 1)
-      store_slab<OUT_KIND>(slab, wbase + (a / APS) * 128, row_bytes, rows_left, lane);
+      store_slab<OUT_KIND, 32 * TB>(slab, wbase + (a / APS) * 128, row_bytes, rows_left, lane);
   }
 }
 
-template <int OUT_KIND>
+template <int OUT_KIND, int TB>
 __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
+  using Cfg = W4Cfg<TB>;
+  constexpr int kXLoads = Cfg::XLOADS, kStageBytes = Cfg::STAGE_BYTES, kParams = Cfg::PARAMS;
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   float *s_mult = reinterpret_cast<float *>(smem + kParams);
   float *s_fb = reinterpret_cast<float *>(smem + kParams + 1024);
 
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
-  const int64_t bm0 = (int64_t)tile_m * 256;  // row edges: clamped loads, predicated stores
+  const int64_t bm0 = (int64_t)tile_m * Cfg::BM;  // row edges: clamped loads, predicated stores
   int bn0 = tile_n * 256;
   if (bn0 > p.n - 256) bn0 = p.n - 256;  // channel edge: tile shifted inwards (n % 32 == 0)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave & 1, wave_n = wave >> 1;  // 2 x 4 wavefronts of 128 tokens x 64 channels
+  const int wave_m = wave & 1, wave_n = wave >> 1;  // 2 x 4 wavefronts of 32*TB tokens x 64 channels
   const int l32 = lane & 31, half = lane >> 5;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
 
@@ -323,13 +338,13 @@ __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
     if (p.fbias) p_fb = p.fbias[bn0 + tid];
   }
 
-  // ---- activations, global -> LDS: wavefront `wave` owns rows [32*wave, 32*wave + 32), 8 loads
-  // of 4 rows; lane = (row lr, slot pc) fetches 16-byte chunk pc ^ (row & 15) of its row
+  // ---- activations, global -> LDS: wavefront `wave` owns XROWS consecutive rows, fetched 4
+  // rows per load; lane = (row lr, slot pc) fetches 16-byte chunk pc ^ (row & 15) of its row
   const int lr = lane >> 4, pc = lane & 15;
   uint32_t xvo[kXLoads];
 #pragma unroll
   for (int i = 0; i < kXLoads; ++i) {
-    const int row = wave * 32 + i * 4 + lr;
+    const int row = wave * Cfg::XROWS + i * 4 + lr;
     int64_t grow = bm0 + row;
     if (grow > p.m - 1) grow = p.m - 1;
     xvo[i] = (uint32_t)((grow - bm0) * p.ldx_bytes) + (uint32_t)((pc ^ (row & 15)) << 4);
@@ -344,7 +359,7 @@ __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
     return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
   };
   auto issue_x = [&](int buf, int stage) {
-    int8_t *sx = smem + buf * kStageBytes + wave_s * 32 * 256;
+    int8_t *sx = smem + buf * kStageBytes + wave_s * Cfg::XROWS * 256;
     const char *xk = uniform(xtile + (int64_t)stage * 256);
 #pragma unroll
     for (int i = 0; i < kXLoads; ++i)
@@ -375,51 +390,51 @@ __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
   constexpr int kWLoads = 3 * kTA;
 
   // ---- LDS -> activation operand fragments
-  const int x_off = (wave_m * 128 + l32) * 256;
+  const int x_off = (wave_m * 32 * TB + l32) * 256;
   const int swz_l = l32 & 15;
-  auto read_x = [&](int buf, int kk, h8(&fx)[kTB]) {
+  auto read_x = [&](int buf, int kk, h8(&fx)[TB]) {
     const int8_t *base = smem + buf * kStageBytes + x_off + (((2 * kk + half) ^ swz_l) << 4);
 #pragma unroll
-    for (int b = 0; b < kTB; ++b) fx[b] = *reinterpret_cast<const h8 *>(base + b * 32 * 256);
+    for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const h8 *>(base + b * 32 * 256);
   };
   auto expand_w = [&](const RawW &r, const GroupConst (&gc)[kTA], int kk, h8(&fw)[kTA]) {
 #pragma unroll
     for (int a = 0; a < kTA; ++a) fw[a] = expand8(r.c[a][kk >> 2][kk & 3], gc[a]);
   };
 
-  v16f acc[kTA][kTB];
+  v16f acc[kTA][TB];
 #pragma unroll
   for (int a = 0; a < kTA; ++a)
 #pragma unroll
-    for (int b = 0; b < kTB; ++b)
+    for (int b = 0; b < TB; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
-  auto mma = [&](const h8(&fw)[kTA], const h8(&fx)[kTB]) {
+  auto mma = [&](const h8(&fw)[kTA], const h8(&fx)[TB]) {
 #pragma unroll
     for (int a = 0; a < kTA; ++a)
 #pragma unroll
-      for (int b = 0; b < kTB; ++b)
+      for (int b = 0; b < TB; ++b)
         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[a], fx[b], acc[a][b], 0, 0, 0);
   };
   // Scheduler hint for one k-step: first the LDS reads of the next step's activation fragments,
-  // then 8 MFMAs; the expansion of the next step's weight fragments (about
+  // then kTA * TB MFMAs; the expansion of the next step's weight fragments (about
   // 35 vector ALU operations) spread evenly behind all of them; `vmem` loads spread likewise.
   auto interleave = [&](int vmem) {
-    __builtin_amdgcn_sched_group_barrier(0x100, kTB, 0);  // the next step's LDS reads go first
+    __builtin_amdgcn_sched_group_barrier(0x100, TB, 0);  // the next step's LDS reads go first
 #pragma unroll
-    for (int i = 0; i < kTA * kTB; ++i) {
+    for (int i = 0; i < kTA * TB; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       if (i < vmem) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 40 / (kTA * TB), 0);
     }
     __builtin_amdgcn_sched_barrier(0);  // one k-step per scheduling region
   };
 
-  // ---- prologue.  Load order: X(0), W(0), X(1); waiting for all but the last 8 leaves X(1) in flight.
+  // ---- prologue.  Load order: X(0), W(0), X(1); waiting for all but the last kXLoads leaves X(1) in flight.
   const int stages = p.k / kGroup;
   RawW rawA, rawB;
   GroupConst gc[kTA];
-  h8 fxA[kTB], fxB[kTB], fwA[kTA], fwB[kTA];
+  h8 fxA[TB], fxB[TB], fwA[kTA], fwB[kTA];
   issue_x(0, 0);
   issue_w(rawA, 0);
   if (stages > 1) issue_x(1, 1);
@@ -481,18 +496,18 @@ __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
   if (s < stages) stage_body(s, 0, rawA, rawB);
 
   // every wavefront is past its last LDS read of the ring (the barrier of the last stage)
-  w4_epilogue<OUT_KIND>(p, acc, smem, s_mult, s_fb, bm0, bn0, wave_m, wave_n, lane);
+  w4_epilogue<OUT_KIND, TB>(p, acc, smem, s_mult, s_fb, bm0, bn0, wave_m, wave_n, lane);
 }
 
-template <int OUT_KIND>
+template <int OUT_KIND, int TB>
 cwac_status launch_w4(const W4Params &p, hipStream_t st) {
   static const hipError_t attr =
-      hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a16_kernel<OUT_KIND>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, kW4Lds);
+      hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a16_kernel<OUT_KIND, TB>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, W4Cfg<TB>::LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  w4a16_kernel<OUT_KIND><<<dim3((unsigned)blocks), kFwdThreads, kW4Lds, st>>>(p);
+  w4a16_kernel<OUT_KIND, TB><<<dim3((unsigned)blocks), kFwdThreads, W4Cfg<TB>::LDS, st>>>(p);
   return launch_status();
 }
 
@@ -507,6 +522,7 @@ cwac_status launch_w4(const W4Params &p, hipStream_t st) {
 // (deterministic), then the epilogue of the tiled kernel.  No workspace, no atomics.
 // ------------------------------------------------------------------------------------------
 constexpr int kSmallM = 32;
+constexpr int kHalfTileUpTo = 256;  // 128-token tiles in a launch up to which they are taken (one per compute unit)
 constexpr int kSmallPasses = 4;  // batches of up to 128 rows take this kernel, 32 rows per launch
 
 template <int OUT_KIND, int NW>
@@ -696,12 +712,12 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
   p.fbias = fbias;
   p.out = static_cast<char *>(out);
   p.ldo = ldo;
-  p.tiles_m = (int)ceil_div(m, 256);
   p.tiles_n = (int)ceil_div(n, 256);
-  // Tuning / testing knob (results agree to the rounding of the fp32 sums): CWAC_W4_PIPE=tile keeps
-  // the 256-token tiles for small batches too.
+  // Tuning / testing knobs (results agree to the rounding of the fp32 sums): CWAC_W4_PIPE=tile keeps
+  // the 256-token tiles at every batch size, =half the 128-token tiles.
   const char *e = getenv("CWAC_W4_PIPE");
-  if (m <= kSmallPasses * kSmallM && !(e && e[0] == 't')) {
+  const char knob = e ? e[0] : 0;
+  if (m <= kSmallPasses * kSmallM && knob != 't' && knob != 'h') {
     // up to four passes of the weight-streaming kernel over blocks of 32 rows: the packed weights
     // of a layer stay in the last-level cache between passes, and a 256-token tile would leave
     // most of the chip idle at these sizes (one row of tiles, each as long as its K loop)
@@ -716,8 +732,19 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
     }
     return CWAC_OK;
   }
-  return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16>(p, as_stream(stream))
-                                   : launch_w4<CWAC_OUT_FP32>(p, as_stream(stream));
+  // 128-token tiles while they fit the chip in one round (one tile per compute unit): a half tile
+  // takes about two thirds of a full tile's time (the weight expansion is per channel block, not
+  // per token, so it spends more vector work per MFMA), which pays exactly while the full tiles
+  // would leave compute units idle
+  const bool half = knob == 'h' || (knob != 't' && ceil_div(m, 128) * p.tiles_n <= kHalfTileUpTo);
+  if (half) {
+    p.tiles_m = (int)ceil_div(m, 128);
+    return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16, 2>(p, as_stream(stream))
+                                     : launch_w4<CWAC_OUT_FP32, 2>(p, as_stream(stream));
+  }
+  p.tiles_m = (int)ceil_div(m, 256);
+  return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16, 4>(p, as_stream(stream))
+                                   : launch_w4<CWAC_OUT_FP32, 4>(p, as_stream(stream));
 }
 
 }  // extern "C"

@@ -156,7 +156,7 @@ def test_weight_only_random_shape(m, n, k):
     pw = torch.empty(P.cwac_w4_packed_w_bytes(n, k), dtype=torch.uint8, device=DEV)
     psz = torch.empty((k // 128) * n, dtype=torch.int32, device=DEV)
     P.cwac_w4_pack(dev(codes), dev(scales), dev(zeros), pw, psz)
-    for pipe in (None, "tile"):
+    for pipe in (None, "tile", "half"):
         os.environ.pop("CWAC_W4_PIPE", None)
         if pipe:
             os.environ["CWAC_W4_PIPE"] = pipe

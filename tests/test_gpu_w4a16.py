@@ -142,7 +142,7 @@ def _exact_case(seed, m, n, k):
 
 
 @pytest.mark.parametrize("m,n,k", [(256, 256, 128), (300, 512, 384), (1, 256, 256), (513, 288, 256),
-                                   (77, 800, 1024), (1024, 256, 2048)])
+                                   (77, 800, 1024), (1024, 256, 2048), (129, 544, 640), (385, 256, 512)])
 def test_forward_exact_operands(w4, m, n, k):
     print(f"w4a16 exact operands {m} x {n} x {k}", flush=True)
     x16, codes, scales, zeros = _exact_case(100 + m + n + k, m, n, k)
@@ -151,30 +151,35 @@ def test_forward_exact_operands(w4, m, n, k):
     acc32 = acc.astype(np.float32)
     assert np.array_equal(acc32.astype(np.float64), acc)          # exactly representable
     pw, psz = _pack(codes, scales, zeros)
-    # raw product, fp32 out
-    out = _forward(x16, pw, psz, n, None, None, torch.float32)
-    np.testing.assert_array_equal(out.cpu().numpy(), acc32)
-    # folded epilogue, fp32 and binary16 out, padded output pitch
     rng = np.random.default_rng(5)
     mult = (1 + 0.25 * rng.standard_normal(n)).astype(np.float32)
     fbias = rng.standard_normal(n).astype(np.float32)
     o32, o16 = w4.epilogue_f32(acc32, mult, fbias)
-    out = _forward(x16, pw, psz, n, mult, fbias, torch.float32, ldo=n + 12)
-    np.testing.assert_array_equal(out.cpu().numpy(), o32)
-    outh = _forward(x16, pw, psz, n, mult, fbias, torch.float16, ldo=n + 24)
-    np.testing.assert_array_equal(outh.cpu().numpy().view(np.uint16), o16.view(np.uint16))
-    # only one of the two epilogue vectors
     o32m, _ = w4.epilogue_f32(acc32, mult, None)
-    np.testing.assert_array_equal(_forward(x16, pw, psz, n, mult, None, torch.float32).cpu().numpy(), o32m)
     o32b, _ = w4.epilogue_f32(acc32, None, fbias)
-    np.testing.assert_array_equal(_forward(x16, pw, psz, n, None, fbias, torch.float32).cpu().numpy(), o32b)
+    # the automatic choice, then the 256-token and the 128-token tile forced
+    for pipe in (None, "tile", "half"):
+        # raw product, fp32 out
+        out = _forward(x16, pw, psz, n, None, None, torch.float32, pipe=pipe)
+        np.testing.assert_array_equal(out.cpu().numpy(), acc32)
+        # folded epilogue, fp32 and binary16 out, padded output pitch
+        out = _forward(x16, pw, psz, n, mult, fbias, torch.float32, ldo=n + 12, pipe=pipe)
+        np.testing.assert_array_equal(out.cpu().numpy(), o32)
+        outh = _forward(x16, pw, psz, n, mult, fbias, torch.float16, ldo=n + 24, pipe=pipe)
+        np.testing.assert_array_equal(outh.cpu().numpy().view(np.uint16), o16.view(np.uint16))
+        # only one of the two epilogue vectors
+        np.testing.assert_array_equal(
+            _forward(x16, pw, psz, n, mult, None, torch.float32, pipe=pipe).cpu().numpy(), o32m)
+        np.testing.assert_array_equal(
+            _forward(x16, pw, psz, n, None, fbias, torch.float32, pipe=pipe).cpu().numpy(), o32b)
 
 
 @pytest.mark.parametrize("n,k", [(256, 128), (320, 384), (512, 1024), (288, 640)])
 @pytest.mark.parametrize("m", [1, 5, 17, 32])
 def test_small_batch_exact_operands(w4, m, n, k):
     """Batches of at most 32 tokens take the weight-streaming kernel (one workgroup per 32 channels,
-    K split over its four wavefronts - here 1, 3, 8 and 5 groups); `tile` forces the tiled kernel.
+    K split over its four wavefronts - here 1, 3, 8 and 5 groups); `tile` and `half` force the tiled kernel
+    with 256- and 128-token tiles.
     Exact operands: both give the oracle's bits."""
     print(f"w4a16 small batch {m} x {n} x {k}", flush=True)
     x16, codes, scales, zeros = _exact_case(300 + m + n + k, m, n, k)
@@ -189,7 +194,7 @@ def test_small_batch_exact_operands(w4, m, n, k):
     o32, o16 = w4.epilogue_f32(acc32, mult, fbias)
     o32m, _ = w4.epilogue_f32(acc32, mult, None)
     o32b, _ = w4.epilogue_f32(acc32, None, fbias)
-    for pipe in (None, "tile"):
+    for pipe in (None, "tile", "half"):
         out = _forward(x16, pw, psz, n, None, None, torch.float32, pipe=pipe)
         np.testing.assert_array_equal(out.cpu().numpy(), acc32)
         out = _forward(x16, pw, psz, n, mult, fbias, torch.float32, ldo=n + 12, pipe=pipe)
@@ -295,15 +300,16 @@ def test_forward_workload_like(w4, m, n, k):
     beta = (0.02 * synth.normal(7, 1, n).numpy()).astype(np.float32)
     mult, fbias = w4.fold(alpha, beta, None, n)
     ref = w4.folded_real(acc, mult, fbias)
-    for dtype in (torch.float32, torch.float16):
-        out = _forward(x16, pw, psz, n, mult, fbias, dtype).cpu().numpy().astype(np.float64)
-        err = np.abs(out - ref)
-        tol = _tolerance(mag, ref, k, mult, fbias, dtype == torch.float16)
-        assert (err <= tol).all(), float((err / tol).max())
-    # the fp32 result sits far inside the bound: a dropped or misplaced term would not
-    out = _forward(x16, pw, psz, n, None, None, torch.float32).cpu().numpy().astype(np.float64)
-    assert (np.abs(out - acc) <= 8.0 * np.sqrt(k) * U * mag + 1e-30).all()
-    assert np.abs(out - acc).max() <= 0.05 * (mag / k).mean()
+    for pipe in ("tile", "half"):
+        for dtype in (torch.float32, torch.float16):
+            out = _forward(x16, pw, psz, n, mult, fbias, dtype, pipe=pipe).cpu().numpy().astype(np.float64)
+            err = np.abs(out - ref)
+            tol = _tolerance(mag, ref, k, mult, fbias, dtype == torch.float16)
+            assert (err <= tol).all(), float((err / tol).max())
+        # the fp32 result sits far inside the bound: a dropped or misplaced term would not
+        out = _forward(x16, pw, psz, n, None, None, torch.float32, pipe=pipe).cpu().numpy().astype(np.float64)
+        assert (np.abs(out - acc) <= 8.0 * np.sqrt(k) * U * mag + 1e-30).all()
+        assert np.abs(out - acc).max() <= 0.05 * (mag / k).mean()
 
 
 def test_calibration_pipeline(w4, orc):
@@ -403,3 +409,12 @@ def test_full_size_llm_layers(w4, layer):
     err = np.abs(got - ref)
     tol = _tolerance(mag, ref, k, mult, fbias, True)
     assert (err <= tol).all(), float((err / tol).max())
+    # a prompt of 500 tokens on the same layer: the 128-token tile, at the launch shape it has there
+    mh = 500
+    out_h = torch.empty(mh, n, dtype=torch.float16, device=DEV)
+    P.qlinear_w4a16_cwac_forward(x_d[:mh], pw, psz, n, _dev(mult), _dev(fbias), out_h)
+    torch.cuda.synchronize()
+    sel = np.nonzero(rows < mh)[0]
+    got_h = out_h[torch.from_numpy(rows[sel]).to(DEV)].cpu().numpy().astype(np.float64)
+    err_h = np.abs(got_h - ref[sel])
+    assert (err_h <= tol[sel]).all(), float((err_h / tol[sel]).max())
