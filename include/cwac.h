@@ -389,6 +389,60 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
                                        void *out, int64_t ldo, void *stream);
 
 /* ------------------------------------------------------------------------- */
+/* Glue of a Transformer block between its W8A8 linear layers                  */
+/* ------------------------------------------------------------------------- */
+/* Per-layer compensation exists because the rest of the block is non-linear (Sec. 3.2); the
+ * paper does not define that rest.  These entry points are the standard pre-norm Vision
+ * Transformer block around the linear layers of Sec. 3.4 (int8 codes in, int8 codes out, Eq. 10):
+ *   x1 = Q(LN1(h))  r1 = qkv(x1)  a = Q(MHSA(deq(r1)))  r2 = proj(a)  h1 = RN16(h + deq(r2))
+ *   x2 = Q(LN2(h1)) r3 = fc1(x2)  g = Q(GELU(deq(r3)))  r4 = fc2(g)   h2 = RN16(h1 + deq(r4))
+ * Q(y) = clip(rne(y / s + z), -128, 127) (Eq. 1), deq(c) = s * (c - z); the residual stream h is
+ * IEEE binary16.  All pointers are device pointers owned by the caller; work is enqueued on
+ * `stream`; argument errors are returned before anything is launched. */
+
+/* Residual add, layer normalization and quantizer of one row-major [m, c] tensor, any subset
+ * that makes sense:
+ *   r != NULL:    t = h + s_r * (r - z_r) in fp32; h_out (nullable) receives RN16(t), and the
+ *                 layer norm reads that rounded value
+ *   x_q != NULL:  x_q = Q(LN(t; gamma, beta, eps); s_x, z_x); LN over the c channels of a row,
+ *                 biased variance, fp32, two passes over the register-resident row
+ *   h, h_out   binary16 [m, c], pitches ldh, ldho (elements); 16-byte aligned, pitch % 8 == 0
+ *   r, x_q     int8 [m, c], pitches ldr, ldxq; 8-byte aligned, pitch % 8 == 0
+ *   gamma, beta  fp32 [c], 16-byte aligned (required with x_q)
+ *   8 <= c <= 2048, c % 8 == 0, m >= 1; s_x > 0
+ * Errors: CWAC_E_NULL (h missing, or neither r nor x_q), CWAC_E_MODE (h_out without r, s_x <= 0),
+ * CWAC_E_SHAPE, CWAC_E_ALIGN. */
+cwac_status vit_residual_ln_quant(const uint16_t *h, int64_t ldh, const int8_t *r, int64_t ldr,
+                                  float s_r, int32_t z_r, uint16_t *h_out, int64_t ldho,
+                                  const float *gamma, const float *beta, float eps, float s_x,
+                                  int32_t z_x, int8_t *x_q, int64_t ldxq, int64_t m, int32_t c,
+                                  void *stream);
+
+/* The GELU between fc1 and fc2 acts on one int8 code at a time, so it is a table:
+ * table[code + 128] = Q(GELU(s_in * (code - z_in)); s_out, z_out), GELU(x) = x * Phi(x) with the
+ * exact normal distribution function, evaluated in fp64.  table: device int8 [256]. */
+cwac_status vit_gelu_table(float s_in, int32_t z_in, float s_out, int32_t z_out, int8_t *table,
+                           void *stream);
+
+/* out[i, j] = table[in[i, j] + 128] for an int8 [m, n] tensor (n % 16 == 0; both pitches % 16 == 0,
+ * both base pointers 16-byte aligned; in and out may be the same buffer). */
+cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *table, int8_t *out,
+                             int64_t ld_out, int64_t m, int32_t n, void *stream);
+
+/* Multi-head self-attention on the requantized output of the qkv layer, head width 64:
+ *   r_qkv  int8 [batch * tokens, 3 * c], c = 64 * heads, row = (q | k | v), head h in columns
+ *          [64 h, 64 h + 64) of each third; pitch ld (ld % 8 == 0, base 8-byte aligned);
+ *          quantization parameters (s, z) of the whole tensor
+ *   a_q    int8 [batch * tokens, c] = Q(softmax(q k^T / 8) v; s_a, z_a) per image and head;
+ *          pitch lda (lda % 16 == 0, base 16-byte aligned)
+ *   1 <= tokens <= 224 (one workgroup holds a head's keys and values), heads <= 64
+ * Scores are exact (integers in fp32 accumulators), the softmax is fp32, the weights meet the
+ * values as binary16 (relative error 2^-11 per term), accumulation in fp32. */
+cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t z, int32_t batch,
+                               int32_t tokens, int32_t heads, float s_a, int32_t z_a, int8_t *a_q,
+                               int64_t lda, void *stream);
+
+/* ------------------------------------------------------------------------- */
 /* Diagnostic (measurement aid, not a step of the method)                     */
 /* ------------------------------------------------------------------------- */
 

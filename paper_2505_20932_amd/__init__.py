@@ -17,4 +17,5 @@ from .binding import (  # noqa: F401
     cwac_quantize_act_bits, cwac_quantize_rows_sym_bits,
     CWAC_OUT_FP16, CWAC_W4_GROUP, cwac_w4_quantize_groupwise, cwac_w4_packed_w_bytes, cwac_w4_pack,
     cwac_fold_weight_only, qlinear_w4a16_cwac_forward, qconv2d_cwac_forward,
+    vit_residual_ln_quant, vit_gelu_table, vit_table_lookup, vit_attention_int8,
 )

@@ -29,6 +29,7 @@ EXPORTS = (
     "cwac_quantize_act_bits", "cwac_quantize_rows_sym_bits",
     "cwac_w4_quantize_groupwise", "cwac_w4_packed_w_bytes", "cwac_w4_pack",
     "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward", "qconv2d_cwac_forward",
+    "vit_residual_ln_quant", "vit_gelu_table", "vit_table_lookup", "vit_attention_int8",
 )
 
 
@@ -90,6 +91,11 @@ def lib() -> C.CDLL:
             "cwac_fold_weight_only": (i32, [vp, vp, vp, i32, vp, vp, vp]),
             "qlinear_w4a16_cwac_forward": (i32, [vp, i64, vp, vp, i64, i32, i32, vp, vp, i32, vp,
                                                  i64, vp]),
+            "vit_residual_ln_quant": (i32, [vp, i64, vp, i64, f32, i32, vp, i64, vp, vp, f32, f32, i32,
+                                            vp, i64, i64, i32, vp]),
+            "vit_gelu_table": (i32, [f32, i32, f32, i32, vp, vp]),
+            "vit_table_lookup": (i32, [vp, i64, vp, vp, i64, i64, i32, vp]),
+            "vit_attention_int8": (i32, [vp, i64, f32, i32, i32, i32, i32, f32, i32, vp, i64, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
@@ -364,6 +370,38 @@ def qlinear_w4a16_cwac_forward(x: torch.Tensor, packed_w: torch.Tensor, packed_s
                                             m, n, k, _ptr(mult), _ptr(fbias), kind, _ptr(out),
                                             _rowmajor(out), _stream(stream)),
            "qlinear_w4a16_cwac_forward")
+
+
+# --------------------------------------------------------------------------- block glue
+def vit_residual_ln_quant(h: torch.Tensor, r, s_r: float, z_r: int, h_out, gamma, beta, eps: float,
+                          s_x: float, z_x: int, x_q, stream=None):
+    """h float16 [m, c]; r / x_q int8 [m, c] or None; h_out float16 [m, c] or None."""
+    assert h.dtype == torch.float16
+    m, c = h.shape
+    _check(lib().vit_residual_ln_quant(_ptr(h), _rowmajor(h), _ptr(r), _rowmajor(r) if r is not None else 0,
+                                       s_r, z_r, _ptr(h_out), _rowmajor(h_out) if h_out is not None else 0,
+                                       _ptr(gamma), _ptr(beta), eps, s_x, z_x, _ptr(x_q),
+                                       _rowmajor(x_q) if x_q is not None else 0, m, c, _stream(stream)),
+           "vit_residual_ln_quant")
+
+
+def vit_gelu_table(s_in: float, z_in: int, s_out: float, z_out: int, table: torch.Tensor, stream=None):
+    assert table.dtype == torch.int8 and table.numel() == 256
+    _check(lib().vit_gelu_table(s_in, z_in, s_out, z_out, _ptr(table), _stream(stream)), "vit_gelu_table")
+
+
+def vit_table_lookup(x: torch.Tensor, table: torch.Tensor, out: torch.Tensor, stream=None):
+    assert x.dtype == torch.int8 and out.dtype == torch.int8 and x.shape == out.shape
+    _check(lib().vit_table_lookup(_ptr(x), _rowmajor(x), _ptr(table), _ptr(out), _rowmajor(out),
+                                  x.shape[0], x.shape[1], _stream(stream)), "vit_table_lookup")
+
+
+def vit_attention_int8(r_qkv: torch.Tensor, s: float, z: int, batch: int, tokens: int, heads: int,
+                       s_a: float, z_a: int, a_q: torch.Tensor, stream=None):
+    assert r_qkv.dtype == torch.int8 and a_q.dtype == torch.int8
+    assert r_qkv.shape == (batch * tokens, 3 * 64 * heads) and a_q.shape == (batch * tokens, 64 * heads)
+    _check(lib().vit_attention_int8(_ptr(r_qkv), _rowmajor(r_qkv), s, z, batch, tokens, heads, s_a, z_a,
+                                    _ptr(a_q), _rowmajor(a_q), _stream(stream)), "vit_attention_int8")
 
 
 # --------------------------------------------------------------------------- diagnostic

@@ -13,7 +13,7 @@ BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libcwac_hip.so")
 
 SOURCES = ["status.hip", "quantize.hip", "calib_stats.hip", "fold_epilogue.hip", "qlinear_forward.hip", "qlinear_fast.hip",
-           "probe.hip", "w4a16.hip"]
+           "probe.hip", "w4a16.hip", "block_glue.hip"]
 
 # -ffp-contract=off: the epilogue and the fold are defined as sequences of single
 # roundings; packed fp32 instructions are disabled for the device pass.

@@ -1,0 +1,436 @@
+// The non-linear glue between the W8A8 linear layers of a pre-norm Transformer block (the part
+// of the block that per-layer compensation steps around, Sec. 3.2): residual add + layer
+// normalization + quantizer, the GELU of the MLP as a 256-entry code table, and multi-head
+// self-attention on the requantized output of the qkv layer.  Every linear layer consumes int8
+// codes and requantizes to int8 codes (Eq. 10); the residual stream is binary16.
+//
+// Arithmetic, in fp32 unless stated (no contraction: each line is one rounding):
+//   residual   t = h + s_r * (float)(c - z_r);  h1 = RN16(t);  the layer norm reads h1
+//   layer norm mean = sum(x) / C;  var = sum((x - mean)^2) / C;  y = (x - mean) * (1 / sqrt(var + eps)) * gamma + beta
+//   quantizer  code = clip(rne(y / s + z), -128, 127)                                   (Eq. 1)
+//   attention  S = (K - z)(Q - z)^T exactly (integers below 2^24 in the fp32 MFMA accumulators);
+//              p = exp2((S - max S) * s^2 / sqrt(d) * log2 e);  O = (sum_j RN16(1024 p_j) (V_j - z)) * s / (1024 sum_j p_j)
+//   GELU table entry(c) = clip(rne(GELU(s_in (c - z_in)) / s_out + z_out)) evaluated in fp64 (erf form)
+#include <hip/hip_runtime.h>
+
+#include <math.h>
+
+#include "cwac_internal.h"
+
+namespace cwac {
+namespace {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__device__ __forceinline__ int quant_code(float y, float s, float zf) {
+  const float v = y / s + zf;
+  const float r = fminf(fmaxf(rintf(v), -128.0f), 127.0f);
+  return (int)r;
+}
+
+// ------------------------------------------------------------------------------------------
+// Residual add + layer norm + quantizer: one wavefront per token row, the row in registers
+// (NV vectors of 8 channels per lane: C <= 512 * NV), two-pass mean / variance, no LDS.
+// HBM bytes per element: 2 (h) [+ 1 (codes) + 2 (h1)] + 1 (x_q).
+// ------------------------------------------------------------------------------------------
+struct LnParams {
+  const _Float16 *h;
+  int64_t ldh;
+  const int8_t *r;
+  int64_t ldr;
+  float s_r;
+  int z_r;
+  _Float16 *h_out;
+  int64_t ldho;
+  const float *gamma, *beta;
+  float eps, s_x;
+  int z_x;
+  int8_t *x_q;
+  int64_t ldxq;
+  int64_t m;
+  int c;
+};
+
+template <int NV>
+__global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= p.m) return;  // whole wavefronts leave; no barrier in this kernel
+  const int nvec = p.c >> 3;
+  float x[NV][8];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int v = lane + 64 * j;
+    if (v < nvec) {
+      const h8 hv = *reinterpret_cast<const h8 *>(p.h + row * p.ldh + 8 * v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[j][e] = (float)hv[e];
+      if (p.r) {
+        const uint2 cw = *reinterpret_cast<const uint2 *>(p.r + row * p.ldr + 8 * v);
+        h8 ho;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t w = e < 4 ? cw.x : cw.y;
+          const int code = (int)(int8_t)(w >> (8 * (e & 3)));
+          const float t = x[j][e] + p.s_r * (float)(code - p.z_r);
+          ho[e] = (_Float16)t;
+          x[j][e] = (float)ho[e];
+        }
+        if (p.h_out) *reinterpret_cast<h8 *>(p.h_out + row * p.ldho + 8 * v) = ho;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[j][e] = 0.0f;
+    }
+  }
+  if (!p.x_q) return;
+  float s = 0.0f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += x[j][e];
+  const float mean = wave_sum(s) / (float)p.c;
+  float ss = 0.0f;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const bool ok = lane + 64 * j < nvec;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float d = ok ? x[j][e] - mean : 0.0f;
+      x[j][e] = d;
+      ss += d * d;
+    }
+  }
+  const float var = wave_sum(ss) / (float)p.c;
+  const float rstd = 1.0f / sqrtf(var + p.eps);
+  const float zf = (float)p.z_x;
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int v = lane + 64 * j;
+    if (v < nvec) {
+      const float4 g0 = *reinterpret_cast<const float4 *>(p.gamma + 8 * v);
+      const float4 g1 = *reinterpret_cast<const float4 *>(p.gamma + 8 * v + 4);
+      const float4 b0 = *reinterpret_cast<const float4 *>(p.beta + 8 * v);
+      const float4 b1 = *reinterpret_cast<const float4 *>(p.beta + 8 * v + 4);
+      const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+      uint32_t w[2] = {0u, 0u};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float y = x[j][e] * rstd * g[e] + b[e];
+        const int code = quant_code(y, p.s_x, zf);
+        w[e >> 2] |= (uint32_t)(code & 0xff) << (8 * (e & 3));
+      }
+      *reinterpret_cast<uint2 *>(p.x_q + row * p.ldxq + 8 * v) = make_uint2(w[0], w[1]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// GELU between fc1 and fc2 on int8 codes: a function of one code, so a 256-entry table.
+// ------------------------------------------------------------------------------------------
+__global__ void gelu_table_kernel(float s_in, int z_in, float s_out, int z_out, int8_t *table) {
+  const int code = (int)threadIdx.x - 128;
+  const double x = (double)s_in * (double)(code - z_in);
+  const double g = 0.5 * x * (1.0 + erf(x * 0.70710678118654752440));
+  double v = rint(g / (double)s_out + (double)z_out);
+  v = fmin(fmax(v, -128.0), 127.0);
+  table[threadIdx.x] = (int8_t)(int)v;
+}
+
+// out[i] = table[in[i] + 128]; 16 codes per lane and pass, the table in LDS (64 words: the lanes
+// of a read hit distinct banks or the same word).  HBM bytes per element: 1 + 1.
+__global__ __launch_bounds__(256) void table_lookup_kernel(const int8_t *in, int64_t ld_in, const int8_t *table,
+                                                           int8_t *out, int64_t ld_out, int64_t m, int n) {
+  __shared__ uint8_t s_tab[256];
+  s_tab[threadIdx.x] = (uint8_t)table[threadIdx.x];
+  __syncthreads();
+  const int vec_per_row = n >> 4;
+  const int64_t total = m * vec_per_row;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t row = i / vec_per_row;
+    const int v = (int)(i - row * vec_per_row);
+    const v4i cw = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(in + row * ld_in + 16 * v));
+    v4i ow;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t w = (uint32_t)cw[q];
+      uint32_t o = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o |= (uint32_t)s_tab[((w >> (8 * e)) & 0xff) ^ 0x80] << (8 * e);
+      ow[q] = (int)o;
+    }
+    *reinterpret_cast<v4i *>(out + row * ld_out + 16 * v) = ow;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Multi-head self-attention, head width 64, up to 224 tokens: one workgroup per (image, head),
+// one wavefront per 32 queries.  K (as (code - z) in binary16, row-major, 144-byte rows) and V
+// (transposed, 520-byte rows) of the head sit in LDS; both row strides make the operand reads
+// conflict-free.  S^T = K Q^T: 32 x 32 x 16 MFMA tiles with keys along M, so a lane owns one
+// query (its N index) and, with its partner lane ^ 32, all of that query's scores - the softmax
+// is a reduction over the lane's own registers plus one exchange.  Registers 8u .. 8u + 7 of score
+// tile t are, in order, the B operand of k-step (t, u) of O^T = V^T P^T; the A operand gathers
+// the same keys, 32 t + 16 u + 8 (e >> 2) + 4 half + (e & 3), from the transposed V with two
+// 8-byte reads.  Scores are exact integers; p is scaled by 1024 before its conversion to binary16
+// so that no term that matters falls into the subnormal range.
+// ------------------------------------------------------------------------------------------
+constexpr int kHeadDim = 64;
+constexpr int kKStride = 144;  // bytes per K row in LDS
+constexpr int kVStride = 520;  // bytes per V^T row in LDS
+
+struct AttnParams {
+  const int8_t *r;
+  int64_t ld;
+  float s;
+  int z;
+  int tokens, heads;
+  float s_a;
+  int z_a;
+  int8_t *a;
+  int64_t lda;
+};
+
+template <int NT>
+__global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParams p) {
+  constexpr int TP = 32 * NT;
+  __shared__ __attribute__((aligned(16))) int8_t s_k[TP * kKStride];
+  __shared__ __attribute__((aligned(16))) int8_t s_v[kHeadDim * kVStride];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int head = blockIdx.x % p.heads;
+  const int64_t row0 = (int64_t)(blockIdx.x / p.heads) * p.tokens;
+  const int c = p.heads * kHeadDim;
+  const int8_t *qbase = p.r + row0 * p.ld + head * kHeadDim;
+
+  // K and V of the head -> LDS as (code - z) in binary16; rows beyond the last token are zero
+  for (int i = tid; i < TP * 8; i += 64 * NT) {
+    const int key = i >> 3, ch = i & 7;
+    h8 kv, vv;
+    if (key < p.tokens) {
+      const uint2 kc = *reinterpret_cast<const uint2 *>(qbase + key * p.ld + c + 8 * ch);
+      const uint2 vc = *reinterpret_cast<const uint2 *>(qbase + key * p.ld + 2 * c + 8 * ch);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int sh = 8 * (e & 3);
+        kv[e] = (_Float16)((int)(int8_t)((e < 4 ? kc.x : kc.y) >> sh) - p.z);
+        vv[e] = (_Float16)((int)(int8_t)((e < 4 ? vc.x : vc.y) >> sh) - p.z);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) kv[e] = vv[e] = (_Float16)0.0f;
+    }
+    *reinterpret_cast<h8 *>(s_k + key * kKStride + ch * 16) = kv;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) *reinterpret_cast<_Float16 *>(s_v + (8 * ch + e) * kVStride + key * 2) = vv[e];
+  }
+
+  // this lane's query row as B operands (rows beyond the last token repeat it; never stored)
+  const int q = wave * 32 + l32;
+  const int qrow = q < p.tokens ? q : p.tokens - 1;
+  h8 fq[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const uint2 qc = *reinterpret_cast<const uint2 *>(qbase + qrow * p.ld + 16 * s + 8 * half);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      fq[s][e] = (_Float16)((int)(int8_t)((e < 4 ? qc.x : qc.y) >> (8 * (e & 3))) - p.z);
+  }
+  __syncthreads();
+
+  v16f sc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sc[t][i] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const h8 fk = *reinterpret_cast<const h8 *>(s_k + (32 * t + l32) * kKStride + (2 * s + half) * 16);
+      sc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sc[t], 0, 0, 0);
+    }
+  }
+  // softmax over the keys of this lane's query: register 4 g + r of tile t is key 32 t + 8 g + 4 half + r
+  float mx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int key = 32 * t + 8 * (i >> 2) + 4 * half + (i & 3);
+      if (key >= p.tokens) sc[t][i] = -INFINITY;
+      mx = fmaxf(mx, sc[t][i]);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float lscale = p.s * p.s * 0.125f * 1.44269504088896340736f;  // s^2 / sqrt(64) * log2(e)
+  float sum = 0.0f;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float pr = __builtin_amdgcn_exp2f((sc[t][i] - mx) * lscale);  // exp2(-inf) = 0 for masked keys
+      sum += pr;
+      sc[t][i] = pr * 1024.0f;
+    }
+  sum += __shfl_xor(sum, 32, 64);
+
+  v16f oc[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oc[a][i] = 0.0f;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      h8 fp;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) fp[e] = (_Float16)sc[t][8 * u + e];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        const int8_t *vb = s_v + (32 * a + l32) * kVStride + (32 * t + 16 * u + 4 * half) * 2;
+        const h4 lo = *reinterpret_cast<const h4 *>(vb), hi = *reinterpret_cast<const h4 *>(vb + 16);
+        const h8 fv = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        oc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp, oc[a], 0, 0, 0);
+      }
+    }
+  // O^T: register 4 g + r of tile a is channel 32 a + 8 g + 4 half + r of this lane's query
+  const float onorm = p.s * (1.0f / (sum * 1024.0f));
+  const float zf = (float)p.z_a;
+  int8_t *orow = p.a + (row0 + qrow) * p.lda + head * kHeadDim;
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    uint32_t packed[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint32_t w = 0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) w |= (uint32_t)(quant_code(oc[a][4 * g + r] * onorm, p.s_a, zf) & 0xff) << (8 * r);
+      packed[g] = w;
+    }
+    // lower half-wave holds channels 8g .. 8g+3, upper 8g+4 .. 8g+7: after the two swaps the lower
+    // lane owns channels 0 .. 15 of this 32-channel tile and the upper lane 16 .. 31
+    const auto s02 = __builtin_amdgcn_permlane32_swap(packed[0], packed[2], false, false);
+    const auto s13 = __builtin_amdgcn_permlane32_swap(packed[1], packed[3], false, false);
+    const v4i o = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+    if (q < p.tokens) *reinterpret_cast<v4i *>(orow + 32 * a + 16 * half) = o;
+  }
+}
+
+template <int NT>
+cwac_status launch_attention(const AttnParams &p, int batch, hipStream_t st) {
+  attention_int8_kernel<NT><<<dim3((unsigned)(batch * p.heads)), 64 * NT, 0, st>>>(p);
+  return launch_status();
+}
+
+}  // namespace
+}  // namespace cwac
+
+using namespace cwac;
+
+extern "C" {
+
+cwac_status vit_residual_ln_quant(const uint16_t *h, int64_t ldh, const int8_t *r, int64_t ldr, float s_r,
+                                  int32_t z_r, uint16_t *h_out, int64_t ldho, const float *gamma,
+                                  const float *beta, float eps, float s_x, int32_t z_x, int8_t *x_q,
+                                  int64_t ldxq, int64_t m, int32_t c, void *stream) {
+  if (!h || (!r && !x_q)) return CWAC_E_NULL;
+  if (x_q && (!gamma || !beta)) return CWAC_E_NULL;
+  if (h_out && !r) return CWAC_E_MODE;
+  if (m < 1 || c < 8 || c % 8 != 0 || c > 2048 || ldh < c || (r && ldr < c) || (h_out && ldho < c) ||
+      (x_q && ldxq < c) || (m + 3) / 4 > 0x7fffffff)
+    return CWAC_E_SHAPE;
+  if (!(s_x > 0.0f) && x_q) return CWAC_E_MODE;
+  if (!aligned(h, 16) || ldh % 8 != 0 || (r && (!aligned(r, 8) || ldr % 8 != 0)) ||
+      (h_out && (!aligned(h_out, 16) || ldho % 8 != 0)) || (x_q && (!aligned(x_q, 8) || ldxq % 8 != 0)) ||
+      (x_q && (!aligned(gamma, 16) || !aligned(beta, 16))))
+    return CWAC_E_ALIGN;
+  LnParams p;
+  p.h = reinterpret_cast<const _Float16 *>(h);
+  p.ldh = ldh;
+  p.r = r;
+  p.ldr = ldr;
+  p.s_r = s_r;
+  p.z_r = z_r;
+  p.h_out = reinterpret_cast<_Float16 *>(h_out);
+  p.ldho = ldho;
+  p.gamma = gamma;
+  p.beta = beta;
+  p.eps = eps;
+  p.s_x = s_x;
+  p.z_x = z_x;
+  p.x_q = x_q;
+  p.ldxq = ldxq;
+  p.m = m;
+  p.c = c;
+  const dim3 grid((unsigned)((m + 3) / 4));
+  hipStream_t st = as_stream(stream);
+  if (c <= 512)
+    residual_ln_quant_kernel<1><<<grid, 256, 0, st>>>(p);
+  else if (c <= 1024)
+    residual_ln_quant_kernel<2><<<grid, 256, 0, st>>>(p);
+  else
+    residual_ln_quant_kernel<4><<<grid, 256, 0, st>>>(p);
+  return launch_status();
+}
+
+cwac_status vit_gelu_table(float s_in, int32_t z_in, float s_out, int32_t z_out, int8_t *table, void *stream) {
+  if (!table) return CWAC_E_NULL;
+  if (!(s_in > 0.0f) || !(s_out > 0.0f)) return CWAC_E_MODE;
+  gelu_table_kernel<<<1, 256, 0, as_stream(stream)>>>(s_in, z_in, s_out, z_out, table);
+  return launch_status();
+}
+
+cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *table, int8_t *out, int64_t ld_out,
+                             int64_t m, int32_t n, void *stream) {
+  if (!in || !table || !out) return CWAC_E_NULL;
+  if (m < 1 || n < 16 || n % 16 != 0 || ld_in < n || ld_out < n) return CWAC_E_SHAPE;
+  if (!aligned(in, 16) || !aligned(out, 16) || ld_in % 16 != 0 || ld_out % 16 != 0) return CWAC_E_ALIGN;
+  const int64_t vecs = m * (n / 16);
+  int64_t blocks = ceil_div(vecs, 256);
+  if (blocks > 256 * 16) blocks = 256 * 16;  // grid-stride beyond 16 workgroups per compute unit
+  table_lookup_kernel<<<dim3((unsigned)blocks), 256, 0, as_stream(stream)>>>(in, ld_in, table, out, ld_out, m, n);
+  return launch_status();
+}
+
+cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t z, int32_t batch, int32_t tokens,
+                               int32_t heads, float s_a, int32_t z_a, int8_t *a_q, int64_t lda, void *stream) {
+  if (!r_qkv || !a_q) return CWAC_E_NULL;
+  if (batch < 1 || tokens < 1 || tokens > 224 || heads < 1 || heads > 64) return CWAC_E_SHAPE;
+  const int64_t c = (int64_t)heads * kHeadDim;
+  if (ld < 3 * c || lda < c || (int64_t)batch * heads > 0x7fffffff) return CWAC_E_SHAPE;
+  if (!(s > 0.0f) || !(s_a > 0.0f) || z < -128 || z > 127) return CWAC_E_MODE;
+  if (!aligned(r_qkv, 8) || ld % 8 != 0 || !aligned(a_q, 16) || lda % 16 != 0) return CWAC_E_ALIGN;
+  if (tokens * ld > 0x7fffffff) return CWAC_E_SHAPE;  // 32-bit row offsets inside one image
+  AttnParams p;
+  p.r = r_qkv;
+  p.ld = ld;
+  p.s = s;
+  p.z = z;
+  p.tokens = tokens;
+  p.heads = heads;
+  p.s_a = s_a;
+  p.z_a = z_a;
+  p.a = a_q;
+  p.lda = lda;
+  hipStream_t st = as_stream(stream);
+  switch ((tokens + 31) / 32) {
+    case 1: return launch_attention<1>(p, batch, st);
+    case 2: return launch_attention<2>(p, batch, st);
+    case 3: return launch_attention<3>(p, batch, st);
+    case 4: return launch_attention<4>(p, batch, st);
+    case 5: return launch_attention<5>(p, batch, st);
+    case 6: return launch_attention<6>(p, batch, st);
+    default: return launch_attention<7>(p, batch, st);
+  }
+}
+
+}  // extern "C"

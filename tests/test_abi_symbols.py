@@ -185,3 +185,38 @@ def test_eq2_host_function_matches_oracle(orc, lib):
             s, z = P.cwac_qparams_from_range(mn, mx, bits)
             s0, z0 = orc.qparams_asym(mn, mx, bits)
             assert np.float32(s) == s0 and z == z0, (mn, mx, bits)
+
+
+def test_argument_errors_of_the_block_glue_entry_points(lib):
+    null = None
+    a = C.c_void_p(4096)
+    ln = lib.vit_residual_ln_quant
+    #        h  ldh  r  ldr  s_r z_r h_out ldho gamma beta eps   s_x z_x x_q ldxq m  c
+    assert ln(null, 64, a, 64, 1.0, 0, a, 64, a, a, 1e-6, 1.0, 0, a, 64, 4, 64, null) == -1
+    assert ln(a, 64, null, 0, 1.0, 0, null, 0, a, a, 1e-6, 1.0, 0, null, 0, 4, 64, null) == -1  # nothing to do
+    assert ln(a, 64, null, 0, 1.0, 0, null, 0, null, a, 1e-6, 1.0, 0, a, 64, 4, 64, null) == -1  # no gamma
+    assert ln(a, 64, null, 0, 1.0, 0, a, 64, a, a, 1e-6, 1.0, 0, a, 64, 4, 64, null) == -4      # h_out without r
+    assert ln(a, 64, a, 64, 1.0, 0, a, 64, a, a, 1e-6, 0.0, 0, a, 64, 4, 64, null) == -4        # s_x = 0
+    assert ln(a, 60, a, 64, 1.0, 0, a, 64, a, a, 1e-6, 1.0, 0, a, 64, 4, 60, null) == -2        # c % 8
+    assert ln(a, 4096, a, 4096, 1.0, 0, a, 4096, a, a, 1e-6, 1.0, 0, a, 4096, 4, 4096, null) == -2  # c > 2048
+    assert ln(a, 32, a, 64, 1.0, 0, a, 64, a, a, 1e-6, 1.0, 0, a, 64, 4, 64, null) == -2        # ldh < c
+    assert ln(a, 68, a, 64, 1.0, 0, a, 64, a, a, 1e-6, 1.0, 0, a, 64, 4, 64, null) == -3        # ldh % 8
+    assert ln(a, 64, C.c_void_p(4100), 64, 1.0, 0, a, 64, a, a, 1e-6, 1.0, 0, a, 64, 4, 64, null) == -3
+    gt = lib.vit_gelu_table
+    assert gt(1.0, 0, 1.0, 0, null, null) == -1
+    assert gt(0.0, 0, 1.0, 0, a, null) == -4
+    tl = lib.vit_table_lookup
+    assert tl(a, 64, null, a, 64, 4, 64, null) == -1
+    assert tl(a, 64, a, a, 64, 4, 40, null) == -2            # n % 16
+    assert tl(a, 64, a, a, 32, 4, 64, null) == -2            # ld_out < n
+    assert tl(a, 72, a, a, 64, 4, 64, null) == -3            # ld_in % 16
+    at = lib.vit_attention_int8
+    #        r  ld   s    z  batch tokens heads s_a z_a a  lda
+    assert at(null, 192, 1.0, 0, 1, 16, 1, 1.0, 0, a, 64, null) == -1
+    assert at(a, 192, 1.0, 0, 1, 225, 1, 1.0, 0, a, 64, null) == -2   # more tokens than one workgroup holds
+    assert at(a, 128, 1.0, 0, 1, 16, 1, 1.0, 0, a, 64, null) == -2    # ld < 3 c
+    assert at(a, 192, 1.0, 0, 1, 16, 1, 1.0, 0, a, 32, null) == -2    # lda < c
+    assert at(a, 192, 0.0, 0, 1, 16, 1, 1.0, 0, a, 64, null) == -4
+    assert at(a, 192, 1.0, 200, 1, 16, 1, 1.0, 0, a, 64, null) == -4  # zero-point outside int8
+    assert at(a, 196, 1.0, 0, 1, 16, 1, 1.0, 0, a, 64, null) == -3    # ld % 8
+    assert at(a, 192, 1.0, 0, 1, 16, 1, 1.0, 0, C.c_void_p(4104), 64, null) == -3

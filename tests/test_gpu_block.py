@@ -1,0 +1,224 @@
+"""GPU parity of the Transformer-block glue (residual + layer norm + quantizer, GELU table,
+multi-head self-attention on int8 codes) against oracle/block_oracle.py, through the C ABI.
+
+Where fp32 arithmetic decides an int8 code, the oracle supplies the real number v whose rounding is
+the code and the test derives a bound `delta` on what the kernel's fp32 (attention: binary16
+weights) evaluation can be off by; the kernel's code must be the rounding of some number in
+[v - delta, v + delta] - exact wherever v is farther than delta from a tie."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2505_20932_amd as P
+from oracle import block_oracle as blk
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+U32 = 2.0 ** -24
+
+
+def _dev(a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _codes_within(got, v, delta, qmin=-128, qmax=127):
+    lo = np.clip(np.rint(v - delta), qmin, qmax)
+    hi = np.clip(np.rint(v + delta), qmin, qmax)
+    g = got.astype(np.float64)
+    bad = (g < lo) | (g > hi)
+    assert not bad.any(), (int(bad.sum()), float(np.abs(g - np.clip(np.rint(v), qmin, qmax)).max()))
+    return float((lo == hi).mean())  # share of outputs the check pins to one code
+
+
+# ------------------------------------------------------------------ residual + layer norm + quantizer
+def _ln_case(seed, m, c):
+    rng = np.random.default_rng(seed)
+    h = (rng.standard_normal((m, c)) * (1 + 4 * (rng.random(c) < 0.02))).astype(np.float16)
+    r = rng.integers(-128, 128, (m, c)).astype(np.int8)
+    gamma = (1 + 0.2 * rng.standard_normal(c)).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(c)).astype(np.float32)
+    return h, r, gamma, beta
+
+
+@pytest.mark.parametrize("m,c", [(5, 64), (197, 768), (33, 1024), (10, 2048), (64, 384), (3, 8), (9, 1280)])
+@pytest.mark.parametrize("with_residual", [False, True])
+def test_residual_ln_quant(m, c, with_residual):
+    print(f"residual + layer norm + quantizer {m} x {c}, residual {with_residual}", flush=True)
+    h, r, gamma, beta = _ln_case(11 + m + c, m, c)
+    s_r, z_r, eps = 0.01, 3, 1e-6
+    # pitches wider than the row, outputs pre-filled: nothing outside the row may be written
+    hp = torch.zeros(m, c + 8, dtype=torch.float16, device=DEV)
+    hp[:, :c] = _dev(h)
+    hout_full = torch.full((m, c + 16), 7.0, dtype=torch.float16, device=DEV)
+    xq_full = torch.full((m, c + 8), 77, dtype=torch.int8, device=DEV)
+    h_out = hout_full[:, :c] if with_residual else None
+    r_d = _dev(r) if with_residual else None
+    P.vit_residual_ln_quant(hp[:, :c], r_d, s_r, z_r, h_out, _dev(gamma), _dev(beta), eps, 0.03, -5,
+                            xq_full[:, :c])
+    torch.cuda.synchronize()
+    assert (xq_full[:, c:] == 77).all() and (hout_full[:, c:] == 7.0).all()
+    if with_residual:
+        want16, t = blk.residual(h, r, s_r, z_r)
+        got16 = h_out.cpu().numpy()
+        # one fp32 product and one fp32 sum before the rounding to binary16
+        slack = 2 * U32 * (np.abs(h.astype(np.float64)) + np.abs(t)) + 1e-30
+        lo = (t - slack).astype(np.float16).astype(np.float64)
+        hi = (t + slack).astype(np.float16).astype(np.float64)
+        g = got16.astype(np.float64)
+        assert ((g >= lo) & (g <= hi)).all()
+        assert (got16 == want16).mean() > 0.999
+        ln_in = got16.astype(np.float64)  # the layer norm reads the stored binary16 value
+    else:
+        assert (hout_full == 7.0).all()
+        ln_in = h.astype(np.float64)
+    y = blk.layernorm(ln_in, gamma, beta, eps)
+    _, v = blk.quantize(y, 0.03, -5)
+    # fp32: the two row sums (relative error ~ log2(c) u each), a handful of roundings per element
+    delta = 64 * U32 * (np.abs(v) + 128) + 1e-4
+    pinned = _codes_within(xq_full[:, :c].cpu().numpy(), v, delta)
+    assert pinned > 0.99
+
+
+def test_residual_only_and_quantizer_saturation():
+    m, c = 6, 128
+    h, r, gamma, beta = _ln_case(5, m, c)
+    out = torch.empty(m, c, dtype=torch.float16, device=DEV)
+    P.vit_residual_ln_quant(_dev(h), _dev(r), 0.5, -1, out, None, None, 0.0, 1.0, 0, None)
+    torch.cuda.synchronize()
+    want, _ = blk.residual(h, r, 0.5, -1)  # h + 0.5 * integer: exact in fp32, one rounding to binary16
+    np.testing.assert_array_equal(out.cpu().numpy().view(np.uint16), want.view(np.uint16))
+    # a tiny scale saturates the codes at both ends
+    xq = torch.empty(m, c, dtype=torch.int8, device=DEV)
+    P.vit_residual_ln_quant(_dev(h), None, 0.0, 0, None, _dev(gamma), _dev(beta), 1e-6, 1e-4, 0, xq)
+    torch.cuda.synchronize()
+    y = blk.layernorm(h.astype(np.float64), gamma, beta, 1e-6)
+    sat = np.abs(y) > 0.02
+    np.testing.assert_array_equal(xq.cpu().numpy()[sat], np.where(y[sat] > 0, 127, -128))
+
+
+# ------------------------------------------------------------------ GELU table
+@pytest.mark.parametrize("s_in,z_in,s_out,z_out", [(0.05, -20, 0.02, -120), (0.013, 7, 0.011, -113),
+                                                   (0.2, 0, 0.1, -128), (1e-3, -128, 1e-3, -128)])
+def test_gelu_table(s_in, z_in, s_out, z_out):
+    tab = torch.empty(256, dtype=torch.int8, device=DEV)
+    P.vit_gelu_table(s_in, z_in, s_out, z_out, tab)
+    torch.cuda.synchronize()
+    # the scales reach the kernel as fp32
+    want, v = blk.gelu_table(np.float32(s_in), z_in, np.float32(s_out), z_out)
+    got = tab.cpu().numpy()
+    tie = np.abs(v - np.floor(v) - 0.5) < 1e-9
+    np.testing.assert_array_equal(got[~tie], want[~tie])
+    assert np.abs(got.astype(int) - want.astype(int)).max() <= 1
+
+
+@pytest.mark.parametrize("m,n,pad", [(1, 16, 0), (197, 3072, 0), (33, 48, 16), (1000, 1536, 32)])
+def test_table_lookup(m, n, pad):
+    rng = np.random.default_rng(m + n)
+    x = rng.integers(-128, 128, (m, n)).astype(np.int8)
+    tab = rng.integers(-128, 128, 256).astype(np.int8)
+    xp = torch.zeros(m, n + pad, dtype=torch.int8, device=DEV)
+    xp[:, :n] = _dev(x)
+    full = torch.full((m, n + pad), 55, dtype=torch.int8, device=DEV)
+    P.vit_table_lookup(xp[:, :n], _dev(tab), full[:, :n])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(full[:, :n].cpu().numpy(), tab[x.astype(int) + 128])
+    assert (full[:, n:] == 55).all()
+    # in place
+    P.vit_table_lookup(xp[:, :n], _dev(tab), xp[:, :n])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(xp[:, :n].cpu().numpy(), tab[x.astype(int) + 128])
+
+
+# ------------------------------------------------------------------ attention
+def _attention(r, s, z, batch, tokens, heads, s_a, z_a, pad=0):
+    c = 64 * heads
+    rp = torch.zeros(batch * tokens, 3 * c + pad, dtype=torch.int8, device=DEV)
+    rp[:, :3 * c] = _dev(r)
+    full = torch.full((batch * tokens, c + 2 * pad), 99, dtype=torch.int8, device=DEV)
+    P.vit_attention_int8(rp[:, :3 * c], s, z, batch, tokens, heads, s_a, z_a, full[:, :c])
+    torch.cuda.synchronize()
+    assert (full[:, c:] == 99).all()
+    return full[:, :c].cpu().numpy()
+
+
+def _out_params(o):
+    lo, hi = float(o.min()), float(o.max())
+    s_a = np.float32(max(hi - lo, 1e-6) / 255.0)
+    z_a = int(np.clip(round(-128 - lo / float(s_a)), -128, 127))
+    return float(s_a), z_a
+
+
+@pytest.mark.parametrize("batch,tokens,heads", [(2, 197, 3), (1, 224, 1), (3, 49, 2), (2, 1, 1), (1, 33, 2),
+                                                (1, 64, 1), (2, 100, 12), (1, 193, 2)])
+def test_attention_random_codes(batch, tokens, heads):
+    print(f"attention {batch} x {tokens} tokens x {heads} heads", flush=True)
+    rng = np.random.default_rng(batch * 1000 + tokens * 10 + heads)
+    c = 64 * heads
+    r = np.clip(np.rint(rng.standard_normal((batch * tokens, 3 * c)) * 30 + 4), -128, 127).astype(np.int8)
+    s, z = np.float32(0.04), 4
+    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads)
+    s_a, z_a = _out_params(o)
+    got = _attention(r, float(s), z, batch, tokens, heads, s_a, z_a, pad=16)
+    _, v = blk.quantize(o, np.float32(s_a), z_a)
+    # weights rounded to binary16 (2^-11 relative, per term), fp32 exp2 / sums / normalization
+    delta = (2.0 ** -11 + 256 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
+    pinned = _codes_within(got, v, delta)
+    want, _ = blk.quantize(o, np.float32(s_a), z_a)
+    assert (got == want).mean() > 0.9, float((got == want).mean())
+    print(f"  pinned to one code: {pinned:.3f}, equal to the oracle's code: {(got == want).mean():.4f}", flush=True)
+
+
+def test_attention_uniform_weights_is_the_mean_value():
+    """All keys of a head equal: every weight is exactly 1 / tokens, the output is the mean value row -
+    sharp in the layout of V, the head split, the masking of the padded keys and the normalization."""
+    batch, tokens, heads = 2, 77, 2
+    c = 64 * heads
+    rng = np.random.default_rng(3)
+    r = rng.integers(-128, 128, (batch * tokens, 3 * c)).astype(np.int8)
+    kk = rng.integers(-128, 128, (batch, 1, c)).astype(np.int8)
+    r[:, c:2 * c] = np.broadcast_to(kk, (batch, tokens, c)).reshape(batch * tokens, c)
+    s, z = np.float32(0.02), -9
+    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads)
+    vmean = blk.dequantize(r[:, 2 * c:], s, z).reshape(batch, tokens, c).mean(axis=1)
+    np.testing.assert_allclose(o.reshape(batch, tokens, c), np.broadcast_to(vmean[:, None, :], (batch, tokens, c)),
+                               rtol=1e-12, atol=1e-12)
+    s_a, z_a = _out_params(o)
+    got = _attention(r, float(s), z, batch, tokens, heads, s_a, z_a)
+    _, v = blk.quantize(o, np.float32(s_a), z_a)
+    pinned = _codes_within(got, v, 64 * U32 * (np.abs(v) + 128 + mag / s_a) + 1e-4)
+    assert pinned > 0.99
+
+
+def test_attention_one_dominant_key_picks_its_value():
+    """Query i scores key perm[i] far above the rest: the output row is that key's value row - sharp in
+    which key's weight meets which value row (the key order of the second product)."""
+    batch, tokens, heads = 1, 197, 1
+    c = 64
+    rng = np.random.default_rng(4)
+    perm = rng.permutation(tokens)
+    # keys: distinct +-1 patterns scaled to +-100; query i = key perm[i]: score 64 * 100^2 against at most ~0.6 of it
+    pat = rng.choice([-100, 100], size=(tokens, c))
+    r = np.zeros((tokens, 3 * c), dtype=np.int8)
+    r[:, c:2 * c] = pat
+    r[:, :c] = pat[perm]
+    r[:, 2 * c:] = rng.integers(-128, 128, (tokens, c))
+    s, z = np.float32(0.05), 0
+    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads)
+    vsel = blk.dequantize(r[perm, 2 * c:], s, z)
+    np.testing.assert_allclose(o, vsel, atol=1e-9)
+    s_a, z_a = float(s), 0
+    got = _attention(r, float(s), z, batch, tokens, heads, s_a, z_a)
+    np.testing.assert_array_equal(got, r[perm, 2 * c:])
+
+
+def test_attention_row_subset_of_a_batch_matches_single_image():
+    """Images are independent: image 1 of a batch of 3 equals the same image alone."""
+    tokens, heads = 60, 2
+    c = 64 * heads
+    rng = np.random.default_rng(8)
+    r = np.clip(np.rint(rng.standard_normal((3 * tokens, 3 * c)) * 25), -128, 127).astype(np.int8)
+    a3 = _attention(r, 0.05, 1, 3, tokens, heads, 0.03, -2)
+    a1 = _attention(r[tokens:2 * tokens], 0.05, 1, 1, tokens, heads, 0.03, -2)
+    np.testing.assert_array_equal(a3[tokens:2 * tokens], a1)
