@@ -442,6 +442,40 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
                                int32_t tokens, int32_t heads, float s_a, int32_t z_a, int8_t *a_q,
                                int64_t lda, void *stream);
 
+/* One whole block: the nine launches of the chain above on `stream`, from the residual stream h
+ * [batch * tokens, c] (c = 64 * heads, pitch c) to h_out (same shape; may not alias h).  Linear
+ * layer i (0 qkv [3c, c], 1 proj [c, c], 2 fc1 [hidden, c], 3 fc2 [c, hidden]; weights int8
+ * row-major [n, k], pitch k) runs qlinear_cwac_forward in CWAC_EPI_INT_OFFSET form with per-tensor
+ * activations: mult / offset are cwac_fold's, (s_x, z_x) its input quantizer - which is the
+ * quantizer of the glue step that produces its input - and (s_r, z_r) its requantization.
+ * gelu_table is vit_gelu_table(layer[2].s_r, layer[2].z_r, layer[3].s_x, layer[3].z_x).
+ * workspace: device, vit_block_workspace(...) bytes, 16-byte aligned; after the call it holds, in
+ * this order: x2 = Q(LN2(h1)) [m, c], r1 (qkv output) [m, 3c], r4 (fc2 output) [m, c],
+ * g (GELU codes) [m, hidden] - exposed so that a caller can check every stage.
+ * Errors: those of the nine calls; CWAC_E_WORKSPACE if workspace_bytes is too small. */
+typedef struct vit_block_layer {
+  const int8_t *w_q;
+  const float *mult;
+  const int32_t *offset;
+  float s_x;
+  int32_t z_x;
+  float s_r;
+  int32_t z_r;
+} vit_block_layer;
+
+typedef struct vit_block_params {
+  int32_t batch, tokens, heads, hidden;
+  float eps;
+  const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
+  vit_block_layer layer[4];
+  const int8_t *gelu_table;
+} vit_block_params;
+
+size_t vit_block_workspace(int32_t batch, int32_t tokens, int32_t heads, int32_t hidden);
+cwac_status vit_block_w8a8_forward(const vit_block_params *params /* host */, const uint16_t *h,
+                                   uint16_t *h_out, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
 /* ------------------------------------------------------------------------- */
 /* Diagnostic (measurement aid, not a step of the method)                     */
 /* ------------------------------------------------------------------------- */

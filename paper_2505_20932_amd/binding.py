@@ -30,6 +30,7 @@ EXPORTS = (
     "cwac_w4_quantize_groupwise", "cwac_w4_packed_w_bytes", "cwac_w4_pack",
     "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward", "qconv2d_cwac_forward",
     "vit_residual_ln_quant", "vit_gelu_table", "vit_table_lookup", "vit_attention_int8",
+    "vit_block_workspace", "vit_block_w8a8_forward",
 )
 
 
@@ -37,6 +38,18 @@ class cwac_qparams(C.Structure):
     _fields_ = [("mode", C.c_int32), ("act_per_token", C.c_int32), ("s_x", C.c_float),
                 ("z_x", C.c_int32), ("s_r", C.c_float), ("z_r", C.c_int32),
                 ("qmin", C.c_int32), ("qmax", C.c_int32)]
+
+
+class vit_block_layer(C.Structure):
+    _fields_ = [("w_q", C.c_void_p), ("mult", C.c_void_p), ("offset", C.c_void_p), ("s_x", C.c_float),
+                ("z_x", C.c_int32), ("s_r", C.c_float), ("z_r", C.c_int32)]
+
+
+class vit_block_params(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("tokens", C.c_int32), ("heads", C.c_int32), ("hidden", C.c_int32),
+                ("eps", C.c_float), ("ln1_gamma", C.c_void_p), ("ln1_beta", C.c_void_p),
+                ("ln2_gamma", C.c_void_p), ("ln2_beta", C.c_void_p), ("layer", vit_block_layer * 4),
+                ("gelu_table", C.c_void_p)]
 
 
 class CwacError(RuntimeError):
@@ -96,6 +109,8 @@ def lib() -> C.CDLL:
             "vit_gelu_table": (i32, [f32, i32, f32, i32, vp, vp]),
             "vit_table_lookup": (i32, [vp, i64, vp, vp, i64, i64, i32, vp]),
             "vit_attention_int8": (i32, [vp, i64, f32, i32, i32, i32, i32, f32, i32, vp, i64, vp]),
+            "vit_block_workspace": (sz, [i32, i32, i32, i32]),
+            "vit_block_w8a8_forward": (i32, [C.POINTER(vit_block_params), vp, vp, vp, sz, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
@@ -402,6 +417,36 @@ def vit_attention_int8(r_qkv: torch.Tensor, s: float, z: int, batch: int, tokens
     assert r_qkv.shape == (batch * tokens, 3 * 64 * heads) and a_q.shape == (batch * tokens, 64 * heads)
     _check(lib().vit_attention_int8(_ptr(r_qkv), _rowmajor(r_qkv), s, z, batch, tokens, heads, s_a, z_a,
                                     _ptr(a_q), _rowmajor(a_q), _stream(stream)), "vit_attention_int8")
+
+
+def vit_block_workspace(batch: int, tokens: int, heads: int, hidden: int) -> int:
+    return int(lib().vit_block_workspace(batch, tokens, heads, hidden))
+
+
+def make_block_params(batch, tokens, heads, hidden, eps, ln1, ln2, layers, gelu_table) -> vit_block_params:
+    """ln1 / ln2: (gamma, beta) device tensors; layers: four dicts with w_q, mult, offset (device
+    tensors) and s_x, z_x, s_r, z_r.  The tensors must outlive the returned struct's use."""
+    bp = vit_block_params()
+    bp.batch, bp.tokens, bp.heads, bp.hidden, bp.eps = batch, tokens, heads, hidden, eps
+    bp.ln1_gamma, bp.ln1_beta = ln1[0].data_ptr(), ln1[1].data_ptr()
+    bp.ln2_gamma, bp.ln2_beta = ln2[0].data_ptr(), ln2[1].data_ptr()
+    for i, ly in enumerate(layers):
+        bp.layer[i].w_q = ly["w_q"].data_ptr()
+        bp.layer[i].mult = ly["mult"].data_ptr()
+        bp.layer[i].offset = ly["offset"].data_ptr()
+        bp.layer[i].s_x, bp.layer[i].z_x = ly["s_x"], ly["z_x"]
+        bp.layer[i].s_r, bp.layer[i].z_r = ly["s_r"], ly["z_r"]
+    bp.gelu_table = gelu_table.data_ptr()
+    return bp
+
+
+def vit_block_w8a8_forward(bp: vit_block_params, h: torch.Tensor, h_out: torch.Tensor,
+                           workspace: torch.Tensor, stream=None):
+    assert h.dtype == torch.float16 and h_out.dtype == torch.float16 and h.is_contiguous() and h_out.is_contiguous()
+    assert h.shape == h_out.shape == (bp.batch * bp.tokens, 64 * bp.heads)
+    _check(lib().vit_block_w8a8_forward(C.byref(bp), _ptr(h), _ptr(h_out), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)),
+           "vit_block_w8a8_forward")
 
 
 # --------------------------------------------------------------------------- diagnostic

@@ -433,4 +433,60 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
   }
 }
 
+size_t vit_block_workspace(int32_t batch, int32_t tokens, int32_t heads, int32_t hidden) {
+  if (batch < 1 || tokens < 1 || heads < 1 || hidden < 1) return 0;
+  const size_t m = (size_t)batch * (size_t)tokens, c = (size_t)heads * kHeadDim;
+  return m * (5 * c + (size_t)hidden);
+}
+
+cwac_status vit_block_w8a8_forward(const vit_block_params *bp, const uint16_t *h, uint16_t *h_out, void *workspace,
+                                   size_t workspace_bytes, void *stream) {
+  if (!bp || !h || !h_out || !workspace || !bp->gelu_table) return CWAC_E_NULL;
+  if (bp->batch < 1 || bp->tokens < 1 || bp->heads < 1 || bp->heads > 64 || bp->hidden < 16 || bp->hidden % 16 != 0)
+    return CWAC_E_SHAPE;
+  if (h == h_out) return CWAC_E_MODE;
+  for (int i = 0; i < 4; ++i)
+    if (!bp->layer[i].w_q || !bp->layer[i].mult || !bp->layer[i].offset) return CWAC_E_NULL;
+  if (workspace_bytes < vit_block_workspace(bp->batch, bp->tokens, bp->heads, bp->hidden)) return CWAC_E_WORKSPACE;
+  if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
+  const int64_t m = (int64_t)bp->batch * bp->tokens;
+  const int32_t c = bp->heads * kHeadDim, hid = bp->hidden;
+  int8_t *xq = static_cast<int8_t *>(workspace);  // x1, then the attention output, then x2
+  int8_t *r_qkv = xq + m * c;
+  int8_t *r_c = r_qkv + m * 3 * c;  // proj output, then fc2 output
+  int8_t *r_h = r_c + m * c;        // fc1 output, then the GELU codes in place
+  const vit_block_layer *L = bp->layer;
+  auto linear = [&](int i, const int8_t *x, int32_t n, int32_t k, int8_t *out) {
+    cwac_qparams qp;
+    qp.mode = CWAC_EPI_INT_OFFSET;
+    qp.act_per_token = 0;
+    qp.s_x = L[i].s_x;
+    qp.z_x = L[i].z_x;
+    qp.s_r = L[i].s_r;
+    qp.z_r = L[i].z_r;
+    qp.qmin = -128;
+    qp.qmax = 127;
+    return qlinear_cwac_forward(x, k, L[i].w_q, k, m, n, k, &qp, L[i].mult, L[i].offset, nullptr, nullptr, CWAC_OUT_INT8,
+                                out, n, stream);
+  };
+  cwac_status st;
+  st = vit_residual_ln_quant(h, c, nullptr, 0, 0.0f, 0, nullptr, 0, bp->ln1_gamma, bp->ln1_beta, bp->eps, L[0].s_x,
+                             L[0].z_x, xq, c, m, c, stream);
+  if (st != CWAC_OK) return st;
+  if ((st = linear(0, xq, 3 * c, c, r_qkv)) != CWAC_OK) return st;
+  st = vit_attention_int8(r_qkv, 3 * c, L[0].s_r, L[0].z_r, bp->batch, bp->tokens, bp->heads, L[1].s_x, L[1].z_x, xq, c,
+                          stream);
+  if (st != CWAC_OK) return st;
+  if ((st = linear(1, xq, c, c, r_c)) != CWAC_OK) return st;
+  st = vit_residual_ln_quant(h, c, r_c, c, L[1].s_r, L[1].z_r, h_out, c, bp->ln2_gamma, bp->ln2_beta, bp->eps, L[2].s_x,
+                             L[2].z_x, xq, c, m, c, stream);
+  if (st != CWAC_OK) return st;
+  if ((st = linear(2, xq, hid, c, r_h)) != CWAC_OK) return st;
+  if ((st = vit_table_lookup(r_h, hid, bp->gelu_table, r_h, hid, m, hid, stream)) != CWAC_OK) return st;
+  if ((st = linear(3, r_h, c, hid, r_c)) != CWAC_OK) return st;
+  // h2 = RN16(h1 + deq(r4)), in place over h1: every lane reads its own elements before it writes them
+  return vit_residual_ln_quant(h_out, c, r_c, c, L[3].s_r, L[3].z_r, h_out, c, nullptr, nullptr, 0.0f, 1.0f, 0, nullptr,
+                               0, m, c, stream);
+}
+
 }  // extern "C"

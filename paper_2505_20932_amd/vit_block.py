@@ -1,0 +1,146 @@
+"""Set-up of one W8A8 Vision Transformer block for ``vit_block_w8a8_forward``.
+
+The floating-point block (the model upstream of the method) is evaluated with torch on the
+device to obtain the ranges of the tensors that get quantized; every step of the method itself
+- Eq. 2 on those ranges, the weight quantizer, the column sums, the fold of Sec. 3.4 and the
+GELU table - runs in the library's kernels.  Weights, layer-norm parameters, biases and the
+compensation vectors are seeded synthetic tensors (``synth``)."""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List
+
+import torch
+import torch.nn.functional as F
+
+from . import binding as B
+from . import synth
+
+LAYERS = ("qkv", "proj", "fc1", "fc2")
+
+
+@dataclass
+class Block:
+    batch: int
+    tokens: int
+    heads: int
+    hidden: int
+    eps: float
+    ln: List[torch.Tensor]                  # ln1 gamma, ln1 beta, ln2 gamma, ln2 beta (fp32, device)
+    layers: List[Dict] = field(default_factory=list)   # per linear layer: w_q, s_w, bias, alpha, beta, mult, offset, s_x, z_x, s_r, z_r
+    gelu_table: torch.Tensor = None
+    params: B.vit_block_params = None
+
+    @property
+    def c(self) -> int:
+        return 64 * self.heads
+
+    @property
+    def m(self) -> int:
+        return self.batch * self.tokens
+
+
+def residual_stream(seed: int, m: int, c: int, device) -> torch.Tensor:
+    """Seeded residual stream: N(0, 1) with 1 % of the channels scaled by 8 (the systematic outlier
+    channels of Transformer activations)."""
+    h = synth.normal(seed, 0, m * c, device=device).reshape(m, c)
+    ch = synth.uniform_ints(seed, 1, max(1, c // 100), c)
+    h[:, ch] *= 8.0
+    return h.to(torch.float16)
+
+
+def _range_params(x: torch.Tensor):
+    x = x.contiguous().float()
+    mm = torch.empty(2, dtype=torch.float32, device=x.device)
+    ws = torch.empty(max(B.cwac_range_workspace(x.numel()), 16), dtype=torch.uint8, device=x.device)
+    B.cwac_range_f32(x, mm, ws)
+    mn, mx = (float(v) for v in mm.cpu())
+    s, z_u = B.cwac_qparams_from_range(mn, mx, 8)
+    return s, z_u - 128  # zero-point of the signed storage
+
+
+def build_block(seed: int, batch: int, tokens: int, heads: int, hidden: int, device="cuda:0",
+                eps: float = 1e-6, set_up_images: int = 4) -> Block:
+    """Draws the block's parameters and calibrates its quantizers on the first `set_up_images`
+    images of the seeded residual stream."""
+    c = 64 * heads
+    shapes = {"qkv": (3 * c, c), "proj": (c, c), "fc1": (hidden, c), "fc2": (c, hidden)}
+    ln = [1.0 + 0.1 * synth.normal(seed, 10, c, device=device), 0.05 * synth.normal(seed, 11, c, device=device),
+          1.0 + 0.1 * synth.normal(seed, 12, c, device=device), 0.05 * synth.normal(seed, 13, c, device=device)]
+    blk = Block(batch, tokens, heads, hidden, eps, ln)
+    w, bias = {}, {}
+    for i, name in enumerate(LAYERS):
+        n, k = shapes[name]
+        w[name] = (synth.normal(seed, 20 + i, n * k, device=device) * (1.0 / math.sqrt(k))).reshape(n, k)
+        bias[name] = 0.02 * synth.normal(seed, 30 + i, n, device=device)
+
+    # floating-point block on a few images -> ranges of every tensor that gets quantized
+    ms = min(batch, set_up_images) * tokens
+    h = residual_stream(seed, batch * tokens, c, device)[:ms].float()
+    y1 = F.layer_norm(h, (c,), ln[0], ln[1], eps)
+    qkv = y1 @ w["qkv"].t() + bias["qkv"]
+    q, k_, v = (qkv[:, j * c:(j + 1) * c].reshape(-1, tokens, heads, 64).permute(0, 2, 1, 3) for j in range(3))
+    att = F.scaled_dot_product_attention(q, k_, v).permute(0, 2, 1, 3).reshape(ms, c)
+    proj = att @ w["proj"].t() + bias["proj"]
+    h1 = h + proj
+    y2 = F.layer_norm(h1, (c,), ln[2], ln[3], eps)
+    fc1 = y2 @ w["fc1"].t() + bias["fc1"]
+    g = F.gelu(fc1)
+    fc2 = g @ w["fc2"].t() + bias["fc2"]
+    inputs = {"qkv": y1, "proj": att, "fc1": y2, "fc2": g}
+    outputs = {"qkv": qkv, "proj": proj, "fc1": fc1, "fc2": fc2}
+
+    for i, name in enumerate(LAYERS):
+        n, kk = shapes[name]
+        s_x, z_x = _range_params(inputs[name])
+        s_r, z_r = _range_params(outputs[name])
+        w_q = torch.empty(n, kk, dtype=torch.int8, device=device)
+        s_w = torch.empty(n, dtype=torch.float32, device=device)
+        B.cwac_quantize_rows_sym(w[name].contiguous(), s_w, w_q)
+        colsum = torch.empty(n, dtype=torch.int32, device=device)
+        B.cwac_colsum(w_q, colsum)
+        alpha = 1.0 + 0.03 * synth.normal(seed, 40 + i, n, device=device)
+        beta = 0.01 * synth.normal(seed, 50 + i, n, device=device)
+        qp = B.make_qparams(mode=B.CWAC_EPI_INT_OFFSET, s_x=s_x, z_x=z_x, s_r=s_r, z_r=z_r)
+        mult = torch.empty(n, dtype=torch.float32, device=device)
+        offset = torch.empty(n, dtype=torch.int32, device=device)
+        B.cwac_fold(alpha, beta, s_w, bias[name], colsum, qp, mult, offset)
+        blk.layers.append(dict(name=name, w_q=w_q, s_w=s_w, bias=bias[name], alpha=alpha, beta=beta, colsum=colsum,
+                               mult=mult, offset=offset, s_x=s_x, z_x=z_x, s_r=s_r, z_r=z_r))
+    blk.gelu_table = torch.empty(256, dtype=torch.int8, device=device)
+    B.vit_gelu_table(blk.layers[2]["s_r"], blk.layers[2]["z_r"], blk.layers[3]["s_x"], blk.layers[3]["z_x"],
+                     blk.gelu_table)
+    blk.params = B.make_block_params(batch, tokens, heads, hidden, eps, (ln[0], ln[1]), (ln[2], ln[3]), blk.layers,
+                                     blk.gelu_table)
+    torch.cuda.synchronize()
+    return blk
+
+
+def staged_forward(blk: Block, h: torch.Tensor) -> Dict[str, torch.Tensor]:
+    """The same nine launches as ``vit_block_w8a8_forward`` through the single entry points, every
+    intermediate kept: x1, r1, a, r2, h1, x2, r3, g, r4, h2."""
+    m, c, hid, dev = blk.m, blk.c, blk.hidden, h.device
+    L = blk.layers
+    i8 = lambda *s: torch.empty(*s, dtype=torch.int8, device=dev)  # noqa: E731
+    t = dict(x1=i8(m, c), r1=i8(m, 3 * c), a=i8(m, c), r2=i8(m, c), x2=i8(m, c), r3=i8(m, hid), g=i8(m, hid),
+             r4=i8(m, c), h1=torch.empty(m, c, dtype=torch.float16, device=dev),
+             h2=torch.empty(m, c, dtype=torch.float16, device=dev))
+
+    def linear(i, x, out):
+        qp = B.make_qparams(mode=B.CWAC_EPI_INT_OFFSET, s_x=L[i]["s_x"], z_x=L[i]["z_x"], s_r=L[i]["s_r"],
+                            z_r=L[i]["z_r"])
+        B.qlinear_cwac_forward(x, L[i]["w_q"], qp, L[i]["mult"], L[i]["offset"], None, None, B.CWAC_OUT_INT8, out)
+
+    B.vit_residual_ln_quant(h, None, 0.0, 0, None, blk.ln[0], blk.ln[1], blk.eps, L[0]["s_x"], L[0]["z_x"], t["x1"])
+    linear(0, t["x1"], t["r1"])
+    B.vit_attention_int8(t["r1"], L[0]["s_r"], L[0]["z_r"], blk.batch, blk.tokens, blk.heads, L[1]["s_x"],
+                         L[1]["z_x"], t["a"])
+    linear(1, t["a"], t["r2"])
+    B.vit_residual_ln_quant(h, t["r2"], L[1]["s_r"], L[1]["z_r"], t["h1"], blk.ln[2], blk.ln[3], blk.eps,
+                            L[2]["s_x"], L[2]["z_x"], t["x2"])
+    linear(2, t["x2"], t["r3"])
+    B.vit_table_lookup(t["r3"], blk.gelu_table, t["g"])
+    linear(3, t["g"], t["r4"])
+    B.vit_residual_ln_quant(t["h1"], t["r4"], L[3]["s_r"], L[3]["z_r"], t["h2"], None, None, 0.0, 1.0, 0, None)
+    return t

@@ -222,3 +222,113 @@ def test_attention_row_subset_of_a_batch_matches_single_image():
     a3 = _attention(r, 0.05, 1, 3, tokens, heads, 0.03, -2)
     a1 = _attention(r[tokens:2 * tokens], 0.05, 1, 1, tokens, heads, 0.03, -2)
     np.testing.assert_array_equal(a3[tokens:2 * tokens], a1)
+
+
+# ------------------------------------------------------------------ the whole block
+def _check_block_stages(orc, bk, h, t, rows):
+    """Every stage of the staged run against the oracle, each fed the device's own previous output,
+    on the token rows `rows` (attention: on the images those rows belong to)."""
+    L = bk.layers
+    tok = bk.tokens
+    cpu = {k: v.cpu().numpy() for k, v in t.items()}
+    h_np = h.cpu().numpy()
+    ln = [x.cpu().numpy() for x in bk.ln]
+    d_ln = lambda v: 64 * U32 * (np.abs(v) + 128) + 1e-4  # noqa: E731
+
+    # x1 = Q(LN1(h))
+    _, v = blk_quant(blk_ln(h_np[rows], ln[0], ln[1], bk.eps), L[0]["s_x"], L[0]["z_x"])
+    assert _codes_within(cpu["x1"][rows], v, d_ln(v)) > 0.99
+    # the four linear layers: fold and folded forward of the main oracle, bit-exact
+    for i, (x, r) in enumerate((("x1", "r1"), ("a", "r2"), ("x2", "r3"), ("g", "r4"))):
+        ly = L[i]
+        mult, offset, _ = orc.fold_int_offset(ly["alpha"].cpu().numpy(), ly["beta"].cpu().numpy(),
+                                              ly["s_w"].cpu().numpy(), ly["bias"].cpu().numpy(),
+                                              ly["colsum"].cpu().numpy(), ly["s_x"], ly["z_x"], ly["s_r"])
+        np.testing.assert_array_equal(ly["mult"].cpu().numpy(), mult)
+        np.testing.assert_array_equal(ly["offset"].cpu().numpy(), offset)
+        acc = orc.gemm_i8(cpu[x], ly["w_q"].cpu().numpy(), rows=rows)
+        np.testing.assert_array_equal(cpu[r][rows], orc.folded_forward(acc, offset, mult, ly["z_r"]))
+    # attention on the images of the sampled rows
+    images = np.unique(rows // tok)
+    for b in images:
+        sl = slice(b * tok, (b + 1) * tok)
+        o, mag = blk_attn(cpu["r1"][sl], np.float32(L[0]["s_r"]), L[0]["z_r"], 1, tok, bk.heads)
+        s_a = np.float32(L[1]["s_x"])
+        _, v = blk_quant(o, s_a, L[1]["z_x"])
+        delta = (2.0 ** -11 + 256 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
+        _codes_within(cpu["a"][sl], v, delta)
+    # h1 = RN16(h + deq(r2)), x2 = Q(LN2(h1))
+    want16, tt = blk_res(h_np[rows], cpu["r2"][rows], np.float32(L[1]["s_r"]), L[1]["z_r"])
+    slack = 2 * U32 * (np.abs(h_np[rows].astype(np.float64)) + np.abs(tt)) + 1e-30
+    g16 = cpu["h1"][rows].astype(np.float64)
+    assert ((g16 >= (tt - slack).astype(np.float16)) & (g16 <= (tt + slack).astype(np.float16))).all()
+    _, v = blk_quant(blk_ln(cpu["h1"][rows], ln[2], ln[3], bk.eps), L[2]["s_x"], L[2]["z_x"])
+    assert _codes_within(cpu["x2"][rows], v, d_ln(v)) > 0.99
+    # g = table[r3]
+    want_tab, v = blk_table(np.float32(L[2]["s_r"]), L[2]["z_r"], np.float32(L[3]["s_x"]), L[3]["z_x"])
+    got_tab = bk.gelu_table.cpu().numpy()
+    tie = np.abs(v - np.floor(v) - 0.5) < 1e-9
+    np.testing.assert_array_equal(got_tab[~tie], want_tab[~tie])
+    np.testing.assert_array_equal(cpu["g"][rows], got_tab[cpu["r3"][rows].astype(int) + 128])
+    # h2 = RN16(h1 + deq(r4))
+    _, tt = blk_res(cpu["h1"][rows], cpu["r4"][rows], np.float32(L[3]["s_r"]), L[3]["z_r"])
+    slack = 2 * U32 * (np.abs(cpu["h1"][rows].astype(np.float64)) + np.abs(tt)) + 1e-30
+    g16 = cpu["h2"][rows].astype(np.float64)
+    assert ((g16 >= (tt - slack).astype(np.float16)) & (g16 <= (tt + slack).astype(np.float16))).all()
+
+
+blk_ln, blk_quant, blk_attn, blk_res, blk_table = (blk.layernorm, blk.quantize, blk.attention_codes, blk.residual,
+                                                   blk.gelu_table)
+
+
+def _run_block(orc, seed, batch, tokens, heads, hidden, rows):
+    from paper_2505_20932_amd import vit_block
+    b = vit_block.build_block(seed, batch, tokens, heads, hidden, device=DEV)
+    h = vit_block.residual_stream(seed, b.m, b.c, DEV)
+    t = vit_block.staged_forward(b, h)
+    ws = torch.empty(P.vit_block_workspace(batch, tokens, heads, hidden), dtype=torch.int8, device=DEV)
+    h_out = torch.empty_like(h)
+    P.vit_block_w8a8_forward(b.params, h, h_out, ws)
+    torch.cuda.synchronize()
+    # the chained entry point is the same nine launches: bit-identical results, documented workspace
+    m, c = b.m, b.c
+    assert torch.equal(h_out, t["h2"])
+    assert torch.equal(ws[:m * c].view(m, c), t["x2"])
+    assert torch.equal(ws[m * c:4 * m * c].view(m, 3 * c), t["r1"])
+    assert torch.equal(ws[4 * m * c:5 * m * c].view(m, c), t["r4"])
+    assert torch.equal(ws[5 * m * c:].view(m, hidden), t["g"])
+    # the codes use their ranges (a block whose tensors saturate or collapse would test nothing)
+    for k in ("x1", "r1", "a", "r2", "x2", "r3", "g", "r4"):
+        codes = t[k].cpu().numpy()
+        assert np.unique(codes).size > 60, (k, np.unique(codes).size)
+    _check_block_stages(orc, b, h, t, rows)
+    return b, t
+
+
+def test_block_chain_small(orc):
+    print("block: 3 images x 197 tokens, 3 heads, MLP 768", flush=True)
+    _run_block(orc, 3, 3, 197, 3, 768, np.arange(3 * 197))
+
+
+def test_block_chain_other_shapes(orc):
+    print("block: 5 images x 50 tokens, 2 heads, MLP 256", flush=True)
+    _run_block(orc, 4, 5, 50, 2, 256, np.arange(250))
+
+
+def test_block_full_size_sampled(orc):
+    """ViT-B/16: 128 images x 197 tokens, 12 heads, MLP 3072 - the launch configuration the benchmark's
+    block section times; the oracle checks three images' rows."""
+    print("block: 128 images x 197 tokens, 12 heads, MLP 3072", flush=True)
+    rows = np.concatenate([np.arange(0, 197), np.arange(63 * 197, 64 * 197), np.arange(127 * 197, 128 * 197)])
+    _run_block(orc, 5, 128, 197, 12, 3072, rows)
+
+
+def test_block_argument_errors():
+    from paper_2505_20932_amd import vit_block
+    b = vit_block.build_block(6, 1, 16, 1, 64, device=DEV)
+    h = vit_block.residual_stream(6, 16, 64, DEV)
+    ws = torch.empty(P.vit_block_workspace(1, 16, 1, 64), dtype=torch.int8, device=DEV)
+    with pytest.raises(P.CwacError):
+        P.vit_block_w8a8_forward(b.params, h, h, ws)            # in place
+    with pytest.raises(P.CwacError):
+        P.vit_block_w8a8_forward(b.params, h, torch.empty_like(h), ws[:100])
