@@ -676,6 +676,137 @@ def conv_section(P, synth, torch, dev: str, batch: int, steps: int, cpu_batch: i
 
 
 
+def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_images: int):
+    """One W8A8 Vision Transformer block (ViT-B/16: 197 tokens, 12 heads, MLP 3072) from residual
+    stream to residual stream: the four compensated linear layers (Sec. 3.4) chained with the
+    non-linear glue that per-layer compensation steps around (Sec. 3.2).  A step = one call of
+    vit_block_w8a8_forward (nine launches); every stage is also timed alone."""
+    import numpy as np
+    from paper_2505_20932_amd import vit_block
+    tokens, heads, hidden = 197, 12, 3072
+    blk = vit_block.build_block(2, batch, tokens, heads, hidden, device=dev)
+    m, c = blk.m, blk.c
+    h = vit_block.residual_stream(2, m, c, dev)
+    h_out = torch.empty_like(h)
+    ws = torch.empty(P.vit_block_workspace(batch, tokens, heads, hidden), dtype=torch.int8, device=dev)
+    for _ in range(warmup):
+        P.vit_block_w8a8_forward(blk.params, h, h_out, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        P.vit_block_w8a8_forward(blk.params, h, h_out, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / steps
+    ms_block = e0.elapsed_time(e1) / steps
+
+    t = vit_block.staged_forward(blk, h)
+    L = blk.layers
+    B = P.binding
+
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e3  # us
+
+    def linear(i, x, out):
+        qp = B.make_qparams(mode=B.CWAC_EPI_INT_OFFSET, s_x=L[i]["s_x"], z_x=L[i]["z_x"], s_r=L[i]["s_r"],
+                            z_r=L[i]["z_r"])
+        return lambda: B.qlinear_cwac_forward(x, L[i]["w_q"], qp, L[i]["mult"], L[i]["offset"], None, None,
+                                              B.CWAC_OUT_INT8, out)
+
+    stages = [
+        ("ln1_quant", lambda: B.vit_residual_ln_quant(h, None, 0.0, 0, None, blk.ln[0], blk.ln[1], blk.eps,
+                                                      L[0]["s_x"], L[0]["z_x"], t["x1"]), "hbm", 3.0 * m * c),
+        ("qkv", linear(0, t["x1"], t["r1"]), "mfma", 2.0 * m * 3 * c * c),
+        ("attention", lambda: B.vit_attention_int8(t["r1"], L[0]["s_r"], L[0]["z_r"], batch, tokens, heads,
+                                                   L[1]["s_x"], L[1]["z_x"], t["a"]), "mfma_f16",
+         4.0 * batch * heads * tokens * tokens * 64),
+        ("proj", linear(1, t["a"], t["r2"]), "mfma", 2.0 * m * c * c),
+        ("residual_ln2_quant", lambda: B.vit_residual_ln_quant(h, t["r2"], L[1]["s_r"], L[1]["z_r"], t["h1"], blk.ln[2],
+                                                               blk.ln[3], blk.eps, L[2]["s_x"], L[2]["z_x"], t["x2"]),
+         "hbm", 6.0 * m * c),
+        ("fc1", linear(2, t["x2"], t["r3"]), "mfma", 2.0 * m * hidden * c),
+        ("gelu_table_lookup", lambda: B.vit_table_lookup(t["r3"], blk.gelu_table, t["g"]), "hbm", 2.0 * m * hidden),
+        ("fc2", linear(3, t["g"], t["r4"]), "mfma", 2.0 * m * c * hidden),
+        ("residual", lambda: B.vit_residual_ln_quant(t["h1"], t["r4"], L[3]["s_r"], L[3]["z_r"], t["h2"], None, None,
+                                                     0.0, 1.0, 0, None), "hbm", 5.0 * m * c),
+    ]
+    per_stage, lin_us, glue_us = [], 0.0, 0.0
+    for name, fn, bound, work in stages:
+        us = timed(fn)
+        ent = {"stage": name, "us": round(us, 1), "bound": bound}
+        if bound == "hbm":
+            ent["algorithmic_gbs"] = round(work / us / 1e3, 1)
+            ent["frac"] = round(work / us / 1e3 / HBM_PEAK_GBS, 4)
+            glue_us += us
+        elif bound == "mfma":
+            ent["tops"] = round(work / us / 1e6, 1)
+            ent["frac"] = round(work / us / 1e6 / INT8_MFMA_PEAK_TOPS, 4)
+            lin_us += us
+        else:
+            ent["tflops"] = round(work / us / 1e6, 1)
+            ent["frac"] = round(work / us / 1e6 / 2500.0, 4)
+            glue_us += us
+        per_stage.append(ent)
+    lin_ops = 2.0 * m * c * (3 * c + c + 2 * hidden)
+    att = next(e for e in per_stage if e["stage"] == "attention")
+    res = {
+        "metric": "W8A8 Transformer block forward, linear-layer TOPS over the whole block's time",
+        "value": round(lin_ops / (ms_block * 1e-3) / 1e12, 2), "unit": "TOPS", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"ViT-B/16 block, {batch} images x {tokens} tokens, 12 heads x 64, MLP 3072, "
+                               f"per-tensor int8 activations, binary16 residual stream"},
+        "block_ms": round(ms_block, 4), "images_per_s": round(batch / (ms_block * 1e-3), 1),
+        "linear_layers_us": round(lin_us, 1), "glue_us": round(glue_us, 1),
+        "glue_share_of_stage_sum": round(glue_us / (glue_us + lin_us), 4),
+        "roofline": {"bound": "mfma", "achieved": round(att["tflops"] / 1e3, 4), "peak": 2.5, "unit": "PFLOP/s",
+                     "frac": att["frac"], "traffic": None,
+                     "kernel": "attention_int8_kernel (the longest glue stage; fp16 MFMA, 4 T^2 d flops per head)"},
+        "stages": per_stage,
+    }
+    if cpu_images > 0:
+        from oracle import block_oracle as blk_o
+        from oracle import cwac_oracle as orc
+        rows = cpu_images * tokens
+        cpu = {k: v[:rows].cpu().numpy() for k, v in t.items()}
+        hh = h[:rows].cpu().numpy()
+        ln = [x.cpu().numpy() for x in blk.ln]
+        t0 = time.perf_counter()
+        x1, _ = blk_o.quantize(blk_o.layernorm(hh, ln[0], ln[1], blk.eps), L[0]["s_x"], L[0]["z_x"])
+        fwd = lambda i, x: orc.folded_forward(orc.gemm_i8(x, L[i]["w_q"].cpu().numpy()),  # noqa: E731
+                                              L[i]["offset"].cpu().numpy(), L[i]["mult"].cpu().numpy(), L[i]["z_r"])
+        r1 = fwd(0, x1)
+        o, _ = blk_o.attention_codes(r1, L[0]["s_r"], L[0]["z_r"], cpu_images, tokens, heads)
+        a, _ = blk_o.quantize(o, L[1]["s_x"], L[1]["z_x"])
+        r2 = fwd(1, a)
+        h1, _ = blk_o.residual(hh, r2, L[1]["s_r"], L[1]["z_r"])
+        x2, _ = blk_o.quantize(blk_o.layernorm(h1, ln[2], ln[3], blk.eps), L[2]["s_x"], L[2]["z_x"])
+        r3 = fwd(2, x2)
+        tab, _ = blk_o.gelu_table(L[2]["s_r"], L[2]["z_r"], L[3]["s_x"], L[3]["z_x"])
+        g = tab[r3.astype(int) + 128]
+        r4 = fwd(3, g)
+        blk_o.residual(h1, r4, L[3]["s_r"], L[3]["z_r"])
+        secs = time.perf_counter() - t0
+        agree = float((r4 == cpu["r4"]).mean())
+        res["cpu_baseline"] = {"value": round(2.0 * rows * c * (3 * c + c + 2 * hidden) / secs / 1e12, 5), "unit": "TOPS",
+                               "cores": orc.get_threads(), "kind": "oracle",
+                               "sample": f"the same block on {cpu_images} images ({secs:.1f} s of oracle time; its "
+                                         f"fc2 output codes equal the GPU's on {agree:.4f} of the elements - the rest "
+                                         f"are fp32 ties of the glue stages carried through the chain)"}
+    return res
+
+
 def cpu_baseline(synth, cfg: int, sample_rows: int):
     """The oracle, as it stands, timed on this host on a bounded row sample of the same step."""
     import numpy as np
@@ -738,6 +869,10 @@ def main():
                     help="the convolutional-layer section instead: ResNet-50 bottleneck convolutions "
                          "(its own JSON line)")
     ap.add_argument("--conv-batch", type=int, default=128)
+    ap.add_argument("--block", action="store_true",
+                    help="the Transformer-block section instead: one ViT-B/16 block, linear layers chained "
+                         "with the non-linear glue (its own JSON line)")
+    ap.add_argument("--block-batch", type=int, default=128)
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -757,6 +892,10 @@ def main():
     if args.conv:
         print(json.dumps(conv_section(P, synth, torch, dev, args.conv_batch, args.steps,
                                       0 if args.no_cpu_baseline else 8)))
+        return
+    if args.block:
+        print(json.dumps(block_section(P, torch, dev, args.block_batch, args.steps, args.warmup,
+                                       0 if args.no_cpu_baseline else 2)))
         return
     wl = synth.WORKLOADS[args.config]
     cal_rows = args.cal_rows or wl.m

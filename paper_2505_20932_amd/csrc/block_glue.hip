@@ -7,9 +7,10 @@
 // Arithmetic, in fp32 unless stated (no contraction: each line is one rounding):
 //   residual   t = h + s_r * (float)(c - z_r);  h1 = RN16(t);  the layer norm reads h1
 //   layer norm mean = sum(x) / C;  var = sum((x - mean)^2) / C;  y = (x - mean) * (1 / sqrt(var + eps)) * gamma + beta
-//   quantizer  code = clip(rne(y / s + z), -128, 127)                                   (Eq. 1)
+//   quantizer  code = clip(rne(y * (1 / s) + z), -128, 127)                             (Eq. 1)
 //   attention  S = (K - z)(Q - z)^T exactly (integers below 2^24 in the fp32 MFMA accumulators);
-//              p = exp2((S - max S) * s^2 / sqrt(d) * log2 e);  O = (sum_j RN16(1024 p_j) (V_j - z)) * s / (1024 sum_j p_j)
+//              P = 1024 p = exp2(fma(S, s^2 / sqrt(d) * log2 e, 10 - that * max S));  O = (sum_j RN16(P_j) (V_j - z)) * s / sum_j P_j,
+//              keys taken in groups of 96 with the running maximum (earlier partial sums rescaled)
 //   GELU table entry(c) = clip(rne(GELU(s_in (c - z_in)) / s_out + z_out)) evaluated in fp64 (erf form)
 #include <hip/hip_runtime.h>
 
@@ -31,10 +32,11 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-__device__ __forceinline__ int quant_code(float y, float s, float zf) {
-  const float v = y / s + zf;
-  const float r = fminf(fmaxf(rintf(v), -128.0f), 127.0f);
-  return (int)r;
+// Eq. 1 with the division by the scale as a multiplication by its fp32 reciprocal (one rounding
+// more than a division: far inside what decides a code only at a tie).
+__device__ __forceinline__ int quant_code(float y, float inv_s, float zf) {
+  const float v = y * inv_s + zf;
+  return (int)__builtin_amdgcn_fmed3f(rintf(v), -128.0f, 127.0f);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -93,6 +95,16 @@ __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p
     }
   }
   if (!p.x_q) return;
+  // gamma and beta of this lane's channels, requested before the reductions need the row
+  float4 gb[NV][4];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    const int v = lane + 64 * j < nvec ? lane + 64 * j : 0;
+    gb[j][0] = *reinterpret_cast<const float4 *>(p.gamma + 8 * v);
+    gb[j][1] = *reinterpret_cast<const float4 *>(p.gamma + 8 * v + 4);
+    gb[j][2] = *reinterpret_cast<const float4 *>(p.beta + 8 * v);
+    gb[j][3] = *reinterpret_cast<const float4 *>(p.beta + 8 * v + 4);
+  }
   float s = 0.0f;
 #pragma unroll
   for (int j = 0; j < NV; ++j)
@@ -112,22 +124,19 @@ __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p
   }
   const float var = wave_sum(ss) / (float)p.c;
   const float rstd = 1.0f / sqrtf(var + p.eps);
-  const float zf = (float)p.z_x;
+  const float zf = (float)p.z_x, inv_s = 1.0f / p.s_x;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     const int v = lane + 64 * j;
     if (v < nvec) {
-      const float4 g0 = *reinterpret_cast<const float4 *>(p.gamma + 8 * v);
-      const float4 g1 = *reinterpret_cast<const float4 *>(p.gamma + 8 * v + 4);
-      const float4 b0 = *reinterpret_cast<const float4 *>(p.beta + 8 * v);
-      const float4 b1 = *reinterpret_cast<const float4 *>(p.beta + 8 * v + 4);
+      const float4 g0 = gb[j][0], g1 = gb[j][1], b0 = gb[j][2], b1 = gb[j][3];
       const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
       const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
       uint32_t w[2] = {0u, 0u};
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float y = x[j][e] * rstd * g[e] + b[e];
-        const int code = quant_code(y, p.s_x, zf);
+        const int code = quant_code(y, inv_s, zf);
         w[e >> 2] |= (uint32_t)(code & 0xff) << (8 * (e & 3));
       }
       *reinterpret_cast<uint2 *>(p.x_q + row * p.ldxq + 8 * v) = make_uint2(w[0], w[1]);
@@ -201,6 +210,80 @@ struct AttnParams {
   int64_t lda;
 };
 
+// Scores, softmax weights and the second product for CNT key tiles starting at tile t0, with the
+// running maximum `mx`, the running (lane-local) sum of weights and the output accumulators
+// rescaled when a later group raises the maximum (the usual streaming form of the softmax: the
+// result is the same up to fp32 rounding, and only CNT score tiles are live at a time).
+template <int CNT>
+__device__ __forceinline__ void attention_key_group(int t0, bool first, const int8_t *s_k, const int8_t *s_v,
+                                                    const h8 (&fq)[4], int tokens, float lscale, int l32, int half,
+                                                    float &mx, float &sum, v16f (&oc)[2]) {
+  v16f sc[CNT];
+#pragma unroll
+  for (int t = 0; t < CNT; ++t) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sc[t][i] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const h8 fk = *reinterpret_cast<const h8 *>(s_k + (32 * (t0 + t) + l32) * kKStride + (2 * s + half) * 16);
+      sc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sc[t], 0, 0, 0);
+    }
+  }
+  // register 4 g + r of tile t is key 32 t + 8 g + 4 half + r of this lane's query
+  float gmx = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < CNT; ++t) {
+    if (32 * (t0 + t) + 32 > tokens) {  // only the last tile can hold padded keys (uniform branch)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = 32 * (t0 + t) + 8 * (i >> 2) + 4 * half + (i & 3);
+        if (key >= tokens) sc[t][i] = -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) gmx = fmaxf(gmx, sc[t][i]);
+  }
+  gmx = fmaxf(gmx, __shfl_xor(gmx, 32, 64));  // every tile holds at least one real key: finite
+  if (first) {
+    mx = gmx;
+  } else if (gmx > mx) {  // the same decision in both lanes of a query
+    const float corr = __builtin_amdgcn_exp2f((mx - gmx) * lscale);
+    sum *= corr;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oc[a][i] *= corr;
+    mx = gmx;
+  }
+  // 1024 p = exp2(S * lscale + (10 - mx * lscale)), one fused multiply-add per exponent;
+  // exp2(-inf) = 0 for masked keys
+  const float eoff = 10.0f - mx * lscale;
+#pragma unroll
+  for (int t = 0; t < CNT; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      sc[t][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[t][i], lscale, eoff));
+      sum += sc[t][i];
+    }
+#pragma unroll
+  for (int t = 0; t < CNT; ++t)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      h8 fp;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) fp[e] = (_Float16)sc[t][8 * u + e];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        const int8_t *vb = s_v + (32 * a + l32) * kVStride + (32 * (t0 + t) + 16 * u + 4 * half) * 2;
+        const h4 lo = *reinterpret_cast<const h4 *>(vb), hi = *reinterpret_cast<const h4 *>(vb + 16);
+        const h8 fv = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        oc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp, oc[a], 0, 0, 0);
+      }
+    }
+}
+
+constexpr int kKeyGroup = 3;  // key tiles per group: 48 score registers live, two workgroups per compute unit
+
 template <int NT>
 __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParams p) {
   constexpr int TP = 32 * NT;
@@ -248,63 +331,26 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
   }
   __syncthreads();
 
-  v16f sc[NT];
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-#pragma unroll
-    for (int i = 0; i < 16; ++i) sc[t][i] = 0.0f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const h8 fk = *reinterpret_cast<const h8 *>(s_k + (32 * t + l32) * kKStride + (2 * s + half) * 16);
-      sc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sc[t], 0, 0, 0);
-    }
-  }
-  // softmax over the keys of this lane's query: register 4 g + r of tile t is key 32 t + 8 g + 4 half + r
-  float mx = -INFINITY;
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int key = 32 * t + 8 * (i >> 2) + 4 * half + (i & 3);
-      if (key >= p.tokens) sc[t][i] = -INFINITY;
-      mx = fmaxf(mx, sc[t][i]);
-    }
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
   const float lscale = p.s * p.s * 0.125f * 1.44269504088896340736f;  // s^2 / sqrt(64) * log2(e)
-  float sum = 0.0f;
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float pr = __builtin_amdgcn_exp2f((sc[t][i] - mx) * lscale);  // exp2(-inf) = 0 for masked keys
-      sum += pr;
-      sc[t][i] = pr * 1024.0f;
-    }
-  sum += __shfl_xor(sum, 32, 64);
-
+  float mx = 0.0f, sum = 0.0f;
   v16f oc[2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oc[a][i] = 0.0f;
 #pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      h8 fp;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) fp[e] = (_Float16)sc[t][8 * u + e];
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        const int8_t *vb = s_v + (32 * a + l32) * kVStride + (32 * t + 16 * u + 4 * half) * 2;
-        const h4 lo = *reinterpret_cast<const h4 *>(vb), hi = *reinterpret_cast<const h4 *>(vb + 16);
-        const h8 fv = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        oc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp, oc[a], 0, 0, 0);
-      }
-    }
+  for (int g = 0; g < NT / kKeyGroup; ++g) {
+    attention_key_group<kKeyGroup>(g * kKeyGroup, g == 0, s_k, s_v, fq, p.tokens, lscale, l32, half, mx, sum, oc);
+    __builtin_amdgcn_sched_barrier(0);  // one group's score tiles live at a time
+  }
+  if constexpr (NT % kKeyGroup != 0)
+    attention_key_group<NT % kKeyGroup>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq, p.tokens, lscale, l32,
+                                        half, mx, sum, oc);
+  sum += __shfl_xor(sum, 32, 64);
+
   // O^T: register 4 g + r of tile a is channel 32 a + 8 g + 4 half + r of this lane's query
-  const float onorm = p.s * (1.0f / (sum * 1024.0f));
-  const float zf = (float)p.z_a;
+  const float onorm = p.s * (1.0f / sum);  // sum and the accumulators both carry the factor 1024
+  const float zf = (float)p.z_a, inv_sa = 1.0f / p.s_a;
   int8_t *orow = p.a + (row0 + qrow) * p.lda + head * kHeadDim;
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
@@ -313,7 +359,7 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
     for (int g = 0; g < 4; ++g) {
       uint32_t w = 0;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) w |= (uint32_t)(quant_code(oc[a][4 * g + r] * onorm, p.s_a, zf) & 0xff) << (8 * r);
+      for (int r = 0; r < 4; ++r) w |= (uint32_t)(quant_code(oc[a][4 * g + r] * onorm, inv_sa, zf) & 0xff) << (8 * r);
       packed[g] = w;
     }
     // lower half-wave holds channels 8g .. 8g+3, upper 8g+4 .. 8g+7: after the two swaps the lower

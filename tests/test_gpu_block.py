@@ -162,8 +162,9 @@ def test_attention_random_codes(batch, tokens, heads):
     s_a, z_a = _out_params(o)
     got = _attention(r, float(s), z, batch, tokens, heads, s_a, z_a, pad=16)
     _, v = blk.quantize(o, np.float32(s_a), z_a)
-    # weights rounded to binary16 (2^-11 relative, per term), fp32 exp2 / sums / normalization
-    delta = (2.0 ** -11 + 256 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
+    # weights rounded to binary16 (2^-11 relative, per term); fp32 exponent arguments of size up to a few
+    # hundred (absolute error ~1e-5 in the exponent), fp32 exp2 / sums / normalization
+    delta = (2.0 ** -11 + 1024 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
     pinned = _codes_within(got, v, delta)
     want, _ = blk.quantize(o, np.float32(s_a), z_a)
     assert (got == want).mean() > 0.9, float((got == want).mean())
@@ -255,7 +256,7 @@ def _check_block_stages(orc, bk, h, t, rows):
         o, mag = blk_attn(cpu["r1"][sl], np.float32(L[0]["s_r"]), L[0]["z_r"], 1, tok, bk.heads)
         s_a = np.float32(L[1]["s_x"])
         _, v = blk_quant(o, s_a, L[1]["z_x"])
-        delta = (2.0 ** -11 + 256 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
+        delta = (2.0 ** -11 + 1024 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
         _codes_within(cpu["a"][sl], v, delta)
     # h1 = RN16(h + deq(r2)), x2 = Q(LN2(h1))
     want16, tt = blk_res(h_np[rows], cpu["r2"][rows], np.float32(L[1]["s_r"]), L[1]["z_r"])
