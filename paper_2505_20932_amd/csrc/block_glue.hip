@@ -26,10 +26,30 @@ typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float wave_sum(float v) {
+// sum over aligned groups of LPR lanes (the same value in every lane of a group)
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
   return v;
+}
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+
+// Four int8 codes (one word) -> (code - z) as four binary16 values, exactly: a byte u = code + 128 under
+// the high byte 0x64 is the binary16 number 1024 + u, and (1024 + u) - (1152 + z) is an integer below
+// 2048 in magnitude.  `bias` = 1152 + z in both halves.
+__device__ __forceinline__ void codes_to_h4(uint32_t w, h2 bias, h2 &lo, h2 &hi) {
+  const uint32_t u = w ^ 0x80808080u;
+  lo = __builtin_bit_cast(h2, __builtin_amdgcn_perm(0x64646464u, u, 0x04010400u)) - bias;
+  hi = __builtin_bit_cast(h2, __builtin_amdgcn_perm(0x64646464u, u, 0x04030402u)) - bias;
+}
+
+__device__ __forceinline__ h8 codes_to_h8(uint2 c, h2 bias) {
+  h2 a, b, d, e;
+  codes_to_h4(c.x, bias, a, b);
+  codes_to_h4(c.y, bias, d, e);
+  return h8{a[0], a[1], b[0], b[1], d[0], d[1], e[0], e[1]};
 }
 
 // Eq. 1 with the division by the scale as a multiplication by its fp32 reciprocal (one rounding
@@ -40,8 +60,9 @@ __device__ __forceinline__ int quant_code(float y, float inv_s, float zf) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Residual add + layer norm + quantizer: one wavefront per token row, the row in registers
-// (NV vectors of 8 channels per lane: C <= 512 * NV), two-pass mean / variance, no LDS.
+// Residual add + layer norm + quantizer: LPR (16, 32 or 64) lanes per token row, the row in
+// registers (NV vectors of 8 channels per lane: C <= 8 * LPR * NV; the host picks the pair that
+// leaves the fewest idle lanes, e.g. 32 x 3 for C = 768), two-pass mean / variance, no LDS.
 // HBM bytes per element: 2 (h) [+ 1 (codes) + 2 (h1)] + 1 (x_q).
 // ------------------------------------------------------------------------------------------
 struct LnParams {
@@ -62,16 +83,19 @@ struct LnParams {
   int c;
 };
 
-template <int NV>
+template <int LPR, int NV>
 __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= p.m) return;  // whole wavefronts leave; no barrier in this kernel
+  const int lane = threadIdx.x & (LPR - 1);  // position inside the row's group of LPR lanes
+  int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+  // lane groups past the end read the last row and store nothing: the shuffles below then always run
+  // with every lane active (h_out may be h itself, so such a group must not store)
+  const bool live = row < p.m;
+  if (!live) row = p.m - 1;
   const int nvec = p.c >> 3;
   float x[NV][8];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    const int v = lane + 64 * j;
+    const int v = lane + LPR * j;
     if (v < nvec) {
       const h8 hv = *reinterpret_cast<const h8 *>(p.h + row * p.ldh + 8 * v);
 #pragma unroll
@@ -87,7 +111,7 @@ __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p
           ho[e] = (_Float16)t;
           x[j][e] = (float)ho[e];
         }
-        if (p.h_out) *reinterpret_cast<h8 *>(p.h_out + row * p.ldho + 8 * v) = ho;
+        if (p.h_out && live) *reinterpret_cast<h8 *>(p.h_out + row * p.ldho + 8 * v) = ho;
       }
     } else {
 #pragma unroll
@@ -99,7 +123,7 @@ __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p
   float4 gb[NV][4];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    const int v = lane + 64 * j < nvec ? lane + 64 * j : 0;
+    const int v = lane + LPR * j < nvec ? lane + LPR * j : 0;
     gb[j][0] = *reinterpret_cast<const float4 *>(p.gamma + 8 * v);
     gb[j][1] = *reinterpret_cast<const float4 *>(p.gamma + 8 * v + 4);
     gb[j][2] = *reinterpret_cast<const float4 *>(p.beta + 8 * v);
@@ -110,11 +134,11 @@ __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p
   for (int j = 0; j < NV; ++j)
 #pragma unroll
     for (int e = 0; e < 8; ++e) s += x[j][e];
-  const float mean = wave_sum(s) / (float)p.c;
+  const float mean = group_sum<LPR>(s) / (float)p.c;
   float ss = 0.0f;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    const bool ok = lane + 64 * j < nvec;
+    const bool ok = lane + LPR * j < nvec;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float d = ok ? x[j][e] - mean : 0.0f;
@@ -122,12 +146,12 @@ __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p
       ss += d * d;
     }
   }
-  const float var = wave_sum(ss) / (float)p.c;
+  const float var = group_sum<LPR>(ss) / (float)p.c;
   const float rstd = 1.0f / sqrtf(var + p.eps);
   const float zf = (float)p.z_x, inv_s = 1.0f / p.s_x;
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
-    const int v = lane + 64 * j;
+    const int v = lane + LPR * j;
     if (v < nvec) {
       const float4 g0 = gb[j][0], g1 = gb[j][1], b0 = gb[j][2], b1 = gb[j][3];
       const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
@@ -139,7 +163,7 @@ __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p
         const int code = quant_code(y, inv_s, zf);
         w[e >> 2] |= (uint32_t)(code & 0xff) << (8 * (e & 3));
       }
-      *reinterpret_cast<uint2 *>(p.x_q + row * p.ldxq + 8 * v) = make_uint2(w[0], w[1]);
+      if (live) *reinterpret_cast<uint2 *>(p.x_q + row * p.ldxq + 8 * v) = make_uint2(w[0], w[1]);
     }
   }
 }
@@ -296,19 +320,15 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
   const int c = p.heads * kHeadDim;
   const int8_t *qbase = p.r + row0 * p.ld + head * kHeadDim;
 
+  const _Float16 zb = (_Float16)(float)(1152 + p.z);
+  const h2 zbias = {zb, zb};
   // K and V of the head -> LDS as (code - z) in binary16; rows beyond the last token are zero
   for (int i = tid; i < TP * 8; i += 64 * NT) {
     const int key = i >> 3, ch = i & 7;
     h8 kv, vv;
     if (key < p.tokens) {
-      const uint2 kc = *reinterpret_cast<const uint2 *>(qbase + key * p.ld + c + 8 * ch);
-      const uint2 vc = *reinterpret_cast<const uint2 *>(qbase + key * p.ld + 2 * c + 8 * ch);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int sh = 8 * (e & 3);
-        kv[e] = (_Float16)((int)(int8_t)((e < 4 ? kc.x : kc.y) >> sh) - p.z);
-        vv[e] = (_Float16)((int)(int8_t)((e < 4 ? vc.x : vc.y) >> sh) - p.z);
-      }
+      kv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + key * p.ld + c + 8 * ch), zbias);
+      vv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + key * p.ld + 2 * c + 8 * ch), zbias);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) kv[e] = vv[e] = (_Float16)0.0f;
@@ -324,10 +344,7 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
   h8 fq[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    const uint2 qc = *reinterpret_cast<const uint2 *>(qbase + qrow * p.ld + 16 * s + 8 * half);
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      fq[s][e] = (_Float16)((int)(int8_t)((e < 4 ? qc.x : qc.y) >> (8 * (e & 3))) - p.z);
+    fq[s] = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + qrow * p.ld + 16 * s + 8 * half), zbias);
   }
   __syncthreads();
 
@@ -392,7 +409,7 @@ cwac_status vit_residual_ln_quant(const uint16_t *h, int64_t ldh, const int8_t *
   if (x_q && (!gamma || !beta)) return CWAC_E_NULL;
   if (h_out && !r) return CWAC_E_MODE;
   if (m < 1 || c < 8 || c % 8 != 0 || c > 2048 || ldh < c || (r && ldr < c) || (h_out && ldho < c) ||
-      (x_q && ldxq < c) || (m + 3) / 4 > 0x7fffffff)
+      (x_q && ldxq < c) || m > 0x7fffffff)
     return CWAC_E_SHAPE;
   if (!(s_x > 0.0f) && x_q) return CWAC_E_MODE;
   if (!aligned(h, 16) || ldh % 8 != 0 || (r && (!aligned(r, 8) || ldr % 8 != 0)) ||
@@ -417,14 +434,22 @@ cwac_status vit_residual_ln_quant(const uint16_t *h, int64_t ldh, const int8_t *
   p.ldxq = ldxq;
   p.m = m;
   p.c = c;
-  const dim3 grid((unsigned)((m + 3) / 4));
+  // lanes per row and vectors per lane: the pair with the fewest idle vector slots, ties to the wider group
+  const int nvec = c / 8;
+  int lpr = 64, nv = (nvec + 63) / 64;
+  for (int cand = 32; cand >= 16; cand /= 2) {
+    const int cnv = (nvec + cand - 1) / cand;
+    if (cnv <= 4 && cnv * cand < nv * lpr) lpr = cand, nv = cnv;
+  }
+  const dim3 grid((unsigned)ceil_div(m, 256 / lpr));
   hipStream_t st = as_stream(stream);
-  if (c <= 512)
-    residual_ln_quant_kernel<1><<<grid, 256, 0, st>>>(p);
-  else if (c <= 1024)
-    residual_ln_quant_kernel<2><<<grid, 256, 0, st>>>(p);
-  else
-    residual_ln_quant_kernel<4><<<grid, 256, 0, st>>>(p);
+#define CWAC_LN_CASE(L, N) \
+  if (lpr == L && nv == N) residual_ln_quant_kernel<L, N><<<grid, 256, 0, st>>>(p)
+  CWAC_LN_CASE(64, 1); else CWAC_LN_CASE(64, 2); else CWAC_LN_CASE(64, 3); else CWAC_LN_CASE(64, 4);
+  else CWAC_LN_CASE(32, 1); else CWAC_LN_CASE(32, 2); else CWAC_LN_CASE(32, 3); else CWAC_LN_CASE(32, 4);
+  else CWAC_LN_CASE(16, 1); else CWAC_LN_CASE(16, 2); else CWAC_LN_CASE(16, 3); else CWAC_LN_CASE(16, 4);
+  else return CWAC_E_SHAPE;
+#undef CWAC_LN_CASE
   return launch_status();
 }
 
