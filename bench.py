@@ -702,6 +702,23 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
     t_step = (time.perf_counter() - t0) / steps
     ms_block = e0.elapsed_time(e1) / steps
 
+    # the same call replayed from a HIP graph (nine kernel nodes)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            P.vit_block_w8a8_forward(blk.params, h, h_out, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    graph.replay()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_graph = e0.elapsed_time(e1) / steps
+
     t = vit_block.staged_forward(blk, h)
     L = blk.layers
     B = P.binding
@@ -768,6 +785,7 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
         "config": {"workload": f"ViT-B/16 block, {batch} images x {tokens} tokens, 12 heads x 64, MLP 3072, "
                                f"per-tensor int8 activations, binary16 residual stream"},
         "block_ms": round(ms_block, 4), "images_per_s": round(batch / (ms_block * 1e-3), 1),
+        "graph_replay_ms": round(ms_graph, 4),
         "linear_layers_us": round(lin_us, 1), "glue_us": round(glue_us, 1),
         "glue_share_of_stage_sum": round(glue_us / (glue_us + lin_us), 4),
         "roofline": {"bound": "mfma", "achieved": round(att["tflops"] / 1e3, 4), "peak": 2.5, "unit": "PFLOP/s",

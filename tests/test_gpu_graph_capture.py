@@ -158,3 +158,29 @@ def test_weight_only_and_convolution_replay_from_a_graph(monkeypatch):
         torch.cuda.synchronize()
         for a, b in zip(want, (out, outc, mult, fb, out8, outw)):
             assert torch.equal(a, b), f"replay {seed} differs from the eager step"
+
+
+def test_transformer_block_replays_from_a_graph():
+    """vit_block_w8a8_forward is nine kernel launches and nothing else."""
+    from paper_2505_20932_amd import vit_block
+    batch, tokens, heads, hidden = 4, 50, 2, 256
+    blk = vit_block.build_block(9, batch, tokens, heads, hidden, device=DEV)
+    h = vit_block.residual_stream(9, blk.m, blk.c, DEV)
+    h_out = torch.empty_like(h)
+    ws = torch.empty(P.vit_block_workspace(batch, tokens, heads, hidden), dtype=torch.int8, device=DEV)
+    P.vit_block_w8a8_forward(blk.params, h, h_out, ws)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        P.vit_block_w8a8_forward(blk.params, h, h_out, ws)
+    for seed in (10, 11, 12):
+        h.copy_(vit_block.residual_stream(seed, blk.m, blk.c, DEV))
+        P.vit_block_w8a8_forward(blk.params, h, h_out, ws)
+        torch.cuda.synchronize()
+        want, want_ws = h_out.clone(), ws.clone()
+        h_out.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(want, h_out) and torch.equal(want_ws, ws), f"replay {seed} differs from the eager call"
