@@ -226,6 +226,18 @@ cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w
                                  const float *s_x_row, int32_t out_kind, void *out, int64_t ldo,
                                  void *stream);
 
+/* qlinear_cwac_forward (CWAC_OUT_INT8, integer-offset epilogue of Eq. 10: no fbias, no per-row scales)
+ * followed by a 256-entry code table: out = table[r_q + 128].  An activation function between two
+ * int8 layers acts on one code at a time (vit_gelu_table builds the GELU's table), so it costs a
+ * byte read from LDS in the epilogue of large layers and no pass over the tensor; small layers run
+ * the forward and then a lookup pass in place.  Arguments as qlinear_cwac_forward, plus
+ *   table  device int8 [256], 4-byte aligned
+ *   n % 16 == 0; out 16-byte aligned, ldo % 16 == 0 */
+cwac_status qlinear_cwac_forward_table(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
+                                       int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
+                                       const float *mult, const int32_t *offset, const int8_t *table,
+                                       int8_t *out, int64_t ldo, void *stream);
+
 /* Quantized convolutional layer with the compensation in its epilogue: the CWAC
  * module that follows every quantized convolutional layer of a CNN (Sec. 3.3)
  * folds into it as into a linear layer (Sec. 3.4).  Implicit GEMM: row m = (b, oh,
@@ -442,7 +454,8 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
                                int32_t tokens, int32_t heads, float s_a, int32_t z_a, int8_t *a_q,
                                int64_t lda, void *stream);
 
-/* One whole block: the nine launches of the chain above on `stream`, from the residual stream h
+/* One whole block: the chain above in eight launches (the GELU table rides in fc1's epilogue where
+ * qlinear_cwac_forward_table fuses it) on `stream`, from the residual stream h
  * [batch * tokens, c] (c = 64 * heads, pitch c) to h_out (same shape; may not alias h).  Linear
  * layer i (0 qkv [3c, c], 1 proj [c, c], 2 fc1 [hidden, c], 3 fc2 [c, hidden]; weights int8
  * row-major [n, k], pitch k) runs qlinear_cwac_forward in CWAC_EPI_INT_OFFSET form with per-tensor
@@ -452,7 +465,7 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
  * workspace: device, vit_block_workspace(...) bytes, 16-byte aligned; after the call it holds, in
  * this order: x2 = Q(LN2(h1)) [m, c], r1 (qkv output) [m, 3c], r4 (fc2 output) [m, c],
  * g (GELU codes) [m, hidden] - exposed so that a caller can check every stage.
- * Errors: those of the nine calls; CWAC_E_WORKSPACE if workspace_bytes is too small. */
+ * Errors: those of the single calls; CWAC_E_WORKSPACE if workspace_bytes is too small. */
 typedef struct vit_block_layer {
   const int8_t *w_q;
   const float *mult;

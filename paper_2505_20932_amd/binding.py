@@ -30,7 +30,7 @@ EXPORTS = (
     "cwac_w4_quantize_groupwise", "cwac_w4_packed_w_bytes", "cwac_w4_pack",
     "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward", "qconv2d_cwac_forward",
     "vit_residual_ln_quant", "vit_gelu_table", "vit_table_lookup", "vit_attention_int8",
-    "vit_block_workspace", "vit_block_w8a8_forward",
+    "vit_block_workspace", "vit_block_w8a8_forward", "qlinear_cwac_forward_table",
 )
 
 
@@ -110,6 +110,7 @@ def lib() -> C.CDLL:
             "vit_table_lookup": (i32, [vp, i64, vp, vp, i64, i64, i32, vp]),
             "vit_attention_int8": (i32, [vp, i64, f32, i32, i32, i32, i32, f32, i32, vp, i64, vp]),
             "vit_block_workspace": (sz, [i32, i32, i32, i32]),
+            "qlinear_cwac_forward_table": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp, vp, vp, i64, vp]),
             "vit_block_w8a8_forward": (i32, [C.POINTER(vit_block_params), vp, vp, vp, sz, vp]),
         }
         for name, (res, args) in sig.items():
@@ -261,6 +262,19 @@ def qlinear_cwac_forward(x_q: torch.Tensor, w_q: torch.Tensor, qp: Optional[cwac
                                       k, C.byref(qp) if qp is not None else None, _ptr(mult),
                                       _ptr(offset), _ptr(fbias), _ptr(s_x_row), out_kind, _ptr(out),
                                       _rowmajor(out), _stream(stream)), "qlinear_cwac_forward")
+
+
+def qlinear_cwac_forward_table(x_q: torch.Tensor, w_q: torch.Tensor, qp: cwac_qparams, mult, offset,
+                               table: torch.Tensor, out: torch.Tensor, stream=None):
+    """int8 forward (integer-offset epilogue) with out = table[code + 128]."""
+    assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8 and out.dtype == torch.int8
+    assert table.dtype == torch.int8 and table.numel() == 256
+    m, k = x_q.shape
+    n, k2 = w_q.shape
+    assert k == k2 and out.shape == (m, n)
+    _check(lib().qlinear_cwac_forward_table(_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n, k,
+                                            C.byref(qp), _ptr(mult), _ptr(offset), _ptr(table), _ptr(out),
+                                            _rowmajor(out), _stream(stream)), "qlinear_cwac_forward_table")
 
 
 def cwac_calibrate_fused_workspace(m: int, n: int) -> int:

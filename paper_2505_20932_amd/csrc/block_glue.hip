@@ -552,8 +552,20 @@ cwac_status vit_block_w8a8_forward(const vit_block_params *bp, const uint16_t *h
   st = vit_residual_ln_quant(h, c, r_c, c, L[1].s_r, L[1].z_r, h_out, c, bp->ln2_gamma, bp->ln2_beta, bp->eps, L[2].s_x,
                              L[2].z_x, xq, c, m, c, stream);
   if (st != CWAC_OK) return st;
-  if ((st = linear(2, xq, hid, c, r_h)) != CWAC_OK) return st;
-  if ((st = vit_table_lookup(r_h, hid, bp->gelu_table, r_h, hid, m, hid, stream)) != CWAC_OK) return st;
+  {  // fc1 with the GELU table in its epilogue (large layers) or as a pass in place behind it
+    cwac_qparams qp;
+    qp.mode = CWAC_EPI_INT_OFFSET;
+    qp.act_per_token = 0;
+    qp.s_x = L[2].s_x;
+    qp.z_x = L[2].z_x;
+    qp.s_r = L[2].s_r;
+    qp.z_r = L[2].z_r;
+    qp.qmin = -128;
+    qp.qmax = 127;
+    st = qlinear_cwac_forward_table(xq, c, L[2].w_q, c, m, hid, c, &qp, L[2].mult, L[2].offset, bp->gelu_table, r_h,
+                                    hid, stream);
+    if (st != CWAC_OK) return st;
+  }
   if ((st = linear(3, r_h, c, hid, r_c)) != CWAC_OK) return st;
   // h2 = RN16(h1 + deq(r4)), in place over h1: every lane reads its own elements before it writes them
   return vit_residual_ln_quant(h_out, c, r_c, c, L[3].s_r, L[3].z_r, h_out, c, nullptr, nullptr, 0.0f, 1.0f, 0, nullptr,

@@ -40,6 +40,7 @@ struct FwdParams {
   // positions outside the image read cv_pad4 (the zero-point code in all four bytes)
   int cv_h, cv_w, cv_cin, cv_kw, cv_stride, cv_pad, cv_oh, cv_ow;
   int cv_pad4;
+  const int8_t *code_table;  // kOutTable: table[code + 128]
 };
 
 // Internal output kind of the large-problem kernel: nothing is stored but the per-channel sums
@@ -47,6 +48,9 @@ struct FwdParams {
 constexpr int kOutStats = 3;
 // Internal output kind: int8 codes through the integer-only epilogue (no floating point).
 constexpr int kOutFixed = 4;
+// Internal output kind: the int8 codes of the integer-offset epilogue mapped through a 256-entry code
+// table (an activation function between two int8 layers) before they are stored.
+constexpr int kOutTable = 5;
 
 // Integer-only requantization (fixed-point form of Eq. 10): the nearest integer to
 // t * m0 * 2^-shift, ties towards +infinity, exact in 64 bits (|t|, |m0| < 2^31, 1 <= shift <= 62),
@@ -213,6 +217,9 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 // Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 64, k % 64 == 0 (its 256 x 256
 // tile: n >= 256 and k % 128 == 0).
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st);
+// The integer-offset int8 forward with p.code_table applied to every output code (kOutTable); shapes as
+// launch_fast with n >= 256.
+cwac_status launch_fast_table(FwdParams p, hipStream_t st);
 // True where that kernel would take its 128-token tile shape (two workgroups per compute unit).
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);
 // True where it would take 128 x 128 tiles (layers with few tiles and a long K loop).

@@ -123,7 +123,7 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
     // streamed out: written normally they linger as dirty lines whose write-back then competes
     // with the reads of the statistics pass that follows
     // (int8 results stay cacheable for the layer that consumes them)
-    if (OUT_KIND != CWAC_OUT_INT8 && OUT_KIND != kOutFixed)
+    if (OUT_KIND != CWAC_OUT_INT8 && OUT_KIND != kOutFixed && OUT_KIND != kOutTable)
       __builtin_nontemporal_store(v, dst);
     else
       *dst = v;
@@ -135,7 +135,9 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[TA
                                               const float *s_mult, const float *s_fb,
                                               const float *s_rs, int64_t bm0, int bn0, int wave_m,
                                               int wave_n, int lane) {
-  constexpr bool I8 = OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed;  // packed int8 codes
+  constexpr bool I8 = OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed || OUT_KIND == kOutTable;  // packed int8 codes
+  // kOutTable: the code table sits in the (otherwise unused) fp-bias slot of the parameter block
+  const uint8_t *s_tab = reinterpret_cast<const uint8_t *>(s_fb);
   constexpr int ESZ = I8 ? 1 : 4;
   const int l32 = lane & 31, half = lane >> 5;
   const int wave = wave_m + WM * wave_n;
@@ -225,6 +227,7 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[TA
             // of (clamped + 1.5 * 2^23) are its rounded value in two's complement
             const float cl_u = __builtin_amdgcn_fmed3f(u[r], p.lo, p.hi);
             c[r] = __float_as_int(cl_u + magic) + p.zr;
+            if (OUT_KIND == kOutTable) c[r] = s_tab[(c[r] + 128) & 255];  // low byte of the sum: the code
           }
           if (VEC) {
             packed[g] = pack4(c[0], c[1], c[2], c[3]);
@@ -463,6 +466,8 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
   } else if (OUT_KIND != CWAC_OUT_INT32) {
     p_mult = p.mult[bn0 + ptid];
   }
+  if (OUT_KIND == kOutTable)  // 64 words of code table ride in the fp-bias slot (INT_ONLY: unused)
+    p_fb = __int_as_float(reinterpret_cast<const int32_t *>(p.code_table)[tid & 63]);
   if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32 && OUT_KIND != kOutFixed) {
     if (p.fbias) p_fb = p.fbias[bn0 + ptid];
     if (p.sx_row && tid < BM) p_rs = p.sx_row[bm0 + tid];
@@ -721,7 +726,7 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
                            wave_s, lane);
   } else {
     // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
-    constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed) ? 1 : 4;
+    constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed || OUT_KIND == kOutTable) ? 1 : 4;
     const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
     if (vs)
       fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
@@ -762,7 +767,23 @@ cwac_status launch_cfg(FwdParams p, int out_kind, bool int_only, hipStream_t st)
   return launch_one<BM, WM, BK, NSTAGE, NCHUNK, CWAC_OUT_INT32, false, CONV, BN, TA>(p, grid, st);
 }
 
+template <int BM, int WM, int BK, int NSTAGE>
+cwac_status launch_table_cfg(FwdParams p, hipStream_t st) {
+  p.tiles_m = (int)ceil_div(p.m, BM);
+  p.tiles_n = (int)ceil_div(p.n, 256);
+  const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
+  if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
+  return launch_one<BM, WM, BK, NSTAGE, 2, kOutTable, true>(p, dim3((unsigned)blocks), st);
+}
+
 }  // namespace
+
+cwac_status launch_fast_table(FwdParams p, hipStream_t st) {
+  p.vec_store = aligned(p.out, 16) && (p.ldo % 16) == 0;
+  // the same two tiles, by the same rule, as the plain int8 forward of a layer with n >= 256
+  if ((p.k % 128) != 0 || fast_prefers_half_tile(p.m, p.n, p.k, 1)) return launch_table_cfg<128, 2, 64, 3>(p, st);
+  return launch_table_cfg<256, 4, 128, 2>(p, st);
+}
 
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes) {
   // Cost model fitted to a sweep of 140 layer shapes per output width (microseconds per compute

@@ -297,6 +297,45 @@ extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, cons
   return dispatch_forward(p, out_kind, int_only, as_stream(stream));
 }
 
+extern "C" cwac_status qlinear_cwac_forward_table(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
+                                                  int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
+                                                  const float *mult, const int32_t *offset, const int8_t *table,
+                                                  int8_t *out, int64_t ldo, void *stream) {
+  if (!x_q || !w_q || !out || !qp || !mult || !table) return CWAC_E_NULL;
+  if (m < 1 || m > ((int64_t)1 << 40) || n < 16 || (n % 16) != 0 || k < 16 || k > 32768 || (k % 16) != 0)
+    return CWAC_E_SHAPE;
+  if (ldx < k || ldw < k || ldo < n) return CWAC_E_SHAPE;
+  if (qp->qmin < -128 || qp->qmax > 127 || qp->qmin > qp->qmax) return CWAC_E_SHAPE;
+  if (qp->z_r < -(1 << 20) || qp->z_r > (1 << 20)) return CWAC_E_SHAPE;
+  if (!aligned(x_q, 16) || !aligned(w_q, 16) || (ldx % 16) != 0 || (ldw % 16) != 0 || !aligned(out, 16) ||
+      (ldo % 16) != 0 || !aligned(table, 4))
+    return CWAC_E_ALIGN;
+  // Where the plain forward would take the direct-to-LDS kernel in one of its two large tiles, the table
+  // is applied in that kernel's epilogue; elsewhere the forward is followed by a lookup pass in place.
+  const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256), t_half = ceil_div(m, 128) * ceil_div(n, 256);
+  const bool fused_ok = m >= kFastTile && n >= kFastTile && (k % 64) == 0;
+  bool fused = fused_ok && !fast_prefers_quarter_tile(m, n);
+  if (fused) fused = (k % kFastKStep) == 0 ? (t256 >= 160 || fast_prefers_half_tile(m, n, k, 1)) : t_half >= 160;
+  // the testing knob of the plain forward: "fast" forces the fused form where its shape constraints
+  // hold, a forced generic tile means two passes
+  if (const char *e = getenv("CWAC_FWD_TILE")) fused = fused_ok && e[0] == 'f';
+  if (!fused) {
+    const cwac_status st = qlinear_cwac_forward(x_q, ldx, w_q, ldw, m, n, k, qp, mult, offset, nullptr, nullptr,
+                                                CWAC_OUT_INT8, out, ldo, stream);
+    if (st != CWAC_OK) return st;
+    return vit_table_lookup(out, ldo, table, out, ldo, m, n, stream);
+  }
+  FwdParams p = {};
+  p.x = x_q; p.w = w_q; p.ldx = ldx; p.ldw = ldw; p.ldo = ldo;
+  p.m = m; p.n = n; p.k = k;
+  p.mult = mult; p.offset = offset; p.out = out;
+  p.zr = qp->z_r;
+  p.lo = (float)(qp->qmin - qp->z_r);
+  p.hi = (float)(qp->qmax - qp->z_r);
+  p.code_table = table;
+  return launch_fast_table(p, as_stream(stream));
+}
+
 extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q, int32_t batch,
                                             int32_t h, int32_t w, int32_t c_in, int32_t c_out,
                                             int32_t kh, int32_t kw, int32_t stride, int32_t pad,

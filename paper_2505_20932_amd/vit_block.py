@@ -118,7 +118,7 @@ def build_block(seed: int, batch: int, tokens: int, heads: int, hidden: int, dev
 
 
 def staged_forward(blk: Block, h: torch.Tensor) -> Dict[str, torch.Tensor]:
-    """The same nine launches as ``vit_block_w8a8_forward`` through the single entry points, every
+    """The steps of ``vit_block_w8a8_forward`` one entry point at a time (fc1 and the GELU table apart), every
     intermediate kept: x1, r1, a, r2, h1, x2, r3, g, r4, h2."""
     m, c, hid, dev = blk.m, blk.c, blk.hidden, h.device
     L = blk.layers

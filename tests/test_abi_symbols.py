@@ -220,3 +220,9 @@ def test_argument_errors_of_the_block_glue_entry_points(lib):
     assert at(a, 192, 1.0, 200, 1, 16, 1, 1.0, 0, a, 64, null) == -4  # zero-point outside int8
     assert at(a, 196, 1.0, 0, 1, 16, 1, 1.0, 0, a, 64, null) == -3    # ld % 8
     assert at(a, 192, 1.0, 0, 1, 16, 1, 1.0, 0, C.c_void_p(4104), 64, null) == -3
+    ft = lib.qlinear_cwac_forward_table
+    qp = binding.make_qparams()
+    assert ft(a, 64, a, 64, 256, 256, 64, C.byref(qp), a, null, null, a, 256, null) == -1     # no table
+    assert ft(a, 64, a, 64, 256, 250, 64, C.byref(qp), a, null, a, a, 256, null) == -2        # n % 16
+    assert ft(a, 64, a, 64, 256, 256, 64, C.byref(qp), a, null, a, a, 264, null) == -3        # ldo % 16
+    assert ft(a, 64, a, 64, 256, 256, 64, C.byref(qp), a, null, C.c_void_p(4098), a, 256, null) == -3

@@ -291,7 +291,7 @@ def _run_block(orc, seed, batch, tokens, heads, hidden, rows):
     h_out = torch.empty_like(h)
     P.vit_block_w8a8_forward(b.params, h, h_out, ws)
     torch.cuda.synchronize()
-    # the chained entry point is the same nine launches: bit-identical results, documented workspace
+    # the chained entry point computes the same steps: bit-identical results, documented workspace
     m, c = b.m, b.c
     assert torch.equal(h_out, t["h2"])
     assert torch.equal(ws[:m * c].view(m, c), t["x2"])
@@ -333,3 +333,49 @@ def test_block_argument_errors():
         P.vit_block_w8a8_forward(b.params, h, h, ws)            # in place
     with pytest.raises(P.CwacError):
         P.vit_block_w8a8_forward(b.params, h, torch.empty_like(h), ws[:100])
+
+
+# ------------------------------------------------------------------ forward with a code table in its epilogue
+@pytest.mark.parametrize("m,n,k,force", [
+    (4096, 3072, 768, False),     # fused, 128-token tile pairs
+    (16384, 1024, 1024, False),   # fused, 256-token tile
+    (20001, 768, 768, False),     # fused, ragged last row tile
+    (9000, 2048, 192, False),     # fused, K a multiple of 64 only
+    (300, 256, 128, False),       # too small: forward, then a lookup pass in place
+    (1000, 48, 64, False),        # narrow: two passes
+    (256, 256, 64, True), (1000, 512, 192, True), (777, 1024, 128, True), (513, 272, 256, True),
+])
+def test_forward_with_code_table(m, n, k, force, monkeypatch):
+    """out = table[forward + 128], bit for bit, against the plain forward (itself checked against the
+    oracle in test_gpu_parity.py) followed by numpy indexing."""
+    print(f"forward with code table {m} x {n} x {k}, forced {force}", flush=True)
+    rng = np.random.default_rng(m + n + k)
+    x = torch.from_numpy(rng.integers(-128, 128, (m, k)).astype(np.int8)).to(DEV)
+    w = torch.from_numpy(rng.integers(-127, 128, (n, k)).astype(np.int8)).to(DEV)
+    mult = torch.from_numpy((rng.uniform(0.5, 1.5, n) * 40.0 / (74.0 * 73.0 * np.sqrt(k))).astype(np.float32)).to(DEV)
+    offset = torch.from_numpy(rng.integers(-2000, 2000, n).astype(np.int32)).to(DEV)
+    table = rng.permutation(256).astype(np.uint8).view(np.int8)   # a bijection: every code is told apart
+    qp = P.make_qparams(z_r=-7)
+    plain = torch.empty(m, n, dtype=torch.int8, device=DEV)
+    P.qlinear_cwac_forward(x, w, qp, mult, offset, None, None, P.CWAC_OUT_INT8, plain)
+    full = torch.full((m, n + 16), 33, dtype=torch.int8, device=DEV)
+    if force:
+        monkeypatch.setenv("CWAC_FWD_TILE", "fast")
+    P.qlinear_cwac_forward_table(x, w, qp, mult, offset, _dev(table), full[:, :n])
+    torch.cuda.synchronize()
+    codes = plain.cpu().numpy()
+    assert np.unique(codes).size > 100                      # the codes spread over the range
+    np.testing.assert_array_equal(full[:, :n].cpu().numpy(), table[codes.astype(int) + 128])
+    assert (full[:, n:] == 33).all()
+
+
+def test_forward_with_code_table_argument_errors():
+    x = torch.zeros(256, 64, dtype=torch.int8, device=DEV)
+    w = torch.zeros(256, 64, dtype=torch.int8, device=DEV)
+    mult = torch.ones(256, device=DEV)
+    tab = torch.zeros(256, dtype=torch.int8, device=DEV)
+    out = torch.empty(256, 264, dtype=torch.int8, device=DEV)
+    with pytest.raises(P.CwacError):
+        P.qlinear_cwac_forward_table(x, w[:250], P.make_qparams(), mult, None, tab, out[:, :250])   # n % 16
+    with pytest.raises(P.CwacError):
+        P.qlinear_cwac_forward_table(x, w, P.make_qparams(), mult, None, tab, out[:, 8:264])   # misaligned out

@@ -161,7 +161,7 @@ def test_weight_only_and_convolution_replay_from_a_graph(monkeypatch):
 
 
 def test_transformer_block_replays_from_a_graph():
-    """vit_block_w8a8_forward is nine kernel launches and nothing else."""
+    """vit_block_w8a8_forward is kernel launches and nothing else."""
     from paper_2505_20932_amd import vit_block
     batch, tokens, heads, hidden = 4, 50, 2, 256
     blk = vit_block.build_block(9, batch, tokens, heads, hidden, device=DEV)
