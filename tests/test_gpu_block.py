@@ -237,7 +237,7 @@ def _check_block_stages(orc, bk, h, t, rows):
     d_ln = lambda v: 64 * U32 * (np.abs(v) + 128) + 1e-4  # noqa: E731
 
     # x1 = Q(LN1(h))
-    _, v = blk_quant(blk_ln(h_np[rows], ln[0], ln[1], bk.eps), L[0]["s_x"], L[0]["z_x"])
+    _, v = blk.quantize(blk.layernorm(h_np[rows], ln[0], ln[1], bk.eps), L[0]["s_x"], L[0]["z_x"])
     assert _codes_within(cpu["x1"][rows], v, d_ln(v)) > 0.99
     # the four linear layers: fold and folded forward of the main oracle, bit-exact
     for i, (x, r) in enumerate((("x1", "r1"), ("a", "r2"), ("x2", "r3"), ("g", "r4"))):
@@ -253,33 +253,29 @@ def _check_block_stages(orc, bk, h, t, rows):
     images = np.unique(rows // tok)
     for b in images:
         sl = slice(b * tok, (b + 1) * tok)
-        o, mag = blk_attn(cpu["r1"][sl], np.float32(L[0]["s_r"]), L[0]["z_r"], 1, tok, bk.heads)
+        o, mag = blk.attention_codes(cpu["r1"][sl], np.float32(L[0]["s_r"]), L[0]["z_r"], 1, tok, bk.heads)
         s_a = np.float32(L[1]["s_x"])
-        _, v = blk_quant(o, s_a, L[1]["z_x"])
+        _, v = blk.quantize(o, s_a, L[1]["z_x"])
         delta = (2.0 ** -11 + 1024 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
         _codes_within(cpu["a"][sl], v, delta)
     # h1 = RN16(h + deq(r2)), x2 = Q(LN2(h1))
-    want16, tt = blk_res(h_np[rows], cpu["r2"][rows], np.float32(L[1]["s_r"]), L[1]["z_r"])
+    want16, tt = blk.residual(h_np[rows], cpu["r2"][rows], np.float32(L[1]["s_r"]), L[1]["z_r"])
     slack = 2 * U32 * (np.abs(h_np[rows].astype(np.float64)) + np.abs(tt)) + 1e-30
     g16 = cpu["h1"][rows].astype(np.float64)
     assert ((g16 >= (tt - slack).astype(np.float16)) & (g16 <= (tt + slack).astype(np.float16))).all()
-    _, v = blk_quant(blk_ln(cpu["h1"][rows], ln[2], ln[3], bk.eps), L[2]["s_x"], L[2]["z_x"])
+    _, v = blk.quantize(blk.layernorm(cpu["h1"][rows], ln[2], ln[3], bk.eps), L[2]["s_x"], L[2]["z_x"])
     assert _codes_within(cpu["x2"][rows], v, d_ln(v)) > 0.99
     # g = table[r3]
-    want_tab, v = blk_table(np.float32(L[2]["s_r"]), L[2]["z_r"], np.float32(L[3]["s_x"]), L[3]["z_x"])
+    want_tab, v = blk.gelu_table(np.float32(L[2]["s_r"]), L[2]["z_r"], np.float32(L[3]["s_x"]), L[3]["z_x"])
     got_tab = bk.gelu_table.cpu().numpy()
     tie = np.abs(v - np.floor(v) - 0.5) < 1e-9
     np.testing.assert_array_equal(got_tab[~tie], want_tab[~tie])
     np.testing.assert_array_equal(cpu["g"][rows], got_tab[cpu["r3"][rows].astype(int) + 128])
     # h2 = RN16(h1 + deq(r4))
-    _, tt = blk_res(cpu["h1"][rows], cpu["r4"][rows], np.float32(L[3]["s_r"]), L[3]["z_r"])
+    _, tt = blk.residual(cpu["h1"][rows], cpu["r4"][rows], np.float32(L[3]["s_r"]), L[3]["z_r"])
     slack = 2 * U32 * (np.abs(cpu["h1"][rows].astype(np.float64)) + np.abs(tt)) + 1e-30
     g16 = cpu["h2"][rows].astype(np.float64)
     assert ((g16 >= (tt - slack).astype(np.float16)) & (g16 <= (tt + slack).astype(np.float16))).all()
-
-
-blk_ln, blk_quant, blk_attn, blk_res, blk_table = (blk.layernorm, blk.quantize, blk.attention_codes, blk.residual,
-                                                   blk.gelu_table)
 
 
 def _run_block(orc, seed, batch, tokens, heads, hidden, rows):

@@ -181,9 +181,9 @@ def test_residual_rounds_once_to_binary16():
     codes = np.array([[3, 1, -4, 0]], dtype=np.int8)
     s, z = 2.0 ** -12, -1
     out, t = blk.residual(h, codes, s, z)
-    # 1 + 4 * 2^-12 = 1 + 2^-10 (representable); 2048 + 2 * 2^-12 rounds back to 2048;
-    # -0.5 - 3 * 2^-12 is a multiple of the spacing 2^-11 below 0.5 ... in [0.5, 1) the spacing is 2^-11:
-    # 3 * 2^-12 = 1.5 * 2^-11 is a tie between 1 and 2 spacings -> even (2): -0.5 - 2^-10
+    # deq = 2^-12 * (code + 1).  1 + 4 * 2^-12 = 1 + 2^-10 is representable; 2048 + 2^-11 rounds back to 2048;
+    # -0.5 - 3 * 2^-12 sits in [0.5, 1), spacing 2^-11: 1.5 spacings below -0.5, a tie, goes to the even
+    # neighbour -0.5 - 2^-10; 1 + 2^-12 is a quarter of the spacing 2^-10 above 1 and rounds to 1
     np.testing.assert_array_equal(t, [[1 + 2.0 ** -10, 2048 + 2.0 ** -11, -0.5 - 3 * 2.0 ** -12, 1 + 2.0 ** -12]])
     np.testing.assert_array_equal(out.astype(np.float64),
                                   [[1 + 2.0 ** -10, 2048.0, -0.5 - 2.0 ** -10, 1.0]])
