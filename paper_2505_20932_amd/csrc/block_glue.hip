@@ -22,6 +22,7 @@ namespace cwac {
 namespace {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -33,8 +34,6 @@ __device__ __forceinline__ float group_sum(float v) {
   for (int off = LPR / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
   return v;
 }
-
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 
 // Four int8 codes (one word) -> (code - z) as four binary16 values, exactly: a byte u = code + 128 under
 // the high byte 0x64 is the binary16 number 1024 + u, and (1024 + u) - (1152 + z) is an integer below

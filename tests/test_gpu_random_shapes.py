@@ -170,3 +170,66 @@ def test_weight_only_random_shape(m, n, k):
             os.environ.pop("CWAC_W4_PIPE", None)
         np.testing.assert_array_equal(out.cpu().numpy(), o32)
         np.testing.assert_array_equal(outh.cpu().numpy().view(np.uint16), o16.view(np.uint16))
+
+
+# ------------------------------------------------------------------ Transformer-block glue
+def _ln_shapes():
+    rng = np.random.default_rng(77)
+    shapes = [(int(rng.integers(1, 300)), 8 * int(rng.integers(1, 257))) for _ in range(16)]
+    # channel counts on either side of the lanes-per-row choices (16, 32, 64 lanes x 1..4 vectors)
+    return shapes + [(7, 8), (7, 128), (7, 136), (7, 384), (7, 392), (7, 512), (7, 520), (7, 768), (7, 776),
+                     (7, 1024), (7, 1032), (7, 1536), (7, 1544), (7, 2048), (1, 640), (64, 16)]
+
+
+@pytest.mark.parametrize("m,c", _ln_shapes())
+def test_residual_ln_quant_random_shape(m, c):
+    from oracle import block_oracle as blk
+    print(f"residual + layer norm + quantizer {m} x {c}", flush=True)
+    rng = np.random.default_rng(m * 4099 + c)
+    h = (rng.standard_normal((m, c)) * 2).astype(np.float16)
+    r = rng.integers(-128, 128, (m, c)).astype(np.int8)
+    gamma = (1 + 0.2 * rng.standard_normal(c)).astype(np.float32)
+    beta = (0.1 * rng.standard_normal(c)).astype(np.float32)
+    s_r, z_r, s_x, z_x = np.float32(0.02), -3, np.float32(0.025), 9
+    h1 = torch.empty(m, c, dtype=torch.float16, device=DEV)
+    xq = torch.empty(m, c, dtype=torch.int8, device=DEV)
+    P.vit_residual_ln_quant(dev(h), dev(r), float(s_r), z_r, h1, dev(gamma), dev(beta), 1e-5, float(s_x), z_x, xq)
+    torch.cuda.synchronize()
+    want16, t = blk.residual(h, r, s_r, z_r)
+    got16 = h1.cpu().numpy()
+    slack = 2 * 2.0 ** -24 * (np.abs(h.astype(np.float64)) + np.abs(t)) + 1e-30
+    g = got16.astype(np.float64)
+    assert ((g >= (t - slack).astype(np.float16)) & (g <= (t + slack).astype(np.float16))).all()
+    _, v = blk.quantize(blk.layernorm(g, gamma, beta, 1e-5), s_x, z_x)
+    delta = 64 * 2.0 ** -24 * (np.abs(v) + 128) + 1e-4
+    lo, hi = np.clip(np.rint(v - delta), -128, 127), np.clip(np.rint(v + delta), -128, 127)
+    got = xq.cpu().numpy().astype(np.float64)
+    assert ((got >= lo) & (got <= hi)).all()
+
+
+def _attention_shapes():
+    rng = np.random.default_rng(78)
+    shapes = [(int(rng.integers(1, 4)), int(rng.integers(1, 225)), int(rng.integers(1, 5))) for _ in range(10)]
+    return shapes + [(1, 32, 1), (1, 31, 1), (1, 96, 1), (1, 97, 1), (1, 192, 1), (1, 223, 1), (2, 224, 2)]
+
+
+@pytest.mark.parametrize("batch,tokens,heads", _attention_shapes())
+def test_attention_random_shape(batch, tokens, heads):
+    from oracle import block_oracle as blk
+    print(f"attention {batch} x {tokens} x {heads}", flush=True)
+    rng = np.random.default_rng(batch * 100000 + tokens * 100 + heads)
+    c = 64 * heads
+    r = np.clip(np.rint(rng.standard_normal((batch * tokens, 3 * c)) * 35 - 6), -128, 127).astype(np.int8)
+    s, z = np.float32(0.035), -6
+    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads)
+    s_a = np.float32(max(float(o.max() - o.min()), 1e-6) / 255.0)
+    z_a = int(np.clip(round(-128 - float(o.min()) / float(s_a)), -128, 127))
+    a = torch.empty(batch * tokens, c, dtype=torch.int8, device=DEV)
+    P.vit_attention_int8(dev(r), float(s), z, batch, tokens, heads, float(s_a), z_a, a)
+    torch.cuda.synchronize()
+    _, v = blk.quantize(o, s_a, z_a)
+    delta = (2.0 ** -11 + 1024 * 2.0 ** -24) * mag / s_a + 64 * 2.0 ** -24 * (np.abs(v) + 128) + 1e-4
+    lo, hi = np.clip(np.rint(v - delta), -128, 127), np.clip(np.rint(v + delta), -128, 127)
+    got = a.cpu().numpy().astype(np.float64)
+    assert ((got >= lo) & (got <= hi)).all()
+    assert (got == np.clip(np.rint(v), -128, 127)).mean() > 0.85
