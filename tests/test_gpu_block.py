@@ -312,6 +312,12 @@ def test_block_chain_other_shapes(orc):
     _run_block(orc, 4, 5, 50, 2, 256, np.arange(250))
 
 
+@pytest.mark.parametrize("heads,hidden,name", [(6, 1536, "ViT-S"), (16, 4096, "ViT-L"), (20, 5120, "ViT-H")])
+def test_block_other_model_widths(orc, heads, hidden, name):
+    print(f"block: {name}, 2 images x 197 tokens, {heads} heads, MLP {hidden}", flush=True)
+    _run_block(orc, 7 + heads, 2, 197, heads, hidden, np.arange(0, 394, 3))
+
+
 def test_block_full_size_sampled(orc):
     """ViT-B/16: 128 images x 197 tokens, 12 heads, MLP 3072 - the launch configuration the benchmark's
     block section times; the oracle checks three images' rows."""
