@@ -185,12 +185,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
 }
 
 // Stage 2: fixed-order sum over row groups, added into the state; the first batch also
-// records the pivots (row 0 of that batch).  One workgroup per (statistic, 64 channels):
-// wavefront w sums row groups w, w+16, ... and the 16 wave sums are combined in order.
+// records the pivots (row 0 of that batch).  One workgroup of W wavefronts per (statistic, 64
+// channels): wavefront w sums row groups w, w + W, ... (eight loads in flight per lane) and the W
+// wave sums are combined in order.  W follows the number of row groups (1 for the few groups of a
+// wide layer: no LDS, no barrier - the kernel is then one load latency long).
 // The last workgroup to finish bumps the row count: every workgroup reads the count before
 // it takes its ticket, so none can see the new value.
 constexpr int kMergeWaves = 16;
-__global__ __launch_bounds__(kMergeWaves *kWave) void stats_merge_kernel(
+template <int W>
+__global__ __launch_bounds__(W *kWave) void stats_merge_kernel(
     const double *__restrict__ partial, int row_blocks, int c_out, const float *__restrict__ yf,
     const float *__restrict__ yq, void *stats, int64_t n_rows) {
   const int groups = (c_out + kWave - 1) / kWave;
@@ -204,21 +207,27 @@ __global__ __launch_bounds__(kMergeWaves *kWave) void stats_merge_kernel(
     const double *src = partial + (int64_t)s * c_out + ch;
     const int64_t step = (int64_t)kStats * c_out;
     int rb = w;
-    for (; rb + 3 * kMergeWaves < row_blocks; rb += 4 * kMergeWaves) {
-      const double a0 = src[(int64_t)rb * step], a1 = src[(int64_t)(rb + kMergeWaves) * step],
-                   a2 = src[(int64_t)(rb + 2 * kMergeWaves) * step],
-                   a3 = src[(int64_t)(rb + 3 * kMergeWaves) * step];
-      t += a0; t += a1; t += a2; t += a3;
-    }
-    for (; rb < row_blocks; rb += kMergeWaves) t += src[(int64_t)rb * step];
-  }
-  __shared__ double red[kMergeWaves][kWave];
-  red[w][lane] = t;
-  __syncthreads();
-  if (w == 0 && ch < c_out) {
-    double total = red[0][lane];
+    for (; rb + 7 * W < row_blocks; rb += 8 * W) {
+      double a[8];
 #pragma unroll
-    for (int i = 1; i < kMergeWaves; ++i) total += red[i][lane];
+      for (int j = 0; j < 8; ++j) a[j] = src[(int64_t)(rb + j * W) * step];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) t += a[j];
+    }
+    for (; rb < row_blocks; rb += W) t += src[(int64_t)rb * step];
+  }
+  double total = t;
+  if (W > 1) {
+    __shared__ double red[W][kWave];
+    red[w][lane] = t;
+    __syncthreads();
+    if (w == 0) {
+      total = red[0][lane];
+#pragma unroll
+      for (int i = 1; i < W; ++i) total += red[i][lane];
+    }
+  }
+  if (w == 0 && ch < c_out) {
     const int i = s * c_out + ch;
     sv.sum[i] = first ? total : sv.sum[i] + total;
     if (first && s == 0) {
@@ -226,7 +235,7 @@ __global__ __launch_bounds__(kMergeWaves *kWave) void stats_merge_kernel(
       sv.pivot_f[ch] = yf[ch];
     }
   }
-  __syncthreads();
+  if (W > 1) __syncthreads();
   if (threadIdx.x == 0) {
     // no fence needed: this workgroup's read of the count has already returned its value, and
     // its sums only have to be visible at the end of the kernel
@@ -317,8 +326,15 @@ __global__ __launch_bounds__(256) void solve_kernel(const void *stats, int c_out
 cwac_status launch_stats_merge(const double *partial, int row_groups, int c_out,
                                const float *pivot_f_src, const float *pivot_q_src, void *stats,
                                int64_t n_rows, hipStream_t st) {
-  stats_merge_kernel<<<(unsigned)(kStats * ceil_div(c_out, kWave)), kMergeWaves * kWave, 0, st>>>(
-      partial, row_groups, c_out, pivot_f_src, pivot_q_src, stats, n_rows);
+  const unsigned grid = (unsigned)(kStats * ceil_div(c_out, kWave));
+  if (row_groups <= 32)
+    stats_merge_kernel<1><<<grid, kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src, pivot_q_src, stats, n_rows);
+  else if (row_groups <= 128)
+    stats_merge_kernel<4><<<grid, 4 * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src, pivot_q_src, stats,
+                                                      n_rows);
+  else
+    stats_merge_kernel<kMergeWaves><<<grid, kMergeWaves * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src,
+                                                                          pivot_q_src, stats, n_rows);
   return launch_status();
 }
 
