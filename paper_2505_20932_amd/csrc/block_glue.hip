@@ -6,8 +6,8 @@
 //
 // Arithmetic, in fp32 unless stated (no contraction: each line is one rounding):
 //   residual   t = h + s_r * (float)(c - z_r);  h1 = RN16(t);  the layer norm reads h1
-//   layer norm mean = sum(x) / C;  var = sum((x - mean)^2) / C;  y = (x - mean) * (1 / sqrt(var + eps)) * gamma + beta
-//   quantizer  code = clip(rne(y * (1 / s) + z), -128, 127)                             (Eq. 1)
+//   layer norm mean = sum(x) * (1 / C);  var = sum((x - mean)^2) * (1 / C);  y = fma((x - mean) * rsq(var + eps), gamma, beta)
+//   quantizer  code = clip(rne(fma(y, 1 / s, z)), -128, 127)                            (Eq. 1)
 //   attention  S = (K - z)(Q - z)^T exactly (integers below 2^24 in the fp32 MFMA accumulators);
 //              P = 1024 p = exp2(fma(S, s^2 / sqrt(d) * log2 e, 10 - that * max S));  O = (sum_j RN16(P_j) (V_j - z)) * s / sum_j P_j,
 //              keys taken in groups of 96 with the running maximum (earlier partial sums rescaled)
@@ -51,17 +51,17 @@ __device__ __forceinline__ h8 codes_to_h8(uint2 c, h2 bias) {
   return h8{a[0], a[1], b[0], b[1], d[0], d[1], e[0], e[1]};
 }
 
-// Eq. 1 with the division by the scale as a multiplication by its fp32 reciprocal (one rounding
-// more than a division: far inside what decides a code only at a tie).
+// Eq. 1 with the division by the scale as a fused multiply-add with its fp32 reciprocal (the
+// reciprocal's rounding instead of the division's: far inside what decides a code only at a tie).
 __device__ __forceinline__ int quant_code(float y, float inv_s, float zf) {
-  const float v = y * inv_s + zf;
+  const float v = __builtin_fmaf(y, inv_s, zf);
   return (int)__builtin_amdgcn_fmed3f(rintf(v), -128.0f, 127.0f);
 }
 
 // ------------------------------------------------------------------------------------------
 // Residual add + layer norm + quantizer: LPR (16, 32 or 64) lanes per token row, the row in
 // registers (NV vectors of 8 channels per lane: C <= 8 * LPR * NV; the host picks the pair that
-// leaves the fewest idle lanes, e.g. 32 x 3 for C = 768), two-pass mean / variance, no LDS.
+// leaves the fewest idle lanes, e.g. 32 x 3 for C = 768), two-pass mean / variance; LDS holds gamma and beta only.
 // HBM bytes per element: 2 (h) [+ 1 (codes) + 2 (h1)] + 1 (x_q).
 // ------------------------------------------------------------------------------------------
 struct LnParams {
@@ -74,7 +74,7 @@ struct LnParams {
   _Float16 *h_out;
   int64_t ldho;
   const float *gamma, *beta;
-  float eps, s_x;
+  float eps, inv_s_x, inv_c;  // 1 / s_x and 1 / c, rounded once on the host
   int z_x;
   int8_t *x_q;
   int64_t ldxq;
@@ -82,88 +82,109 @@ struct LnParams {
   int c;
 };
 
-template <int LPR, int NV>
+// FULL: every lane's every vector is inside the row (C = 8 * LPR * NV): no masks.
+template <int LPR, int NV, bool FULL>
 __global__ __launch_bounds__(256) void residual_ln_quant_kernel(const LnParams p) {
   const int lane = threadIdx.x & (LPR - 1);  // position inside the row's group of LPR lanes
-  int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
-  // lane groups past the end read the last row and store nothing: the shuffles below then always run
-  // with every lane active (h_out may be h itself, so such a group must not store)
-  const bool live = row < p.m;
-  if (!live) row = p.m - 1;
   const int nvec = p.c >> 3;
-  float x[NV][8];
+  // A lane group walks rows first, first + stride, ...; the loads of its next row are in flight while it
+  // reduces and quantizes the current one.  Groups past the end read the last row and store nothing: the
+  // shuffles then always run with every lane active, and the trip count is uniform over the workgroup
+  // (h_out may be h itself, so such a group must not store).
+  const int64_t stride = (int64_t)gridDim.x * (256 / LPR);
+  int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+  const int64_t block_row0 = (int64_t)blockIdx.x * (256 / LPR);
+  struct Raw {
+    h8 hv[NV];
+    uint2 cw[NV];
+  };
+  auto load = [&](Raw &r, int64_t at) {
+    if (at > p.m - 1) at = p.m - 1;
 #pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    const int v = lane + LPR * j;
-    if (v < nvec) {
-      const h8 hv = *reinterpret_cast<const h8 *>(p.h + row * p.ldh + 8 * v);
+    for (int j = 0; j < NV; ++j) {
+      const int v = (FULL || lane + LPR * j < nvec) ? lane + LPR * j : 0;
+      r.hv[j] = *reinterpret_cast<const h8 *>(p.h + at * p.ldh + 8 * v);
+      if (p.r) r.cw[j] = *reinterpret_cast<const uint2 *>(p.r + at * p.ldr + 8 * v);
+    }
+  };
+  // gamma and beta are the same for every row: staged once per workgroup in LDS (c <= 2048)
+  __shared__ __attribute__((aligned(16))) float s_gamma[2048], s_beta[2048];
+  if (p.x_q) {
+    for (int i = threadIdx.x; i < p.c; i += 256) {
+      s_gamma[i] = p.gamma[i];
+      s_beta[i] = p.beta[i];
+    }
+  }
+  __syncthreads();
+  const float zf = (float)p.z_x, inv_s = p.inv_s_x;
+  Raw cur, nxt;
+  load(cur, row);
+  for (int64_t base = block_row0; base < p.m; base += stride, row += stride) {
+    const bool more = base + stride < p.m;  // uniform over the workgroup
+    if (more) load(nxt, row + stride);
+    const bool live = row < p.m;
+    const int64_t at = live ? row : p.m - 1;
+    float x[NV][8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[j][e] = (float)hv[e];
+    for (int j = 0; j < NV; ++j) {
+      const int v = lane + LPR * j;
+      const bool ok = FULL || v < nvec;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[j][e] = ok ? (float)cur.hv[j][e] : 0.0f;
       if (p.r) {
-        const uint2 cw = *reinterpret_cast<const uint2 *>(p.r + row * p.ldr + 8 * v);
         h8 ho;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const uint32_t w = e < 4 ? cw.x : cw.y;
+          const uint32_t w = e < 4 ? cur.cw[j].x : cur.cw[j].y;
           const int code = (int)(int8_t)(w >> (8 * (e & 3)));
           const float t = x[j][e] + p.s_r * (float)(code - p.z_r);
           ho[e] = (_Float16)t;
-          x[j][e] = (float)ho[e];
+          x[j][e] = ok ? (float)ho[e] : 0.0f;
         }
-        if (p.h_out && live) *reinterpret_cast<h8 *>(p.h_out + row * p.ldho + 8 * v) = ho;
+        if (p.h_out && live && ok) *reinterpret_cast<h8 *>(p.h_out + at * p.ldho + 8 * v) = ho;
       }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[j][e] = 0.0f;
     }
-  }
-  if (!p.x_q) return;
-  // gamma and beta of this lane's channels, requested before the reductions need the row
-  float4 gb[NV][4];
+    if (p.x_q) {
+      float s = 0.0f;
 #pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    const int v = lane + LPR * j < nvec ? lane + LPR * j : 0;
-    gb[j][0] = *reinterpret_cast<const float4 *>(p.gamma + 8 * v);
-    gb[j][1] = *reinterpret_cast<const float4 *>(p.gamma + 8 * v + 4);
-    gb[j][2] = *reinterpret_cast<const float4 *>(p.beta + 8 * v);
-    gb[j][3] = *reinterpret_cast<const float4 *>(p.beta + 8 * v + 4);
-  }
-  float s = 0.0f;
+      for (int j = 0; j < NV; ++j)
 #pragma unroll
-  for (int j = 0; j < NV; ++j)
+        for (int e = 0; e < 8; ++e) s += x[j][e];
+      const float mean = group_sum<LPR>(s) * p.inv_c;
+      float ss = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s += x[j][e];
-  const float mean = group_sum<LPR>(s) / (float)p.c;
-  float ss = 0.0f;
+      for (int j = 0; j < NV; ++j) {
+        const bool ok = FULL || lane + LPR * j < nvec;
 #pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    const bool ok = lane + LPR * j < nvec;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float d = ok ? x[j][e] - mean : 0.0f;
-      x[j][e] = d;
-      ss += d * d;
-    }
-  }
-  const float var = group_sum<LPR>(ss) / (float)p.c;
-  const float rstd = 1.0f / sqrtf(var + p.eps);
-  const float zf = (float)p.z_x, inv_s = 1.0f / p.s_x;
-#pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    const int v = lane + LPR * j;
-    if (v < nvec) {
-      const float4 g0 = gb[j][0], g1 = gb[j][1], b0 = gb[j][2], b1 = gb[j][3];
-      const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-      const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-      uint32_t w[2] = {0u, 0u};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float y = x[j][e] * rstd * g[e] + b[e];
-        const int code = quant_code(y, inv_s, zf);
-        w[e >> 2] |= (uint32_t)(code & 0xff) << (8 * (e & 3));
+        for (int e = 0; e < 8; ++e) {
+          const float d = ok ? x[j][e] - mean : 0.0f;
+          x[j][e] = d;
+          ss += d * d;
+        }
       }
-      if (live) *reinterpret_cast<uint2 *>(p.x_q + row * p.ldxq + 8 * v) = make_uint2(w[0], w[1]);
+      const float var = group_sum<LPR>(ss) * p.inv_c;
+      const float rstd = __builtin_amdgcn_rsqf(var + p.eps);  // 1 ulp
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        const int v = lane + LPR * j;
+        const int vs = (FULL || v < nvec) ? v : 0;
+        const float4 g0 = *reinterpret_cast<const float4 *>(s_gamma + 8 * vs),
+                     g1 = *reinterpret_cast<const float4 *>(s_gamma + 8 * vs + 4),
+                     b0 = *reinterpret_cast<const float4 *>(s_beta + 8 * vs),
+                     b1 = *reinterpret_cast<const float4 *>(s_beta + 8 * vs + 4);
+        const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+        uint32_t w[2] = {0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float y = __builtin_fmaf(x[j][e] * rstd, g[e], b[e]);
+          const int code = quant_code(y, inv_s, zf);
+          w[e >> 2] |= (uint32_t)(code & 0xff) << (8 * (e & 3));
+        }
+        if (live && (FULL || v < nvec)) *reinterpret_cast<uint2 *>(p.x_q + at * p.ldxq + 8 * v) = make_uint2(w[0], w[1]);
+      }
     }
+    if (more) cur = nxt;
   }
 }
 
@@ -427,7 +448,8 @@ cwac_status vit_residual_ln_quant(const uint16_t *h, int64_t ldh, const int8_t *
   p.gamma = gamma;
   p.beta = beta;
   p.eps = eps;
-  p.s_x = s_x;
+  p.inv_s_x = x_q ? 1.0f / s_x : 1.0f;
+  p.inv_c = 1.0f / (float)c;
   p.z_x = z_x;
   p.x_q = x_q;
   p.ldxq = ldxq;
@@ -440,14 +462,24 @@ cwac_status vit_residual_ln_quant(const uint16_t *h, int64_t ldh, const int8_t *
     const int cnv = (nvec + cand - 1) / cand;
     if (cnv <= 4 && cnv * cand < nv * lpr) lpr = cand, nv = cnv;
   }
-  const dim3 grid((unsigned)ceil_div(m, 256 / lpr));
+  // at most 8 workgroups per compute unit: beyond that a lane group walks several rows
+  int64_t blocks = ceil_div(m, 256 / lpr);
+  if (blocks > 2048) blocks = 2048;
+  const dim3 grid((unsigned)blocks);
   hipStream_t st = as_stream(stream);
-#define CWAC_LN_CASE(L, N) \
-  if (lpr == L && nv == N) residual_ln_quant_kernel<L, N><<<grid, 256, 0, st>>>(p)
-  CWAC_LN_CASE(64, 1); else CWAC_LN_CASE(64, 2); else CWAC_LN_CASE(64, 3); else CWAC_LN_CASE(64, 4);
-  else CWAC_LN_CASE(32, 1); else CWAC_LN_CASE(32, 2); else CWAC_LN_CASE(32, 3); else CWAC_LN_CASE(32, 4);
-  else CWAC_LN_CASE(16, 1); else CWAC_LN_CASE(16, 2); else CWAC_LN_CASE(16, 3); else CWAC_LN_CASE(16, 4);
+#define CWAC_LN_CASE(L, N)                                                                     \
+  if (lpr == L && nv == N) {                                                                   \
+    if (nvec == L * N)                                                                         \
+      residual_ln_quant_kernel<L, N, true><<<grid, 256, 0, st>>>(p);                           \
+    else                                                                                       \
+      residual_ln_quant_kernel<L, N, false><<<grid, 256, 0, st>>>(p);                          \
+  }
+  // clang-format off
+  CWAC_LN_CASE(64, 1) else CWAC_LN_CASE(64, 2) else CWAC_LN_CASE(64, 3) else CWAC_LN_CASE(64, 4)
+  else CWAC_LN_CASE(32, 1) else CWAC_LN_CASE(32, 2) else CWAC_LN_CASE(32, 3) else CWAC_LN_CASE(32, 4)
+  else CWAC_LN_CASE(16, 1) else CWAC_LN_CASE(16, 2) else CWAC_LN_CASE(16, 3) else CWAC_LN_CASE(16, 4)
   else return CWAC_E_SHAPE;
+  // clang-format on
 #undef CWAC_LN_CASE
   return launch_status();
 }
