@@ -185,25 +185,29 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
 }
 
 // Stage 2: fixed-order sum over row groups, added into the state; the first batch also
-// records the pivots (row 0 of that batch).  One workgroup of W wavefronts per (statistic, 64
-// channels): wavefront w sums row groups w, w + W, ... (eight loads in flight per lane) and the W
-// wave sums are combined in order.  W follows the number of row groups (1 for the few groups of a
-// wide layer: no LDS, no barrier - the kernel is then one load latency long).
+// records the pivots (row 0 of that batch).  A task = (statistic, 64 channels); a workgroup holds G
+// tasks of W wavefronts each: wavefront w of a task sums row groups w, w + W, ... (eight loads in
+// flight per lane) and the W wave sums are combined in order.  W follows the number of row groups;
+// G keeps the workgroups few, because each ends with one ticket on a single counter and those
+// serialize (960 tickets cost as much as the rest of the kernel).
 // The last workgroup to finish bumps the row count: every workgroup reads the count before
 // it takes its ticket, so none can see the new value.
-constexpr int kMergeWaves = 16;
-template <int W>
-__global__ __launch_bounds__(W *kWave) void stats_merge_kernel(
+template <int W, int G>
+__global__ __launch_bounds__(W *G *kWave) void stats_merge_kernel(
     const double *__restrict__ partial, int row_blocks, int c_out, const float *__restrict__ yf,
     const float *__restrict__ yq, void *stats, int64_t n_rows) {
   const int groups = (c_out + kWave - 1) / kWave;
-  const int s = blockIdx.x / groups, cg = blockIdx.x - s * groups;
-  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int g = wave / W, w = wave % W;
+  const int task = blockIdx.x * G + g;
+  const bool has_task = task < kStats * groups;
+  const int s = has_task ? task / groups : 0, cg = has_task ? task - s * groups : 0;
   const int ch = cg * kWave + lane;
+  const bool active = has_task && ch < c_out;
   const StatsView sv = stats_view(stats, c_out);
   const bool first = (*sv.n == 0);
   double t = 0.0;
-  if (ch < c_out) {
+  if (active) {
     const double *src = partial + (int64_t)s * c_out + ch;
     const int64_t step = (int64_t)kStats * c_out;
     int rb = w;
@@ -218,16 +222,16 @@ __global__ __launch_bounds__(W *kWave) void stats_merge_kernel(
   }
   double total = t;
   if (W > 1) {
-    __shared__ double red[W][kWave];
-    red[w][lane] = t;
+    __shared__ double red[G][W][kWave];
+    red[g][w][lane] = t;
     __syncthreads();
     if (w == 0) {
-      total = red[0][lane];
+      total = red[g][0][lane];
 #pragma unroll
-      for (int i = 1; i < W; ++i) total += red[i][lane];
+      for (int i = 1; i < W; ++i) total += red[g][i][lane];
     }
   }
-  if (w == 0 && ch < c_out) {
+  if (w == 0 && active) {
     const int i = s * c_out + ch;
     sv.sum[i] = first ? total : sv.sum[i] + total;
     if (first && s == 0) {
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(W *kWave) void stats_merge_kernel(
       sv.pivot_f[ch] = yf[ch];
     }
   }
-  if (W > 1) __syncthreads();
+  __syncthreads();
   if (threadIdx.x == 0) {
     // no fence needed: this workgroup's read of the count has already returned its value, and
     // its sums only have to be visible at the end of the kernel
@@ -326,15 +330,16 @@ __global__ __launch_bounds__(256) void solve_kernel(const void *stats, int c_out
 cwac_status launch_stats_merge(const double *partial, int row_groups, int c_out,
                                const float *pivot_f_src, const float *pivot_q_src, void *stats,
                                int64_t n_rows, hipStream_t st) {
-  const unsigned grid = (unsigned)(kStats * ceil_div(c_out, kWave));
+  const int tasks = (int)(kStats * ceil_div(c_out, kWave));
   if (row_groups <= 32)
-    stats_merge_kernel<1><<<grid, kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src, pivot_q_src, stats, n_rows);
+    stats_merge_kernel<1, 8><<<(unsigned)ceil_div(tasks, 8), 8 * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src,
+                                                                             pivot_q_src, stats, n_rows);
   else if (row_groups <= 128)
-    stats_merge_kernel<4><<<grid, 4 * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src, pivot_q_src, stats,
-                                                      n_rows);
+    stats_merge_kernel<4, 4><<<(unsigned)ceil_div(tasks, 4), 16 * kWave, 0, st>>>(partial, row_groups, c_out,
+                                                                              pivot_f_src, pivot_q_src, stats, n_rows);
   else
-    stats_merge_kernel<kMergeWaves><<<grid, kMergeWaves * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src,
-                                                                          pivot_q_src, stats, n_rows);
+    stats_merge_kernel<16, 1><<<(unsigned)tasks, 16 * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src,
+                                                                      pivot_q_src, stats, n_rows);
   return launch_status();
 }
 
