@@ -369,6 +369,24 @@ def test_stats_generic_layout_and_hard_channels(orc):
     _check_moments(mom4[:, :ch], ref)
 
 
+@pytest.mark.parametrize("rows,ch", [(60000, 64), (20000, 1024), (3000, 4096), (2500, 200), (40000, 1000)])
+def test_stats_merge_every_width(orc, rows, ch):
+    """Row-group counts on either side of the merge kernel's widths (235, 78, 12, 10 and 157 partial sums per
+    channel) and channel counts that leave tasks of the last merge workgroup empty."""
+    print(f"statistics {rows} x {ch}", flush=True)
+    yq = synth.normal(83 + ch, 0, rows * ch).numpy().reshape(rows, ch).astype(np.float32)
+    e = synth.normal(83 + ch, 1, rows * ch).numpy().reshape(rows, ch)
+    yf = (0.9 * yq - 0.1 + 0.1 * e).astype(np.float32)
+    ref = orc.channel_moments(yf, yq)
+    a0, b0, _ = orc.solve(ref)
+    alpha, beta, mom, ndeg, _ = _stats(dev(yf), dev(yq), splits=(rows // 3,))
+    _check_moments(mom, ref)
+    assert ndeg == 0
+    sf = np.sqrt(ref[4])
+    assert np.max(np.abs(alpha - a0) / np.maximum(np.abs(a0), 1.0)) <= RTOL
+    assert np.max(np.abs(beta - b0) / np.maximum(np.abs(b0), sf)) <= RTOL
+
+
 def test_stats_empty_state_and_single_row(orc):
     ch = 8
     st = torch.empty(P.cwac_stats_bytes(ch) // 8 + 2, dtype=torch.float64, device=DEV)
