@@ -676,7 +676,7 @@ def conv_section(P, synth, torch, dev: str, batch: int, steps: int, cpu_batch: i
 
 
 
-def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_images: int):
+def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_images: int, n_blocks: int = 12):
     """One W8A8 Vision Transformer block (ViT-B/16: 197 tokens, 12 heads, MLP 3072) from residual
     stream to residual stream: the four compensated linear layers (Sec. 3.4) chained with the
     non-linear glue that per-layer compensation steps around (Sec. 3.2).  A step = one call of
@@ -718,6 +718,22 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
     e1.record()
     torch.cuda.synchronize()
     ms_graph = e0.elapsed_time(e1) / steps
+
+    # a stack of n_blocks such blocks in one call (ViT-B/16's encoder is 12): between two blocks the last
+    # residual of one and the LN1 + quantizer of the next are one pass; the stream is updated in place
+    stack = [blk] + [vit_block.build_block(100 + i, batch, tokens, heads, hidden, device=dev)
+                     for i in range(1, n_blocks)]
+    stack_params = [b.params for b in stack]
+    hs = h.clone()
+    for _ in range(2):
+        P.vit_encoder_w8a8_forward(stack_params, h, hs, ws)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        P.vit_encoder_w8a8_forward(stack_params, h, hs, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_stack = e0.elapsed_time(e1) / steps
 
     t = vit_block.staged_forward(blk, h)
     L = blk.layers
@@ -790,6 +806,10 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
                                f"per-tensor int8 activations, binary16 residual stream"},
         "block_ms": round(ms_block, 4), "images_per_s": round(batch / (ms_block * 1e-3), 1),
         "graph_replay_ms": round(ms_graph, 4),
+        "encoder_stack": {"blocks": n_blocks, "ms": round(ms_stack, 4), "ms_per_block": round(ms_stack / n_blocks, 4),
+                          "images_per_s": round(batch / (ms_stack * 1e-3), 1),
+                          "linear_layer_tops": round(n_blocks * 2.0 * m * c * (3 * c + c + 2 * hidden)
+                                                     / (ms_stack * 1e-3) / 1e12, 1)},
         "linear_layers_us": round(lin_us, 1), "glue_us": round(glue_us, 1),
         "glue_share_of_stage_sum": round(glue_us / (glue_us + lin_us), 4),
         "fc1_then_table_lookup_pass_us": round(unfused_us, 1),
@@ -904,6 +924,7 @@ def main():
                     help="the Transformer-block section instead: one ViT-B/16 block, linear layers chained "
                          "with the non-linear glue (its own JSON line)")
     ap.add_argument("--block-batch", type=int, default=128)
+    ap.add_argument("--blocks", type=int, default=12, help="depth of the stack timed beside the single block")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -926,7 +947,7 @@ def main():
         return
     if args.block:
         print(json.dumps(block_section(P, torch, dev, args.block_batch, args.steps, args.warmup,
-                                       0 if args.no_cpu_baseline else 2)))
+                                       0 if args.no_cpu_baseline else 2, args.blocks)))
         return
     wl = synth.WORKLOADS[args.config]
     cal_rows = args.cal_rows or wl.m

@@ -456,7 +456,7 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
 
 /* One whole block: the chain above in eight launches (the GELU table rides in fc1's epilogue where
  * qlinear_cwac_forward_table fuses it) on `stream`, from the residual stream h
- * [batch * tokens, c] (c = 64 * heads, pitch c) to h_out (same shape; may not alias h).  Linear
+ * [batch * tokens, c] (c = 64 * heads, pitch c) to h_out (same shape; may be h itself).  Linear
  * layer i (0 qkv [3c, c], 1 proj [c, c], 2 fc1 [hidden, c], 3 fc2 [c, hidden]; weights int8
  * row-major [n, k], pitch k) runs qlinear_cwac_forward in CWAC_EPI_INT_OFFSET form with per-tensor
  * activations: mult / offset are cwac_fold's, (s_x, z_x) its input quantizer - which is the
@@ -485,6 +485,13 @@ typedef struct vit_block_params {
 } vit_block_params;
 
 size_t vit_block_workspace(int32_t batch, int32_t tokens, int32_t heads, int32_t hidden);
+/* A stack of n_blocks blocks of one shape (blocks[b].batch / tokens / heads / hidden all equal;
+ * CWAC_E_SHAPE otherwise), block b + 1 reading what block b wrote.  Between two blocks the last residual
+ * add of one and the LN1 + quantizer of the next are one pass over the stream.  The same workspace
+ * (vit_block_workspace bytes) serves every block; h_out may be h. */
+cwac_status vit_encoder_w8a8_forward(const vit_block_params *blocks /* host, [n_blocks] */, int32_t n_blocks,
+                                     const uint16_t *h, uint16_t *h_out, void *workspace,
+                                     size_t workspace_bytes, void *stream);
 cwac_status vit_block_w8a8_forward(const vit_block_params *params /* host */, const uint16_t *h,
                                    uint16_t *h_out, void *workspace, size_t workspace_bytes,
                                    void *stream);

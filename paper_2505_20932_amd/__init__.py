@@ -18,5 +18,5 @@ from .binding import (  # noqa: F401
     CWAC_OUT_FP16, CWAC_W4_GROUP, cwac_w4_quantize_groupwise, cwac_w4_packed_w_bytes, cwac_w4_pack,
     cwac_fold_weight_only, qlinear_w4a16_cwac_forward, qconv2d_cwac_forward,
     vit_residual_ln_quant, vit_gelu_table, vit_table_lookup, vit_attention_int8,
-    qlinear_cwac_forward_table, vit_block_workspace, vit_block_w8a8_forward, vit_block_params, vit_block_layer, make_block_params,
+    qlinear_cwac_forward_table, vit_block_workspace, vit_block_w8a8_forward, vit_encoder_w8a8_forward, vit_block_params, vit_block_layer, make_block_params,
 )

@@ -31,6 +31,7 @@ EXPORTS = (
     "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward", "qconv2d_cwac_forward",
     "vit_residual_ln_quant", "vit_gelu_table", "vit_table_lookup", "vit_attention_int8",
     "vit_block_workspace", "vit_block_w8a8_forward", "qlinear_cwac_forward_table",
+    "vit_encoder_w8a8_forward",
 )
 
 
@@ -112,6 +113,7 @@ def lib() -> C.CDLL:
             "vit_block_workspace": (sz, [i32, i32, i32, i32]),
             "qlinear_cwac_forward_table": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp, vp, vp, i64, vp]),
             "vit_block_w8a8_forward": (i32, [C.POINTER(vit_block_params), vp, vp, vp, sz, vp]),
+            "vit_encoder_w8a8_forward": (i32, [C.POINTER(vit_block_params), i32, vp, vp, vp, sz, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
@@ -461,6 +463,17 @@ def vit_block_w8a8_forward(bp: vit_block_params, h: torch.Tensor, h_out: torch.T
     _check(lib().vit_block_w8a8_forward(C.byref(bp), _ptr(h), _ptr(h_out), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)),
            "vit_block_w8a8_forward")
+
+
+def vit_encoder_w8a8_forward(blocks, h: torch.Tensor, h_out: torch.Tensor, workspace: torch.Tensor,
+                             stream=None):
+    """blocks: a sequence of vit_block_params of one shape; h_out may be h."""
+    assert h.dtype == torch.float16 and h_out.dtype == torch.float16 and h.is_contiguous() and h_out.is_contiguous()
+    arr = (vit_block_params * len(blocks))(*blocks)
+    assert h.shape == h_out.shape == (arr[0].batch * arr[0].tokens, 64 * arr[0].heads)
+    _check(lib().vit_encoder_w8a8_forward(arr, len(blocks), _ptr(h), _ptr(h_out), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+           "vit_encoder_w8a8_forward")
 
 
 # --------------------------------------------------------------------------- diagnostic

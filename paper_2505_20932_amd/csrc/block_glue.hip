@@ -541,24 +541,33 @@ size_t vit_block_workspace(int32_t batch, int32_t tokens, int32_t heads, int32_t
   return m * (5 * c + (size_t)hidden);
 }
 
-cwac_status vit_block_w8a8_forward(const vit_block_params *bp, const uint16_t *h, uint16_t *h_out, void *workspace,
-                                   size_t workspace_bytes, void *stream) {
-  if (!bp || !h || !h_out || !workspace || !bp->gelu_table) return CWAC_E_NULL;
+}  // extern "C"
+
+namespace {
+
+cwac_status check_block(const vit_block_params *bp) {
+  if (!bp->gelu_table || !bp->ln1_gamma || !bp->ln1_beta || !bp->ln2_gamma || !bp->ln2_beta) return CWAC_E_NULL;
   if (bp->batch < 1 || bp->tokens < 1 || bp->heads < 1 || bp->heads > 64 || bp->hidden < 16 || bp->hidden % 16 != 0)
     return CWAC_E_SHAPE;
-  if (h == h_out) return CWAC_E_MODE;
   for (int i = 0; i < 4; ++i)
     if (!bp->layer[i].w_q || !bp->layer[i].mult || !bp->layer[i].offset) return CWAC_E_NULL;
-  if (workspace_bytes < vit_block_workspace(bp->batch, bp->tokens, bp->heads, bp->hidden)) return CWAC_E_WORKSPACE;
-  if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
+  return CWAC_OK;
+}
+
+// One block.  x1_ready: the workspace already holds x1 = Q(LN1(h)) (the block before produced it with its
+// last residual); next: the block that follows, whose LN1 and input quantizer then ride on this block's
+// last residual pass.  h_out may be h: every kernel that writes the stream reads, in the same lanes, only
+// the elements it writes, and the stream is otherwise read by earlier launches only.
+cwac_status run_block(const vit_block_params *bp, bool x1_ready, const vit_block_params *next, const uint16_t *h,
+                      uint16_t *h_out, void *workspace, void *stream) {
   const int64_t m = (int64_t)bp->batch * bp->tokens;
   const int32_t c = bp->heads * kHeadDim, hid = bp->hidden;
-  int8_t *xq = static_cast<int8_t *>(workspace);  // x1, then the attention output, then x2
+  int8_t *xq = static_cast<int8_t *>(workspace);  // x1, then the attention output, then x2 (then the next x1)
   int8_t *r_qkv = xq + m * c;
   int8_t *r_c = r_qkv + m * 3 * c;  // proj output, then fc2 output
-  int8_t *r_h = r_c + m * c;        // fc1 output, then the GELU codes in place
+  int8_t *r_h = r_c + m * c;        // GELU codes (fc1's output through the table)
   const vit_block_layer *L = bp->layer;
-  auto linear = [&](int i, const int8_t *x, int32_t n, int32_t k, int8_t *out) {
+  auto params = [&](int i) {
     cwac_qparams qp;
     qp.mode = CWAC_EPI_INT_OFFSET;
     qp.act_per_token = 0;
@@ -568,13 +577,19 @@ cwac_status vit_block_w8a8_forward(const vit_block_params *bp, const uint16_t *h
     qp.z_r = L[i].z_r;
     qp.qmin = -128;
     qp.qmax = 127;
+    return qp;
+  };
+  auto linear = [&](int i, const int8_t *x, int32_t n, int32_t k, int8_t *out) {
+    const cwac_qparams qp = params(i);
     return qlinear_cwac_forward(x, k, L[i].w_q, k, m, n, k, &qp, L[i].mult, L[i].offset, nullptr, nullptr, CWAC_OUT_INT8,
                                 out, n, stream);
   };
   cwac_status st;
-  st = vit_residual_ln_quant(h, c, nullptr, 0, 0.0f, 0, nullptr, 0, bp->ln1_gamma, bp->ln1_beta, bp->eps, L[0].s_x,
-                             L[0].z_x, xq, c, m, c, stream);
-  if (st != CWAC_OK) return st;
+  if (!x1_ready) {
+    st = vit_residual_ln_quant(h, c, nullptr, 0, 0.0f, 0, nullptr, 0, bp->ln1_gamma, bp->ln1_beta, bp->eps, L[0].s_x,
+                               L[0].z_x, xq, c, m, c, stream);
+    if (st != CWAC_OK) return st;
+  }
   if ((st = linear(0, xq, 3 * c, c, r_qkv)) != CWAC_OK) return st;
   st = vit_attention_int8(r_qkv, 3 * c, L[0].s_r, L[0].z_r, bp->batch, bp->tokens, bp->heads, L[1].s_x, L[1].z_x, xq, c,
                           stream);
@@ -584,23 +599,49 @@ cwac_status vit_block_w8a8_forward(const vit_block_params *bp, const uint16_t *h
                              L[2].z_x, xq, c, m, c, stream);
   if (st != CWAC_OK) return st;
   {  // fc1 with the GELU table in its epilogue (large layers) or as a pass in place behind it
-    cwac_qparams qp;
-    qp.mode = CWAC_EPI_INT_OFFSET;
-    qp.act_per_token = 0;
-    qp.s_x = L[2].s_x;
-    qp.z_x = L[2].z_x;
-    qp.s_r = L[2].s_r;
-    qp.z_r = L[2].z_r;
-    qp.qmin = -128;
-    qp.qmax = 127;
+    const cwac_qparams qp = params(2);
     st = qlinear_cwac_forward_table(xq, c, L[2].w_q, c, m, hid, c, &qp, L[2].mult, L[2].offset, bp->gelu_table, r_h,
                                     hid, stream);
     if (st != CWAC_OK) return st;
   }
   if ((st = linear(3, r_h, c, hid, r_c)) != CWAC_OK) return st;
-  // h2 = RN16(h1 + deq(r4)), in place over h1: every lane reads its own elements before it writes them
+  // h2 = RN16(h1 + deq(r4)) in place over h1, with the next block's x1 = Q(LN1(h2)) in the same pass
+  if (next)
+    return vit_residual_ln_quant(h_out, c, r_c, c, L[3].s_r, L[3].z_r, h_out, c, next->ln1_gamma, next->ln1_beta,
+                                 next->eps, next->layer[0].s_x, next->layer[0].z_x, xq, c, m, c, stream);
   return vit_residual_ln_quant(h_out, c, r_c, c, L[3].s_r, L[3].z_r, h_out, c, nullptr, nullptr, 0.0f, 1.0f, 0, nullptr,
                                0, m, c, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+cwac_status vit_block_w8a8_forward(const vit_block_params *bp, const uint16_t *h, uint16_t *h_out, void *workspace,
+                                   size_t workspace_bytes, void *stream) {
+  return vit_encoder_w8a8_forward(bp, 1, h, h_out, workspace, workspace_bytes, stream);
+}
+
+cwac_status vit_encoder_w8a8_forward(const vit_block_params *blocks, int32_t n_blocks, const uint16_t *h,
+                                     uint16_t *h_out, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!blocks || !h || !h_out || !workspace) return CWAC_E_NULL;
+  if (n_blocks < 1) return CWAC_E_SHAPE;
+  for (int b = 0; b < n_blocks; ++b) {
+    const cwac_status st = check_block(blocks + b);
+    if (st != CWAC_OK) return st;
+    if (blocks[b].batch != blocks[0].batch || blocks[b].tokens != blocks[0].tokens ||
+        blocks[b].heads != blocks[0].heads || blocks[b].hidden != blocks[0].hidden)
+      return CWAC_E_SHAPE;
+  }
+  if (workspace_bytes < vit_block_workspace(blocks[0].batch, blocks[0].tokens, blocks[0].heads, blocks[0].hidden))
+    return CWAC_E_WORKSPACE;
+  if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
+  for (int b = 0; b < n_blocks; ++b) {
+    const cwac_status st = run_block(blocks + b, b > 0, b + 1 < n_blocks ? blocks + b + 1 : nullptr, b == 0 ? h : h_out,
+                                     h_out, workspace, stream);
+    if (st != CWAC_OK) return st;
+  }
+  return CWAC_OK;
 }
 
 }  // extern "C"

@@ -226,3 +226,7 @@ def test_argument_errors_of_the_block_glue_entry_points(lib):
     assert ft(a, 64, a, 64, 256, 250, 64, C.byref(qp), a, null, a, a, 256, null) == -2        # n % 16
     assert ft(a, 64, a, 64, 256, 256, 64, C.byref(qp), a, null, a, a, 264, null) == -3        # ldo % 16
     assert ft(a, 64, a, 64, 256, 256, 64, C.byref(qp), a, null, C.c_void_p(4098), a, 256, null) == -3
+    assert lib.vit_encoder_w8a8_forward(null, 1, a, a, a, 1 << 30, null) == -1
+    bp = binding.vit_block_params()
+    assert lib.vit_encoder_w8a8_forward(C.byref(bp), 0, a, a, a, 1 << 30, null) == -2   # no blocks
+    assert lib.vit_encoder_w8a8_forward(C.byref(bp), 1, a, a, a, 1 << 30, null) == -1   # empty parameter block

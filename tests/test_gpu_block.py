@@ -326,13 +326,40 @@ def test_block_full_size_sampled(orc):
     _run_block(orc, 5, 128, 197, 12, 3072, rows)
 
 
+def test_encoder_stack_equals_block_by_block():
+    """Three blocks in one call (the residual of one block and the LN1 + quantizer of the next in one pass)
+    against three single-block calls; then the same in place over the residual stream."""
+    from paper_2505_20932_amd import vit_block
+    batch, tokens, heads, hidden = 6, 197, 3, 768
+    blocks = [vit_block.build_block(20 + i, batch, tokens, heads, hidden, device=DEV) for i in range(3)]
+    h = vit_block.residual_stream(20, batch * tokens, 64 * heads, DEV)
+    ws = torch.empty(P.vit_block_workspace(batch, tokens, heads, hidden), dtype=torch.int8, device=DEV)
+    a, b = h.clone(), torch.empty_like(h)
+    for blk_ in blocks:
+        P.vit_block_w8a8_forward(blk_.params, a, b, ws)
+        a, b = b, a
+    torch.cuda.synchronize()
+    want = a.clone()
+    assert not torch.equal(want, h)
+    out = torch.empty_like(h)
+    P.vit_encoder_w8a8_forward([x.params for x in blocks], h, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+    inplace = h.clone()
+    P.vit_encoder_w8a8_forward([x.params for x in blocks], inplace, inplace, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(inplace, want)
+    # blocks of different shapes do not stack
+    other = vit_block.build_block(30, batch, tokens, heads, 512, device=DEV)
+    with pytest.raises(P.CwacError):
+        P.vit_encoder_w8a8_forward([blocks[0].params, other.params], h, out, ws)
+
+
 def test_block_argument_errors():
     from paper_2505_20932_amd import vit_block
     b = vit_block.build_block(6, 1, 16, 1, 64, device=DEV)
     h = vit_block.residual_stream(6, 16, 64, DEV)
     ws = torch.empty(P.vit_block_workspace(1, 16, 1, 64), dtype=torch.int8, device=DEV)
-    with pytest.raises(P.CwacError):
-        P.vit_block_w8a8_forward(b.params, h, h, ws)            # in place
     with pytest.raises(P.CwacError):
         P.vit_block_w8a8_forward(b.params, h, torch.empty_like(h), ws[:100])
 
