@@ -408,8 +408,8 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
  * Transformer block around the linear layers of Sec. 3.4 (int8 codes in, int8 codes out, Eq. 10):
  *   x1 = Q(LN1(h))  r1 = qkv(x1)  a = Q(MHSA(deq(r1)))  r2 = proj(a)  h1 = RN16(h + deq(r2))
  *   x2 = Q(LN2(h1)) r3 = fc1(x2)  g = Q(GELU(deq(r3)))  r4 = fc2(g)   h2 = RN16(h1 + deq(r4))
- * Q(y) = clip(rne(y / s + z), -128, 127) (Eq. 1), deq(c) = s * (c - z); the residual stream h is
- * IEEE binary16.  All pointers are device pointers owned by the caller; work is enqueued on
+ * Q(y) = clip(rne(y / s + z), -128, 127) (Eq. 1; evaluated in fp32 as one fused multiply-add with the
+ * rounded reciprocal of s), deq(c) = s * (c - z); the residual stream h is IEEE binary16.  All pointers are device pointers owned by the caller; work is enqueued on
  * `stream`; argument errors are returned before anything is launched. */
 
 /* Residual add, layer normalization and quantizer of one row-major [m, c] tensor, any subset
