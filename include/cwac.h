@@ -441,22 +441,23 @@ cwac_status vit_gelu_table(float s_in, int32_t z_in, float s_out, int32_t z_out,
 cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *table, int8_t *out,
                              int64_t ld_out, int64_t m, int32_t n, void *stream);
 
-/* Multi-head self-attention on the requantized output of the qkv layer, head width 64:
- *   r_qkv  int8 [batch * tokens, 3 * c], c = 64 * heads, row = (q | k | v), head h in columns
- *          [64 h, 64 h + 64) of each third; pitch ld (ld % 8 == 0, base 8-byte aligned);
+/* Multi-head self-attention on the requantized output of the qkv layer, head width d = head_dim (64 or 32):
+ *   r_qkv  int8 [batch * tokens, 3 * c], c = d * heads, row = (q | k | v), head h in columns
+ *          [d h, d h + d) of each third; pitch ld (ld % 8 == 0, base 8-byte aligned);
  *          quantization parameters (s, z) of the whole tensor
- *   a_q    int8 [batch * tokens, c] = Q(softmax(q k^T / 8) v; s_a, z_a) per image and head;
+ *   a_q    int8 [batch * tokens, c] = Q(softmax(q k^T / sqrt(d)) v; s_a, z_a) per image and head;
  *          pitch lda (lda % 16 == 0, base 16-byte aligned)
  *   1 <= tokens <= 224 (one workgroup holds a head's keys and values), heads <= 64
+ * "image" is whatever attends within itself: an image of a ViT, a window of a windowed model.
  * Scores are exact (integers in fp32 accumulators), the softmax is fp32, the weights meet the
  * values as binary16 (relative error 2^-11 per term), accumulation in fp32. */
 cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t z, int32_t batch,
-                               int32_t tokens, int32_t heads, float s_a, int32_t z_a, int8_t *a_q,
-                               int64_t lda, void *stream);
+                               int32_t tokens, int32_t heads, int32_t head_dim, float s_a, int32_t z_a,
+                               int8_t *a_q, int64_t lda, void *stream);
 
 /* One whole block: the chain above in eight launches (the GELU table rides in fc1's epilogue where
  * qlinear_cwac_forward_table fuses it) on `stream`, from the residual stream h
- * [batch * tokens, c] (c = 64 * heads, pitch c) to h_out (same shape; may be h itself).  Linear
+ * [batch * tokens, c] (c = head_dim * heads, pitch c) to h_out (same shape; may be h itself).  Linear
  * layer i (0 qkv [3c, c], 1 proj [c, c], 2 fc1 [hidden, c], 3 fc2 [c, hidden]; weights int8
  * row-major [n, k], pitch k) runs qlinear_cwac_forward in CWAC_EPI_INT_OFFSET form with per-tensor
  * activations: mult / offset are cwac_fold's, (s_x, z_x) its input quantizer - which is the
@@ -482,8 +483,10 @@ typedef struct vit_block_params {
   const float *ln1_gamma, *ln1_beta, *ln2_gamma, *ln2_beta;
   vit_block_layer layer[4];
   const int8_t *gelu_table;
+  int32_t head_dim; /* 64 or 32; 0 means 64 */
 } vit_block_params;
 
+/* Bytes of workspace of a block; sized for head width 64 (a block of 32-wide heads needs less). */
 size_t vit_block_workspace(int32_t batch, int32_t tokens, int32_t heads, int32_t hidden);
 /* A stack of n_blocks blocks of one shape (blocks[b].batch / tokens / heads / hidden all equal;
  * CWAC_E_SHAPE otherwise), block b + 1 reading what block b wrote.  Between two blocks the last residual

@@ -50,7 +50,7 @@ class vit_block_params(C.Structure):
     _fields_ = [("batch", C.c_int32), ("tokens", C.c_int32), ("heads", C.c_int32), ("hidden", C.c_int32),
                 ("eps", C.c_float), ("ln1_gamma", C.c_void_p), ("ln1_beta", C.c_void_p),
                 ("ln2_gamma", C.c_void_p), ("ln2_beta", C.c_void_p), ("layer", vit_block_layer * 4),
-                ("gelu_table", C.c_void_p)]
+                ("gelu_table", C.c_void_p), ("head_dim", C.c_int32)]
 
 
 class CwacError(RuntimeError):
@@ -109,7 +109,7 @@ def lib() -> C.CDLL:
                                             vp, i64, i64, i32, vp]),
             "vit_gelu_table": (i32, [f32, i32, f32, i32, vp, vp]),
             "vit_table_lookup": (i32, [vp, i64, vp, vp, i64, i64, i32, vp]),
-            "vit_attention_int8": (i32, [vp, i64, f32, i32, i32, i32, i32, f32, i32, vp, i64, vp]),
+            "vit_attention_int8": (i32, [vp, i64, f32, i32, i32, i32, i32, i32, f32, i32, vp, i64, vp]),
             "vit_block_workspace": (sz, [i32, i32, i32, i32]),
             "qlinear_cwac_forward_table": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp, vp, vp, i64, vp]),
             "vit_block_w8a8_forward": (i32, [C.POINTER(vit_block_params), vp, vp, vp, sz, vp]),
@@ -428,10 +428,11 @@ def vit_table_lookup(x: torch.Tensor, table: torch.Tensor, out: torch.Tensor, st
 
 
 def vit_attention_int8(r_qkv: torch.Tensor, s: float, z: int, batch: int, tokens: int, heads: int,
-                       s_a: float, z_a: int, a_q: torch.Tensor, stream=None):
+                       s_a: float, z_a: int, a_q: torch.Tensor, head_dim: int = 64, stream=None):
     assert r_qkv.dtype == torch.int8 and a_q.dtype == torch.int8
-    assert r_qkv.shape == (batch * tokens, 3 * 64 * heads) and a_q.shape == (batch * tokens, 64 * heads)
-    _check(lib().vit_attention_int8(_ptr(r_qkv), _rowmajor(r_qkv), s, z, batch, tokens, heads, s_a, z_a,
+    c = head_dim * heads
+    assert r_qkv.shape == (batch * tokens, 3 * c) and a_q.shape == (batch * tokens, c)
+    _check(lib().vit_attention_int8(_ptr(r_qkv), _rowmajor(r_qkv), s, z, batch, tokens, heads, head_dim, s_a, z_a,
                                     _ptr(a_q), _rowmajor(a_q), _stream(stream)), "vit_attention_int8")
 
 
@@ -439,7 +440,8 @@ def vit_block_workspace(batch: int, tokens: int, heads: int, hidden: int) -> int
     return int(lib().vit_block_workspace(batch, tokens, heads, hidden))
 
 
-def make_block_params(batch, tokens, heads, hidden, eps, ln1, ln2, layers, gelu_table) -> vit_block_params:
+def make_block_params(batch, tokens, heads, hidden, eps, ln1, ln2, layers, gelu_table,
+                      head_dim: int = 64) -> vit_block_params:
     """ln1 / ln2: (gamma, beta) device tensors; layers: four dicts with w_q, mult, offset (device
     tensors) and s_x, z_x, s_r, z_r.  The tensors must outlive the returned struct's use."""
     bp = vit_block_params()
@@ -453,13 +455,14 @@ def make_block_params(batch, tokens, heads, hidden, eps, ln1, ln2, layers, gelu_
         bp.layer[i].s_x, bp.layer[i].z_x = ly["s_x"], ly["z_x"]
         bp.layer[i].s_r, bp.layer[i].z_r = ly["s_r"], ly["z_r"]
     bp.gelu_table = gelu_table.data_ptr()
+    bp.head_dim = head_dim
     return bp
 
 
 def vit_block_w8a8_forward(bp: vit_block_params, h: torch.Tensor, h_out: torch.Tensor,
                            workspace: torch.Tensor, stream=None):
     assert h.dtype == torch.float16 and h_out.dtype == torch.float16 and h.is_contiguous() and h_out.is_contiguous()
-    assert h.shape == h_out.shape == (bp.batch * bp.tokens, 64 * bp.heads)
+    assert h.shape == h_out.shape == (bp.batch * bp.tokens, (bp.head_dim or 64) * bp.heads)
     _check(lib().vit_block_w8a8_forward(C.byref(bp), _ptr(h), _ptr(h_out), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)),
            "vit_block_w8a8_forward")
@@ -470,7 +473,7 @@ def vit_encoder_w8a8_forward(blocks, h: torch.Tensor, h_out: torch.Tensor, works
     """blocks: a sequence of vit_block_params of one shape; h_out may be h."""
     assert h.dtype == torch.float16 and h_out.dtype == torch.float16 and h.is_contiguous() and h_out.is_contiguous()
     arr = (vit_block_params * len(blocks))(*blocks)
-    assert h.shape == h_out.shape == (arr[0].batch * arr[0].tokens, 64 * arr[0].heads)
+    assert h.shape == h_out.shape == (arr[0].batch * arr[0].tokens, (arr[0].head_dim or 64) * arr[0].heads)
     _check(lib().vit_encoder_w8a8_forward(arr, len(blocks), _ptr(h), _ptr(h_out), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream(stream)),
            "vit_encoder_w8a8_forward")

@@ -227,8 +227,8 @@ __global__ __launch_bounds__(256) void table_lookup_kernel(const int8_t *in, int
 }
 
 // ------------------------------------------------------------------------------------------
-// Multi-head self-attention, head width 64, up to 224 tokens: one workgroup per (image, head),
-// one wavefront per 32 queries.  K (as (code - z) in binary16, row-major, 144-byte rows) and V
+// Multi-head self-attention, head width D = 64 or 32, up to 224 tokens: one workgroup per (image, head),
+// one wavefront per 32 queries.  K (as (code - z) in binary16, row-major, rows of 2 D + 16 bytes) and V
 // (transposed, 520-byte rows) of the head sit in LDS; both row strides make the operand reads
 // conflict-free.  S^T = K Q^T: 32 x 32 x 16 MFMA tiles with keys along M, so a lane owns one
 // query (its N index) and, with its partner lane ^ 32, all of that query's scores - the softmax
@@ -238,8 +238,9 @@ __global__ __launch_bounds__(256) void table_lookup_kernel(const int8_t *in, int
 // 8-byte reads.  Scores are exact integers; p is scaled by 1024 before its conversion to binary16
 // so that no term that matters falls into the subnormal range.
 // ------------------------------------------------------------------------------------------
-constexpr int kHeadDim = 64;
-constexpr int kKStride = 144;  // bytes per K row in LDS
+constexpr int kHeadDim = 64;     // widest head; 32 is the other width
+// bytes per K row in LDS: the head's binary16 values + 16 (conflict-free 16-byte operand reads for both widths)
+constexpr int k_stride(int d) { return 2 * d + 16; }
 constexpr int kVStride = 520;  // bytes per V^T row in LDS
 
 struct AttnParams {
@@ -258,18 +259,18 @@ struct AttnParams {
 // running maximum `mx`, the running (lane-local) sum of weights and the output accumulators
 // rescaled when a later group raises the maximum (the usual streaming form of the softmax: the
 // result is the same up to fp32 rounding, and only CNT score tiles are live at a time).
-template <int CNT>
+template <int CNT, int D>
 __device__ __forceinline__ void attention_key_group(int t0, bool first, const int8_t *s_k, const int8_t *s_v,
-                                                    const h8 (&fq)[4], int tokens, float lscale, int l32, int half,
-                                                    float &mx, float &sum, v16f (&oc)[2]) {
+                                                    const h8 (&fq)[D / 16], int tokens, float lscale, int l32, int half,
+                                                    float &mx, float &sum, v16f (&oc)[D / 32]) {
   v16f sc[CNT];
 #pragma unroll
   for (int t = 0; t < CNT; ++t) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) sc[t][i] = 0.0f;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const h8 fk = *reinterpret_cast<const h8 *>(s_k + (32 * (t0 + t) + l32) * kKStride + (2 * s + half) * 16);
+    for (int s = 0; s < D / 16; ++s) {
+      const h8 fk = *reinterpret_cast<const h8 *>(s_k + (32 * (t0 + t) + l32) * k_stride(D) + (2 * s + half) * 16);
       sc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sc[t], 0, 0, 0);
     }
   }
@@ -294,7 +295,7 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
     const float corr = __builtin_amdgcn_exp2f((mx - gmx) * lscale);
     sum *= corr;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < D / 32; ++a)
 #pragma unroll
       for (int i = 0; i < 16; ++i) oc[a][i] *= corr;
     mx = gmx;
@@ -317,7 +318,7 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
 #pragma unroll
       for (int e = 0; e < 8; ++e) fp[e] = (_Float16)sc[t][8 * u + e];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) {
+      for (int a = 0; a < D / 32; ++a) {
         const int8_t *vb = s_v + (32 * a + l32) * kVStride + (32 * (t0 + t) + 16 * u + 4 * half) * 2;
         const h4 lo = *reinterpret_cast<const h4 *>(vb), hi = *reinterpret_cast<const h4 *>(vb + 16);
         const h8 fv = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
@@ -328,23 +329,24 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
 
 constexpr int kKeyGroup = 3;  // key tiles per group: 48 score registers live, two workgroups per compute unit
 
-template <int NT>
+template <int NT, int D>
 __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParams p) {
   constexpr int TP = 32 * NT;
-  __shared__ __attribute__((aligned(16))) int8_t s_k[TP * kKStride];
-  __shared__ __attribute__((aligned(16))) int8_t s_v[kHeadDim * kVStride];
+  __shared__ __attribute__((aligned(16))) int8_t s_k[TP * k_stride(D)];
+  __shared__ __attribute__((aligned(16))) int8_t s_v[D * kVStride];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int head = blockIdx.x % p.heads;
   const int64_t row0 = (int64_t)(blockIdx.x / p.heads) * p.tokens;
-  const int c = p.heads * kHeadDim;
-  const int8_t *qbase = p.r + row0 * p.ld + head * kHeadDim;
+  const int c = p.heads * D;
+  const int8_t *qbase = p.r + row0 * p.ld + head * D;
 
   const _Float16 zb = (_Float16)(float)(1152 + p.z);
   const h2 zbias = {zb, zb};
   // K and V of the head -> LDS as (code - z) in binary16; rows beyond the last token are zero
-  for (int i = tid; i < TP * 8; i += 64 * NT) {
-    const int key = i >> 3, ch = i & 7;
+  constexpr int CH = D / 8;  // 8-channel chunks per row
+  for (int i = tid; i < TP * CH; i += 64 * NT) {
+    const int key = i / CH, ch = i % CH;
     h8 kv, vv;
     if (key < p.tokens) {
       kv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + key * p.ld + c + 8 * ch), zbias);
@@ -353,7 +355,7 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
 #pragma unroll
       for (int e = 0; e < 8; ++e) kv[e] = vv[e] = (_Float16)0.0f;
     }
-    *reinterpret_cast<h8 *>(s_k + key * kKStride + ch * 16) = kv;
+    *reinterpret_cast<h8 *>(s_k + key * k_stride(D) + ch * 16) = kv;
 #pragma unroll
     for (int e = 0; e < 8; ++e) *reinterpret_cast<_Float16 *>(s_v + (8 * ch + e) * kVStride + key * 2) = vv[e];
   }
@@ -361,36 +363,37 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
   // this lane's query row as B operands (rows beyond the last token repeat it; never stored)
   const int q = wave * 32 + l32;
   const int qrow = q < p.tokens ? q : p.tokens - 1;
-  h8 fq[4];
+  h8 fq[D / 16];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
+  for (int s = 0; s < D / 16; ++s) {
     fq[s] = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + qrow * p.ld + 16 * s + 8 * half), zbias);
   }
   __syncthreads();
 
-  const float lscale = p.s * p.s * 0.125f * 1.44269504088896340736f;  // s^2 / sqrt(64) * log2(e)
+  // s^2 / sqrt(D) * log2(e)
+  const float lscale = p.s * p.s * (D == 64 ? 0.125f : 0.17677669529663687f) * 1.44269504088896340736f;
   float mx = 0.0f, sum = 0.0f;
-  v16f oc[2];
+  v16f oc[D / 32];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < D / 32; ++a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) oc[a][i] = 0.0f;
 #pragma unroll
   for (int g = 0; g < NT / kKeyGroup; ++g) {
-    attention_key_group<kKeyGroup>(g * kKeyGroup, g == 0, s_k, s_v, fq, p.tokens, lscale, l32, half, mx, sum, oc);
+    attention_key_group<kKeyGroup, D>(g * kKeyGroup, g == 0, s_k, s_v, fq, p.tokens, lscale, l32, half, mx, sum, oc);
     __builtin_amdgcn_sched_barrier(0);  // one group's score tiles live at a time
   }
   if constexpr (NT % kKeyGroup != 0)
-    attention_key_group<NT % kKeyGroup>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq, p.tokens, lscale, l32,
+    attention_key_group<NT % kKeyGroup, D>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq, p.tokens, lscale, l32,
                                         half, mx, sum, oc);
   sum += __shfl_xor(sum, 32, 64);
 
   // O^T: register 4 g + r of tile a is channel 32 a + 8 g + 4 half + r of this lane's query
   const float onorm = p.s * (1.0f / sum);  // sum and the accumulators both carry the factor 1024
   const float zf = (float)p.z_a, inv_sa = 1.0f / p.s_a;
-  int8_t *orow = p.a + (row0 + qrow) * p.lda + head * kHeadDim;
+  int8_t *orow = p.a + (row0 + qrow) * p.lda + head * D;
 #pragma unroll
-  for (int a = 0; a < 2; ++a) {
+  for (int a = 0; a < D / 32; ++a) {
     uint32_t packed[4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -408,10 +411,23 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
   }
 }
 
-template <int NT>
+template <int NT, int D>
 cwac_status launch_attention(const AttnParams &p, int batch, hipStream_t st) {
-  attention_int8_kernel<NT><<<dim3((unsigned)(batch * p.heads)), 64 * NT, 0, st>>>(p);
+  attention_int8_kernel<NT, D><<<dim3((unsigned)(batch * p.heads)), 64 * NT, 0, st>>>(p);
   return launch_status();
+}
+
+template <int D>
+cwac_status launch_attention_d(const AttnParams &p, int batch, hipStream_t st) {
+  switch ((p.tokens + 31) / 32) {
+    case 1: return launch_attention<1, D>(p, batch, st);
+    case 2: return launch_attention<2, D>(p, batch, st);
+    case 3: return launch_attention<3, D>(p, batch, st);
+    case 4: return launch_attention<4, D>(p, batch, st);
+    case 5: return launch_attention<5, D>(p, batch, st);
+    case 6: return launch_attention<6, D>(p, batch, st);
+    default: return launch_attention<7, D>(p, batch, st);
+  }
 }
 
 }  // namespace
@@ -504,10 +520,12 @@ cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *tabl
 }
 
 cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t z, int32_t batch, int32_t tokens,
-                               int32_t heads, float s_a, int32_t z_a, int8_t *a_q, int64_t lda, void *stream) {
+                               int32_t heads, int32_t head_dim, float s_a, int32_t z_a, int8_t *a_q, int64_t lda,
+                               void *stream) {
   if (!r_qkv || !a_q) return CWAC_E_NULL;
+  if (head_dim != 64 && head_dim != 32) return CWAC_E_SHAPE;
   if (batch < 1 || tokens < 1 || tokens > 224 || heads < 1 || heads > 64) return CWAC_E_SHAPE;
-  const int64_t c = (int64_t)heads * kHeadDim;
+  const int64_t c = (int64_t)heads * head_dim;
   if (ld < 3 * c || lda < c || (int64_t)batch * heads > 0x7fffffff) return CWAC_E_SHAPE;
   if (!(s > 0.0f) || !(s_a > 0.0f) || z < -128 || z > 127) return CWAC_E_MODE;
   if (!aligned(r_qkv, 8) || ld % 8 != 0 || !aligned(a_q, 16) || lda % 16 != 0) return CWAC_E_ALIGN;
@@ -524,15 +542,7 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
   p.a = a_q;
   p.lda = lda;
   hipStream_t st = as_stream(stream);
-  switch ((tokens + 31) / 32) {
-    case 1: return launch_attention<1>(p, batch, st);
-    case 2: return launch_attention<2>(p, batch, st);
-    case 3: return launch_attention<3>(p, batch, st);
-    case 4: return launch_attention<4>(p, batch, st);
-    case 5: return launch_attention<5>(p, batch, st);
-    case 6: return launch_attention<6>(p, batch, st);
-    default: return launch_attention<7>(p, batch, st);
-  }
+  return head_dim == 64 ? launch_attention_d<64>(p, batch, st) : launch_attention_d<32>(p, batch, st);
 }
 
 size_t vit_block_workspace(int32_t batch, int32_t tokens, int32_t heads, int32_t hidden) {
@@ -549,6 +559,7 @@ cwac_status check_block(const vit_block_params *bp) {
   if (!bp->gelu_table || !bp->ln1_gamma || !bp->ln1_beta || !bp->ln2_gamma || !bp->ln2_beta) return CWAC_E_NULL;
   if (bp->batch < 1 || bp->tokens < 1 || bp->heads < 1 || bp->heads > 64 || bp->hidden < 16 || bp->hidden % 16 != 0)
     return CWAC_E_SHAPE;
+  if (bp->head_dim != 0 && bp->head_dim != 64 && bp->head_dim != 32) return CWAC_E_SHAPE;
   for (int i = 0; i < 4; ++i)
     if (!bp->layer[i].w_q || !bp->layer[i].mult || !bp->layer[i].offset) return CWAC_E_NULL;
   return CWAC_OK;
@@ -561,7 +572,8 @@ cwac_status check_block(const vit_block_params *bp) {
 cwac_status run_block(const vit_block_params *bp, bool x1_ready, const vit_block_params *next, const uint16_t *h,
                       uint16_t *h_out, void *workspace, void *stream) {
   const int64_t m = (int64_t)bp->batch * bp->tokens;
-  const int32_t c = bp->heads * kHeadDim, hid = bp->hidden;
+  const int32_t hd = bp->head_dim ? bp->head_dim : kHeadDim;
+  const int32_t c = bp->heads * hd, hid = bp->hidden;
   int8_t *xq = static_cast<int8_t *>(workspace);  // x1, then the attention output, then x2 (then the next x1)
   int8_t *r_qkv = xq + m * c;
   int8_t *r_c = r_qkv + m * 3 * c;  // proj output, then fc2 output
@@ -591,8 +603,8 @@ cwac_status run_block(const vit_block_params *bp, bool x1_ready, const vit_block
     if (st != CWAC_OK) return st;
   }
   if ((st = linear(0, xq, 3 * c, c, r_qkv)) != CWAC_OK) return st;
-  st = vit_attention_int8(r_qkv, 3 * c, L[0].s_r, L[0].z_r, bp->batch, bp->tokens, bp->heads, L[1].s_x, L[1].z_x, xq, c,
-                          stream);
+  st = vit_attention_int8(r_qkv, 3 * c, L[0].s_r, L[0].z_r, bp->batch, bp->tokens, bp->heads, hd, L[1].s_x, L[1].z_x, xq,
+                          c, stream);
   if (st != CWAC_OK) return st;
   if ((st = linear(1, xq, c, c, r_c)) != CWAC_OK) return st;
   st = vit_residual_ln_quant(h, c, r_c, c, L[1].s_r, L[1].z_r, h_out, c, bp->ln2_gamma, bp->ln2_beta, bp->eps, L[2].s_x,
@@ -630,7 +642,8 @@ cwac_status vit_encoder_w8a8_forward(const vit_block_params *blocks, int32_t n_b
     const cwac_status st = check_block(blocks + b);
     if (st != CWAC_OK) return st;
     if (blocks[b].batch != blocks[0].batch || blocks[b].tokens != blocks[0].tokens ||
-        blocks[b].heads != blocks[0].heads || blocks[b].hidden != blocks[0].hidden)
+        blocks[b].heads != blocks[0].heads || blocks[b].hidden != blocks[0].hidden ||
+        blocks[b].head_dim != blocks[0].head_dim)
       return CWAC_E_SHAPE;
   }
   if (workspace_bytes < vit_block_workspace(blocks[0].batch, blocks[0].tokens, blocks[0].heads, blocks[0].hidden))

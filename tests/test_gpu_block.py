@@ -278,9 +278,9 @@ def _check_block_stages(orc, bk, h, t, rows):
     assert ((g16 >= (tt - slack).astype(np.float16)) & (g16 <= (tt + slack).astype(np.float16))).all()
 
 
-def _run_block(orc, seed, batch, tokens, heads, hidden, rows):
+def _run_block(orc, seed, batch, tokens, heads, hidden, rows, head_dim=64):
     from paper_2505_20932_amd import vit_block
-    b = vit_block.build_block(seed, batch, tokens, heads, hidden, device=DEV)
+    b = vit_block.build_block(seed, batch, tokens, heads, hidden, device=DEV, head_dim=head_dim)
     h = vit_block.residual_stream(seed, b.m, b.c, DEV)
     t = vit_block.staged_forward(b, h)
     ws = torch.empty(P.vit_block_workspace(batch, tokens, heads, hidden), dtype=torch.int8, device=DEV)
@@ -293,7 +293,7 @@ def _run_block(orc, seed, batch, tokens, heads, hidden, rows):
     assert torch.equal(ws[:m * c].view(m, c), t["x2"])
     assert torch.equal(ws[m * c:4 * m * c].view(m, 3 * c), t["r1"])
     assert torch.equal(ws[4 * m * c:5 * m * c].view(m, c), t["r4"])
-    assert torch.equal(ws[5 * m * c:].view(m, hidden), t["g"])
+    assert torch.equal(ws[5 * m * c:5 * m * c + m * hidden].view(m, hidden), t["g"])
     # the codes use their ranges (a block whose tensors saturate or collapse would test nothing)
     for k in ("x1", "r1", "a", "r2", "x2", "r3", "g", "r4"):
         codes = t[k].cpu().numpy()
@@ -316,6 +316,12 @@ def test_block_chain_other_shapes(orc):
 def test_block_other_model_widths(orc, heads, hidden, name):
     print(f"block: {name}, 2 images x 197 tokens, {heads} heads, MLP {hidden}", flush=True)
     _run_block(orc, 7 + heads, 2, 197, heads, hidden, np.arange(0, 394, 3))
+
+
+def test_block_windowed_model_shapes(orc):
+    """Swin-B stage 3: windows of 49 tokens as the attending units, 16 heads of 32, C = 512, MLP 2048."""
+    print("block: 64 windows x 49 tokens, 16 heads of 32, MLP 2048", flush=True)
+    _run_block(orc, 31, 64, 49, 16, 2048, np.arange(0, 64 * 49, 5), head_dim=32)
 
 
 def test_block_full_size_sampled(orc):

@@ -213,19 +213,20 @@ def _attention_shapes():
     return shapes + [(1, 32, 1), (1, 31, 1), (1, 96, 1), (1, 97, 1), (1, 192, 1), (1, 223, 1), (2, 224, 2)]
 
 
+@pytest.mark.parametrize("head_dim", [64, 32])
 @pytest.mark.parametrize("batch,tokens,heads", _attention_shapes())
-def test_attention_random_shape(batch, tokens, heads):
+def test_attention_random_shape(batch, tokens, heads, head_dim):
     from oracle import block_oracle as blk
-    print(f"attention {batch} x {tokens} x {heads}", flush=True)
-    rng = np.random.default_rng(batch * 100000 + tokens * 100 + heads)
-    c = 64 * heads
+    print(f"attention {batch} x {tokens} x {heads} heads of {head_dim}", flush=True)
+    rng = np.random.default_rng(batch * 100000 + tokens * 100 + heads + head_dim)
+    c = head_dim * heads
     r = np.clip(np.rint(rng.standard_normal((batch * tokens, 3 * c)) * 35 - 6), -128, 127).astype(np.int8)
     s, z = np.float32(0.035), -6
     o, mag = blk.attention_codes(r, s, z, batch, tokens, heads)
     s_a = np.float32(max(float(o.max() - o.min()), 1e-6) / 255.0)
     z_a = int(np.clip(round(-128 - float(o.min()) / float(s_a)), -128, 127))
     a = torch.empty(batch * tokens, c, dtype=torch.int8, device=DEV)
-    P.vit_attention_int8(dev(r), float(s), z, batch, tokens, heads, float(s_a), z_a, a)
+    P.vit_attention_int8(dev(r), float(s), z, batch, tokens, heads, float(s_a), z_a, a, head_dim=head_dim)
     torch.cuda.synchronize()
     _, v = blk.quantize(o, s_a, z_a)
     delta = (2.0 ** -11 + 1024 * 2.0 ** -24) * mag / s_a + 64 * 2.0 ** -24 * (np.abs(v) + 128) + 1e-4
