@@ -676,15 +676,16 @@ def conv_section(P, synth, torch, dev: str, batch: int, steps: int, cpu_batch: i
 
 
 
-def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_images: int, n_blocks: int = 12):
+def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_images: int, n_blocks: int = 12,
+                  shape=(197, 12, 64, 3072)):
     """One W8A8 Vision Transformer block (ViT-B/16: 197 tokens, 12 heads, MLP 3072) from residual
     stream to residual stream: the four compensated linear layers (Sec. 3.4) chained with the
     non-linear glue that per-layer compensation steps around (Sec. 3.2).  A step = one call of
     vit_block_w8a8_forward (eight launches); every stage is also timed alone."""
     import numpy as np
     from paper_2505_20932_amd import vit_block
-    tokens, heads, hidden = 197, 12, 3072
-    blk = vit_block.build_block(2, batch, tokens, heads, hidden, device=dev)
+    tokens, heads, head_dim, hidden = shape
+    blk = vit_block.build_block(2, batch, tokens, heads, hidden, device=dev, head_dim=head_dim)
     m, c = blk.m, blk.c
     h = vit_block.residual_stream(2, m, c, dev)
     h_out = torch.empty_like(h)
@@ -721,7 +722,7 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
 
     # a stack of n_blocks such blocks in one call (ViT-B/16's encoder is 12): between two blocks the last
     # residual of one and the LN1 + quantizer of the next are one pass; the stream is updated in place
-    stack = [blk] + [vit_block.build_block(100 + i, batch, tokens, heads, hidden, device=dev)
+    stack = [blk] + [vit_block.build_block(100 + i, batch, tokens, heads, hidden, device=dev, head_dim=head_dim)
                      for i in range(1, n_blocks)]
     stack_params = [b.params for b in stack]
     hs = h.clone()
@@ -762,8 +763,8 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
                                                       L[0]["s_x"], L[0]["z_x"], t["x1"]), "hbm", 3.0 * m * c),
         ("qkv", linear(0, t["x1"], t["r1"]), "mfma", 2.0 * m * 3 * c * c),
         ("attention", lambda: B.vit_attention_int8(t["r1"], L[0]["s_r"], L[0]["z_r"], batch, tokens, heads,
-                                                   L[1]["s_x"], L[1]["z_x"], t["a"]), "mfma_f16",
-         4.0 * batch * heads * tokens * tokens * 64),
+                                                   L[1]["s_x"], L[1]["z_x"], t["a"], head_dim=head_dim), "mfma_f16",
+         4.0 * batch * heads * tokens * tokens * head_dim),
         ("proj", linear(1, t["a"], t["r2"]), "mfma", 2.0 * m * c * c),
         ("residual_ln2_quant", lambda: B.vit_residual_ln_quant(h, t["r2"], L[1]["s_r"], L[1]["z_r"], t["h1"], blk.ln[2],
                                                                blk.ln[3], blk.eps, L[2]["s_x"], L[2]["z_x"], t["x2"]),
@@ -802,7 +803,8 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
         "value": round(lin_ops / (ms_block * 1e-3) / 1e12, 2), "unit": "TOPS", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": round(t_step * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": f"ViT-B/16 block, {batch} images x {tokens} tokens, 12 heads x 64, MLP 3072, "
+        "config": {"workload": f"{'ViT-B/16' if shape == (197, 12, 64, 3072) else 'Transformer'} block, {batch} images "
+                               f"(attending units) x {tokens} tokens, {heads} heads x {head_dim}, MLP {hidden}, "
                                f"per-tensor int8 activations, binary16 residual stream"},
         "block_ms": round(ms_block, 4), "images_per_s": round(batch / (ms_block * 1e-3), 1),
         "graph_replay_ms": round(ms_graph, 4),
@@ -925,6 +927,9 @@ def main():
                          "with the non-linear glue (its own JSON line)")
     ap.add_argument("--block-batch", type=int, default=128)
     ap.add_argument("--blocks", type=int, default=12, help="depth of the stack timed beside the single block")
+    ap.add_argument("--block-shape", type=str, default="197,12,64,3072",
+                    help="tokens,heads,head width (64 or 32),MLP width of the block (default: ViT-B/16); e.g. "
+                         "49,16,32,2048 with --block-batch 512 is Swin-B's third stage at 8 images")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -947,7 +952,8 @@ def main():
         return
     if args.block:
         print(json.dumps(block_section(P, torch, dev, args.block_batch, args.steps, args.warmup,
-                                       0 if args.no_cpu_baseline else 2, args.blocks)))
+                                       0 if args.no_cpu_baseline else 2, args.blocks,
+                                       tuple(int(v) for v in args.block_shape.split(",")))))
         return
     wl = synth.WORKLOADS[args.config]
     cal_rows = args.cal_rows or wl.m
