@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256) void table_lookup_kernel(const int8_t *in, int
 // ------------------------------------------------------------------------------------------
 // Multi-head self-attention, head width D = 64 or 32, up to 224 tokens: one workgroup per (image, head),
 // one wavefront per 32 queries.  K (as (code - z) in binary16, row-major, rows of 2 D + 16 bytes) and V
-// (transposed, 520-byte rows) of the head sit in LDS; both row strides make the operand reads
+// (transposed, rows of 64 NT + 8 bytes) of the head sit in LDS; both row strides make the operand reads
 // conflict-free.  S^T = K Q^T: 32 x 32 x 16 MFMA tiles with keys along M, so a lane owns one
 // query (its N index) and, with its partner lane ^ 32, all of that query's scores - the softmax
 // is a reduction over the lane's own registers plus one exchange.  Registers 8u .. 8u + 7 of score
@@ -241,7 +241,9 @@ __global__ __launch_bounds__(256) void table_lookup_kernel(const int8_t *in, int
 constexpr int kHeadDim = 64;     // widest head; 32 is the other width
 // bytes per K row in LDS: the head's binary16 values + 16 (conflict-free 16-byte operand reads for both widths)
 constexpr int k_stride(int d) { return 2 * d + 16; }
-constexpr int kVStride = 520;  // bytes per V^T row in LDS
+// bytes per V^T row in LDS: 2 * 32 * NT of keys + 8; in words twice an odd number, so the 8-byte operand
+// reads of 32 consecutive rows cover all 64 banks once
+constexpr int v_stride(int nt) { return 64 * nt + 8; }
 
 struct AttnParams {
   const int8_t *r;
@@ -249,6 +251,7 @@ struct AttnParams {
   float s;
   int z;
   int tokens, heads;
+  int64_t pairs;  // batch * heads
   float s_a;
   int z_a;
   int8_t *a;
@@ -259,7 +262,7 @@ struct AttnParams {
 // running maximum `mx`, the running (lane-local) sum of weights and the output accumulators
 // rescaled when a later group raises the maximum (the usual streaming form of the softmax: the
 // result is the same up to fp32 rounding, and only CNT score tiles are live at a time).
-template <int CNT, int D>
+template <int CNT, int D, int VS>
 __device__ __forceinline__ void attention_key_group(int t0, bool first, const int8_t *s_k, const int8_t *s_v,
                                                     const h8 (&fq)[D / 16], int tokens, float lscale, int l32, int half,
                                                     float &mx, float &sum, v16f (&oc)[D / 32]) {
@@ -319,7 +322,7 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
       for (int e = 0; e < 8; ++e) fp[e] = (_Float16)sc[t][8 * u + e];
 #pragma unroll
       for (int a = 0; a < D / 32; ++a) {
-        const int8_t *vb = s_v + (32 * a + l32) * kVStride + (32 * (t0 + t) + 16 * u + 4 * half) * 2;
+        const int8_t *vb = s_v + (32 * a + l32) * VS + (32 * (t0 + t) + 16 * u + 4 * half) * 2;
         const h4 lo = *reinterpret_cast<const h4 *>(vb), hi = *reinterpret_cast<const h4 *>(vb + 16);
         const h8 fv = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         oc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp, oc[a], 0, 0, 0);
@@ -329,15 +332,24 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
 
 constexpr int kKeyGroup = 3;  // key tiles per group: 48 score registers live, two workgroups per compute unit
 
-template <int NT, int D>
-__global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParams p) {
+// G heads per workgroup (short sequences: a head of two wavefronts alone would leave the compute unit to
+// workgroup turnover); the wavefronts of a head work only on that head's slice of LDS.
+template <int NT, int D, int G>
+__global__ __launch_bounds__(64 * NT * G) void attention_int8_kernel(const AttnParams p) {
   constexpr int TP = 32 * NT;
-  __shared__ __attribute__((aligned(16))) int8_t s_k[TP * k_stride(D)];
-  __shared__ __attribute__((aligned(16))) int8_t s_v[D * kVStride];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ __attribute__((aligned(16))) int8_t s_k_all[G * TP * k_stride(D)];
+  __shared__ __attribute__((aligned(16))) int8_t s_v_all[G * D * v_stride(NT)];
+  const int slot = threadIdx.x / (64 * NT);  // which of the workgroup's heads
+  int8_t *s_k = s_k_all + slot * (TP * k_stride(D));
+  int8_t *s_v = s_v_all + slot * (D * v_stride(NT));
+  const int tid = threadIdx.x % (64 * NT), lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int head = blockIdx.x % p.heads;
-  const int64_t row0 = (int64_t)(blockIdx.x / p.heads) * p.tokens;
+  // (image, head) pairs beyond the last repeat it and store nothing (every wavefront reaches the barrier)
+  int64_t pair = (int64_t)blockIdx.x * G + slot;
+  const bool live = pair < p.pairs;
+  if (!live) pair = p.pairs - 1;
+  const int head = (int)(pair % p.heads);
+  const int64_t row0 = (pair / p.heads) * p.tokens;
   const int c = p.heads * D;
   const int8_t *qbase = p.r + row0 * p.ld + head * D;
 
@@ -357,7 +369,7 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
     }
     *reinterpret_cast<h8 *>(s_k + key * k_stride(D) + ch * 16) = kv;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) *reinterpret_cast<_Float16 *>(s_v + (8 * ch + e) * kVStride + key * 2) = vv[e];
+    for (int e = 0; e < 8; ++e) *reinterpret_cast<_Float16 *>(s_v + (8 * ch + e) * v_stride(NT) + key * 2) = vv[e];
   }
 
   // this lane's query row as B operands (rows beyond the last token repeat it; never stored)
@@ -380,11 +392,11 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
     for (int i = 0; i < 16; ++i) oc[a][i] = 0.0f;
 #pragma unroll
   for (int g = 0; g < NT / kKeyGroup; ++g) {
-    attention_key_group<kKeyGroup, D>(g * kKeyGroup, g == 0, s_k, s_v, fq, p.tokens, lscale, l32, half, mx, sum, oc);
+    attention_key_group<kKeyGroup, D, v_stride(NT)>(g * kKeyGroup, g == 0, s_k, s_v, fq, p.tokens, lscale, l32, half, mx, sum, oc);
     __builtin_amdgcn_sched_barrier(0);  // one group's score tiles live at a time
   }
   if constexpr (NT % kKeyGroup != 0)
-    attention_key_group<NT % kKeyGroup, D>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq, p.tokens, lscale, l32,
+    attention_key_group<NT % kKeyGroup, D, v_stride(NT)>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq, p.tokens, lscale, l32,
                                         half, mx, sum, oc);
   sum += __shfl_xor(sum, 32, 64);
 
@@ -407,13 +419,15 @@ __global__ __launch_bounds__(64 * NT) void attention_int8_kernel(const AttnParam
     const auto s02 = __builtin_amdgcn_permlane32_swap(packed[0], packed[2], false, false);
     const auto s13 = __builtin_amdgcn_permlane32_swap(packed[1], packed[3], false, false);
     const v4i o = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
-    if (q < p.tokens) *reinterpret_cast<v4i *>(orow + 32 * a + 16 * half) = o;
+    if (q < p.tokens && live) *reinterpret_cast<v4i *>(orow + 32 * a + 16 * half) = o;
   }
 }
 
 template <int NT, int D>
 cwac_status launch_attention(const AttnParams &p, int batch, hipStream_t st) {
-  attention_int8_kernel<NT, D><<<dim3((unsigned)(batch * p.heads)), 64 * NT, 0, st>>>(p);
+  constexpr int G = NT == 1 ? 4 : (NT == 2 ? 2 : 1);  // 256 threads per workgroup for short sequences
+  const int64_t blocks = ceil_div((int64_t)batch * p.heads, G);
+  attention_int8_kernel<NT, D, G><<<dim3((unsigned)blocks), 64 * NT * G, 0, st>>>(p);
   return launch_status();
 }
 
@@ -537,6 +551,7 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
   p.z = z;
   p.tokens = tokens;
   p.heads = heads;
+  p.pairs = (int64_t)batch * heads;
   p.s_a = s_a;
   p.z_a = z_a;
   p.a = a_q;
