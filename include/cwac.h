@@ -448,12 +448,16 @@ cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *tabl
  *   a_q    int8 [batch * tokens, c] = Q(softmax(q k^T / sqrt(d)) v; s_a, z_a) per image and head;
  *          pitch lda (lda % 16 == 0, base 16-byte aligned)
  *   1 <= tokens <= 224 (one workgroup holds a head's keys and values), heads <= 64
+ *   bias   NULL, or device binary16 [heads, tokens, ldb] added to the logits q k^T / sqrt(d) before the
+ *          softmax (the relative position bias - or a mask of large negative values - of a windowed
+ *          model; shared by all images); ldb % 4 == 0 and ldb >= tokens rounded up to a multiple of 32
+ *          (the padding is read, not used); 8-byte aligned
  * "image" is whatever attends within itself: an image of a ViT, a window of a windowed model.
  * Scores are exact (integers in fp32 accumulators), the softmax is fp32, the weights meet the
  * values as binary16 (relative error 2^-11 per term), accumulation in fp32. */
 cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t z, int32_t batch,
-                               int32_t tokens, int32_t heads, int32_t head_dim, float s_a, int32_t z_a,
-                               int8_t *a_q, int64_t lda, void *stream);
+                               int32_t tokens, int32_t heads, int32_t head_dim, const uint16_t *bias,
+                               int64_t ldb, float s_a, int32_t z_a, int8_t *a_q, int64_t lda, void *stream);
 
 /* One whole block: the chain above in eight launches (the GELU table rides in fc1's epilogue where
  * qlinear_cwac_forward_table fuses it) on `stream`, from the residual stream h
@@ -484,6 +488,8 @@ typedef struct vit_block_params {
   vit_block_layer layer[4];
   const int8_t *gelu_table;
   int32_t head_dim; /* 64 or 32; 0 means 64 */
+  const uint16_t *attn_bias; /* vit_attention_int8's bias, or NULL */
+  int64_t attn_bias_ld;
 } vit_block_params;
 
 /* Bytes of workspace of a block; sized for head width 64 (a block of 32-wide heads needs less). */

@@ -78,20 +78,24 @@ def softmax_rows(logits):
     return e / e.sum(axis=-1, keepdims=True)
 
 
-def attention(q, k, v):
-    """softmax(q k^T / sqrt(d)) v for one head; q, k, v [T, d] -> (o [T, d], mag [T, d]) with
-    mag = softmax(.) |v|, the scale of the rounding error of a lower-precision evaluation."""
+def attention(q, k, v, bias=None):
+    """softmax(q k^T / sqrt(d) + bias) v for one head; q, k, v [T, d], bias [T, T] or None -> (o [T, d],
+    mag [T, d]) with mag = softmax(.) |v|, the scale of the rounding error of a lower-precision evaluation."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
-    p = softmax_rows(q @ k.T / math.sqrt(q.shape[1]))
+    logits = q @ k.T / math.sqrt(q.shape[1])
+    if bias is not None:
+        logits = logits + np.asarray(bias, dtype=np.float64)
+    p = softmax_rows(logits)
     return p @ v, p @ np.abs(v)
 
 
-def attention_codes(r_qkv, s, z, batch, tokens, heads):
+def attention_codes(r_qkv, s, z, batch, tokens, heads, bias=None):
     """Multi-head self-attention on the requantized output of the qkv layer.
     r_qkv: int8 codes [batch * tokens, 3 * C], row = (q | k | v), each C = heads * d wide with
-    head h in columns [h * d, (h + 1) * d) -> (o [batch * tokens, C], mag) in fp64."""
+    head h in columns [h * d, (h + 1) * d); bias [heads, tokens, tokens] (added to every image's logits) or
+    None -> (o [batch * tokens, C], mag) in fp64."""
     r = np.asarray(r_qkv)
     c3 = r.shape[1]
     c = c3 // 3
@@ -101,7 +105,8 @@ def attention_codes(r_qkv, s, z, batch, tokens, heads):
     mag = np.empty_like(o)
     for b in range(batch):
         for h in range(heads):
-            o[b, :, h, :], mag[b, :, h, :] = attention(x[b, :, 0, h, :], x[b, :, 1, h, :], x[b, :, 2, h, :])
+            o[b, :, h, :], mag[b, :, h, :] = attention(x[b, :, 0, h, :], x[b, :, 1, h, :], x[b, :, 2, h, :],
+                                                       None if bias is None else bias[h])
     return o.reshape(batch * tokens, c), mag.reshape(batch * tokens, c)
 
 

@@ -50,7 +50,8 @@ class vit_block_params(C.Structure):
     _fields_ = [("batch", C.c_int32), ("tokens", C.c_int32), ("heads", C.c_int32), ("hidden", C.c_int32),
                 ("eps", C.c_float), ("ln1_gamma", C.c_void_p), ("ln1_beta", C.c_void_p),
                 ("ln2_gamma", C.c_void_p), ("ln2_beta", C.c_void_p), ("layer", vit_block_layer * 4),
-                ("gelu_table", C.c_void_p), ("head_dim", C.c_int32)]
+                ("gelu_table", C.c_void_p), ("head_dim", C.c_int32),
+                ("attn_bias", C.c_void_p), ("attn_bias_ld", C.c_int64)]
 
 
 class CwacError(RuntimeError):
@@ -109,7 +110,7 @@ def lib() -> C.CDLL:
                                             vp, i64, i64, i32, vp]),
             "vit_gelu_table": (i32, [f32, i32, f32, i32, vp, vp]),
             "vit_table_lookup": (i32, [vp, i64, vp, vp, i64, i64, i32, vp]),
-            "vit_attention_int8": (i32, [vp, i64, f32, i32, i32, i32, i32, i32, f32, i32, vp, i64, vp]),
+            "vit_attention_int8": (i32, [vp, i64, f32, i32, i32, i32, i32, i32, vp, i64, f32, i32, vp, i64, vp]),
             "vit_block_workspace": (sz, [i32, i32, i32, i32]),
             "qlinear_cwac_forward_table": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp, vp, vp, i64, vp]),
             "vit_block_w8a8_forward": (i32, [C.POINTER(vit_block_params), vp, vp, vp, sz, vp]),
@@ -428,12 +429,18 @@ def vit_table_lookup(x: torch.Tensor, table: torch.Tensor, out: torch.Tensor, st
 
 
 def vit_attention_int8(r_qkv: torch.Tensor, s: float, z: int, batch: int, tokens: int, heads: int,
-                       s_a: float, z_a: int, a_q: torch.Tensor, head_dim: int = 64, stream=None):
+                       s_a: float, z_a: int, a_q: torch.Tensor, head_dim: int = 64, bias=None, stream=None):
+    """bias: None or float16 [heads, tokens, ldb] with ldb % 4 == 0, ldb >= tokens rounded up to 32."""
     assert r_qkv.dtype == torch.int8 and a_q.dtype == torch.int8
     c = head_dim * heads
     assert r_qkv.shape == (batch * tokens, 3 * c) and a_q.shape == (batch * tokens, c)
-    _check(lib().vit_attention_int8(_ptr(r_qkv), _rowmajor(r_qkv), s, z, batch, tokens, heads, head_dim, s_a, z_a,
-                                    _ptr(a_q), _rowmajor(a_q), _stream(stream)), "vit_attention_int8")
+    ldb = 0
+    if bias is not None:
+        assert bias.dtype == torch.float16 and bias.is_contiguous() and bias.shape[:2] == (heads, tokens)
+        ldb = bias.shape[2]
+    _check(lib().vit_attention_int8(_ptr(r_qkv), _rowmajor(r_qkv), s, z, batch, tokens, heads, head_dim,
+                                    _ptr(bias), ldb, s_a, z_a, _ptr(a_q), _rowmajor(a_q), _stream(stream)),
+           "vit_attention_int8")
 
 
 def vit_block_workspace(batch: int, tokens: int, heads: int, hidden: int) -> int:
@@ -441,7 +448,7 @@ def vit_block_workspace(batch: int, tokens: int, heads: int, hidden: int) -> int
 
 
 def make_block_params(batch, tokens, heads, hidden, eps, ln1, ln2, layers, gelu_table,
-                      head_dim: int = 64) -> vit_block_params:
+                      head_dim: int = 64, attn_bias=None) -> vit_block_params:
     """ln1 / ln2: (gamma, beta) device tensors; layers: four dicts with w_q, mult, offset (device
     tensors) and s_x, z_x, s_r, z_r.  The tensors must outlive the returned struct's use."""
     bp = vit_block_params()
@@ -456,6 +463,9 @@ def make_block_params(batch, tokens, heads, hidden, eps, ln1, ln2, layers, gelu_
         bp.layer[i].s_r, bp.layer[i].z_r = ly["s_r"], ly["z_r"]
     bp.gelu_table = gelu_table.data_ptr()
     bp.head_dim = head_dim
+    if attn_bias is not None:
+        assert attn_bias.dtype == torch.float16 and attn_bias.is_contiguous()
+        bp.attn_bias, bp.attn_bias_ld = attn_bias.data_ptr(), attn_bias.shape[2]
     return bp
 
 

@@ -252,6 +252,8 @@ struct AttnParams {
   int z;
   int tokens, heads;
   int64_t pairs;  // batch * heads
+  const uint16_t *bias;  // binary16 [heads][tokens][ldb] added to the logits, or NULL
+  int64_t ldb;
   float s_a;
   int z_a;
   int8_t *a;
@@ -262,9 +264,10 @@ struct AttnParams {
 // running maximum `mx`, the running (lane-local) sum of weights and the output accumulators
 // rescaled when a later group raises the maximum (the usual streaming form of the softmax: the
 // result is the same up to fp32 rounding, and only CNT score tiles are live at a time).
-template <int CNT, int D, int VS>
+template <int CNT, int D, int VS, bool BIAS>
 __device__ __forceinline__ void attention_key_group(int t0, bool first, const int8_t *s_k, const int8_t *s_v,
-                                                    const h8 (&fq)[D / 16], int tokens, float lscale, int l32, int half,
+                                                    const h8 (&fq)[D / 16], const uint16_t *bias_row, int tokens,
+                                                    float lscale, int l32, int half,
                                                     float &mx, float &sum, v16f (&oc)[D / 32]) {
   v16f sc[CNT];
 #pragma unroll
@@ -278,6 +281,22 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
     }
   }
   // register 4 g + r of tile t is key 32 t + 8 g + 4 half + r of this lane's query
+  if (BIAS) {
+    // with a bias the scores become logits in the log2 domain first: x = S * lscale + bias * log2(e)
+    // (the bias rows are padded to whole key tiles, so the loads of padded keys stay inside them)
+#pragma unroll
+    for (int t = 0; t < CNT; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const uint2 bw = *reinterpret_cast<const uint2 *>(bias_row + 32 * (t0 + t) + 8 * g + 4 * half);
+        const h2 b01 = __builtin_bit_cast(h2, bw.x), b23 = __builtin_bit_cast(h2, bw.y);
+        const float bf[4] = {(float)b01[0], (float)b01[1], (float)b23[0], (float)b23[1]};
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          sc[t][4 * g + r] = __builtin_fmaf(sc[t][4 * g + r], lscale, bf[r] * 1.44269504088896340736f);
+      }
+  }
+  const float dscale = BIAS ? 1.0f : lscale;  // what turns a score difference into a log2 difference
   float gmx = -INFINITY;
 #pragma unroll
   for (int t = 0; t < CNT; ++t) {
@@ -295,7 +314,7 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
   if (first) {
     mx = gmx;
   } else if (gmx > mx) {  // the same decision in both lanes of a query
-    const float corr = __builtin_amdgcn_exp2f((mx - gmx) * lscale);
+    const float corr = __builtin_amdgcn_exp2f((mx - gmx) * dscale);
     sum *= corr;
 #pragma unroll
     for (int a = 0; a < D / 32; ++a)
@@ -305,12 +324,12 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
   }
   // 1024 p = exp2(S * lscale + (10 - mx * lscale)), one fused multiply-add per exponent;
   // exp2(-inf) = 0 for masked keys
-  const float eoff = 10.0f - mx * lscale;
+  const float eoff = 10.0f - mx * dscale;
 #pragma unroll
   for (int t = 0; t < CNT; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      sc[t][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[t][i], lscale, eoff));
+      sc[t][i] = __builtin_amdgcn_exp2f(BIAS ? sc[t][i] + eoff : __builtin_fmaf(sc[t][i], lscale, eoff));
       sum += sc[t][i];
     }
 #pragma unroll
@@ -334,7 +353,7 @@ constexpr int kKeyGroup = 3;  // key tiles per group: 48 score registers live, t
 
 // G heads per workgroup (short sequences: a head of two wavefronts alone would leave the compute unit to
 // workgroup turnover); the wavefronts of a head work only on that head's slice of LDS.
-template <int NT, int D, int G>
+template <int NT, int D, int G, bool BIAS>
 __global__ __launch_bounds__(64 * NT * G) void attention_int8_kernel(const AttnParams p) {
   constexpr int TP = 32 * NT;
   __shared__ __attribute__((aligned(16))) int8_t s_k_all[G * TP * k_stride(D)];
@@ -384,6 +403,8 @@ __global__ __launch_bounds__(64 * NT * G) void attention_int8_kernel(const AttnP
 
   // s^2 / sqrt(D) * log2(e)
   const float lscale = p.s * p.s * (D == 64 ? 0.125f : 0.17677669529663687f) * 1.44269504088896340736f;
+  // this lane's row of the bias: [head][query][key], rows padded to whole key tiles
+  const uint16_t *bias_row = BIAS ? p.bias + ((int64_t)head * p.tokens + qrow) * p.ldb : nullptr;
   float mx = 0.0f, sum = 0.0f;
   v16f oc[D / 32];
 #pragma unroll
@@ -392,11 +413,12 @@ __global__ __launch_bounds__(64 * NT * G) void attention_int8_kernel(const AttnP
     for (int i = 0; i < 16; ++i) oc[a][i] = 0.0f;
 #pragma unroll
   for (int g = 0; g < NT / kKeyGroup; ++g) {
-    attention_key_group<kKeyGroup, D, v_stride(NT)>(g * kKeyGroup, g == 0, s_k, s_v, fq, p.tokens, lscale, l32, half, mx, sum, oc);
+    attention_key_group<kKeyGroup, D, v_stride(NT), BIAS>(g * kKeyGroup, g == 0, s_k, s_v, fq, bias_row, p.tokens, lscale, l32, half, mx, sum, oc);
     __builtin_amdgcn_sched_barrier(0);  // one group's score tiles live at a time
   }
   if constexpr (NT % kKeyGroup != 0)
-    attention_key_group<NT % kKeyGroup, D, v_stride(NT)>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq, p.tokens, lscale, l32,
+    attention_key_group<NT % kKeyGroup, D, v_stride(NT), BIAS>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq,
+                                                               bias_row, p.tokens, lscale, l32,
                                         half, mx, sum, oc);
   sum += __shfl_xor(sum, 32, 64);
 
@@ -427,7 +449,10 @@ template <int NT, int D>
 cwac_status launch_attention(const AttnParams &p, int batch, hipStream_t st) {
   constexpr int G = NT == 1 ? 4 : (NT == 2 ? 2 : 1);  // 256 threads per workgroup for short sequences
   const int64_t blocks = ceil_div((int64_t)batch * p.heads, G);
-  attention_int8_kernel<NT, D, G><<<dim3((unsigned)blocks), 64 * NT * G, 0, st>>>(p);
+  if (p.bias)
+    attention_int8_kernel<NT, D, G, true><<<dim3((unsigned)blocks), 64 * NT * G, 0, st>>>(p);
+  else
+    attention_int8_kernel<NT, D, G, false><<<dim3((unsigned)blocks), 64 * NT * G, 0, st>>>(p);
   return launch_status();
 }
 
@@ -534,9 +559,11 @@ cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *tabl
 }
 
 cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t z, int32_t batch, int32_t tokens,
-                               int32_t heads, int32_t head_dim, float s_a, int32_t z_a, int8_t *a_q, int64_t lda,
-                               void *stream) {
+                               int32_t heads, int32_t head_dim, const uint16_t *bias, int64_t ldb, float s_a,
+                               int32_t z_a, int8_t *a_q, int64_t lda, void *stream) {
   if (!r_qkv || !a_q) return CWAC_E_NULL;
+  if (bias && (ldb < 32 * ((tokens + 31) / 32) || ldb % 4 != 0)) return CWAC_E_SHAPE;
+  if (bias && !aligned(bias, 8)) return CWAC_E_ALIGN;
   if (head_dim != 64 && head_dim != 32) return CWAC_E_SHAPE;
   if (batch < 1 || tokens < 1 || tokens > 224 || heads < 1 || heads > 64) return CWAC_E_SHAPE;
   const int64_t c = (int64_t)heads * head_dim;
@@ -552,6 +579,8 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
   p.tokens = tokens;
   p.heads = heads;
   p.pairs = (int64_t)batch * heads;
+  p.bias = bias;
+  p.ldb = ldb;
   p.s_a = s_a;
   p.z_a = z_a;
   p.a = a_q;
@@ -618,8 +647,8 @@ cwac_status run_block(const vit_block_params *bp, bool x1_ready, const vit_block
     if (st != CWAC_OK) return st;
   }
   if ((st = linear(0, xq, 3 * c, c, r_qkv)) != CWAC_OK) return st;
-  st = vit_attention_int8(r_qkv, 3 * c, L[0].s_r, L[0].z_r, bp->batch, bp->tokens, bp->heads, hd, L[1].s_x, L[1].z_x, xq,
-                          c, stream);
+  st = vit_attention_int8(r_qkv, 3 * c, L[0].s_r, L[0].z_r, bp->batch, bp->tokens, bp->heads, hd, bp->attn_bias, bp->attn_bias_ld,
+                          L[1].s_x, L[1].z_x, xq, c, stream);
   if (st != CWAC_OK) return st;
   if ((st = linear(1, xq, c, c, r_c)) != CWAC_OK) return st;
   st = vit_residual_ln_quant(h, c, r_c, c, L[1].s_r, L[1].z_r, h_out, c, bp->ln2_gamma, bp->ln2_beta, bp->eps, L[2].s_x,
@@ -658,7 +687,7 @@ cwac_status vit_encoder_w8a8_forward(const vit_block_params *blocks, int32_t n_b
     if (st != CWAC_OK) return st;
     if (blocks[b].batch != blocks[0].batch || blocks[b].tokens != blocks[0].tokens ||
         blocks[b].heads != blocks[0].heads || blocks[b].hidden != blocks[0].hidden ||
-        blocks[b].head_dim != blocks[0].head_dim)
+        blocks[b].head_dim != blocks[0].head_dim)  // (each block may bring its own attention bias)
       return CWAC_E_SHAPE;
   }
   if (workspace_bytes < vit_block_workspace(blocks[0].batch, blocks[0].tokens, blocks[0].heads, blocks[0].hidden))

@@ -32,6 +32,7 @@ class Block:
     gelu_table: torch.Tensor = None
     params: B.vit_block_params = None
     head_dim: int = 64
+    attn_bias: torch.Tensor = None         # float16 [heads, tokens, ldb] or None
 
     @property
     def c(self) -> int:
@@ -62,14 +63,14 @@ def _range_params(x: torch.Tensor):
 
 
 def build_block(seed: int, batch: int, tokens: int, heads: int, hidden: int, device="cuda:0",
-                eps: float = 1e-6, set_up_images: int = 4, head_dim: int = 64) -> Block:
+                eps: float = 1e-6, set_up_images: int = 4, head_dim: int = 64, attn_bias=None) -> Block:
     """Draws the block's parameters and calibrates its quantizers on the first `set_up_images`
     images of the seeded residual stream."""
     c = head_dim * heads
     shapes = {"qkv": (3 * c, c), "proj": (c, c), "fc1": (hidden, c), "fc2": (c, hidden)}
     ln = [1.0 + 0.1 * synth.normal(seed, 10, c, device=device), 0.05 * synth.normal(seed, 11, c, device=device),
           1.0 + 0.1 * synth.normal(seed, 12, c, device=device), 0.05 * synth.normal(seed, 13, c, device=device)]
-    blk = Block(batch, tokens, heads, hidden, eps, ln, head_dim=head_dim)
+    blk = Block(batch, tokens, heads, hidden, eps, ln, head_dim=head_dim, attn_bias=attn_bias)
     w, bias = {}, {}
     for i, name in enumerate(LAYERS):
         n, k = shapes[name]
@@ -82,7 +83,8 @@ def build_block(seed: int, batch: int, tokens: int, heads: int, hidden: int, dev
     y1 = F.layer_norm(h, (c,), ln[0], ln[1], eps)
     qkv = y1 @ w["qkv"].t() + bias["qkv"]
     q, k_, v = (qkv[:, j * c:(j + 1) * c].reshape(-1, tokens, heads, head_dim).permute(0, 2, 1, 3) for j in range(3))
-    att = F.scaled_dot_product_attention(q, k_, v).permute(0, 2, 1, 3).reshape(ms, c)
+    mask = None if attn_bias is None else attn_bias[None, :, :, :tokens].float()
+    att = F.scaled_dot_product_attention(q, k_, v, attn_mask=mask).permute(0, 2, 1, 3).reshape(ms, c)
     proj = att @ w["proj"].t() + bias["proj"]
     h1 = h + proj
     y2 = F.layer_norm(h1, (c,), ln[2], ln[3], eps)
@@ -113,7 +115,7 @@ def build_block(seed: int, batch: int, tokens: int, heads: int, hidden: int, dev
     B.vit_gelu_table(blk.layers[2]["s_r"], blk.layers[2]["z_r"], blk.layers[3]["s_x"], blk.layers[3]["z_x"],
                      blk.gelu_table)
     blk.params = B.make_block_params(batch, tokens, heads, hidden, eps, (ln[0], ln[1]), (ln[2], ln[3]), blk.layers,
-                                     blk.gelu_table, head_dim)
+                                     blk.gelu_table, head_dim, attn_bias)
     torch.cuda.synchronize()
     return blk
 
@@ -136,7 +138,7 @@ def staged_forward(blk: Block, h: torch.Tensor) -> Dict[str, torch.Tensor]:
     B.vit_residual_ln_quant(h, None, 0.0, 0, None, blk.ln[0], blk.ln[1], blk.eps, L[0]["s_x"], L[0]["z_x"], t["x1"])
     linear(0, t["x1"], t["r1"])
     B.vit_attention_int8(t["r1"], L[0]["s_r"], L[0]["z_r"], blk.batch, blk.tokens, blk.heads, L[1]["s_x"],
-                         L[1]["z_x"], t["a"], head_dim=blk.head_dim)
+                         L[1]["z_x"], t["a"], head_dim=blk.head_dim, bias=blk.attn_bias)
     linear(1, t["a"], t["r2"])
     B.vit_residual_ln_quant(h, t["r2"], L[1]["s_r"], L[1]["z_r"], t["h1"], blk.ln[2], blk.ln[3], blk.eps,
                             L[2]["s_x"], L[2]["z_x"], t["x2"])

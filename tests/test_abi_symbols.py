@@ -211,16 +211,18 @@ def test_argument_errors_of_the_block_glue_entry_points(lib):
     assert tl(a, 64, a, a, 32, 4, 64, null) == -2            # ld_out < n
     assert tl(a, 72, a, a, 64, 4, 64, null) == -3            # ld_in % 16
     at = lib.vit_attention_int8
-    #        r  ld   s    z  batch tokens heads d s_a z_a a  lda
-    assert at(null, 192, 1.0, 0, 1, 16, 1, 64, 1.0, 0, a, 64, null) == -1
-    assert at(a, 192, 1.0, 0, 1, 225, 1, 64, 1.0, 0, a, 64, null) == -2   # more tokens than one workgroup holds
-    assert at(a, 192, 1.0, 0, 1, 16, 1, 48, 1.0, 0, a, 64, null) == -2    # head width other than 64 or 32
-    assert at(a, 128, 1.0, 0, 1, 16, 1, 64, 1.0, 0, a, 64, null) == -2    # ld < 3 c
-    assert at(a, 192, 1.0, 0, 1, 16, 1, 64, 1.0, 0, a, 32, null) == -2    # lda < c
-    assert at(a, 192, 0.0, 0, 1, 16, 1, 64, 1.0, 0, a, 64, null) == -4
-    assert at(a, 192, 1.0, 200, 1, 16, 1, 64, 1.0, 0, a, 64, null) == -4  # zero-point outside int8
-    assert at(a, 196, 1.0, 0, 1, 16, 1, 64, 1.0, 0, a, 64, null) == -3    # ld % 8
-    assert at(a, 192, 1.0, 0, 1, 16, 1, 64, 1.0, 0, C.c_void_p(4104), 64, null) == -3
+    #        r  ld   s    z  batch tokens heads d  bias ldb s_a z_a a  lda
+    assert at(null, 192, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 64, null) == -1
+    assert at(a, 192, 1.0, 0, 1, 225, 1, 64, null, 0, 1.0, 0, a, 64, null) == -2   # more tokens than one workgroup holds
+    assert at(a, 192, 1.0, 0, 1, 16, 1, 48, null, 0, 1.0, 0, a, 64, null) == -2    # head width other than 64 or 32
+    assert at(a, 128, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 64, null) == -2    # ld < 3 c
+    assert at(a, 192, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 32, null) == -2    # lda < c
+    assert at(a, 192, 1.0, 0, 1, 16, 1, 64, a, 16, 1.0, 0, a, 64, null) == -2      # bias rows not padded to a key tile
+    assert at(a, 192, 1.0, 0, 1, 16, 1, 64, C.c_void_p(4100), 32, 1.0, 0, a, 64, null) == -3
+    assert at(a, 192, 0.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 64, null) == -4
+    assert at(a, 192, 1.0, 200, 1, 16, 1, 64, null, 0, 1.0, 0, a, 64, null) == -4  # zero-point outside int8
+    assert at(a, 196, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 64, null) == -3    # ld % 8
+    assert at(a, 192, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, C.c_void_p(4104), 64, null) == -3
     ft = lib.qlinear_cwac_forward_table
     qp = binding.make_qparams()
     assert ft(a, 64, a, 64, 256, 256, 64, C.byref(qp), a, null, null, a, 256, null) == -1     # no table

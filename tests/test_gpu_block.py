@@ -171,6 +171,41 @@ def test_attention_random_codes(batch, tokens, heads):
     print(f"  pinned to one code: {pinned:.3f}, equal to the oracle's code: {(got == want).mean():.4f}", flush=True)
 
 
+@pytest.mark.parametrize("batch,tokens,heads,head_dim", [(6, 49, 4, 32), (2, 197, 2, 64), (3, 64, 1, 32),
+                                                         (5, 20, 3, 64), (1, 224, 1, 32)])
+def test_attention_with_logit_bias(batch, tokens, heads, head_dim):
+    """A relative-position-like bias per head (binary16, rows padded to whole key tiles), shared by all images,
+    with a few masked (very negative) entries."""
+    print(f"attention with bias {batch} x {tokens} x {heads} heads of {head_dim}", flush=True)
+    rng = np.random.default_rng(batch + 10 * tokens + heads + head_dim)
+    c = head_dim * heads
+    r = np.clip(np.rint(rng.standard_normal((batch * tokens, 3 * c)) * 30 + 4), -128, 127).astype(np.int8)
+    s, z = np.float32(0.04), 4
+    ldb = 32 * ((tokens + 31) // 32)
+    bias16 = np.full((heads, tokens, ldb), 123.0, dtype=np.float16)          # padding: read, never used
+    bias16[:, :, :tokens] = (rng.standard_normal((heads, tokens, tokens)) * 2).astype(np.float16)
+    masked = rng.random((heads, tokens, tokens)) < 0.05
+    masked[:, np.arange(tokens), np.arange(tokens)] = False                  # every query keeps a key
+    bias16[:, :, :tokens][masked] = np.float16(-100.0)
+    bias = bias16[:, :, :tokens].astype(np.float64)
+    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads, bias)
+    s_a, z_a = _out_params(o)
+    a = torch.empty(batch * tokens, c, dtype=torch.int8, device=DEV)
+    P.vit_attention_int8(_dev(r), float(s), z, batch, tokens, heads, s_a, z_a, a, head_dim=head_dim,
+                         bias=_dev(bias16))
+    torch.cuda.synchronize()
+    _, v = blk.quantize(o, np.float32(s_a), z_a)
+    delta = (2.0 ** -11 + 1024 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
+    got = a.cpu().numpy()
+    _codes_within(got, v, delta)
+    want, _ = blk.quantize(o, np.float32(s_a), z_a)
+    assert (got == want).mean() > 0.9
+    # the bias matters: without it the codes differ
+    o0, _ = blk.attention_codes(r, s, z, batch, tokens, heads)
+    w0, _ = blk.quantize(o0, np.float32(s_a), z_a)
+    assert (w0 != want).mean() > 0.2
+
+
 def test_attention_uniform_weights_is_the_mean_value():
     """All keys of a head equal: every weight is exactly 1 / tokens, the output is the mean value row -
     sharp in the layout of V, the head split, the masking of the padded keys and the normalization."""
@@ -253,7 +288,8 @@ def _check_block_stages(orc, bk, h, t, rows):
     images = np.unique(rows // tok)
     for b in images:
         sl = slice(b * tok, (b + 1) * tok)
-        o, mag = blk.attention_codes(cpu["r1"][sl], np.float32(L[0]["s_r"]), L[0]["z_r"], 1, tok, bk.heads)
+        bias = None if bk.attn_bias is None else bk.attn_bias.cpu().numpy()[:, :, :tok].astype(np.float64)
+        o, mag = blk.attention_codes(cpu["r1"][sl], np.float32(L[0]["s_r"]), L[0]["z_r"], 1, tok, bk.heads, bias)
         s_a = np.float32(L[1]["s_x"])
         _, v = blk.quantize(o, s_a, L[1]["z_x"])
         delta = (2.0 ** -11 + 1024 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
@@ -278,9 +314,10 @@ def _check_block_stages(orc, bk, h, t, rows):
     assert ((g16 >= (tt - slack).astype(np.float16)) & (g16 <= (tt + slack).astype(np.float16))).all()
 
 
-def _run_block(orc, seed, batch, tokens, heads, hidden, rows, head_dim=64):
+def _run_block(orc, seed, batch, tokens, heads, hidden, rows, head_dim=64, attn_bias=None):
     from paper_2505_20932_amd import vit_block
-    b = vit_block.build_block(seed, batch, tokens, heads, hidden, device=DEV, head_dim=head_dim)
+    b = vit_block.build_block(seed, batch, tokens, heads, hidden, device=DEV, head_dim=head_dim,
+                              attn_bias=None if attn_bias is None else _dev(attn_bias))
     h = vit_block.residual_stream(seed, b.m, b.c, DEV)
     t = vit_block.staged_forward(b, h)
     ws = torch.empty(P.vit_block_workspace(batch, tokens, heads, hidden), dtype=torch.int8, device=DEV)
@@ -319,9 +356,14 @@ def test_block_other_model_widths(orc, heads, hidden, name):
 
 
 def test_block_windowed_model_shapes(orc):
-    """Swin-B stage 3: windows of 49 tokens as the attending units, 16 heads of 32, C = 512, MLP 2048."""
-    print("block: 64 windows x 49 tokens, 16 heads of 32, MLP 2048", flush=True)
-    _run_block(orc, 31, 64, 49, 16, 2048, np.arange(0, 64 * 49, 5), head_dim=32)
+    """Swin-B stage 3: windows of 49 tokens as the attending units, 16 heads of 32, C = 512, MLP 2048, a
+    relative-position-like bias per head on the logits."""
+    print("block: 64 windows x 49 tokens, 16 heads of 32, MLP 2048, attention bias", flush=True)
+    rng = np.random.default_rng(31)
+    bias = np.zeros((16, 49, 64), dtype=np.float16)
+    bias[:, :, :49] = rng.standard_normal((16, 49, 49)).astype(np.float16)
+    _run_block(orc, 31, 64, 49, 16, 2048, np.arange(0, 64 * 49, 5), head_dim=32, attn_bias=bias)
+    _run_block(orc, 32, 16, 49, 16, 2048, np.arange(0, 16 * 49, 3), head_dim=32)
 
 
 def test_block_full_size_sampled(orc):

@@ -129,6 +129,37 @@ def test_attention_against_library():
     assert (mag >= np.abs(o) - 1e-14).all()
 
 
+def test_attention_bias_against_library_and_as_mask():
+    rng = _rng(9)
+    t, d = 13, 8
+    q, k, v = (rng.standard_normal((t, d)) for _ in range(3))
+    bias = rng.standard_normal((t, t))
+    ref = F.scaled_dot_product_attention(torch.from_numpy(q)[None], torch.from_numpy(k)[None],
+                                         torch.from_numpy(v)[None], attn_mask=torch.from_numpy(bias)[None])[0].numpy()
+    o, _ = blk.attention(q, k, v, bias)
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-13)
+    # a bias that is constant along the keys changes nothing; a very negative column removes that key
+    o0, _ = blk.attention(q, k, v)
+    o1, _ = blk.attention(q, k, v, np.tile(rng.standard_normal((t, 1)), (1, t)))
+    np.testing.assert_allclose(o1, o0, rtol=1e-12, atol=1e-13)
+    mask = np.zeros((t, t))
+    mask[:, 4] = -1e4
+    o2, _ = blk.attention(q, k, v, mask)
+    keep = np.arange(t) != 4
+    o3, _ = blk.attention(q, k[keep], v[keep])
+    np.testing.assert_allclose(o2, o3, rtol=1e-12, atol=1e-13)
+    # per-head biases in the code-level entry point
+    heads = 2
+    r = rng.integers(-128, 128, (t, 3 * heads * d)).astype(np.int8)
+    bh = rng.standard_normal((heads, t, t))
+    ob, _ = blk.attention_codes(r, 0.05, 2, 1, t, heads, bh)
+    x = 0.05 * (r.astype(np.float64) - 2)
+    for h in range(heads):
+        sl = slice(h * d, (h + 1) * d)
+        oh, _ = blk.attention(x[:, sl], x[:, heads * d:][:, sl], x[:, 2 * heads * d:][:, sl], bh[h])
+        np.testing.assert_allclose(ob[:, sl], oh, rtol=1e-13)
+
+
 def test_attention_closed_forms():
     rng = _rng(6)
     t, d = 11, 4
