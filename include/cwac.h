@@ -447,7 +447,8 @@ cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *tabl
  *          quantization parameters (s, z) of the whole tensor
  *   a_q    int8 [batch * tokens, c] = Q(softmax(q k^T / sqrt(d)) v; s_a, z_a) per image and head;
  *          pitch lda (lda % 16 == 0, base 16-byte aligned)
- *   1 <= tokens <= 224 (one workgroup holds a head's keys and values), heads <= 64
+ *   1 <= tokens <= 4096 (up to 224 tokens one workgroup holds a head's keys and values; beyond, the keys
+ *   pass through it in chunks of 224 with a running softmax), heads <= 64
  *   bias   NULL, or device binary16 [heads, tokens, ldb] added to the logits q k^T / sqrt(d) before the
  *          softmax (the relative position bias - or a mask of large negative values - of a windowed
  *          model; shared by all images); ldb % 4 == 0 and ldb >= tokens rounded up to a multiple of 32

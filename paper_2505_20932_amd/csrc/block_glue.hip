@@ -239,6 +239,7 @@ __global__ __launch_bounds__(256) void table_lookup_kernel(const int8_t *in, int
 // so that no term that matters falls into the subnormal range.
 // ------------------------------------------------------------------------------------------
 constexpr int kHeadDim = 64;     // widest head; 32 is the other width
+constexpr int kMaxTokens = 4096; // longest sequence
 // bytes per K row in LDS: the head's binary16 values + 16 (conflict-free 16-byte operand reads for both widths)
 constexpr int k_stride(int d) { return 2 * d + 16; }
 // bytes per V^T row in LDS: 2 * 32 * NT of keys + 8; in words twice an odd number, so the 8-byte operand
@@ -264,11 +265,14 @@ struct AttnParams {
 // running maximum `mx`, the running (lane-local) sum of weights and the output accumulators
 // rescaled when a later group raises the maximum (the usual streaming form of the softmax: the
 // result is the same up to fp32 rounding, and only CNT score tiles are live at a time).
-template <int CNT, int D, int VS, bool BIAS>
+// With LONG the tiles in LDS are one chunk of a longer sequence: tile t0 + t holds keys from
+// key0 + 32 (t0 + t) on, and a tile may lie wholly beyond the last token (its scores are masked and its
+// bias is not read).
+template <int CNT, int D, int VS, bool BIAS, bool LONG = false>
 __device__ __forceinline__ void attention_key_group(int t0, bool first, const int8_t *s_k, const int8_t *s_v,
                                                     const h8 (&fq)[D / 16], const uint16_t *bias_row, int tokens,
                                                     float lscale, int l32, int half,
-                                                    float &mx, float &sum, v16f (&oc)[D / 32]) {
+                                                    float &mx, float &sum, v16f (&oc)[D / 32], int key0 = 0) {
   v16f sc[CNT];
 #pragma unroll
   for (int t = 0; t < CNT; ++t) {
@@ -288,7 +292,8 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
     for (int t = 0; t < CNT; ++t)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const uint2 bw = *reinterpret_cast<const uint2 *>(bias_row + 32 * (t0 + t) + 8 * g + 4 * half);
+        if (LONG && key0 + 32 * (t0 + t) >= tokens) continue;  // uniform: the tile is masked below
+        const uint2 bw = *reinterpret_cast<const uint2 *>(bias_row + key0 + 32 * (t0 + t) + 8 * g + 4 * half);
         const h2 b01 = __builtin_bit_cast(h2, bw.x), b23 = __builtin_bit_cast(h2, bw.y);
         const float bf[4] = {(float)b01[0], (float)b01[1], (float)b23[0], (float)b23[1]};
 #pragma unroll
@@ -300,17 +305,17 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
   float gmx = -INFINITY;
 #pragma unroll
   for (int t = 0; t < CNT; ++t) {
-    if (32 * (t0 + t) + 32 > tokens) {  // only the last tile can hold padded keys (uniform branch)
+    if (key0 + 32 * (t0 + t) + 32 > tokens) {  // only the last tiles can hold padded keys (uniform branch)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int key = 32 * (t0 + t) + 8 * (i >> 2) + 4 * half + (i & 3);
+        const int key = key0 + 32 * (t0 + t) + 8 * (i >> 2) + 4 * half + (i & 3);
         if (key >= tokens) sc[t][i] = -INFINITY;
       }
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) gmx = fmaxf(gmx, sc[t][i]);
   }
-  gmx = fmaxf(gmx, __shfl_xor(gmx, 32, 64));  // every tile holds at least one real key: finite
+  gmx = fmaxf(gmx, __shfl_xor(gmx, 32, 64));  // a group's first tile holds at least one real key: finite
   if (first) {
     mx = gmx;
   } else if (gmx > mx) {  // the same decision in both lanes of a query
@@ -347,6 +352,33 @@ __device__ __forceinline__ void attention_key_group(int t0, bool first, const in
         oc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp, oc[a], 0, 0, 0);
       }
     }
+}
+
+// Normalizes, quantizes and stores one query's output row.  O^T: register 4 g + r of tile a is channel
+// 32 a + 8 g + 4 half + r of this lane's query; `sum` is the lane-local sum of weights.
+template <int D>
+__device__ __forceinline__ void attention_store_row(const AttnParams &p, float sum, const v16f (&oc)[D / 32], int8_t *orow,
+                                                    int half, bool store) {
+  sum += __shfl_xor(sum, 32, 64);
+  const float onorm = p.s * (1.0f / sum);  // sum and the accumulators both carry the factor 1024
+  const float zf = (float)p.z_a, inv_sa = 1.0f / p.s_a;
+#pragma unroll
+  for (int a = 0; a < D / 32; ++a) {
+    uint32_t packed[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint32_t w = 0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) w |= (uint32_t)(quant_code(oc[a][4 * g + r] * onorm, inv_sa, zf) & 0xff) << (8 * r);
+      packed[g] = w;
+    }
+    // lower half-wave holds channels 8g .. 8g+3, upper 8g+4 .. 8g+7: after the two swaps the lower
+    // lane owns channels 0 .. 15 of this 32-channel tile and the upper lane 16 .. 31
+    const auto s02 = __builtin_amdgcn_permlane32_swap(packed[0], packed[2], false, false);
+    const auto s13 = __builtin_amdgcn_permlane32_swap(packed[1], packed[3], false, false);
+    const v4i o = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
+    if (store) *reinterpret_cast<v4i *>(orow + 32 * a + 16 * half) = o;
+  }
 }
 
 constexpr int kKeyGroup = 3;  // key tiles per group: 48 score registers live, two workgroups per compute unit
@@ -420,29 +452,8 @@ __global__ __launch_bounds__(64 * NT * G) void attention_int8_kernel(const AttnP
     attention_key_group<NT % kKeyGroup, D, v_stride(NT), BIAS>(NT / kKeyGroup * kKeyGroup, NT < kKeyGroup, s_k, s_v, fq,
                                                                bias_row, p.tokens, lscale, l32,
                                         half, mx, sum, oc);
-  sum += __shfl_xor(sum, 32, 64);
 
-  // O^T: register 4 g + r of tile a is channel 32 a + 8 g + 4 half + r of this lane's query
-  const float onorm = p.s * (1.0f / sum);  // sum and the accumulators both carry the factor 1024
-  const float zf = (float)p.z_a, inv_sa = 1.0f / p.s_a;
-  int8_t *orow = p.a + (row0 + qrow) * p.lda + head * D;
-#pragma unroll
-  for (int a = 0; a < D / 32; ++a) {
-    uint32_t packed[4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint32_t w = 0;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) w |= (uint32_t)(quant_code(oc[a][4 * g + r] * onorm, inv_sa, zf) & 0xff) << (8 * r);
-      packed[g] = w;
-    }
-    // lower half-wave holds channels 8g .. 8g+3, upper 8g+4 .. 8g+7: after the two swaps the lower
-    // lane owns channels 0 .. 15 of this 32-channel tile and the upper lane 16 .. 31
-    const auto s02 = __builtin_amdgcn_permlane32_swap(packed[0], packed[2], false, false);
-    const auto s13 = __builtin_amdgcn_permlane32_swap(packed[1], packed[3], false, false);
-    const v4i o = {(int)s02[0], (int)s02[1], (int)s13[0], (int)s13[1]};
-    if (q < p.tokens && live) *reinterpret_cast<v4i *>(orow + 32 * a + 16 * half) = o;
-  }
+  attention_store_row<D>(p, sum, oc, p.a + (row0 + qrow) * p.lda + head * D, half, q < p.tokens && live);
 }
 
 template <int NT, int D>
@@ -456,8 +467,91 @@ cwac_status launch_attention(const AttnParams &p, int batch, hipStream_t st) {
   return launch_status();
 }
 
+// Sequences of more than 224 tokens: one workgroup per (image, head, block of 224 queries); the keys and
+// values pass through LDS in chunks of 224, the running maximum, sum and accumulators carried from chunk
+// to chunk exactly as from key group to key group.
+constexpr int kChunkTiles = 7, kChunk = 32 * kChunkTiles;
+template <int D, bool BIAS>
+__global__ __launch_bounds__(64 * kChunkTiles) void attention_long_kernel(const AttnParams p) {
+  constexpr int NT = kChunkTiles;
+  __shared__ __attribute__((aligned(16))) int8_t s_k[kChunk * k_stride(D)];
+  __shared__ __attribute__((aligned(16))) int8_t s_v[D * v_stride(NT)];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int64_t pair = blockIdx.x;
+  const int head = (int)(pair % p.heads);
+  const int64_t row0 = (pair / p.heads) * p.tokens;
+  const int c = p.heads * D;
+  const int8_t *qbase = p.r + row0 * p.ld + head * D;
+  const _Float16 zb = (_Float16)(float)(1152 + p.z);
+  const h2 zbias = {zb, zb};
+
+  const int q0 = blockIdx.y * kChunk + wave * 32;  // this wavefront's first query
+  const bool wave_live = q0 < p.tokens;            // otherwise it only helps to fill LDS
+  const int q = q0 + l32;
+  const int qrow = q < p.tokens ? q : p.tokens - 1;
+  h8 fq[D / 16];
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) {
+    fq[s] = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + (int64_t)qrow * p.ld + 16 * s + 8 * half), zbias);
+  }
+  const float lscale = p.s * p.s * (D == 64 ? 0.125f : 0.17677669529663687f) * 1.44269504088896340736f;
+  const uint16_t *bias_row = BIAS ? p.bias + ((int64_t)head * p.tokens + qrow) * p.ldb : nullptr;
+  float mx = 0.0f, sum = 0.0f;
+  v16f oc[D / 32];
+#pragma unroll
+  for (int a = 0; a < D / 32; ++a)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) oc[a][i] = 0.0f;
+
+  constexpr int CH = D / 8;
+  for (int key0 = 0; key0 < p.tokens; key0 += kChunk) {
+    if (key0 > 0) __syncthreads();  // every wavefront is done with the previous chunk
+    for (int i = tid; i < kChunk * CH; i += 64 * NT) {
+      const int kl = i / CH, ch = i % CH, key = key0 + kl;
+      h8 kv, vv;
+      if (key < p.tokens) {
+        kv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + (int64_t)key * p.ld + c + 8 * ch), zbias);
+        vv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + (int64_t)key * p.ld + 2 * c + 8 * ch), zbias);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kv[e] = vv[e] = (_Float16)0.0f;
+      }
+      *reinterpret_cast<h8 *>(s_k + kl * k_stride(D) + ch * 16) = kv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) *reinterpret_cast<_Float16 *>(s_v + (8 * ch + e) * v_stride(NT) + kl * 2) = vv[e];
+    }
+    __syncthreads();
+    if (wave_live) {
+#pragma unroll
+      for (int t0 = 0; t0 + kKeyGroup <= NT; t0 += kKeyGroup) {
+        if (key0 + 32 * t0 < p.tokens)
+          attention_key_group<kKeyGroup, D, v_stride(NT), BIAS, true>(t0, key0 + t0 == 0, s_k, s_v, fq, bias_row, p.tokens,
+                                                                     lscale, l32, half, mx, sum, oc, key0);
+      }
+      constexpr int TAIL = NT / kKeyGroup * kKeyGroup;
+      if (NT % kKeyGroup != 0 && key0 + 32 * TAIL < p.tokens)
+        attention_key_group<(NT % kKeyGroup ? NT % kKeyGroup : 1), D, v_stride(NT), BIAS, true>(
+            TAIL, false, s_k, s_v, fq, bias_row, p.tokens, lscale, l32, half, mx, sum, oc, key0);
+    }
+  }
+  if (wave_live)
+    attention_store_row<D>(p, sum, oc, p.a + (row0 + qrow) * p.lda + head * D, half, q < p.tokens);
+}
+
+template <int D>
+cwac_status launch_attention_long(const AttnParams &p, int batch, hipStream_t st) {
+  const dim3 grid((unsigned)((int64_t)batch * p.heads), (unsigned)ceil_div(p.tokens, kChunk));
+  if (p.bias)
+    attention_long_kernel<D, true><<<grid, 64 * kChunkTiles, 0, st>>>(p);
+  else
+    attention_long_kernel<D, false><<<grid, 64 * kChunkTiles, 0, st>>>(p);
+  return launch_status();
+}
+
 template <int D>
 cwac_status launch_attention_d(const AttnParams &p, int batch, hipStream_t st) {
+  if (p.tokens > kChunk) return launch_attention_long<D>(p, batch, st);
   switch ((p.tokens + 31) / 32) {
     case 1: return launch_attention<1, D>(p, batch, st);
     case 2: return launch_attention<2, D>(p, batch, st);
@@ -565,7 +659,7 @@ cwac_status vit_attention_int8(const int8_t *r_qkv, int64_t ld, float s, int32_t
   if (bias && (ldb < 32 * ((tokens + 31) / 32) || ldb % 4 != 0)) return CWAC_E_SHAPE;
   if (bias && !aligned(bias, 8)) return CWAC_E_ALIGN;
   if (head_dim != 64 && head_dim != 32) return CWAC_E_SHAPE;
-  if (batch < 1 || tokens < 1 || tokens > 224 || heads < 1 || heads > 64) return CWAC_E_SHAPE;
+  if (batch < 1 || tokens < 1 || tokens > kMaxTokens || heads < 1 || heads > 64) return CWAC_E_SHAPE;
   const int64_t c = (int64_t)heads * head_dim;
   if (ld < 3 * c || lda < c || (int64_t)batch * heads > 0x7fffffff) return CWAC_E_SHAPE;
   if (!(s > 0.0f) || !(s_a > 0.0f) || z < -128 || z > 127) return CWAC_E_MODE;

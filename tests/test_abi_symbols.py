@@ -213,7 +213,7 @@ def test_argument_errors_of_the_block_glue_entry_points(lib):
     at = lib.vit_attention_int8
     #        r  ld   s    z  batch tokens heads d  bias ldb s_a z_a a  lda
     assert at(null, 192, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 64, null) == -1
-    assert at(a, 192, 1.0, 0, 1, 225, 1, 64, null, 0, 1.0, 0, a, 64, null) == -2   # more tokens than one workgroup holds
+    assert at(a, 192, 1.0, 0, 1, 4097, 1, 64, null, 0, 1.0, 0, a, 64, null) == -2   # more tokens than the longest sequence
     assert at(a, 192, 1.0, 0, 1, 16, 1, 48, null, 0, 1.0, 0, a, 64, null) == -2    # head width other than 64 or 32
     assert at(a, 128, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 64, null) == -2    # ld < 3 c
     assert at(a, 192, 1.0, 0, 1, 16, 1, 64, null, 0, 1.0, 0, a, 32, null) == -2    # lda < c

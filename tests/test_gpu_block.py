@@ -206,10 +206,46 @@ def test_attention_with_logit_bias(batch, tokens, heads, head_dim):
     assert (w0 != want).mean() > 0.2
 
 
-def test_attention_uniform_weights_is_the_mean_value():
+@pytest.mark.parametrize("batch,tokens,heads,head_dim,with_bias", [
+    (2, 225, 2, 64, False), (1, 448, 1, 64, False), (1, 449, 2, 32, False), (2, 577, 3, 64, False),
+    (1, 1000, 2, 64, True), (1, 577, 2, 32, True), (1, 300, 1, 64, True), (1, 4096, 1, 64, False)])
+def test_attention_long_sequences(batch, tokens, heads, head_dim, with_bias):
+    """More than 224 tokens: the keys pass through the workgroup in chunks and the queries split into blocks
+    of 224 - chunk counts 2 .. 19, last chunks of 1 token up to a full one, last query blocks ragged."""
+    print(f"attention {batch} x {tokens} tokens x {heads} heads of {head_dim}, bias {with_bias}", flush=True)
+    rng = np.random.default_rng(batch * 7 + tokens + heads + head_dim)
+    c = head_dim * heads
+    r = np.clip(np.rint(rng.standard_normal((batch * tokens, 3 * c)) * 30 + 4), -128, 127).astype(np.int8)
+    s, z = np.float32(0.04), 4
+    bias = bias16 = None
+    if with_bias:
+        ldb = 32 * ((tokens + 31) // 32)
+        bias16 = np.full((heads, tokens, ldb), 123.0, dtype=np.float16)
+        bias16[:, :, :tokens] = (rng.standard_normal((heads, tokens, tokens)) * 2).astype(np.float16)
+        masked = rng.random((heads, tokens, tokens)) < 0.05
+        masked[:, np.arange(tokens), np.arange(tokens)] = False
+        bias16[:, :, :tokens][masked] = np.float16(-100.0)
+        bias = bias16[:, :, :tokens].astype(np.float64)
+    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads, bias)
+    s_a, z_a = _out_params(o)
+    full = torch.full((batch * tokens, c + 16), 99, dtype=torch.int8, device=DEV)
+    P.vit_attention_int8(_dev(r), float(s), z, batch, tokens, heads, s_a, z_a, full[:, :c], head_dim=head_dim,
+                         bias=None if bias16 is None else _dev(bias16))
+    torch.cuda.synchronize()
+    assert (full[:, c:] == 99).all()
+    got = full[:, :c].cpu().numpy()
+    _, v = blk.quantize(o, np.float32(s_a), z_a)
+    delta = (2.0 ** -11 + 1024 * U32) * mag / s_a + 64 * U32 * (np.abs(v) + 128) + 1e-4
+    _codes_within(got, v, delta)
+    want, _ = blk.quantize(o, np.float32(s_a), z_a)
+    assert (got == want).mean() > 0.9, float((got == want).mean())
+
+
+@pytest.mark.parametrize("tokens", [77, 500])
+def test_attention_uniform_weights_is_the_mean_value(tokens):
     """All keys of a head equal: every weight is exactly 1 / tokens, the output is the mean value row -
     sharp in the layout of V, the head split, the masking of the padded keys and the normalization."""
-    batch, tokens, heads = 2, 77, 2
+    batch, heads = 2, 2
     c = 64 * heads
     rng = np.random.default_rng(3)
     r = rng.integers(-128, 128, (batch * tokens, 3 * c)).astype(np.int8)
@@ -227,10 +263,11 @@ def test_attention_uniform_weights_is_the_mean_value():
     assert pinned > 0.99
 
 
-def test_attention_one_dominant_key_picks_its_value():
+@pytest.mark.parametrize("tokens", [197, 600])
+def test_attention_one_dominant_key_picks_its_value(tokens):
     """Query i scores key perm[i] far above the rest: the output row is that key's value row - sharp in
     which key's weight meets which value row (the key order of the second product)."""
-    batch, tokens, heads = 1, 197, 1
+    batch, heads = 1, 1
     c = 64
     rng = np.random.default_rng(4)
     perm = rng.permutation(tokens)
@@ -364,6 +401,12 @@ def test_block_windowed_model_shapes(orc):
     bias[:, :, :49] = rng.standard_normal((16, 49, 49)).astype(np.float16)
     _run_block(orc, 31, 64, 49, 16, 2048, np.arange(0, 64 * 49, 5), head_dim=32, attn_bias=bias)
     _run_block(orc, 32, 16, 49, 16, 2048, np.arange(0, 16 * 49, 3), head_dim=32)
+
+
+def test_block_long_sequence(orc):
+    """ViT-B/16 at 384 x 384 pixels: 577 tokens per image, attention over key chunks."""
+    print("block: 2 images x 577 tokens, 12 heads, MLP 3072", flush=True)
+    _run_block(orc, 9, 2, 577, 12, 3072, np.arange(0, 2 * 577, 2))
 
 
 def test_block_full_size_sampled(orc):

@@ -210,7 +210,9 @@ def test_residual_ln_quant_random_shape(m, c):
 def _attention_shapes():
     rng = np.random.default_rng(78)
     shapes = [(int(rng.integers(1, 4)), int(rng.integers(1, 225)), int(rng.integers(1, 5))) for _ in range(10)]
-    return shapes + [(1, 32, 1), (1, 31, 1), (1, 96, 1), (1, 97, 1), (1, 192, 1), (1, 223, 1), (2, 224, 2)]
+    long_ones = [(int(rng.integers(1, 3)), int(rng.integers(225, 900)), int(rng.integers(1, 3))) for _ in range(5)]
+    return shapes + long_ones + [(1, 32, 1), (1, 31, 1), (1, 96, 1), (1, 97, 1), (1, 192, 1), (1, 223, 1), (2, 224, 2),
+                                 (1, 672, 1), (1, 673, 1), (1, 257, 2)]
 
 
 @pytest.mark.parametrize("head_dim", [64, 32])
