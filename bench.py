@@ -822,7 +822,8 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
                      "launches_per_step": 4, "avg_launch_ms": round(lin_us / 4e3, 4), "ops_per_step": lin_ops},
         "roofline_attention": {"bound": "mfma", "achieved": round(att["tflops"] / 1e3, 4), "peak": 2.5,
                                "unit": "PFLOP/s", "frac": att["frac"], "traffic": None,
-                               "kernel": "attention_int8_kernel (the longest glue stage; fp16 MFMA, 4 T^2 d flops "
+                               "kernel": ("attention_int8_kernel" if tokens <= 224 else "attention_long_kernel")
+                                         + " (the longest glue stage; fp16 MFMA, 4 T^2 d flops "
                                          "per head; bound by its vector work, not by the matrix cores)"},
         "stages": per_stage,
     }
