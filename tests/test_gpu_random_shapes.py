@@ -215,20 +215,28 @@ def _attention_shapes():
                                  (1, 672, 1), (1, 673, 1), (1, 257, 2)]
 
 
+@pytest.mark.parametrize("with_bias", [False, True])
 @pytest.mark.parametrize("head_dim", [64, 32])
 @pytest.mark.parametrize("batch,tokens,heads", _attention_shapes())
-def test_attention_random_shape(batch, tokens, heads, head_dim):
+def test_attention_random_shape(batch, tokens, heads, head_dim, with_bias):
     from oracle import block_oracle as blk
-    print(f"attention {batch} x {tokens} x {heads} heads of {head_dim}", flush=True)
+    print(f"attention {batch} x {tokens} x {heads} heads of {head_dim}, bias {with_bias}", flush=True)
     rng = np.random.default_rng(batch * 100000 + tokens * 100 + heads + head_dim)
     c = head_dim * heads
     r = np.clip(np.rint(rng.standard_normal((batch * tokens, 3 * c)) * 35 - 6), -128, 127).astype(np.int8)
     s, z = np.float32(0.035), -6
-    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads)
+    bias = bias16 = None
+    if with_bias:  # rows padded to whole key tiles plus a random surplus of 4-element steps
+        ldb = 32 * ((tokens + 31) // 32) + 4 * int(rng.integers(0, 5))
+        bias16 = np.full((heads, tokens, ldb), -77.0, dtype=np.float16)
+        bias16[:, :, :tokens] = (rng.standard_normal((heads, tokens, tokens)) * 1.5).astype(np.float16)
+        bias = bias16[:, :, :tokens].astype(np.float64)
+    o, mag = blk.attention_codes(r, s, z, batch, tokens, heads, bias)
     s_a = np.float32(max(float(o.max() - o.min()), 1e-6) / 255.0)
     z_a = int(np.clip(round(-128 - float(o.min()) / float(s_a)), -128, 127))
     a = torch.empty(batch * tokens, c, dtype=torch.int8, device=DEV)
-    P.vit_attention_int8(dev(r), float(s), z, batch, tokens, heads, float(s_a), z_a, a, head_dim=head_dim)
+    P.vit_attention_int8(dev(r), float(s), z, batch, tokens, heads, float(s_a), z_a, a, head_dim=head_dim,
+                         bias=None if bias16 is None else dev(bias16))
     torch.cuda.synchronize()
     _, v = blk.quantize(o, s_a, z_a)
     delta = (2.0 ** -11 + 1024 * 2.0 ** -24) * mag / s_a + 64 * 2.0 ** -24 * (np.abs(v) + 128) + 1e-4
