@@ -683,7 +683,8 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
     non-linear glue that per-layer compensation steps around (Sec. 3.2).  A step = one call of
     vit_block_w8a8_forward (eight launches); every stage is also timed alone."""
     import numpy as np
-    from paper_2505_20932_amd import vit_block
+    sys.path.insert(0, os.path.join(ROOT, "tests"))   # the block's set-up (an upstream fp32 model in torch) is a fixture
+    import vit_block_fixture as vit_block
     tokens, heads, head_dim, hidden = shape
     blk = vit_block.build_block(2, batch, tokens, heads, hidden, device=dev, head_dim=head_dim)
     m, c = blk.m, blk.c

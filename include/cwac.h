@@ -10,7 +10,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *     device work is enqueued asynchronously on it; no call synchronizes.
  *   - The library allocates no device memory and keeps no state between calls;
- *     scratch space is passed in as an explicit workspace.
+ *     scratch space is passed in as an explicit workspace.  It reads no environment
+ *     variable: where several kernels compute the same result, the choice is the
+ *     library's unless the caller passes a cwac_tuning to an _ex entry point.
  *   - Errors are reported through the return value; when a call returns an error
  *     nothing has been launched.  No call aborts or throws.
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
@@ -139,6 +141,15 @@ cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full, const flo
                                  int64_t ld_quant, int64_t n_rows, int32_t c_out, void *stats,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* cwac_calibrate_stats for the FIRST batch of a calibration run: the state is taken
+ * as "no rows seen" whatever it holds (it need not have been reset or even
+ * initialised), so a run is reset-free: _first for batch 0, cwac_calibrate_stats for
+ * the others.  Afterwards the state is exactly what cwac_stats_reset followed by
+ * cwac_calibrate_stats leaves.  n_rows >= 1; other arguments and errors as there. */
+cwac_status cwac_calibrate_stats_first(const float *y_full, int64_t ld_full, const float *y_quant,
+                                       int64_t ld_quant, int64_t n_rows, int32_t c_out, void *stats,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Eq. 4-5 per channel from the state, evaluated in fp64 and rounded to fp32:
  *   alpha = Cov(Y_full, Y_quant) / Var(Y_quant),  beta = E[Y_full] - alpha E[Y_quant].
  * Channels where the regression is undetermined (no rows; Var(Y_quant) not above
@@ -213,13 +224,18 @@ enum { CWAC_OUT_INT8 = 0, CWAC_OUT_FP32 = 1, CWAC_OUT_INT32 = 2 };
  *   x_q   device int8 [m, k], ldx;  w_q device int8 [n, k], ldw (nn.Linear layout)
  *   m >= 1, n >= 1, 16 <= k <= 32768, k % 16 == 0; x_q, w_q 16-byte aligned,
  *   ldx % 16 == 0, ldw % 16 == 0
- *   qp    host; supplies z_r, qmin, qmax for CWAC_OUT_INT8 (may be NULL otherwise)
+ *   qp    host; supplies z_r, qmin, qmax for CWAC_OUT_INT8 (may be NULL otherwise).  When given,
+ *         it is checked against the vectors that define the epilogue (CWAC_E_MODE, nothing
+ *         launched): act_per_token must equal (s_x_row != NULL), and for CWAC_OUT_INT8 mode
+ *         CWAC_EPI_FP_BIAS requires fbias (a fold in that mode always produces one)
  *   mult  device fp32 [n] (required unless CWAC_OUT_INT32)
  *   offset device int32 [n] or NULL; fbias device fp32 [n] or NULL;
  *   s_x_row device fp32 [m] or NULL
  *   out   device, element type per out_kind, [m, n] with leading dimension ldo >= n;
  *         vectorized stores need out aligned to 16 bytes and ldo * sizeof(element)
- *         a multiple of 16, other layouts take an element-wise store path */
+ *         a multiple of 16, other layouts take an element-wise store path
+ *   Any ldx, ldw >= k is legal; the direct-to-LDS kernel keeps per-lane byte offsets in 32 bits
+ *   and is only chosen while ldx, ldw <= 2^24 (larger pitches take the generic kernel). */
 cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
                                  int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
                                  const float *mult, const int32_t *offset, const float *fbias,
@@ -305,7 +321,10 @@ cwac_status cwac_fold_fixed_point(const float *alpha, const float *beta, const f
  *   out = (int8)(clamp(v, qmin - Z_r, qmax - Z_r) + Z_r)
  * It differs from the fp32 epilogue by at most one code, and only where the real
  * value lies within that epilogue's own rounding error of a tie.
- *   m0, shift  device int32 [n] as produced by cwac_fold_fixed_point (1 <= shift <= 62)
+ *   m0, shift  device int32 [n] as produced by cwac_fold_fixed_point.  Precondition: 1 <= shift[n] <= 62.
+ *              They are device data and are not checked: a shift outside that range gives
+ *              unspecified codes for its channel (no fault, no error status)
+ *   qp         host, required; act_per_token must be 0 and mode CWAC_EPI_INT_OFFSET (CWAC_E_MODE)
  *   out        device int8 [m, n], ldo;  other arguments and limits as in qlinear_cwac_forward */
 cwac_status qlinear_cwac_forward_fixed_point(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
                                              int64_t ldw, int64_t m, int32_t n, int32_t k,
@@ -452,7 +471,9 @@ cwac_status vit_table_lookup(const int8_t *in, int64_t ld_in, const int8_t *tabl
  *   bias   NULL, or device binary16 [heads, tokens, ldb] added to the logits q k^T / sqrt(d) before the
  *          softmax (the relative position bias - or a mask of large negative values - of a windowed
  *          model; shared by all images); ldb % 4 == 0 and ldb >= tokens rounded up to a multiple of 32
- *          (the padding is read, not used); 8-byte aligned
+ *          (the padding is read, not used); 8-byte aligned.  Every entry must be FINITE: mask with a
+ *          large negative value such as -100, not with -inf (a query whose leading keys are all
+ *          -inf would get NaN weights)
  * "image" is whatever attends within itself: an image of a ViT, a window of a windowed model.
  * Scores are exact (integers in fp32 accumulators), the softmax is fp32, the weights meet the
  * values as binary16 (relative error 2^-11 per term), accumulation in fp32. */
@@ -505,6 +526,83 @@ cwac_status vit_encoder_w8a8_forward(const vit_block_params *blocks /* host, [n_
 cwac_status vit_block_w8a8_forward(const vit_block_params *params /* host */, const uint16_t *h,
                                    uint16_t *h_out, void *workspace, size_t workspace_bytes,
                                    void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Kernel choice override (_ex entry points)                                  */
+/* ------------------------------------------------------------------------- */
+/* Several kernels and tile shapes stand behind each forward entry point; all compute the values
+ * the entry point documents (the int8 layer: bit for bit; the weight-only layer: up to the order
+ * of its fp32 sums) and the library picks by problem size.  An _ex entry point is the plain one
+ * with a trailing `tuning` (host struct, read during the call; NULL = the plain call) that
+ * overrides the pick - for tests that must reach every kernel and for tuning sweeps.  A field
+ * left 0 keeps the library's choice for that aspect; a value outside the lists below returns
+ * CWAC_E_MODE; a forced shape whose constraints the problem does not meet falls back as stated. */
+enum {
+  CWAC_KERNEL_AUTO = 0,
+  CWAC_KERNEL_DIRECT_LDS = 1,    /* the direct-to-LDS kernel wherever its constraints hold (m >= 256,
+                                    n >= 64, k % 64 == 0, ldx and ldw <= 2^24; convolution: c_in % 64
+                                    == 0, image below 2 GiB); otherwise the automatic choice */
+  CWAC_KERNEL_GENERIC_64 = 64,   /* the register-staged kernel with 64 x 64, 128 x 128 or 256 x 256 */
+  CWAC_KERNEL_GENERIC_128 = 128, /* output tiles (any shape)                                       */
+  CWAC_KERNEL_GENERIC_256 = 256
+};
+enum {
+  CWAC_SHAPE_AUTO = 0,
+  CWAC_SHAPE_256_8W = 1,      /* 256 tokens x 256 channels, eight wavefronts, K steps of 128 (k % 128 == 0) */
+  CWAC_SHAPE_256_4W_K128 = 2, /* the same tile, four wavefronts, K steps of 128, two stages */
+  CWAC_SHAPE_256_4W_K64 = 3,  /* four wavefronts, K steps of 64, four stages */
+  CWAC_SHAPE_128_PAIR = 4,    /* 128 tokens x 256 channels, two workgroups per compute unit */
+  CWAC_SHAPE_128_128 = 5      /* 128 x 128, four wavefronts of 64 x 64 */
+};
+typedef struct cwac_tuning {
+  int32_t kernel;         /* CWAC_KERNEL_*: int8 linear / convolution / table / fixed-point forwards */
+  int32_t shape;          /* CWAC_SHAPE_*: tile shape of the direct-to-LDS kernel for n >= 256 (used when that
+                             kernel runs; k % 128 != 0 always takes CWAC_SHAPE_128_PAIR or _128_128) */
+  int32_t stats_waves;    /* qlinear_cwac_calibrate_fused_ex: 0 (= 8) | 8 | 4 wavefronts per tile */
+  int32_t w4_tile;        /* qlinear_w4a16_cwac_forward_ex: 0 | 256 | 128: the tiled kernel with that
+                             many tokens per tile at every batch size */
+  int32_t w4_small_waves; /* ... its weight-streaming kernel (m <= 128): 0 | 4 | 8 wavefronts per workgroup */
+  int32_t reserved[3];    /* zero */
+} cwac_tuning;
+
+/* Which kernel qlinear_cwac_forward(_ex) would run for these sizes and this tuning (host
+ * arithmetic only; nothing is launched, no pointer is involved): CWAC_KERNEL_DIRECT_LDS or
+ * CWAC_KERNEL_GENERIC_64 / _128 / _256; a negative cwac_status for sizes the forward rejects. */
+int32_t cwac_forward_kernel_for(int64_t m, int32_t n, int32_t k, int64_t ldx, int64_t ldw,
+                                int32_t out_kind, const cwac_tuning *tuning);
+
+cwac_status qlinear_cwac_forward_ex(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
+                                    int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
+                                    const float *mult, const int32_t *offset, const float *fbias,
+                                    const float *s_x_row, int32_t out_kind, void *out, int64_t ldo,
+                                    const cwac_tuning *tuning, void *stream);
+cwac_status qlinear_cwac_forward_table_ex(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
+                                          int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
+                                          const float *mult, const int32_t *offset, const int8_t *table,
+                                          int8_t *out, int64_t ldo, const cwac_tuning *tuning, void *stream);
+cwac_status qconv2d_cwac_forward_ex(const int8_t *x_q, const int8_t *w_q, int32_t batch, int32_t h,
+                                    int32_t w, int32_t c_in, int32_t c_out, int32_t kh, int32_t kw,
+                                    int32_t stride, int32_t pad, const cwac_qparams *qp,
+                                    const float *mult, const int32_t *offset, const float *fbias,
+                                    int32_t out_kind, void *out, int64_t ldo, const cwac_tuning *tuning,
+                                    void *stream);
+cwac_status qlinear_cwac_calibrate_fused_ex(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                            int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                            const float *mult, const int32_t *offset,
+                                            const float *fbias, const float *s_x_row,
+                                            const float *y_full, int64_t ld_full, void *stats,
+                                            void *workspace, size_t workspace_bytes,
+                                            const cwac_tuning *tuning, void *stream);
+cwac_status qlinear_cwac_forward_fixed_point_ex(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                                int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                                const cwac_qparams *qp, const int32_t *m0,
+                                                const int32_t *shift, const int32_t *offset,
+                                                int8_t *out, int64_t ldo, const cwac_tuning *tuning,
+                                                void *stream);
+cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const void *packed_w,
+                                          const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
+                                          const float *mult, const float *fbias, int32_t out_kind,
+                                          void *out, int64_t ldo, const cwac_tuning *tuning, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Diagnostic (measurement aid, not a step of the method)                     */

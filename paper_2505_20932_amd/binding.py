@@ -18,6 +18,11 @@ CWAC_OK = 0
 CWAC_EPI_INT_OFFSET, CWAC_EPI_FP_BIAS = 0, 1
 CWAC_OUT_INT8, CWAC_OUT_FP32, CWAC_OUT_INT32, CWAC_OUT_FP16 = 0, 1, 2, 3
 CWAC_W4_GROUP = 128
+# cwac_tuning.kernel / .shape
+CWAC_KERNEL_AUTO, CWAC_KERNEL_DIRECT_LDS = 0, 1
+CWAC_KERNEL_GENERIC_64, CWAC_KERNEL_GENERIC_128, CWAC_KERNEL_GENERIC_256 = 64, 128, 256
+(CWAC_SHAPE_AUTO, CWAC_SHAPE_256_8W, CWAC_SHAPE_256_4W_K128, CWAC_SHAPE_256_4W_K64, CWAC_SHAPE_128_PAIR,
+ CWAC_SHAPE_128_128) = range(6)
 
 EXPORTS = (
     "cwac_status_string", "cwac_range_workspace", "cwac_range_f32", "cwac_qparams_from_range",
@@ -31,7 +36,10 @@ EXPORTS = (
     "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward", "qconv2d_cwac_forward",
     "vit_residual_ln_quant", "vit_gelu_table", "vit_table_lookup", "vit_attention_int8",
     "vit_block_workspace", "vit_block_w8a8_forward", "qlinear_cwac_forward_table",
-    "vit_encoder_w8a8_forward",
+    "vit_encoder_w8a8_forward", "cwac_calibrate_stats_first",
+    "qlinear_cwac_forward_ex", "qlinear_cwac_forward_table_ex", "qconv2d_cwac_forward_ex",
+    "qlinear_cwac_calibrate_fused_ex", "qlinear_cwac_forward_fixed_point_ex",
+    "qlinear_w4a16_cwac_forward_ex", "cwac_forward_kernel_for",
 )
 
 
@@ -39,6 +47,11 @@ class cwac_qparams(C.Structure):
     _fields_ = [("mode", C.c_int32), ("act_per_token", C.c_int32), ("s_x", C.c_float),
                 ("z_x", C.c_int32), ("s_r", C.c_float), ("z_r", C.c_int32),
                 ("qmin", C.c_int32), ("qmax", C.c_int32)]
+
+
+class cwac_tuning(C.Structure):
+    _fields_ = [("kernel", C.c_int32), ("shape", C.c_int32), ("stats_waves", C.c_int32),
+                ("w4_tile", C.c_int32), ("w4_small_waves", C.c_int32), ("reserved", C.c_int32 * 3)]
 
 
 class vit_block_layer(C.Structure):
@@ -71,6 +84,7 @@ def lib() -> C.CDLL:
         l = C.CDLL(LIB_PATH)
         vp, i64, i32, f32, f64, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_float, C.c_double, C.c_size_t
         qpp = C.POINTER(cwac_qparams)
+        tup = C.POINTER(cwac_tuning)
         sig = {
             "cwac_status_string": (C.c_char_p, [i32]),
             "cwac_range_workspace": (sz, [i64]),
@@ -116,6 +130,13 @@ def lib() -> C.CDLL:
             "vit_block_w8a8_forward": (i32, [C.POINTER(vit_block_params), vp, vp, vp, sz, vp]),
             "vit_encoder_w8a8_forward": (i32, [C.POINTER(vit_block_params), i32, vp, vp, vp, sz, vp]),
         }
+        sig["cwac_calibrate_stats_first"] = sig["cwac_calibrate_stats"]
+        sig["cwac_forward_kernel_for"] = (i32, [i64, i32, i32, i64, i64, i32, tup])
+        for name in ("qlinear_cwac_forward", "qlinear_cwac_forward_table", "qconv2d_cwac_forward",
+                     "qlinear_cwac_calibrate_fused", "qlinear_cwac_forward_fixed_point",
+                     "qlinear_w4a16_cwac_forward"):
+            res, args = sig[name]                       # _ex: the same call with a tuning before the stream
+            sig[name + "_ex"] = (res, args[:-1] + [tup, vp])
         for name, (res, args) in sig.items():
             fn = getattr(l, name)
             fn.restype, fn.argtypes = res, args
@@ -144,6 +165,15 @@ def _stream(stream=None):
 def _rowmajor(t: torch.Tensor) -> int:
     assert t.dim() == 2 and t.stride(1) == 1, "row-major 2-D tensor expected"
     return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def make_tuning(kernel=0, shape=0, stats_waves=0, w4_tile=0, w4_small_waves=0) -> cwac_tuning:
+    """Kernel choice override for the ``tuning=`` argument of the forward calls (same results)."""
+    return cwac_tuning(int(kernel), int(shape), int(stats_waves), int(w4_tile), int(w4_small_waves))
+
+
+def _tun(tuning: Optional[cwac_tuning]):
+    return C.byref(tuning) if tuning is not None else None
 
 
 def make_qparams(mode=CWAC_EPI_INT_OFFSET, act_per_token=False, s_x=1.0, z_x=0, s_r=1.0, z_r=0,
@@ -222,15 +252,19 @@ def cwac_calibrate_stats_workspace(n_rows: int, c_out: int) -> int:
 
 
 def cwac_calibrate_stats(y_full: torch.Tensor, y_quant: torch.Tensor, stats: torch.Tensor,
-                         workspace: torch.Tensor, stream=None):
+                         workspace: torch.Tensor, stream=None, first: bool = False):
+    """first=True calls cwac_calibrate_stats_first (the state is taken as empty: no reset needed)."""
     assert y_full.dtype == torch.float32 and y_quant.dtype == torch.float32
     assert y_full.shape == y_quant.shape
     n_rows, c_out = y_full.shape
-    _check(lib().cwac_calibrate_stats(_ptr(y_full), _rowmajor(y_full), _ptr(y_quant),
-                                      _rowmajor(y_quant), n_rows, c_out, _ptr(stats),
-                                      _ptr(workspace),
-                                      workspace.numel() * workspace.element_size(),
-                                      _stream(stream)), "cwac_calibrate_stats")
+    fn = lib().cwac_calibrate_stats_first if first else lib().cwac_calibrate_stats
+    _check(fn(_ptr(y_full), _rowmajor(y_full), _ptr(y_quant), _rowmajor(y_quant), n_rows, c_out,
+              _ptr(stats), _ptr(workspace), workspace.numel() * workspace.element_size(),
+              _stream(stream)), "cwac_calibrate_stats_first" if first else "cwac_calibrate_stats")
+
+
+def cwac_calibrate_stats_first(y_full, y_quant, stats, workspace, stream=None):
+    cwac_calibrate_stats(y_full, y_quant, stats, workspace, stream, first=True)
 
 
 def cwac_solve(stats: torch.Tensor, c_out: int, alpha: torch.Tensor, beta: torch.Tensor,
@@ -255,29 +289,39 @@ _OUT_DTYPE = {CWAC_OUT_INT8: torch.int8, CWAC_OUT_FP32: torch.float32, CWAC_OUT_
 
 
 def qlinear_cwac_forward(x_q: torch.Tensor, w_q: torch.Tensor, qp: Optional[cwac_qparams], mult,
-                         offset, fbias, s_x_row, out_kind: int, out: torch.Tensor, stream=None):
+                         offset, fbias, s_x_row, out_kind: int, out: torch.Tensor, stream=None,
+                         tuning: Optional[cwac_tuning] = None):
+    """tuning given: qlinear_cwac_forward_ex (the forward calls below likewise)."""
     assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8
     assert out.dtype == _OUT_DTYPE[out_kind]
     m, k = x_q.shape
     n, k2 = w_q.shape
     assert k == k2 and out.shape == (m, n)
-    _check(lib().qlinear_cwac_forward(_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n,
-                                      k, C.byref(qp) if qp is not None else None, _ptr(mult),
-                                      _ptr(offset), _ptr(fbias), _ptr(s_x_row), out_kind, _ptr(out),
-                                      _rowmajor(out), _stream(stream)), "qlinear_cwac_forward")
+    args = (_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n, k,
+            C.byref(qp) if qp is not None else None, _ptr(mult), _ptr(offset), _ptr(fbias),
+            _ptr(s_x_row), out_kind, _ptr(out), _rowmajor(out))
+    if tuning is None:
+        _check(lib().qlinear_cwac_forward(*args, _stream(stream)), "qlinear_cwac_forward")
+    else:
+        _check(lib().qlinear_cwac_forward_ex(*args, _tun(tuning), _stream(stream)),
+               "qlinear_cwac_forward_ex")
 
 
 def qlinear_cwac_forward_table(x_q: torch.Tensor, w_q: torch.Tensor, qp: cwac_qparams, mult, offset,
-                               table: torch.Tensor, out: torch.Tensor, stream=None):
+                               table: torch.Tensor, out: torch.Tensor, stream=None, tuning=None):
     """int8 forward (integer-offset epilogue) with out = table[code + 128]."""
     assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8 and out.dtype == torch.int8
     assert table.dtype == torch.int8 and table.numel() == 256
     m, k = x_q.shape
     n, k2 = w_q.shape
     assert k == k2 and out.shape == (m, n)
-    _check(lib().qlinear_cwac_forward_table(_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n, k,
-                                            C.byref(qp), _ptr(mult), _ptr(offset), _ptr(table), _ptr(out),
-                                            _rowmajor(out), _stream(stream)), "qlinear_cwac_forward_table")
+    args = (_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n, k, C.byref(qp), _ptr(mult),
+            _ptr(offset), _ptr(table), _ptr(out), _rowmajor(out))
+    if tuning is None:
+        _check(lib().qlinear_cwac_forward_table(*args, _stream(stream)), "qlinear_cwac_forward_table")
+    else:
+        _check(lib().qlinear_cwac_forward_table_ex(*args, _tun(tuning), _stream(stream)),
+               "qlinear_cwac_forward_table_ex")
 
 
 def cwac_calibrate_fused_workspace(m: int, n: int) -> int:
@@ -286,17 +330,19 @@ def cwac_calibrate_fused_workspace(m: int, n: int) -> int:
 
 def qlinear_cwac_calibrate_fused(x_q: torch.Tensor, w_q: torch.Tensor, mult, offset, fbias, s_x_row,
                                  y_full: torch.Tensor, stats: torch.Tensor,
-                                 workspace: torch.Tensor, stream=None):
+                                 workspace: torch.Tensor, stream=None, tuning=None):
     assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8 and y_full.dtype == torch.float32
     m, k = x_q.shape
     n, k2 = w_q.shape
     assert k == k2 and y_full.shape == (m, n)
-    _check(lib().qlinear_cwac_calibrate_fused(_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q),
-                                              m, n, k, _ptr(mult), _ptr(offset), _ptr(fbias),
-                                              _ptr(s_x_row), _ptr(y_full), _rowmajor(y_full),
-                                              _ptr(stats), _ptr(workspace),
-                                              workspace.numel() * workspace.element_size(),
-                                              _stream(stream)), "qlinear_cwac_calibrate_fused")
+    args = (_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n, k, _ptr(mult), _ptr(offset),
+            _ptr(fbias), _ptr(s_x_row), _ptr(y_full), _rowmajor(y_full), _ptr(stats), _ptr(workspace),
+            workspace.numel() * workspace.element_size())
+    if tuning is None:
+        _check(lib().qlinear_cwac_calibrate_fused(*args, _stream(stream)), "qlinear_cwac_calibrate_fused")
+    else:
+        _check(lib().qlinear_cwac_calibrate_fused_ex(*args, _tun(tuning), _stream(stream)),
+               "qlinear_cwac_calibrate_fused_ex")
 
 
 def cwac_epilogue_int32(acc: torch.Tensor, qp, mult, offset, fbias, s_x_row, out_kind: int,
@@ -327,22 +373,25 @@ def cwac_fold_fixed_point(alpha, beta, s_w, bias, colsum, qp: cwac_qparams, m0, 
 
 
 def qlinear_cwac_forward_fixed_point(x_q: torch.Tensor, w_q: torch.Tensor, qp: cwac_qparams, m0,
-                                     shift, offset, out: torch.Tensor, stream=None):
+                                     shift, offset, out: torch.Tensor, stream=None, tuning=None):
     assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8 and out.dtype == torch.int8
     assert m0.dtype == torch.int32 and shift.dtype == torch.int32
     m, k = x_q.shape
     n, k2 = w_q.shape
     assert k == k2 and out.shape == (m, n)
-    _check(lib().qlinear_cwac_forward_fixed_point(_ptr(x_q), _rowmajor(x_q), _ptr(w_q),
-                                                  _rowmajor(w_q), m, n, k, C.byref(qp), _ptr(m0),
-                                                  _ptr(shift), _ptr(offset), _ptr(out),
-                                                  _rowmajor(out), _stream(stream)),
-           "qlinear_cwac_forward_fixed_point")
+    args = (_ptr(x_q), _rowmajor(x_q), _ptr(w_q), _rowmajor(w_q), m, n, k, C.byref(qp), _ptr(m0),
+            _ptr(shift), _ptr(offset), _ptr(out), _rowmajor(out))
+    if tuning is None:
+        _check(lib().qlinear_cwac_forward_fixed_point(*args, _stream(stream)),
+               "qlinear_cwac_forward_fixed_point")
+    else:
+        _check(lib().qlinear_cwac_forward_fixed_point_ex(*args, _tun(tuning), _stream(stream)),
+               "qlinear_cwac_forward_fixed_point_ex")
 
 
 def qconv2d_cwac_forward(x_q: torch.Tensor, w_q: torch.Tensor, stride: int, pad: int,
                          qp: cwac_qparams, mult, offset, fbias, out_kind: int, out: torch.Tensor,
-                         stream=None):
+                         stream=None, tuning=None):
     """x_q int8 [B, H, W, C_in] (channels last), w_q int8 [C_out, KH, KW, C_in];
     out [B*OH*OW, C_out] int8 / float32 / int32 per out_kind."""
     assert x_q.dtype == torch.int8 and w_q.dtype == torch.int8
@@ -350,10 +399,13 @@ def qconv2d_cwac_forward(x_q: torch.Tensor, w_q: torch.Tensor, stride: int, pad:
     b, h, w, c_in = x_q.shape
     c_out, kh, kw, c2 = w_q.shape
     assert c2 == c_in and out.shape[1] == c_out
-    _check(lib().qconv2d_cwac_forward(_ptr(x_q), _ptr(w_q), b, h, w, c_in, c_out, kh, kw, stride,
-                                      pad, C.byref(qp), _ptr(mult), _ptr(offset), _ptr(fbias),
-                                      out_kind, _ptr(out), _rowmajor(out), _stream(stream)),
-           "qconv2d_cwac_forward")
+    args = (_ptr(x_q), _ptr(w_q), b, h, w, c_in, c_out, kh, kw, stride, pad, C.byref(qp), _ptr(mult),
+            _ptr(offset), _ptr(fbias), out_kind, _ptr(out), _rowmajor(out))
+    if tuning is None:
+        _check(lib().qconv2d_cwac_forward(*args, _stream(stream)), "qconv2d_cwac_forward")
+    else:
+        _check(lib().qconv2d_cwac_forward_ex(*args, _tun(tuning), _stream(stream)),
+               "qconv2d_cwac_forward_ex")
 
 
 # --------------------------------------------------------------------------- weight-only INT4
@@ -392,16 +444,19 @@ def cwac_fold_weight_only(alpha, beta, bias, mult: torch.Tensor, fbias: torch.Te
 
 
 def qlinear_w4a16_cwac_forward(x: torch.Tensor, packed_w: torch.Tensor, packed_sz: torch.Tensor,
-                               n: int, mult, fbias, out: torch.Tensor, stream=None):
+                               n: int, mult, fbias, out: torch.Tensor, stream=None, tuning=None):
     """x float16 [m, k]; out float16 (CWAC_OUT_FP16) or float32 (CWAC_OUT_FP32) [m, n]."""
     assert x.dtype == torch.float16 and out.dtype in (torch.float16, torch.float32)
     m, k = x.shape
     assert out.shape == (m, n)
     kind = CWAC_OUT_FP16 if out.dtype == torch.float16 else CWAC_OUT_FP32
-    _check(lib().qlinear_w4a16_cwac_forward(_ptr(x), _rowmajor(x), _ptr(packed_w), _ptr(packed_sz),
-                                            m, n, k, _ptr(mult), _ptr(fbias), kind, _ptr(out),
-                                            _rowmajor(out), _stream(stream)),
-           "qlinear_w4a16_cwac_forward")
+    args = (_ptr(x), _rowmajor(x), _ptr(packed_w), _ptr(packed_sz), m, n, k, _ptr(mult), _ptr(fbias),
+            kind, _ptr(out), _rowmajor(out))
+    if tuning is None:
+        _check(lib().qlinear_w4a16_cwac_forward(*args, _stream(stream)), "qlinear_w4a16_cwac_forward")
+    else:
+        _check(lib().qlinear_w4a16_cwac_forward_ex(*args, _tun(tuning), _stream(stream)),
+               "qlinear_w4a16_cwac_forward_ex")
 
 
 # --------------------------------------------------------------------------- block glue
@@ -487,6 +542,33 @@ def vit_encoder_w8a8_forward(blocks, h: torch.Tensor, h_out: torch.Tensor, works
     _check(lib().vit_encoder_w8a8_forward(arr, len(blocks), _ptr(h), _ptr(h_out), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream(stream)),
            "vit_encoder_w8a8_forward")
+
+
+def cwac_forward_kernel_for(m: int, n: int, k: int, ldx: int, ldw: int, out_kind: int = CWAC_OUT_INT8,
+                            tuning: Optional[cwac_tuning] = None) -> int:
+    """CWAC_KERNEL_* the forward would run for these sizes (host arithmetic only)."""
+    r = int(lib().cwac_forward_kernel_for(m, n, k, ldx, ldw, out_kind, _tun(tuning)))
+    _check(min(r, 0), "cwac_forward_kernel_for")
+    return r
+
+
+# --------------------------------------------------------------------------- _ex entry points
+def _ex(fn):
+    """The _ex entry point of a forward call: the same arguments with a cwac_tuning (an all-zero
+    struct, i.e. the library's own choice, when none is given)."""
+    def call(*args, tuning: Optional[cwac_tuning] = None, **kw):
+        return fn(*args, tuning=tuning if tuning is not None else make_tuning(), **kw)
+    call.__name__ = fn.__name__ + "_ex"
+    call.__doc__ = fn.__doc__
+    return call
+
+
+qlinear_cwac_forward_ex = _ex(qlinear_cwac_forward)
+qlinear_cwac_forward_table_ex = _ex(qlinear_cwac_forward_table)
+qconv2d_cwac_forward_ex = _ex(qconv2d_cwac_forward)
+qlinear_cwac_calibrate_fused_ex = _ex(qlinear_cwac_calibrate_fused)
+qlinear_cwac_forward_fixed_point_ex = _ex(qlinear_cwac_forward_fixed_point)
+qlinear_w4a16_cwac_forward_ex = _ex(qlinear_w4a16_cwac_forward)
 
 
 # --------------------------------------------------------------------------- diagnostic

@@ -68,7 +68,7 @@ template <int VEC>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))) void stats_partial_kernel(
     const float *__restrict__ yf, int64_t ldf, const float *__restrict__ yq, int64_t ldq,
     int64_t n_rows, int c_out, int col_groups, int row_blocks, int64_t rows_per_block,
-    const void *stats, double *__restrict__ partial) {
+    const void *stats, int fresh, double *__restrict__ partial) {
   using V = typename Ld<VEC>::T;
   __shared__ double red[kWaves - 1][kStats * VEC][kWave];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -81,7 +81,8 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
   const bool active = lane_in && rb < row_blocks;
 
   const StatsView sv = stats_view(const_cast<void *>(stats), c_out);
-  const bool first = (*sv.n == 0);
+  // fresh: the caller declares the state empty (its contents are not even read)
+  const bool first = fresh ? true : (*sv.n == 0);
   float pq[VEC], pf[VEC];
 #pragma unroll
   for (int j = 0; j < VEC; ++j) pq[j] = pf[j] = 0.0f;
@@ -191,11 +192,12 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3, 8))
 // G keeps the workgroups few, because each ends with one ticket on a single counter and those
 // serialize (960 tickets cost as much as the rest of the kernel).
 // The last workgroup to finish bumps the row count: every workgroup reads the count before
-// it takes its ticket, so none can see the new value.
+// it takes its ticket, so none can see the new value.  fresh (a run's first batch, state taken as
+// empty): nobody reads the count, so workgroup 0 simply writes the whole 64-byte header.
 template <int W, int G>
 __global__ __launch_bounds__(W *G *kWave) void stats_merge_kernel(
     const double *__restrict__ partial, int row_blocks, int c_out, const float *__restrict__ yf,
-    const float *__restrict__ yq, void *stats, int64_t n_rows) {
+    const float *__restrict__ yq, void *stats, int64_t n_rows, int fresh) {
   const int groups = (c_out + kWave - 1) / kWave;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int g = wave / W, w = wave % W;
@@ -205,7 +207,7 @@ __global__ __launch_bounds__(W *G *kWave) void stats_merge_kernel(
   const int ch = cg * kWave + lane;
   const bool active = has_task && ch < c_out;
   const StatsView sv = stats_view(stats, c_out);
-  const bool first = (*sv.n == 0);
+  const bool first = fresh ? true : (*sv.n == 0);
   double t = 0.0;
   if (active) {
     const double *src = partial + (int64_t)s * c_out + ch;
@@ -238,6 +240,16 @@ __global__ __launch_bounds__(W *G *kWave) void stats_merge_kernel(
       sv.pivot_q[ch] = yq[ch];
       sv.pivot_f[ch] = yf[ch];
     }
+  }
+  if (fresh) {
+    if (blockIdx.x == 0 && threadIdx.x < kStatsHeaderBytes / 4) {
+      uint32_t v = 0;  // header: int64 row count, int32 channel count, zeros (ticket included)
+      if (threadIdx.x == 0) v = (uint32_t)((uint64_t)n_rows & 0xffffffffu);
+      if (threadIdx.x == 1) v = (uint32_t)((uint64_t)n_rows >> 32);
+      if (threadIdx.x == 2) v = (uint32_t)c_out;
+      static_cast<uint32_t *>(stats)[threadIdx.x] = v;
+    }
+    return;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -329,18 +341,55 @@ __global__ __launch_bounds__(256) void solve_kernel(const void *stats, int c_out
 
 cwac_status launch_stats_merge(const double *partial, int row_groups, int c_out,
                                const float *pivot_f_src, const float *pivot_q_src, void *stats,
-                               int64_t n_rows, hipStream_t st) {
+                               int64_t n_rows, bool fresh, hipStream_t st) {
   const int tasks = (int)(kStats * ceil_div(c_out, kWave));
+  const int fr = fresh ? 1 : 0;
   if (row_groups <= 32)
     stats_merge_kernel<1, 8><<<(unsigned)ceil_div(tasks, 8), 8 * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src,
-                                                                             pivot_q_src, stats, n_rows);
+                                                                             pivot_q_src, stats, n_rows, fr);
   else if (row_groups <= 128)
     stats_merge_kernel<4, 4><<<(unsigned)ceil_div(tasks, 4), 16 * kWave, 0, st>>>(partial, row_groups, c_out,
-                                                                              pivot_f_src, pivot_q_src, stats, n_rows);
+                                                                              pivot_f_src, pivot_q_src, stats, n_rows, fr);
   else
     stats_merge_kernel<16, 1><<<(unsigned)tasks, 16 * kWave, 0, st>>>(partial, row_groups, c_out, pivot_f_src,
-                                                                      pivot_q_src, stats, n_rows);
+                                                                      pivot_q_src, stats, n_rows, fr);
   return launch_status();
+}
+
+// Argument checks and the two launches shared by the statistics entry points.  `partial` is the
+// caller's workspace (or the library's static scratch), already known to be large enough.
+static cwac_status calibrate_stats_impl(const float *y_full, int64_t ld_full, const float *y_quant,
+                                        int64_t ld_quant, int64_t n_rows, int32_t c_out, void *stats,
+                                        double *partial, bool fresh, hipStream_t st) {
+  const bool vec = (c_out % 4 == 0) && (ld_full % 4 == 0) && (ld_quant % 4 == 0) &&
+                   aligned(y_full, 16) && aligned(y_quant, 16);
+  const Split sp = make_split(n_rows, c_out, vec ? 4 : 1);
+  const int64_t blocks = (int64_t)sp.col_groups * sp.row_groups;
+  if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
+  const unsigned grid = (unsigned)blocks;
+  const int fr = fresh ? 1 : 0;
+  if (vec)
+    stats_partial_kernel<4><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
+                                                       c_out, sp.col_groups, sp.row_blocks,
+                                                       sp.rows_per_block, stats, fr, partial);
+  else
+    stats_partial_kernel<1><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
+                                                       c_out, sp.col_groups, sp.row_blocks,
+                                                       sp.rows_per_block, stats, fr, partial);
+  const cwac_status rc = launch_status();
+  if (rc != CWAC_OK) return rc;
+  return launch_stats_merge(partial, sp.row_groups, c_out, y_full, y_quant, stats, n_rows, fresh, st);
+}
+
+static cwac_status calibrate_stats_check(const float *y_full, int64_t ld_full, const float *y_quant,
+                                         int64_t ld_quant, int64_t n_rows, int32_t c_out, const void *stats) {
+  if (!stats) return CWAC_E_NULL;
+  if (c_out < 1 || c_out > 65536 || n_rows < 0) return CWAC_E_SHAPE;
+  if (n_rows == 0) return CWAC_OK;
+  if (!y_full || !y_quant) return CWAC_E_NULL;
+  if (ld_full < c_out || ld_quant < c_out) return CWAC_E_SHAPE;
+  if (!aligned(stats, 16) || !aligned(y_full, 4) || !aligned(y_quant, 4)) return CWAC_E_ALIGN;
+  return CWAC_OK;
 }
 
 }  // namespace cwac
@@ -375,32 +424,28 @@ extern "C" cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full
                                             int64_t n_rows, int32_t c_out, void *stats,
                                             void *workspace, size_t workspace_bytes,
                                             void *stream) {
-  if (!stats) return CWAC_E_NULL;
-  if (c_out < 1 || c_out > 65536 || n_rows < 0) return CWAC_E_SHAPE;
-  if (n_rows == 0) return CWAC_OK;
-  if (!y_full || !y_quant) return CWAC_E_NULL;
-  if (ld_full < c_out || ld_quant < c_out) return CWAC_E_SHAPE;
-  if (!aligned(stats, 16) || !aligned(y_full, 4) || !aligned(y_quant, 4)) return CWAC_E_ALIGN;
+  const cwac_status rc = calibrate_stats_check(y_full, ld_full, y_quant, ld_quant, n_rows, c_out, stats);
+  if (rc != CWAC_OK || n_rows == 0) return rc;
   if (!workspace || workspace_bytes < cwac_calibrate_stats_workspace(n_rows, c_out))
     return CWAC_E_WORKSPACE;
   if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
-  const bool vec = (c_out % 4 == 0) && (ld_full % 4 == 0) && (ld_quant % 4 == 0) &&
-                   aligned(y_full, 16) && aligned(y_quant, 16);
-  const Split sp = make_split(n_rows, c_out, vec ? 4 : 1);
-  double *partial = static_cast<double *>(workspace);
-  const int64_t blocks = (int64_t)sp.col_groups * sp.row_groups;
-  if (blocks > 0x7fffffff) return CWAC_E_SHAPE;
-  const unsigned grid = (unsigned)blocks;
-  hipStream_t st = as_stream(stream);
-  if (vec)
-    stats_partial_kernel<4><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
-                                                       c_out, sp.col_groups, sp.row_blocks,
-                                                       sp.rows_per_block, stats, partial);
-  else
-    stats_partial_kernel<1><<<grid, kThreads, 0, st>>>(y_full, ld_full, y_quant, ld_quant, n_rows,
-                                                       c_out, sp.col_groups, sp.row_blocks,
-                                                       sp.rows_per_block, stats, partial);
-  return launch_stats_merge(partial, sp.row_groups, c_out, y_full, y_quant, stats, n_rows, st);
+  return calibrate_stats_impl(y_full, ld_full, y_quant, ld_quant, n_rows, c_out, stats,
+                              static_cast<double *>(workspace), false, as_stream(stream));
+}
+
+extern "C" cwac_status cwac_calibrate_stats_first(const float *y_full, int64_t ld_full,
+                                                  const float *y_quant, int64_t ld_quant,
+                                                  int64_t n_rows, int32_t c_out, void *stats,
+                                                  void *workspace, size_t workspace_bytes,
+                                                  void *stream) {
+  const cwac_status rc = calibrate_stats_check(y_full, ld_full, y_quant, ld_quant, n_rows, c_out, stats);
+  if (rc != CWAC_OK) return rc;
+  if (n_rows < 1) return CWAC_E_SHAPE;  // a first batch has a first row: it fixes the pivots
+  if (!workspace || workspace_bytes < cwac_calibrate_stats_workspace(n_rows, c_out))
+    return CWAC_E_WORKSPACE;
+  if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
+  return calibrate_stats_impl(y_full, ld_full, y_quant, ld_quant, n_rows, c_out, stats,
+                              static_cast<double *>(workspace), true, as_stream(stream));
 }
 
 extern "C" cwac_status cwac_solve(const void *stats, int32_t c_out, double var_eps, float *alpha,

@@ -71,9 +71,10 @@ __host__ __device__ inline StatsView stats_view(void *stats, int c) {
 
 // Second stage of a statistics pass (calib_stats.hip): adds partial[row_group][kStats][c_out] into
 // the state in a fixed order and bumps its row count by n_rows.  A first batch also records the
-// pivots: pivot_q = pivot_q_src[0..c_out), pivot_f = pivot_f_src[0..c_out).
+// pivots: pivot_q = pivot_q_src[0..c_out), pivot_f = pivot_f_src[0..c_out).  fresh: the state is
+// taken as empty whatever it holds (sums overwritten, header written, row count = n_rows).
 cwac_status launch_stats_merge(const double *partial, int row_groups, int c_out,
                                const float *pivot_f_src, const float *pivot_q_src, void *stats,
-                               int64_t n_rows, hipStream_t st);
+                               int64_t n_rows, bool fresh, hipStream_t st);
 
 }  // namespace cwac

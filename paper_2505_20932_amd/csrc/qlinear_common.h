@@ -214,12 +214,36 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 }
 
 
+// Kernel choice override of the _ex entry points (cwac.h: cwac_tuning), validated.
+struct Tune {
+  int kernel = CWAC_KERNEL_AUTO, shape = CWAC_SHAPE_AUTO, stats_waves = 0;
+};
+// False where a field holds a value outside its list (the entry point returns CWAC_E_MODE).
+inline bool tune_from(const cwac_tuning *t, Tune &o) {
+  o = Tune{};
+  if (!t) return true;
+  if (t->kernel != CWAC_KERNEL_AUTO && t->kernel != CWAC_KERNEL_DIRECT_LDS && t->kernel != CWAC_KERNEL_GENERIC_64 &&
+      t->kernel != CWAC_KERNEL_GENERIC_128 && t->kernel != CWAC_KERNEL_GENERIC_256)
+    return false;
+  if (t->shape < CWAC_SHAPE_AUTO || t->shape > CWAC_SHAPE_128_128) return false;
+  if (t->stats_waves != 0 && t->stats_waves != 4 && t->stats_waves != 8) return false;
+  o.kernel = t->kernel;
+  o.shape = t->shape;
+  o.stats_waves = t->stats_waves;
+  return true;
+}
+
+// The direct-to-LDS kernel keeps a lane's byte offset inside a tile's panel (row * pitch + chunk,
+// rows < 256) in 32 bits: pitches up to 2^24 bytes cannot wrap it (255 * 2^24 + 128 < 2^32).
+constexpr int64_t kFastMaxPitch = (int64_t)1 << 24;
+inline bool fast_pitch_ok(int64_t ldx, int64_t ldw) { return ldx <= kFastMaxPitch && ldw <= kFastMaxPitch; }
+
 // Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 64, k % 64 == 0 (its 256 x 256
-// tile: n >= 256 and k % 128 == 0).
-cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st);
+// tile: n >= 256 and k % 128 == 0) and fast_pitch_ok(ldx, ldw).  `shape`: CWAC_SHAPE_* (0 = by cost model).
+cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, int shape, hipStream_t st);
 // The integer-offset int8 forward with p.code_table applied to every output code (kOutTable); shapes as
 // launch_fast with n >= 256.
-cwac_status launch_fast_table(FwdParams p, hipStream_t st);
+cwac_status launch_fast_table(FwdParams p, int shape, hipStream_t st);
 // True where that kernel would take its 128-token tile shape (two workgroups per compute unit).
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);
 // True where it would take 128 x 128 tiles (layers with few tiles and a long K loop).
@@ -227,10 +251,10 @@ bool fast_prefers_quarter_tile(int64_t m, int n);
 // The same kernel as an implicit-GEMM convolution (p.cv_* set, p.ldx unused).  fast_conv_ok: its shape
 // constraints (m >= 256, n >= 64, c_in % 64 == 0, image below 2 GiB).
 bool fast_conv_ok(const FwdParams &p, int64_t image_bytes);
-cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, hipStream_t st);
+cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, int shape, hipStream_t st);
 // Same kernel with the statistics epilogue; additionally requires n % 4 == 0, ld_full % 4 == 0
-// and a 16-byte aligned y_full.  p.partial receives ceil(m / 256) row groups.
-cwac_status launch_fast_stats(FwdParams p, hipStream_t st);
+// and a 16-byte aligned y_full.  p.partial receives ceil(m / 256) row groups.  waves: 8 (0) or 4.
+cwac_status launch_fast_stats(FwdParams p, int waves, hipStream_t st);
 constexpr int kFastTile = 256;
 constexpr int kFastKStep = 128;
 

@@ -24,9 +24,6 @@
 //
 // Requires m >= 256, n >= 256, k % 128 == 0 (the 128-token shape: k % 64 == 0).  Edge tiles are shifted inwards to overlap their
 // neighbours (identical values are written twice) instead of being predicated.
-#include <stdlib.h>
-#include <string.h>
-
 #include <type_traits>
 
 #include "qlinear_common.h"
@@ -778,10 +775,13 @@ cwac_status launch_table_cfg(FwdParams p, hipStream_t st) {
 
 }  // namespace
 
-cwac_status launch_fast_table(FwdParams p, hipStream_t st) {
+cwac_status launch_fast_table(FwdParams p, int shape, hipStream_t st) {
   p.vec_store = aligned(p.out, 16) && (p.ldo % 16) == 0;
   // the same two tiles, by the same rule, as the plain int8 forward of a layer with n >= 256
-  if ((p.k % 128) != 0 || fast_prefers_half_tile(p.m, p.n, p.k, 1)) return launch_table_cfg<128, 2, 64, 3>(p, st);
+  bool half = (p.k % 128) != 0 || fast_prefers_half_tile(p.m, p.n, p.k, 1);
+  if ((p.k % 128) == 0 && shape == CWAC_SHAPE_256_8W) half = false;
+  if (shape == CWAC_SHAPE_128_PAIR) half = true;
+  if (half) return launch_table_cfg<128, 2, 64, 3>(p, st);
   return launch_table_cfg<256, 4, 128, 2>(p, st);
 }
 
@@ -815,24 +815,24 @@ bool fast_prefers_quarter_tile(int64_t m, int n) {
   return n >= 128 && t_half < 160 && t_q >= 96;
 }
 
-cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
+cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, int shape, hipStream_t st) {
   const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
-  // Tuning knob (same results): CWAC_FWD_PIPE=8w is the 256-token tile with eight wavefronts (the
-  // default for large layers), 128x2 | 64x4 the same tile with four wavefronts and that K step
-  // and ring depth; "duo" the 128-token tile, two workgroups of four wavefronts per compute unit.
   // layers narrower than 256 channels: 256 tokens x 128 (64) channels, four wavefronts (4 x 1) of
   // 64 x 128 (64 x 64), 64-byte K steps, two workgroups per compute unit
   if (p.n < 128) return launch_cfg<256, 4, 64, 3, 2, false, 64>(p, out_kind, int_only, st);
   if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, false, 128>(p, out_kind, int_only, st);
-  const char *e = getenv("CWAC_FWD_PIPE");
-  if ((e && e[0] == 'q') || (!e && fast_prefers_quarter_tile(p.m, p.n)))
+  // `shape` (cwac_tuning, same results): CWAC_SHAPE_256_8W is the 256-token tile with eight
+  // wavefronts (the choice for large layers), _256_4W_K128 / _K64 the same tile with four wavefronts
+  // and that K step and ring depth, _128_PAIR the 128-token tile, two workgroups of four wavefronts
+  // per compute unit, _128_128 the quarter tile.
+  if (shape == CWAC_SHAPE_128_128 || (shape == CWAC_SHAPE_AUTO && fast_prefers_quarter_tile(p.m, p.n)))
     return launch_cfg<128, 2, 64, 3, 2, false, 128, 2>(p, out_kind, int_only, st);
-  if ((p.k % 128) != 0) e = "duo";  // K a multiple of 64 only: the tile that steps K by 64
-  if (e && e[0] == 'd') return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
-  if (e && e[0] == '6') return launch_cfg<256, 2, 64, 4, 2>(p, out_kind, int_only, st);
-  if (e && e[0] == '8') return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
-  if (e && e[0] == '1') return launch_cfg<256, 2, 128, 2, 2>(p, out_kind, int_only, st);
+  if ((p.k % 128) != 0) shape = CWAC_SHAPE_128_PAIR;  // K a multiple of 64 only: the tile that steps K by 64
+  if (shape == CWAC_SHAPE_128_PAIR) return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
+  if (shape == CWAC_SHAPE_256_4W_K64) return launch_cfg<256, 2, 64, 4, 2>(p, out_kind, int_only, st);
+  if (shape == CWAC_SHAPE_256_8W) return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
+  if (shape == CWAC_SHAPE_256_4W_K128) return launch_cfg<256, 2, 128, 2, 2>(p, out_kind, int_only, st);
   const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   if (fast_prefers_half_tile(p.m, p.n, p.k, out_bytes))
     return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
@@ -844,34 +844,33 @@ bool fast_conv_ok(const FwdParams &p, int64_t image_bytes) {
          (p.cv_cin % 64) == 0 && image_bytes < ((int64_t)1 << 31);
 }
 
-cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, hipStream_t st) {
+cwac_status launch_fast_conv(FwdParams p, int out_kind, bool int_only, int shape, hipStream_t st) {
   const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
   if (p.n < 128) return launch_cfg<256, 4, 64, 3, 2, true, 64>(p, out_kind, int_only, st);
   if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, true, 128>(p, out_kind, int_only, st);
   // a stage must lie inside one filter tap: the 256-token tile steps K by 128, the 128-token tile by 64
   const bool full_ok = (p.cv_cin % 128) == 0;
-  const char *e = getenv("CWAC_FWD_PIPE");  // tuning knob (same results): "8w" | "duo" | "q"
-  if ((e && e[0] == 'q') || (!e && fast_prefers_quarter_tile(p.m, p.n)))
+  // `shape` (cwac_tuning, same results): _256_8W | _128_PAIR | _128_128; the four-wavefront forms of
+  // the 256-token tile are not instantiated for the convolution and leave the choice automatic
+  if (shape == CWAC_SHAPE_128_128 || (shape == CWAC_SHAPE_AUTO && fast_prefers_quarter_tile(p.m, p.n)))
     return launch_cfg<128, 2, 64, 3, 2, true, 128, 2>(p, out_kind, int_only, st);
   bool half = !full_ok || fast_prefers_half_tile(p.m, p.n, p.k, (int)esz) ||
               ceil_div(p.m, 256) * ceil_div(p.n, 256) < 160;
-  if (e && e[0] == 'd') half = true;
-  if (e && e[0] == '8' && full_ok) half = false;
+  if (shape == CWAC_SHAPE_128_PAIR) half = true;
+  if (shape == CWAC_SHAPE_256_8W && full_ok) half = false;
   if (half) return launch_cfg<128, 2, 64, 3, 2, true>(p, out_kind, int_only, st);
   return launch_cfg<256, 4, 128, 2, 2, true>(p, out_kind, int_only, st);
 }
 
-cwac_status launch_fast_stats(FwdParams p, hipStream_t st) {
+cwac_status launch_fast_stats(FwdParams p, int waves, hipStream_t st) {
   p.tiles_m = (int)ceil_div(p.m, 256);
   p.tiles_n = (int)ceil_div(p.n, 256);
   p.vec_store = 0;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  // Tuning knob: CWAC_STATS_PIPE=4w keeps four wavefronts per tile (the fp64 sums then add up in
-  // another order).
-  const char *e = getenv("CWAC_STATS_PIPE");
-  if (e && e[0] == '4') return launch_one<256, 2, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
+  // four wavefronts per tile add the fp64 sums up in another order than eight (cwac_tuning.stats_waves)
+  if (waves == 4) return launch_one<256, 2, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
   return launch_one<256, 4, 128, 2, 2, kOutStats, false>(p, dim3((unsigned)blocks), st);
 }
 

@@ -12,8 +12,6 @@
 // as B (j <-> token row m) makes every lane hold 4 consecutive output channels
 // of one token, which is exactly a packed 4 x int8 (or one float4) store into
 // the row-major [M, N] output.
-#include <stdlib.h>
-
 #include "qlinear_common.h"
 
 namespace cwac {
@@ -223,10 +221,9 @@ __global__ __launch_bounds__(256) void row0_kernel(const FwdParams p, float *__r
 
 using namespace cwac;
 
-// Kernel and tile choice shared by the forward entry points.
-static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_only, hipStream_t st) {
-  const int64_t m = p.m;
-  const int n = p.n, k = p.k;
+// Kernel and tile choice shared by the forward entry points: CWAC_KERNEL_DIRECT_LDS or the generic
+// kernel's tile (CWAC_KERNEL_GENERIC_*).  Host arithmetic on sizes only.
+static int choose_forward(int64_t m, int n, int k, int64_t ldx, int64_t ldw, int out_kind, const Tune &tune) {
   // Tile choice: the largest tile that still gives the 256 compute units at least
   // two workgroups each; small problems fall back to small tiles.
   const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
@@ -236,8 +233,8 @@ static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_o
   if (n <= 160 && tile > 128) tile = 128;
   if (n <= 80 && tile > 64) tile = 64;
   // the large-problem kernel: K a multiple of 128, or of 64 (then only its 128-token tile, which
-  // steps K by 64); 64 <= N < 256: its 256 x 128 or 256 x 64 tile
-  const bool fast_ok = m >= kFastTile && n >= 64 && (k % 64) == 0;
+  // steps K by 64); 64 <= N < 256: its 256 x 128 or 256 x 64 tile; pitches its 32-bit lane offsets hold
+  const bool fast_ok = m >= kFastTile && n >= 64 && (k % 64) == 0 && fast_pitch_ok(ldx, ldw);
   // it wants most compute units busy: 160 full tiles, or 256 half tiles
   const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   bool fast = fast_ok && n >= kFastTile && (k % kFastKStep) == 0 &&
@@ -245,38 +242,56 @@ static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_o
   if (fast_ok && n >= kFastTile && (k % kFastKStep) != 0) fast = ceil_div(m, 128) * ceil_div(n, 256) >= 160;
   if (fast_ok && n < kFastTile) fast = ceil_div(m, 256) * ceil_div(n, n < 128 ? 64 : 128) >= 160;
   if (fast_ok && n >= kFastTile && fast_prefers_quarter_tile(m, n)) fast = true;
-  // Testing / tuning knob: CWAC_FWD_TILE=256|128|64 forces a generic tile shape, "fast" forces
-  // the large-problem kernel where its shape constraints hold (results are identical).
-  if (const char *e = getenv("CWAC_FWD_TILE")) {
-    const int v = atoi(e);
-    if (v == 256 || v == 128 || v == 64) {
-      tile = v;
-      fast = false;
-    } else if (e[0] == 'f') {
-      fast = fast_ok;
-    }
+  // the caller's override (results are identical)
+  if (tune.kernel == CWAC_KERNEL_DIRECT_LDS) {
+    fast = fast_ok;
+  } else if (tune.kernel != CWAC_KERNEL_AUTO) {
+    tile = tune.kernel;
+    fast = false;
   }
-  if (fast) return launch_fast(p, out_kind, int_only, st);
-  if (tile == 256) return launch_tile<256, 256, 128, 2, 2>(p, out_kind, int_only, st);
-  if (tile == 128) return launch_tile<128, 128, 128, 2, 2>(p, out_kind, int_only, st);
+  return fast ? CWAC_KERNEL_DIRECT_LDS : tile;
+}
+
+static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_only, const Tune &tune,
+                                    hipStream_t st) {
+  const int choice = choose_forward(p.m, p.n, p.k, p.ldx, p.ldw, out_kind, tune);
+  if (choice == CWAC_KERNEL_DIRECT_LDS) return launch_fast(p, out_kind, int_only, tune.shape, st);
+  if (choice == 256) return launch_tile<256, 256, 128, 2, 2>(p, out_kind, int_only, st);
+  if (choice == 128) return launch_tile<128, 128, 128, 2, 2>(p, out_kind, int_only, st);
   return launch_tile<64, 64, 128, 2, 2>(p, out_kind, int_only, st);
 }
 
-extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
-                                            int64_t ldw, int64_t m, int32_t n, int32_t k,
-                                            const cwac_qparams *qp, const float *mult,
-                                            const int32_t *offset, const float *fbias,
-                                            const float *s_x_row, int32_t out_kind, void *out,
-                                            int64_t ldo, void *stream) {
+extern "C" int32_t cwac_forward_kernel_for(int64_t m, int32_t n, int32_t k, int64_t ldx, int64_t ldw,
+                                           int32_t out_kind, const cwac_tuning *tuning) {
+  Tune tune;
+  if (!tune_from(tuning, tune)) return CWAC_E_MODE;
+  if (out_kind != CWAC_OUT_INT8 && out_kind != CWAC_OUT_FP32 && out_kind != CWAC_OUT_INT32) return CWAC_E_MODE;
+  if (m < 1 || n < 1 || k < 16 || k > 32768 || (k % 16) != 0 || ldx < k || ldw < k) return CWAC_E_SHAPE;
+  return choose_forward(m, n, k, ldx, ldw, out_kind, tune);
+}
+
+extern "C" cwac_status qlinear_cwac_forward_ex(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                               int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                               const cwac_qparams *qp, const float *mult,
+                                               const int32_t *offset, const float *fbias,
+                                               const float *s_x_row, int32_t out_kind, void *out,
+                                               int64_t ldo, const cwac_tuning *tuning, void *stream) {
   if (!x_q || !w_q || !out) return CWAC_E_NULL;
   if (out_kind != CWAC_OUT_INT8 && out_kind != CWAC_OUT_FP32 && out_kind != CWAC_OUT_INT32)
     return CWAC_E_MODE;
+  Tune tune;
+  if (!tune_from(tuning, tune)) return CWAC_E_MODE;
   if (out_kind != CWAC_OUT_INT32 && !mult) return CWAC_E_NULL;
   if (m < 1 || m > ((int64_t)1 << 40) || n < 1 || k < 16 || k > 32768 || (k % 16) != 0)
     return CWAC_E_SHAPE;
   if (ldx < k || ldw < k || ldo < n) return CWAC_E_SHAPE;
   if (!aligned(x_q, 16) || !aligned(w_q, 16) || (ldx % 16) != 0 || (ldw % 16) != 0)
     return CWAC_E_ALIGN;
+  if (qp && out_kind != CWAC_OUT_INT32) {
+    // the vectors define the epilogue; a qp that says otherwise was folded for another one
+    if ((qp->act_per_token != 0) != (s_x_row != nullptr)) return CWAC_E_MODE;
+    if (out_kind == CWAC_OUT_INT8 && qp->mode == CWAC_EPI_FP_BIAS && !fbias) return CWAC_E_MODE;
+  }
   FwdParams p = {};
   p.x = x_q; p.w = w_q; p.ldx = ldx; p.ldw = ldw; p.ldo = ldo;
   p.m = m; p.n = n; p.k = k;
@@ -294,14 +309,28 @@ extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, cons
   if (!aligned(out, esz)) return CWAC_E_ALIGN;
   p.vec_store = ((ldo * esz) % (4 * esz) == 0) && aligned(out, 4 * esz);
   const bool int_only = (out_kind == CWAC_OUT_INT8) && !fbias && !s_x_row;
-  return dispatch_forward(p, out_kind, int_only, as_stream(stream));
+  return dispatch_forward(p, out_kind, int_only, tune, as_stream(stream));
 }
 
-extern "C" cwac_status qlinear_cwac_forward_table(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
-                                                  int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
-                                                  const float *mult, const int32_t *offset, const int8_t *table,
-                                                  int8_t *out, int64_t ldo, void *stream) {
+extern "C" cwac_status qlinear_cwac_forward(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                            int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                            const cwac_qparams *qp, const float *mult,
+                                            const int32_t *offset, const float *fbias,
+                                            const float *s_x_row, int32_t out_kind, void *out,
+                                            int64_t ldo, void *stream) {
+  return qlinear_cwac_forward_ex(x_q, ldx, w_q, ldw, m, n, k, qp, mult, offset, fbias, s_x_row, out_kind, out,
+                                 ldo, nullptr, stream);
+}
+
+extern "C" cwac_status qlinear_cwac_forward_table_ex(const int8_t *x_q, int64_t ldx, const int8_t *w_q,
+                                                     int64_t ldw, int64_t m, int32_t n, int32_t k,
+                                                     const cwac_qparams *qp, const float *mult,
+                                                     const int32_t *offset, const int8_t *table, int8_t *out,
+                                                     int64_t ldo, const cwac_tuning *tuning, void *stream) {
   if (!x_q || !w_q || !out || !qp || !mult || !table) return CWAC_E_NULL;
+  Tune tune;
+  if (!tune_from(tuning, tune)) return CWAC_E_MODE;
+  if (qp->act_per_token) return CWAC_E_MODE;  // the integer-offset epilogue has no per-row scales
   if (m < 1 || m > ((int64_t)1 << 40) || n < 16 || (n % 16) != 0 || k < 16 || k > 32768 || (k % 16) != 0)
     return CWAC_E_SHAPE;
   if (ldx < k || ldw < k || ldo < n) return CWAC_E_SHAPE;
@@ -313,15 +342,15 @@ extern "C" cwac_status qlinear_cwac_forward_table(const int8_t *x_q, int64_t ldx
   // Where the plain forward would take the direct-to-LDS kernel in one of its two large tiles, the table
   // is applied in that kernel's epilogue; elsewhere the forward is followed by a lookup pass in place.
   const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256), t_half = ceil_div(m, 128) * ceil_div(n, 256);
-  const bool fused_ok = m >= kFastTile && n >= kFastTile && (k % 64) == 0;
+  const bool fused_ok = m >= kFastTile && n >= kFastTile && (k % 64) == 0 && fast_pitch_ok(ldx, ldw);
   bool fused = fused_ok && !fast_prefers_quarter_tile(m, n);
   if (fused) fused = (k % kFastKStep) == 0 ? (t256 >= 160 || fast_prefers_half_tile(m, n, k, 1)) : t_half >= 160;
-  // the testing knob of the plain forward: "fast" forces the fused form where its shape constraints
-  // hold, a forced generic tile means two passes
-  if (const char *e = getenv("CWAC_FWD_TILE")) fused = fused_ok && e[0] == 'f';
+  // the caller's override: the direct-to-LDS kernel means the fused form where its shape constraints
+  // hold, a generic tile means two passes
+  if (tune.kernel != CWAC_KERNEL_AUTO) fused = fused_ok && tune.kernel == CWAC_KERNEL_DIRECT_LDS;
   if (!fused) {
-    const cwac_status st = qlinear_cwac_forward(x_q, ldx, w_q, ldw, m, n, k, qp, mult, offset, nullptr, nullptr,
-                                                CWAC_OUT_INT8, out, ldo, stream);
+    const cwac_status st = qlinear_cwac_forward_ex(x_q, ldx, w_q, ldw, m, n, k, qp, mult, offset, nullptr, nullptr,
+                                                   CWAC_OUT_INT8, out, ldo, tuning, stream);
     if (st != CWAC_OK) return st;
     return vit_table_lookup(out, ldo, table, out, ldo, m, n, stream);
   }
@@ -333,16 +362,27 @@ extern "C" cwac_status qlinear_cwac_forward_table(const int8_t *x_q, int64_t ldx
   p.lo = (float)(qp->qmin - qp->z_r);
   p.hi = (float)(qp->qmax - qp->z_r);
   p.code_table = table;
-  return launch_fast_table(p, as_stream(stream));
+  return launch_fast_table(p, tune.shape, as_stream(stream));
 }
 
-extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q, int32_t batch,
-                                            int32_t h, int32_t w, int32_t c_in, int32_t c_out,
-                                            int32_t kh, int32_t kw, int32_t stride, int32_t pad,
-                                            const cwac_qparams *qp, const float *mult,
-                                            const int32_t *offset, const float *fbias,
-                                            int32_t out_kind, void *out, int64_t ldo, void *stream) {
+extern "C" cwac_status qlinear_cwac_forward_table(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,
+                                                  int64_t m, int32_t n, int32_t k, const cwac_qparams *qp,
+                                                  const float *mult, const int32_t *offset, const int8_t *table,
+                                                  int8_t *out, int64_t ldo, void *stream) {
+  return qlinear_cwac_forward_table_ex(x_q, ldx, w_q, ldw, m, n, k, qp, mult, offset, table, out, ldo, nullptr,
+                                       stream);
+}
+
+extern "C" cwac_status qconv2d_cwac_forward_ex(const int8_t *x_q, const int8_t *w_q, int32_t batch,
+                                               int32_t h, int32_t w, int32_t c_in, int32_t c_out,
+                                               int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                               const cwac_qparams *qp, const float *mult,
+                                               const int32_t *offset, const float *fbias,
+                                               int32_t out_kind, void *out, int64_t ldo,
+                                               const cwac_tuning *tuning, void *stream) {
   if (!x_q || !w_q || !out || !qp) return CWAC_E_NULL;
+  Tune tune;
+  if (!tune_from(tuning, tune)) return CWAC_E_MODE;
   if (out_kind != CWAC_OUT_INT8 && out_kind != CWAC_OUT_FP32 && out_kind != CWAC_OUT_INT32)
     return CWAC_E_MODE;
   if (out_kind != CWAC_OUT_INT32 && !mult) return CWAC_E_NULL;
@@ -381,7 +421,7 @@ extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q
   if (kh == 1 && kw == 1 && stride == 1 && pad == 0) {
     // a pointwise convolution is the linear layer on the [batch * h * w, c_in] matrix
     p.ldx = c_in;
-    return dispatch_forward(p, out_kind, int_only, st);
+    return dispatch_forward(p, out_kind, int_only, tune, st);
   }
   const int64_t t256 = ceil_div(m, 256) * ceil_div(c_out, 256);
   const int64_t t128 = ceil_div(m, 128) * ceil_div(c_out, 128);
@@ -397,19 +437,26 @@ extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q
   bool fast = fast_ok && (c_out >= 256 ? ceil_div(m, 128) * ceil_div(c_out, 256)
                                       : ceil_div(m, 256) * ceil_div(c_out, c_out < 128 ? 64 : 128)) >= 64;
   if (fast_ok && c_out >= 256 && fast_prefers_quarter_tile(m, c_out)) fast = true;
-  if (const char *e = getenv("CWAC_FWD_TILE")) {  // testing / tuning knob, as for the linear layer
-    const int v = atoi(e);
-    if (v == 256 || v == 128 || v == 64) {
-      tile = v;
-      fast = false;
-    } else if (e[0] == 'f') {
-      fast = fast_ok;
-    }
+  if (tune.kernel == CWAC_KERNEL_DIRECT_LDS) {  // the caller's override, as for the linear layer
+    fast = fast_ok;
+  } else if (tune.kernel != CWAC_KERNEL_AUTO) {
+    tile = tune.kernel;
+    fast = false;
   }
-  if (fast) return launch_fast_conv(p, out_kind, int_only, st);
+  if (fast) return launch_fast_conv(p, out_kind, int_only, tune.shape, st);
   if (tile == 256) return launch_tile<256, 256, 128, 2, 2, true>(p, out_kind, int_only, st);
   if (tile == 128) return launch_tile<128, 128, 128, 2, 2, true>(p, out_kind, int_only, st);
   return launch_tile<64, 64, 128, 2, 2, true>(p, out_kind, int_only, st);
+}
+
+extern "C" cwac_status qconv2d_cwac_forward(const int8_t *x_q, const int8_t *w_q, int32_t batch,
+                                            int32_t h, int32_t w, int32_t c_in, int32_t c_out,
+                                            int32_t kh, int32_t kw, int32_t stride, int32_t pad,
+                                            const cwac_qparams *qp, const float *mult,
+                                            const int32_t *offset, const float *fbias,
+                                            int32_t out_kind, void *out, int64_t ldo, void *stream) {
+  return qconv2d_cwac_forward_ex(x_q, w_q, batch, h, w, c_in, c_out, kh, kw, stride, pad, qp, mult, offset, fbias,
+                                 out_kind, out, ldo, nullptr, stream);
 }
 
 extern "C" size_t cwac_calibrate_fused_workspace(int64_t m, int32_t n) {
@@ -418,14 +465,17 @@ extern "C" size_t cwac_calibrate_fused_workspace(int64_t m, int32_t n) {
   return (size_t)ceil_div(m, kFastTile) * kStats * (size_t)n * sizeof(double) + (size_t)n * sizeof(float);
 }
 
-extern "C" cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t ldx,
-                                                    const int8_t *w_q, int64_t ldw, int64_t m,
-                                                    int32_t n, int32_t k, const float *mult,
-                                                    const int32_t *offset, const float *fbias,
-                                                    const float *s_x_row, const float *y_full,
-                                                    int64_t ld_full, void *stats, void *workspace,
-                                                    size_t workspace_bytes, void *stream) {
+extern "C" cwac_status qlinear_cwac_calibrate_fused_ex(const int8_t *x_q, int64_t ldx,
+                                                       const int8_t *w_q, int64_t ldw, int64_t m,
+                                                       int32_t n, int32_t k, const float *mult,
+                                                       const int32_t *offset, const float *fbias,
+                                                       const float *s_x_row, const float *y_full,
+                                                       int64_t ld_full, void *stats, void *workspace,
+                                                       size_t workspace_bytes,
+                                                       const cwac_tuning *tuning, void *stream) {
   if (!x_q || !w_q || !mult || !y_full || !stats) return CWAC_E_NULL;
+  Tune tune;
+  if (!tune_from(tuning, tune)) return CWAC_E_MODE;
   if (m < kFastTile || m > ((int64_t)1 << 40) || n < kFastTile || n > 65536 || (n % 4) != 0 ||
       k < kFastKStep || k > 32768 || (k % kFastKStep) != 0)
     return CWAC_E_SHAPE;
@@ -433,8 +483,8 @@ extern "C" cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t l
   if (!aligned(x_q, 16) || !aligned(w_q, 16) || (ldx % 16) != 0 || (ldw % 16) != 0 ||
       !aligned(y_full, 16) || (ld_full % 4) != 0 || !aligned(stats, 16))
     return CWAC_E_ALIGN;
-  // per-lane byte offsets into a tile of Y_full are kept in 32 bits
-  if (ld_full > ((int64_t)1 << 26)) return CWAC_E_SHAPE;
+  // per-lane byte offsets into a tile of Y_full and into the panels are kept in 32 bits
+  if (ld_full > ((int64_t)1 << 26) || !fast_pitch_ok(ldx, ldw)) return CWAC_E_SHAPE;
   if (!workspace || workspace_bytes < cwac_calibrate_fused_workspace(m, n)) return CWAC_E_WORKSPACE;
   if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
   FwdParams p = {};
@@ -450,18 +500,34 @@ extern "C" cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t l
   row0_kernel<<<(unsigned)ceil_div(n, 4), 256, 0, st>>>(p, yq_row0);  // one channel per wavefront
   cwac_status rc = launch_status();
   if (rc != CWAC_OK) return rc;
-  rc = launch_fast_stats(p, st);
+  rc = launch_fast_stats(p, tune.stats_waves, st);
   if (rc != CWAC_OK) return rc;
-  return launch_stats_merge(p.partial, row_tiles, n, y_full, yq_row0, stats, m, st);
+  return launch_stats_merge(p.partial, row_tiles, n, y_full, yq_row0, stats, m, false, st);
 }
 
-extern "C" cwac_status qlinear_cwac_forward_fixed_point(const int8_t *x_q, int64_t ldx,
-                                                        const int8_t *w_q, int64_t ldw, int64_t m,
-                                                        int32_t n, int32_t k, const cwac_qparams *qp,
-                                                        const int32_t *m0, const int32_t *shift,
-                                                        const int32_t *offset, int8_t *out,
-                                                        int64_t ldo, void *stream) {
+extern "C" cwac_status qlinear_cwac_calibrate_fused(const int8_t *x_q, int64_t ldx,
+                                                    const int8_t *w_q, int64_t ldw, int64_t m,
+                                                    int32_t n, int32_t k, const float *mult,
+                                                    const int32_t *offset, const float *fbias,
+                                                    const float *s_x_row, const float *y_full,
+                                                    int64_t ld_full, void *stats, void *workspace,
+                                                    size_t workspace_bytes, void *stream) {
+  return qlinear_cwac_calibrate_fused_ex(x_q, ldx, w_q, ldw, m, n, k, mult, offset, fbias, s_x_row, y_full,
+                                         ld_full, stats, workspace, workspace_bytes, nullptr, stream);
+}
+
+extern "C" cwac_status qlinear_cwac_forward_fixed_point_ex(const int8_t *x_q, int64_t ldx,
+                                                           const int8_t *w_q, int64_t ldw, int64_t m,
+                                                           int32_t n, int32_t k, const cwac_qparams *qp,
+                                                           const int32_t *m0, const int32_t *shift,
+                                                           const int32_t *offset, int8_t *out,
+                                                           int64_t ldo, const cwac_tuning *tuning,
+                                                           void *stream) {
   if (!x_q || !w_q || !out || !qp || !m0 || !shift) return CWAC_E_NULL;
+  Tune tune;
+  if (!tune_from(tuning, tune)) return CWAC_E_MODE;
+  // per-row scales and an fp32 bias have no fixed-point form
+  if (qp->act_per_token || qp->mode != CWAC_EPI_INT_OFFSET) return CWAC_E_MODE;
   if (m < 1 || m > ((int64_t)1 << 40) || n < 1 || k < 16 || k > 32768 || (k % 16) != 0)
     return CWAC_E_SHAPE;
   if (ldx < k || ldw < k || ldo < n) return CWAC_E_SHAPE;
@@ -478,5 +544,15 @@ extern "C" cwac_status qlinear_cwac_forward_fixed_point(const int8_t *x_q, int64
   p.qlo = qp->qmin - qp->z_r;
   p.qhi = qp->qmax - qp->z_r;
   p.vec_store = (ldo % 4 == 0) && aligned(out, 4);
-  return dispatch_forward(p, kOutFixed, true, as_stream(stream));
+  return dispatch_forward(p, kOutFixed, true, tune, as_stream(stream));
+}
+
+extern "C" cwac_status qlinear_cwac_forward_fixed_point(const int8_t *x_q, int64_t ldx,
+                                                        const int8_t *w_q, int64_t ldw, int64_t m,
+                                                        int32_t n, int32_t k, const cwac_qparams *qp,
+                                                        const int32_t *m0, const int32_t *shift,
+                                                        const int32_t *offset, int8_t *out,
+                                                        int64_t ldo, void *stream) {
+  return qlinear_cwac_forward_fixed_point_ex(x_q, ldx, w_q, ldw, m, n, k, qp, m0, shift, offset, out, ldo, nullptr,
+                                             stream);
 }

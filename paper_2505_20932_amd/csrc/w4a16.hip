@@ -25,7 +25,6 @@
 // weight-streaming kernel further down.
 #include <hip/hip_runtime.h>
 
-#include <stdlib.h>
 
 #include "qlinear_common.h"
 
@@ -618,10 +617,10 @@ __global__ __launch_bounds__(64 * NW) void w4a16_small_m_kernel(const W4Params p
 }
 
 template <int OUT_KIND>
-cwac_status launch_w4_small(const W4Params &p, hipStream_t st) {
+cwac_status launch_w4_small(const W4Params &p, int waves, hipStream_t st) {
   // four wavefronts per workgroup; eight where there are fewer workgroups than compute units
-  const char *e = getenv("CWAC_W4_WAVES");  // tuning knob
-  const int nw = e ? atoi(e) : (p.n / 32 < 256 ? 8 : 4);
+  // (waves: the caller's override, cwac_tuning.w4_small_waves)
+  const int nw = waves ? waves : (p.n / 32 < 256 ? 8 : 4);
   if (nw == 4)
     w4a16_small_m_kernel<OUT_KIND, 4><<<dim3((unsigned)(p.n / 32)), 256, 0, st>>>(p);
   else
@@ -685,12 +684,16 @@ cwac_status cwac_fold_weight_only(const float *alpha, const float *beta, const f
   return launch_status();
 }
 
-cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const void *packed_w,
-                                       const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
-                                       const float *mult, const float *fbias, int32_t out_kind, void *out,
-                                       int64_t ldo, void *stream) {
+cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const void *packed_w,
+                                          const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
+                                          const float *mult, const float *fbias, int32_t out_kind, void *out,
+                                          int64_t ldo, const cwac_tuning *tuning, void *stream) {
   if (!x || !packed_w || !packed_sz || !out) return CWAC_E_NULL;
   if (out_kind != CWAC_OUT_FP16 && out_kind != CWAC_OUT_FP32) return CWAC_E_MODE;
+  const int w4_tile = tuning ? tuning->w4_tile : 0, small_waves = tuning ? tuning->w4_small_waves : 0;
+  if ((w4_tile != 0 && w4_tile != 256 && w4_tile != 128) ||
+      (small_waves != 0 && small_waves != 4 && small_waves != 8))
+    return CWAC_E_MODE;
   if (m < 1 || n < 256 || n % 32 != 0 || k < kGroup || k > 32768 || k % kGroup != 0 || ldx < k || ldo < n)
     return CWAC_E_SHAPE;
   const int64_t esz = out_kind == CWAC_OUT_FP16 ? 2 : 4;
@@ -713,11 +716,9 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
   p.out = static_cast<char *>(out);
   p.ldo = ldo;
   p.tiles_n = (int)ceil_div(n, 256);
-  // Tuning / testing knobs (results agree to the rounding of the fp32 sums): CWAC_W4_PIPE=tile keeps
-  // the 256-token tiles at every batch size, =half the 128-token tiles.
-  const char *e = getenv("CWAC_W4_PIPE");
-  const char knob = e ? e[0] : 0;
-  if (m <= kSmallPasses * kSmallM && knob != 't' && knob != 'h') {
+  // The caller's override (results agree to the rounding of the fp32 sums): w4_tile = 256 keeps the
+  // 256-token tiles at every batch size, 128 the 128-token tiles.
+  if (m <= kSmallPasses * kSmallM && w4_tile == 0) {
     // up to four passes of the weight-streaming kernel over blocks of 32 rows: the packed weights
     // of a layer stay in the last-level cache between passes, and a 256-token tile would leave
     // most of the chip idle at these sizes (one row of tiles, each as long as its K loop)
@@ -726,8 +727,9 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
       q.x = p.x + r0 * p.ldx_bytes;
       q.out = p.out + r0 * ldo * esz;
       q.m = m - r0 < kSmallM ? m - r0 : kSmallM;
-      const cwac_status s = out_kind == CWAC_OUT_FP16 ? launch_w4_small<CWAC_OUT_FP16>(q, as_stream(stream))
-                                                      : launch_w4_small<CWAC_OUT_FP32>(q, as_stream(stream));
+      const cwac_status s = out_kind == CWAC_OUT_FP16
+                                ? launch_w4_small<CWAC_OUT_FP16>(q, small_waves, as_stream(stream))
+                                : launch_w4_small<CWAC_OUT_FP32>(q, small_waves, as_stream(stream));
       if (s != CWAC_OK) return s;
     }
     return CWAC_OK;
@@ -736,7 +738,7 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
   // takes about two thirds of a full tile's time (the weight expansion is per channel block, not
   // per token, so it spends more vector work per MFMA), which pays exactly while the full tiles
   // would leave compute units idle
-  const bool half = knob == 'h' || (knob != 't' && ceil_div(m, 128) * p.tiles_n <= kHalfTileUpTo);
+  const bool half = w4_tile == 128 || (w4_tile == 0 && ceil_div(m, 128) * p.tiles_n <= kHalfTileUpTo);
   if (half) {
     p.tiles_m = (int)ceil_div(m, 128);
     return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16, 2>(p, as_stream(stream))
@@ -745,6 +747,14 @@ cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const voi
   p.tiles_m = (int)ceil_div(m, 256);
   return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16, 4>(p, as_stream(stream))
                                    : launch_w4<CWAC_OUT_FP32, 4>(p, as_stream(stream));
+}
+
+cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const void *packed_w,
+                                       const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
+                                       const float *mult, const float *fbias, int32_t out_kind, void *out,
+                                       int64_t ldo, void *stream) {
+  return qlinear_w4a16_cwac_forward_ex(x, ldx, packed_w, packed_sz, m, n, k, mult, fbias, out_kind, out, ldo,
+                                       nullptr, stream);
 }
 
 }  // extern "C"

@@ -17,7 +17,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "cwac.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b(?:cwac_status|size_t|const char \*)\s*\*?\s*(\w+)\s*\(", text)
+    names = re.findall(r"^(?:cwac_status|size_t|int32_t|const char \*)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
@@ -166,6 +166,79 @@ def test_argument_errors_of_the_convolution_entry_point(lib):
     per_token = binding.make_qparams(mode=1, act_per_token=True)
     assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 1, 1, C.byref(per_token), a, a, a, 0, a, 64, null) == -4
     assert f(a, a, 1, 8, 8, 16, 64, 3, 3, 1, 1, null, a, a, null, 0, a, 64, null) == -1          # qp required
+
+
+def test_mode_checks_of_the_forward(lib):
+    """A qp that contradicts the vectors defining the epilogue is refused before any launch."""
+    null = None
+    a = C.c_void_p(4096)
+    f = lib.qlinear_cwac_forward
+    per_tensor = binding.make_qparams()
+    per_token = binding.make_qparams(mode=1, act_per_token=True)
+    fp_bias = binding.make_qparams(mode=1)
+    #         x  ldx w ldw  m  n   k   qp                   mult off fbias sxrow kind out ldo
+    assert f(a, 32, a, 32, 4, 4, 32, C.byref(per_token), a, a, a, null, 0, a, 4, null) == -4   # folded per token, no row scales
+    assert f(a, 32, a, 32, 4, 4, 32, C.byref(per_tensor), a, a, null, a, 0, a, 4, null) == -4  # row scales, per-tensor qp
+    assert f(a, 32, a, 32, 4, 4, 32, C.byref(fp_bias), a, a, null, null, 0, a, 4, null) == -4  # fp-bias fold, no fbias
+    assert f(a, 32, a, 32, 4, 4, 32, C.byref(per_token), a, a, null, null, 1, a, 4, null) == -4  # fp32 output too
+    h = lib.qlinear_cwac_forward_fixed_point
+    assert h(a, 32, a, 32, 4, 4, 32, C.byref(per_token), a, a, null, a, 4, null) == -4
+    assert h(a, 32, a, 32, 4, 4, 32, C.byref(fp_bias), a, a, null, a, 4, null) == -4
+    ft = lib.qlinear_cwac_forward_table
+    assert ft(a, 64, a, 64, 256, 256, 64, C.byref(per_token), a, null, a, a, 256, null) == -4
+
+
+def test_tuning_is_validated_and_no_environment_variable_is_read(lib):
+    null = None
+    a = C.c_void_p(4096)
+    qp = binding.make_qparams()
+    for bad in (binding.make_tuning(kernel=7), binding.make_tuning(shape=6), binding.make_tuning(shape=-1),
+                binding.make_tuning(stats_waves=3)):
+        assert lib.qlinear_cwac_forward_ex(a, 32, a, 32, 4, 4, 32, C.byref(qp), a, a, null, null, 0, a, 4,
+                                           C.byref(bad), null) == -4
+        assert lib.cwac_forward_kernel_for(4, 4, 32, 32, 32, 0, C.byref(bad)) == -4
+    bad = binding.make_tuning(w4_tile=64)
+    assert lib.qlinear_w4a16_cwac_forward_ex(a, 128, a, a, 1, 256, 128, null, null, 3, a, 256, C.byref(bad),
+                                             null) == -4
+    # the dispatcher's choice is a function of sizes and the tuning argument alone
+    want = binding.cwac_forward_kernel_for(16384, 4096, 4096, 4096, 4096)
+    assert want == binding.CWAC_KERNEL_DIRECT_LDS
+    os.environ["CWAC_FWD_TILE"] = "64"
+    try:
+        assert binding.cwac_forward_kernel_for(16384, 4096, 4096, 4096, 4096) == want
+    finally:
+        del os.environ["CWAC_FWD_TILE"]
+    assert binding.cwac_forward_kernel_for(16384, 4096, 4096, 4096, 4096,
+                                     tuning=binding.make_tuning(kernel=64)) == 64
+    src = os.path.join(ROOT, "paper_2505_20932_amd", "csrc")
+    for name in os.listdir(src):
+        assert "getenv" not in open(os.path.join(src, name)).read(), name
+
+
+def test_pitches_beyond_the_32_bit_lane_offsets_leave_the_direct_to_lds_kernel(lib):
+    """The direct-to-LDS kernel forms row * pitch + chunk (rows < 256) in 32 bits; any pitch >= k is a
+    legal argument, so pitches above 2^24 must take the generic kernel (64-bit row addresses)."""
+    lds, g256 = binding.CWAC_KERNEL_DIRECT_LDS, binding.CWAC_KERNEL_GENERIC_256
+    big = (1 << 24) + 16
+    assert binding.cwac_forward_kernel_for(16384, 4096, 4096, 4096, 4096) == lds
+    assert binding.cwac_forward_kernel_for(16384, 4096, 4096, 1 << 24, 1 << 24) == lds      # 255 * 2^24 + 128 < 2^32
+    assert binding.cwac_forward_kernel_for(16384, 4096, 4096, big, 4096) == g256
+    assert binding.cwac_forward_kernel_for(16384, 4096, 4096, 4096, big) == g256
+    forced = binding.make_tuning(kernel=lds)
+    assert binding.cwac_forward_kernel_for(16384, 4096, 4096, big, 4096, tuning=forced) == g256  # forcing cannot override it
+    assert binding.cwac_forward_kernel_for(16384, 4096, 4096, 4096, 4096, tuning=forced) == lds
+    # entry points that have no generic form refuse such pitches
+    a = C.c_void_p(4096)
+    null = None
+    f = lib.qlinear_cwac_calibrate_fused
+    assert f(a, big, a, 128, 256, 256, 128, a, null, null, null, a, 256, a, a, 1 << 30, null) == -2
+    assert f(a, 128, a, big, 256, 256, 128, a, null, null, null, a, 256, a, a, 1 << 30, null) == -2
+    assert f(a, 128, a, 128, 256, 256, 128, a, null, null, null, a, (1 << 26) + 4, a, a, 1 << 30, null) == -2
+    # first-batch statistics: same checks as the accumulating call, and a first batch has rows
+    g = lib.cwac_calibrate_stats_first
+    assert g(null, 4, null, 4, 4, 4, null, null, 0, null) == -1
+    assert g(a, 4, a, 4, 0, 4, a, a, 1 << 20, null) == -2
+    assert g(a, 4, a, 4, 8, 4, a, null, 0, null) == -5
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -352,7 +352,7 @@ def _check_block_stages(orc, bk, h, t, rows):
 
 
 def _run_block(orc, seed, batch, tokens, heads, hidden, rows, head_dim=64, attn_bias=None):
-    from paper_2505_20932_amd import vit_block
+    import vit_block_fixture as vit_block
     b = vit_block.build_block(seed, batch, tokens, heads, hidden, device=DEV, head_dim=head_dim,
                               attn_bias=None if attn_bias is None else _dev(attn_bias))
     h = vit_block.residual_stream(seed, b.m, b.c, DEV)
@@ -420,7 +420,7 @@ def test_block_full_size_sampled(orc):
 def test_encoder_stack_equals_block_by_block():
     """Three blocks in one call (the residual of one block and the LN1 + quantizer of the next in one pass)
     against three single-block calls; then the same in place over the residual stream."""
-    from paper_2505_20932_amd import vit_block
+    import vit_block_fixture as vit_block
     batch, tokens, heads, hidden = 6, 197, 3, 768
     blocks = [vit_block.build_block(20 + i, batch, tokens, heads, hidden, device=DEV) for i in range(3)]
     h = vit_block.residual_stream(20, batch * tokens, 64 * heads, DEV)
@@ -447,7 +447,7 @@ def test_encoder_stack_equals_block_by_block():
 
 
 def test_block_argument_errors():
-    from paper_2505_20932_amd import vit_block
+    import vit_block_fixture as vit_block
     b = vit_block.build_block(6, 1, 16, 1, 64, device=DEV)
     h = vit_block.residual_stream(6, 16, 64, DEV)
     ws = torch.empty(P.vit_block_workspace(1, 16, 1, 64), dtype=torch.int8, device=DEV)
@@ -465,7 +465,7 @@ def test_block_argument_errors():
     (1000, 48, 64, False),        # narrow: two passes
     (256, 256, 64, True), (1000, 512, 192, True), (777, 1024, 128, True), (513, 272, 256, True),
 ])
-def test_forward_with_code_table(m, n, k, force, monkeypatch):
+def test_forward_with_code_table(m, n, k, force):
     """out = table[forward + 128], bit for bit, against the plain forward (itself checked against the
     oracle in test_gpu_parity.py) followed by numpy indexing."""
     print(f"forward with code table {m} x {n} x {k}, forced {force}", flush=True)
@@ -479,9 +479,8 @@ def test_forward_with_code_table(m, n, k, force, monkeypatch):
     plain = torch.empty(m, n, dtype=torch.int8, device=DEV)
     P.qlinear_cwac_forward(x, w, qp, mult, offset, None, None, P.CWAC_OUT_INT8, plain)
     full = torch.full((m, n + 16), 33, dtype=torch.int8, device=DEV)
-    if force:
-        monkeypatch.setenv("CWAC_FWD_TILE", "fast")
-    P.qlinear_cwac_forward_table(x, w, qp, mult, offset, _dev(table), full[:, :n])
+    P.qlinear_cwac_forward_table(x, w, qp, mult, offset, _dev(table), full[:, :n],
+                                 tuning=P.make_tuning(kernel=P.binding.CWAC_KERNEL_DIRECT_LDS) if force else None)
     torch.cuda.synchronize()
     codes = plain.cpu().numpy()
     assert np.unique(codes).size > 100                      # the codes spread over the range

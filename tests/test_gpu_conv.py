@@ -1,6 +1,5 @@
 """GPU parity of the quantized convolutional layer with the CWAC epilogue (implicit GEMM on the
 int8 matrix cores) against the CPU oracle, bit for bit, through the C ABI."""
-import os
 from types import SimpleNamespace
 
 import numpy as np
@@ -9,6 +8,7 @@ import torch
 
 import paper_2505_20932_amd as P
 from paper_2505_20932_amd import synth
+from tuning import tuning_of
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -26,16 +26,8 @@ def _conv(xq, wq, stride, pad, qp, out_kind, mult=None, offset=None, fbias=None,
     dt = {0: torch.int8, 1: torch.float32, 2: torch.int32}[out_kind]
     full = torch.full((b * oh * ow, ldo or n), 77, dtype=dt, device=DEV)
     view = full[:, :n]
-    if tile is not None:
-        os.environ["CWAC_FWD_TILE"] = str(tile)
-    if pipe is not None:
-        os.environ["CWAC_FWD_PIPE"] = pipe
-    try:
-        P.qconv2d_cwac_forward(dev(xq), dev(wq), stride, pad, qp, dev(mult), dev(offset), dev(fbias),
-                               out_kind, view)
-    finally:
-        os.environ.pop("CWAC_FWD_TILE", None)
-        os.environ.pop("CWAC_FWD_PIPE", None)
+    P.qconv2d_cwac_forward(dev(xq), dev(wq), stride, pad, qp, dev(mult), dev(offset), dev(fbias),
+                           out_kind, view, tuning=tuning_of(tile, pipe))
     torch.cuda.synchronize()
     got = full.cpu().numpy()
     if ldo:

@@ -1,7 +1,6 @@
 """GPU parity of the integer-only engine form: cwac_fold_fixed_point and
 qlinear_cwac_forward_fixed_point against the oracle, bit for bit (integer work), on every kernel
 and tile shape, edge tiles, extreme multipliers and shifts; at a full layer size on sampled rows."""
-import os
 
 import numpy as np
 import pytest
@@ -9,6 +8,7 @@ import torch
 
 import paper_2505_20932_amd as P
 from paper_2505_20932_amd import synth
+from tuning import tuning_of
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -79,12 +79,8 @@ def _forward(xq, wq, qp, m0, sh, off, tile=None, ldo=None):
     else:
         out = torch.full((m, ldo), 77, dtype=torch.int8, device=DEV)
         view = out[:, :n]
-    if tile is not None:
-        os.environ["CWAC_FWD_TILE"] = str(tile)
-    try:
-        P.qlinear_cwac_forward_fixed_point(dev(xq), dev(wq), qp, dev(m0), dev(sh), dev(off), view)
-    finally:
-        os.environ.pop("CWAC_FWD_TILE", None)
+    P.qlinear_cwac_forward_fixed_point(dev(xq), dev(wq), qp, dev(m0), dev(sh), dev(off), view,
+                                       tuning=tuning_of(tile))
     return host(out)
 
 

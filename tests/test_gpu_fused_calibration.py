@@ -67,10 +67,11 @@ def _new_state(n):
     return st
 
 
-def _fused(xq, wq, mult, off, fb, sxr, yf, st):
+def _fused(xq, wq, mult, off, fb, sxr, yf, st, waves=0):
     m, n = yf.shape
     ws = torch.empty(P.cwac_calibrate_fused_workspace(m, n), dtype=torch.uint8, device=DEV)
-    P.qlinear_cwac_calibrate_fused(xq, wq, mult, off, fb, sxr, yf, st, ws)
+    P.qlinear_cwac_calibrate_fused(xq, wq, mult, off, fb, sxr, yf, st, ws,
+                                   tuning=P.make_tuning(stats_waves=waves) if waves else None)
 
 
 def _two_calls(xq, wq, mult, off, fb, sxr, yf, st):
@@ -88,19 +89,16 @@ def _two_calls(xq, wq, mult, off, fb, sxr, yf, st):
     (513, 768, 256, True, False),       # a last row tile that keeps a single row
 ])
 @pytest.mark.parametrize("pipe", [None, "4w"])
-def test_fused_calibration_against_oracle(orc, monkeypatch, m, n, k, per_token, bias, pipe):
+def test_fused_calibration_against_oracle(orc, m, n, k, per_token, bias, pipe):
     """`pipe`: the default tile of eight wavefronts, or the four-wavefront shape of the same kernel."""
     print(f"fused calibration {m} x {n} x {k} per_token={per_token} bias={bias} pipe={pipe}", flush=True)
-    if pipe:
-        monkeypatch.setenv("CWAC_STATS_PIPE", pipe)
-    else:
-        monkeypatch.delenv("CWAC_STATS_PIPE", raising=False)
+    waves = 4 if pipe == "4w" else 0
     xq, wq, mult, off, fb, sxr, yq, yf = _inputs(orc, 4100 + m, m, n, k, per_token, bias)
     ref = orc.channel_moments(yf, yq)
     a0, b0, _ = orc.solve(ref)
     d = [dev(v) for v in (xq, wq, mult, off, fb, sxr, yf)]
     st = _new_state(n)
-    _fused(*d, st)
+    _fused(*d, st, waves)
     alpha, beta, mom = _solve(st, n)
     _check_moments(mom, ref)
     sf = np.sqrt(ref[4])
@@ -114,7 +112,7 @@ def test_fused_calibration_against_oracle(orc, monkeypatch, m, n, k, per_token, 
     _check_moments(mom, mom2, rtol=1e-9)
     # bit-reproducible
     st3 = _new_state(n)
-    _fused(*d, st3)
+    _fused(*d, st3, waves)
     words = P.cwac_stats_bytes(n) // 8                   # the buffers carry spare words
     assert torch.equal(st[:words], st3[:words])
 

@@ -90,10 +90,10 @@ def test_step_replays_from_a_graph(orc):
                                   orc.folded_forward(acc, off.cpu().numpy(), mult.cpu().numpy(), zr))
 
 
-def test_weight_only_and_convolution_replay_from_a_graph(monkeypatch):
+def test_weight_only_and_convolution_replay_from_a_graph():
     """The weight-only INT4 entry points and the convolution launch only kernels too."""
     # the wide convolution below is too small for the dispatcher to pick the direct-to-LDS kernel
-    monkeypatch.setenv("CWAC_FWD_TILE", "fast")
+    lds = P.make_tuning(kernel=P.binding.CWAC_KERNEL_DIRECT_LDS)
     f32 = dict(dtype=torch.float32, device=DEV)
     m, n, k = 300, 512, 384
     w = synth.normal(3, 0, n * k, device=DEV).view(n, k) * 0.02
@@ -130,8 +130,8 @@ def test_weight_only_and_convolution_replay_from_a_graph(monkeypatch):
         P.cwac_fold_weight_only(alpha, beta, None, mult, fb)
         P.qlinear_w4a16_cwac_forward(x, pw, psz, n, mult, fb, out)
         P.qlinear_w4a16_cwac_forward(x[:8], pw, psz, n, mult, fb, out8)
-        P.qconv2d_cwac_forward(xc, wc, 1, 1, qp, cm, co, None, P.CWAC_OUT_INT8, outc)
-        P.qconv2d_cwac_forward(xw, ww, 1, 1, qp, wm, wo, None, P.CWAC_OUT_INT8, outw)
+        P.qconv2d_cwac_forward(xc, wc, 1, 1, qp, cm, co, None, P.CWAC_OUT_INT8, outc, tuning=lds)
+        P.qconv2d_cwac_forward(xw, ww, 1, 1, qp, wm, wo, None, P.CWAC_OUT_INT8, outw, tuning=lds)
 
     def load(seed):
         x.copy_(synth.normal(seed, 0, m * k, device=DEV).view(m, k))
@@ -162,7 +162,7 @@ def test_weight_only_and_convolution_replay_from_a_graph(monkeypatch):
 
 def test_transformer_block_replays_from_a_graph():
     """vit_block_w8a8_forward is kernel launches and nothing else."""
-    from paper_2505_20932_amd import vit_block
+    import vit_block_fixture as vit_block
     batch, tokens, heads, hidden = 4, 50, 2, 256
     blk = vit_block.build_block(9, batch, tokens, heads, hidden, device=DEV)
     h = vit_block.residual_stream(9, blk.m, blk.c, DEV)

@@ -1,7 +1,6 @@
 """GPU parity at low bit widths (W4A4, W6A6; codes in int8 containers): the b-bit quantizers and
 the whole pipeline - calibration forward, statistics, fit, fold, folded forward with a b-bit
 output range - against the oracle, through the C ABI."""
-import os
 
 import numpy as np
 import pytest
@@ -9,6 +8,7 @@ import torch
 
 import paper_2505_20932_amd as P
 from paper_2505_20932_amd import synth
+from tuning import tuning_of
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -55,15 +55,10 @@ def test_low_bit_pipeline(orc, bits, fast):
     wl = synth.WORKLOADS[1]
     half, qmin, qmax = 1 << (bits - 1), -(1 << (bits - 1)), (1 << (bits - 1)) - 1
     m, cal = (512, 768) if fast else (197, 1024)
-    if fast:
-        os.environ["CWAC_FWD_TILE"] = "fast"
-    try:
-        _pipeline(orc, wl, bits, half, qmin, qmax, m, cal)
-    finally:
-        os.environ.pop("CWAC_FWD_TILE", None)
+    _pipeline(orc, wl, bits, half, qmin, qmax, m, cal, tuning_of("fast") if fast else None)
 
 
-def _pipeline(orc, wl, bits, half, qmin, qmax, m, cal):
+def _pipeline(orc, wl, bits, half, qmin, qmax, m, cal, tun=None):
     w_t, b_t = synth.weights(wl, 0)
     w, bias = w_t.numpy(), b_t.numpy()
     n, k = w.shape
@@ -102,7 +97,7 @@ def _pipeline(orc, wl, bits, half, qmin, qmax, m, cal):
     P.cwac_fold(None, None, sw, dev(bias), colsum,
                 P.make_qparams(P.CWAC_EPI_FP_BIAS, False, float(s0), zx, 1.0, 0), dm, do, dfb)
     yq = torch.empty(cal, n, **f32)
-    P.qlinear_cwac_forward(xqc, wq, None, dm, do, dfb, None, P.CWAC_OUT_FP32, yq)
+    P.qlinear_cwac_forward(xqc, wq, None, dm, do, dfb, None, P.CWAC_OUT_FP32, yq, tuning=tun)
     np.testing.assert_array_equal(host(yq), yq0)
     st = torch.empty(P.cwac_stats_bytes(n) // 8 + 2, dtype=torch.float64, device=DEV)
     P.cwac_stats_reset(st, n)
@@ -123,7 +118,7 @@ def _pipeline(orc, wl, bits, half, qmin, qmax, m, cal):
     np.testing.assert_array_equal(host(mult), m1)
     np.testing.assert_array_equal(host(off), o1)
     out = torch.empty(m, n, dtype=torch.int8, device=DEV)
-    P.qlinear_cwac_forward(xq, wq, qp, mult, off, None, None, P.CWAC_OUT_INT8, out)
+    P.qlinear_cwac_forward(xq, wq, qp, mult, off, None, None, P.CWAC_OUT_INT8, out, tuning=tun)
     acc = orc.gemm_i8(xq0, wq0)
     want = orc.folded_forward(acc, o1, m1, zr, None, None, qmin, qmax)
     got = host(out)
@@ -133,6 +128,6 @@ def _pipeline(orc, wl, bits, half, qmin, qmax, m, cal):
     m0 = torch.empty(n, dtype=torch.int32, device=DEV)
     sh = torch.empty(n, dtype=torch.int32, device=DEV)
     P.cwac_fold_fixed_point(alpha, beta, sw, dev(bias), colsum, qp, m0, sh, off)
-    P.qlinear_cwac_forward_fixed_point(xq, wq, qp, m0, sh, off, out)
+    P.qlinear_cwac_forward_fixed_point(xq, wq, qp, m0, sh, off, out, tuning=tun)
     q0, s1, o2, _ = orc.fold_fixed_point(a, b, sw0, bias, cs0, s0, zx, sr0)
     np.testing.assert_array_equal(host(out), orc.fixed_point_forward(acc, o2, q0, s1, zr, qmin, qmax))

@@ -2,7 +2,6 @@
 same seeded inputs, through the C ABI.  Integer results (codes, accumulators,
 offsets) must be bit-exact; fp32 statistics and (alpha, beta) within 1e-5
 relative (scale-aware where the reference is near zero)."""
-import os
 
 import numpy as np
 import pytest
@@ -11,6 +10,7 @@ import torch
 import paper_2505_20932_amd as P
 from paper_2505_20932_amd import synth
 from cases import build_case
+from tuning import tuning_of
 
 pytestmark = pytest.mark.gpu
 
@@ -129,16 +129,8 @@ def _forward(c, out_kind, mult=None, offset=None, fbias=None, sx_row=None, qp=No
     else:
         out = torch.full((m, ldo), 77, dtype=dt, device=DEV)
         view = out[:, :c.n]
-    if tile is not None:
-        os.environ["CWAC_FWD_TILE"] = str(tile)
-    if pipe:
-        os.environ["CWAC_FWD_PIPE"] = pipe
-    try:
-        P.qlinear_cwac_forward(dev(xq), dev(c.wq), qp, dev(mult), dev(offset), dev(fbias),
-                               dev(sx_row), out_kind, view)
-    finally:
-        os.environ.pop("CWAC_FWD_TILE", None)
-        os.environ.pop("CWAC_FWD_PIPE", None)
+    P.qlinear_cwac_forward(dev(xq), dev(c.wq), qp, dev(mult), dev(offset), dev(fbias),
+                           dev(sx_row), out_kind, view, tuning=tuning_of(tile, pipe))
     return host(out)
 
 
@@ -200,6 +192,7 @@ def test_forward_ragged_shapes(orc, m, n, k):
     from types import SimpleNamespace
     c = SimpleNamespace(xq=xq, wq=wq, n=n)
     qp = P.make_qparams(z_r=-3)
+    qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, z_r=-3)      # per-row scales, fp bias
     for tile in (64, 128, 256):
         for ldo in (None, n + 3):
             got = _forward(c, P.CWAC_OUT_INT32, tile=tile, ldo=ldo)
@@ -208,7 +201,7 @@ def test_forward_ragged_shapes(orc, m, n, k):
                 assert np.all(got[:, n:] == 77)          # nothing written past N
             got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, tile=tile, ldo=ldo)
             np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, -3))
-            got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qp, tile=tile,
+            got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, tile=tile,
                            ldo=ldo)
             np.testing.assert_array_equal(got[:, :n],
                                           orc.folded_forward(acc, off, mult, -3, fb, sxr))
@@ -244,6 +237,7 @@ def test_forward_large_tile_kernel(orc, m, n, k, pipe):
     from types import SimpleNamespace
     c = SimpleNamespace(xq=xq, wq=wq, n=n)
     qp = P.make_qparams(z_r=5)
+    qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, z_r=5)
     for ldo in (None, n + 5):
         got = _forward(c, P.CWAC_OUT_INT32, tile="fast", ldo=ldo, pipe=pipe)
         np.testing.assert_array_equal(got[:, :n], acc)
@@ -251,7 +245,7 @@ def test_forward_large_tile_kernel(orc, m, n, k, pipe):
             assert np.all(got[:, n:] == 77)
         got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, tile="fast", ldo=ldo, pipe=pipe)
         np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5))
-        got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qp, tile="fast",
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, tile="fast",
                        ldo=ldo, pipe=pipe)
         np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5, fb, sxr))
         _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)

@@ -2,13 +2,13 @@
 size thresholds and divisibility; whatever they pick, integer results must equal the oracle's bit
 for bit.  Every shape runs in the automatic choice and, where the direct-to-LDS kernel's
 constraints hold, with that kernel forced."""
-import os
 
 import numpy as np
 import pytest
 import torch
 
 import paper_2505_20932_amd as P
+from tuning import tuning_of
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -19,9 +19,8 @@ def dev(a):
 
 
 def _knobs(force_fast):
-    os.environ.pop("CWAC_FWD_TILE", None)
-    if force_fast:
-        os.environ["CWAC_FWD_TILE"] = "fast"
+    """The kernel-choice override of a forward call: the direct-to-LDS kernel forced, or none."""
+    return tuning_of("fast") if force_fast else None
 
 
 def _linear_shapes():
@@ -51,11 +50,11 @@ def test_linear_random_shape(orc, m, n, k):
     qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, 1.0, 0, 1.0, zr)
     ldo = n + int(rng.integers(0, 3)) * 4
     for force_fast in (False, True):
-        _knobs(force_fast)
-        try:
+        tun = _knobs(force_fast)
+        if True:
             def run(out_kind, dt, *args):
                 full = torch.full((m, ldo), 55, dtype=dt, device=DEV)
-                P.qlinear_cwac_forward(dev(xq), dev(wq), *args, out_kind, full[:, :n])
+                P.qlinear_cwac_forward(dev(xq), dev(wq), *args, out_kind, full[:, :n], tuning=tun)
                 torch.cuda.synchronize()
                 got = full.cpu().numpy()
                 assert np.all(got[:, n:] == 55), "wrote outside the output columns"
@@ -74,8 +73,6 @@ def test_linear_random_shape(orc, m, n, k):
             _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)
             np.testing.assert_array_equal(
                 run(P.CWAC_OUT_FP32, torch.float32, None, dev(mult), dev(off), dev(fb), dev(sxr)), want)
-        finally:
-            _knobs(False)
 
 
 def _conv_shapes():
@@ -108,11 +105,11 @@ def test_conv_random_shape(orc, shape):
     fb = rng.standard_normal(n).astype(np.float32)
     qp = P.make_qparams(z_x=zx, z_r=zr)
     for force_fast in (False, True):
-        _knobs(force_fast)
-        try:
+        tun = _knobs(force_fast)
+        if True:
             def run(out_kind, dt, *args):
                 out = torch.empty(m, n, dtype=dt, device=DEV)
-                P.qconv2d_cwac_forward(dev(xq), dev(wq), stride, pad, qp, *args, out_kind, out)
+                P.qconv2d_cwac_forward(dev(xq), dev(wq), stride, pad, qp, *args, out_kind, out, tuning=tun)
                 torch.cuda.synchronize()
                 return out.cpu().numpy()
             np.testing.assert_array_equal(run(P.CWAC_OUT_INT32, torch.int32, None, dev(off), None), acc + off[None, :])
@@ -122,8 +119,6 @@ def test_conv_random_shape(orc, shape):
                                           orc.folded_forward(acc, off, mult, zr, fb))
             _, want = orc.folded_forward(acc, off, mult, 0, fb, want_f32=True)
             np.testing.assert_array_equal(run(P.CWAC_OUT_FP32, torch.float32, dev(mult), dev(off), dev(fb)), want)
-        finally:
-            _knobs(False)
 
 
 def _w4_shapes():
@@ -157,17 +152,12 @@ def test_weight_only_random_shape(m, n, k):
     psz = torch.empty((k // 128) * n, dtype=torch.int32, device=DEV)
     P.cwac_w4_pack(dev(codes), dev(scales), dev(zeros), pw, psz)
     for pipe in (None, "tile", "half"):
-        os.environ.pop("CWAC_W4_PIPE", None)
-        if pipe:
-            os.environ["CWAC_W4_PIPE"] = pipe
-        try:
-            out = torch.empty(m, n, dtype=torch.float32, device=DEV)
-            P.qlinear_w4a16_cwac_forward(dev(x16), pw, psz, n, dev(mult), dev(fbias), out)
-            outh = torch.empty(m, n, dtype=torch.float16, device=DEV)
-            P.qlinear_w4a16_cwac_forward(dev(x16), pw, psz, n, dev(mult), dev(fbias), outh)
-            torch.cuda.synchronize()
-        finally:
-            os.environ.pop("CWAC_W4_PIPE", None)
+        tun = tuning_of(w4_pipe=pipe)
+        out = torch.empty(m, n, dtype=torch.float32, device=DEV)
+        P.qlinear_w4a16_cwac_forward(dev(x16), pw, psz, n, dev(mult), dev(fbias), out, tuning=tun)
+        outh = torch.empty(m, n, dtype=torch.float16, device=DEV)
+        P.qlinear_w4a16_cwac_forward(dev(x16), pw, psz, n, dev(mult), dev(fbias), outh, tuning=tun)
+        torch.cuda.synchronize()
         np.testing.assert_array_equal(out.cpu().numpy(), o32)
         np.testing.assert_array_equal(outh.cpu().numpy().view(np.uint16), o16.view(np.uint16))
 

@@ -16,6 +16,7 @@ import torch
 
 import paper_2505_20932_amd as P
 from paper_2505_20932_amd import synth
+from tuning import tuning_of
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -48,12 +49,8 @@ def _forward(x16, pw, psz, n, mult, fbias, dtype, ldo=None, pipe=None):
     else:
         full = torch.full((m, ldo), 7.0, dtype=dtype, device=DEV)
         out = full[:, :n]
-    if pipe:
-        os.environ["CWAC_W4_PIPE"] = pipe
-    try:
-        P.qlinear_w4a16_cwac_forward(_dev(x16), pw, psz, n, _dev(mult), _dev(fbias), out)
-    finally:
-        os.environ.pop("CWAC_W4_PIPE", None)
+    P.qlinear_w4a16_cwac_forward(_dev(x16), pw, psz, n, _dev(mult), _dev(fbias), out,
+                                 tuning=tuning_of(w4_pipe=pipe))
     torch.cuda.synchronize()
     if ldo is not None:
         assert (full[:, n:] == 7.0).all(), "wrote outside the output columns"

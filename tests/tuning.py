@@ -1,0 +1,19 @@
+"""Kernel-choice overrides for the GPU tests: the forced tile / pipeline names the tests use,
+as cwac_tuning structs for the ``tuning=`` argument of the binding (the _ex entry points)."""
+import paper_2505_20932_amd as P
+
+_B = P.binding
+_SHAPES = {"8w": _B.CWAC_SHAPE_256_8W, "128x2": _B.CWAC_SHAPE_256_4W_K128, "64x4": _B.CWAC_SHAPE_256_4W_K64,
+           "duo": _B.CWAC_SHAPE_128_PAIR, "q": _B.CWAC_SHAPE_128_128}
+
+
+def tuning_of(tile=None, pipe=None, w4_pipe=None, stats_waves=0):
+    """tile: None | 64 | 128 | 256 (generic kernel with that tile) | "fast" (direct-to-LDS kernel);
+    pipe: None | "8w" | "128x2" | "64x4" | "duo" | "q" (its tile shape);
+    w4_pipe: None | "tile" | "half" (weight-only layer: 256- / 128-token tiles at every batch size).
+    Returns None when nothing is forced (the plain entry point is then called)."""
+    if tile is None and pipe is None and w4_pipe is None and not stats_waves:
+        return None
+    kernel = 0 if tile is None else (_B.CWAC_KERNEL_DIRECT_LDS if tile == "fast" else int(tile))
+    return P.make_tuning(kernel=kernel, shape=_SHAPES[pipe] if pipe else 0, stats_waves=stats_waves,
+                         w4_tile={None: 0, "tile": 256, "half": 128}[w4_pipe])

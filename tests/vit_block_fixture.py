@@ -1,4 +1,4 @@
-"""Set-up of one W8A8 Vision Transformer block for ``vit_block_w8a8_forward``.
+"""Test and benchmark fixture: set-up of one W8A8 Vision Transformer block for ``vit_block_w8a8_forward``.
 
 The floating-point block (the model upstream of the method) is evaluated with torch on the
 device to obtain the ranges of the tensors that get quantized; every step of the method itself
@@ -14,8 +14,8 @@ from typing import Dict, List
 import torch
 import torch.nn.functional as F
 
-from . import binding as B
-from . import synth
+from paper_2505_20932_amd import binding as B
+from paper_2505_20932_amd import synth
 
 LAYERS = ("qkv", "proj", "fc1", "fc2")
 
