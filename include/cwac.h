@@ -10,7 +10,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
  *     device work is enqueued asynchronously on it; no call synchronizes.
  *   - The library allocates no device memory and keeps no state between calls;
- *     scratch space is passed in as an explicit workspace.  It reads no environment
+ *     scratch space is passed in as an explicit workspace (one entry point,
+ *     cwac_calibrate_stats_static, uses a fixed buffer of the library's own instead and says so).
+ *     It reads no environment
  *     variable: where several kernels compute the same result, the choice is the
  *     library's unless the caller passes a cwac_tuning to an _ex entry point.
  *   - Errors are reported through the return value; when a call returns an error
@@ -149,6 +151,26 @@ cwac_status cwac_calibrate_stats(const float *y_full, int64_t ld_full, const flo
 cwac_status cwac_calibrate_stats_first(const float *y_full, int64_t ld_full, const float *y_quant,
                                        int64_t ld_quant, int64_t n_rows, int32_t c_out, void *stats,
                                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* cwac_calibrate_stats for callers that cannot allocate device memory or carry a workspace -
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: the partial
+ * sums go to a fixed buffer of cwac_static_scratch_bytes() = 8 MiB that is part of the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends).  The
+ * call allocates nothing, frees nothing and computes exactly what cwac_calibrate_stats computes
+ * (same kernels, same split: the state is bit-identical).
+ *   - Sizes whose partial sums would not fit return CWAC_E_WORKSPACE (nothing launched); with the
+ *     present row split every n_rows and c_out <= 65536 needs at most 7.5 MiB.
+ *   - All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it.  Serialize them, or use cwac_calibrate_stats with
+ *     workspaces of your own.  Nothing needs clearing between calls: a call writes every partial
+ *     sum it later reads.
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress, not an
+ *     allocation); make that first call outside a stream capture.
+ * Arguments and the other errors as cwac_calibrate_stats. */
+size_t cwac_static_scratch_bytes(void);
+cwac_status cwac_calibrate_stats_static(const float *y_full, int64_t ld_full, const float *y_quant,
+                                        int64_t ld_quant, int64_t n_rows, int32_t c_out, void *stats,
+                                        void *stream);
 
 /* Eq. 4-5 per channel from the state, evaluated in fp64 and rounded to fp32:
  *   alpha = Cov(Y_full, Y_quant) / Var(Y_quant),  beta = E[Y_full] - alpha E[Y_quant].

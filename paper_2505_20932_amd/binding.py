@@ -40,6 +40,7 @@ EXPORTS = (
     "qlinear_cwac_forward_ex", "qlinear_cwac_forward_table_ex", "qconv2d_cwac_forward_ex",
     "qlinear_cwac_calibrate_fused_ex", "qlinear_cwac_forward_fixed_point_ex",
     "qlinear_w4a16_cwac_forward_ex", "cwac_forward_kernel_for",
+    "cwac_static_scratch_bytes", "cwac_calibrate_stats_static",
 )
 
 
@@ -131,6 +132,8 @@ def lib() -> C.CDLL:
             "vit_encoder_w8a8_forward": (i32, [C.POINTER(vit_block_params), i32, vp, vp, vp, sz, vp]),
         }
         sig["cwac_calibrate_stats_first"] = sig["cwac_calibrate_stats"]
+        sig["cwac_static_scratch_bytes"] = (sz, [])
+        sig["cwac_calibrate_stats_static"] = (i32, [vp, i64, vp, i64, i64, i32, vp, vp])
         sig["cwac_forward_kernel_for"] = (i32, [i64, i32, i32, i64, i64, i32, tup])
         for name in ("qlinear_cwac_forward", "qlinear_cwac_forward_table", "qconv2d_cwac_forward",
                      "qlinear_cwac_calibrate_fused", "qlinear_cwac_forward_fixed_point",
@@ -261,6 +264,21 @@ def cwac_calibrate_stats(y_full: torch.Tensor, y_quant: torch.Tensor, stats: tor
     _check(fn(_ptr(y_full), _rowmajor(y_full), _ptr(y_quant), _rowmajor(y_quant), n_rows, c_out,
               _ptr(stats), _ptr(workspace), workspace.numel() * workspace.element_size(),
               _stream(stream)), "cwac_calibrate_stats_first" if first else "cwac_calibrate_stats")
+
+
+def cwac_static_scratch_bytes() -> int:
+    return int(lib().cwac_static_scratch_bytes())
+
+
+def cwac_calibrate_stats_static(y_full: torch.Tensor, y_quant: torch.Tensor, stats: torch.Tensor,
+                                stream=None):
+    """cwac_calibrate_stats on the library's own fixed scratch buffer: no workspace, no allocation."""
+    assert y_full.dtype == torch.float32 and y_quant.dtype == torch.float32
+    assert y_full.shape == y_quant.shape
+    n_rows, c_out = y_full.shape
+    _check(lib().cwac_calibrate_stats_static(_ptr(y_full), _rowmajor(y_full), _ptr(y_quant),
+                                             _rowmajor(y_quant), n_rows, c_out, _ptr(stats),
+                                             _stream(stream)), "cwac_calibrate_stats_static")
 
 
 def cwac_calibrate_stats_first(y_full, y_quant, stats, workspace, stream=None):

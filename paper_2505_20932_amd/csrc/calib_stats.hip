@@ -8,6 +8,8 @@
 // sums (the four wavefronts of a workgroup add theirs up through LDS first).  Sums are taken of pivot-shifted values
 // in fp64, so channels whose mean dwarfs their spread lose no precision, and in a
 // fixed order (no floating-point atomics), so results are bit-reproducible.
+#include <mutex>
+
 #include "cwac_internal.h"
 
 namespace cwac {
@@ -446,6 +448,48 @@ extern "C" cwac_status cwac_calibrate_stats_first(const float *y_full, int64_t l
   if (!aligned(workspace, 16)) return CWAC_E_ALIGN;
   return calibrate_stats_impl(y_full, ld_full, y_quant, ld_quant, n_rows, c_out, stats,
                               static_cast<double *>(workspace), true, as_stream(stream));
+}
+
+// ---- statistics for callers that cannot allocate: the partial sums go to a buffer that is part of
+// the library's device image.  Each GPU holds its own copy of the array at its own address; host
+// code never uses the array's name as an address, only the per-device pointer looked up below.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on device i, once looked up
+
+static cwac_status static_scratch(double **out) {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return CWAC_E_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return CWAC_E_LAUNCH;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = static_cast<double *>(g_scratch_ptr[device]);
+  return CWAC_OK;
+}
+
+extern "C" size_t cwac_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" cwac_status cwac_calibrate_stats_static(const float *y_full, int64_t ld_full,
+                                                   const float *y_quant, int64_t ld_quant,
+                                                   int64_t n_rows, int32_t c_out, void *stats,
+                                                   void *stream) {
+  const cwac_status rc = calibrate_stats_check(y_full, ld_full, y_quant, ld_quant, n_rows, c_out, stats);
+  if (rc != CWAC_OK || n_rows == 0) return rc;
+  if (cwac_calibrate_stats_workspace(n_rows, c_out) > kStaticScratchBytes) return CWAC_E_WORKSPACE;
+  double *partial = nullptr;
+  const cwac_status rs = static_scratch(&partial);
+  if (rs != CWAC_OK) return rs;
+  // every partial sum the merge reads is written by this call's first kernel: nothing to clear
+  return calibrate_stats_impl(y_full, ld_full, y_quant, ld_quant, n_rows, c_out, stats, partial, false,
+                              as_stream(stream));
 }
 
 extern "C" cwac_status cwac_solve(const void *stats, int32_t c_out, double var_eps, float *alpha,
