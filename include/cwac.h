@@ -574,7 +574,10 @@ enum {
   CWAC_SHAPE_256_4W_K128 = 2, /* the same tile, four wavefronts, K steps of 128, two stages */
   CWAC_SHAPE_256_4W_K64 = 3,  /* four wavefronts, K steps of 64, four stages */
   CWAC_SHAPE_128_PAIR = 4,    /* 128 tokens x 256 channels, two workgroups per compute unit */
-  CWAC_SHAPE_128_128 = 5      /* 128 x 128, four wavefronts of 64 x 64 */
+  CWAC_SHAPE_128_128 = 5,     /* 128 x 128, four wavefronts of 64 x 64 */
+  CWAC_SHAPE_256_PERSIST = 6  /* CWAC_SHAPE_256_8W's tile on persistent workgroups, one per compute unit, the
+                                 next tile's first loads in flight under a tile's epilogue (linear layers with
+                                 int8 / fp32 / int32 output; other calls take CWAC_SHAPE_256_8W) */
 };
 typedef struct cwac_tuning {
   int32_t kernel;         /* CWAC_KERNEL_*: int8 linear / convolution / table / fixed-point forwards */
@@ -584,7 +587,9 @@ typedef struct cwac_tuning {
   int32_t w4_tile;        /* qlinear_w4a16_cwac_forward_ex: 0 | 256 | 128: the tiled kernel with that
                              many tokens per tile at every batch size */
   int32_t w4_small_waves; /* ... its weight-streaming kernel (m <= 128): 0 | 4 | 8 wavefronts per workgroup */
-  int32_t reserved[3];    /* zero */
+  int32_t persist_workgroups; /* CWAC_SHAPE_256_PERSIST: 0 = one workgroup per compute unit; n > 0 = at most n
+                                 (each then walks more tiles; leaves compute units to concurrent work) */
+  int32_t reserved[2];    /* zero */
 } cwac_tuning;
 
 /* Which kernel qlinear_cwac_forward(_ex) would run for these sizes and this tuning (host

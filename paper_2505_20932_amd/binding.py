@@ -22,7 +22,7 @@ CWAC_W4_GROUP = 128
 CWAC_KERNEL_AUTO, CWAC_KERNEL_DIRECT_LDS = 0, 1
 CWAC_KERNEL_GENERIC_64, CWAC_KERNEL_GENERIC_128, CWAC_KERNEL_GENERIC_256 = 64, 128, 256
 (CWAC_SHAPE_AUTO, CWAC_SHAPE_256_8W, CWAC_SHAPE_256_4W_K128, CWAC_SHAPE_256_4W_K64, CWAC_SHAPE_128_PAIR,
- CWAC_SHAPE_128_128) = range(6)
+ CWAC_SHAPE_128_128, CWAC_SHAPE_256_PERSIST) = range(7)
 
 EXPORTS = (
     "cwac_status_string", "cwac_range_workspace", "cwac_range_f32", "cwac_qparams_from_range",
@@ -52,7 +52,8 @@ class cwac_qparams(C.Structure):
 
 class cwac_tuning(C.Structure):
     _fields_ = [("kernel", C.c_int32), ("shape", C.c_int32), ("stats_waves", C.c_int32),
-                ("w4_tile", C.c_int32), ("w4_small_waves", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("w4_tile", C.c_int32), ("w4_small_waves", C.c_int32), ("persist_workgroups", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
 
 
 class vit_block_layer(C.Structure):
@@ -170,9 +171,11 @@ def _rowmajor(t: torch.Tensor) -> int:
     return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
 
 
-def make_tuning(kernel=0, shape=0, stats_waves=0, w4_tile=0, w4_small_waves=0) -> cwac_tuning:
+def make_tuning(kernel=0, shape=0, stats_waves=0, w4_tile=0, w4_small_waves=0,
+                persist_workgroups=0) -> cwac_tuning:
     """Kernel choice override for the ``tuning=`` argument of the forward calls (same results)."""
-    return cwac_tuning(int(kernel), int(shape), int(stats_waves), int(w4_tile), int(w4_small_waves))
+    return cwac_tuning(int(kernel), int(shape), int(stats_waves), int(w4_tile), int(w4_small_waves),
+                       int(persist_workgroups))
 
 
 def _tun(tuning: Optional[cwac_tuning]):

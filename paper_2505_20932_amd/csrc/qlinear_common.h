@@ -216,7 +216,7 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 
 // Kernel choice override of the _ex entry points (cwac.h: cwac_tuning), validated.
 struct Tune {
-  int kernel = CWAC_KERNEL_AUTO, shape = CWAC_SHAPE_AUTO, stats_waves = 0;
+  int kernel = CWAC_KERNEL_AUTO, shape = CWAC_SHAPE_AUTO, stats_waves = 0, persist_workgroups = 0;
 };
 // False where a field holds a value outside its list (the entry point returns CWAC_E_MODE).
 inline bool tune_from(const cwac_tuning *t, Tune &o) {
@@ -225,11 +225,13 @@ inline bool tune_from(const cwac_tuning *t, Tune &o) {
   if (t->kernel != CWAC_KERNEL_AUTO && t->kernel != CWAC_KERNEL_DIRECT_LDS && t->kernel != CWAC_KERNEL_GENERIC_64 &&
       t->kernel != CWAC_KERNEL_GENERIC_128 && t->kernel != CWAC_KERNEL_GENERIC_256)
     return false;
-  if (t->shape < CWAC_SHAPE_AUTO || t->shape > CWAC_SHAPE_128_128) return false;
+  if (t->shape < CWAC_SHAPE_AUTO || t->shape > CWAC_SHAPE_256_PERSIST) return false;
   if (t->stats_waves != 0 && t->stats_waves != 4 && t->stats_waves != 8) return false;
   o.kernel = t->kernel;
   o.shape = t->shape;
   o.stats_waves = t->stats_waves;
+  if (t->persist_workgroups < 0) return false;
+  o.persist_workgroups = t->persist_workgroups;
   return true;
 }
 
@@ -239,8 +241,8 @@ constexpr int64_t kFastMaxPitch = (int64_t)1 << 24;
 inline bool fast_pitch_ok(int64_t ldx, int64_t ldw) { return ldx <= kFastMaxPitch && ldw <= kFastMaxPitch; }
 
 // Large-problem kernel (qlinear_fast.hip).  Requires m >= 256, n >= 64, k % 64 == 0 (its 256 x 256
-// tile: n >= 256 and k % 128 == 0) and fast_pitch_ok(ldx, ldw).  `shape`: CWAC_SHAPE_* (0 = by cost model).
-cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, int shape, hipStream_t st);
+// tile: n >= 256 and k % 128 == 0) and fast_pitch_ok(ldx, ldw).  tune.shape: CWAC_SHAPE_* (0 = by cost model).
+cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, const Tune &tune, hipStream_t st);
 // The integer-offset int8 forward with p.code_table applied to every output code (kOutTable); shapes as
 // launch_fast with n >= 256.
 cwac_status launch_fast_table(FwdParams p, int shape, hipStream_t st);

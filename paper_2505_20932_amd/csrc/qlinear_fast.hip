@@ -44,6 +44,20 @@ struct PadCodes {
 };
 __device__ __attribute__((aligned(16))) const PadCodes kPadCodes{};
 
+#ifdef CWAC_V_STAMP
+// timing probe (development builds only): 100 MHz time stamps of every wavefront at five points
+__device__ unsigned long long g_stamps[4096 * 8 * 5];
+#define CWAC_STAMP(i)                                                                                  \
+  if (blockIdx.x < 4096 && (threadIdx.x & 63) == 0)                                                    \
+  g_stamps[(blockIdx.x * 8 + (threadIdx.x >> 6)) * 5 + (i)] = __builtin_amdgcn_s_memrealtime()
+#define CWAC_STAMPT(id, i)                                                                             \
+  if ((id) < 4096 && (threadIdx.x & 63) == 0)                                                          \
+  g_stamps[((id) * 8 + (threadIdx.x >> 6)) * 5 + (i)] = __builtin_amdgcn_s_memrealtime()
+#else
+#define CWAC_STAMP(i)
+#define CWAC_STAMPT(id, i)
+#endif
+
 constexpr int s_waitcnt_imm(int vmcnt, int lgkmcnt) {
   // gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14 ; expcnt = 7 (no wait)
   return (vmcnt & 15) | (7 << 4) | ((lgkmcnt & 15) << 8) | (((vmcnt >> 4) & 3) << 14);
@@ -451,6 +465,7 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
   const int lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave % WM, wave_n = wave / WM;
   const int l32 = lane & 31, half = lane >> 5;
+  CWAC_STAMP(0);
 
   // ---- epilogue parameters of this tile: issue their loads first (oldest in the load queue);
   // thread t < BN stages channel t (and thread t < BM row t)
@@ -735,6 +750,7 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
   };
 
   int s = 0;
+  CWAC_STAMP(1);
   if (stages > 0) stage_body(0, 0, std::false_type{});
   s = 1;
   // steady state, unrolled over the ring so that LDS offsets are compile-time constants
@@ -746,6 +762,7 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
   for (; s + NSTAGE < stages; ++s) stage_body(s, s % NSTAGE, std::true_type{});
   for (; s < stages; ++s) stage_body(s, s % NSTAGE, std::false_type{});
 
+  CWAC_STAMP(2);
   if constexpr (OUT_KIND == kOutStats) {
     __builtin_amdgcn_s_barrier();  // every wavefront is done with the ring, which the slabs overlay
     stats_epilogue<TB, WM>(p, acc, smem, s_mult, s_fb, s_rs, s_pq, s_pf, bm0, bn0, tile_m, wave_m, wave_n,
@@ -759,6 +776,318 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
     else
       fast_epilogue<OUT_KIND, INT_ONLY, false, TB, WM, TA>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
   }
+  CWAC_STAMP(3);
+#ifdef CWAC_V_STAMP
+  __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));  // stores acknowledged
+  CWAC_STAMP(4);
+#endif
+}
+
+// Persistent form of the 256 x 256 tile of eight wavefronts (linear layers; int8 / fp32 / int32 output):
+// one workgroup per compute unit walks tiles id = blockIdx.x + j * gridDim.x (the same XCD-aware
+// tile order: ids congruent mod 8 stay on one XCD).  What a fresh workgroup pays per tile - kernel
+// arguments, tile arithmetic, the round trip of the epilogue parameters and of the first panels,
+// the gap between two workgroups on a compute unit: 2.5-3 us, a quarter of a K = 512 tile - is
+// taken off the critical path:
+//   * once the last fragments of tile i have been fetched (the ring is free), the parameter
+//     loads of tile i + 1 (into registers) and the panel loads of its stage 0 (into ring stage 0)
+//     are issued, and travel while the epilogue of tile i runs;
+//   * the epilogue's transposition slabs therefore live behind stage 0 (they overlap stage 1 and
+//     28 KiB the ring leaves free); after a barrier that ends the epilogue, stage 1 of tile i + 1
+//     is issued and the parameters go to LDS.
+// Panel loads are buffer loads (descriptor of the tile's panel in scalar registers, extent = the
+// tile's own rows, scalar row / K offset): a wavefront's load i covers rows 8 i + lr of its share,
+// and the swizzle of row r depends on bits 1-3 of r only, so two per-lane offsets (i even, i odd)
+// serve all loads of a panel and stay live across the epilogue instead of eight.
+template <int OUT_KIND, bool INT_ONLY>
+__global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams p) {
+  using C = FastCfg<256, 4, 128, 2, 2, 256>;
+  constexpr int BK = 128, TA = 4, TB = 2, WM = 4, NSTAGE = 2, LPS = C::LPS;
+  constexpr int kSlabBase = C::STAGE;                         // slabs: behind stage 0
+  constexpr int kParamBase = 160 * 1024 - 2 * C::PARAM_BYTES;  // two parameter blocks: the top 8 KiB
+  static_assert(C::LOADS_X == 4 && C::LOADS_W == 4 && C::RPL == 8 && C::KK == 4, "load schedule below");
+  static_assert(kSlabBase + C::NWAVES * 32 * TB * kSlabStride <= kParamBase, "slabs clear of the parameters");
+  extern __shared__ __attribute__((aligned(16))) int8_t smem[];
+  // parameter block b (tiles alternate between the two): offset, mult, fbias [256 channels], row scale [256 rows]
+  auto param_block = [&](int b) { return smem + kParamBase + b * C::PARAM_BYTES; };
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % WM, wave_n = wave / WM;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  const int lr = lane >> 3, pc = lane & 7;
+  // per-lane byte offset inside a load: row lr of the load's 8 rows, chunk pc ^ swz(row); loads with
+  // odd i sit 8 rows further, which flips bit 2 of the swizzle
+  const int sw0 = (lr >> 1) & 7;
+  const uint32_t xv0 = (uint32_t)lr * (uint32_t)p.ldx + (uint32_t)((pc ^ sw0) << 4);
+  const uint32_t xv1 = (uint32_t)lr * (uint32_t)p.ldx + (uint32_t)((pc ^ sw0 ^ 4) << 4);
+  const uint32_t wv0 = (uint32_t)lr * (uint32_t)p.ldw + (uint32_t)((pc ^ sw0) << 4);
+  const uint32_t wv1 = (uint32_t)lr * (uint32_t)p.ldw + (uint32_t)((pc ^ sw0 ^ 4) << 4);
+  // scalar byte offset of the first row of this wavefront's share (32 rows of either panel)
+  const uint32_t xrow0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldx, wrow0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldw;
+  const uint32_t xstep = 8u * (uint32_t)p.ldx, wstep = 8u * (uint32_t)p.ldw;
+
+  const int total = p.tiles_m * p.tiles_n;
+  const int stages = p.k / BK;
+  const uint32_t x_extent = (uint32_t)((uint64_t)255 * (uint64_t)p.ldx + (uint64_t)p.k);
+  const uint32_t w_extent = (uint32_t)((uint64_t)255 * (uint64_t)p.ldw + (uint64_t)p.k);
+
+  // state of the tile whose panels are being loaded / multiplied
+  int64_t bm0 = 0;
+  int bn0 = 0;
+  __amdgpu_buffer_rsrc_t xdesc, wdesc;
+  // The parameters go global -> LDS directly as well (4 bytes per lane, 256 bytes per wavefront load):
+  // wavefronts 2a and 2a + 1 fetch the four quarters of array a (0 offset, 1 mult, 2 fbias, 3 row scale).
+  // An absent offset vector reads as zeros (both blocks cleared once); absent fbias / row scales are
+  // never read by the epilogue.
+  const int p_arr = wave_s >> 1, p_elem = (wave_s & 1) * 128 + lane;
+  if (!p.offset && tid < 512) {
+    reinterpret_cast<int32_t *>(param_block(tid >> 8))[tid & 255] = 0;
+  }
+
+  auto open_tile = [&](int id, int pb) {  // tile origin, panel descriptors, parameter loads into block pb
+    int tile_m, tile_n;
+    tile_of_block(id, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    bm0 = (int64_t)tile_m * 256;
+    if (bm0 > p.m - 256) bm0 = p.m - 256;
+    bn0 = tile_n * 256;
+    if (bn0 > p.n - 256) bn0 = p.n - 256;
+    xdesc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x + bm0 * p.ldx), 0, (int)x_extent, 0x00020000);
+    wdesc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.w + (int64_t)bn0 * p.ldw), 0, (int)w_extent,
+                                              0x00020000);
+    const void *src = nullptr;
+    if (p_arr == 0) src = p.offset ? p.offset + bn0 : nullptr;
+    if (p_arr == 1 && OUT_KIND != CWAC_OUT_INT32) src = p.mult + bn0;
+    if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32) {
+      if (p_arr == 2) src = p.fbias ? p.fbias + bn0 : nullptr;
+      if (p_arr == 3) src = p.sx_row ? p.sx_row + bm0 : nullptr;
+    }
+    if (src) {  // wave-uniform
+      int8_t *dst = param_block(pb) + p_arr * 1024 + (wave_s & 1) * 512;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(static_cast<const int32_t *>(src) + p_elem + j * 64),
+                                         CWAC_LDS_PTR(dst + j * 256), 4, 0, 0);
+    }
+  };
+  // chunk 0 of a stage = the four activation loads, chunk 1 = the four weight loads
+  auto issue_chunk = [&](int buf, int k0, int c) {
+    int8_t *dst = smem + buf * C::STAGE + (c ? C::X_BYTES : 0) + wave_s * (32 * BK);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (c == 0)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? xv1 : xv0),
+                                                 (int)(xrow0 + (uint32_t)i * xstep + (uint32_t)k0), 0, 0);
+      else
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(wdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? wv1 : wv0),
+                                                 (int)(wrow0 + (uint32_t)i * wstep + (uint32_t)k0), 0, 0);
+    }
+  };
+  const int swz_l = C::swz(l32);
+  const int x_off = (wave_m * 32 * TB + l32) * BK;
+  const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
+  auto read_frags = [&](int buf, int kk, v4i(&fw)[TA], v4i(&fx)[TB]) {
+    const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
+    fw[0] = *reinterpret_cast<const v4i *>(base + w_off);
+#pragma unroll
+    for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
+#pragma unroll
+    for (int a = 1; a < TA; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
+  };
+  v16i acc[TA][TB];
+  auto mma = [&](const v4i(&fw)[TA], const v4i(&fx)[TB]) {
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+      for (int b = 0; b < TB; ++b)
+        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
+  };
+  // one k-step for the scheduler: 8 MFMAs, 6 LDS reads of the next step's fragments behind the first six,
+  // and (loads) four panel loads behind the last two
+  auto interleave = [&](bool loads) {
+#pragma unroll
+    for (int i = 0; i < TA + TB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    if (loads) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+      }
+    } else {
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  v4i fwA[TA], fxA[TB], fwB[TA], fxB[TB];
+  // Stage s of the current tile (buffer s % 2), as in the one-tile kernel: the weight loads of stage
+  // s + 1 go out in the first k-step, the activation loads of stage s + 2 in the last one, behind the
+  // barrier that frees this stage's buffer.
+  auto stage_body = [&](int s, int buf, auto steady_tag) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
+    const bool late_ok = STEADY || (s >= 1 && s + 1 < stages);
+    const bool first_ok = STEADY || (s + NSTAGE < stages);
+#pragma unroll
+    for (int kk = 0; kk + 1 < C::KK; ++kk) {
+      const bool ld = kk == 0 && late_ok;
+      if (ld) issue_chunk(buf ^ 1, (s + 1) * BK, 1);
+      if (kk & 1) {
+        read_frags(buf, kk + 1, fwA, fxA);
+        mma(fwB, fxB);
+      } else {
+        read_frags(buf, kk + 1, fwB, fxB);
+        mma(fwA, fxA);
+      }
+      interleave(ld);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));  // stage s + 1 has landed (nothing else is in flight)
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (first_ok) issue_chunk(buf, (s + NSTAGE) * BK, 0);
+    if (STEADY || s + 1 < stages) read_frags(buf ^ 1, 0, fwA, fxA);
+    mma(fwB, fxB);
+    interleave(first_ok);
+  };
+
+  // ---- first tile: nothing was prefetched
+  int id = blockIdx.x;
+  if (id >= total) return;
+  int pb = 0;  // parameter block of the tile being multiplied
+  open_tile(id, 0);
+  issue_chunk(0, 0, 0);
+  issue_chunk(0, 0, 1);
+  while (true) {
+    CWAC_STAMPT(id, 0);
+    // stage 0 of this tile is in flight (or has landed), its parameters are in registers; ring stage 1,
+    // the slabs and the parameter block are free (barrier at the end of the previous epilogue)
+    if (stages > 1) {
+      issue_chunk(1, BK, 0);
+      issue_chunk(1, BK, 1);
+    }
+    if (stages > 1)
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(LPS, 0));  // all but stage 1: stage 0 has landed
+    else
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    __builtin_amdgcn_s_barrier();
+    const int32_t *s_off = reinterpret_cast<const int32_t *>(param_block(pb));
+#pragma unroll
+    for (int a = 0; a < TA; ++a)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const v4i o = *reinterpret_cast<const v4i *>(s_off + wave_n * (32 * TA) + a * 32 + 8 * g + 4 * half);
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[a][b][4 * g + r] = o[r];
+      }
+    read_frags(0, 0, fwA, fxA);
+    CWAC_STAMPT(id, 1);
+    // stage 0: the loads of stage 1 are out already (above), so only its last k-step issues loads
+    {
+#pragma unroll
+      for (int kk = 0; kk + 1 < C::KK; ++kk) {
+        if (kk & 1) {
+          read_frags(0, kk + 1, fwA, fxA);
+          mma(fwB, fxB);
+        } else {
+          read_frags(0, kk + 1, fwB, fxB);
+          mma(fwA, fxA);
+        }
+        interleave(false);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      const bool first_ok = NSTAGE < stages;
+      if (first_ok) issue_chunk(0, NSTAGE * BK, 0);
+      if (stages > 1) read_frags(1, 0, fwA, fxA);
+      mma(fwB, fxB);
+      interleave(first_ok);
+    }
+    int s = 1;
+    for (; s + 2 * NSTAGE <= stages; s += NSTAGE) {  // steady state, unrolled over the ring
+      stage_body(s, 1, std::true_type{});
+      stage_body(s + 1, 0, std::true_type{});
+    }
+    for (; s + NSTAGE < stages; ++s) stage_body(s, s & 1, std::true_type{});
+    for (; s < stages; ++s) stage_body(s, s & 1, std::false_type{});
+
+    // ---- the ring is free (every wavefront fetched its last fragments before the last barrier):
+    // open the next tile - its parameter loads and the panel loads of its stage 0 travel under this
+    // tile's epilogue.  The epilogue reads this tile's origin, so that is kept aside first.
+    CWAC_STAMPT(id, 2);
+    const int64_t e_bm0 = bm0;
+    const int e_bn0 = bn0;
+    const int next = id + (int)gridDim.x;
+    const bool more = next < total;
+    if (more) {
+      open_tile(next, pb ^ 1);
+      issue_chunk(0, 0, 0);
+      issue_chunk(0, 0, 1);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      const float *s_mult = reinterpret_cast<const float *>(param_block(pb) + 1024);
+      const float *s_fb = reinterpret_cast<const float *>(param_block(pb) + 2048);
+      const float *s_rs = reinterpret_cast<const float *>(param_block(pb) + 3072);
+      // the lane index the epilogue derives its addresses from is made opaque per tile: otherwise all of
+      // that lane arithmetic is hoisted out of the tile loop and lives (spilled) across the main loop
+      int lane_e = lane;
+      asm volatile("" : "+v"(lane_e));
+      constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8) ? 1 : 4;
+      const int vs = p.vec_store && (((e_bn0 * ESZ) & 15) == 0);
+      if (vs)
+        fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0, e_bn0,
+                                                            wave_m, wave_n, lane_e);
+      else
+        fast_epilogue<OUT_KIND, INT_ONLY, false, TB, WM, TA>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0, e_bn0,
+                                                             wave_m, wave_n, lane_e);
+    }
+    CWAC_STAMPT(id, 3);
+    CWAC_STAMPT(id, 4);
+    if (!more) break;
+    id = next;
+    pb ^= 1;
+    __builtin_amdgcn_s_barrier();  // every wavefront is done with the slabs and this tile's parameter block
+  }
+}
+
+template <int OUT_KIND, bool INT_ONLY>
+cwac_status launch_persist_one(const FwdParams &p, int workgroups, hipStream_t st) {
+  constexpr int LDS = 160 * 1024;
+  static const hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void *>(&qlinear_persist_kernel<OUT_KIND, INT_ONLY>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+  if (attr != hipSuccess) return CWAC_E_LAUNCH;
+  qlinear_persist_kernel<OUT_KIND, INT_ONLY><<<dim3((unsigned)workgroups), 512, LDS, st>>>(p);
+  return launch_status();
+}
+
+// The persistent kernel on a 256 x 256 tiling of the layer: one workgroup per compute unit (fewer
+// when there are fewer tiles).  out_kind: CWAC_OUT_INT8 | CWAC_OUT_FP32 | CWAC_OUT_INT32.
+cwac_status launch_persist(FwdParams p, int out_kind, bool int_only, int max_workgroups, hipStream_t st) {
+  const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
+  p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
+  p.tiles_m = (int)ceil_div(p.m, 256);
+  p.tiles_n = (int)ceil_div(p.n, 256);
+  const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+  if (tiles > 0x7fffffff) return CWAC_E_LAUNCH;
+  int device = 0, cus = 0;
+  if (hipGetDevice(&device) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus < 1)
+    return CWAC_E_LAUNCH;
+  int wgs = (int)(tiles < cus ? tiles : cus);
+  if (max_workgroups > 0 && max_workgroups < wgs) wgs = max_workgroups;  // cwac_tuning.persist_workgroups
+  if (out_kind == CWAC_OUT_INT8)
+    return int_only ? launch_persist_one<CWAC_OUT_INT8, true>(p, wgs, st)
+                    : launch_persist_one<CWAC_OUT_INT8, false>(p, wgs, st);
+  if (out_kind == CWAC_OUT_FP32) return launch_persist_one<CWAC_OUT_FP32, false>(p, wgs, st);
+  return launch_persist_one<CWAC_OUT_INT32, false>(p, wgs, st);
 }
 
 template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false,
@@ -844,7 +1173,8 @@ bool fast_prefers_quarter_tile(int64_t m, int n) {
   return n >= 128 && t_half < 160 && t_q >= 96;
 }
 
-cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, int shape, hipStream_t st) {
+cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, const Tune &tune, hipStream_t st) {
+  int shape = tune.shape;
   const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
   // layers narrower than 256 channels: 256 tokens x 128 (64) channels, four wavefronts (4 x 1) of
@@ -863,8 +1193,12 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, int shape, hip
   if (shape == CWAC_SHAPE_256_8W) return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
   if (shape == CWAC_SHAPE_256_4W_K128) return launch_cfg<256, 2, 128, 2, 2>(p, out_kind, int_only, st);
   const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
-  if (fast_prefers_half_tile(p.m, p.n, p.k, out_bytes))
+  if (shape == CWAC_SHAPE_AUTO && fast_prefers_half_tile(p.m, p.n, p.k, out_bytes))
     return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
+  // the eight-wavefront 256 x 256 tile: persistent workgroups (CWAC_SHAPE_256_PERSIST, and the automatic
+  // choice) for the output kinds it is built for
+  if (out_kind == CWAC_OUT_INT8 || out_kind == CWAC_OUT_FP32 || out_kind == CWAC_OUT_INT32)
+    return launch_persist(p, out_kind, int_only, tune.persist_workgroups, st);
   return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
 }
 
@@ -904,3 +1238,10 @@ cwac_status launch_fast_stats(FwdParams p, int waves, hipStream_t st) {
 }
 
 }  // namespace cwac
+
+#ifdef CWAC_V_STAMP
+extern "C" int cwac_debug_stamps(void *dst_device, size_t bytes, void *stream) {
+  return (int)hipMemcpyFromSymbolAsync(dst_device, HIP_SYMBOL(cwac::g_stamps), bytes, 0, hipMemcpyDeviceToDevice,
+                                       (hipStream_t)stream);
+}
+#endif

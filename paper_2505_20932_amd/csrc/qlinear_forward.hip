@@ -255,7 +255,7 @@ static int choose_forward(int64_t m, int n, int k, int64_t ldx, int64_t ldw, int
 static cwac_status dispatch_forward(const FwdParams &p, int out_kind, bool int_only, const Tune &tune,
                                     hipStream_t st) {
   const int choice = choose_forward(p.m, p.n, p.k, p.ldx, p.ldw, out_kind, tune);
-  if (choice == CWAC_KERNEL_DIRECT_LDS) return launch_fast(p, out_kind, int_only, tune.shape, st);
+  if (choice == CWAC_KERNEL_DIRECT_LDS) return launch_fast(p, out_kind, int_only, tune, st);
   if (choice == 256) return launch_tile<256, 256, 128, 2, 2>(p, out_kind, int_only, st);
   if (choice == 128) return launch_tile<128, 128, 128, 2, 2>(p, out_kind, int_only, st);
   return launch_tile<64, 64, 128, 2, 2>(p, out_kind, int_only, st);

@@ -192,7 +192,7 @@ def test_tuning_is_validated_and_no_environment_variable_is_read(lib):
     null = None
     a = C.c_void_p(4096)
     qp = binding.make_qparams()
-    for bad in (binding.make_tuning(kernel=7), binding.make_tuning(shape=6), binding.make_tuning(shape=-1),
+    for bad in (binding.make_tuning(kernel=7), binding.make_tuning(shape=7), binding.make_tuning(shape=-1),
                 binding.make_tuning(stats_waves=3)):
         assert lib.qlinear_cwac_forward_ex(a, 32, a, 32, 4, 4, 32, C.byref(qp), a, a, null, null, 0, a, 4,
                                            C.byref(bad), null) == -4

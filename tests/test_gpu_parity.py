@@ -119,7 +119,7 @@ def test_quantize_rows_sym_and_colsum(orc, case1, case5s):
 
 # --------------------------------------------------------------------------- forward
 def _forward(c, out_kind, mult=None, offset=None, fbias=None, sx_row=None, qp=None, tile=None,
-             xq=None, ldo=None, pipe=None):
+             xq=None, ldo=None, pipe=None, wgs=0):
     xq = c.xq if xq is None else xq
     m = xq.shape[0]
     dt = {0: torch.int8, 1: torch.float32, 2: torch.int32}[out_kind]
@@ -130,7 +130,7 @@ def _forward(c, out_kind, mult=None, offset=None, fbias=None, sx_row=None, qp=No
         out = torch.full((m, ldo), 77, dtype=dt, device=DEV)
         view = out[:, :c.n]
     P.qlinear_cwac_forward(dev(xq), dev(c.wq), qp, dev(mult), dev(offset), dev(fbias),
-                           dev(sx_row), out_kind, view, tuning=tuning_of(tile, pipe))
+                           dev(sx_row), out_kind, view, tuning=tuning_of(tile, pipe, persist_workgroups=wgs))
     return host(out)
 
 
@@ -210,7 +210,7 @@ def test_forward_ragged_shapes(orc, m, n, k):
             np.testing.assert_array_equal(got[:, :n], want)
 
 
-@pytest.mark.parametrize("pipe", ["128x2", "64x4", "duo", "8w", "q"])
+@pytest.mark.parametrize("pipe", ["128x2", "64x4", "duo", "8w", "q", "persist"])
 @pytest.mark.parametrize("m,n,k", [(256, 256, 128), (300, 520, 384), (700, 1030, 1152),
                                    (513, 768, 256),
                                    # K a multiple of 64 only: every pipe falls to the 64-byte K step
@@ -395,6 +395,43 @@ def test_stats_empty_state_and_single_row(orc):
     a, b, mom, nd, _ = _stats(yf, yq)                       # one row: variance 0 -> shift only
     assert np.all(a == 1.0) and nd == ch
     np.testing.assert_array_equal(b, np.arange(8, dtype=np.float32) * 0.5)
+
+
+@pytest.mark.parametrize("wgs", [1, 3, 7, 0])
+@pytest.mark.parametrize("m,n,k", [(1300, 1030, 512), (600, 780, 128), (777, 520, 256), (520, 1290, 384),
+                                   (1030, 600, 1152)])
+def test_forward_persistent_tiles(orc, m, n, k, wgs):
+    """The persistent form of the 256 x 256 tile with fewer workgroups than tiles, so that every
+    workgroup walks several tiles (the next tile's first loads in flight under a tile's epilogue):
+    one to nine K stages (odd and even: the last stage ends in either ring buffer), ragged edge
+    tiles, every output kind, padded output rows."""
+    print(f"persistent tiles {m} x {n} x {k}, {wgs or 'one per CU'} workgroups", flush=True)
+    g = synth.normal(1700 + m, 0, m * k).numpy().reshape(m, k)
+    xq = np.clip(np.rint(g * 60), -128, 127).astype(np.int8)
+    g = synth.normal(1700 + m, 1, n * k).numpy().reshape(n, k)
+    wq = np.clip(np.rint(g * 60), -127, 127).astype(np.int8)
+    acc = orc.gemm_i8(xq, wq)
+    mult = (np.abs(synth.normal(1700 + m, 2, n).numpy()) * 1e-3 + 1e-4).astype(np.float32)
+    off = np.rint(synth.normal(1700 + m, 3, n).numpy() * 500).astype(np.int32)
+    fb = synth.normal(1700 + m, 4, n).numpy().astype(np.float32)
+    sxr = (np.abs(synth.normal(1700 + m, 5, m).numpy()) + 0.5).astype(np.float32)
+    from types import SimpleNamespace
+    c = SimpleNamespace(xq=xq, wq=wq, n=n)
+    qp = P.make_qparams(z_r=5)
+    qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, z_r=5)
+    kw = dict(tile="fast", pipe="persist", wgs=wgs)
+    for ldo in (None, n + 5):
+        got = _forward(c, P.CWAC_OUT_INT32, offset=off, ldo=ldo, **kw)
+        np.testing.assert_array_equal(got[:, :n], acc + off[None, :])
+        if ldo:
+            assert np.all(got[:, n:] == 77)
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, ldo=ldo, **kw)
+        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5))
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, ldo=ldo, **kw)
+        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5, fb, sxr))
+        _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)
+        got = _forward(c, P.CWAC_OUT_FP32, mult, off, fbias=fb, sx_row=sxr, ldo=ldo, **kw)
+        np.testing.assert_array_equal(got[:, :n], want)
 
 
 # --------------------------------------------------------------------------- fold
