@@ -906,6 +906,108 @@ def cpu_baseline(synth, cfg: int, sample_rows: int):
     return ops / t_total / 1e12, orc.get_threads(), t_total
 
 
+def power_trace(P, synth, torch, dev: str, cfg: int, seconds: float = 5.0):
+    """What the device's power management does under the path's kernels: shader clock and socket
+    power (amd-smi, sampled from a helper thread as fast as the tool answers) while one phase is
+    launched back to back - idle, the fused int8 forward of the workload, its fp32 calibration forward,
+    the statistics pass, and the register-resident MFMA probe on operand words of the workload."""
+    import subprocess
+    import threading
+    wl, layers = setup_layers(P, synth, torch, cfg, dev, synth.WORKLOADS[cfg].m)
+    run_step(P, layers)
+    torch.cuda.synchronize()
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    L0 = layers[0]
+    words = torch.cat([L0.wq.contiguous().view(-1).view(torch.int32)[:2048].view(-1, 4),
+                       L0.xq.contiguous().view(-1).view(torch.int32)[:2048].view(-1, 4)]).contiguous()
+
+    def sample():
+        """socket power (W) and the mean shader clock over the XCDs (MHz) from amd-smi."""
+        try:
+            out = subprocess.run(["amd-smi", "metric", "-g", "0", "--power", "--clock", "--json"],
+                                 capture_output=True, text=True, timeout=20).stdout
+            doc = json.loads(out[out.index("{"):])
+            gpu = (doc.get("gpu_data") or doc)[0] if isinstance(doc.get("gpu_data", doc), list) else doc
+            got = {}
+            pw = gpu.get("power", {}).get("socket_power", {})
+            if isinstance(pw, dict) and isinstance(pw.get("value"), (int, float)):
+                got["power_w"] = float(pw["value"])
+            clk = [v["clk"]["value"] for k, v in gpu.get("clock", {}).items()
+                   if k.startswith("gfx_") and isinstance(v, dict) and isinstance(v.get("clk", {}).get("value"), (int, float))]
+            if clk:
+                got["sclk_mhz"] = sum(clk) / len(clk)
+            return got
+        except Exception as exc:  # amd-smi missing or unreadable: report it, do not fail the bench
+            return {"error": str(exc)[:80]}
+
+    def phase(name, fn):
+        samples, stop = [], threading.Event()
+
+        def watcher():
+            while not stop.is_set():
+                samples.append(sample())
+                stop.wait(0.15)
+        th = threading.Thread(target=watcher)
+        launches = 0
+        t_end = time.perf_counter() + seconds
+        th.start()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        while time.perf_counter() < t_end:
+            if fn is None:
+                time.sleep(0.05)
+            else:
+                for _ in range(4):
+                    fn()
+                launches += 4
+                torch.cuda.synchronize()
+        e1.record()
+        torch.cuda.synchronize()
+        stop.set()
+        th.join()
+        ent = {"seconds": round(e0.elapsed_time(e1) / 1e3, 2), "passes": launches, "samples": len(samples)}
+        keep = samples[len(samples) // 3:]                      # the settled part
+        for key in ("sclk_mhz", "power_w"):
+            vals = sorted(v[key] for v in keep if v.get(key) is not None)
+            if vals:
+                ent[key] = {"min": round(vals[0], 1), "median": round(vals[len(vals) // 2], 1), "max": round(vals[-1], 1)}
+        if fn is not None and launches:
+            ent["ms_per_pass"] = round(e0.elapsed_time(e1) / launches, 4)
+        errs = [v["error"] for v in samples if "error" in v]
+        if errs:
+            ent["amd_smi_error"] = errs[0]
+        return name, ent
+
+    def fwd():
+        for L in layers:
+            _forward_int8(P, L, L.mult, L.offset, L.fbias)
+
+    def cal():
+        for L in layers:
+            P.qlinear_cwac_forward(L.xq_cal, L.wq, None, L.deq_mult, L.deq_off,
+                                   L.deq_fb if L.bias is not None else None, L.sx_row_cal, P.CWAC_OUT_FP32, L.yq)
+
+    def stats():
+        for L in layers:
+            P.cwac_calibrate_stats_first(L.y_full, L.yq, L.stats, L.ws)
+
+    def probe():
+        P.cwac_mfma_probe(words, 20000, cus, sink)
+
+    fwd_ops = sum(2.0 * L.m * L.n * L.k for L in layers)
+    out = dict(phase(n, f) for n, f in (("idle", None), ("forward_int8", fwd), ("calibration_forward_fp32", cal),
+                                        ("statistics", stats), ("mfma_probe_workload_operands", probe),
+                                        ("forward_int8_again", fwd)))
+    for key in ("forward_int8", "forward_int8_again"):
+        out[key]["pops"] = round(fwd_ops / (out[key]["ms_per_pass"] * 1e-3) / 1e15, 4)
+    out["mfma_probe_workload_operands"]["pops"] = round(
+        2.0 * 32768 * 16 * 20000 * 4 * cus / (out["mfma_probe_workload_operands"]["ms_per_pass"] * 1e-3) / 1e15, 4)
+    return {"power_trace": f"config {cfg}: each phase launched back to back for {seconds} s; rocm-smi sampled "
+                           "from a helper thread; statistics of the last two thirds of the samples",
+            "phases": out}
+
+
 def time_steps(P, torch, layers, steps: int, warmup: int):
     """warmup untimed passes of run_step, then `steps` timed ones (host clock around the whole
     region, HIP events on the launch stream around every phase of every layer)."""
@@ -1132,6 +1234,9 @@ def main():
     ap.add_argument("--no-full-stream", action="store_true",
                     help="skip the leg that streams workload 5's whole calibration set (262144 rows per layer)")
     ap.add_argument("--per-config-steps", type=int, default=5)
+    ap.add_argument("--power-trace", action="store_true",
+                    help="instead of the benchmark: shader clock and socket power (amd-smi) under each of the "
+                         "path's kernels launched back to back (its own JSON line)")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -1156,6 +1261,9 @@ def main():
         print(json.dumps(block_section(P, torch, dev, args.block_batch, args.steps, args.warmup,
                                        0 if args.no_cpu_baseline else 2, args.blocks,
                                        tuple(int(v) for v in args.block_shape.split(",")))))
+        return
+    if args.power_trace:
+        print(json.dumps(power_trace(P, synth, torch, dev, args.config)))
         return
     wl = synth.WORKLOADS[args.config]
     cal_rows = args.cal_rows or wl.m

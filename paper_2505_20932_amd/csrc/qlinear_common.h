@@ -250,6 +250,8 @@ cwac_status launch_fast_table(FwdParams p, int shape, hipStream_t st);
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);
 // True where it would take 128 x 128 tiles (layers with few tiles and a long K loop).
 bool fast_prefers_quarter_tile(int64_t m, int n);
+// The tile shape (CWAC_SHAPE_*) launch_fast picks by itself for a linear layer with n >= 256.
+int fast_linear_shape(int64_t m, int n, int k, int out_bytes);
 // The same kernel as an implicit-GEMM convolution (p.cv_* set, p.ldx unused).  fast_conv_ok: its shape
 // constraints (m >= 256, n >= 64, c_in % 64 == 0, image below 2 GiB).
 bool fast_conv_ok(const FwdParams &p, int64_t image_bytes);

@@ -974,22 +974,30 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
     __builtin_amdgcn_s_barrier();
     const int32_t *s_off = reinterpret_cast<const int32_t *>(param_block(pb));
-#pragma unroll
-    for (int a = 0; a < TA; ++a)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const v4i o = *reinterpret_cast<const v4i *>(s_off + wave_n * (32 * TA) + a * 32 + 8 * g + 4 * half);
-#pragma unroll
-        for (int b = 0; b < TB; ++b)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) acc[a][b][4 * g + r] = o[r];
-      }
     read_frags(0, 0, fwA, fxA);
     CWAC_STAMPT(id, 1);
-    // stage 0: the loads of stage 1 are out already (above), so only its last k-step issues loads
+    // stage 0: the loads of stage 1 are out already (above), so only its last k-step issues loads.
+    // The accumulators START at offset[n] (the integer offset add of Eq. 10 costs nothing): the first
+    // MFMA of every accumulator takes the offsets of its 32 channels - four 16-byte LDS reads that land
+    // in 16 consecutive registers - as its C operand, so no register is initialised by hand.
     {
+      read_frags(0, 1, fwB, fxB);
 #pragma unroll
-      for (int kk = 0; kk + 1 < C::KK; ++kk) {
+      for (int a = 0; a < TA; ++a) {
+        v16i pat;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const v4i o = *reinterpret_cast<const v4i *>(s_off + wave_n * (32 * TA) + a * 32 + 8 * g + 4 * half);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) pat[4 * g + r] = o[r];
+        }
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fwA[a], fxA[b], pat, 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 1; kk + 1 < C::KK; ++kk) {
         if (kk & 1) {
           read_frags(0, kk + 1, fwA, fxA);
           mma(fwB, fxB);
@@ -1181,25 +1189,41 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, const Tune &tu
   // 64 x 128 (64 x 64), 64-byte K steps, two workgroups per compute unit
   if (p.n < 128) return launch_cfg<256, 4, 64, 3, 2, false, 64>(p, out_kind, int_only, st);
   if (p.n < 256) return launch_cfg<256, 4, 64, 3, 2, false, 128>(p, out_kind, int_only, st);
-  // `shape` (cwac_tuning, same results): CWAC_SHAPE_256_8W is the 256-token tile with eight
-  // wavefronts (the choice for large layers), _256_4W_K128 / _K64 the same tile with four wavefronts
-  // and that K step and ring depth, _128_PAIR the 128-token tile, two workgroups of four wavefronts
-  // per compute unit, _128_128 the quarter tile.
-  if (shape == CWAC_SHAPE_128_128 || (shape == CWAC_SHAPE_AUTO && fast_prefers_quarter_tile(p.m, p.n)))
-    return launch_cfg<128, 2, 64, 3, 2, false, 128, 2>(p, out_kind, int_only, st);
+  // `shape` (cwac_tuning, same results): CWAC_SHAPE_256_PERSIST is the 256 x 256 tile of eight wavefronts
+  // on persistent workgroups (the choice for large layers), _256_8W the same tile with one workgroup per
+  // tile, _256_4W_K128 / _K64 that tile with four wavefronts and that K step and ring depth, _128_PAIR
+  // the 128-token tile, two workgroups of four wavefronts per compute unit, _128_128 the quarter tile.
+  const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
+  if (shape == CWAC_SHAPE_AUTO) shape = fast_linear_shape(p.m, p.n, p.k, out_bytes);
+  if (shape == CWAC_SHAPE_128_128) return launch_cfg<128, 2, 64, 3, 2, false, 128, 2>(p, out_kind, int_only, st);
   if ((p.k % 128) != 0) shape = CWAC_SHAPE_128_PAIR;  // K a multiple of 64 only: the tile that steps K by 64
   if (shape == CWAC_SHAPE_128_PAIR) return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
   if (shape == CWAC_SHAPE_256_4W_K64) return launch_cfg<256, 2, 64, 4, 2>(p, out_kind, int_only, st);
   if (shape == CWAC_SHAPE_256_8W) return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
   if (shape == CWAC_SHAPE_256_4W_K128) return launch_cfg<256, 2, 128, 2, 2>(p, out_kind, int_only, st);
-  const int out_bytes = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed) ? 1 : 4;
-  if (shape == CWAC_SHAPE_AUTO && fast_prefers_half_tile(p.m, p.n, p.k, out_bytes))
-    return launch_cfg<128, 2, 64, 3, 2>(p, out_kind, int_only, st);
-  // the eight-wavefront 256 x 256 tile: persistent workgroups (CWAC_SHAPE_256_PERSIST, and the automatic
-  // choice) for the output kinds it is built for
+  // CWAC_SHAPE_256_PERSIST: the eight-wavefront 256 x 256 tile on persistent workgroups, for the output
+  // kinds it is built for
   if (out_kind == CWAC_OUT_INT8 || out_kind == CWAC_OUT_FP32 || out_kind == CWAC_OUT_INT32)
     return launch_persist(p, out_kind, int_only, tune.persist_workgroups, st);
   return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
+}
+
+int fast_linear_shape(int64_t m, int n, int k, int out_bytes) {
+  // The automatic tile shape of a linear layer with n >= 256, from measurements on the ViT / Swin / LLM
+  // layer shapes (K 512 .. 11008, 196 .. 3072 tiles of 256 x 256).
+  //  * Few tiles and a long K loop: 128 x 128 tiles (fast_prefers_quarter_tile).
+  //  * Less than a round of 256 x 256 tiles: the 128-token tile where the one-tile cost model prefers it.
+  //  * Otherwise the persistent 256 x 256 tile - except for short K loops whose last round of tiles
+  //    leaves much of the chip idle: there the 128 x 128 tile (three workgroups per compute unit, four
+  //    times as many tiles) finishes sooner; with 4-byte outputs, whose store bursts it also spreads,
+  //    already at a milder imbalance.
+  if (fast_prefers_quarter_tile(m, n)) return CWAC_SHAPE_128_128;
+  if ((k % 128) != 0) return CWAC_SHAPE_128_PAIR;
+  const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
+  if (t256 < 160) return fast_prefers_half_tile(m, n, k, out_bytes) ? CWAC_SHAPE_128_PAIR : CWAC_SHAPE_256_PERSIST;
+  const double fill = (double)t256 / (double)(256 * ceil_div(t256, 256));  // busy share of the rounds
+  if (k <= 1024 && fill < (out_bytes > 1 ? 0.85 : 0.70)) return CWAC_SHAPE_128_128;
+  return CWAC_SHAPE_256_PERSIST;
 }
 
 bool fast_conv_ok(const FwdParams &p, int64_t image_bytes) {
