@@ -1008,6 +1008,65 @@ def power_trace(P, synth, torch, dev: str, cfg: int, seconds: float = 5.0):
             "phases": out}
 
 
+def tile_timeline(torch, synth, dev: str, cfgs):
+    """Where a tile's time goes inside the direct-to-LDS forward kernels: 100 MHz time stamps that every
+    wavefront takes at five points of each tile (needs the development build of the library,
+    `python -m paper_2505_20932_amd.build --timeline`, loaded here instead of the product library).
+    One launch per layer after ten warm-up launches; means over all wavefronts of all tiles, us."""
+    import ctypes
+    import numpy as np
+    from paper_2505_20932_amd import build as B
+    if not os.path.exists(B.STAMP_LIB):
+        raise SystemExit(f"{B.STAMP_LIB} is missing: python -m paper_2505_20932_amd.build --timeline")
+    os.environ["CWAC_LIB"] = B.STAMP_LIB
+    import paper_2505_20932_amd as P
+    lib = P.binding.lib()
+    lib.cwac_debug_stamps.restype = ctypes.c_int
+    lib.cwac_debug_stamps.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    buf = torch.zeros(4096 * 8 * 5, dtype=torch.int64, device=dev)
+    shapes = {"one workgroup per tile (CWAC_SHAPE_256_8W)": P.binding.CWAC_SHAPE_256_8W,
+              "persistent workgroups (CWAC_SHAPE_256_PERSIST)": P.binding.CWAC_SHAPE_256_PERSIST}
+    out = []
+    for cfg in cfgs:
+        wl, layers = setup_layers(P, synth, torch, cfg, dev, synth.WORKLOADS[cfg].m)
+        layers = layers[:4] if cfg == 3 else layers
+        run_step(P, layers)
+        torch.cuda.synchronize()
+        for L in layers:
+            tiles = ((L.m + 255) // 256) * ((L.n + 255) // 256)
+            if L.n < 256 or L.k % 128 or L.m < 256 or tiles > 4096:
+                continue
+            ent = {"workload": cfg, "layer": L.name, "m": L.m, "n": L.n, "k": L.k, "tiles_256x256": tiles,
+                   "ideal_mfma_us_per_tile_at_2.4GHz": round(2.0 * 256 * 256 * L.k / (INT8_MFMA_PEAK_TOPS * 1e6 / 256), 2)}
+            for name, shape in shapes.items():
+                tun = P.make_tuning(kernel=P.binding.CWAC_KERNEL_DIRECT_LDS, shape=shape)
+
+                def fwd():
+                    P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
+                                           L.sx_row, P.CWAC_OUT_INT8, L.out, tuning=tun)
+                for _ in range(10):
+                    fwd()
+                torch.cuda.synchronize()
+                buf.zero_()
+                fwd()
+                torch.cuda.synchronize()
+                assert lib.cwac_debug_stamps(buf.data_ptr(), buf.numel() * 8, None) == 0
+                torch.cuda.synchronize()
+                st = buf.cpu().numpy().reshape(4096, 8, 5)[:tiles].astype(np.float64) * 0.01       # us
+                st -= st[:, :, 0].min()
+                d = [float((st[:, :, i + 1] - st[:, :, i]).mean()) for i in range(4)]
+                ent[name] = {"kernel_span_us": round(float(st[:, :, 4].max()), 1),
+                             "start_to_first_mfma_us": round(d[0], 2), "k_loop_us": round(d[1], 2),
+                             "epilogue_us": round(d[2], 2), "store_drain_us": round(d[3], 2)}
+            out.append(ent)
+        del layers
+        torch.cuda.empty_cache()
+    return {"tile_timeline": "int8 forward, 256 x 256 tiles of eight wavefronts; per tile and wavefront: from its start "
+                             "(persistent: from the barrier that ends the previous tile) to the first MFMA, the K loop, "
+                             "the epilogue up to its last store instruction, and the wait for the stores",
+            "layers": out}
+
+
 def time_steps(P, torch, layers, steps: int, warmup: int):
     """warmup untimed passes of run_step, then `steps` timed ones (host clock around the whole
     region, HIP events on the launch stream around every phase of every layer)."""
@@ -1237,6 +1296,9 @@ def main():
     ap.add_argument("--power-trace", action="store_true",
                     help="instead of the benchmark: shader clock and socket power (amd-smi) under each of the "
                          "path's kernels launched back to back (its own JSON line)")
+    ap.add_argument("--tile-timeline", action="store_true",
+                    help="instead of the benchmark: in-kernel time stamps of the int8 forward's tiles on workloads "
+                         "2-5 (needs `python -m paper_2505_20932_amd.build --timeline`; its own JSON line)")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -1247,6 +1309,12 @@ def main():
         sys.exit(2)
 
     import torch
+    if args.tile_timeline:
+        from paper_2505_20932_amd import synth
+        assert torch.cuda.is_available(), "bench.py needs the MI355X"
+        torch.cuda.set_device(0)
+        print(json.dumps(tile_timeline(torch, synth, "cuda:0", (2, 3, 4, 5))))
+        return
     import paper_2505_20932_amd as P
     from paper_2505_20932_amd import synth
     assert torch.cuda.is_available(), "bench.py needs the MI355X"

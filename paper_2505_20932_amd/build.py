@@ -29,9 +29,9 @@ def _hipcc() -> str:
     return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, extra=(), suffix: str = "") -> str:
+    obj = os.path.join(BUILD, os.path.splitext(src)[0] + suffix + ".o")
+    cmd = [_hipcc(), *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     subprocess.run(cmd, check=True, stderr=subprocess.PIPE, text=True)
     return obj
 
@@ -51,5 +51,30 @@ def build_library(verbose: bool = True) -> str:
     return LIB
 
 
+STAMP_LIB = os.path.join(PKG, "libcwac_hip_timeline.so")
+
+
+def build_timeline_library(verbose: bool = True) -> str:
+    """Development build for `bench.py --tile-timeline`: the same library with the forward kernels
+    compiled with -DCWAC_V_STAMP, which makes every wavefront of the direct-to-LDS kernels record
+    100 MHz time stamps at five points of each tile and exports cwac_debug_stamps to read them.
+    Never loaded by the product path (binding.lib() loads libcwac_hip.so)."""
+    build_library(verbose=False)
+    try:
+        obj = _compile("qlinear_fast.hip", extra=("-DCWAC_V_STAMP",), suffix="_timeline")
+        others = [os.path.join(BUILD, os.path.splitext(f)[0] + ".o") for f in SOURCES if f != "qlinear_fast.hip"]
+        subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *others, obj, "-o", STAMP_LIB],
+                       check=True, stderr=subprocess.PIPE, text=True)
+    except subprocess.CalledProcessError as e:
+        sys.stderr.write(e.stderr or "")
+        raise
+    if verbose:
+        print(f"built {STAMP_LIB}")
+    return STAMP_LIB
+
+
 if __name__ == "__main__":
-    build_library()
+    if "--timeline" in sys.argv[1:]:
+        build_timeline_library()
+    else:
+        build_library()

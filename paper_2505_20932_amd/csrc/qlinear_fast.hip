@@ -784,31 +784,36 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
 }
 
 // Persistent form of the 256 x 256 tile of eight wavefronts (linear layers; int8 / fp32 / int32 output):
-// one workgroup per compute unit walks tiles id = blockIdx.x + j * gridDim.x (the same XCD-aware
+// one workgroup per compute unit walks work items id = blockIdx.x + j * gridDim.x (the same XCD-aware
 // tile order: ids congruent mod 8 stay on one XCD).  What a fresh workgroup pays per tile - kernel
 // arguments, tile arithmetic, the round trip of the epilogue parameters and of the first panels,
 // the gap between two workgroups on a compute unit: 2.5-3 us, a quarter of a K = 512 tile - is
 // taken off the critical path:
-//   * once the last fragments of tile i have been fetched (the ring is free), the parameter
-//     loads of tile i + 1 (into registers) and the panel loads of its stage 0 (into ring stage 0)
-//     are issued, and travel while the epilogue of tile i runs;
+//   * once the last fragments of item i have been fetched (the ring is free), the parameter loads of
+//     item i + 1 (global -> LDS, into the other of two parameter blocks) and the panel loads of its
+//     stage 0 (into ring stage 0) are issued, and travel while the epilogue of item i runs;
 //   * the epilogue's transposition slabs therefore live behind stage 0 (they overlap stage 1 and
-//     28 KiB the ring leaves free); after a barrier that ends the epilogue, stage 1 of tile i + 1
-//     is issued and the parameters go to LDS.
-// Panel loads are buffer loads (descriptor of the tile's panel in scalar registers, extent = the
-// tile's own rows, scalar row / K offset): a wavefront's load i covers rows 8 i + lr of its share,
+//     part of what the ring leaves free); after a barrier that ends the epilogue, stage 1 of item
+//     i + 1 is issued.
+// Panel loads are buffer loads (descriptor of the item's panel in scalar registers, extent = the
+// item's own rows, scalar row / K offset): a wavefront's load i covers rows 8 i + lr of its share,
 // and the swizzle of row r depends on bits 1-3 of r only, so two per-lane offsets (i even, i odd)
 // serve all loads of a panel and stay live across the epilogue instead of eight.
+// The last round.  With T tiles on G workgroups the last T mod G tiles would keep that many compute
+// units busy for a whole tile while the others idle.  When they are at most G / 2, each of them is
+// split into two work items of 128 tokens x 256 channels (the same eight wavefronts, each 32 tokens
+// x 128 channels: one activation fragment per k-step instead of two), so the last round takes about
+// half a tile.  Items [0, F) are the full tiles, [F, F + 2R) the halves (F = T - R).
 template <int OUT_KIND, bool INT_ONLY>
 __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams p) {
   using C = FastCfg<256, 4, 128, 2, 2, 256>;
-  constexpr int BK = 128, TA = 4, TB = 2, WM = 4, NSTAGE = 2, LPS = C::LPS;
+  constexpr int BK = 128, TA = 4, WM = 4, NSTAGE = 2;
   constexpr int kSlabBase = C::STAGE;                         // slabs: behind stage 0
   constexpr int kParamBase = 160 * 1024 - 2 * C::PARAM_BYTES;  // two parameter blocks: the top 8 KiB
   static_assert(C::LOADS_X == 4 && C::LOADS_W == 4 && C::RPL == 8 && C::KK == 4, "load schedule below");
-  static_assert(kSlabBase + C::NWAVES * 32 * TB * kSlabStride <= kParamBase, "slabs clear of the parameters");
+  static_assert(kSlabBase + C::NWAVES * 64 * kSlabStride <= kParamBase, "slabs clear of the parameters");
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
-  // parameter block b (tiles alternate between the two): offset, mult, fbias [256 channels], row scale [256 rows]
+  // parameter block b (items alternate between the two): offset, mult, fbias [256 channels], row scale [256 rows]
   auto param_block = [&](int b) { return smem + kParamBase + b * C::PARAM_BYTES; };
 
   const int tid = threadIdx.x;
@@ -818,24 +823,29 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int lr = lane >> 3, pc = lane & 7;
   // per-lane byte offset inside a load: row lr of the load's 8 rows, chunk pc ^ swz(row); loads with
-  // odd i sit 8 rows further, which flips bit 2 of the swizzle
+  // odd i sit 8 rows further, which flips bit 2 of the swizzle (a wavefront's share starts at a
+  // multiple of 16 rows, which does not touch bits 1-3)
   const int sw0 = (lr >> 1) & 7;
   const uint32_t xv0 = (uint32_t)lr * (uint32_t)p.ldx + (uint32_t)((pc ^ sw0) << 4);
   const uint32_t xv1 = (uint32_t)lr * (uint32_t)p.ldx + (uint32_t)((pc ^ sw0 ^ 4) << 4);
   const uint32_t wv0 = (uint32_t)lr * (uint32_t)p.ldw + (uint32_t)((pc ^ sw0) << 4);
   const uint32_t wv1 = (uint32_t)lr * (uint32_t)p.ldw + (uint32_t)((pc ^ sw0 ^ 4) << 4);
-  // scalar byte offset of the first row of this wavefront's share (32 rows of either panel)
-  const uint32_t xrow0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldx, wrow0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldw;
+  const uint32_t wrow0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldw;
   const uint32_t xstep = 8u * (uint32_t)p.ldx, wstep = 8u * (uint32_t)p.ldw;
 
   const int total = p.tiles_m * p.tiles_n;
   const int stages = p.k / BK;
-  const uint32_t x_extent = (uint32_t)((uint64_t)255 * (uint64_t)p.ldx + (uint64_t)p.k);
-  const uint32_t w_extent = (uint32_t)((uint64_t)255 * (uint64_t)p.ldw + (uint64_t)p.k);
+  // work items: full tiles, then the halves of the last round's tiles
+  const int G = (int)gridDim.x;
+  const int rest = total % G;
+  const int n_split = (rest > 0 && 2 * rest <= G) ? rest : 0;
+  const int n_full = total - n_split;
+  const int n_items = n_full + 2 * n_split;
 
-  // state of the tile whose panels are being loaded / multiplied
+  // state of the item whose panels are being loaded / multiplied
   int64_t bm0 = 0;
   int bn0 = 0;
+  bool is_half = false;
   __amdgpu_buffer_rsrc_t xdesc, wdesc;
   // The parameters go global -> LDS directly as well (4 bytes per lane, 256 bytes per wavefront load):
   // wavefronts 2a and 2a + 1 fetch the four quarters of array a (0 offset, 1 mult, 2 fbias, 3 row scale).
@@ -846,13 +856,20 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     reinterpret_cast<int32_t *>(param_block(tid >> 8))[tid & 255] = 0;
   }
 
-  auto open_tile = [&](int id, int pb) {  // tile origin, panel descriptors, parameter loads into block pb
+  // item origin and kind, panel descriptors, parameter loads into block pb, panel loads of stage 0
+  auto open_item = [&](int id, int pb) {
+    const int tile = id < n_full ? id : n_full + ((id - n_full) >> 1);
+    is_half = id >= n_full;
     int tile_m, tile_n;
-    tile_of_block(id, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    tile_of_block(tile, p.tiles_m, p.tiles_n, tile_m, tile_n);
     bm0 = (int64_t)tile_m * 256;
     if (bm0 > p.m - 256) bm0 = p.m - 256;
+    if (is_half) bm0 += ((id - n_full) & 1) * 128;
     bn0 = tile_n * 256;
     if (bn0 > p.n - 256) bn0 = p.n - 256;
+    const int rows = is_half ? 128 : 256;
+    const uint32_t x_extent = (uint32_t)((uint64_t)(rows - 1) * (uint64_t)p.ldx + (uint64_t)p.k);
+    const uint32_t w_extent = (uint32_t)((uint64_t)255 * (uint64_t)p.ldw + (uint64_t)p.k);
     xdesc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x + bm0 * p.ldx), 0, (int)x_extent, 0x00020000);
     wdesc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.w + (int64_t)bn0 * p.ldw), 0, (int)w_extent,
                                               0x00020000);
@@ -861,7 +878,8 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     if (p_arr == 1 && OUT_KIND != CWAC_OUT_INT32) src = p.mult + bn0;
     if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32) {
       if (p_arr == 2) src = p.fbias ? p.fbias + bn0 : nullptr;
-      if (p_arr == 3) src = p.sx_row ? p.sx_row + bm0 : nullptr;
+      // a half item has 128 rows: only the first of the two wavefronts of this array loads
+      if (p_arr == 3 && !(is_half && (wave_s & 1))) src = p.sx_row ? p.sx_row + bm0 : nullptr;
     }
     if (src) {  // wave-uniform
       int8_t *dst = param_block(pb) + p_arr * 1024 + (wave_s & 1) * 512;
@@ -871,107 +889,137 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
                                          CWAC_LDS_PTR(dst + j * 256), 4, 0, 0);
     }
   };
-  // chunk 0 of a stage = the four activation loads, chunk 1 = the four weight loads
-  auto issue_chunk = [&](int buf, int k0, int c) {
-    int8_t *dst = smem + buf * C::STAGE + (c ? C::X_BYTES : 0) + wave_s * (32 * BK);
+  // activation loads of one stage: a wavefront's share is 32 rows (four loads) of a full item's 256,
+  // 16 rows (two loads) of a half item's 128; weight loads: always 32 rows of 256
+  auto issue_x = [&](int buf, int k0, bool hf) {
+    if (!hf) {
+      int8_t *dst = smem + buf * C::STAGE + wave_s * (32 * BK);
+      const uint32_t row0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldx + (uint32_t)k0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (c == 0)
+      for (int i = 0; i < 4; ++i)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? xv1 : xv0),
-                                                 (int)(xrow0 + (uint32_t)i * xstep + (uint32_t)k0), 0, 0);
-      else
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(wdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? wv1 : wv0),
-                                                 (int)(wrow0 + (uint32_t)i * wstep + (uint32_t)k0), 0, 0);
+                                                 (int)(row0 + (uint32_t)i * xstep), 0, 0);
+    } else {
+      int8_t *dst = smem + buf * C::STAGE + wave_s * (16 * BK);
+      const uint32_t row0 = (uint32_t)(wave_s * 16) * (uint32_t)p.ldx + (uint32_t)k0;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? xv1 : xv0),
+                                                 (int)(row0 + (uint32_t)i * xstep), 0, 0);
     }
+  };
+  auto issue_w = [&](int buf, int k0) {
+    int8_t *dst = smem + buf * C::STAGE + C::X_BYTES + wave_s * (32 * BK);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(wdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? wv1 : wv0),
+                                               (int)(wrow0 + (uint32_t)i * wstep + (uint32_t)k0), 0, 0);
   };
   const int swz_l = C::swz(l32);
-  const int x_off = (wave_m * 32 * TB + l32) * BK;
   const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
-  auto read_frags = [&](int buf, int kk, v4i(&fw)[TA], v4i(&fx)[TB]) {
-    const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
-    fw[0] = *reinterpret_cast<const v4i *>(base + w_off);
-#pragma unroll
-    for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
-#pragma unroll
-    for (int a = 1; a < TA; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
-  };
-  v16i acc[TA][TB];
-  auto mma = [&](const v4i(&fw)[TA], const v4i(&fx)[TB]) {
-#pragma unroll
-    for (int a = 0; a < TA; ++a)
-#pragma unroll
-      for (int b = 0; b < TB; ++b)
-        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
-  };
-  // one k-step for the scheduler: 8 MFMAs, 6 LDS reads of the next step's fragments behind the first six,
-  // and (loads) four panel loads behind the last two
-  auto interleave = [&](bool loads) {
-#pragma unroll
-    for (int i = 0; i < TA + TB; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    if (loads) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
-      }
-    } else {
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  };
-  v4i fwA[TA], fxA[TB], fwB[TA], fxB[TB];
-  // Stage s of the current tile (buffer s % 2), as in the one-tile kernel: the weight loads of stage
-  // s + 1 go out in the first k-step, the activation loads of stage s + 2 in the last one, behind the
-  // barrier that frees this stage's buffer.
-  auto stage_body = [&](int s, int buf, auto steady_tag) {
-    constexpr bool STEADY = decltype(steady_tag)::value;
-    const bool late_ok = STEADY || (s >= 1 && s + 1 < stages);
-    const bool first_ok = STEADY || (s + NSTAGE < stages);
-#pragma unroll
-    for (int kk = 0; kk + 1 < C::KK; ++kk) {
-      const bool ld = kk == 0 && late_ok;
-      if (ld) issue_chunk(buf ^ 1, (s + 1) * BK, 1);
-      if (kk & 1) {
-        read_frags(buf, kk + 1, fwA, fxA);
-        mma(fwB, fxB);
-      } else {
-        read_frags(buf, kk + 1, fwB, fxB);
-        mma(fwA, fxA);
-      }
-      interleave(ld);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));  // stage s + 1 has landed (nothing else is in flight)
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    if (first_ok) issue_chunk(buf, (s + NSTAGE) * BK, 0);
-    if (STEADY || s + 1 < stages) read_frags(buf ^ 1, 0, fwA, fxA);
-    mma(fwB, fxB);
-    interleave(first_ok);
-  };
 
-  // ---- first tile: nothing was prefetched
   int id = blockIdx.x;
-  if (id >= total) return;
-  int pb = 0;  // parameter block of the tile being multiplied
-  open_tile(id, 0);
-  issue_chunk(0, 0, 0);
-  issue_chunk(0, 0, 1);
-  while (true) {
+  if (id >= n_items) return;
+  int pb = 0;  // parameter block of the item being multiplied
+  bool more = true;
+
+  // One work item from the barrier that ended the previous one to the barrier that ends this one;
+  // TB = 32-token MFMA tiles per wavefront: 2 (full tile) or 1 (half).
+  auto run_item = [&](auto tb_tag) {
+    constexpr int TB = decltype(tb_tag)::value;
+    constexpr bool HF = TB == 1;
+    constexpr int LPS = HF ? 6 : 8;  // panel loads per wavefront and stage
+    const int x_off = (wave_m * 32 * TB + l32) * BK;
+    auto read_frags = [&](int buf, int kk, v4i(&fw)[TA], v4i(&fx)[TB]) {
+      const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
+      fw[0] = *reinterpret_cast<const v4i *>(base + w_off);
+#pragma unroll
+      for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
+#pragma unroll
+      for (int a = 1; a < TA; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
+    };
+    v16i acc[TA][TB];
+    auto mma = [&](const v4i(&fw)[TA], const v4i(&fx)[TB]) {
+#pragma unroll
+      for (int a = 0; a < TA; ++a)
+#pragma unroll
+        for (int b = 0; b < TB; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[a], fx[b], acc[a][b], 0, 0, 0);
+    };
+    // one k-step for the scheduler: TA * TB MFMAs, the TA + TB LDS reads of the next step's fragments
+    // spread behind the first of them, and (loads: how many) panel loads behind the last two
+    auto interleave = [&](int loads) {
+      if constexpr (!HF) {
+#pragma unroll
+        for (int i = 0; i < TA + TB; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        if (loads) {
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+          }
+        } else {
+          __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        }
+      } else {  // four MFMAs, five reads
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (loads == 4) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+        if (loads == 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (loads == 4) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+        if (loads == 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    v4i fwA[TA], fxA[TB], fwB[TA], fxB[TB];
+    // Stage s of this item (buffer s % 2), as in the one-tile kernel: the weight loads of stage
+    // s + 1 go out in the first k-step, the activation loads of stage s + 2 in the last one, behind the
+    // barrier that frees this stage's buffer.
+    auto stage_body = [&](int s, int buf, auto steady_tag) {
+      constexpr bool STEADY = decltype(steady_tag)::value;
+      const bool late_ok = STEADY || (s >= 1 && s + 1 < stages);
+      const bool first_ok = STEADY || (s + NSTAGE < stages);
+#pragma unroll
+      for (int kk = 0; kk + 1 < C::KK; ++kk) {
+        const bool ld = kk == 0 && late_ok;
+        if (ld) issue_w(buf ^ 1, (s + 1) * BK);
+        if (kk & 1) {
+          read_frags(buf, kk + 1, fwA, fxA);
+          mma(fwB, fxB);
+        } else {
+          read_frags(buf, kk + 1, fwB, fxB);
+          mma(fwA, fxA);
+        }
+        interleave(ld ? 4 : 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));  // stage s + 1 has landed (nothing else is in flight)
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      if (first_ok) issue_x(buf, (s + NSTAGE) * BK, HF);
+      if (STEADY || s + 1 < stages) read_frags(buf ^ 1, 0, fwA, fxA);
+      mma(fwB, fxB);
+      interleave(first_ok ? (HF ? 2 : 4) : 0);
+    };
+
     CWAC_STAMPT(id, 0);
-    // stage 0 of this tile is in flight (or has landed), its parameters are in registers; ring stage 1,
-    // the slabs and the parameter block are free (barrier at the end of the previous epilogue)
+    // stage 0 of this item is in flight (or has landed), as are its parameters; ring stage 1, the slabs
+    // and the other parameter block are free (barrier at the end of the previous epilogue)
     if (stages > 1) {
-      issue_chunk(1, BK, 0);
-      issue_chunk(1, BK, 1);
-    }
-    if (stages > 1)
-      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(LPS, 0));  // all but stage 1: stage 0 has landed
-    else
+      issue_x(1, BK, HF);
+      issue_w(1, BK);
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(LPS, 0));  // all but stage 1: stage 0 and the parameters have landed
+    } else {
       __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    }
     __builtin_amdgcn_s_barrier();
     const int32_t *s_off = reinterpret_cast<const int32_t *>(param_block(pb));
     read_frags(0, 0, fwA, fxA);
@@ -1005,17 +1053,17 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
           read_frags(0, kk + 1, fwB, fxB);
           mma(fwA, fxA);
         }
-        interleave(false);
+        interleave(0);
       }
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
       const bool first_ok = NSTAGE < stages;
-      if (first_ok) issue_chunk(0, NSTAGE * BK, 0);
+      if (first_ok) issue_x(0, NSTAGE * BK, HF);
       if (stages > 1) read_frags(1, 0, fwA, fxA);
       mma(fwB, fxB);
-      interleave(first_ok);
+      interleave(first_ok ? (HF ? 2 : 4) : 0);
     }
     int s = 1;
     for (; s + 2 * NSTAGE <= stages; s += NSTAGE) {  // steady state, unrolled over the ring
@@ -1026,25 +1074,25 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     for (; s < stages; ++s) stage_body(s, s & 1, std::false_type{});
 
     // ---- the ring is free (every wavefront fetched its last fragments before the last barrier):
-    // open the next tile - its parameter loads and the panel loads of its stage 0 travel under this
-    // tile's epilogue.  The epilogue reads this tile's origin, so that is kept aside first.
+    // open the next item - its parameter loads and the panel loads of its stage 0 travel under this
+    // item's epilogue.  The epilogue reads this item's origin, so that is kept aside first.
     CWAC_STAMPT(id, 2);
     const int64_t e_bm0 = bm0;
     const int e_bn0 = bn0;
-    const int next = id + (int)gridDim.x;
-    const bool more = next < total;
+    const int next = id + G;
+    more = next < n_items;
     if (more) {
-      open_tile(next, pb ^ 1);
-      issue_chunk(0, 0, 0);
-      issue_chunk(0, 0, 1);
+      open_item(next, pb ^ 1);
+      issue_x(0, 0, is_half);
+      issue_w(0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
     {
       const float *s_mult = reinterpret_cast<const float *>(param_block(pb) + 1024);
       const float *s_fb = reinterpret_cast<const float *>(param_block(pb) + 2048);
       const float *s_rs = reinterpret_cast<const float *>(param_block(pb) + 3072);
-      // the lane index the epilogue derives its addresses from is made opaque per tile: otherwise all of
-      // that lane arithmetic is hoisted out of the tile loop and lives (spilled) across the main loop
+      // the lane index the epilogue derives its addresses from is made opaque per item: otherwise all of
+      // that lane arithmetic is hoisted out of the item loop and lives (spilled) across the main loop
       int lane_e = lane;
       asm volatile("" : "+v"(lane_e));
       constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8) ? 1 : 4;
@@ -1058,10 +1106,22 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     }
     CWAC_STAMPT(id, 3);
     CWAC_STAMPT(id, 4);
-    if (!more) break;
     id = next;
+  };
+
+  // ---- first item: nothing was prefetched
+  open_item(id, 0);
+  issue_x(0, 0, is_half);
+  issue_w(0, 0);
+  while (true) {
+    const bool hf = is_half;  // of the item about to run (open_item inside run_item overwrites it)
+    if (hf)
+      run_item(std::integral_constant<int, 1>{});
+    else
+      run_item(std::integral_constant<int, 2>{});
+    if (!more) break;
     pb ^= 1;
-    __builtin_amdgcn_s_barrier();  // every wavefront is done with the slabs and this tile's parameter block
+    __builtin_amdgcn_s_barrier();  // every wavefront is done with the slabs and that item's parameter block
   }
 }
 
@@ -1213,16 +1273,16 @@ int fast_linear_shape(int64_t m, int n, int k, int out_bytes) {
   // layer shapes (K 512 .. 11008, 196 .. 3072 tiles of 256 x 256).
   //  * Few tiles and a long K loop: 128 x 128 tiles (fast_prefers_quarter_tile).
   //  * Less than a round of 256 x 256 tiles: the 128-token tile where the one-tile cost model prefers it.
-  //  * Otherwise the persistent 256 x 256 tile - except for short K loops whose last round of tiles
-  //    leaves much of the chip idle: there the 128 x 128 tile (three workgroups per compute unit, four
-  //    times as many tiles) finishes sooner; with 4-byte outputs, whose store bursts it also spreads,
-  //    already at a milder imbalance.
+  //  * Otherwise the persistent 256 x 256 tile (which splits the tiles of a thin last round in two).
+  //    With 4-byte outputs and a short K loop the tile's store burst weighs as much as its K loop:
+  //    when, on top, the last round leaves a good part of the chip idle, the 128 x 128 tile (three
+  //    workgroups per compute unit, four times as many tiles, stores spread out) finishes sooner.
   if (fast_prefers_quarter_tile(m, n)) return CWAC_SHAPE_128_128;
   if ((k % 128) != 0) return CWAC_SHAPE_128_PAIR;
   const int64_t t256 = ceil_div(m, 256) * ceil_div(n, 256);
   if (t256 < 160) return fast_prefers_half_tile(m, n, k, out_bytes) ? CWAC_SHAPE_128_PAIR : CWAC_SHAPE_256_PERSIST;
   const double fill = (double)t256 / (double)(256 * ceil_div(t256, 256));  // busy share of the rounds
-  if (k <= 1024 && fill < (out_bytes > 1 ? 0.85 : 0.70)) return CWAC_SHAPE_128_128;
+  if (out_bytes > 1 && k <= 1024 && fill < 0.85) return CWAC_SHAPE_128_128;
   return CWAC_SHAPE_256_PERSIST;
 }
 

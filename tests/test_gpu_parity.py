@@ -397,7 +397,7 @@ def test_stats_empty_state_and_single_row(orc):
     np.testing.assert_array_equal(b, np.arange(8, dtype=np.float32) * 0.5)
 
 
-@pytest.mark.parametrize("wgs", [1, 3, 7, 0])
+@pytest.mark.parametrize("wgs", [1, 3, 5, 7, 11, 0])
 @pytest.mark.parametrize("m,n,k", [(1300, 1030, 512), (600, 780, 128), (777, 520, 256), (520, 1290, 384),
                                    (1030, 600, 1152)])
 def test_forward_persistent_tiles(orc, m, n, k, wgs):
