@@ -1003,7 +1003,7 @@ def power_trace(P, synth, torch, dev: str, cfg: int, seconds: float = 5.0):
         out[key]["pops"] = round(fwd_ops / (out[key]["ms_per_pass"] * 1e-3) / 1e15, 4)
     out["mfma_probe_workload_operands"]["pops"] = round(
         2.0 * 32768 * 16 * 20000 * 4 * cus / (out["mfma_probe_workload_operands"]["ms_per_pass"] * 1e-3) / 1e15, 4)
-    return {"power_trace": f"config {cfg}: each phase launched back to back for {seconds} s; rocm-smi sampled "
+    return {"power_trace": f"config {cfg}: each phase launched back to back for {seconds} s; amd-smi sampled "
                            "from a helper thread; statistics of the last two thirds of the samples",
             "phases": out}
 
@@ -1018,8 +1018,8 @@ def tile_timeline(torch, synth, dev: str, cfgs):
     from paper_2505_20932_amd import build as B
     if not os.path.exists(B.STAMP_LIB):
         raise SystemExit(f"{B.STAMP_LIB} is missing: python -m paper_2505_20932_amd.build --timeline")
-    os.environ["CWAC_LIB"] = B.STAMP_LIB
     import paper_2505_20932_amd as P
+    assert P.binding.LIB_PATH == B.STAMP_LIB, P.binding.LIB_PATH
     lib = P.binding.lib()
     lib.cwac_debug_stamps.restype = ctypes.c_int
     lib.cwac_debug_stamps.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
@@ -1047,17 +1047,45 @@ def tile_timeline(torch, synth, dev: str, cfgs):
                 for _ in range(10):
                     fwd()
                 torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(20):
+                    fwd()
+                e1.record()
+                torch.cuda.synchronize()
+                launch_us = e0.elapsed_time(e1) / 20 * 1e3
                 buf.zero_()
                 fwd()
                 torch.cuda.synchronize()
                 assert lib.cwac_debug_stamps(buf.data_ptr(), buf.numel() * 8, None) == 0
                 torch.cuda.synchronize()
-                st = buf.cpu().numpy().reshape(4096, 8, 5)[:tiles].astype(np.float64) * 0.01       # us
+                # work items of the launch: tiles, or, persistent, whole tiles followed by the two
+                # 128-token halves of every tile of a thin last round
+                items, wgs, n_whole = tiles, tiles, tiles
+                if shape == P.binding.CWAC_SHAPE_256_PERSIST:
+                    wgs = min(tiles, torch.cuda.get_device_properties(0).multi_processor_count)
+                    rest = tiles % wgs
+                    if 0 < rest and 2 * rest <= wgs:
+                        n_whole, items = tiles - rest, tiles + rest
+                st = buf.cpu().numpy().reshape(4096, 8, 5)[:min(items, 4096)].astype(np.float64) * 0.01       # us
                 st -= st[:, :, 0].min()
-                d = [float((st[:, :, i + 1] - st[:, :, i]).mean()) for i in range(4)]
-                ent[name] = {"kernel_span_us": round(float(st[:, :, 4].max()), 1),
+                whole = st[:n_whole]
+                d = [float((whole[:, :, i + 1] - whole[:, :, i]).mean()) for i in range(4)]
+                ent[name] = {"back_to_back_launch_us": round(launch_us, 1),
+                             "kernel_span_us": round(float(st[:, :, 4].max()), 1), "workgroups": wgs,
                              "start_to_first_mfma_us": round(d[0], 2), "k_loop_us": round(d[1], 2),
                              "epilogue_us": round(d[2], 2), "store_drain_us": round(d[3], 2)}
+                if shape == P.binding.CWAC_SHAPE_256_PERSIST:
+                    # the rounds of the walk: work items [r * workgroups, (r + 1) * workgroups)
+                    rounds = []
+                    for r0 in range(0, st.shape[0], wgs):
+                        blk = st[r0:r0 + wgs]
+                        rounds.append({"items": int(blk.shape[0]), "rows": 256 if r0 < n_whole else 128,
+                                       "first_start_us": round(float(blk[:, :, 0].min()), 1),
+                                       "mean_start_us": round(float(blk[:, :, 0].mean()), 1),
+                                       "mean_end_us": round(float(blk[:, :, 4].mean()), 1),
+                                       "last_end_us": round(float(blk[:, :, 4].max()), 1)})
+                    ent[name]["rounds"] = rounds
             out.append(ent)
         del layers
         torch.cuda.empty_cache()
@@ -1081,6 +1109,12 @@ def time_steps(P, torch, layers, steps: int, warmup: int):
     return time.perf_counter() - t0, events
 
 
+def forward_floors_us(m: int, n: int, k: int):
+    """Lower bounds of one int8 forward launch: its operations at the published int8 MFMA peak and
+    its compulsory bytes (activations, weights and int8 codes, each once) at the published HBM peak."""
+    return 2.0 * m * n * k / INT8_MFMA_PEAK_TOPS / 1e6, (m * k + n * k + m * n) / HBM_PEAK_GBS / 1e3
+
+
 def summarize(layers, events, steps: int, elapsed: float):
     """Phase totals (ms per step) and the per-layer table of one timed run."""
     nl = len(layers)
@@ -1094,10 +1128,16 @@ def summarize(layers, events, steps: int, elapsed: float):
         ev = [events[s * nl + i] for s in range(steps)]
         us = [sum(e[j].elapsed_time(e[j + 1]) for e in ev) / steps * 1e3 for j in range(4)]
         ops = 2.0 * L.m * L.n * L.k
+        mfma_floor, hbm_floor = forward_floors_us(L.m, L.n, L.k)
         per_layer.append({
             "layer": L.name, "m": L.m, "n": L.n, "k": L.k, "calibration_rows": L.cal_rows,
             "forward_int8_us": round(us[3], 1), "forward_int8_tops": round(ops / us[3] / 1e6, 1),
             "forward_int8_frac": round(ops / us[3] / 1e6 / INT8_MFMA_PEAK_TOPS, 4),
+            # what the two published peaks allow: the layer's operations at the int8 MFMA peak, its
+            # compulsory bytes (X, W_q, int8 output, once each) at the HBM peak; a layer cannot
+            # pass mfma_floor / max(mfma_floor, hbm_floor) of the MFMA peak
+            "forward_int8_mfma_floor_us": round(mfma_floor, 2), "forward_int8_hbm_floor_us": round(hbm_floor, 2),
+            "forward_int8_frac_ceiling": round(mfma_floor / max(mfma_floor, hbm_floor), 4),
             "calibration_forward_us": round(us[0], 1),
             "calibration_forward_tops": round(2.0 * L.cal_rows * L.n * L.k / us[0] / 1e6, 1),
             "statistics_us": round(us[1], 1),
@@ -1140,7 +1180,11 @@ def per_config_entry(wl, layers, sm, collapse=None):
                     + ("per-token" if wl.per_token else "per-tensor") + " activations",
         "ms_per_step": round(sm["ms_per_step"], 4),
         "forward_int8": {"tops": round(sm["fwd_tops"], 1), "frac": round(sm["fwd_tops"] / INT8_MFMA_PEAK_TOPS, 4),
-                         "ms": round(sm["t_fwd"], 4), "bound": "mfma", "peak_tops": INT8_MFMA_PEAK_TOPS},
+                         "ms": round(sm["t_fwd"], 4), "bound": "mfma", "peak_tops": INT8_MFMA_PEAK_TOPS,
+                         # sum of MFMA floors over sum of max(MFMA floor, HBM floor): the fraction of the
+                         # MFMA peak that the two published peaks leave to this mix of layer shapes
+                         "frac_ceiling": round(sum(forward_floors_us(L.m, L.n, L.k)[0] for L in layers)
+                                               / sum(max(forward_floors_us(L.m, L.n, L.k)) for L in layers), 4)},
         "statistics": {"gbs": round(sm["stats_gbs"], 1), "frac": round(sm["stats_gbs"] / HBM_PEAK_GBS, 4),
                        "ms": round(sm["t_stats"], 4), "bound": "hbm", "peak_gbs": HBM_PEAK_GBS,
                        "launches": "cwac_calibrate_stats_first: stats_partial_kernel + stats_merge_kernel"},
@@ -1290,6 +1334,10 @@ def main():
                          "49,16,32,2048 with --block-batch 512 is Swin-B's third stage at 8 images")
     ap.add_argument("--no-per-config", action="store_true",
                     help="skip the per_config block (workloads 1-5, each through the same step)")
+    ap.add_argument("--step-only", action="store_true",
+                    help="only the warm-up and timed steps (no graph replay, comparators, probe, CPU baseline, "
+                         "per-config, streaming or weight-only sections): the launch mix of a profiler run then is "
+                         "the timed region's own")
     ap.add_argument("--no-full-stream", action="store_true",
                     help="skip the leg that streams workload 5's whole calibration set (262144 rows per layer)")
     ap.add_argument("--per-config-steps", type=int, default=5)
@@ -1310,6 +1358,9 @@ def main():
 
     import torch
     if args.tile_timeline:
+        # the package reads the library path when it is first imported
+        os.environ["CWAC_LIB"] = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2505_20932_amd",
+                                              "libcwac_hip_timeline.so")
         from paper_2505_20932_amd import synth
         assert torch.cuda.is_available(), "bench.py needs the MI355X"
         torch.cuda.set_device(0)
@@ -1365,10 +1416,14 @@ def main():
     nl = len(layers)
     default_run = cal_rows == wl.m
     # the kernel the dispatcher takes for most of the int8 forward's launches
-    big = sum(1 for L in layers if L.n >= 256 and L.k % 128 == 0 and L.m >= 256)
-    fwd_kernel = ("qlinear_fast_kernel<256,4,128,2,2,CWAC_OUT_INT8,...> (direct-to-LDS, 256 x 256 tile, eight "
-                  "wavefronts; int8 out, fused CWAC epilogue)" if big and wl.cfg == 5 else
-                  "qlinear_fast_kernel / qlinear_kernel as the dispatcher picks per layer (int8 out, fused CWAC epilogue)")
+    direct = all(P.binding.cwac_forward_kernel_for(L.m, L.n, L.k, L.k, L.k, P.CWAC_OUT_INT8)
+                 == P.binding.CWAC_KERNEL_DIRECT_LDS
+                 for L in layers)
+    fwd_kernel = ("qlinear_persist_kernel<CWAC_OUT_INT8, ...> (persistent 256 x 256 tile, eight wavefronts, one "
+                  "workgroup per compute unit, direct-to-LDS panels; int8 out, fused CWAC epilogue)"
+                  if direct and all(L.k % 128 == 0 for L in layers) else
+                  "qlinear_persist_kernel / qlinear_fast_kernel / qlinear_kernel as the dispatcher picks per layer "
+                  "(int8 out, fused CWAC epilogue)")
     result = {
         # the metric's named quantity: int8 operations of the fused forward over its own time inside
         # the step (HIP events); the whole step's blended rate is whole_step_tops
@@ -1403,6 +1458,10 @@ def main():
         "stats_gbs": round(stats_gbs, 1),
     }
     headline_entry = per_config_entry(wl, layers, sm, (4, 12) if wl.cfg == 3 else None) if default_run else None
+    if args.step_only:
+        result["layers"] = sm["per_layer"]
+        print(json.dumps(result))
+        return
     # the same step captured once in a HIP graph and replayed (what a launch-bound caller would do)
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
