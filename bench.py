@@ -1095,6 +1095,69 @@ def tile_timeline(torch, synth, dev: str, cfgs):
             "layers": out}
 
 
+def forward_shapes(P, synth, torch, dev: str, cfgs, reps: int = 20):
+    """Every tile shape of the direct-to-LDS forward that a layer admits, chosen through cwac_tuning, timed
+    on each distinct layer shape of the workloads (int8 output, the layer's own folded epilogue): `reps`
+    back-to-back launches after 5 warm-up launches, HIP events.  `auto` is the dispatcher's own choice."""
+    B = P.binding
+    shapes = [("auto", None), ("256_8W", B.CWAC_SHAPE_256_8W), ("256_4W_K128", B.CWAC_SHAPE_256_4W_K128),
+              ("256_4W_K64", B.CWAC_SHAPE_256_4W_K64), ("128_PAIR", B.CWAC_SHAPE_128_PAIR),
+              ("128_128", B.CWAC_SHAPE_128_128), ("256_PERSIST", B.CWAC_SHAPE_256_PERSIST)]
+    out = []
+    for cfg in cfgs:
+        wl, layers = setup_layers(P, synth, torch, cfg, dev, synth.WORKLOADS[cfg].m)
+        run_step(P, layers)
+        torch.cuda.synchronize()
+        seen = set()
+        for L in layers:
+            if (L.n, L.k) in seen:
+                continue
+            seen.add((L.n, L.k))
+            ent = {"workload": cfg, "layer": L.name, "m": L.m, "n": L.n, "k": L.k, "us": {}}
+            for name, shape in shapes:
+                tun = None if shape is None else P.make_tuning(kernel=B.CWAC_KERNEL_DIRECT_LDS, shape=shape)
+
+                def fwd():
+                    P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
+                                           L.sx_row, P.CWAC_OUT_INT8, L.out, tuning=tun)
+                try:
+                    for _ in range(5):
+                        fwd()
+                except Exception:   # the shape does not admit this layer (status code from the library)
+                    ent["us"][name] = None
+                    continue
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(reps):
+                    fwd()
+                e1.record()
+                torch.cuda.synchronize()
+                ent["us"][name] = round(e0.elapsed_time(e1) / reps * 1e3, 1)
+            # the vendor library's int8 GEMM on the same operands: the raw int32 product, no epilogue
+            try:
+                wt = L.wq.t()
+                for _ in range(5):
+                    torch._int_mm(L.xq, wt)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(reps):
+                    torch._int_mm(L.xq, wt)
+                e1.record()
+                torch.cuda.synchronize()
+                ent["us"]["torch._int_mm (int32 product only)"] = round(e0.elapsed_time(e1) / reps * 1e3, 1)
+            except Exception as exc:
+                ent["us"]["torch._int_mm (int32 product only)"] = f"unavailable: {type(exc).__name__}"
+            ent["tops"] = {k: (round(2.0 * L.m * L.n * L.k / v / 1e6, 1) if isinstance(v, float) else None)
+                           for k, v in ent["us"].items()}
+            out.append(ent)
+        del layers
+        torch.cuda.empty_cache()
+    return {"forward_shapes": "int8 forward per layer shape and tile shape (cwac_tuning.shape), microseconds per launch, "
+                              f"{reps} back-to-back launches", "layers": out}
+
+
 def time_steps(P, torch, layers, steps: int, warmup: int):
     """warmup untimed passes of run_step, then `steps` timed ones (host clock around the whole
     region, HIP events on the launch stream around every phase of every layer)."""
@@ -1347,6 +1410,9 @@ def main():
     ap.add_argument("--tile-timeline", action="store_true",
                     help="instead of the benchmark: in-kernel time stamps of the int8 forward's tiles on workloads "
                          "2-5 (needs `python -m paper_2505_20932_amd.build --timeline`; its own JSON line)")
+    ap.add_argument("--forward-shapes", action="store_true",
+                    help="instead of the benchmark: the int8 forward of every distinct layer shape of workloads 2-5 "
+                         "under each tile shape of the direct-to-LDS kernel (its own JSON line)")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -1380,6 +1446,9 @@ def main():
         print(json.dumps(block_section(P, torch, dev, args.block_batch, args.steps, args.warmup,
                                        0 if args.no_cpu_baseline else 2, args.blocks,
                                        tuple(int(v) for v in args.block_shape.split(",")))))
+        return
+    if args.forward_shapes:
+        print(json.dumps(forward_shapes(P, synth, torch, dev, (2, 3, 4, 5))))
         return
     if args.power_trace:
         print(json.dumps(power_trace(P, synth, torch, dev, args.config)))
