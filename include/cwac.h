@@ -589,7 +589,9 @@ typedef struct cwac_tuning {
   int32_t w4_small_waves; /* ... its weight-streaming kernel (m <= 128): 0 | 4 | 8 wavefronts per workgroup */
   int32_t persist_workgroups; /* CWAC_SHAPE_256_PERSIST: 0 = one workgroup per compute unit; n > 0 = at most n
                                  (each then walks more tiles; leaves compute units to concurrent work) */
-  int32_t reserved[2];    /* zero */
+  int32_t w4_small_depth; /* ... and its ring depth: 0 | 2 | 3 | 4 groups of 128 input channels in flight per
+                             wavefront (a depth whose rings do not fit the LDS is lowered to one that does) */
+  int32_t reserved;       /* zero */
 } cwac_tuning;
 
 /* Which kernel qlinear_cwac_forward(_ex) would run for these sizes and this tuning (host

@@ -512,21 +512,42 @@ cwac_status launch_w4(const W4Params &p, hipStream_t st) {
 
 // ------------------------------------------------------------------------------------------
 // Small batches (32 tokens per launch: the decode step of an LLM).  The layer is then bound by the
-// stream of 4-bit weights, not by the matrix cores: one workgroup of NW (4 or 8) wavefronts owns 32 output
-// channels (one row of 1 KiB blocks of the packed layout) over the whole of K, each wavefront a
-// contiguous quarter of the groups; the codes arrive with the same contiguous 16-byte-per-lane loads
-// as in the tiled kernel, are expanded in registers and meet the activations (read straight from
-// memory: m rows of K binary16 values stay in the caches) in one 32 x 32 MFMA tile per 16 input
-// channels, rows beyond m idle.  The four partial tiles are added in wavefront order through LDS
+// stream of 4-bit weights, not by the matrix cores: one workgroup of NW (4 or 8) wavefronts owns 32
+// output channels (one row of 1 KiB blocks of the packed layout) over the whole of K, each wavefront
+// a contiguous share of the groups.  Neither operand passes through registers on its way in: every
+// wavefront owns a ring of D slots in LDS - per group 2 KiB of codes, the 32 scale / zero-point
+// words and the group's block of activations (MP rows x 256 bytes, MP = m rounded up to 8, 16 or
+// 32) - that global_load_lds fills D groups ahead of the arithmetic.  The activations are fetched
+// four rows per instruction (whole 256-byte row pieces: a lane-per-row register load would touch 32
+// cache lines per instruction, which bounded the kernel by the L1's tag rate), with the chunk
+// position XOR (row & 15) applied on the global-address side so that the MFMA operand reads
+// (lane = token row) are free of bank conflicts.  Rows beyond m repeat row m - 1 (their results are
+// not stored).  Codes are expanded in registers and meet the activations in one 32 x 32 MFMA tile
+// per 16 input channels.  The wavefronts' partial tiles are added in wavefront order through LDS
 // (deterministic), then the epilogue of the tiled kernel.  No workspace, no atomics.
 // ------------------------------------------------------------------------------------------
 constexpr int kSmallM = 32;
 constexpr int kHalfTileUpTo = 256;  // 128-token tiles in a launch up to which they are taken (one per compute unit)
 constexpr int kSmallPasses = 4;  // batches of up to 128 rows take this kernel, 32 rows per launch
 
-template <int OUT_KIND, int NW>
+template <int NW, int MP, int D_>
+struct StreamCfg {
+  static constexpr int D = D_;                     // ring slots per wavefront
+  static constexpr int X_OFF = 2048 + 256;         // codes, then 64 lanes x 4 bytes of scale words, then activations
+  static constexpr int SLOT = X_OFF + MP * 256;
+  static constexpr int RING = D * SLOT;
+  static constexpr int LX = MP / 4, LW = 3, L = LX + LW;  // load instructions per group
+  static constexpr int PART = (NW - 1) * 16 * 64 * 4;  // partial tiles of wavefronts 1 .. NW - 1 (over the rings)
+  static constexpr int LDS = NW * RING > PART ? NW * RING : PART;
+  static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
+  static_assert(D >= 2 && D <= 4 && (D - 1) * L < 64, "waits below are written for up to three groups in flight");
+};
+
+template <int OUT_KIND, int NW, int MP, int D_>
 __global__ __launch_bounds__(64 * NW) void w4a16_small_m_kernel(const W4Params p) {
-  __shared__ float s_part[NW - 1][16][64];
+  using S = StreamCfg<NW, MP, D_>;
+  constexpr int D = S::D, L = S::L;
+  extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, half = lane >> 5;
@@ -534,66 +555,102 @@ __global__ __launch_bounds__(64 * NW) void w4a16_small_m_kernel(const W4Params p
   const int groups = p.k / kGroup, kb64 = p.k / 64;
   const int g_begin = wave * groups / NW, g_end = (wave + 1) * groups / NW;
   const bool row_ok = l32 < p.m;
+  int8_t *ring = smem + wave * S::RING;
 
   const char *wrow = reinterpret_cast<const char *>(p.wp) + (int64_t)nb * kb64 * 1024 + lane * 16;
-  // activations through a buffer descriptor that ends with row m - 1: the lanes of rows beyond m
-  // read zeros without touching memory, and the loads need no branches
-  const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<char *>(p.x), 0, (int)((p.m - 1) * p.ldx_bytes + (int64_t)p.k * 2), 0x00020000);
-  const uint32_t xvo = (uint32_t)l32 * (uint32_t)p.ldx_bytes + (uint32_t)half * 16u;
-  struct Raw {
-    u4 c[2];
-    uint32_t sz;
-    h8 x[8];
-  };
-  auto fetch = [&](Raw &r, int g) {
-    r.c[0] = *reinterpret_cast<const GU4 *>(CWAC_GLOBAL_PTR(wrow + (int64_t)(2 * g) * 1024));
-    r.c[1] = *reinterpret_cast<const GU4 *>(CWAC_GLOBAL_PTR(wrow + (int64_t)(2 * g + 1) * 1024));
-    r.sz = p.sz[(int64_t)g * p.n + n0 + l32];
+  const uint32_t *szp = p.sz + n0 + l32;
+  // activation loads: instruction t covers rows 4 t .. 4 t + 3 of the block, lane i = (row i / 16,
+  // chunk position i % 16), which receives the row's chunk (i % 16) ^ (row & 15)
+  uint32_t xoff[S::LX];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
-      r.x[kk] = __builtin_bit_cast(h8, __builtin_amdgcn_raw_buffer_load_b128(xres, xvo + g * 256 + kk * 32, 0, 0));
+  for (int t = 0; t < S::LX; ++t) {
+    const int row = 4 * t + (lane >> 4);
+    const int src_row = row < (int)p.m ? row : (int)p.m - 1;
+    xoff[t] = (uint32_t)src_row * (uint32_t)p.ldx_bytes + (uint32_t)(((lane & 15) ^ (row & 15)) << 4);
+  }
+  // group g -> slot: two 1 KiB blocks of codes, one scale word per lane (the upper half-wave repeats
+  // the lower one's 32 words), MP / 4 blocks of four activation rows
+  auto issue = [&](int g, int slot_i) {
+    int8_t *slot = ring + slot_i * S::SLOT;
+    __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wrow + (int64_t)(2 * g) * 1024), CWAC_LDS_PTR(slot), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(wrow + (int64_t)(2 * g + 1) * 1024), CWAC_LDS_PTR(slot + 1024),
+                                     16, 0, 0);
+    __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(szp + (int64_t)g * p.n), CWAC_LDS_PTR(slot + 2048), 4, 0, 0);
+    const char *xg = p.x + (int64_t)g * 256;
+#pragma unroll
+    for (int t = 0; t < S::LX; ++t)
+      __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xg + xoff[t]), CWAC_LDS_PTR(slot + S::X_OFF + t * 1024), 16, 0,
+                                       0);
   };
+  // MFMA operand of k-step kk: row l32 (clamped into the block), chunk 2 kk + half
+  const int xrow = l32 < MP ? l32 : MP - 1;
+  const int xrd = S::X_OFF + xrow * 256, xsw = xrow & 15;
   // two accumulators (even / odd k-steps): consecutive MFMAs do not wait for each other
   v16f acc, acc1;
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = acc1[i] = 0.0f;
   const ExpandConst ec = expand_const();
-  auto consume = [&](const Raw &r) {
-    const GroupConst gc = group_const(r.sz);
+
+  // Memory operations return in order, so "at most N outstanding" means everything older than the
+  // newest N has arrived: with r groups issued behind group g, group g is complete at r * L.
+  int slot_i = 0;
+#pragma unroll 1
+  for (int i = 0; i < D; ++i)
+    if (g_begin + i < g_end) issue(g_begin + i, i);
+#pragma unroll 1
+  for (int g = g_begin; g < g_end; ++g) {
+    const int behind = g_end - 1 - g < D - 1 ? g_end - 1 - g : D - 1;
+    if (behind >= 3)
+      __builtin_amdgcn_s_waitcnt(wait_imm(3 * L, 15));
+    else if (behind == 2)
+      __builtin_amdgcn_s_waitcnt(wait_imm(2 * L, 15));
+    else if (behind == 1)
+      __builtin_amdgcn_s_waitcnt(wait_imm(L, 15));
+    else
+      __builtin_amdgcn_s_waitcnt(wait_imm(0, 15));
+    asm volatile("" ::: "memory");  // the slot reads stay below the wait
+    __builtin_amdgcn_sched_barrier(0);
+    const int8_t *slot = ring + slot_i * S::SLOT;
+    const u4 c0 = *reinterpret_cast<const u4 *>(slot + lane * 16);
+    const u4 c1 = *reinterpret_cast<const u4 *>(slot + 1024 + lane * 16);
+    const uint32_t sz = *reinterpret_cast<const uint32_t *>(slot + 2048 + l32 * 4);
+    h8 x[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      x[kk] = *reinterpret_cast<const h8 *>(slot + xrd + (((2 * kk + half) ^ xsw) << 4));
+    if (g + D < g_end) {
+      // the slot's contents are in registers before the next group may land in it
+      __builtin_amdgcn_s_waitcnt(wait_imm(63, 0));
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+      issue(g + D, slot_i);
+    }
+    slot_i = slot_i + 1 == D ? 0 : slot_i + 1;
+    const GroupConst gc = group_const(sz);
 #pragma unroll
     for (int kk = 0; kk < 8; kk += 2) {
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand8(r.c[kk >> 2][kk & 3], gc, ec), r.x[kk], acc, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand8(r.c[(kk + 1) >> 2][(kk + 1) & 3], gc, ec),
-                                                    r.x[kk + 1], acc1, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand8(kk < 4 ? c0[kk & 3] : c1[kk & 3], gc, ec), x[kk], acc, 0, 0,
+                                                   0);
+      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(expand8(kk + 1 < 4 ? c0[(kk + 1) & 3] : c1[(kk + 1) & 3], gc, ec),
+                                                    x[kk + 1], acc1, 0, 0, 0);
     }
-  };
-  // two groups in flight: the loads of group g + 1 are issued before group g is consumed.  (A
-  // deeper ring does not pay: the kernel is bound by the expansion arithmetic, about 140 vector
-  // instructions per group and wavefront, not by the latency of the stream.)
-  Raw ra, rb;
-  int g = g_begin;
-  if (g < g_end) fetch(ra, g);
-  for (; g + 2 <= g_end; g += 2) {
-    fetch(rb, g + 1);
-    consume(ra);
-    if (g + 2 < g_end) fetch(ra, g + 2);
-    consume(rb);
   }
-  if (g < g_end) consume(ra);
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] += acc1[i];
 
+  // partial tiles over the rings, once every wavefront has left its ring
+  float *s_part = reinterpret_cast<float *>(smem);
+  __syncthreads();
   if (wave > 0) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) s_part[wave - 1][i][lane] = acc[i];
+    for (int i = 0; i < 16; ++i) s_part[((wave - 1) * 16 + i) * 64 + lane] = acc[i];
   }
   __syncthreads();
   if (wave != 0) return;
-#pragma unroll
+#pragma unroll 1
   for (int w = 0; w < NW - 1; ++w)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] += s_part[w][i][lane];
+    for (int i = 0; i < 16; ++i) acc[i] += s_part[(w * 16 + i) * 64 + lane];
   if (!row_ok) return;
   constexpr int ESZ = OUT_KIND == CWAC_OUT_FP16 ? 2 : 4;
   char *orow = p.out + ((int64_t)l32 * p.ldo + n0) * ESZ;
@@ -616,16 +673,48 @@ __global__ __launch_bounds__(64 * NW) void w4a16_small_m_kernel(const W4Params p
   }
 }
 
-template <int OUT_KIND>
-cwac_status launch_w4_small(const W4Params &p, int waves, hipStream_t st) {
-  // four wavefronts per workgroup; eight where there are fewer workgroups than compute units
-  // (waves: the caller's override, cwac_tuning.w4_small_waves)
-  const int nw = waves ? waves : (p.n / 32 < 256 ? 8 : 4);
-  if (nw == 4)
-    w4a16_small_m_kernel<OUT_KIND, 4><<<dim3((unsigned)(p.n / 32)), 256, 0, st>>>(p);
-  else
-    w4a16_small_m_kernel<OUT_KIND, 8><<<dim3((unsigned)(p.n / 32)), 512, 0, st>>>(p);
+template <int OUT_KIND, int NW, int MP, int D>
+cwac_status launch_w4_small_cfg(const W4Params &p, hipStream_t st) {
+  static const hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a16_small_m_kernel<OUT_KIND, NW, MP, D>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, StreamCfg<NW, MP, D>::LDS);
+  if (attr != hipSuccess) return CWAC_E_LAUNCH;
+  w4a16_small_m_kernel<OUT_KIND, NW, MP, D><<<dim3((unsigned)(p.n / 32)), 64 * NW, StreamCfg<NW, MP, D>::LDS, st>>>(p);
   return launch_status();
+}
+
+template <int OUT_KIND>
+cwac_status launch_w4_small(const W4Params &p, int waves, int depth, hipStream_t st) {
+  // Four wavefronts per workgroup where the layer has at least as many channel blocks as the chip
+  // has compute units, eight with fewer blocks (waves, depth: the caller's overrides,
+  // cwac_tuning.w4_small_waves / w4_small_depth).  The ring depth trades bytes in flight per
+  // wavefront against resident wavefronts per compute unit (the rings are what fills its LDS):
+  // two slots - four workgroups of four wavefronts per compute unit at up to 8 rows - measured
+  // best on every layer shape, since what a wavefront waits for most is its first group.  A
+  // combination whose rings do not fit the LDS takes the nearest one that does.
+  int nw = waves ? waves : (p.n / 32 >= 256 ? 4 : 8);
+  const int mp = p.m <= 8 ? 8 : (p.m <= 16 ? 16 : 32);
+  if (mp == 32) nw = 4;  // 32-row activation blocks leave room for the rings of four wavefronts only
+  int d = depth ? depth : 2;
+  if (mp == 32 && d > 3) d = 3;
+  if (mp == 16 && nw == 8 && d > 3) d = 3;
+#define CWAC_W4_SMALL(NW, MP, D) \
+  if (nw == NW && mp == MP && d == D) return launch_w4_small_cfg<OUT_KIND, NW, MP, D>(p, st)
+  CWAC_W4_SMALL(4, 8, 2);
+  CWAC_W4_SMALL(4, 8, 3);
+  CWAC_W4_SMALL(4, 8, 4);
+  CWAC_W4_SMALL(8, 8, 2);
+  CWAC_W4_SMALL(8, 8, 3);
+  CWAC_W4_SMALL(8, 8, 4);
+  CWAC_W4_SMALL(4, 16, 2);
+  CWAC_W4_SMALL(4, 16, 3);
+  CWAC_W4_SMALL(4, 16, 4);
+  CWAC_W4_SMALL(8, 16, 2);
+  CWAC_W4_SMALL(8, 16, 3);
+  CWAC_W4_SMALL(4, 32, 2);
+  CWAC_W4_SMALL(4, 32, 3);
+#undef CWAC_W4_SMALL
+  return CWAC_E_MODE;
 }
 
 
@@ -691,8 +780,9 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
   if (!x || !packed_w || !packed_sz || !out) return CWAC_E_NULL;
   if (out_kind != CWAC_OUT_FP16 && out_kind != CWAC_OUT_FP32) return CWAC_E_MODE;
   const int w4_tile = tuning ? tuning->w4_tile : 0, small_waves = tuning ? tuning->w4_small_waves : 0;
+  const int small_depth = tuning ? tuning->w4_small_depth : 0;
   if ((w4_tile != 0 && w4_tile != 256 && w4_tile != 128) ||
-      (small_waves != 0 && small_waves != 4 && small_waves != 8))
+      (small_waves != 0 && small_waves != 4 && small_waves != 8) || (small_depth != 0 && (small_depth < 2 || small_depth > 4)))
     return CWAC_E_MODE;
   if (m < 1 || n < 256 || n % 32 != 0 || k < kGroup || k > 32768 || k % kGroup != 0 || ldx < k || ldo < n)
     return CWAC_E_SHAPE;
@@ -728,8 +818,8 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
       q.out = p.out + r0 * ldo * esz;
       q.m = m - r0 < kSmallM ? m - r0 : kSmallM;
       const cwac_status s = out_kind == CWAC_OUT_FP16
-                                ? launch_w4_small<CWAC_OUT_FP16>(q, small_waves, as_stream(stream))
-                                : launch_w4_small<CWAC_OUT_FP32>(q, small_waves, as_stream(stream));
+                                ? launch_w4_small<CWAC_OUT_FP16>(q, small_waves, small_depth, as_stream(stream))
+                                : launch_w4_small<CWAC_OUT_FP32>(q, small_waves, small_depth, as_stream(stream));
       if (s != CWAC_OK) return s;
     }
     return CWAC_OK;

@@ -42,7 +42,7 @@ def _pack(codes, scales, zeros):
     return pw, psz
 
 
-def _forward(x16, pw, psz, n, mult, fbias, dtype, ldo=None, pipe=None):
+def _forward(x16, pw, psz, n, mult, fbias, dtype, ldo=None, pipe=None, waves=0, depth=0):
     m = x16.shape[0]
     if ldo is None:
         out = torch.empty(m, n, dtype=dtype, device=DEV)
@@ -50,7 +50,7 @@ def _forward(x16, pw, psz, n, mult, fbias, dtype, ldo=None, pipe=None):
         full = torch.full((m, ldo), 7.0, dtype=dtype, device=DEV)
         out = full[:, :n]
     P.qlinear_w4a16_cwac_forward(_dev(x16), pw, psz, n, _dev(mult), _dev(fbias), out,
-                                 tuning=tuning_of(w4_pipe=pipe))
+                                 tuning=tuning_of(w4_pipe=pipe, w4_small_waves=waves, w4_small_depth=depth))
     torch.cuda.synchronize()
     if ldo is not None:
         assert (full[:, n:] == 7.0).all(), "wrote outside the output columns"
@@ -202,6 +202,35 @@ def test_small_batch_exact_operands(w4, m, n, k):
             _forward(x16, pw, psz, n, mult, None, torch.float32, pipe=pipe).cpu().numpy(), o32m)
         np.testing.assert_array_equal(
             _forward(x16, pw, psz, n, None, fbias, torch.float32, pipe=pipe).cpu().numpy(), o32b)
+
+
+@pytest.mark.parametrize("waves,depth", [(4, 0), (8, 0), (4, 2), (8, 2), (4, 3), (8, 3), (4, 4), (8, 4)])
+@pytest.mark.parametrize("m,n,k", [(1, 256, 128), (7, 288, 640), (32, 256, 1152), (19, 320, 2560), (32, 256, 4224),
+                                   (3, 256, 9088), (8, 256, 2048), (9, 256, 1536), (16, 288, 3072), (13, 256, 4224)])
+def test_small_batch_every_wave_count(w4, m, n, k, waves, depth):
+    """The weight-streaming kernel with 4 and 8 wavefronts per workgroup and every ring depth, for each padded row
+    count (8, 16, 32; by default rings of 4, 3 and 3 groups per wavefront): wavefronts without a group (K = 128), with fewer groups than ring
+    slots, with exactly a ring, and with several rounds of the ring plus a ragged rest (33 and 71 groups).  Exact
+    operands: the oracle's bits."""
+    print(f"w4a16 small batch {m} x {n} x {k}, {waves} wavefronts, depth {depth}", flush=True)
+    x16, codes, scales, zeros = _exact_case(900 + m + n + k, m, n, k)
+    if k > 2048:
+        scales[:] = np.float16(0.5)
+    acc, _ = w4.product(x16, w4.dequant(codes, scales, zeros))
+    acc32 = acc.astype(np.float32)
+    assert np.array_equal(acc32.astype(np.float64), acc)
+    pw, psz = _pack(codes, scales, zeros)
+    rng = np.random.default_rng(16)
+    mult = (1 + 0.25 * rng.standard_normal(n)).astype(np.float32)
+    fbias = rng.standard_normal(n).astype(np.float32)
+    o32, o16 = w4.epilogue_f32(acc32, mult, fbias)
+    out = _forward(x16, pw, psz, n, None, None, torch.float32, waves=waves, depth=depth)
+    np.testing.assert_array_equal(out.cpu().numpy(), acc32)
+    outh = _forward(x16, pw, psz, n, mult, fbias, torch.float16, ldo=n + 24, waves=waves, depth=depth)
+    np.testing.assert_array_equal(outh.cpu().numpy().view(np.uint16), o16.view(np.uint16))
+    # bit-reproducible
+    again = _forward(x16, pw, psz, n, None, None, torch.float32, waves=waves, depth=depth)
+    assert torch.equal(out, again)
 
 
 def test_small_batch_padded_activation_pitch(w4):
