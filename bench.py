@@ -1018,7 +1018,7 @@ def power_trace(P, synth, torch, dev: str, cfg: int, seconds: float = 5.0):
             "phases": out}
 
 
-def tile_timeline(torch, synth, dev: str, cfgs):
+def tile_timeline(torch, synth, dev: str, cfgs, fp32_out: bool = False):
     """Where a tile's time goes inside the direct-to-LDS forward kernels: 100 MHz time stamps that every
     wavefront takes at five points of each tile (needs the development build of the library,
     `python -m paper_2505_20932_amd.build --timeline`, loaded here instead of the product library).
@@ -1052,8 +1052,13 @@ def tile_timeline(torch, synth, dev: str, cfgs):
                 tun = P.make_tuning(kernel=P.binding.CWAC_KERNEL_DIRECT_LDS, shape=shape)
 
                 def fwd():
-                    P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
-                                           L.sx_row, P.CWAC_OUT_INT8, L.out, tuning=tun)
+                    if fp32_out:    # the calibration forward of the step: Y_quant in fp32
+                        P.qlinear_cwac_forward(L.xq_cal, L.wq, None, L.deq_mult, L.deq_off,
+                                               L.deq_fb if L.bias is not None else None, L.sx_row_cal,
+                                               P.CWAC_OUT_FP32, L.yq, tuning=tun)
+                    else:
+                        P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
+                                               L.sx_row, P.CWAC_OUT_INT8, L.out, tuning=tun)
                 for _ in range(10):
                     fwd()
                 torch.cuda.synchronize()
@@ -1099,7 +1104,8 @@ def tile_timeline(torch, synth, dev: str, cfgs):
             out.append(ent)
         del layers
         torch.cuda.empty_cache()
-    return {"tile_timeline": "int8 forward, 256 x 256 tiles of eight wavefronts; per tile and wavefront: from its start "
+    return {"output": "fp32 (calibration forward)" if fp32_out else "int8 (fused CWAC forward)",
+            "tile_timeline": "forward, 256 x 256 tiles of eight wavefronts; per tile and wavefront: from its start "
                              "(persistent: from the barrier that ends the previous tile) to the first MFMA, the K loop, "
                              "the epilogue up to its last store instruction, and the wait for the stores",
             "layers": out}
@@ -1166,6 +1172,84 @@ def forward_shapes(P, synth, torch, dev: str, cfgs, reps: int = 20):
         torch.cuda.empty_cache()
     return {"forward_shapes": "int8 forward per layer shape and tile shape (cwac_tuning.shape), microseconds per launch, "
                               f"{reps} back-to-back launches", "layers": out}
+
+
+def small_batch_sweep(P, synth, torch, dev: str):
+    """The weight-only layer at decode-sized batches (its own JSON line): every distinct layer shape of
+    workload 5 at 1, 8, 16 and 32 tokens, the dispatcher's choice and every (wavefronts, ring depth) of the
+    weight-streaming kernel; enough copies of the packed weights cycle that each launch reads them from HBM
+    (more than 400 MB per shape); three passes over the copies replayed from a HIP graph."""
+    layers = setup_weight_only(P, synth, torch, 5, dev)
+    for L in layers:
+        del L.y_full, L.xcal, L.wh
+    torch.cuda.empty_cache()
+    out = []
+    seen = set()
+    for L in layers:
+        if (L.n, L.k) in seen:
+            continue
+        seen.add((L.n, L.k))
+        wbytes = L.n * L.k // 2 + L.n * (L.k // 128) * 4
+        copies = max(2, (400 << 20) // wbytes)
+        pws = [L.pw.clone() for _ in range(copies)]
+        pszs = [L.psz.clone() for _ in range(copies)]
+        ent = {"n": L.n, "k": L.k, "weight_bytes": wbytes, "copies": copies, "us": {}}
+        for sm in (1, 8, 16, 32):
+            o = torch.empty(sm, L.n, dtype=torch.float16, device=dev)
+            row = {}
+            for waves, depth in ((0, 0), (4, 2), (4, 3), (4, 4), (8, 2), (8, 3), (8, 4)):
+                tun = P.make_tuning(w4_small_waves=waves, w4_small_depth=depth) if waves else None
+
+                def one_pass():
+                    for pw, psz in zip(pws, pszs):
+                        P.qlinear_w4a16_cwac_forward(L.x[:sm], pw, psz, L.n, L.mult, L.fbias, o, tuning=tun)
+                one_pass()
+                torch.cuda.synchronize()
+                side = torch.cuda.Stream()
+                with torch.cuda.stream(side):
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=side):
+                        for _ in range(3):
+                            one_pass()
+                g.replay()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                row["auto" if not waves else f"{waves}w_d{depth}"] = round(e0.elapsed_time(e1) / (3 * copies) * 1e3, 2)
+                del g
+            row["auto_gbs"] = round(wbytes / row["auto"] / 1e3, 1)
+            ent["us"][f"m={sm}"] = row
+        out.append(ent)
+        del pws, pszs
+        torch.cuda.empty_cache()
+    # one wide matrix (a vocabulary-sized head), random codes: what the stream sustains once the
+    # fixed cost of a launch is small beside its bytes
+    n, k, sm = 131072, 4096, 8
+    pws = [torch.randint(0, 255, (n * k // 2,), dtype=torch.uint8, device=dev) for _ in range(2)]
+    sc = torch.full((k // 128, n), 0.01, dtype=torch.float16, device=dev)
+    psz = (sc.view(torch.int16).to(torch.int32) & 0xffff) | (8 << 16)
+    x = torch.randn(sm, k, dtype=torch.float16, device=dev)
+    o = torch.empty(sm, n, dtype=torch.float16, device=dev)
+    for pw in pws:
+        P.qlinear_w4a16_cwac_forward(x, pw, psz.view(-1), n, None, None, o)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        for pw in pws:
+            P.qlinear_w4a16_cwac_forward(x, pw, psz.view(-1), n, None, None, o)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) / 10 * 1e3
+    wbytes = n * k // 2 + n * (k // 128) * 4
+    out.append({"n": n, "k": k, "weight_bytes": wbytes, "copies": 2,
+                "us": {f"m={sm}": {"auto": round(us, 1), "auto_gbs": round(wbytes / us / 1e3, 1)}}})
+    return {"small_batch_sweep": "w4a16_small_m_kernel, microseconds per launch from a HIP graph, weights from HBM; "
+                                 "columns: the dispatcher's choice, then <wavefronts per workgroup>w_d<ring depth>",
+            "layers": out}
 
 
 def time_steps(P, torch, layers, steps: int, warmup: int):
@@ -1420,9 +1504,14 @@ def main():
     ap.add_argument("--tile-timeline", action="store_true",
                     help="instead of the benchmark: in-kernel time stamps of the int8 forward's tiles on workloads "
                          "2-5 (needs `python -m paper_2505_20932_amd.build --timeline`; its own JSON line)")
+    ap.add_argument("--timeline-fp32", action="store_true",
+                    help="with --tile-timeline: the fp32-output calibration forward instead of the int8 forward")
     ap.add_argument("--forward-shapes", action="store_true",
                     help="instead of the benchmark: the int8 forward of every distinct layer shape of workloads 2-5 "
                          "under each tile shape of the direct-to-LDS kernel (its own JSON line)")
+    ap.add_argument("--small-batch", action="store_true",
+                    help="instead of the benchmark: the weight-only layer at 1-32 tokens on workload 5's layer shapes, "
+                         "every wavefront count and ring depth of its weight-streaming kernel (its own JSON line)")
     ap.add_argument("--probe", action="store_true",
                     help="profiling aid: one plain 1 GiB device copy (a kernel of known traffic, to "
                          "calibrate rocprofv3 byte counters) followed by ONE step, then exit")
@@ -1440,7 +1529,7 @@ def main():
         from paper_2505_20932_amd import synth
         assert torch.cuda.is_available(), "bench.py needs the MI355X"
         torch.cuda.set_device(0)
-        print(json.dumps(tile_timeline(torch, synth, "cuda:0", (2, 3, 4, 5))))
+        print(json.dumps(tile_timeline(torch, synth, "cuda:0", (2, 3, 4, 5), args.timeline_fp32)))
         return
     import paper_2505_20932_amd as P
     from paper_2505_20932_amd import synth
@@ -1459,6 +1548,9 @@ def main():
         return
     if args.forward_shapes:
         print(json.dumps(forward_shapes(P, synth, torch, dev, (2, 3, 4, 5))))
+        return
+    if args.small_batch:
+        print(json.dumps(small_batch_sweep(P, synth, torch, dev)))
         return
     if args.power_trace:
         print(json.dumps(power_trace(P, synth, torch, dev, args.config)))

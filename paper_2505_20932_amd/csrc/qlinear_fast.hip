@@ -546,17 +546,6 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
   uint32_t tap_sel = 0x10001u;  // bit kh | bit 16 + kw
   const int8_t *pad = reinterpret_cast<const int8_t *>(kPadCodes.v) + (p.cv_pad4 & 255) * 16;
 
-#ifdef CWAC_V_BUFLOAD
-  // Buffer descriptors of the two panels of this tile (base = tile origin, byte-addressed, no
-  // stride, extent = the tile's own rows): a load is then descriptor + per-lane 32-bit offset +
-  // scalar K offset, with no vector address arithmetic, and the hardware range check covers it.
-  const __amdgpu_buffer_rsrc_t xdesc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<int8_t *>(xtile), 0, (int)(uint32_t)((uint64_t)(C::BM - 1) * (uint64_t)p.ldx + (uint64_t)p.k),
-      0x00020000);
-  const __amdgpu_buffer_rsrc_t wdesc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<int8_t *>(wtile), 0, (int)(uint32_t)((uint64_t)(C::BN - 1) * (uint64_t)p.ldw + (uint64_t)p.k),
-      0x00020000);
-#endif
   // chunk c of a stage's 2*LOADS loads (activation loads first, then weight loads)
   auto issue_chunk = [&](int buf, int k0, int c) {
     int8_t *sx = smem + buf * C::STAGE + wave_s * C::XROWS * BK;
@@ -583,13 +572,6 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
         const int8_t *src = inside ? xtile + (uint32_t)(xvo[i] + tap_off) : pad;
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(src), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
       }
-#ifdef CWAC_V_BUFLOAD
-      else if (!CONV && i < C::LOADS_X)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, (int)xvo[i], k0, 0, 0);
-      else if (!CONV)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(wdesc, CWAC_LDS_PTR(sw + (i - C::LOADS_X) * C::RPL * BK), 16,
-                                             (int)wvo[i - C::LOADS_X], k0, 0, 0);
-#endif
       else if (i < C::LOADS_X)
         __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(xk + xvo[i]), CWAC_LDS_PTR(sx + i * C::RPL * BK), 16, 0, 0);
       else
@@ -608,20 +590,10 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
   const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
   auto read_frags = [&](int buf, int kk, v4i(&fw)[TA], v4i(&fx)[TB]) {
     const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
-#ifdef CWAC_V_RDORDER
-    // in the order the MFMAs of the next k-step consume them (weight tile a-major): the first MFMA
-    // then waits for two reads, not for all of them
-    fw[0] = *reinterpret_cast<const v4i *>(base + w_off);
-#pragma unroll
-    for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
-#pragma unroll
-    for (int a = 1; a < TA; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
-#else
 #pragma unroll
     for (int a = 0; a < TA; ++a) fw[a] = *reinterpret_cast<const v4i *>(base + w_off + a * 32 * BK);
 #pragma unroll
     for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
-#endif
   };
 
   v16i acc[TA][TB];
