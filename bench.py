@@ -443,6 +443,8 @@ def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: 
                      "peak": FP16_MFMA_PEAK_TFLOPS / 1e3, "unit": "PFLOP/s",
                      "frac": round(tf / FP16_MFMA_PEAK_TFLOPS, 4),
                      "traffic": PMC_TRAFFIC_BYTES.get(wl.cfg, {}).get("forward_w4a16"),
+                     "traffic_source": "profiles/bench_config5_w4a16_pmc.md (constant from that profile, not measured "
+                                       "in this run)",
                      "kernel": "w4a16_kernel (fp16 out, fused CWAC epilogue)",
                      "launches_per_step": len(layers), "avg_launch_ms": round(t_fwd / len(layers), 4),
                      "flops_per_step": fwd_flops},
