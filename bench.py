@@ -650,7 +650,7 @@ def conv_section(P, synth, torch, dev: str, batch: int, steps: int, cpu_batch: i
                                f"batch {batch}, channels-last int8 images, per-tensor activations"},
         "roofline": {"bound": "mfma", "achieved": round(tops / 1e3, 4), "peak": INT8_MFMA_PEAK_TOPS / 1e3,
                      "unit": "POP/s", "frac": round(tops / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
-                     "kernel": "qlinear_fast_kernel / qlinear_kernel, convolution instantiations "
+                     "kernel": "qlinear_fast_kernel / qlinear_persist_kernel / qlinear_kernel as the dispatcher picks per layer "
                                "(int8 out, fused CWAC epilogue)",
                      "launches_per_step": nl, "avg_launch_ms": round(t_fwd / nl, 4),
                      "ops_per_step": fwd_ops},
@@ -829,7 +829,7 @@ def block_section(P, torch, dev: str, batch: int, steps: int, warmup: int, cpu_i
         # the dominant kernel of the block: the int8 forward (four launches, one with the GELU table)
         "roofline": {"bound": "mfma", "achieved": round(lin_ops / lin_us / 1e9, 4), "peak": INT8_MFMA_PEAK_TOPS / 1e3,
                      "unit": "POP/s", "frac": round(lin_ops / lin_us / 1e6 / INT8_MFMA_PEAK_TOPS, 4), "traffic": None,
-                     "kernel": "qlinear_fast_kernel (int8 out, fused CWAC epilogue; K = 768 / 3072)",
+                     "kernel": "qlinear_persist_kernel (int8 out, fused CWAC epilogue, fc1 with the GELU code table; K = 768 / 3072)",
                      "launches_per_step": 4, "avg_launch_ms": round(lin_us / 4e3, 4), "ops_per_step": lin_ops},
         "roofline_attention": {"bound": "mfma", "achieved": round(att["tflops"] / 1e3, 4), "peak": 2.5,
                                "unit": "PFLOP/s", "frac": att["frac"], "traffic": None,

@@ -576,8 +576,8 @@ enum {
   CWAC_SHAPE_128_PAIR = 4,    /* 128 tokens x 256 channels, two workgroups per compute unit */
   CWAC_SHAPE_128_128 = 5,     /* 128 x 128, four wavefronts of 64 x 64 */
   CWAC_SHAPE_256_PERSIST = 6  /* CWAC_SHAPE_256_8W's tile on persistent workgroups, one per compute unit, the
-                                 next tile's first loads in flight under a tile's epilogue (linear layers with
-                                 int8 / fp32 / int32 output; other calls take CWAC_SHAPE_256_8W) */
+                                 next tile's first loads in flight under a tile's epilogue (linear layers, every
+                                 epilogue but the fused statistics; convolutions take CWAC_SHAPE_256_8W) */
 };
 typedef struct cwac_tuning {
   int32_t kernel;         /* CWAC_KERNEL_*: int8 linear / convolution / table / fixed-point forwards */

@@ -755,7 +755,8 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
 #endif
 }
 
-// Persistent form of the 256 x 256 tile of eight wavefronts (linear layers; int8 / fp32 / int32 output):
+// Persistent form of the 256 x 256 tile of eight wavefronts (linear layers; int8 / fp32 / int32 output, the
+// integer-only epilogue and the code-table epilogue):
 // one workgroup per compute unit walks work items id = blockIdx.x + j * gridDim.x (the same XCD-aware
 // tile order: ids congruent mod 8 stay on one XCD).  What a fresh workgroup pays per tile - kernel
 // arguments, tile arithmetic, the round trip of the epilogue parameters and of the first panels,
@@ -827,6 +828,10 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   if (!p.offset && tid < 512) {
     reinterpret_cast<int32_t *>(param_block(tid >> 8))[tid & 255] = 0;
   }
+  // the code table (64 words) rides in the fp-bias slot of both blocks, which that epilogue leaves unused
+  if (OUT_KIND == kOutTable && tid < 128)
+    reinterpret_cast<int32_t *>(param_block(tid >> 6) + 2048)[tid & 63] =
+        reinterpret_cast<const int32_t *>(p.code_table)[tid & 63];
 
   // item origin and kind, panel descriptors, parameter loads into block pb, panel loads of stage 0
   auto open_item = [&](int id, int pb) {
@@ -848,6 +853,10 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     const void *src = nullptr;
     if (p_arr == 0) src = p.offset ? p.offset + bn0 : nullptr;
     if (p_arr == 1 && OUT_KIND != CWAC_OUT_INT32) src = p.mult + bn0;
+    if (OUT_KIND == kOutFixed) {  // integer multiplier and shift travel in the two float slots
+      if (p_arr == 1) src = p.m0 + bn0;
+      if (p_arr == 2) src = p.shift + bn0;
+    }
     if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32) {
       if (p_arr == 2) src = p.fbias ? p.fbias + bn0 : nullptr;
       // a half item has 128 rows: only the first of the two wavefronts of this array loads
@@ -1067,7 +1076,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       // that lane arithmetic is hoisted out of the item loop and lives (spilled) across the main loop
       int lane_e = lane;
       asm volatile("" : "+v"(lane_e));
-      constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8) ? 1 : 4;
+      constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed || OUT_KIND == kOutTable) ? 1 : 4;
       const int vs = p.vec_store && (((e_bn0 * ESZ) & 15) == 0);
       if (vs)
         fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0, e_bn0,
@@ -1109,9 +1118,9 @@ cwac_status launch_persist_one(const FwdParams &p, int workgroups, hipStream_t s
 }
 
 // The persistent kernel on a 256 x 256 tiling of the layer: one workgroup per compute unit (fewer
-// when there are fewer tiles).  out_kind: CWAC_OUT_INT8 | CWAC_OUT_FP32 | CWAC_OUT_INT32.
+// when there are fewer tiles).  out_kind: CWAC_OUT_INT8 | CWAC_OUT_FP32 | CWAC_OUT_INT32 | kOutFixed | kOutTable.
 cwac_status launch_persist(FwdParams p, int out_kind, bool int_only, int max_workgroups, hipStream_t st) {
-  const size_t esz = out_kind == CWAC_OUT_INT8 ? 1 : 4;
+  const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed || out_kind == kOutTable) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
   p.tiles_m = (int)ceil_div(p.m, 256);
   p.tiles_n = (int)ceil_div(p.n, 256);
@@ -1127,6 +1136,8 @@ cwac_status launch_persist(FwdParams p, int out_kind, bool int_only, int max_wor
     return int_only ? launch_persist_one<CWAC_OUT_INT8, true>(p, wgs, st)
                     : launch_persist_one<CWAC_OUT_INT8, false>(p, wgs, st);
   if (out_kind == CWAC_OUT_FP32) return launch_persist_one<CWAC_OUT_FP32, false>(p, wgs, st);
+  if (out_kind == kOutFixed) return launch_persist_one<kOutFixed, true>(p, wgs, st);
+  if (out_kind == kOutTable) return launch_persist_one<kOutTable, true>(p, wgs, st);
   return launch_persist_one<CWAC_OUT_INT32, false>(p, wgs, st);
 }
 
@@ -1175,11 +1186,12 @@ cwac_status launch_table_cfg(FwdParams p, hipStream_t st) {
 
 cwac_status launch_fast_table(FwdParams p, int shape, hipStream_t st) {
   p.vec_store = aligned(p.out, 16) && (p.ldo % 16) == 0;
-  // the same two tiles, by the same rule, as the plain int8 forward of a layer with n >= 256
-  bool half = (p.k % 128) != 0 || fast_prefers_half_tile(p.m, p.n, p.k, 1);
-  if ((p.k % 128) == 0 && shape == CWAC_SHAPE_256_8W) half = false;
-  if (shape == CWAC_SHAPE_128_PAIR) half = true;
-  if (half) return launch_table_cfg<128, 2, 64, 3>(p, st);
+  // the tiles of the plain int8 forward of a layer with n >= 256, by the same rule: the persistent
+  // 256 x 256 tile, the same tile with one workgroup per tile, or the 128-token pair
+  if (shape == CWAC_SHAPE_AUTO) shape = fast_linear_shape(p.m, p.n, p.k, 1);
+  if ((p.k % 128) != 0 || shape == CWAC_SHAPE_128_128) shape = CWAC_SHAPE_128_PAIR;
+  if (shape == CWAC_SHAPE_128_PAIR) return launch_table_cfg<128, 2, 64, 3>(p, st);
+  if (shape == CWAC_SHAPE_256_PERSIST) return launch_persist(p, kOutTable, true, 0, st);
   return launch_table_cfg<256, 4, 128, 2>(p, st);
 }
 
@@ -1233,11 +1245,8 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, const Tune &tu
   if (shape == CWAC_SHAPE_256_4W_K64) return launch_cfg<256, 2, 64, 4, 2>(p, out_kind, int_only, st);
   if (shape == CWAC_SHAPE_256_8W) return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
   if (shape == CWAC_SHAPE_256_4W_K128) return launch_cfg<256, 2, 128, 2, 2>(p, out_kind, int_only, st);
-  // CWAC_SHAPE_256_PERSIST: the eight-wavefront 256 x 256 tile on persistent workgroups, for the output
-  // kinds it is built for
-  if (out_kind == CWAC_OUT_INT8 || out_kind == CWAC_OUT_FP32 || out_kind == CWAC_OUT_INT32)
-    return launch_persist(p, out_kind, int_only, tune.persist_workgroups, st);
-  return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
+  // CWAC_SHAPE_256_PERSIST: the eight-wavefront 256 x 256 tile on persistent workgroups
+  return launch_persist(p, out_kind, int_only, tune.persist_workgroups, st);
 }
 
 int fast_linear_shape(int64_t m, int n, int k, int out_bytes) {
