@@ -1196,11 +1196,17 @@ def small_batch_sweep(P, synth, torch, dev: str):
         pws = [L.pw.clone() for _ in range(copies)]
         pszs = [L.psz.clone() for _ in range(copies)]
         ent = {"n": L.n, "k": L.k, "weight_bytes": wbytes, "copies": copies, "us": {}}
-        for sm in (1, 8, 16, 32):
+        for sm in (1, 8, 16, 32, 64, 128, 256, 512):
             o = torch.empty(sm, L.n, dtype=torch.float16, device=dev)
             row = {}
-            for waves, depth in ((0, 0), (4, 2), (4, 3), (4, 4), (8, 2), (8, 3), (8, 4)):
-                tun = P.make_tuning(w4_small_waves=waves, w4_small_depth=depth) if waves else None
+            # up to 32 rows: every (wavefronts, ring depth) of the weight-streaming kernel; above: the dispatcher's
+            # choice (passes of that kernel up to 128 rows, 128-token tiles while they fit one round) against the
+            # tiled kernel with 128- and 256-token tiles
+            choices = (((0, 0, 0), (4, 2, 0), (4, 3, 0), (4, 4, 0), (8, 2, 0), (8, 3, 0), (8, 4, 0)) if sm <= 32 else
+                       ((0, 0, 0), (0, 0, 128), (0, 0, 256)))
+            for waves, depth, tile in choices:
+                tun = (P.make_tuning(w4_small_waves=waves, w4_small_depth=depth, w4_tile=tile)
+                       if (waves or tile) else None)
 
                 def one_pass():
                     for pw, psz in zip(pws, pszs):
@@ -1220,7 +1226,8 @@ def small_batch_sweep(P, synth, torch, dev: str):
                 g.replay()
                 e1.record()
                 torch.cuda.synchronize()
-                row["auto" if not waves else f"{waves}w_d{depth}"] = round(e0.elapsed_time(e1) / (3 * copies) * 1e3, 2)
+                name = "auto" if not (waves or tile) else (f"tile{tile}" if tile else f"{waves}w_d{depth}")
+                row[name] = round(e0.elapsed_time(e1) / (3 * copies) * 1e3, 2)
                 del g
             row["auto_gbs"] = round(wbytes / row["auto"] / 1e3, 1)
             ent["us"][f"m={sm}"] = row
@@ -1250,7 +1257,8 @@ def small_batch_sweep(P, synth, torch, dev: str):
     out.append({"n": n, "k": k, "weight_bytes": wbytes, "copies": 2,
                 "us": {f"m={sm}": {"auto": round(us, 1), "auto_gbs": round(wbytes / us / 1e3, 1)}}})
     return {"small_batch_sweep": "w4a16_small_m_kernel, microseconds per launch from a HIP graph, weights from HBM; "
-                                 "columns: the dispatcher's choice, then <wavefronts per workgroup>w_d<ring depth>",
+                                 "columns: the dispatcher's choice, then <wavefronts per workgroup>w_d<ring depth> (up to 32 tokens) or "
+                                 "the tiled kernel with tile<tokens per tile> (above)",
             "layers": out}
 
 

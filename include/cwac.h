@@ -432,9 +432,11 @@ cwac_status cwac_fold_weight_only(const float *alpha, const float *beta, const f
  *   m >= 1, n >= 256, n % 32 == 0, 128 <= k <= 32768, k % 128 == 0
  *   mult, fbias  device fp32 [n] or NULL
  *   out        device [m, n], ldo; 16-byte aligned, ldo * sizeof(element) % 16 == 0
- * Batches of at most 128 rows (decoding steps) take a kernel that streams the packed
- * weights once per 32 rows, 32 output channels per workgroup; larger batches tiles of
- * 256 channels x 128 tokens while those fit the chip in one round, else x 256 tokens.
+ * Batches of at most 32 rows (decoding steps) take a kernel that streams the packed
+ * weights once, 32 output channels per workgroup; batches of up to 256 rows take one such
+ * pass per 32 rows while that is estimated to beat a tile's K loop (it does up to 96-256
+ * rows, the more the smaller n and the longer k); larger batches tiles of 256 channels x 128
+ * tokens while those fit the chip in one round, else x 256 tokens.
  * All compute the sum above; they differ in the order of the fp32 accumulation only. */
 cwac_status qlinear_w4a16_cwac_forward(const uint16_t *x, int64_t ldx, const void *packed_w,
                                        const uint32_t *packed_sz, int64_t m, int32_t n, int32_t k,
@@ -586,7 +588,7 @@ typedef struct cwac_tuning {
   int32_t stats_waves;    /* qlinear_cwac_calibrate_fused_ex: 0 (= 8) | 8 | 4 wavefronts per tile */
   int32_t w4_tile;        /* qlinear_w4a16_cwac_forward_ex: 0 | 256 | 128: the tiled kernel with that
                              many tokens per tile at every batch size */
-  int32_t w4_small_waves; /* ... its weight-streaming kernel (m <= 128): 0 | 4 | 8 wavefronts per workgroup */
+  int32_t w4_small_waves; /* ... its weight-streaming kernel (small batches): 0 | 4 | 8 wavefronts per workgroup */
   int32_t persist_workgroups; /* CWAC_SHAPE_256_PERSIST: 0 = one workgroup per compute unit; n > 0 = at most n
                                  (each then walks more tiles; leaves compute units to concurrent work) */
   int32_t w4_small_depth; /* ... and its ring depth: 0 | 2 | 3 | 4 groups of 128 input channels in flight per

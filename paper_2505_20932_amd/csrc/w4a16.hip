@@ -528,7 +528,16 @@ cwac_status launch_w4(const W4Params &p, hipStream_t st) {
 // ------------------------------------------------------------------------------------------
 constexpr int kSmallM = 32;
 constexpr int kHalfTileUpTo = 256;  // 128-token tiles in a launch up to which they are taken (one per compute unit)
-constexpr int kSmallPasses = 4;  // batches of up to 128 rows take this kernel, 32 rows per launch
+constexpr int kSmallPasses = 8;  // at most this many launches of 32 rows each
+// Whether ceil(m / 32) passes of the weight-streaming kernel beat one launch of the tiled kernel with
+// 128-token tiles.  Fitted to measurements on 4096 .. 12288 channels x 4096 .. 11008 input channels
+// (microseconds): a pass costs 5.5 + packed bytes / 2.6 MB, a single round of 128-token tiles 3 + 0.0127 k.
+inline bool small_passes_pay(int64_t m, int n, int k) {
+  if (m > kSmallPasses * kSmallM) return false;
+  const double passes = (double)((m + kSmallM - 1) / kSmallM);
+  const double pass_us = 5.5 + (double)n * (double)k * 0.5 / 2.6e6;
+  return m <= kSmallM || passes * pass_us < 3.0 + 0.0127 * (double)k;
+}
 
 template <int NW, int MP, int D_>
 struct StreamCfg {
@@ -808,10 +817,10 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
   p.tiles_n = (int)ceil_div(n, 256);
   // The caller's override (results agree to the rounding of the fp32 sums): w4_tile = 256 keeps the
   // 256-token tiles at every batch size, 128 the 128-token tiles.
-  if (m <= kSmallPasses * kSmallM && w4_tile == 0) {
-    // up to four passes of the weight-streaming kernel over blocks of 32 rows: the packed weights
-    // of a layer stay in the last-level cache between passes, and a 256-token tile would leave
-    // most of the chip idle at these sizes (one row of tiles, each as long as its K loop)
+  if (w4_tile == 0 && small_passes_pay(m, n, k)) {
+    // passes of the weight-streaming kernel over blocks of 32 rows: the packed weights of a layer
+    // stay in the last-level cache between passes, and a row of 128- or 256-token tiles would leave
+    // most of the chip idle at these sizes (each tile as long as its K loop)
     for (int64_t r0 = 0; r0 < m; r0 += kSmallM) {
       W4Params q = p;
       q.x = p.x + r0 * p.ldx_bytes;

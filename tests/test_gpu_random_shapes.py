@@ -127,7 +127,10 @@ def _w4_shapes():
               for _ in range(10)]
     shapes += [(int(rng.integers(1, 33)), 32 * int(rng.integers(8, 21)), 128 * int(rng.integers(1, 12)))
                for _ in range(6)]            # decode-sized batches: the weight-streaming kernel
-    return shapes + [(32, 256, 128), (33, 256, 128), (1, 288, 1408)]
+    # several passes of the weight-streaming kernel (7 and 5 passes, a last pass of 8 rows / 1 row), and shapes just
+    # past the point where its estimated cost exceeds a tile's K loop
+    return shapes + [(32, 256, 128), (33, 256, 128), (1, 288, 1408), (200, 256, 4096), (129, 288, 3072),
+                     (130, 256, 1536), (256, 256, 2560)]
 
 
 @pytest.mark.parametrize("m,n,k", _w4_shapes())
