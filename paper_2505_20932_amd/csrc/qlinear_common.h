@@ -245,7 +245,7 @@ inline bool fast_pitch_ok(int64_t ldx, int64_t ldw) { return ldx <= kFastMaxPitc
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, const Tune &tune, hipStream_t st);
 // The integer-offset int8 forward with p.code_table applied to every output code (kOutTable); shapes as
 // launch_fast with n >= 256.
-cwac_status launch_fast_table(FwdParams p, int shape, hipStream_t st);
+cwac_status launch_fast_table(FwdParams p, int shape, int max_workgroups, hipStream_t st);
 // True where that kernel would take its 128-token tile shape (two workgroups per compute unit).
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);
 // True where it would take 128 x 128 tiles (layers with few tiles and a long K loop).

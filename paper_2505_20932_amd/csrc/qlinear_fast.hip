@@ -1184,14 +1184,14 @@ cwac_status launch_table_cfg(FwdParams p, hipStream_t st) {
 
 }  // namespace
 
-cwac_status launch_fast_table(FwdParams p, int shape, hipStream_t st) {
+cwac_status launch_fast_table(FwdParams p, int shape, int max_workgroups, hipStream_t st) {
   p.vec_store = aligned(p.out, 16) && (p.ldo % 16) == 0;
   // the tiles of the plain int8 forward of a layer with n >= 256, by the same rule: the persistent
   // 256 x 256 tile, the same tile with one workgroup per tile, or the 128-token pair
   if (shape == CWAC_SHAPE_AUTO) shape = fast_linear_shape(p.m, p.n, p.k, 1);
   if ((p.k % 128) != 0 || shape == CWAC_SHAPE_128_128) shape = CWAC_SHAPE_128_PAIR;
   if (shape == CWAC_SHAPE_128_PAIR) return launch_table_cfg<128, 2, 64, 3>(p, st);
-  if (shape == CWAC_SHAPE_256_PERSIST) return launch_persist(p, kOutTable, true, 0, st);
+  if (shape == CWAC_SHAPE_256_PERSIST) return launch_persist(p, kOutTable, true, max_workgroups, st);
   return launch_table_cfg<256, 4, 128, 2>(p, st);
 }
 

@@ -461,6 +461,7 @@ def test_block_argument_errors():
     (16384, 1024, 1024, False),   # fused, 256-token tile
     (20001, 768, 768, False),     # fused, ragged last row tile
     (9000, 2048, 192, False),     # fused, K a multiple of 64 only
+    (25216, 3072, 768, False),    # fused, persistent tile, 4.6 rounds of tiles
     (300, 256, 128, False),       # too small: forward, then a lookup pass in place
     (1000, 48, 64, False),        # narrow: two passes
     (256, 256, 64, True), (1000, 512, 192, True), (777, 1024, 128, True), (513, 272, 256, True),
@@ -486,6 +487,16 @@ def test_forward_with_code_table(m, n, k, force):
     assert np.unique(codes).size > 100                      # the codes spread over the range
     np.testing.assert_array_equal(full[:, :n].cpu().numpy(), table[codes.astype(int) + 128])
     assert (full[:, n:] == 33).all()
+    if m >= 256 and n >= 256 and k % 128 == 0:
+        # persistent workgroups that walk several tiles each (the table is staged once per workgroup)
+        for wgs in (3, 7):
+            again = torch.full((m, n + 16), 33, dtype=torch.int8, device=DEV)
+            P.qlinear_cwac_forward_table(x, w, qp, mult, offset, _dev(table), again[:, :n],
+                                         tuning=P.make_tuning(kernel=P.binding.CWAC_KERNEL_DIRECT_LDS,
+                                                              shape=P.binding.CWAC_SHAPE_256_PERSIST,
+                                                              persist_workgroups=wgs))
+            torch.cuda.synchronize()
+            assert torch.equal(again, full), wgs
 
 
 def test_forward_with_code_table_argument_errors():

@@ -71,7 +71,7 @@ def test_fold_fixed_point_bit_exact(orc):
                                 P.make_qparams(P.CWAC_EPI_FP_BIAS, True, 1.0, 0, 1.0, 0), m0, sh, off)
 
 
-def _forward(xq, wq, qp, m0, sh, off, tile=None, ldo=None):
+def _forward(xq, wq, qp, m0, sh, off, tile=None, ldo=None, wgs=0):
     m, n = xq.shape[0], wq.shape[0]
     if ldo is None:
         out = torch.empty(m, n, dtype=torch.int8, device=DEV)
@@ -80,7 +80,8 @@ def _forward(xq, wq, qp, m0, sh, off, tile=None, ldo=None):
         out = torch.full((m, ldo), 77, dtype=torch.int8, device=DEV)
         view = out[:, :n]
     P.qlinear_cwac_forward_fixed_point(dev(xq), dev(wq), qp, dev(m0), dev(sh), dev(off), view,
-                                       tuning=tuning_of(tile))
+                                       tuning=tuning_of(tile, pipe="persist" if wgs else None,
+                                                        persist_workgroups=wgs))
     return host(out)
 
 
@@ -120,6 +121,11 @@ def test_forward_fixed_point_bit_exact(orc, m, n, k, tile):
             np.testing.assert_array_equal(got[:, :n], want)
             if ldo:
                 assert np.all(got[:, n:] == 77)
+        if tile == "fast" and k % 128 == 0:
+            # persistent workgroups that walk several tiles each (the multiplier and shift of the next tile are
+            # fetched under a tile's epilogue), with and without a split last round
+            for wgs in (1, 2, 3):
+                np.testing.assert_array_equal(_forward(xq, wq, qp, m0, sh, off, tile=tile, wgs=wgs), want)
     assert 0.05 < np.mean(np.abs(want.astype(np.int32)) < 7)
 
 
