@@ -21,8 +21,9 @@
 //   * Epilogue in registers: acc * mult[n] + fbias[n] (two fp32 operations), conversion to
 //     binary16, transposition through a wave-private LDS slab, whole 128-byte line stores.
 // The same kernel with 128-token tiles (two token blocks per wavefront) serves batches whose
-// 128-token tiles fit the chip in one round; batches of up to 128 tokens take the
-// weight-streaming kernel further down.
+// 128-token tiles fit the chip in one round; small batches (a decoding step, and up to 256
+// tokens while passes of 32 rows are estimated to be cheaper) take the weight-streaming kernel
+// further down.
 #include <hip/hip_runtime.h>
 
 
