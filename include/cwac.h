@@ -652,6 +652,21 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
 cwac_status cwac_mfma_probe(const int32_t *operands, int32_t iters, int32_t workgroups,
                             int32_t *sink, void *stream);
 
+/* Diagnostic as well: the K loop of the forward's 256 x 256 tile (512 threads, 128 KiB of
+ * LDS, one workgroup per compute unit; per stage 256 MFMAs of 32x32x32 per workgroup =
+ * 2 * 32768 * 256 int8 operations) with its ingredients added one at a time -
+ *   mode 0  the MFMAs alone, fragments in registers
+ *   mode 1  + the six 16-byte LDS fragment reads per wavefront and k-step
+ *   mode 2  + the wait and barrier that end a stage
+ *   mode 3  + the panel stream: eight direct-to-LDS loads of 1 KiB per wavefront and stage
+ *   mode 4  the same stream issued by wavefronts 0-3 only (sixteen loads each, one loading wavefront per SIMD)
+ * - timed by the caller: what each ingredient costs of the matrix cores' rate.
+ *   operands  device, 16 KiB as for cwac_mfma_probe (they also fill the LDS panels)
+ *   panels    device, 64 KiB, 16-byte aligned: the source of mode 3's loads (read by every workgroup)
+ *   1 <= stages <= 2^24, 1 <= workgroups <= 2^20; mode outside 0..4: CWAC_E_MODE */
+cwac_status cwac_kloop_probe(const int32_t *operands, const int8_t *panels, int32_t mode, int32_t stages,
+                             int32_t workgroups, int32_t *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

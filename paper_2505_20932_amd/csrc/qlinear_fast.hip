@@ -777,8 +777,10 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
 // split into two work items of 128 tokens x 256 channels (the same eight wavefronts, each 32 tokens
 // x 128 channels: one activation fragment per k-step instead of two), so the last round takes about
 // half a tile.  Items [0, F) are the full tiles, [F, F + 2R) the halves (F = T - R).
-template <int OUT_KIND, bool INT_ONLY>
+template <int OUT_KIND, bool INT_ONLY, int LOADERS>
 __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams p) {
+  static_assert(LOADERS == 8 || LOADERS == 4, "wavefronts that issue the panel loads");
+  constexpr int SHARES = 8 / LOADERS;  // 32-row shares of a panel per loading wavefront
   using C = FastCfg<256, 4, 128, 2, 2, 256>;
   constexpr int BK = 128, TA = 4, WM = 4, NSTAGE = 2;
   constexpr int kSlabBase = C::STAGE;                         // slabs: behind stage 0
@@ -803,7 +805,6 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   const uint32_t xv1 = (uint32_t)lr * (uint32_t)p.ldx + (uint32_t)((pc ^ sw0 ^ 4) << 4);
   const uint32_t wv0 = (uint32_t)lr * (uint32_t)p.ldw + (uint32_t)((pc ^ sw0) << 4);
   const uint32_t wv1 = (uint32_t)lr * (uint32_t)p.ldw + (uint32_t)((pc ^ sw0 ^ 4) << 4);
-  const uint32_t wrow0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldw;
   const uint32_t xstep = 8u * (uint32_t)p.ldx, wstep = 8u * (uint32_t)p.ldw;
 
   const int total = p.tiles_m * p.tiles_n;
@@ -870,31 +871,49 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
                                          CWAC_LDS_PTR(dst + j * 256), 4, 0, 0);
     }
   };
-  // activation loads of one stage: a wavefront's share is 32 rows (four loads) of a full item's 256,
-  // 16 rows (two loads) of a half item's 128; weight loads: always 32 rows of 256
+  // Panel loads of one stage.  A share is 32 rows (four loads) of a 256-row panel, 16 rows (two loads) of a
+  // half item's 128 activation rows.  LOADERS = 8: every wavefront loads its own share.  LOADERS = 4: only
+  // wavefronts 0-3 - one per SIMD - issue loads, each for shares w and w + 4: a direct-to-LDS load holds up
+  // the issuing wavefront's MFMAs for some tens of cycles, and with one loading wavefront per SIMD the other
+  // one keeps the matrix pipe fed meanwhile (with all eight loading, both wavefronts of a SIMD stall at about
+  // the same time; cwac_kloop_probe's pattern behaves alike).  That pays in long K loops (measured: -2 to -6 %
+  // time at K = 4096 .. 11008); in short ones the loading wavefronts' doubled share at the start of every tile
+  // costs more (+1 to +5 % at K = 512 .. 3072), so the launcher picks by K.
+  const bool loader = wave_s < LOADERS;
   auto issue_x = [&](int buf, int k0, bool hf) {
-    if (!hf) {
-      int8_t *dst = smem + buf * C::STAGE + wave_s * (32 * BK);
-      const uint32_t row0 = (uint32_t)(wave_s * 32) * (uint32_t)p.ldx + (uint32_t)k0;
+    if (!loader) return;
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? xv1 : xv0),
-                                                 (int)(row0 + (uint32_t)i * xstep), 0, 0);
-    } else {
-      int8_t *dst = smem + buf * C::STAGE + wave_s * (16 * BK);
-      const uint32_t row0 = (uint32_t)(wave_s * 16) * (uint32_t)p.ldx + (uint32_t)k0;
+    for (int h = 0; h < SHARES; ++h) {
+      const int share = wave_s + LOADERS * h;
+      if (!hf) {
+        int8_t *dst = smem + buf * C::STAGE + share * (32 * BK);
+        const uint32_t row0 = (uint32_t)(share * 32) * (uint32_t)p.ldx + (uint32_t)k0;
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? xv1 : xv0),
-                                                 (int)(row0 + (uint32_t)i * xstep), 0, 0);
+        for (int i = 0; i < 4; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16,
+                                                   (int)((i & 1) ? xv1 : xv0), (int)(row0 + (uint32_t)i * xstep), 0, 0);
+      } else {
+        int8_t *dst = smem + buf * C::STAGE + share * (16 * BK);
+        const uint32_t row0 = (uint32_t)(share * 16) * (uint32_t)p.ldx + (uint32_t)k0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16,
+                                                   (int)((i & 1) ? xv1 : xv0), (int)(row0 + (uint32_t)i * xstep), 0, 0);
+      }
     }
   };
   auto issue_w = [&](int buf, int k0) {
-    int8_t *dst = smem + buf * C::STAGE + C::X_BYTES + wave_s * (32 * BK);
+    if (!loader) return;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(wdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? wv1 : wv0),
-                                               (int)(wrow0 + (uint32_t)i * wstep + (uint32_t)k0), 0, 0);
+    for (int h = 0; h < SHARES; ++h) {
+      const int share = wave_s + LOADERS * h;
+      int8_t *dst = smem + buf * C::STAGE + C::X_BYTES + share * (32 * BK);
+      const uint32_t row0 = (uint32_t)(share * 32) * (uint32_t)p.ldw + (uint32_t)k0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(wdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16, (int)((i & 1) ? wv1 : wv0),
+                                                 (int)(row0 + (uint32_t)i * wstep), 0, 0);
+    }
   };
   const int swz_l = C::swz(l32);
   const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
@@ -997,7 +1016,12 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     if (stages > 1) {
       issue_x(1, BK, HF);
       issue_w(1, BK);
-      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(LPS, 0));  // all but stage 1: stage 0 and the parameters have landed
+      // all but stage 1: stage 0 and the parameters have landed (a loading wavefront has its shares of
+      // stage 1 in flight, the others nothing)
+      if (loader)
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(SHARES * LPS, 0));
+      else
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
     } else {
       __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
     }
@@ -1106,15 +1130,23 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   }
 }
 
-template <int OUT_KIND, bool INT_ONLY>
-cwac_status launch_persist_one(const FwdParams &p, int workgroups, hipStream_t st) {
+template <int OUT_KIND, bool INT_ONLY, int LOADERS>
+cwac_status launch_persist_loaders(const FwdParams &p, int workgroups, hipStream_t st) {
   constexpr int LDS = 160 * 1024;
   static const hipError_t attr =
-      hipFuncSetAttribute(reinterpret_cast<const void *>(&qlinear_persist_kernel<OUT_KIND, INT_ONLY>),
+      hipFuncSetAttribute(reinterpret_cast<const void *>(&qlinear_persist_kernel<OUT_KIND, INT_ONLY, LOADERS>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
-  qlinear_persist_kernel<OUT_KIND, INT_ONLY><<<dim3((unsigned)workgroups), 512, LDS, st>>>(p);
+  qlinear_persist_kernel<OUT_KIND, INT_ONLY, LOADERS><<<dim3((unsigned)workgroups), 512, LDS, st>>>(p);
   return launch_status();
+}
+
+constexpr int kLoaderWavesFromK = 4096;  // K from which four wavefronts issue all panel loads (see the kernel)
+
+template <int OUT_KIND, bool INT_ONLY>
+cwac_status launch_persist_one(const FwdParams &p, int workgroups, hipStream_t st) {
+  return p.k >= kLoaderWavesFromK ? launch_persist_loaders<OUT_KIND, INT_ONLY, 4>(p, workgroups, st)
+                                  : launch_persist_loaders<OUT_KIND, INT_ONLY, 8>(p, workgroups, st);
 }
 
 // The persistent kernel on a 256 x 256 tiling of the layer: one workgroup per compute unit (fewer

@@ -399,12 +399,13 @@ def test_stats_empty_state_and_single_row(orc):
 
 @pytest.mark.parametrize("wgs", [1, 3, 5, 7, 11, 0])
 @pytest.mark.parametrize("m,n,k", [(1300, 1030, 512), (600, 780, 128), (777, 520, 256), (520, 1290, 384),
-                                   (1030, 600, 1152)])
+                                   (1030, 600, 1152), (520, 780, 4096), (777, 520, 4224)])
 def test_forward_persistent_tiles(orc, m, n, k, wgs):
     """The persistent form of the 256 x 256 tile with fewer workgroups than tiles, so that every
     workgroup walks several tiles (the next tile's first loads in flight under a tile's epilogue):
     one to nine K stages (odd and even: the last stage ends in either ring buffer), ragged edge
-    tiles, every output kind, padded output rows."""
+    tiles, every output kind, padded output rows; from K = 4096 the form in which four of the eight
+    wavefronts issue all panel loads (32 and 33 stages)."""
     print(f"persistent tiles {m} x {n} x {k}, {wgs or 'one per CU'} workgroups", flush=True)
     g = synth.normal(1700 + m, 0, m * k).numpy().reshape(m, k)
     xq = np.clip(np.rint(g * 60), -128, 127).astype(np.int8)
