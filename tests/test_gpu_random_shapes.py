@@ -49,8 +49,10 @@ def test_linear_random_shape(orc, m, n, k):
     qp = P.make_qparams(z_r=zr)
     qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, 1.0, 0, 1.0, zr)
     ldo = n + int(rng.integers(0, 3)) * 4
-    for force_fast in (False, True):
-        tun = _knobs(force_fast)
+    # the automatic choice, the direct-to-LDS kernel forced, and its persistent tile on one to three
+    # workgroups (every workgroup then walks several tiles; shapes it does not admit fall back)
+    for tun in (None, tuning_of("fast"),
+                tuning_of("fast", pipe="persist", persist_workgroups=int(rng.integers(1, 4)))):
         if True:
             def run(out_kind, dt, *args):
                 full = torch.full((m, ldo), 55, dtype=dt, device=DEV)
@@ -104,8 +106,10 @@ def test_conv_random_shape(orc, shape):
     off = rng.integers(-5000, 5000, n).astype(np.int32)
     fb = rng.standard_normal(n).astype(np.float32)
     qp = P.make_qparams(z_x=zx, z_r=zr)
-    for force_fast in (False, True):
-        tun = _knobs(force_fast)
+    # the automatic choice, the direct-to-LDS kernel forced, and its persistent tile on one to three
+    # workgroups (every workgroup then walks several tiles; shapes it does not admit fall back)
+    for tun in (None, tuning_of("fast"),
+                tuning_of("fast", pipe="persist", persist_workgroups=int(rng.integers(1, 4)))):
         if True:
             def run(out_kind, dt, *args):
                 out = torch.empty(m, n, dtype=dt, device=DEV)
