@@ -1148,9 +1148,12 @@ def forward_shapes(P, synth, torch, dev: str, cfgs, reps: int = 20):
     on each distinct layer shape of the workloads (int8 output, the layer's own folded epilogue): `reps`
     back-to-back launches after 5 warm-up launches, HIP events.  `auto` is the dispatcher's own choice."""
     B = P.binding
-    shapes = [("auto", None), ("256_8W", B.CWAC_SHAPE_256_8W), ("256_4W_K128", B.CWAC_SHAPE_256_4W_K128),
-              ("256_4W_K64", B.CWAC_SHAPE_256_4W_K64), ("128_PAIR", B.CWAC_SHAPE_128_PAIR),
-              ("128_128", B.CWAC_SHAPE_128_128), ("256_PERSIST", B.CWAC_SHAPE_256_PERSIST)]
+    shapes = [("auto", None, 0), ("256_8W", B.CWAC_SHAPE_256_8W, 0), ("256_4W_K128", B.CWAC_SHAPE_256_4W_K128, 0),
+              ("256_4W_K64", B.CWAC_SHAPE_256_4W_K64, 0), ("128_PAIR", B.CWAC_SHAPE_128_PAIR, 0),
+              ("128_128", B.CWAC_SHAPE_128_128, 0), ("256_PERSIST", B.CWAC_SHAPE_256_PERSIST, 0),
+              # the persistent tile with the panel loads issued by four / by all eight of its wavefronts
+              ("256_PERSIST, 4 loading wavefronts", B.CWAC_SHAPE_256_PERSIST, 4),
+              ("256_PERSIST, 8 loading wavefronts", B.CWAC_SHAPE_256_PERSIST, 8)]
     out = []
     for cfg in cfgs:
         wl, layers = setup_layers(P, synth, torch, cfg, dev, synth.WORKLOADS[cfg].m)
@@ -1162,8 +1165,9 @@ def forward_shapes(P, synth, torch, dev: str, cfgs, reps: int = 20):
                 continue
             seen.add((L.n, L.k))
             ent = {"workload": cfg, "layer": L.name, "m": L.m, "n": L.n, "k": L.k, "us": {}}
-            for name, shape in shapes:
-                tun = None if shape is None else P.make_tuning(kernel=B.CWAC_KERNEL_DIRECT_LDS, shape=shape)
+            for name, shape, loaders in shapes:
+                tun = None if shape is None else P.make_tuning(kernel=B.CWAC_KERNEL_DIRECT_LDS, shape=shape,
+                                                               persist_loaders=loaders)
 
                 def fwd():
                     P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
@@ -1182,6 +1186,24 @@ def forward_shapes(P, synth, torch, dev: str, cfgs, reps: int = 20):
                 e1.record()
                 torch.cuda.synchronize()
                 ent["us"][name] = round(e0.elapsed_time(e1) / reps * 1e3, 1)
+            # four against eight loading wavefronts once more, alternated (five rounds of `reps` launches each,
+            # the median per side), so that clock and power drift over the sweep falls on both alike
+            sides = {4: [], 8: []}
+            for _ in range(5):
+                for loaders in (4, 8):
+                    tun = P.make_tuning(kernel=B.CWAC_KERNEL_DIRECT_LDS, shape=B.CWAC_SHAPE_256_PERSIST,
+                                        persist_loaders=loaders)
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(reps):
+                        P.qlinear_cwac_forward(L.xq, L.wq, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
+                                               L.sx_row, P.CWAC_OUT_INT8, L.out, tuning=tun)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    sides[loaders].append(e0.elapsed_time(e1) / reps * 1e3)
+            med = {k: sorted(v)[2] for k, v in sides.items()}
+            ent["loading_wavefronts_alternated_us"] = {"4": round(med[4], 1), "8": round(med[8], 1),
+                                                       "4_over_8": round(med[4] / med[8], 4)}
             # the vendor library's int8 GEMM on the same operands: the raw int32 product, no epilogue
             try:
                 wt = L.wq.t()

@@ -593,7 +593,8 @@ typedef struct cwac_tuning {
                                  (each then walks more tiles; leaves compute units to concurrent work) */
   int32_t w4_small_depth; /* ... and its ring depth: 0 | 2 | 3 | 4 groups of 128 input channels in flight per
                              wavefront (a depth whose rings do not fit the LDS is lowered to one that does) */
-  int32_t reserved;       /* zero */
+  int32_t persist_loaders; /* CWAC_SHAPE_256_PERSIST: how many of the eight wavefronts issue the panel loads:
+                              0 (= 4 from k = 4096, else 8) | 4 | 8 */
 } cwac_tuning;
 
 /* Which kernel qlinear_cwac_forward(_ex) would run for these sizes and this tuning (host

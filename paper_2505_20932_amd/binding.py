@@ -53,7 +53,7 @@ class cwac_qparams(C.Structure):
 class cwac_tuning(C.Structure):
     _fields_ = [("kernel", C.c_int32), ("shape", C.c_int32), ("stats_waves", C.c_int32),
                 ("w4_tile", C.c_int32), ("w4_small_waves", C.c_int32), ("persist_workgroups", C.c_int32),
-                ("w4_small_depth", C.c_int32), ("reserved", C.c_int32)]
+                ("w4_small_depth", C.c_int32), ("persist_loaders", C.c_int32)]
 
 
 class vit_block_layer(C.Structure):
@@ -173,10 +173,10 @@ def _rowmajor(t: torch.Tensor) -> int:
 
 
 def make_tuning(kernel=0, shape=0, stats_waves=0, w4_tile=0, w4_small_waves=0,
-                persist_workgroups=0, w4_small_depth=0) -> cwac_tuning:
+                persist_workgroups=0, w4_small_depth=0, persist_loaders=0) -> cwac_tuning:
     """Kernel choice override for the ``tuning=`` argument of the forward calls (same results)."""
     return cwac_tuning(int(kernel), int(shape), int(stats_waves), int(w4_tile), int(w4_small_waves),
-                       int(persist_workgroups), int(w4_small_depth))
+                       int(persist_workgroups), int(w4_small_depth), int(persist_loaders))
 
 
 def _tun(tuning: Optional[cwac_tuning]):

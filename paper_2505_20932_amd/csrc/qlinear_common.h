@@ -216,7 +216,7 @@ __device__ __forceinline__ void epilogue_tiles(const FwdParams &p, v16i (&acc)[T
 
 // Kernel choice override of the _ex entry points (cwac.h: cwac_tuning), validated.
 struct Tune {
-  int kernel = CWAC_KERNEL_AUTO, shape = CWAC_SHAPE_AUTO, stats_waves = 0, persist_workgroups = 0;
+  int kernel = CWAC_KERNEL_AUTO, shape = CWAC_SHAPE_AUTO, stats_waves = 0, persist_workgroups = 0, persist_loaders = 0;
 };
 // False where a field holds a value outside its list (the entry point returns CWAC_E_MODE).
 inline bool tune_from(const cwac_tuning *t, Tune &o) {
@@ -232,6 +232,8 @@ inline bool tune_from(const cwac_tuning *t, Tune &o) {
   o.stats_waves = t->stats_waves;
   if (t->persist_workgroups < 0) return false;
   o.persist_workgroups = t->persist_workgroups;
+  if (t->persist_loaders != 0 && t->persist_loaders != 4 && t->persist_loaders != 8) return false;
+  o.persist_loaders = t->persist_loaders;
   return true;
 }
 
@@ -245,7 +247,7 @@ inline bool fast_pitch_ok(int64_t ldx, int64_t ldw) { return ldx <= kFastMaxPitc
 cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, const Tune &tune, hipStream_t st);
 // The integer-offset int8 forward with p.code_table applied to every output code (kOutTable); shapes as
 // launch_fast with n >= 256.
-cwac_status launch_fast_table(FwdParams p, int shape, int max_workgroups, hipStream_t st);
+cwac_status launch_fast_table(FwdParams p, int shape, int max_workgroups, int loaders, hipStream_t st);
 // True where that kernel would take its 128-token tile shape (two workgroups per compute unit).
 bool fast_prefers_half_tile(int64_t m, int n, int k, int out_bytes);
 // True where it would take 128 x 128 tiles (layers with few tiles and a long K loop).

@@ -876,9 +876,10 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   // wavefronts 0-3 - one per SIMD - issue loads, each for shares w and w + 4: a direct-to-LDS load holds up
   // the issuing wavefront's MFMAs for some tens of cycles, and with one loading wavefront per SIMD the other
   // one keeps the matrix pipe fed meanwhile (with all eight loading, both wavefronts of a SIMD stall at about
-  // the same time; cwac_kloop_probe's pattern behaves alike).  That pays in long K loops (measured: -2 to -6 %
-  // time at K = 4096 .. 11008); in short ones the loading wavefronts' doubled share at the start of every tile
-  // costs more (+1 to +5 % at K = 512 .. 3072), so the launcher picks by K.
+  // the same time).  That pays in long K loops (measured, the two forms alternated
+  // on workload 5's layers: -1 to -3.5 % time at K = 4096 .. 11008); in short ones the loading wavefronts'
+  // doubled share at the start of every tile takes the gain back (within +-1 % at K = 512 .. 3072), so the
+  // launcher picks by K; cwac_tuning.persist_loaders forces either form.
   const bool loader = wave_s < LOADERS;
   auto issue_x = [&](int buf, int k0, bool hf) {
     if (!loader) return;
@@ -1144,14 +1145,15 @@ cwac_status launch_persist_loaders(const FwdParams &p, int workgroups, hipStream
 constexpr int kLoaderWavesFromK = 4096;  // K from which four wavefronts issue all panel loads (see the kernel)
 
 template <int OUT_KIND, bool INT_ONLY>
-cwac_status launch_persist_one(const FwdParams &p, int workgroups, hipStream_t st) {
-  return p.k >= kLoaderWavesFromK ? launch_persist_loaders<OUT_KIND, INT_ONLY, 4>(p, workgroups, st)
-                                  : launch_persist_loaders<OUT_KIND, INT_ONLY, 8>(p, workgroups, st);
+cwac_status launch_persist_one(const FwdParams &p, int workgroups, int loaders, hipStream_t st) {
+  if (loaders == 0) loaders = p.k >= kLoaderWavesFromK ? 4 : 8;  // else: the caller's override (cwac_tuning)
+  return loaders == 4 ? launch_persist_loaders<OUT_KIND, INT_ONLY, 4>(p, workgroups, st)
+                      : launch_persist_loaders<OUT_KIND, INT_ONLY, 8>(p, workgroups, st);
 }
 
 // The persistent kernel on a 256 x 256 tiling of the layer: one workgroup per compute unit (fewer
 // when there are fewer tiles).  out_kind: CWAC_OUT_INT8 | CWAC_OUT_FP32 | CWAC_OUT_INT32 | kOutFixed | kOutTable.
-cwac_status launch_persist(FwdParams p, int out_kind, bool int_only, int max_workgroups, hipStream_t st) {
+cwac_status launch_persist(FwdParams p, int out_kind, bool int_only, int max_workgroups, int loaders, hipStream_t st) {
   const size_t esz = (out_kind == CWAC_OUT_INT8 || out_kind == kOutFixed || out_kind == kOutTable) ? 1 : 4;
   p.vec_store = aligned(p.out, 16) && ((p.ldo * esz) % 16) == 0;
   p.tiles_m = (int)ceil_div(p.m, 256);
@@ -1165,12 +1167,12 @@ cwac_status launch_persist(FwdParams p, int out_kind, bool int_only, int max_wor
   int wgs = (int)(tiles < cus ? tiles : cus);
   if (max_workgroups > 0 && max_workgroups < wgs) wgs = max_workgroups;  // cwac_tuning.persist_workgroups
   if (out_kind == CWAC_OUT_INT8)
-    return int_only ? launch_persist_one<CWAC_OUT_INT8, true>(p, wgs, st)
-                    : launch_persist_one<CWAC_OUT_INT8, false>(p, wgs, st);
-  if (out_kind == CWAC_OUT_FP32) return launch_persist_one<CWAC_OUT_FP32, false>(p, wgs, st);
-  if (out_kind == kOutFixed) return launch_persist_one<kOutFixed, true>(p, wgs, st);
-  if (out_kind == kOutTable) return launch_persist_one<kOutTable, true>(p, wgs, st);
-  return launch_persist_one<CWAC_OUT_INT32, false>(p, wgs, st);
+    return int_only ? launch_persist_one<CWAC_OUT_INT8, true>(p, wgs, loaders, st)
+                    : launch_persist_one<CWAC_OUT_INT8, false>(p, wgs, loaders, st);
+  if (out_kind == CWAC_OUT_FP32) return launch_persist_one<CWAC_OUT_FP32, false>(p, wgs, loaders, st);
+  if (out_kind == kOutFixed) return launch_persist_one<kOutFixed, true>(p, wgs, loaders, st);
+  if (out_kind == kOutTable) return launch_persist_one<kOutTable, true>(p, wgs, loaders, st);
+  return launch_persist_one<CWAC_OUT_INT32, false>(p, wgs, loaders, st);
 }
 
 template <int BM, int WM, int BK, int NSTAGE, int NCHUNK, int OUT_KIND, bool INT_ONLY, bool CONV = false,
@@ -1216,14 +1218,14 @@ cwac_status launch_table_cfg(FwdParams p, hipStream_t st) {
 
 }  // namespace
 
-cwac_status launch_fast_table(FwdParams p, int shape, int max_workgroups, hipStream_t st) {
+cwac_status launch_fast_table(FwdParams p, int shape, int max_workgroups, int loaders, hipStream_t st) {
   p.vec_store = aligned(p.out, 16) && (p.ldo % 16) == 0;
   // the tiles of the plain int8 forward of a layer with n >= 256, by the same rule: the persistent
   // 256 x 256 tile, the same tile with one workgroup per tile, or the 128-token pair
   if (shape == CWAC_SHAPE_AUTO) shape = fast_linear_shape(p.m, p.n, p.k, 1);
   if ((p.k % 128) != 0 || shape == CWAC_SHAPE_128_128) shape = CWAC_SHAPE_128_PAIR;
   if (shape == CWAC_SHAPE_128_PAIR) return launch_table_cfg<128, 2, 64, 3>(p, st);
-  if (shape == CWAC_SHAPE_256_PERSIST) return launch_persist(p, kOutTable, true, max_workgroups, st);
+  if (shape == CWAC_SHAPE_256_PERSIST) return launch_persist(p, kOutTable, true, max_workgroups, loaders, st);
   return launch_table_cfg<256, 4, 128, 2>(p, st);
 }
 
@@ -1278,7 +1280,7 @@ cwac_status launch_fast(FwdParams p, int out_kind, bool int_only, const Tune &tu
   if (shape == CWAC_SHAPE_256_8W) return launch_cfg<256, 4, 128, 2, 2>(p, out_kind, int_only, st);
   if (shape == CWAC_SHAPE_256_4W_K128) return launch_cfg<256, 2, 128, 2, 2>(p, out_kind, int_only, st);
   // CWAC_SHAPE_256_PERSIST: the eight-wavefront 256 x 256 tile on persistent workgroups
-  return launch_persist(p, out_kind, int_only, tune.persist_workgroups, st);
+  return launch_persist(p, out_kind, int_only, tune.persist_workgroups, tune.persist_loaders, st);
 }
 
 int fast_linear_shape(int64_t m, int n, int k, int out_bytes) {

@@ -362,7 +362,7 @@ extern "C" cwac_status qlinear_cwac_forward_table_ex(const int8_t *x_q, int64_t 
   p.lo = (float)(qp->qmin - qp->z_r);
   p.hi = (float)(qp->qmax - qp->z_r);
   p.code_table = table;
-  return launch_fast_table(p, tune.shape, tune.persist_workgroups, as_stream(stream));
+  return launch_fast_table(p, tune.shape, tune.persist_workgroups, tune.persist_loaders, as_stream(stream));
 }
 
 extern "C" cwac_status qlinear_cwac_forward_table(const int8_t *x_q, int64_t ldx, const int8_t *w_q, int64_t ldw,

@@ -193,7 +193,8 @@ def test_tuning_is_validated_and_no_environment_variable_is_read(lib):
     a = C.c_void_p(4096)
     qp = binding.make_qparams()
     for bad in (binding.make_tuning(kernel=7), binding.make_tuning(shape=7), binding.make_tuning(shape=-1),
-                binding.make_tuning(stats_waves=3)):
+                binding.make_tuning(stats_waves=3), binding.make_tuning(persist_loaders=2),
+                binding.make_tuning(persist_loaders=16)):
         assert lib.qlinear_cwac_forward_ex(a, 32, a, 32, 4, 4, 32, C.byref(qp), a, a, null, null, 0, a, 4,
                                            C.byref(bad), null) == -4
         assert lib.cwac_forward_kernel_for(4, 4, 32, 32, 32, 0, C.byref(bad)) == -4

@@ -119,7 +119,7 @@ def test_quantize_rows_sym_and_colsum(orc, case1, case5s):
 
 # --------------------------------------------------------------------------- forward
 def _forward(c, out_kind, mult=None, offset=None, fbias=None, sx_row=None, qp=None, tile=None,
-             xq=None, ldo=None, pipe=None, wgs=0):
+             xq=None, ldo=None, pipe=None, wgs=0, loaders=0):
     xq = c.xq if xq is None else xq
     m = xq.shape[0]
     dt = {0: torch.int8, 1: torch.float32, 2: torch.int32}[out_kind]
@@ -130,7 +130,8 @@ def _forward(c, out_kind, mult=None, offset=None, fbias=None, sx_row=None, qp=No
         out = torch.full((m, ldo), 77, dtype=dt, device=DEV)
         view = out[:, :c.n]
     P.qlinear_cwac_forward(dev(xq), dev(c.wq), qp, dev(mult), dev(offset), dev(fbias),
-                           dev(sx_row), out_kind, view, tuning=tuning_of(tile, pipe, persist_workgroups=wgs))
+                           dev(sx_row), out_kind, view, tuning=tuning_of(tile, pipe, persist_workgroups=wgs,
+                                                                      persist_loaders=loaders))
     return host(out)
 
 
@@ -433,6 +434,14 @@ def test_forward_persistent_tiles(orc, m, n, k, wgs):
         _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)
         got = _forward(c, P.CWAC_OUT_FP32, mult, off, fbias=fb, sx_row=sxr, ldo=ldo, **kw)
         np.testing.assert_array_equal(got[:, :n], want)
+    # the count of loading wavefronts that the launcher would not pick at this K, forced through cwac_tuning
+    other = 8 if k >= 4096 else 4
+    got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, loaders=other, **kw)
+    np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, 5))
+    got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, loaders=other, **kw)
+    np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, 5, fb, sxr))
+    got = _forward(c, P.CWAC_OUT_INT32, offset=off, loaders=other, **kw)
+    np.testing.assert_array_equal(got, acc + off[None, :])
 
 
 # --------------------------------------------------------------------------- fold

@@ -8,17 +8,17 @@ _SHAPES = {"8w": _B.CWAC_SHAPE_256_8W, "128x2": _B.CWAC_SHAPE_256_4W_K128, "64x4
 
 
 def tuning_of(tile=None, pipe=None, w4_pipe=None, stats_waves=0, persist_workgroups=0, w4_small_waves=0,
-              w4_small_depth=0):
+              w4_small_depth=0, persist_loaders=0):
     """tile: None | 64 | 128 | 256 (generic kernel with that tile) | "fast" (direct-to-LDS kernel);
     pipe: None | "8w" | "128x2" | "64x4" | "duo" | "q" | "persist" (its tile shape);
     w4_pipe: None | "tile" | "half" (weight-only layer: 256- / 128-token tiles at every batch size);
     w4_small_waves: 0 | 4 | 8 (wavefronts per workgroup of its weight-streaming kernel), w4_small_depth: 0 | 2 | 3 | 4
-    (its ring depth).
+    (its ring depth); persist_loaders: 0 | 4 | 8 (wavefronts of the persistent tile that issue its panel loads).
     Returns None when nothing is forced (the plain entry point is then called)."""
     if (tile is None and pipe is None and w4_pipe is None and not stats_waves and not persist_workgroups
-            and not w4_small_waves and not w4_small_depth):
+            and not w4_small_waves and not w4_small_depth and not persist_loaders):
         return None
     kernel = 0 if tile is None else (_B.CWAC_KERNEL_DIRECT_LDS if tile == "fast" else int(tile))
     return P.make_tuning(kernel=kernel, shape=_SHAPES[pipe] if pipe else 0, stats_waves=stats_waves,
-                         w4_tile={None: 0, "tile": 256, "half": 128}[w4_pipe], w4_small_waves=w4_small_waves, w4_small_depth=w4_small_depth,
+                         w4_tile={None: 0, "tile": 256, "half": 128}[w4_pipe], w4_small_waves=w4_small_waves, w4_small_depth=w4_small_depth, persist_loaders=persist_loaders,
                          persist_workgroups=persist_workgroups)
