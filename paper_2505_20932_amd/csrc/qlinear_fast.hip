@@ -141,7 +141,16 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
   }
 }
 
-template <int OUT_KIND, bool INT_ONLY, bool VEC, int TB, int WM, int TA>
+//
+// ZFOLD (int8 codes through the floating-point multiplier): how Z_r reaches the code.
+//   0: added to the integer read off the rounding sum (one more instruction per result).
+//   1: Z_r even - it rides in the rounding constant: u + (1.5 * 2^23 + Z_r) rounds u to the nearest integer
+//      with ties to the even SUM, which is the even round(u) exactly when the constant is even.
+//   2: Z_r odd - the chain runs on -u (the converted accumulator enters the first multiply negated and the
+//      bias is subtracted: sign modifiers, and round-to-nearest is symmetric, so every intermediate is the
+//      exact negative), the constant carries the even -Z_r - 1, and the packed word is complemented:
+//      ~(c - n) = n - c - 1 = n + Z_r in every byte.
+template <int OUT_KIND, bool INT_ONLY, bool VEC, int TB, int WM, int TA, int ZFOLD = 0>
 __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[TA][TB], int8_t *smem,
                                               const float *s_mult, const float *s_fb,
                                               const float *s_rs, int64_t bm0, int bn0, int wave_m,
@@ -162,7 +171,11 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[TA
   for (int b = 0; b < TB; ++b) rs[b] = s_rs[wave_m * WROWS + b * 32 + l32];
   const bool use_rs = !INT_ONLY && p.sx_row != nullptr;
   const bool use_fb = !INT_ONLY && p.fbias != nullptr;
-  const float magic = 12582912.0f;  // 1.5 * 2^23: adding it rounds to nearest even at unit steps
+  // 1.5 * 2^23: adding it rounds to nearest even at unit steps; with ZFOLD the zero point rides along (the
+  // code table is indexed by code + 128, which is even and rides along as well)
+  const int zfold = (ZFOLD == 2 ? -p.zr - 1 : ZFOLD == 1 ? p.zr : 0) +
+                    (ZFOLD && OUT_KIND == kOutTable ? (ZFOLD == 2 ? -128 : 128) : 0);
+  const float magic = 12582912.0f + (float)zfold;
 #pragma unroll
   for (int a = 0; a < TA; ++a) {
     float mu[4][4], fb[4][4];
@@ -216,9 +229,10 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[TA
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           float f = (float)acc[a][b][4 * g + r];
+          if (ZFOLD == 2) f = -f;
           if (use_rs) f = f * rs[b];
           float v = f * mu[g][r];
-          if (use_fb) v = v + fb[g][r];
+          if (use_fb) v = ZFOLD == 2 ? v - fb[g][r] : v + fb[g][r];
           u[r] = v;
         }
         if (OUT_KIND == CWAC_OUT_FP32) {
@@ -236,12 +250,18 @@ __device__ __forceinline__ void fast_epilogue(const FwdParams &p, v16i (&acc)[TA
           for (int r = 0; r < 4; ++r) {
             // clamp(rint(u), lo, hi) == rint(clamp(u, lo, hi)) for integer bounds; the low bits
             // of (clamped + 1.5 * 2^23) are its rounded value in two's complement
-            const float cl_u = __builtin_amdgcn_fmed3f(u[r], p.lo, p.hi);
-            c[r] = __float_as_int(cl_u + magic) + p.zr;
-            if (OUT_KIND == kOutTable) c[r] = s_tab[(c[r] + 128) & 255];  // low byte of the sum: the code
+            const float cl_u = ZFOLD == 2 ? __builtin_amdgcn_fmed3f(u[r], -p.lo, -p.hi)
+                                          : __builtin_amdgcn_fmed3f(u[r], p.lo, p.hi);
+            c[r] = __float_as_int(cl_u + magic);
+            if (ZFOLD == 0) c[r] += p.zr;
+            if (OUT_KIND == kOutTable) {  // low byte of the sum: the code (ZFOLD: already code + 128)
+              if (ZFOLD == 2) c[r] = ~c[r];
+              c[r] = s_tab[(ZFOLD ? c[r] : c[r] + 128) & 255];
+            }
           }
           if (VEC) {
             packed[g] = pack4(c[0], c[1], c[2], c[3]);
+            if (ZFOLD == 2 && OUT_KIND != kOutTable) packed[g] = ~packed[g];
           } else {
             int8_t *o = reinterpret_cast<int8_t *>(wbase + row * row_bytes) + col;
 #pragma unroll
@@ -743,9 +763,16 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
     // whole-line stores need 16-byte aligned rows and tile origin (p.vec_store: base and row pitch)
     constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed || OUT_KIND == kOutTable) ? 1 : 4;
     const int vs = p.vec_store && (((bn0 * ESZ) & 15) == 0);
-    if (vs)
-      fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
-    else
+    if (vs) {
+      if constexpr (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutTable) {
+        if (p.zr & 1)
+          fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA, 2>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+        else
+          fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA, 1>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      } else {
+        fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
+      }
+    } else
       fast_epilogue<OUT_KIND, INT_ONLY, false, TB, WM, TA>(p, acc, smem, s_mult, s_fb, s_rs, bm0, bn0, wave_m, wave_n, lane);
   }
   CWAC_STAMP(3);
@@ -1103,10 +1130,19 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       asm volatile("" : "+v"(lane_e));
       constexpr int ESZ = (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutFixed || OUT_KIND == kOutTable) ? 1 : 4;
       const int vs = p.vec_store && (((e_bn0 * ESZ) & 15) == 0);
-      if (vs)
-        fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0, e_bn0,
-                                                            wave_m, wave_n, lane_e);
-      else
+      if (vs) {
+        if constexpr (OUT_KIND == CWAC_OUT_INT8 || OUT_KIND == kOutTable) {
+          if (p.zr & 1)
+            fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA, 2>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0,
+                                                                   e_bn0, wave_m, wave_n, lane_e);
+          else
+            fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA, 1>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0,
+                                                                   e_bn0, wave_m, wave_n, lane_e);
+        } else {
+          fast_epilogue<OUT_KIND, INT_ONLY, true, TB, WM, TA>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0, e_bn0,
+                                                              wave_m, wave_n, lane_e);
+        }
+      } else
         fast_epilogue<OUT_KIND, INT_ONLY, false, TB, WM, TA>(p, acc, smem + kSlabBase, s_mult, s_fb, s_rs, e_bm0, e_bn0,
                                                              wave_m, wave_n, lane_e);
     }

@@ -419,8 +419,9 @@ def test_forward_persistent_tiles(orc, m, n, k, wgs):
     sxr = (np.abs(synth.normal(1700 + m, 5, m).numpy()) + 0.5).astype(np.float32)
     from types import SimpleNamespace
     c = SimpleNamespace(xq=xq, wq=wq, n=n)
-    qp = P.make_qparams(z_r=5)
-    qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, z_r=5)
+    zr = -6 if wgs in (0, 3) else 5      # even and odd: the zero point reaches the code in two different ways
+    qp = P.make_qparams(z_r=zr)
+    qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, z_r=zr)
     kw = dict(tile="fast", pipe="persist", wgs=wgs)
     for ldo in (None, n + 5):
         got = _forward(c, P.CWAC_OUT_INT32, offset=off, ldo=ldo, **kw)
@@ -428,20 +429,51 @@ def test_forward_persistent_tiles(orc, m, n, k, wgs):
         if ldo:
             assert np.all(got[:, n:] == 77)
         got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, ldo=ldo, **kw)
-        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5))
+        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, zr))
         got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, ldo=ldo, **kw)
-        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, 5, fb, sxr))
+        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, zr, fb, sxr))
         _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)
         got = _forward(c, P.CWAC_OUT_FP32, mult, off, fbias=fb, sx_row=sxr, ldo=ldo, **kw)
         np.testing.assert_array_equal(got[:, :n], want)
     # the count of loading wavefronts that the launcher would not pick at this K, forced through cwac_tuning
     other = 8 if k >= 4096 else 4
     got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, loaders=other, **kw)
-    np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, 5))
+    np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, zr))
     got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, loaders=other, **kw)
-    np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, 5, fb, sxr))
+    np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, zr, fb, sxr))
     got = _forward(c, P.CWAC_OUT_INT32, offset=off, loaders=other, **kw)
     np.testing.assert_array_equal(got, acc + off[None, :])
+
+
+@pytest.mark.parametrize("zr", [-128, -77, -6, 0, 1, 5, 126, 127])
+def test_forward_ties_and_saturation_for_every_zero_point_parity(orc, zr):
+    """Multipliers that are powers of two and biases that are multiples of 1/2 put many results exactly half
+    way between two codes (round half to even decides), and a few channels saturate at either end; even and
+    odd zero points, at the ends of their range too.  Persistent tile and the one-workgroup-per-tile form."""
+    m, n, k = 520, 512, 256
+    print(f"ties and saturation, z_r = {zr}", flush=True)
+    g = synth.normal(2100, 0, m * k).numpy().reshape(m, k)
+    xq = np.clip(np.rint(g * 3), -128, 127).astype(np.int8)
+    g = synth.normal(2100, 1, n * k).numpy().reshape(n, k)
+    wq = np.clip(np.rint(g * 3), -127, 127).astype(np.int8)
+    acc = orc.gemm_i8(xq, wq)
+    mult = np.array([0.5, 0.25, 0.125, -0.5, 1.5, 0.0625, 4.0, -8.0], dtype=np.float32)[np.arange(n) % 8]
+    off = np.rint(synth.normal(2100, 3, n).numpy() * 50).astype(np.int32)
+    fb = (np.rint(synth.normal(2100, 4, n).numpy() * 20) * 0.5).astype(np.float32)
+    sxr = np.array([1.0, 0.5, 2.0, 0.25], dtype=np.float32)[np.arange(m) % 4]
+    want = orc.folded_forward(acc, off, mult, zr)
+    u = (acc + off[None, :]).astype(np.float64) * mult[None, :].astype(np.float64)
+    assert np.mean(np.abs(u - np.floor(u)) == 0.5) > 0.1          # the case does hold exact ties
+    assert (want == -128).any() and (want == 127).any()           # and both ends
+    from types import SimpleNamespace
+    c = SimpleNamespace(xq=xq, wq=wq, n=n)
+    qp = P.make_qparams(z_r=zr)
+    qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, z_r=zr)
+    for pipe in ("persist", "8w"):
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, tile="fast", pipe=pipe)
+        np.testing.assert_array_equal(got, want)
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, tile="fast", pipe=pipe)
+        np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, zr, fb, sxr))
 
 
 # --------------------------------------------------------------------------- fold
