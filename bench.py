@@ -1143,6 +1143,107 @@ def tile_timeline(torch, synth, dev: str, cfgs, fp32_out: bool = False):
             "layers": out}
 
 
+def stage_sweep(torch, synth, dev: str):
+    """What sets the K loop's pace: the persistent 256 x 256 tile's time per 128-byte K stage (in-kernel time
+    stamps, development build as for tile_timeline) against the operand values (all zero; normal values of
+    standard deviation 4 and 30 codes; workload 5's own tensors), the number of compute units at work
+    (cwac_tuning.persist_workgroups) and the problem's K and size.  20 back-to-back launches after 30 warm-up
+    launches for the launch time, one more launch for the stamps."""
+    import ctypes
+    import numpy as np
+    from paper_2505_20932_amd import build as B
+    if not os.path.exists(B.STAMP_LIB):
+        raise SystemExit(f"{B.STAMP_LIB} is missing: python -m paper_2505_20932_amd.build --timeline")
+    import paper_2505_20932_amd as P
+    assert P.binding.LIB_PATH == B.STAMP_LIB, P.binding.LIB_PATH
+    lib = P.binding.lib()
+    lib.cwac_debug_stamps.restype = ctypes.c_int
+    lib.cwac_debug_stamps.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    buf = torch.zeros(4096 * 8 * 5, dtype=torch.int64, device=dev)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+
+    def operands(kind, m, n, k):
+        if kind == "zeros":
+            return torch.zeros(m, k, dtype=torch.int8, device=dev), torch.zeros(n, k, dtype=torch.int8, device=dev)
+        sd = {"normal, sd 4": 4.0, "normal, sd 30": 30.0}[kind]
+        x = torch.clamp(torch.round(torch.randn(m, k, device=dev, generator=gen) * sd), -128, 127).to(torch.int8)
+        w = torch.clamp(torch.round(torch.randn(n, k, device=dev, generator=gen) * sd), -127, 127).to(torch.int8)
+        return x, w
+
+    def measure(x, w, wgs, label):
+        m, k = x.shape
+        n = w.shape[0]
+        mult = torch.full((n,), 1e-3, dtype=torch.float32, device=dev)
+        off = torch.zeros(n, dtype=torch.int32, device=dev)
+        out = torch.empty(m, n, dtype=torch.int8, device=dev)
+        qp = P.make_qparams(z_r=4)
+        tun = P.make_tuning(kernel=P.binding.CWAC_KERNEL_DIRECT_LDS, shape=P.binding.CWAC_SHAPE_256_PERSIST,
+                            persist_workgroups=wgs)
+
+        def fwd():
+            P.qlinear_cwac_forward(x, w, qp, mult, off, None, None, P.CWAC_OUT_INT8, out, tuning=tun)
+        for _ in range(30):
+            fwd()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            fwd()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 20 * 1e3
+        buf.zero_()
+        fwd()
+        torch.cuda.synchronize()
+        assert lib.cwac_debug_stamps(buf.data_ptr(), buf.numel() * 8, None) == 0
+        torch.cuda.synchronize()
+        tiles = ((m + 255) // 256) * ((n + 255) // 256)
+        g = min(tiles, wgs or cus, cus)
+        rest = tiles % g
+        n_whole = tiles - rest if (0 < rest and 2 * rest <= g) else tiles
+        st = buf.cpu().numpy().reshape(4096, 8, 5)[:min(n_whole, 4096)].astype(np.float64) * 0.01
+        d = [float((st[:, :, i + 1] - st[:, :, i]).mean()) for i in range(3)]
+        stages = k // 128
+        return {"case": label, "m": m, "n": n, "k": k, "workgroups": g, "launch_us": round(us, 1),
+                "tops": round(2.0 * m * n * k / us / 1e6, 1),
+                "tops_per_workgroup": round(2.0 * m * n * k / us / 1e6 / g, 2),
+                "start_to_first_mfma_us": round(d[0], 2), "k_loop_us": round(d[1], 2),
+                "us_per_stage": round(d[1] / stages, 3),
+                "stage_rate_of_peak": round(2.0 * 256 * 256 * 128 / (d[1] / stages) / (INT8_MFMA_PEAK_TOPS * 1e6 / 256), 3),
+                "epilogue_us": round(d[2], 2)}
+
+    rows = []
+    # operand values, one shape (workload 5's o projection), every compute unit
+    wl, layers = setup_layers(P, synth, torch, 5, dev, synth.WORKLOADS[5].m)
+    L = [l for l in layers if l.name == "o"][0]
+    xw, ww = L.xq.clone(), L.wq.clone()
+    del layers, L
+    torch.cuda.empty_cache()
+    m, n, k = xw.shape[0], ww.shape[0], xw.shape[1]
+    for kind in ("zeros", "normal, sd 4", "normal, sd 30"):
+        x, w = operands(kind, m, n, k)
+        rows.append(measure(x, w, 0, f"operands {kind}"))
+        del x, w
+    rows.append(measure(xw, ww, 0, "operands of workload 5 (o projection)"))
+    # compute units at work, same tensors
+    for wgs in (32, 64, 128, 192):
+        rows.append(measure(xw, ww, wgs, f"workload 5 operands, {wgs} workgroups"))
+    x0, w0 = operands("zeros", m, n, k)
+    for wgs in (32, 128):
+        rows.append(measure(x0, w0, wgs, f"operands zeros, {wgs} workgroups"))
+    del x0, w0
+    # K and problem size, same distribution of values
+    for (mm, nn, kk) in ((16384, 4096, 768), (4096, 4096, 768), (4096, 4096, 4096), (25216, 768, 3072)):
+        x, w = operands("normal, sd 4", mm, nn, kk)
+        rows.append(measure(x, w, 0, "operands normal, sd 4"))
+        del x, w
+    return {"stage_sweep": "persistent 256 x 256 int8 tile: time per 128-byte K stage (ideal at the published peak: "
+                           f"{2.0 * 256 * 256 * 128 / (INT8_MFMA_PEAK_TOPS * 1e6 / 256):.3f} us) against operand values, "
+                           "compute units at work, K and problem size", "rows": rows}
+
+
 def forward_shapes(P, synth, torch, dev: str, cfgs, reps: int = 20):
     """Every tile shape of the direct-to-LDS forward that a layer admits, chosen through cwac_tuning, timed
     on each distinct layer shape of the workloads (int8 output, the layer's own folded epilogue): `reps`
@@ -1566,6 +1667,9 @@ def main():
     ap.add_argument("--tile-timeline", action="store_true",
                     help="instead of the benchmark: in-kernel time stamps of the int8 forward's tiles on workloads "
                          "2-5 (needs `python -m paper_2505_20932_amd.build --timeline`; its own JSON line)")
+    ap.add_argument("--stage-sweep", action="store_true",
+                    help="instead of the benchmark: the persistent tile's time per K stage against operand values, "
+                         "compute units at work, K and problem size (needs the --timeline build; its own JSON line)")
     ap.add_argument("--timeline-fp32", action="store_true",
                     help="with --tile-timeline: the fp32-output calibration forward instead of the int8 forward")
     ap.add_argument("--forward-shapes", action="store_true",
@@ -1584,14 +1688,17 @@ def main():
         sys.exit(2)
 
     import torch
-    if args.tile_timeline:
+    if args.tile_timeline or args.stage_sweep:
         # the package reads the library path when it is first imported
         os.environ["CWAC_LIB"] = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2505_20932_amd",
                                               "libcwac_hip_timeline.so")
         from paper_2505_20932_amd import synth
         assert torch.cuda.is_available(), "bench.py needs the MI355X"
         torch.cuda.set_device(0)
-        print(json.dumps(tile_timeline(torch, synth, "cuda:0", (2, 3, 4, 5), args.timeline_fp32)))
+        if args.stage_sweep:
+            print(json.dumps(stage_sweep(torch, synth, "cuda:0")))
+        else:
+            print(json.dumps(tile_timeline(torch, synth, "cuda:0", (2, 3, 4, 5), args.timeline_fp32)))
         return
     import paper_2505_20932_amd as P
     from paper_2505_20932_amd import synth
