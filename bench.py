@@ -483,6 +483,31 @@ def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: 
         "calibration_forward_tflops": round(fwd_flops / (t_cal * 1e-3) / 1e12, 2),
         "dense_fp16_library_gemm_tflops": round(fwd_flops / (t_dense * 1e-3) / 1e12, 2),
     }
+    # context for roofline.frac: what the binary16 matrix cores sustain on this device with register-resident
+    # operands sampled from this workload (weight values of layer 0 in fp16, its activations), no memory traffic
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    g = torch.Generator(device="cpu").manual_seed(4321)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def sample16(t):
+        v = t.contiguous().view(-1)[:(t.numel() // 8) * 8].view(-1, 8)        # 16-byte operand chunks
+        return v[torch.randint(0, v.shape[0], (512,), generator=g).to(dev)]
+
+    probes = {"zero_operands": torch.zeros(1024, 8, dtype=torch.float16, device=dev),
+              "workload_operands": torch.cat([sample16(layers[0].wh), sample16(layers[0].x)]).contiguous()}
+    ceiling = {}
+    for name, ops_buf in probes.items():
+        P.cwac_mfma_probe_f16(ops_buf, 5000, cus, sink)
+        torch.cuda.synchronize()
+        e0.record()
+        fl = 0.0
+        for _ in range(4):
+            fl += P.cwac_mfma_probe_f16(ops_buf, 20000, cus, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ceiling[name] = round(fl / (e0.elapsed_time(e1) * 1e-3) / 1e15, 3)
+    ceiling["unit"] = "PFLOP/s"
+    res["mfma_ceiling_probe_f16"] = ceiling
     # decode-sized batches (8 tokens): the layer is a stream of 4-bit weights; 20 passes over the
     # five layers replayed from a HIP graph (a launch from Python costs as much as the kernel)
     sm = 8

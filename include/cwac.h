@@ -653,6 +653,15 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
 cwac_status cwac_mfma_probe(const int32_t *operands, int32_t iters, int32_t workgroups,
                             int32_t *sink, void *stream);
 
+/* The same for the binary16 matrix cores, the weight-only layer's (per wavefront 4 x 4 MFMA
+ * 32x32x16 tiles, fp32 accumulators): 2 * 16384 * 16 * iters * 4 * workgroups floating-point
+ * operations.
+ *   operands  device, 16 KiB of binary16 values (1024 x 16 bytes), 16-byte aligned: first half the
+ *             weight fragments, second half the activation fragments
+ *   iters, workgroups, sink: as above */
+cwac_status cwac_mfma_probe_f16(const uint16_t *operands, int32_t iters, int32_t workgroups,
+                                int32_t *sink, void *stream);
+
 /* Diagnostic as well: the K loop of the forward's 256 x 256 tile (512 threads, 128 KiB of
  * LDS, one workgroup per compute unit; per stage 256 MFMAs of 32x32x32 per workgroup =
  * 2 * 32768 * 256 int8 operations) with its ingredients added one at a time -

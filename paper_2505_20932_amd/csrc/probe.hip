@@ -41,6 +41,41 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const v4i *__restrict__
   if (s == 0x12345678) sink[0] = s;  // keeps the loop alive; practically never taken
 }
 
+// The same for the binary16 matrix cores (the weight-only layer's MFMA, 32 x 32 x 16, fp32 accumulators).
+typedef _Float16 probe_h8 __attribute__((ext_vector_type(8)));
+typedef float probe_v16f __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_probe_f16_kernel(const probe_h8 *__restrict__ operands, int iters,
+                                                             int32_t *sink) {
+  probe_h8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = operands[(threadIdx.x + 64 * i) & 511];
+    b[i] = operands[512 + ((threadIdx.x + 64 * i) & 511)];
+  }
+  probe_v16f acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s += acc[i][j][e];
+  if (__float_as_int(s) == 0x12345678) sink[0] = 1;  // keeps the loop alive; practically never taken
+}
+
 // Second diagnostic: the K loop of the 256 x 256 forward tile (eight wavefronts, two stages of 64 KiB, per
 // wavefront and k-step eight MFMAs on 64 tokens x 128 channels) built up one ingredient at a time, so that
 // the cost of each shows as a rate: MODE 0 the MFMAs alone on register-resident fragments; 1 + the six
@@ -191,6 +226,16 @@ extern "C" cwac_status cwac_kloop_probe(const int32_t *operands, const int8_t *p
     case 3: return launch_kloop_probe<3>(operands, panels, stages, workgroups, sink, st);
     default: return launch_kloop_probe<4>(operands, panels, stages, workgroups, sink, st);
   }
+}
+
+extern "C" cwac_status cwac_mfma_probe_f16(const uint16_t *operands, int32_t iters, int32_t workgroups,
+                                           int32_t *sink, void *stream) {
+  if (!operands || !sink) return CWAC_E_NULL;
+  if (iters < 1 || iters > (1 << 24) || workgroups < 1 || workgroups > (1 << 20)) return CWAC_E_SHAPE;
+  if (!aligned(operands, 16)) return CWAC_E_ALIGN;
+  mfma_probe_f16_kernel<<<(unsigned)workgroups, 256, 0, as_stream(stream)>>>(
+      reinterpret_cast<const probe_h8 *>(operands), iters, sink);
+  return launch_status();
 }
 
 extern "C" cwac_status cwac_mfma_probe(const int32_t *operands, int32_t iters, int32_t workgroups,
