@@ -586,8 +586,9 @@ typedef struct cwac_tuning {
   int32_t shape;          /* CWAC_SHAPE_*: tile shape of the direct-to-LDS kernel for n >= 256 (used when that
                              kernel runs; k % 128 != 0 always takes CWAC_SHAPE_128_PAIR or _128_128) */
   int32_t stats_waves;    /* qlinear_cwac_calibrate_fused_ex: 0 (= 8) | 8 | 4 wavefronts per tile */
-  int32_t w4_tile;        /* qlinear_w4a16_cwac_forward_ex: 0 | 256 | 128: the tiled kernel with that
-                             many tokens per tile at every batch size */
+  int32_t w4_tile;        /* qlinear_w4a16_cwac_forward_ex: 0 | 256 | 128: the tiled kernel with that many
+                             tokens per tile (256 channels wide) at every batch size; 512: its tile of 512
+                             channels x 128 tokens (needs n >= 512, else CWAC_E_MODE) */
   int32_t w4_small_waves; /* ... its weight-streaming kernel (small batches): 0 | 4 | 8 wavefronts per workgroup */
   int32_t persist_workgroups; /* CWAC_SHAPE_256_PERSIST: 0 = one workgroup per compute unit; n > 0 = at most n
                                  (each then walks more tiles; leaves compute units to concurrent work) */

@@ -158,12 +158,16 @@ struct W4Params {
 constexpr int kFwdThreads = 512;  // 8 wavefronts: 2 per SIMD
 constexpr int kTA = 2;            // MFMA row blocks per wavefront: 64 channels
 constexpr int kSlabStride = 144;
-// Tile of 256 channels x (64 * TB) tokens: 2 x 4 wavefronts of TB token blocks x kTA channel
-// blocks of 32.  TB = 4 is the tile of large batches; TB = 2 halves it for batches of a few hundred
-// tokens, where one row of 256-token tiles would leave most compute units idle.
-template <int TB>
+// Tile of WM x (8 / WM) wavefronts, each TB token blocks x kTA channel blocks of 32: (32 * TB * WM) tokens x
+// (512 / WM) channels.  WM = 2: 256 channels x 256 tokens (TB = 4), or 128 tokens (TB = 2) for batches of a few
+// hundred tokens, where one row of 256-token tiles would leave most compute units idle.  WM = 1 (TB = 4): 512
+// channels x 128 tokens - every wavefront expands weights that no other wavefront of the tile needs (with WM = 2
+// the two wavefronts of a channel block expand the same codes), so the tile spends half the vector work per MFMA.
+template <int TB, int WM = 2>
 struct W4Cfg {
-  static constexpr int BM = 64 * TB;
+  static_assert(WM == 1 || WM == 2, "wavefronts along the tokens");
+  static constexpr int BM = 32 * TB * WM;
+  static constexpr int BN = 64 * (8 / WM);
   static constexpr int STAGE_BYTES = BM * 256;  // BM rows x 128 binary16
   static constexpr int RING = 2 * STAGE_BYTES;
   static constexpr int XROWS = BM / 8;          // activation rows one wavefront fetches per stage
@@ -172,7 +176,7 @@ struct W4Cfg {
   static constexpr int SLAB_BYTES = SLAB_ROWS * kSlabStride;
   // epilogue parameters sit behind the ring and the slabs
   static constexpr int PARAMS = 8 * SLAB_BYTES > RING ? 8 * SLAB_BYTES : RING;
-  static constexpr int LDS = PARAMS + 2 * 256 * 4;
+  static constexpr int LDS = PARAMS + 2 * BN * 4;
   static_assert(LDS <= 160 * 1024, "LDS budget of one compute unit");
 };
 
@@ -262,15 +266,15 @@ __device__ __forceinline__ void store_slab(const int8_t *slab, char *gbase, int6
 // token m = bm0 + wave_m*32*TB + b*32 + l32.  Each wavefront transposes its 32*TB rows x 128 bytes
 // through a private LDS slab (row stride 144 bytes) and writes whole 128-byte lines: binary16
 // output = all 64 channels of the wave tile in one slab, fp32 output = one slab per MFMA column.
-template <int OUT_KIND, int TB>
+template <int OUT_KIND, int TB, int WM>
 __device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[kTA][TB], int8_t *smem,
                                             const float *s_mult, const float *s_fb, int64_t bm0, int bn0,
                                             int wave_m, int wave_n, int lane) {
   constexpr int ESZ = OUT_KIND == CWAC_OUT_FP16 ? 2 : 4;
   constexpr int APS = OUT_KIND == CWAC_OUT_FP16 ? 2 : 1;  // MFMA columns per 128-byte slab row
   const int l32 = lane & 31, half = lane >> 5;
-  const int wave = wave_m + 2 * wave_n;
-  int8_t *slab = smem + wave * W4Cfg<TB>::SLAB_BYTES;
+  const int wave = wave_m + WM * wave_n;
+  int8_t *slab = smem + wave * W4Cfg<TB, WM>::SLAB_BYTES;
   const int64_t row_bytes = p.ldo * ESZ;
   const int64_t wrow0 = bm0 + wave_m * 32 * TB;
   char *wbase = p.out + (wrow0 * p.ldo + bn0 + wave_n * 64) * ESZ;
@@ -312,28 +316,29 @@ __device__ __forceinline__ void w4_epilogue(const W4Params &p, v16f (&acc)[kTA][
   }
 }
 
-template <int OUT_KIND, int TB>
+template <int OUT_KIND, int TB, int WM>
 __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
-  using Cfg = W4Cfg<TB>;
+  using Cfg = W4Cfg<TB, WM>;
+  constexpr int BN = Cfg::BN;
   constexpr int kXLoads = Cfg::XLOADS, kStageBytes = Cfg::STAGE_BYTES, kParams = Cfg::PARAMS;
   extern __shared__ __attribute__((aligned(16))) int8_t smem[];
   float *s_mult = reinterpret_cast<float *>(smem + kParams);
-  float *s_fb = reinterpret_cast<float *>(smem + kParams + 1024);
+  float *s_fb = reinterpret_cast<float *>(smem + kParams + BN * 4);
 
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
   const int64_t bm0 = (int64_t)tile_m * Cfg::BM;  // row edges: clamped loads, predicated stores
-  int bn0 = tile_n * 256;
-  if (bn0 > p.n - 256) bn0 = p.n - 256;  // channel edge: tile shifted inwards (n % 32 == 0)
+  int bn0 = tile_n * BN;
+  if (bn0 > p.n - BN) bn0 = p.n - BN;  // channel edge: tile shifted inwards (n % 32 == 0)
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave & 1, wave_n = wave >> 1;  // 2 x 4 wavefronts of 32*TB tokens x 64 channels
+  const int wave_m = wave % WM, wave_n = wave / WM;  // WM x (8 / WM) wavefronts of 32*TB tokens x 64 channels
   const int l32 = lane & 31, half = lane >> 5;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
 
   float p_mult = 1.0f, p_fb = 0.0f;
-  if (tid < 256) {
+  if (tid < BN) {
     if (p.mult) p_mult = p.mult[bn0 + tid];
     if (p.fbias) p_fb = p.fbias[bn0 + tid];
   }
@@ -368,7 +373,7 @@ __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
 
   // ---- weights, global -> registers: per MFMA row block a, 2 x 16 bytes per lane and stage
   const int kb64 = p.k / 64;
-  const int n0w = bn0 + wave_s / 2 * 64;  // first channel of this wavefront
+  const int n0w = bn0 + wave_s / WM * 64;  // first channel of this wavefront
   const uint32_t w_lane = (uint32_t)lane * 16u, sz_lane = (uint32_t)l32 * 4u;
   struct RawW {
     u4 c[kTA][2];
@@ -438,7 +443,7 @@ __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
   issue_x(0, 0);
   issue_w(rawA, 0);
   if (stages > 1) issue_x(1, 1);
-  if (tid < 256) {
+  if (tid < BN) {
     s_mult[tid] = p_mult;
     s_fb[tid] = p_fb;
   }
@@ -496,18 +501,18 @@ __global__ __launch_bounds__(kFwdThreads) void w4a16_kernel(const W4Params p) {
   if (s < stages) stage_body(s, 0, rawA, rawB);
 
   // every wavefront is past its last LDS read of the ring (the barrier of the last stage)
-  w4_epilogue<OUT_KIND, TB>(p, acc, smem, s_mult, s_fb, bm0, bn0, wave_m, wave_n, lane);
+  w4_epilogue<OUT_KIND, TB, WM>(p, acc, smem, s_mult, s_fb, bm0, bn0, wave_m, wave_n, lane);
 }
 
-template <int OUT_KIND, int TB>
+template <int OUT_KIND, int TB, int WM = 2>
 cwac_status launch_w4(const W4Params &p, hipStream_t st) {
   static const hipError_t attr =
-      hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a16_kernel<OUT_KIND, TB>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, W4Cfg<TB>::LDS);
+      hipFuncSetAttribute(reinterpret_cast<const void *>(&w4a16_kernel<OUT_KIND, TB, WM>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, W4Cfg<TB, WM>::LDS);
   if (attr != hipSuccess) return CWAC_E_LAUNCH;
   const int64_t blocks = (int64_t)p.tiles_m * p.tiles_n;
   if (blocks > 0x7fffffff) return CWAC_E_LAUNCH;
-  w4a16_kernel<OUT_KIND, TB><<<dim3((unsigned)blocks), kFwdThreads, W4Cfg<TB>::LDS, st>>>(p);
+  w4a16_kernel<OUT_KIND, TB, WM><<<dim3((unsigned)blocks), kFwdThreads, W4Cfg<TB, WM>::LDS, st>>>(p);
   return launch_status();
 }
 
@@ -791,7 +796,7 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
   if (out_kind != CWAC_OUT_FP16 && out_kind != CWAC_OUT_FP32) return CWAC_E_MODE;
   const int w4_tile = tuning ? tuning->w4_tile : 0, small_waves = tuning ? tuning->w4_small_waves : 0;
   const int small_depth = tuning ? tuning->w4_small_depth : 0;
-  if ((w4_tile != 0 && w4_tile != 256 && w4_tile != 128) ||
+  if ((w4_tile != 0 && w4_tile != 256 && w4_tile != 128 && w4_tile != 512) || (w4_tile == 512 && n < 512) ||
       (small_waves != 0 && small_waves != 4 && small_waves != 8) || (small_depth != 0 && (small_depth < 2 || small_depth > 4)))
     return CWAC_E_MODE;
   if (m < 1 || n < 256 || n % 32 != 0 || k < kGroup || k > 32768 || k % kGroup != 0 || ldx < k || ldo < n)
@@ -843,6 +848,13 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
     p.tiles_m = (int)ceil_div(m, 128);
     return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16, 2>(p, as_stream(stream))
                                      : launch_w4<CWAC_OUT_FP32, 2>(p, as_stream(stream));
+  }
+  // large batches: the tile of 512 channels x 128 tokens (no wavefront expands another one's weights)
+  if (w4_tile == 512 || (w4_tile == 0 && n >= 512)) {
+    p.tiles_m = (int)ceil_div(m, 128);
+    p.tiles_n = (int)ceil_div(n, 512);
+    return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16, 4, 1>(p, as_stream(stream))
+                                     : launch_w4<CWAC_OUT_FP32, 4, 1>(p, as_stream(stream));
   }
   p.tiles_m = (int)ceil_div(m, 256);
   return out_kind == CWAC_OUT_FP16 ? launch_w4<CWAC_OUT_FP16, 4>(p, as_stream(stream))

@@ -201,7 +201,7 @@ def test_tuning_is_validated_and_no_environment_variable_is_read(lib):
         assert lib.qlinear_cwac_forward_ex(a, 32, a, 32, 4, 4, 32, C.byref(qp), a, a, null, null, 0, a, 4,
                                            C.byref(bad), null) == -4
         assert lib.cwac_forward_kernel_for(4, 4, 32, 32, 32, 0, C.byref(bad)) == -4
-    for bad in (binding.make_tuning(w4_tile=64), binding.make_tuning(w4_small_waves=16),
+    for bad in (binding.make_tuning(w4_tile=64), binding.make_tuning(w4_tile=512), binding.make_tuning(w4_small_waves=16),
                 binding.make_tuning(w4_small_depth=5), binding.make_tuning(w4_small_depth=1)):
         assert lib.qlinear_w4a16_cwac_forward_ex(a, 128, a, a, 1, 256, 128, null, null, 3, a, 256, C.byref(bad),
                                                  null) == -4

@@ -8,7 +8,7 @@ import pytest
 import torch
 
 import paper_2505_20932_amd as P
-from tuning import tuning_of
+from tuning import tuning_of, w4_pipes
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -158,7 +158,7 @@ def test_weight_only_random_shape(m, n, k):
     pw = torch.empty(P.cwac_w4_packed_w_bytes(n, k), dtype=torch.uint8, device=DEV)
     psz = torch.empty((k // 128) * n, dtype=torch.int32, device=DEV)
     P.cwac_w4_pack(dev(codes), dev(scales), dev(zeros), pw, psz)
-    for pipe in (None, "tile", "half"):
+    for pipe in w4_pipes(n):
         tun = tuning_of(w4_pipe=pipe)
         out = torch.empty(m, n, dtype=torch.float32, device=DEV)
         P.qlinear_w4a16_cwac_forward(dev(x16), pw, psz, n, dev(mult), dev(fbias), out, tuning=tun)

@@ -16,7 +16,7 @@ import torch
 
 import paper_2505_20932_amd as P
 from paper_2505_20932_amd import synth
-from tuning import tuning_of
+from tuning import tuning_of, w4_pipes
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -139,7 +139,8 @@ def _exact_case(seed, m, n, k):
 
 
 @pytest.mark.parametrize("m,n,k", [(256, 256, 128), (300, 512, 384), (1, 256, 256), (513, 288, 256),
-                                   (77, 800, 1024), (1024, 256, 2048), (129, 544, 640), (385, 256, 512)])
+                                   (77, 800, 1024), (1024, 256, 2048), (129, 544, 640), (385, 256, 512),
+                                   (700, 1056, 256), (128, 512, 128), (260, 1024, 1152)])
 def test_forward_exact_operands(w4, m, n, k):
     print(f"w4a16 exact operands {m} x {n} x {k}", flush=True)
     x16, codes, scales, zeros = _exact_case(100 + m + n + k, m, n, k)
@@ -155,7 +156,7 @@ def test_forward_exact_operands(w4, m, n, k):
     o32m, _ = w4.epilogue_f32(acc32, mult, None)
     o32b, _ = w4.epilogue_f32(acc32, None, fbias)
     # the automatic choice, then the 256-token and the 128-token tile forced
-    for pipe in (None, "tile", "half"):
+    for pipe in w4_pipes(n):
         # raw product, fp32 out
         out = _forward(x16, pw, psz, n, None, None, torch.float32, pipe=pipe)
         np.testing.assert_array_equal(out.cpu().numpy(), acc32)
@@ -191,7 +192,7 @@ def test_small_batch_exact_operands(w4, m, n, k):
     o32, o16 = w4.epilogue_f32(acc32, mult, fbias)
     o32m, _ = w4.epilogue_f32(acc32, mult, None)
     o32b, _ = w4.epilogue_f32(acc32, None, fbias)
-    for pipe in (None, "tile", "half"):
+    for pipe in w4_pipes(n):
         out = _forward(x16, pw, psz, n, None, None, torch.float32, pipe=pipe)
         np.testing.assert_array_equal(out.cpu().numpy(), acc32)
         out = _forward(x16, pw, psz, n, mult, fbias, torch.float32, ldo=n + 12, pipe=pipe)
@@ -326,7 +327,7 @@ def test_forward_workload_like(w4, m, n, k):
     beta = (0.02 * synth.normal(7, 1, n).numpy()).astype(np.float32)
     mult, fbias = w4.fold(alpha, beta, None, n)
     ref = w4.folded_real(acc, mult, fbias)
-    for pipe in ("tile", "half"):
+    for pipe in w4_pipes(n, auto=False):
         for dtype in (torch.float32, torch.float16):
             out = _forward(x16, pw, psz, n, mult, fbias, dtype, pipe=pipe).cpu().numpy().astype(np.float64)
             err = np.abs(out - ref)
