@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # --pmc FETCH_SIZE / WRITE_SIZE summaries of `bench.py --probe` (the file named in "traffic_source"),
 # scaled by what the same counters read for a plain 1 GiB copy (x1.997, x1.000); mean over the
 # workload's launches.
-PMC_TRAFFIC_BYTES = {5: {"forward_int8": 979e6 + 139e6, "statistics": 1113e6 + 8e6,
-                         "forward_w4a16": 1535e6 + 331e6}}
+PMC_TRAFFIC_BYTES = {5: {"forward_int8": 982e6 + 139e6, "statistics": 1113e6 + 8e6,
+                         "forward_w4a16": 1044e6 + 292e6}}
 PMC_TRAFFIC_SOURCE = {5: "profiles/bench_config5_pmc_traffic.md (constant from that profile, not measured in this run)"}
 
 
@@ -483,6 +483,36 @@ def weight_only_int4(P, synth, torch, cfg: int, dev: str, steps: int, cpu_rows: 
         "calibration_forward_tflops": round(fwd_flops / (t_cal * 1e-3) / 1e12, 2),
         "dense_fp16_library_gemm_tflops": round(fwd_flops / (t_dense * 1e-3) / 1e12, 2),
     }
+    # the same forward with the earlier 256 x 256 tile, and both (and the library GEMM) on zero activations, which
+    # draw the least power in the matrix cores: what the kernels' own pipelines allow
+    def fwd_pass(xs, tun):
+        for L, x in zip(layers, xs):
+            P.qlinear_w4a16_cwac_forward(x, L.pw, L.psz, L.n, L.mult, L.fbias, L.out, tuning=tun)
+
+    def dense_pass(xs, tun):
+        for L, x in zip(layers, xs):
+            torch.matmul(x, L.wh.t(), out=L.out)
+
+    def timed(fn, xs, tun=None):
+        fn(xs, tun)
+        e0.record()
+        for _ in range(steps):
+            fn(xs, tun)
+        e1.record()
+        torch.cuda.synchronize()
+        return round(fwd_flops / (e0.elapsed_time(e1) / steps * 1e-3) / 1e12, 2)
+
+    xs_w = [L.x for L in layers]
+    zero = torch.zeros(m, max(L.k for L in layers), dtype=torch.float16, device=dev)
+    xs_0 = [zero[:, :L.k] for L in layers]
+    t256 = P.make_tuning(w4_tile=256)
+    res["tile_and_operand_comparison_tflops"] = {
+        "forward_fp16": timed(fwd_pass, xs_w), "forward_fp16_256x256_tile": timed(fwd_pass, xs_w, t256),
+        "forward_fp16_zero_activations": timed(fwd_pass, xs_0),
+        "forward_fp16_256x256_tile_zero_activations": timed(fwd_pass, xs_0, t256),
+        "dense_fp16_library_gemm": timed(dense_pass, xs_w),
+        "dense_fp16_library_gemm_zero_activations": timed(dense_pass, xs_0)}
+    del zero, xs_0
     # context for roofline.frac: what the binary16 matrix cores sustain on this device with register-resident
     # operands sampled from this workload (weight values of layer 0 in fp16, its activations), no memory traffic
     cus = torch.cuda.get_device_properties(dev).multi_processor_count
