@@ -310,6 +310,33 @@ def fused_calibration(P, torch, layers, steps: int, reps: int = 5):
             "whole_step_tops": round(gemm_ops / t_step / 1e12, 2)}
 
 
+def hbm_read_ceiling(P, torch, layers, reps: int = 3):
+    """Context for roofline_stats.frac: the rate of a plain read-only stream (cwac_hbm_read_probe: 16-byte
+    non-temporal loads at a grid stride) over the statistics pass's own inputs - every layer's Y_full, then the
+    shared Y_quant buffer - so that, as in the step, each launch reads what the caches no longer hold."""
+    dev = layers[0].y_full.device
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    bufs = [L.y_full for L in layers] + [max((L.yq for L in layers), key=lambda t: t.numel())]
+    out = {}
+    for wgs_per_cu in (8, 16, 32):
+        for b in bufs:
+            P.cwac_hbm_read_probe(b, cus * wgs_per_cu, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        nbytes = 0.0
+        for _ in range(reps):
+            for b in bufs:
+                nbytes += P.cwac_hbm_read_probe(b, cus * wgs_per_cu, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[f"{wgs_per_cu}_workgroups_per_cu"] = round(nbytes / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    best = max(out.values())
+    return {"gbs": out, "best_gbs": best, "best_of_peak": round(best / HBM_PEAK_GBS, 4),
+            "bytes_per_pass": sum(b.numel() * b.element_size() for b in bufs)}
+
+
 def mfma_ceiling(P, torch, layers, iters: int = 20000, reps: int = 4):
     """Context for roofline.frac: the rate the int8 matrix cores sustain on THIS device with
     register-resident operands and no memory traffic (the forward kernel's 4 x 4 MFMA pattern),
@@ -1873,6 +1900,7 @@ def main():
     result["epilogue_comparators"] = comparators(P, torch, layers)
     result["fused_calibration"] = fused_calibration(P, torch, layers, args.steps)
     result["mfma_ceiling_probe"] = mfma_ceiling(P, torch, layers)
+    result["hbm_read_stream_probe"] = hbm_read_ceiling(P, torch, layers)
     if not args.no_cpu_baseline:
         v, cores, secs = cpu_baseline(synth, args.config, args.cpu_sample_rows)
         result["cpu_baseline"] = {

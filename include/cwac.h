@@ -654,6 +654,15 @@ cwac_status qlinear_w4a16_cwac_forward_ex(const uint16_t *x, int64_t ldx, const 
 cwac_status cwac_mfma_probe(const int32_t *operands, int32_t iters, int32_t workgroups,
                             int32_t *sink, void *stream);
 
+/* Diagnostic: a read-only stream over `bytes` of device memory (16-byte non-temporal loads at a
+ * grid stride, 8 in flight per lane, `workgroups` x 256 threads), timed by the caller: the rate
+ * at which this device delivers a plain stream, beside which the statistics pass (8 bytes read
+ * per row and channel) is reported.
+ *   src    device, 16-byte aligned, bytes >= 16 (a multiple of 16 is read)
+ *   sink   device int32[1]; written only if a checksum takes one particular value */
+cwac_status cwac_hbm_read_probe(const void *src, size_t bytes, int32_t workgroups, int32_t *sink,
+                                void *stream);
+
 /* The same for the binary16 matrix cores, the weight-only layer's (per wavefront 4 x 4 MFMA
  * 32x32x16 tiles, fp32 accumulators): 2 * 16384 * 16 * iters * 4 * workgroups floating-point
  * operations.

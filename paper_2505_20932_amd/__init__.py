@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     cwac_quantize_act, cwac_quantize_rows_sym, cwac_range_f32, cwac_range_workspace, cwac_solve,
     cwac_stats_bytes, cwac_stats_reset, make_qparams, qlinear_cwac_forward,
     cwac_calibrate_stats_first, cwac_tuning, make_tuning, cwac_calibrate_stats_static, cwac_static_scratch_bytes,
-    cwac_calibrate_fused_workspace, qlinear_cwac_calibrate_fused, cwac_mfma_probe, cwac_mfma_probe_f16, cwac_kloop_probe,
+    cwac_calibrate_fused_workspace, qlinear_cwac_calibrate_fused, cwac_mfma_probe, cwac_mfma_probe_f16, cwac_hbm_read_probe, cwac_kloop_probe,
     cwac_fold_fixed_point, qlinear_cwac_forward_fixed_point,
     cwac_quantize_act_bits, cwac_quantize_rows_sym_bits,
     CWAC_OUT_FP16, CWAC_W4_GROUP, cwac_w4_quantize_groupwise, cwac_w4_packed_w_bytes, cwac_w4_pack,

@@ -30,7 +30,7 @@ EXPORTS = (
     "cwac_stats_reset", "cwac_calibrate_stats_workspace", "cwac_calibrate_stats", "cwac_solve",
     "cwac_fold", "qlinear_cwac_forward", "cwac_calibrate_fused_workspace",
     "qlinear_cwac_calibrate_fused", "cwac_epilogue_int32", "cwac_apply_unfolded",
-    "cwac_mfma_probe", "cwac_mfma_probe_f16", "cwac_kloop_probe", "cwac_fold_fixed_point", "qlinear_cwac_forward_fixed_point",
+    "cwac_mfma_probe", "cwac_mfma_probe_f16", "cwac_hbm_read_probe", "cwac_kloop_probe", "cwac_fold_fixed_point", "qlinear_cwac_forward_fixed_point",
     "cwac_quantize_act_bits", "cwac_quantize_rows_sym_bits",
     "cwac_w4_quantize_groupwise", "cwac_w4_packed_w_bytes", "cwac_w4_pack",
     "cwac_fold_weight_only", "qlinear_w4a16_cwac_forward", "qconv2d_cwac_forward",
@@ -112,6 +112,7 @@ def lib() -> C.CDLL:
             "cwac_apply_unfolded": (i32, [vp, i64, i64, i32, vp, vp, vp, i64, vp]),
             "cwac_mfma_probe": (i32, [vp, i32, i32, vp, vp]),
             "cwac_mfma_probe_f16": (i32, [vp, i32, i32, vp, vp]),
+            "cwac_hbm_read_probe": (i32, [vp, C.c_size_t, i32, vp, vp]),
             "cwac_kloop_probe": (i32, [vp, vp, i32, i32, i32, vp, vp]),
             "cwac_fold_fixed_point": (i32, [vp, vp, vp, vp, vp, i32, qpp, vp, vp, vp, vp, vp]),
             "qlinear_cwac_forward_fixed_point": (i32, [vp, i64, vp, i64, i64, i32, i32, qpp, vp, vp,
@@ -602,6 +603,15 @@ def cwac_mfma_probe(operands: torch.Tensor, iters: int, workgroups: int, sink: t
     _check(lib().cwac_mfma_probe(_ptr(operands), iters, workgroups, _ptr(sink), _stream(stream)),
            "cwac_mfma_probe")
     return 2.0 * 32768 * 16 * iters * 4 * workgroups
+
+
+def cwac_hbm_read_probe(src: torch.Tensor, workgroups: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueues a read-only stream over `src`; returns the bytes it reads."""
+    assert src.is_contiguous() and sink.dtype == torch.int32
+    nbytes = src.numel() * src.element_size() // 16 * 16
+    _check(lib().cwac_hbm_read_probe(_ptr(src), nbytes, workgroups, _ptr(sink), _stream(stream)),
+           "cwac_hbm_read_probe")
+    return float(nbytes)
 
 
 def cwac_mfma_probe_f16(operands: torch.Tensor, iters: int, workgroups: int, sink: torch.Tensor,

@@ -41,6 +41,25 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const v4i *__restrict__
   if (s == 0x12345678) sink[0] = s;  // keeps the loop alive; practically never taken
 }
 
+// Read-only stream: every lane sums 16-byte non-temporal loads at a grid stride (8 loads in flight per lane).
+// What the statistics pass - two such streams and a little arithmetic - can be compared with.
+typedef unsigned int probe_u4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void hbm_read_probe_kernel(const probe_u4 *__restrict__ src, size_t n16,
+                                                             int32_t *sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  probe_u4 s = {0u, 0u, 0u, 0u};
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    probe_u4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(src + i + j * stride);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s ^= v[j];
+  }
+  for (; i < n16; i += stride) s ^= __builtin_nontemporal_load(src + i);
+  if ((s.x ^ s.y ^ s.z ^ s.w) == 0x12345678u) sink[0] = 1;  // keeps the loads alive; practically never taken
+}
+
 // The same for the binary16 matrix cores (the weight-only layer's MFMA, 32 x 32 x 16, fp32 accumulators).
 typedef _Float16 probe_h8 __attribute__((ext_vector_type(8)));
 typedef float probe_v16f __attribute__((ext_vector_type(16)));
@@ -226,6 +245,16 @@ extern "C" cwac_status cwac_kloop_probe(const int32_t *operands, const int8_t *p
     case 3: return launch_kloop_probe<3>(operands, panels, stages, workgroups, sink, st);
     default: return launch_kloop_probe<4>(operands, panels, stages, workgroups, sink, st);
   }
+}
+
+extern "C" cwac_status cwac_hbm_read_probe(const void *src, size_t bytes, int32_t workgroups, int32_t *sink,
+                                           void *stream) {
+  if (!src || !sink) return CWAC_E_NULL;
+  if (bytes < 16 || workgroups < 1 || workgroups > (1 << 20)) return CWAC_E_SHAPE;
+  if (!aligned(src, 16)) return CWAC_E_ALIGN;
+  hbm_read_probe_kernel<<<(unsigned)workgroups, 256, 0, as_stream(stream)>>>(
+      static_cast<const probe_u4 *>(src), bytes / 16, sink);
+  return launch_status();
 }
 
 extern "C" cwac_status cwac_mfma_probe_f16(const uint16_t *operands, int32_t iters, int32_t workgroups,

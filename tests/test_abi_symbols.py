@@ -119,6 +119,9 @@ def test_argument_errors_of_the_widened_entry_points(lib):
     # diagnostic
     assert lib.cwac_mfma_probe(null, 10, 1, a, null) == -1
     assert lib.cwac_mfma_probe(a, 0, 1, a, null) == -2
+    assert lib.cwac_hbm_read_probe(null, 4096, 1, a, null) == -1
+    assert lib.cwac_hbm_read_probe(a, 8, 1, a, null) == -2
+    assert lib.cwac_hbm_read_probe(C.c_void_p(4100), 4096, 1, a, null) == -3
     assert lib.cwac_mfma_probe_f16(null, 10, 1, a, null) == -1
     assert lib.cwac_mfma_probe_f16(a, 10, 0, a, null) == -2
     assert lib.cwac_mfma_probe_f16(C.c_void_p(4100), 10, 1, a, null) == -3
