@@ -1190,12 +1190,14 @@ def tile_timeline(torch, synth, dev: str, cfgs, fp32_out: bool = False):
                 torch.cuda.synchronize()
                 # work items of the launch: tiles, or, persistent, whole tiles followed by the two
                 # 128-token halves of every tile of a thin last round
-                items, wgs, n_whole = tiles, tiles, tiles
+                items, wgs, n_whole, piece_rows = tiles, tiles, tiles, 256
                 if shape == P.binding.CWAC_SHAPE_256_PERSIST:
                     wgs = min(tiles, torch.cuda.get_device_properties(0).multi_processor_count)
                     rest = tiles % wgs
-                    if 0 < rest and 2 * rest <= wgs:
-                        n_whole, items = tiles - rest, tiles + rest
+                    # a thin last round is cut into quarters (64 tokens; K below 4096) or halves (128 tokens)
+                    pieces = 1 if rest == 0 else (4 if 4 * rest <= wgs and L.k < 4096 else (2 if 2 * rest <= wgs else 1))
+                    if pieces > 1:
+                        n_whole, items, piece_rows = tiles - rest, tiles + (pieces - 1) * rest, 256 // pieces
                 st = buf.cpu().numpy().reshape(4096, 8, 5)[:min(items, 4096)].astype(np.float64) * 0.01       # us
                 st -= st[:, :, 0].min()
                 whole = st[:n_whole]
@@ -1209,7 +1211,7 @@ def tile_timeline(torch, synth, dev: str, cfgs, fp32_out: bool = False):
                     rounds = []
                     for r0 in range(0, st.shape[0], wgs):
                         blk = st[r0:r0 + wgs]
-                        rounds.append({"items": int(blk.shape[0]), "rows": 256 if r0 < n_whole else 128,
+                        rounds.append({"items": int(blk.shape[0]), "rows": 256 if r0 < n_whole else piece_rows,
                                        "first_start_us": round(float(blk[:, :, 0].min()), 1),
                                        "mean_start_us": round(float(blk[:, :, 0].mean()), 1),
                                        "mean_end_us": round(float(blk[:, :, 4].mean()), 1),

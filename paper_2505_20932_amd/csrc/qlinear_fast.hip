@@ -799,17 +799,18 @@ __global__ __launch_bounds__((FastCfg<BM, WM, BK, NSTAGE, NCHUNK, BN, TA_>::NT),
 // item's own rows, scalar row / K offset): a wavefront's load i covers rows 8 i + lr of its share,
 // and the swizzle of row r depends on bits 1-3 of r only, so two per-lane offsets (i even, i odd)
 // serve all loads of a panel and stay live across the epilogue instead of eight.
-// The last round.  With T tiles on G workgroups the last T mod G tiles would keep that many compute
-// units busy for a whole tile while the others idle.  When they are at most G / 2, each of them is
-// split into two work items of 128 tokens x 256 channels (the same eight wavefronts, each 32 tokens
-// x 128 channels: one activation fragment per k-step instead of two), so the last round takes about
-// half a tile.  Items [0, F) are the full tiles, [F, F + 2R) the halves (F = T - R).
+// The last round.  With T tiles on G workgroups the last R = T mod G tiles would keep that many compute
+// units busy for a whole tile while the others idle.  When R <= G / 2, each of them is split into two
+// work items of 128 tokens x 256 channels (the same eight wavefronts, each 32 tokens x 128 channels: one
+// activation fragment per k-step instead of two), so the last round takes about half a tile; when
+// R <= G / 4, into four items of 64 tokens x 256 channels (the eight wavefronts as 2 x 4, each 32 tokens x
+// 64 channels).  Items [0, F) are the full tiles, [F, F + pieces * R) the pieces (F = T - R).
 template <int OUT_KIND, bool INT_ONLY, int LOADERS>
 __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams p) {
   static_assert(LOADERS == 8 || LOADERS == 4, "wavefronts that issue the panel loads");
   constexpr int SHARES = 8 / LOADERS;  // 32-row shares of a panel per loading wavefront
   using C = FastCfg<256, 4, 128, 2, 2, 256>;
-  constexpr int BK = 128, TA = 4, WM = 4, NSTAGE = 2;
+  constexpr int BK = 128, NSTAGE = 2;
   constexpr int kSlabBase = C::STAGE;                         // slabs: behind stage 0
   constexpr int kParamBase = 160 * 1024 - 2 * C::PARAM_BYTES;  // two parameter blocks: the top 8 KiB
   static_assert(C::LOADS_X == 4 && C::LOADS_W == 4 && C::RPL == 8 && C::KK == 4, "load schedule below");
@@ -820,7 +821,6 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave % WM, wave_n = wave / WM;
   const int l32 = lane & 31, half = lane >> 5;
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int lr = lane >> 3, pc = lane & 7;
@@ -839,14 +839,17 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   // work items: full tiles, then the halves of the last round's tiles
   const int G = (int)gridDim.x;
   const int rest = total % G;
-  const int n_split = (rest > 0 && 2 * rest <= G) ? rest : 0;
+  // quarters only in the form for short K loops (LOADERS = 8): the long-K form runs at the register limit without them
+  constexpr bool kQuarters = LOADERS == 8;
+  const int pieces = rest == 0 ? 1 : (kQuarters && 4 * rest <= G ? 4 : (2 * rest <= G ? 2 : 1));  // of a last-round tile
+  const int n_split = pieces > 1 ? rest : 0;
   const int n_full = total - n_split;
-  const int n_items = n_full + 2 * n_split;
+  const int n_items = n_full + pieces * n_split;
 
   // state of the item whose panels are being loaded / multiplied
   int64_t bm0 = 0;
   int bn0 = 0;
-  bool is_half = false;
+  int kind = 0;  // 0: whole tile (256 tokens), 1: half (128), 2: quarter (64)
   __amdgpu_buffer_rsrc_t xdesc, wdesc;
   // The parameters go global -> LDS directly as well (4 bytes per lane, 256 bytes per wavefront load):
   // wavefronts 2a and 2a + 1 fetch the four quarters of array a (0 offset, 1 mult, 2 fbias, 3 row scale).
@@ -863,16 +866,17 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
 
   // item origin and kind, panel descriptors, parameter loads into block pb, panel loads of stage 0
   auto open_item = [&](int id, int pb) {
-    const int tile = id < n_full ? id : n_full + ((id - n_full) >> 1);
-    is_half = id >= n_full;
+    const int sub = id - n_full;  // index among the pieces
+    const int tile = id < n_full ? id : n_full + sub / pieces;
+    kind = id < n_full ? 0 : (pieces == 4 ? 2 : 1);
     int tile_m, tile_n;
     tile_of_block(tile, p.tiles_m, p.tiles_n, tile_m, tile_n);
     bm0 = (int64_t)tile_m * 256;
     if (bm0 > p.m - 256) bm0 = p.m - 256;
-    if (is_half) bm0 += ((id - n_full) & 1) * 128;
+    const int rows = 256 >> kind;
+    if (kind) bm0 += (sub % pieces) * rows;
     bn0 = tile_n * 256;
     if (bn0 > p.n - 256) bn0 = p.n - 256;
-    const int rows = is_half ? 128 : 256;
     const uint32_t x_extent = (uint32_t)((uint64_t)(rows - 1) * (uint64_t)p.ldx + (uint64_t)p.k);
     const uint32_t w_extent = (uint32_t)((uint64_t)255 * (uint64_t)p.ldw + (uint64_t)p.k);
     xdesc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x + bm0 * p.ldx), 0, (int)x_extent, 0x00020000);
@@ -887,19 +891,22 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     }
     if (!INT_ONLY && OUT_KIND != CWAC_OUT_INT32) {
       if (p_arr == 2) src = p.fbias ? p.fbias + bn0 : nullptr;
-      // a half item has 128 rows: only the first of the two wavefronts of this array loads
-      if (p_arr == 3 && !(is_half && (wave_s & 1))) src = p.sx_row ? p.sx_row + bm0 : nullptr;
+      // a half item has 128 rows, a quarter 64: only the first of the two wavefronts of this array loads,
+      // for a quarter only its first 64 lanes' worth (nothing beyond the item's rows is read)
+      if (p_arr == 3 && !(kind && (wave_s & 1))) src = p.sx_row ? p.sx_row + bm0 : nullptr;
     }
     if (src) {  // wave-uniform
       int8_t *dst = param_block(pb) + p_arr * 1024 + (wave_s & 1) * 512;
+      const int n_loads = (p_arr == 3 && kind == 2) ? 1 : 2;
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(static_cast<const int32_t *>(src) + p_elem + j * 64),
-                                         CWAC_LDS_PTR(dst + j * 256), 4, 0, 0);
+        if (j < n_loads)
+          __builtin_amdgcn_global_load_lds(CWAC_GLOBAL_PTR(static_cast<const int32_t *>(src) + p_elem + j * 64),
+                                           CWAC_LDS_PTR(dst + j * 256), 4, 0, 0);
     }
   };
   // Panel loads of one stage.  A share is 32 rows (four loads) of a 256-row panel, 16 rows (two loads) of a
-  // half item's 128 activation rows.  LOADERS = 8: every wavefront loads its own share.  LOADERS = 4: only
+  // half item's 128 activation rows, 8 rows (one load) of a quarter's 64.  LOADERS = 8: every wavefront loads its own share.  LOADERS = 4: only
   // wavefronts 0-3 - one per SIMD - issue loads, each for shares w and w + 4: a direct-to-LDS load holds up
   // the issuing wavefront's MFMAs for some tens of cycles, and with one loading wavefront per SIMD the other
   // one keeps the matrix pipe fed meanwhile (with all eight loading, both wavefronts of a SIMD stall at about
@@ -908,12 +915,18 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   // doubled share at the start of every tile takes the gain back (within +-1 % at K = 512 .. 3072), so the
   // launcher picks by K; cwac_tuning.persist_loaders forces either form.
   const bool loader = wave_s < LOADERS;
-  auto issue_x = [&](int buf, int k0, bool hf) {
+  auto issue_x = [&](int buf, int k0, int kd) {
     if (!loader) return;
 #pragma unroll
     for (int h = 0; h < SHARES; ++h) {
       const int share = wave_s + LOADERS * h;
-      if (!hf) {
+      if (kQuarters && kd == 2) {
+        // rows 8 share .. 8 share + 7: bit 3 of the row, which the swizzle reads, is the share's parity
+        int8_t *dst = smem + buf * C::STAGE + share * (8 * BK);
+        const uint32_t row0 = (uint32_t)(share * 8) * (uint32_t)p.ldx + (uint32_t)k0;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst), 16, (int)((share & 1) ? xv1 : xv0),
+                                                 (int)row0, 0, 0);
+      } else if (kd == 0) {
         int8_t *dst = smem + buf * C::STAGE + share * (32 * BK);
         const uint32_t row0 = (uint32_t)(share * 32) * (uint32_t)p.ldx + (uint32_t)k0;
 #pragma unroll
@@ -944,7 +957,6 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     }
   };
   const int swz_l = C::swz(l32);
-  const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
 
   int id = blockIdx.x;
   if (id >= n_items) return;
@@ -953,11 +965,16 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
 
   // One work item from the barrier that ended the previous one to the barrier that ends this one;
   // TB = 32-token MFMA tiles per wavefront: 2 (full tile) or 1 (half).
-  auto run_item = [&](auto tb_tag) {
+  auto run_item = [&](auto tb_tag, auto ta_tag) {
     constexpr int TB = decltype(tb_tag)::value;
-    constexpr bool HF = TB == 1;
-    constexpr int LPS = HF ? 6 : 8;  // panel loads per wavefront and stage
+    constexpr int TA = decltype(ta_tag)::value;       // 32-channel MFMA tiles per wavefront: 4, or 2 in a quarter
+    constexpr int KIND = TA == 2 ? 2 : (TB == 1 ? 1 : 0);
+    constexpr bool HF = KIND != 0;
+    constexpr int WM = TA == 2 ? 2 : 4;               // wavefronts along the tokens
+    constexpr int LPS = KIND == 2 ? 5 : (KIND == 1 ? 6 : 8);  // panel loads per wavefront and stage
+    const int wave_m = wave % WM, wave_n = wave / WM;
     const int x_off = (wave_m * 32 * TB + l32) * BK;
+    const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
     auto read_frags = [&](int buf, int kk, v4i(&fw)[TA], v4i(&fx)[TB]) {
       const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
       fw[0] = *reinterpret_cast<const v4i *>(base + w_off);
@@ -992,6 +1009,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
         } else {
           __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
         }
+      } else if constexpr (KIND == 2) {  // two MFMAs, three reads: left to the scheduler
       } else {  // four MFMAs, five reads
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
@@ -1032,7 +1050,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));  // stage s + 1 has landed (nothing else is in flight)
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
-      if (first_ok) issue_x(buf, (s + NSTAGE) * BK, HF);
+      if (first_ok) issue_x(buf, (s + NSTAGE) * BK, KIND);
       if (STEADY || s + 1 < stages) read_frags(buf ^ 1, 0, fwA, fxA);
       mma(fwB, fxB);
       interleave(first_ok ? (HF ? 2 : 4) : 0);
@@ -1042,7 +1060,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     // stage 0 of this item is in flight (or has landed), as are its parameters; ring stage 1, the slabs
     // and the other parameter block are free (barrier at the end of the previous epilogue)
     if (stages > 1) {
-      issue_x(1, BK, HF);
+      issue_x(1, BK, KIND);
       issue_w(1, BK);
       // all but stage 1: stage 0 and the parameters have landed (a loading wavefront has its shares of
       // stage 1 in flight, the others nothing)
@@ -1093,7 +1111,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       __builtin_amdgcn_s_barrier();
       __builtin_amdgcn_sched_barrier(0);
       const bool first_ok = NSTAGE < stages;
-      if (first_ok) issue_x(0, NSTAGE * BK, HF);
+      if (first_ok) issue_x(0, NSTAGE * BK, KIND);
       if (stages > 1) read_frags(1, 0, fwA, fxA);
       mma(fwB, fxB);
       interleave(first_ok ? (HF ? 2 : 4) : 0);
@@ -1116,7 +1134,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     more = next < n_items;
     if (more) {
       open_item(next, pb ^ 1);
-      issue_x(0, 0, is_half);
+      issue_x(0, 0, kind);
       issue_w(0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -1153,14 +1171,16 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
 
   // ---- first item: nothing was prefetched
   open_item(id, 0);
-  issue_x(0, 0, is_half);
+  issue_x(0, 0, kind);
   issue_w(0, 0);
   while (true) {
-    const bool hf = is_half;  // of the item about to run (open_item inside run_item overwrites it)
-    if (hf)
-      run_item(std::integral_constant<int, 1>{});
+    const int kd = kind;  // of the item about to run (open_item inside run_item overwrites it)
+    if (kQuarters && kd == 2) {
+      if constexpr (kQuarters) run_item(std::integral_constant<int, 1>{}, std::integral_constant<int, 2>{});
+    } else if (kd == 1)
+      run_item(std::integral_constant<int, 1>{}, std::integral_constant<int, 4>{});
     else
-      run_item(std::integral_constant<int, 2>{});
+      run_item(std::integral_constant<int, 2>{}, std::integral_constant<int, 4>{});
     if (!more) break;
     pb ^= 1;
     __builtin_amdgcn_s_barrier();  // every wavefront is done with the slabs and that item's parameter block

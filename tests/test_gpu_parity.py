@@ -445,6 +445,39 @@ def test_forward_persistent_tiles(orc, m, n, k, wgs):
     np.testing.assert_array_equal(got, acc + off[None, :])
 
 
+@pytest.mark.parametrize("m,n,k,wgs", [(25216, 768, 256, 0), (4500, 1100, 384, 64), (2100, 512, 128, 16),
+                                       (2100, 512, 4224, 16)])
+def test_forward_persistent_last_round_in_quarters(orc, m, n, k, wgs):
+    """A last round of at most a quarter of the workgroups: its tiles are cut into four items of 64 tokens (short
+    K loops; with K >= 4096 into two halves unless eight loading wavefronts are forced).  Full grid of one
+    workgroup per compute unit (297 tiles, 41 of them in the last round) and smaller grids; ragged edges;
+    per-tensor and per-token epilogues, int8 and fp32 out."""
+    print(f"persistent tiles, quartered last round {m} x {n} x {k}, {wgs or 'one per CU'} workgroups", flush=True)
+    g = synth.normal(1900 + k, 0, m * k).numpy().reshape(m, k)
+    xq = np.clip(np.rint(g * 40), -128, 127).astype(np.int8)
+    g = synth.normal(1900 + k, 1, n * k).numpy().reshape(n, k)
+    wq = np.clip(np.rint(g * 40), -127, 127).astype(np.int8)
+    acc = orc.gemm_i8(xq, wq)
+    mult = (np.abs(synth.normal(1900 + k, 2, n).numpy()) * 1e-3 + 1e-4).astype(np.float32)
+    off = np.rint(synth.normal(1900 + k, 3, n).numpy() * 500).astype(np.int32)
+    fb = synth.normal(1900 + k, 4, n).numpy().astype(np.float32)
+    sxr = (np.abs(synth.normal(1900 + k, 5, m).numpy()) + 0.5).astype(np.float32)
+    from types import SimpleNamespace
+    c = SimpleNamespace(xq=xq, wq=wq, n=n)
+    qp = P.make_qparams(z_r=-3)
+    qpt = P.make_qparams(P.CWAC_EPI_FP_BIAS, True, z_r=-3)
+    for loaders in (0, 8):
+        kw = dict(tile="fast", pipe="persist", wgs=wgs, loaders=loaders)
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, qp=qp, **kw)
+        np.testing.assert_array_equal(got, orc.folded_forward(acc, off, mult, -3))
+        got = _forward(c, P.CWAC_OUT_INT8, mult, off, fbias=fb, sx_row=sxr, qp=qpt, ldo=n + 16, **kw)
+        np.testing.assert_array_equal(got[:, :n], orc.folded_forward(acc, off, mult, -3, fb, sxr))
+        assert np.all(got[:, n:] == 77)
+        _, want = orc.folded_forward(acc, off, mult, 0, fb, sxr, want_f32=True)
+        got = _forward(c, P.CWAC_OUT_FP32, mult, off, fbias=fb, sx_row=sxr, **kw)
+        np.testing.assert_array_equal(got, want)
+
+
 @pytest.mark.parametrize("zr", [-128, -77, -6, 0, 1, 5, 126, 127])
 def test_forward_ties_and_saturation_for_every_zero_point_parity(orc, zr):
     """Multipliers that are powers of two and biases that are multiples of 1/2 put many results exactly half
