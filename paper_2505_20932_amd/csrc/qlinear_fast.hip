@@ -915,6 +915,12 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   // doubled share at the start of every tile takes the gain back (within +-1 % at K = 512 .. 3072), so the
   // launcher picks by K; cwac_tuning.persist_loaders forces either form.
   const bool loader = wave_s < LOADERS;
+  // Ring geometry by item kind.  A whole tile: two stages of 64 KiB (activation panel, weight panel).  A piece has
+  // so little MFMA work per stage that with two stages the loads' round trip would set its pace (a stage's loads
+  // can only go out once the stage two back has been read), so pieces run three compact stages of (rows + 256)
+  // x 128 bytes: 48 KiB (half), 40 KiB (quarter).  Stage 0 starts at the same place for every kind.
+  auto x_bytes = [](int kd) { return (256 >> kd) * BK; };
+  auto stage_bytes = [](int kd) { return ((256 >> kd) + 256) * BK; };
   auto issue_x = [&](int buf, int k0, int kd) {
     if (!loader) return;
 #pragma unroll
@@ -922,7 +928,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       const int share = wave_s + LOADERS * h;
       if (kQuarters && kd == 2) {
         // rows 8 share .. 8 share + 7: bit 3 of the row, which the swizzle reads, is the share's parity
-        int8_t *dst = smem + buf * C::STAGE + share * (8 * BK);
+        int8_t *dst = smem + buf * stage_bytes(2) + share * (8 * BK);
         const uint32_t row0 = (uint32_t)(share * 8) * (uint32_t)p.ldx + (uint32_t)k0;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst), 16, (int)((share & 1) ? xv1 : xv0),
                                                  (int)row0, 0, 0);
@@ -934,7 +940,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
           __builtin_amdgcn_raw_ptr_buffer_load_lds(xdesc, CWAC_LDS_PTR(dst + i * 8 * BK), 16,
                                                    (int)((i & 1) ? xv1 : xv0), (int)(row0 + (uint32_t)i * xstep), 0, 0);
       } else {
-        int8_t *dst = smem + buf * C::STAGE + share * (16 * BK);
+        int8_t *dst = smem + buf * stage_bytes(1) + share * (16 * BK);
         const uint32_t row0 = (uint32_t)(share * 16) * (uint32_t)p.ldx + (uint32_t)k0;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -943,12 +949,12 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       }
     }
   };
-  auto issue_w = [&](int buf, int k0) {
+  auto issue_w = [&](int buf, int k0, int kd) {
     if (!loader) return;
 #pragma unroll
     for (int h = 0; h < SHARES; ++h) {
       const int share = wave_s + LOADERS * h;
-      int8_t *dst = smem + buf * C::STAGE + C::X_BYTES + share * (32 * BK);
+      int8_t *dst = smem + buf * stage_bytes(kd) + x_bytes(kd) + share * (32 * BK);
       const uint32_t row0 = (uint32_t)(share * 32) * (uint32_t)p.ldw + (uint32_t)k0;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -972,11 +978,12 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     constexpr bool HF = KIND != 0;
     constexpr int WM = TA == 2 ? 2 : 4;               // wavefronts along the tokens
     constexpr int LPS = KIND == 2 ? 5 : (KIND == 1 ? 6 : 8);  // panel loads per wavefront and stage
+    constexpr int XB = (256 >> KIND) * BK, STG = XB + 256 * BK;  // bytes of a stage's activation panel, of a stage
     const int wave_m = wave % WM, wave_n = wave / WM;
     const int x_off = (wave_m * 32 * TB + l32) * BK;
-    const int w_off = C::X_BYTES + (wave_n * (32 * TA) + l32) * BK;
+    const int w_off = XB + (wave_n * (32 * TA) + l32) * BK;
     auto read_frags = [&](int buf, int kk, v4i(&fw)[TA], v4i(&fx)[TB]) {
-      const int8_t *base = smem + buf * C::STAGE + (((2 * kk + half) ^ swz_l) << 4);
+      const int8_t *base = smem + buf * STG + (((2 * kk + half) ^ swz_l) << 4);
       fw[0] = *reinterpret_cast<const v4i *>(base + w_off);
 #pragma unroll
       for (int b = 0; b < TB; ++b) fx[b] = *reinterpret_cast<const v4i *>(base + x_off + b * 32 * BK);
@@ -1036,7 +1043,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
 #pragma unroll
       for (int kk = 0; kk + 1 < C::KK; ++kk) {
         const bool ld = kk == 0 && late_ok;
-        if (ld) issue_w(buf ^ 1, (s + 1) * BK);
+        if (ld) issue_w(buf ^ 1, (s + 1) * BK, KIND);
         if (kk & 1) {
           read_frags(buf, kk + 1, fwA, fxA);
           mma(fwB, fxB);
@@ -1057,29 +1064,11 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     };
 
     CWAC_STAMPT(id, 0);
-    // stage 0 of this item is in flight (or has landed), as are its parameters; ring stage 1, the slabs
-    // and the other parameter block are free (barrier at the end of the previous epilogue)
-    if (stages > 1) {
-      issue_x(1, BK, KIND);
-      issue_w(1, BK);
-      // all but stage 1: stage 0 and the parameters have landed (a loading wavefront has its shares of
-      // stage 1 in flight, the others nothing)
-      if (loader)
-        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(SHARES * LPS, 0));
-      else
-        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
-    } else {
-      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
-    }
-    __builtin_amdgcn_s_barrier();
     const int32_t *s_off = reinterpret_cast<const int32_t *>(param_block(pb));
-    read_frags(0, 0, fwA, fxA);
-    CWAC_STAMPT(id, 1);
-    // stage 0: the loads of stage 1 are out already (above), so only its last k-step issues loads.
-    // The accumulators START at offset[n] (the integer offset add of Eq. 10 costs nothing): the first
-    // MFMA of every accumulator takes the offsets of its 32 channels - four 16-byte LDS reads that land
-    // in 16 consecutive registers - as its C operand, so no register is initialised by hand.
-    {
+    // First k-step of an item.  The accumulators START at offset[n] (the integer offset add of Eq. 10 costs
+    // nothing): the first MFMA of every accumulator takes the offsets of its 32 channels - four 16-byte LDS
+    // reads that land in 16 consecutive registers - as its C operand, so no register is initialised by hand.
+    auto first_kstep = [&]() {
       read_frags(0, 1, fwB, fxB);
 #pragma unroll
       for (int a = 0; a < TA; ++a) {
@@ -1095,17 +1084,40 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
           acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fwA[a], fxA[b], pat, 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int kk = 1; kk + 1 < C::KK; ++kk) {
-        if (kk & 1) {
-          read_frags(0, kk + 1, fwA, fxA);
-          mma(fwB, fxB);
-        } else {
-          read_frags(0, kk + 1, fwB, fxB);
-          mma(fwA, fxA);
-        }
-        interleave(0);
+    };
+    auto kstep = [&](int buf, int kk) {  // MFMAs of k-step kk, fragments of k-step kk + 1
+      if (kk & 1) {
+        read_frags(buf, kk + 1, fwA, fxA);
+        mma(fwB, fxB);
+      } else {
+        read_frags(buf, kk + 1, fwB, fxB);
+        mma(fwA, fxA);
       }
+      interleave(0);
+    };
+    if constexpr (KIND == 0) {
+    // stage 0 of this item is in flight (or has landed), as are its parameters; ring stage 1, the slabs
+    // and the other parameter block are free (barrier at the end of the previous epilogue)
+    if (stages > 1) {
+      issue_x(1, BK, KIND);
+      issue_w(1, BK, KIND);
+      // all but stage 1: stage 0 and the parameters have landed (a loading wavefront has its shares of
+      // stage 1 in flight, the others nothing)
+      if (loader)
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(SHARES * LPS, 0));
+      else
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    } else {
+      __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+    }
+    __builtin_amdgcn_s_barrier();
+    read_frags(0, 0, fwA, fxA);
+    CWAC_STAMPT(id, 1);
+    // stage 0: the loads of stage 1 are out already (above), so only its last k-step issues loads.
+    {
+      first_kstep();
+#pragma unroll
+      for (int kk = 1; kk + 1 < C::KK; ++kk) kstep(0, kk);
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
       __builtin_amdgcn_s_barrier();
@@ -1114,7 +1126,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
       if (first_ok) issue_x(0, NSTAGE * BK, KIND);
       if (stages > 1) read_frags(1, 0, fwA, fxA);
       mma(fwB, fxB);
-      interleave(first_ok ? (HF ? 2 : 4) : 0);
+      interleave(first_ok ? 4 : 0);
     }
     int s = 1;
     for (; s + 2 * NSTAGE <= stages; s += NSTAGE) {  // steady state, unrolled over the ring
@@ -1123,6 +1135,62 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     }
     for (; s + NSTAGE < stages; ++s) stage_body(s, s & 1, std::true_type{});
     for (; s < stages; ++s) stage_body(s, s & 1, std::false_type{});
+    } else {
+      // ---- a piece: three stages.  Stage 0 is in flight (or has landed), as are the parameters; stages 1 and 2
+      // go out now (the rest of the ring, the slabs and the other parameter block are free: barrier at the end
+      // of the previous epilogue).  Memory operations return in order, so "at most N outstanding" means that
+      // everything older than the newest N has arrived.
+      if (stages > 1) {
+        issue_x(1, BK, KIND);
+        issue_w(1, BK, KIND);
+      }
+      if (stages > 2) {
+        issue_x(2, 2 * BK, KIND);
+        issue_w(2, 2 * BK, KIND);
+      }
+      if (loader && stages > 2)
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(2 * SHARES * LPS, 0));
+      else if (loader && stages > 1)
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(SHARES * LPS, 0));
+      else
+        __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+      __builtin_amdgcn_s_barrier();
+      read_frags(0, 0, fwA, fxA);
+      CWAC_STAMPT(id, 1);
+      // stage s in ring buffer s % 3: three k-steps, then - every wavefront has fetched the stage's last
+      // fragments, and stage s + 1 has landed once at most the loads of stage s + 2 are outstanding - the
+      // barrier that frees the buffer for stage s + 3, whose loads go out under the last k-step.
+      auto piece_stage = [&](int s, int buf, auto first_tag) {
+        const int nbuf = buf == 2 ? 0 : buf + 1;
+        if constexpr (decltype(first_tag)::value)
+          first_kstep();
+        else
+          kstep(buf, 0);
+        kstep(buf, 1);
+        kstep(buf, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if (loader && s + 2 < stages)
+          __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(SHARES * LPS, 0));
+        else
+          __builtin_amdgcn_s_waitcnt(s_waitcnt_imm(0, 0));
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + 3 < stages) {
+          issue_x(buf, (s + 3) * BK, KIND);
+          issue_w(buf, (s + 3) * BK, KIND);
+        }
+        if (s + 1 < stages) read_frags(nbuf, 0, fwA, fxA);
+        mma(fwB, fxB);
+        interleave(0);
+      };
+      piece_stage(0, 0, std::true_type{});
+      int buf = 1;
+#pragma unroll 1
+      for (int s = 1; s < stages; ++s) {
+        piece_stage(s, buf, std::false_type{});
+        buf = buf == 2 ? 0 : buf + 1;
+      }
+    }
 
     // ---- the ring is free (every wavefront fetched its last fragments before the last barrier):
     // open the next item - its parameter loads and the panel loads of its stage 0 travel under this
@@ -1135,7 +1203,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
     if (more) {
       open_item(next, pb ^ 1);
       issue_x(0, 0, kind);
-      issue_w(0, 0);
+      issue_w(0, 0, kind);
     }
     __builtin_amdgcn_sched_barrier(0);
     {
@@ -1172,7 +1240,7 @@ __global__ __launch_bounds__(512, 1) void qlinear_persist_kernel(const FwdParams
   // ---- first item: nothing was prefetched
   open_item(id, 0);
   issue_x(0, 0, kind);
-  issue_w(0, 0);
+  issue_w(0, 0, kind);
   while (true) {
     const int kd = kind;  // of the item about to run (open_item inside run_item overwrites it)
     if (kQuarters && kd == 2) {
