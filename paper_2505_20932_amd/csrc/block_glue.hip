@@ -408,29 +408,40 @@ __global__ __launch_bounds__(64 * NT * G) void attention_int8_kernel(const AttnP
   const h2 zbias = {zb, zb};
   // K and V of the head -> LDS as (code - z) in binary16; rows beyond the last token are zero
   constexpr int CH = D / 8;  // 8-channel chunks per row
-  for (int i = tid; i < TP * CH; i += 64 * NT) {
-    const int key = i / CH, ch = i % CH;
-    h8 kv, vv;
-    if (key < p.tokens) {
-      kv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + key * p.ld + c + 8 * ch), zbias);
-      vv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + key * p.ld + 2 * c + 8 * ch), zbias);
-    } else {
+  constexpr int IT = CH / 2;  // chunks per thread: TP * CH / (64 * NT)
+  // all of the thread's loads go out before the first conversion (one round trip to memory, not IT + 1);
+  // a key beyond the last token reads as the zero point, i.e. as (code - z) = 0
+  const uint32_t zword = 0x01010101u * (uint32_t)(p.z & 0xff);
+  uint2 kraw[IT], vraw[IT];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) kv[e] = vv[e] = (_Float16)0.0f;
+  for (int j = 0; j < IT; ++j) {
+    const int i = tid + j * (64 * NT);
+    const int key = i / CH, ch = i % CH;
+    kraw[j] = vraw[j] = make_uint2(zword, zword);
+    if (key < p.tokens) {
+      kraw[j] = *reinterpret_cast<const uint2 *>(qbase + key * p.ld + c + 8 * ch);
+      vraw[j] = *reinterpret_cast<const uint2 *>(qbase + key * p.ld + 2 * c + 8 * ch);
     }
+  }
+  // this lane's query row as B operands (rows beyond the last token repeat it; never stored)
+  const int q = wave * 32 + l32;
+  const int qrow = q < p.tokens ? q : p.tokens - 1;
+  uint2 qraw[D / 16];
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s)
+    qraw[s] = *reinterpret_cast<const uint2 *>(qbase + qrow * p.ld + 16 * s + 8 * half);
+#pragma unroll
+  for (int j = 0; j < IT; ++j) {
+    const int i = tid + j * (64 * NT);
+    const int key = i / CH, ch = i % CH;
+    const h8 kv = codes_to_h8(kraw[j], zbias), vv = codes_to_h8(vraw[j], zbias);
     *reinterpret_cast<h8 *>(s_k + key * k_stride(D) + ch * 16) = kv;
 #pragma unroll
     for (int e = 0; e < 8; ++e) *reinterpret_cast<_Float16 *>(s_v + (8 * ch + e) * v_stride(NT) + key * 2) = vv[e];
   }
-
-  // this lane's query row as B operands (rows beyond the last token repeat it; never stored)
-  const int q = wave * 32 + l32;
-  const int qrow = q < p.tokens ? q : p.tokens - 1;
   h8 fq[D / 16];
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    fq[s] = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + qrow * p.ld + 16 * s + 8 * half), zbias);
-  }
+  for (int s = 0; s < D / 16; ++s) fq[s] = codes_to_h8(qraw[s], zbias);
   __syncthreads();
 
   // s^2 / sqrt(D) * log2(e)
@@ -506,17 +517,28 @@ __global__ __launch_bounds__(64 * kChunkTiles) void attention_long_kernel(const 
 
   constexpr int CH = D / 8;
   for (int key0 = 0; key0 < p.tokens; key0 += kChunk) {
-    if (key0 > 0) __syncthreads();  // every wavefront is done with the previous chunk
-    for (int i = tid; i < kChunk * CH; i += 64 * NT) {
-      const int kl = i / CH, ch = i % CH, key = key0 + kl;
-      h8 kv, vv;
-      if (key < p.tokens) {
-        kv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + (int64_t)key * p.ld + c + 8 * ch), zbias);
-        vv = codes_to_h8(*reinterpret_cast<const uint2 *>(qbase + (int64_t)key * p.ld + 2 * c + 8 * ch), zbias);
-      } else {
+    // the chunk's loads first (one round trip), then the conversions; keys beyond the last token read as the
+    // zero point, i.e. as (code - z) = 0
+    static_assert(kChunk * CH % (64 * NT) == 0, "whole chunks per thread");
+    constexpr int IT = kChunk * CH / (64 * NT);
+    const uint32_t zword = 0x01010101u * (uint32_t)(p.z & 0xff);
+    uint2 kraw[IT], vraw[IT];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) kv[e] = vv[e] = (_Float16)0.0f;
+    for (int j = 0; j < IT; ++j) {
+      const int i = tid + j * (64 * NT);
+      const int kl = i / CH, ch = i % CH, key = key0 + kl;
+      kraw[j] = vraw[j] = make_uint2(zword, zword);
+      if (key < p.tokens) {
+        kraw[j] = *reinterpret_cast<const uint2 *>(qbase + (int64_t)key * p.ld + c + 8 * ch);
+        vraw[j] = *reinterpret_cast<const uint2 *>(qbase + (int64_t)key * p.ld + 2 * c + 8 * ch);
       }
+    }
+    if (key0 > 0) __syncthreads();  // every wavefront is done with the previous chunk
+#pragma unroll
+    for (int j = 0; j < IT; ++j) {
+      const int i = tid + j * (64 * NT);
+      const int kl = i / CH, ch = i % CH;
+      const h8 kv = codes_to_h8(kraw[j], zbias), vv = codes_to_h8(vraw[j], zbias);
       *reinterpret_cast<h8 *>(s_k + kl * k_stride(D) + ch * 16) = kv;
 #pragma unroll
       for (int e = 0; e < 8; ++e) *reinterpret_cast<_Float16 *>(s_v + (8 * ch + e) * v_stride(NT) + kl * 2) = vv[e];
