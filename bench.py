@@ -1594,6 +1594,9 @@ def per_config_entry(wl, layers, sm, collapse=None):
                        "launches": "cwac_calibrate_stats_first: stats_partial_kernel + stats_merge_kernel"},
         "calibration_forward_fp32_tops": round(sm["cal_ops"] / (sm["t_cal"] * 1e-3) / 1e12, 1),
         "solve_fold_ms": round(sm["t_fit"], 4),
+        **({"note": "every launch of this workload is shorter than 30 us (a kernel that does nothing is recorded "
+                    "at 4-5 us on this device): launch-bound, the fractions say nothing about the kernels"}
+           if max(sm["t_fwd"], sm["t_stats"]) / len(layers) < 0.03 else {}),
         "layers": table}
 
 
