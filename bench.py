@@ -1615,6 +1615,10 @@ def per_config_block(P, synth, torch, dev: str, steps: int, headline_cfg: int, h
         elapsed, events = time_steps(P, torch, layers, steps, 2)
         sm = summarize(layers, events, steps, elapsed)
         out[str(cfg)] = per_config_entry(wl, layers, sm, (4, 12) if cfg == 3 else None)
+        # the calibration side as one fused call (statistics in the calibration GEMM's epilogue) on this workload
+        fc = fused_calibration(P, torch, layers, 2, reps=3)
+        if fc is not None:
+            out[str(cfg)]["fused_calibration"] = fc
         del layers, events
         torch.cuda.empty_cache()
     return out
