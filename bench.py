@@ -1119,11 +1119,37 @@ def power_trace(P, synth, torch, dev: str, cfg: int, seconds: float = 5.0):
     def probe():
         P.cwac_mfma_probe(words, 20000, cus, sink)
 
+    # the same forward launches on other operand VALUES (zeros; dense normal codes of standard deviation 30) and
+    # on half of the compute units: what the power management makes of each
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(9)
+    k_max, n_max = max(L.k for L in layers), max(L.n for L in layers)
+    m = layers[0].m
+    xz = torch.zeros(m, k_max, dtype=torch.int8, device=dev)
+    wz = torch.zeros(n_max, k_max, dtype=torch.int8, device=dev)
+    xd = torch.clamp(torch.round(torch.randn(m, k_max, device=dev, generator=gen) * 30), -128, 127).to(torch.int8)
+    wd = torch.clamp(torch.round(torch.randn(n_max, k_max, device=dev, generator=gen) * 30), -127, 127).to(torch.int8)
+    half_cus = P.make_tuning(kernel=P.binding.CWAC_KERNEL_DIRECT_LDS, shape=P.binding.CWAC_SHAPE_256_PERSIST,
+                             persist_workgroups=cus // 2)
+
+    def fwd_on(x, w, tun=None):
+        def run():
+            for L in layers:
+                xs, ws = (L.xq, L.wq) if x is None else (x[:, :L.k], w[:L.n, :L.k])
+                P.qlinear_cwac_forward(xs, ws, L.qp, L.mult, L.offset, L.fbias if L.per_token else None,
+                                       L.sx_row if L.per_token else None, P.CWAC_OUT_INT8, L.out, tuning=tun)
+        return run
+
     fwd_ops = sum(2.0 * L.m * L.n * L.k for L in layers)
+    fwd_keys = ("forward_int8", "forward_int8_zero_operands", "forward_int8_dense_normal_operands",
+                "forward_int8_half_of_the_compute_units", "forward_int8_again")
     out = dict(phase(n, f) for n, f in (("idle", None), ("forward_int8", fwd), ("calibration_forward_fp32", cal),
                                         ("statistics", stats), ("mfma_probe_workload_operands", probe),
+                                        ("forward_int8_zero_operands", fwd_on(xz, wz)),
+                                        ("forward_int8_dense_normal_operands", fwd_on(xd, wd)),
+                                        ("forward_int8_half_of_the_compute_units", fwd_on(None, None, half_cus)),
                                         ("forward_int8_again", fwd)))
-    for key in ("forward_int8", "forward_int8_again"):
+    for key in fwd_keys:
         out[key]["pops"] = round(fwd_ops / (out[key]["ms_per_pass"] * 1e-3) / 1e15, 4)
     out["mfma_probe_workload_operands"]["pops"] = round(
         2.0 * 32768 * 16 * 20000 * 4 * cus / (out["mfma_probe_workload_operands"]["ms_per_pass"] * 1e-3) / 1e15, 4)
